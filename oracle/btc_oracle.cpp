@@ -1,0 +1,182 @@
+// CPU oracle for the binary-codebook linear layer  y = W_hat . x
+//
+// TEST INFRASTRUCTURE, NOT PRODUCT.  Only the tests, the smoke check and the
+// benchmark's cpu_baseline leg may build, load or call this file.  It shares
+// no source, header, table or helper with the HIP library and is deliberately
+// plain and slow: no blocking, no fusion, no lookup tables, fp64 throughout.
+//
+// What it computes (paper: Algorithm "Binary Transformation and Compression",
+// steps "Reconstruct binary" and "Dequantize"; appendix "Binary Codebook
+// LUT-GEMM", the blockwise definition of W and of y_r):
+//
+//   idx[i][j]        = bits [j*b, (j+1)*b) of row i's index stream,
+//                      b = ceil(log2 K); bit p of a row lives in bit (p & 31)
+//                      of that row's 32-bit word (p >> 5)           (integers)
+//   B_hat[i][j*v+t]  = +1 if bit t of codebook[idx[i][j]] is set, else -1
+//                      (bit = (B+1)/2, the sign<->bit map of Algorithm
+//                      "Efficient Binary Vector Packing and Unpacking")
+//   W_hat[i][k]      = alpha[i] * B_hat[i][k] + mu[i],   k < in
+//   y[m][i]          = sum_{k < in} W_hat[i][k] * x[m][k]      (Y = X W^T)
+//
+// The paper's two-stage lookup scheme reaches exactly this blockwise dot
+// product by re-association, so the oracle is the definition written out.
+// The weight matrix is materialised as an fp64 array before it is multiplied.
+// Columns k >= in do not exist: surplus positions of the last chunk's pattern
+// are never touched.
+//
+// Pins (tests/test_oracle_pins.py): brute force from a byte view of the
+// stream, full-codebook dense sign matrix, ones vector -> popcount integers,
+// linearity, affine split in (alpha, mu), XNOR-popcount closed form for +-1
+// activations, the paper's two-stage table identity, storage accounting,
+// fp16/bf16 widening against numpy.
+#include <cstdint>
+#include <cstring>
+
+extern "C" {
+
+// ceil(log2 K) for K >= 2 (Compression Analysis: ceil(log2 c) bits per vector)
+int btc_oracle_index_bits(int K) {
+  int b = 0;
+  while ((1L << b) < (long)K) ++b;
+  return b;
+}
+
+long btc_oracle_num_chunks(long in, int v) { return (in + v - 1) / v; }
+
+long btc_oracle_words_per_row(long in, int v, int K) {
+  long nbits = btc_oracle_num_chunks(in, v) * (long)btc_oracle_index_bits(K);
+  return (nbits + 31) / 32;
+}
+
+// Total storage in bits of one layer: v*c for the codebook plus
+// ceil(log2 c) * (number of chunks) for the indices (Compression Analysis),
+// with chunks counted per row, ceil(in / v) of them.
+long btc_oracle_storage_bits(long out, long in, int v, int K) {
+  return (long)v * K + (long)btc_oracle_index_bits(K) * out * btc_oracle_num_chunks(in, v);
+}
+
+// Index matrix -> per-row LSB-first bit stream, one bit at a time.
+// Returns 0, or -1 if some index is outside [0, K).
+int btc_oracle_pack(const int32_t* idx, long out, long nchunks, int K, uint32_t* packed) {
+  const int b = btc_oracle_index_bits(K);
+  const long wpr = (nchunks * b + 31) / 32;
+  for (long i = 0; i < out; ++i)
+    for (long j = 0; j < nchunks; ++j)
+      if (idx[i * nchunks + j] < 0 || idx[i * nchunks + j] >= K) return -1;
+  std::memset(packed, 0, sizeof(uint32_t) * (size_t)out * (size_t)wpr);
+#pragma omp parallel for schedule(static)
+  for (long i = 0; i < out; ++i) {
+    uint32_t* row = packed + i * wpr;
+    for (long j = 0; j < nchunks; ++j) {
+      const uint32_t code = (uint32_t)idx[i * nchunks + j];
+      for (int q = 0; q < b; ++q) {
+        const long p = j * b + q;
+        if ((code >> q) & 1u) row[p >> 5] |= (1u << (p & 31));
+      }
+    }
+  }
+  return 0;
+}
+
+// Bit stream -> index matrix, one bit at a time.
+void btc_oracle_unpack(const uint32_t* packed, long out, long nchunks, int K, int32_t* idx) {
+  const int b = btc_oracle_index_bits(K);
+  const long wpr = (nchunks * b + 31) / 32;
+#pragma omp parallel for schedule(static)
+  for (long i = 0; i < out; ++i) {
+    const uint32_t* row = packed + i * wpr;
+    for (long j = 0; j < nchunks; ++j) {
+      uint32_t code = 0;
+      for (int q = 0; q < b; ++q) {
+        const long p = j * b + q;
+        code |= ((row[p >> 5] >> (p & 31)) & 1u) << q;
+      }
+      idx[i * nchunks + j] = (int32_t)code;
+    }
+  }
+}
+
+// IEEE binary16 bit pattern -> double, exactly.
+double btc_oracle_f16_to_f64(uint16_t h) {
+  const int sign = (h >> 15) & 1;
+  const int e = (h >> 10) & 0x1F;
+  const int m = h & 0x3FF;
+  double val;
+  if (e == 0) {
+    val = (double)m * (1.0 / 16777216.0);  // m * 2^-24 (zero and subnormals)
+  } else if (e == 31) {
+    val = m ? __builtin_nan("") : __builtin_inf();
+  } else {
+    val = (1.0 + (double)m / 1024.0);
+    int k = e - 15;
+    while (k > 0) { val *= 2.0; --k; }
+    while (k < 0) { val *= 0.5; ++k; }
+  }
+  return sign ? -val : val;
+}
+
+// bfloat16 bit pattern -> double, exactly (a bfloat16 is the top half of a float).
+double btc_oracle_bf16_to_f64(uint16_t h) {
+  const uint32_t u = (uint32_t)h << 16;
+  float f;
+  std::memcpy(&f, &u, sizeof f);
+  return (double)f;
+}
+
+// Widen an activation block to fp64.  kind: 0 = fp16, 1 = bf16.
+void btc_oracle_widen(const uint16_t* x, long n, int kind, double* xd) {
+  for (long t = 0; t < n; ++t)
+    xd[t] = kind == 0 ? btc_oracle_f16_to_f64(x[t]) : btc_oracle_bf16_to_f64(x[t]);
+}
+
+// Materialise W_hat rows in fp64.  rows == nullptr: all rows 0..out-1 (then
+// nrows must equal out); otherwise the listed rows, in the listed order.
+// W[r][k] for r < nrows, k < in, row stride `in`.
+void btc_oracle_materialise(const uint32_t* packed, const uint32_t* codebook,
+                            const float* alpha, const float* mu,
+                            long out, long in, int v, int K,
+                            const long* rows, long nrows, double* W) {
+  (void)out;
+  const int b = btc_oracle_index_bits(K);
+  const long nchunks = btc_oracle_num_chunks(in, v);
+  const long wpr = (nchunks * b + 31) / 32;
+#pragma omp parallel for schedule(static)
+  for (long r = 0; r < nrows; ++r) {
+    const long i = rows ? rows[r] : r;
+    const uint32_t* row = packed + i * wpr;
+    const double a = (double)alpha[i];
+    const double m = (double)mu[i];
+    for (long j = 0; j < nchunks; ++j) {
+      uint32_t code = 0;
+      for (int q = 0; q < b; ++q) {
+        const long p = j * b + q;
+        code |= ((row[p >> 5] >> (p & 31)) & 1u) << q;
+      }
+      const uint32_t pattern = codebook[code];
+      for (int t = 0; t < v; ++t) {
+        const long k = j * v + t;
+        if (k >= in) break;
+        const double sgn = ((pattern >> t) & 1u) ? 1.0 : -1.0;
+        W[r * in + k] = a * sgn + m;
+      }
+    }
+  }
+}
+
+// Y[m][r] = sum_k W[r][k] * X[m][k], k ascending, fp64.  X is fp64 [M][in],
+// W is [nrows][in], Y is [M][nrows].
+void btc_oracle_matmul(const double* W, long nrows, long in,
+                       const double* X, long M, double* Y) {
+#pragma omp parallel for schedule(static)
+  for (long r = 0; r < nrows; ++r) {
+    const double* w = W + r * in;
+    for (long m = 0; m < M; ++m) {
+      const double* x = X + m * in;
+      double acc = 0.0;
+      for (long k = 0; k < in; ++k) acc += w[k] * x[k];
+      Y[m * nrows + r] = acc;
+    }
+  }
+}
+
+}  // extern "C"
