@@ -1,0 +1,122 @@
+/* btc.h -- C ABI of the MI355X (gfx950) binary-codebook linear layer.
+ *
+ * The layer computes  y = W_hat . x  for a weight matrix stored as
+ *   - a codebook of K sign patterns of length v (one uint32 bit mask each),
+ *   - per weight row, ceil(in/v) indices of ceil(log2 K) bits, one per
+ *     length-v chunk of the row, and
+ *   - a per-row scale alpha_i and per-row mean mu_i,
+ * with  W_hat[i][j*v+t] = alpha_i * (bit t of codebook[idx[i][j]] ? +1 : -1) + mu_i
+ * (paper: Algorithm "Binary Transformation and Compression", steps
+ * "Reconstruct binary" / "Dequantize"; appendix "Binary Codebook LUT-GEMM",
+ * definition of W and of y_r as a sum over blocks; Section "Compression
+ * Analysis" for the storage format).
+ *
+ * Conventions for every entry point
+ *   - Every array pointer is a DEVICE pointer owned by the caller unless the
+ *     comment says "host".  The library allocates no device memory and keeps
+ *     no state between calls; scratch space is the caller's `workspace`.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Compute calls enqueue work and return; only btc_pack waits (see there).
+ *   - Array pointers must be 16-byte aligned (BTC_ERR_ALIGN otherwise).
+ *   - Errors are returned, never thrown; on an error nothing was enqueued.
+ *   - Matrices are row-major.  Activations are X[rows][in], outputs
+ *     Y[rows][out] (Y = X W^T, Section "Integration into Transformer
+ *     Architecture").  A row of X has exactly `in` elements; positions
+ *     in .. nchunks*v-1 of the last chunk are logical zeros and are never read.
+ */
+#ifndef BTC_H_
+#define BTC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  BTC_OK = 0,
+  BTC_ERR_NULL = -1,         /* a required pointer is NULL                       */
+  BTC_ERR_SHAPE = -2,        /* inconsistent or non-positive sizes               */
+  BTC_ERR_UNSUPPORTED = -3,  /* v, K, batch or dtype outside the supported range */
+  BTC_ERR_ALIGN = -4,        /* pointer not 16-byte aligned                      */
+  BTC_ERR_INDEX_RANGE = -5,  /* btc_pack met an index outside [0, K)             */
+  BTC_ERR_HIP = -6,          /* a HIP runtime call failed                        */
+  BTC_ERR_WORKSPACE = -7     /* workspace missing or too small                   */
+} btc_status;
+
+typedef enum { BTC_F16 = 0, BTC_BF16 = 1, BTC_F32 = 2 } btc_dtype;
+
+/* One packed layer.  Plain data, filled by btc_shape_init. */
+typedef struct {
+  int32_t out;            /* weight rows    = length of y                          */
+  int32_t in;             /* weight columns = length of x                          */
+  int32_t v;              /* chunk (sub-vector) length, 1..32                      */
+  int32_t K;              /* codebook entries, 2..65536                            */
+  int32_t b;              /* index width ceil(log2 K), 1..16                       */
+  int32_t nchunks;        /* ceil(in / v) chunks per row                           */
+  int32_t words_per_row;  /* ceil(nchunks*b / 32): row stride of `packed`, uint32  */
+} btc_shape;
+
+/* Host. Fill *s from (out, in, v, K).  BTC_ERR_SHAPE for non-positive sizes,
+ * BTC_ERR_UNSUPPORTED for v > 32 or K outside 2..65536. */
+btc_status btc_shape_init(btc_shape* s, int32_t out, int32_t in, int32_t v, int32_t K);
+
+/* Host. Bytes of the packed index stream, out * words_per_row * 4
+ * (Compression Analysis: ceil(log2 c) bits per vector, here padded so that
+ * every row starts on a 32-bit word). 0 if s is NULL. */
+size_t btc_packed_bytes(const btc_shape* s);
+
+/* Host. Bytes of workspace the call would need: rows = batch for btc_gemv
+ * (is_gemm = 0), rows = M for btc_gemm (is_gemm != 0).  Always >= 16 so that
+ * one buffer serves btc_pack too. */
+size_t btc_workspace_bytes(const btc_shape* s, int32_t rows, int is_gemm);
+
+/* Index matrix -> bit stream (Compression Analysis; storage format of the
+ * index matrix I in appendix "Binary Codebook LUT-GEMM").
+ *   idx    : int32 [out][nchunks]
+ *   packed : uint32 [out][words_per_row]; index j of row i occupies bits
+ *            [j*b, (j+1)*b) of row i's stream, bit p of the stream being bit
+ *            (p & 31) of word (p >> 5); unused tail bits are written as 0.
+ *   workspace : >= 16 bytes, receives a range-check flag.
+ * Waits for the stream: returns BTC_ERR_INDEX_RANGE if any index is outside
+ * [0, K) (packed is then unspecified). */
+btc_status btc_pack(void* stream, const btc_shape* s, const int32_t* idx, uint32_t* packed,
+                    void* workspace, size_t workspace_bytes);
+
+/* Bit stream -> index matrix; exact inverse of btc_pack. Enqueues and returns. */
+btc_status btc_unpack(void* stream, const btc_shape* s, const uint32_t* packed, int32_t* idx);
+
+/* Decode-time product for a few activation rows (appendix "Binary Codebook
+ * LUT-GEMM": y_r = sum_j <x_j, C[I_rj]>; dequantisation alpha * B_hat + mu):
+ *   y[m][i] = alpha[i] * sum_j <x[m] chunk j, C[idx[i][j]]> + mu[i] * sum_k x[m][k]
+ *   packed   : uint32 [out][words_per_row]    codebook : uint32 [2^b] (entries
+ *              K .. 2^b-1 must be readable; bit t of entry k = element t, 1 => +1)
+ *   alpha,mu : float [out]
+ *   x        : fp16 [batch][in], batch 1..16
+ *   y        : [batch][out] of y_dtype (BTC_F16 or BTC_F32, round to nearest even)
+ * Accumulates in fp32.  A stored index >= K reads codebook[index] inside the
+ * 2^b-entry table. */
+btc_status btc_gemv(void* stream, const btc_shape* s, const uint32_t* packed,
+                    const uint32_t* codebook, const float* alpha, const float* mu,
+                    const void* x, int32_t batch, void* y, btc_dtype y_dtype,
+                    void* workspace, size_t workspace_bytes);
+
+/* Prefill product for many activation rows; same definition as btc_gemv with
+ *   X : [M][in] of x_dtype (BTC_BF16 or BTC_F16), M >= 1
+ *   Y : [M][out] of y_dtype (BTC_F32, BTC_BF16 or BTC_F16)
+ * The +-1 patterns are decoded into LDS tiles and contracted on the matrix
+ * cores with fp32 accumulation; alpha and mu are applied in fp32 afterwards.
+ * Needs btc_workspace_bytes(s, M, 1) bytes of workspace. */
+btc_status btc_gemm(void* stream, const btc_shape* s, const uint32_t* packed,
+                    const uint32_t* codebook, const float* alpha, const float* mu,
+                    const void* X, btc_dtype x_dtype, int32_t M, void* Y, btc_dtype y_dtype,
+                    void* workspace, size_t workspace_bytes);
+
+/* Host. Static string for a status code. */
+const char* btc_status_str(btc_status st);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BTC_H_ */

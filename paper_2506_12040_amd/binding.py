@@ -1,0 +1,130 @@
+"""Thin ctypes binding of libbtc_hip.so: same names as include/btc.h, argument
+marshalling only.  Tensors are torch CUDA(HIP) tensors used purely as device
+buffers; every step of the computation runs in the library's kernels.  There
+is no CPU fallback: a missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(PKG, "libbtc_hip.so")
+
+BTC_OK = 0
+BTC_ERR_NULL, BTC_ERR_SHAPE, BTC_ERR_UNSUPPORTED, BTC_ERR_ALIGN = -1, -2, -3, -4
+BTC_ERR_INDEX_RANGE, BTC_ERR_HIP, BTC_ERR_WORKSPACE = -5, -6, -7
+BTC_F16, BTC_BF16, BTC_F32 = 0, 1, 2
+
+
+class btc_shape(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("out", "in_", "v", "K", "b", "nchunks", "words_per_row")]
+
+
+class BtcError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        super().__init__(f"{what}: {status_str(status)} ({status})")
+        self.status = status
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load the built library; raise if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run paper_2506_12040_amd.build.build() "
+                               "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        sp = ctypes.POINTER(btc_shape)
+        L.btc_shape_init.restype = ctypes.c_int
+        L.btc_shape_init.argtypes = [sp, i32, i32, i32, i32]
+        L.btc_packed_bytes.restype = sz
+        L.btc_packed_bytes.argtypes = [sp]
+        L.btc_workspace_bytes.restype = sz
+        L.btc_workspace_bytes.argtypes = [sp, i32, ctypes.c_int]
+        L.btc_pack.restype = ctypes.c_int
+        L.btc_pack.argtypes = [vp, sp, vp, vp, vp, sz]
+        L.btc_unpack.restype = ctypes.c_int
+        L.btc_unpack.argtypes = [vp, sp, vp, vp]
+        L.btc_gemv.restype = ctypes.c_int
+        L.btc_gemv.argtypes = [vp, sp, vp, vp, vp, vp, vp, i32, vp, ctypes.c_int, vp, sz]
+        L.btc_gemm.restype = ctypes.c_int
+        L.btc_gemm.argtypes = [vp, sp, vp, vp, vp, vp, vp, ctypes.c_int, i32, vp, ctypes.c_int, vp, sz]
+        L.btc_status_str.restype = ctypes.c_char_p
+        L.btc_status_str.argtypes = [ctypes.c_int]
+        _lib = L
+    return _lib
+
+
+def status_str(status: int) -> str:
+    return lib().btc_status_str(int(status)).decode()
+
+
+def _ptr(t) -> ctypes.c_void_p:
+    """Device (or host) address of a torch tensor, a raw int address, or None."""
+    if t is None:
+        return ctypes.c_void_p(0)
+    if isinstance(t, int):
+        return ctypes.c_void_p(t)
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        import torch
+        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return ctypes.c_void_p(stream)
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _nbytes(t) -> int:
+    return 0 if t is None or isinstance(t, int) else t.numel() * t.element_size()
+
+
+def _check(status: int, what: str) -> None:
+    if status != BTC_OK:
+        raise BtcError(status, what)
+
+
+def btc_shape_init(out: int, n_in: int, v: int, K: int) -> btc_shape:
+    s = btc_shape()
+    _check(lib().btc_shape_init(ctypes.byref(s), out, n_in, v, K), "btc_shape_init")
+    return s
+
+
+def btc_packed_bytes(s: btc_shape) -> int:
+    return lib().btc_packed_bytes(ctypes.byref(s))
+
+
+def btc_workspace_bytes(s: btc_shape, rows: int, is_gemm: bool) -> int:
+    return lib().btc_workspace_bytes(ctypes.byref(s), rows, int(is_gemm))
+
+
+def btc_pack(s: btc_shape, idx, packed, workspace, stream=None, workspace_bytes: Optional[int] = None) -> None:
+    wb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
+    _check(lib().btc_pack(_stream(stream), ctypes.byref(s), _ptr(idx), _ptr(packed), _ptr(workspace), wb),
+           "btc_pack")
+
+
+def btc_unpack(s: btc_shape, packed, idx, stream=None) -> None:
+    _check(lib().btc_unpack(_stream(stream), ctypes.byref(s), _ptr(packed), _ptr(idx)), "btc_unpack")
+
+
+def btc_gemv(s: btc_shape, packed, codebook, alpha, mu, x, batch: int, y, y_dtype: int,
+             workspace=None, stream=None, workspace_bytes: Optional[int] = None) -> None:
+    wb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
+    _check(lib().btc_gemv(_stream(stream), ctypes.byref(s), _ptr(packed), _ptr(codebook), _ptr(alpha), _ptr(mu),
+                          _ptr(x), batch, _ptr(y), y_dtype, _ptr(workspace), wb), "btc_gemv")
+
+
+def btc_gemm(s: btc_shape, packed, codebook, alpha, mu, X, x_dtype: int, M: int, Y, y_dtype: int,
+             workspace=None, stream=None, workspace_bytes: Optional[int] = None) -> None:
+    wb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
+    _check(lib().btc_gemm(_stream(stream), ctypes.byref(s), _ptr(packed), _ptr(codebook), _ptr(alpha), _ptr(mu),
+                          _ptr(X), x_dtype, M, _ptr(Y), y_dtype, _ptr(workspace), wb), "btc_gemm")

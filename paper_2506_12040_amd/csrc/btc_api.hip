@@ -1,0 +1,65 @@
+// Host-side entry points that touch no device memory: shape arithmetic,
+// byte counts, status strings.  (Storage format: Section "Compression
+// Analysis" -- ceil(log2 c) index bits per length-v vector.)
+#include "btc_internal.h"
+
+namespace btc {
+
+static int ceil_log2(int K) {
+  int b = 0;
+  while ((1 << b) < K) ++b;
+  return b;
+}
+
+btc_status check_shape(const btc_shape* s) {
+  if (!s) return BTC_ERR_NULL;
+  btc_shape t;
+  btc_status st = btc_shape_init(&t, s->out, s->in, s->v, s->K);
+  if (st != BTC_OK) return st;
+  if (t.b != s->b || t.nchunks != s->nchunks || t.words_per_row != s->words_per_row) return BTC_ERR_SHAPE;
+  return BTC_OK;
+}
+
+}  // namespace btc
+
+extern "C" {
+
+btc_status btc_shape_init(btc_shape* s, int32_t out, int32_t in, int32_t v, int32_t K) {
+  if (!s) return BTC_ERR_NULL;
+  if (out <= 0 || in <= 0 || v <= 0 || K <= 0) return BTC_ERR_SHAPE;
+  if (v > 32 || K < 2 || K > 65536) return BTC_ERR_UNSUPPORTED;
+  const int64_t nchunks = ((int64_t)in + v - 1) / v;
+  const int b = btc::ceil_log2(K);
+  const int64_t wpr = (nchunks * b + 31) / 32;
+  // element counts are kept below 2^31 so that int indexing inside kernels is safe per row
+  if ((int64_t)out * wpr >= ((int64_t)1 << 40)) return BTC_ERR_UNSUPPORTED;
+  s->out = out;
+  s->in = in;
+  s->v = v;
+  s->K = K;
+  s->b = b;
+  s->nchunks = (int32_t)nchunks;
+  s->words_per_row = (int32_t)wpr;
+  return BTC_OK;
+}
+
+size_t btc_packed_bytes(const btc_shape* s) {
+  if (!s) return 0;
+  return (size_t)s->out * (size_t)s->words_per_row * sizeof(uint32_t);
+}
+
+const char* btc_status_str(btc_status st) {
+  switch (st) {
+    case BTC_OK: return "ok";
+    case BTC_ERR_NULL: return "null pointer";
+    case BTC_ERR_SHAPE: return "bad shape";
+    case BTC_ERR_UNSUPPORTED: return "unsupported v, K, batch or dtype";
+    case BTC_ERR_ALIGN: return "pointer not 16-byte aligned";
+    case BTC_ERR_INDEX_RANGE: return "index outside [0, K)";
+    case BTC_ERR_HIP: return "HIP runtime error";
+    case BTC_ERR_WORKSPACE: return "workspace missing or too small";
+  }
+  return "unknown status";
+}
+
+}  // extern "C"

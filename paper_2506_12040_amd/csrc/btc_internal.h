@@ -1,0 +1,38 @@
+// Internal helpers shared by the HIP translation units of the library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "btc.h"
+
+namespace btc {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Shape as the kernels see it (passed by value).
+struct Dims {
+  int out, in, v, K, b, nchunks, wpr;
+};
+
+inline Dims dims_of(const btc_shape& s) {
+  return Dims{s.out, s.in, s.v, s.K, s.b, s.nchunks, s.words_per_row};
+}
+
+// Re-derive the dependent fields and compare: a shape that was not produced by
+// btc_shape_init (or was edited afterwards) is rejected before any launch.
+btc_status check_shape(const btc_shape* s);
+
+inline btc_status launch_status() {
+  return hipGetLastError() == hipSuccess ? BTC_OK : BTC_ERR_HIP;
+}
+
+// Extract the b-bit field that starts at bit p of a row's LSB-first stream.
+// Never reads word index >= wpr.
+__device__ __forceinline__ uint32_t field_at(const uint32_t* __restrict__ row, int wpr, int p, int b) {
+  const int w = p >> 5, s = p & 31;
+  uint64_t lo = row[w];
+  if (s + b > 32 && w + 1 < wpr) lo |= (uint64_t)row[w + 1] << 32;
+  return (uint32_t)(lo >> s) & ((1u << b) - 1u);
+}
+
+}  // namespace btc

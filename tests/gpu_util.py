@@ -1,0 +1,92 @@
+"""Helpers for the GPU parity tests: move a synthetic layer to the device, call
+the C-ABI through the binding, fetch results, compare with the oracle."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import paper_2506_12040_amd as B
+
+REL_L2_TOL = 2e-3       # ||y - y*||_2 / ||y*||_2
+MAX_ABS_TOL = 1e-2      # max|y - y*| / max|y*|
+GUARD = 64              # guard elements on either side of an output buffer
+
+
+def dev(a: np.ndarray) -> torch.Tensor:
+    """numpy -> device tensor with the same bytes (uint16/uint32 via int views)."""
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint32:
+        return torch.from_numpy(a.view(np.int32)).cuda()
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).cuda()
+    return torch.from_numpy(a).cuda()
+
+
+class DeviceLayer:
+    def __init__(self, layer, oracle):
+        self.layer = layer
+        self.shape = B.btc_shape_init(layer.out, layer.n_in, layer.v, layer.K)
+        self.packed_host = oracle.pack(layer.idx, layer.K)
+        self.packed = dev(self.packed_host)
+        cb = np.zeros(1 << self.shape.b, dtype=np.uint32)
+        cb[: layer.K] = layer.codebook
+        self.codebook_host = cb
+        self.codebook = dev(cb)
+        self.alpha = dev(layer.alpha)
+        self.mu = dev(layer.mu)
+
+
+class GuardedOutput:
+    """Output buffer with canary bands before and after the payload."""
+
+    def __init__(self, rows: int, cols: int, dtype: torch.dtype):
+        self.rows, self.cols = rows, cols
+        n = rows * cols
+        self.canary = 12345.0 if dtype != torch.int32 else 0x5A5A5A5A
+        self.buf = torch.full((n + 2 * GUARD,), self.canary, dtype=dtype, device="cuda")
+        self.payload = self.buf[GUARD:GUARD + n]
+        assert self.payload.data_ptr() % 16 == 0
+
+    def check_guards(self):
+        torch.cuda.synchronize()
+        head = self.buf[:GUARD].cpu()
+        tail = self.buf[GUARD + self.rows * self.cols:].cpu()
+        assert bool((head == self.canary).all()) and bool((tail == self.canary).all()), "guard band overwritten"
+
+    def numpy(self) -> np.ndarray:
+        return self.payload.float().cpu().numpy().astype(np.float64).reshape(self.rows, self.cols)
+
+
+def gemv(dl: DeviceLayer, x_bits: np.ndarray, y_dtype: int = B.BTC_F16) -> np.ndarray:
+    batch = x_bits.shape[0]
+    x = dev(x_bits)
+    y = GuardedOutput(batch, dl.layer.out, torch.float16 if y_dtype == B.BTC_F16 else torch.float32)
+    ws = torch.zeros(max(16, B.btc_workspace_bytes(dl.shape, batch, False)), dtype=torch.uint8, device="cuda")
+    B.btc_gemv(dl.shape, dl.packed, dl.codebook, dl.alpha, dl.mu, x, batch, y.payload, y_dtype, ws)
+    y.check_guards()
+    return y.numpy()
+
+
+_TORCH_OF = {B.BTC_F16: torch.float16, B.BTC_BF16: torch.bfloat16, B.BTC_F32: torch.float32}
+
+
+def gemm(dl: DeviceLayer, x_bits: np.ndarray, x_dtype: int, y_dtype: int = B.BTC_F32) -> np.ndarray:
+    M = x_bits.shape[0]
+    X = dev(x_bits)
+    Y = GuardedOutput(M, dl.layer.out, _TORCH_OF[y_dtype])
+    ws = torch.zeros(B.btc_workspace_bytes(dl.shape, M, True), dtype=torch.uint8, device="cuda")
+    B.btc_gemm(dl.shape, dl.packed, dl.codebook, dl.alpha, dl.mu, X, x_dtype, M, Y.payload, y_dtype, ws)
+    Y.check_guards()
+    return Y.numpy()
+
+
+def assert_close(y: np.ndarray, y_ref: np.ndarray, what: str = ""):
+    assert y.shape == y_ref.shape, (y.shape, y_ref.shape)
+    assert np.all(np.isfinite(y)), what
+    denom = np.linalg.norm(y_ref)
+    rel = np.linalg.norm(y - y_ref) / denom if denom > 0 else np.linalg.norm(y)
+    mx = np.max(np.abs(y_ref))
+    mabs = np.max(np.abs(y - y_ref)) / mx if mx > 0 else np.max(np.abs(y))
+    assert rel <= REL_L2_TOL, f"{what}: rel L2 {rel:.3e} > {REL_L2_TOL}"
+    assert mabs <= MAX_ABS_TOL, f"{what}: max abs {mabs:.3e} > {MAX_ABS_TOL}"
+    return rel, mabs

@@ -1,0 +1,103 @@
+"""Host-side checks of the C-ABI library: it loads, exports every function
+that include/btc.h declares, and its host-only entry points and argument
+checks behave as documented.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import btc_synth as S
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    import paper_2506_12040_amd as B
+    if not os.path.exists(B.binding.LIB_PATH):
+        from paper_2506_12040_amd import build
+        build.build()
+    return B
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "btc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(btc_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(B):
+    names = declared_functions()
+    assert {"btc_pack", "btc_unpack", "btc_gemv", "btc_gemm", "btc_shape_init", "btc_packed_bytes",
+            "btc_workspace_bytes", "btc_status_str"} <= set(names)
+    L = B.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_binding_has_the_same_names(B):
+    for n in declared_functions():
+        if n == "btc_status_str":
+            continue
+        assert hasattr(B.binding, n), n
+
+
+@pytest.mark.parametrize("out,n_in,v,K", [(4096, 4096, 10, 512), (11008, 4096, 10, 512), (4096, 11008, 10, 512),
+                                          (5120, 13824, 10, 256), (8192, 28672, 9, 1024), (8192, 8192, 10, 128),
+                                          (7, 33, 4, 9), (3, 100, 20, 65536), (5, 17, 32, 2)])
+def test_shape_arithmetic_matches_recipe(B, out, n_in, v, K):
+    s = B.btc_shape_init(out, n_in, v, K)
+    assert (s.out, s.in_, s.v, s.K) == (out, n_in, v, K)
+    assert s.b == S.index_bits(K) and s.nchunks == S.num_chunks(n_in, v)
+    assert s.words_per_row == S.words_per_row(n_in, v, K)
+    assert B.btc_packed_bytes(s) == out * s.words_per_row * 4
+    assert B.btc_workspace_bytes(s, 1, False) >= 16
+    assert B.btc_workspace_bytes(s, 512, True) >= 16 + 512 * 4
+
+
+def test_shape_errors(B):
+    for args, code in [((0, 8, 4, 4), B.binding.BTC_ERR_SHAPE), ((8, -1, 4, 4), B.binding.BTC_ERR_SHAPE),
+                       ((8, 8, 0, 4), B.binding.BTC_ERR_SHAPE), ((8, 8, 33, 4), B.binding.BTC_ERR_UNSUPPORTED),
+                       ((8, 8, 4, 1), B.binding.BTC_ERR_UNSUPPORTED), ((8, 8, 4, 65537), B.binding.BTC_ERR_UNSUPPORTED)]:
+        with pytest.raises(B.BtcError) as e:
+            B.btc_shape_init(*args)
+        assert e.value.status == code
+    assert B.lib().btc_shape_init(None, 1, 1, 1, 2) == B.binding.BTC_ERR_NULL
+    assert B.lib().btc_packed_bytes(None) == 0
+
+
+def test_status_strings(B):
+    seen = set()
+    for code in range(0, -8, -1):
+        s = B.status_str(code)
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 8 and B.status_str(-99) == "unknown status"
+
+
+def test_argument_checks_need_no_gpu(B):
+    """NULL, tampered shapes, unsupported batch/dtype and misalignment are
+    rejected before anything is enqueued, so these calls are safe without a GPU."""
+    L = B.lib()
+    s = B.btc_shape_init(64, 100, 10, 512)
+    sp = ctypes.byref(s)
+    fake = ctypes.c_void_p(0x1000)       # aligned, never dereferenced by a rejected call
+    odd = ctypes.c_void_p(0x1004)
+    E = B.binding
+    assert L.btc_gemv(None, sp, None, fake, fake, fake, fake, 1, fake, E.BTC_F16, None, 0) == E.BTC_ERR_NULL
+    assert L.btc_gemv(None, sp, fake, fake, fake, fake, fake, 0, fake, E.BTC_F16, None, 0) == E.BTC_ERR_UNSUPPORTED
+    assert L.btc_gemv(None, sp, fake, fake, fake, fake, fake, 17, fake, E.BTC_F16, None, 0) == E.BTC_ERR_UNSUPPORTED
+    assert L.btc_gemv(None, sp, fake, fake, fake, fake, fake, 1, fake, E.BTC_BF16, None, 0) == E.BTC_ERR_UNSUPPORTED
+    assert L.btc_gemv(None, sp, odd, fake, fake, fake, fake, 1, fake, E.BTC_F16, None, 0) == E.BTC_ERR_ALIGN
+    assert L.btc_gemm(None, sp, fake, fake, fake, fake, fake, E.BTC_BF16, 0, fake, E.BTC_F32, fake, 1 << 20) == E.BTC_ERR_SHAPE
+    assert L.btc_gemm(None, sp, fake, fake, fake, fake, fake, E.BTC_F32, 8, fake, E.BTC_F32, fake, 1 << 20) == E.BTC_ERR_UNSUPPORTED
+    assert L.btc_gemm(None, sp, fake, fake, fake, fake, fake, E.BTC_BF16, 8, fake, E.BTC_F32, fake, 8) == E.BTC_ERR_WORKSPACE
+    assert L.btc_gemm(None, sp, fake, fake, fake, fake, fake, E.BTC_BF16, 8, fake, E.BTC_F32, None, 0) == E.BTC_ERR_WORKSPACE
+    assert L.btc_pack(None, sp, fake, fake, None, 0) == E.BTC_ERR_WORKSPACE
+    assert L.btc_pack(None, sp, None, fake, fake, 16) == E.BTC_ERR_NULL
+    assert L.btc_unpack(None, sp, fake, odd) == E.BTC_ERR_ALIGN
+    assert L.btc_unpack(None, None, fake, fake) == E.BTC_ERR_NULL
+    t = B.btc_shape_init(64, 100, 10, 512)
+    t.words_per_row += 1                 # a shape edited after btc_shape_init
+    assert L.btc_unpack(None, ctypes.byref(t), fake, fake) == E.BTC_ERR_SHAPE

@@ -1,0 +1,192 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle
+on the same seeded inputs.  Integer work (pack/unpack) must match bit for bit;
+float outputs must satisfy  ||y-y*||_2/||y*||_2 <= 2e-3  and
+max|y-y*| <= 1e-2 max|y*|  per call."""
+import numpy as np
+import pytest
+
+import btc_synth as S
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def G():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import gpu_util
+    return gpu_util
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------ pack / unpack
+PACK_SHAPES = [(64, 100, 10, 512), (33, 4096, 10, 512), (17, 11008, 10, 512), (40, 5120, 10, 256),
+               (9, 8192, 9, 1024), (21, 8192, 10, 128), (5, 37, 3, 8), (12, 333, 4, 9), (3, 250, 20, 65536),
+               (7, 64, 32, 2), (11, 130, 16, 7132), (1, 1, 1, 2)]
+
+
+@pytest.mark.parametrize("out,n_in,v,K", PACK_SHAPES)
+def test_pack_unpack_bit_exact(G, oracle, out, n_in, v, K):
+    import torch
+    B = G.B
+    say(f"pack/unpack out={out} in={n_in} v={v} K={K}")
+    rng = np.random.default_rng(out * 31 + n_in)
+    s = B.btc_shape_init(out, n_in, v, K)
+    idx = rng.integers(0, K, size=(out, s.nchunks), dtype=np.int32)
+    idx[0, :] = K - 1
+    idx[-1, -1] = K - 1
+    ref = oracle.pack(idx, K)
+    packed = G.GuardedOutput(out, s.words_per_row, torch.int32)
+    ws = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    B.btc_pack(s, G.dev(idx), packed.payload, ws)
+    packed.check_guards()
+    got = packed.payload.cpu().numpy().view(np.uint32).reshape(out, s.words_per_row)
+    assert np.array_equal(got, ref)
+    back = G.GuardedOutput(out, s.nchunks, torch.int32)
+    B.btc_unpack(s, G.dev(ref), back.payload)
+    back.check_guards()
+    assert np.array_equal(back.payload.cpu().numpy().reshape(out, s.nchunks), idx)
+    assert np.array_equal(oracle.unpack(got, s.nchunks, K), idx)
+
+
+def test_pack_rejects_out_of_range_index(G):
+    import torch
+    B = G.B
+    s = B.btc_shape_init(8, 100, 10, 500)          # b = 9: 500..511 fit the field but are invalid
+    ws = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    packed = torch.zeros(8 * s.words_per_row, dtype=torch.int32, device="cuda")
+    for bad in (500, 511, 512, -1, 1 << 20):
+        idx = np.zeros((8, s.nchunks), dtype=np.int32)
+        idx[5, 7] = bad
+        with pytest.raises(B.BtcError) as e:
+            B.btc_pack(s, G.dev(idx), packed, ws)
+        assert e.value.status == B.binding.BTC_ERR_INDEX_RANGE
+    idx = np.full((8, s.nchunks), 499, dtype=np.int32)
+    B.btc_pack(s, G.dev(idx), packed, ws)          # and the flag is cleared on the next call
+
+
+# ------------------------------------------------------------------------- GEMV
+GEMV_SMALL = [
+    # out, in, v, K, batch, dist
+    (300, 4096, 10, 512, 1, "uniform"), (260, 1101 * 10 - 2, 10, 512, 1, "uniform"),
+    (129, 5120, 10, 256, 1, "zipf"), (70, 13824, 10, 256, 1, "zipf"),
+    (200, 8192, 9, 1024, 1, "uniform"), (200, 8192, 10, 128, 1, "uniform"),
+    (67, 1000, 10, 512, 2, "uniform"), (67, 1003, 10, 512, 3, "uniform"), (130, 2049, 10, 512, 4, "uniform"),
+    (65, 777, 10, 256, 5, "uniform"), (96, 4096, 10, 512, 16, "uniform"),
+    (50, 333, 4, 9, 1, "uniform"), (31, 260, 8, 85, 2, "uniform"), (20, 250, 20, 65536, 1, "uniform"),
+    (9, 640, 32, 2, 1, "uniform"), (1, 10, 10, 512, 1, "uniform"), (5, 3, 10, 4, 1, "uniform"),
+    (40, 330, 16, 7132, 4, "uniform"), (64, 96, 12, 777, 16, "uniform"),
+]
+
+
+@pytest.mark.parametrize("out,n_in,v,K,batch,dist", GEMV_SMALL)
+@pytest.mark.parametrize("y_f32", [False, True])
+def test_gemv_small_full_compare(G, oracle, out, n_in, v, K, batch, dist, y_f32):
+    B = G.B
+    say(f"gemv small out={out} in={n_in} v={v} K={K} batch={batch} {dist} f32={y_f32}")
+    layer, x = S.make_case(7, out, n_in, v, K, batch, dist=dist, outlier_frac=0.01 if batch > 1 else 0.0)
+    dl = G.DeviceLayer(layer, oracle)
+    y = G.gemv(dl, x, B.BTC_F32 if y_f32 else B.BTC_F16)
+    y_ref = oracle.linear(dl.packed_host, dl.codebook_host, layer.alpha, layer.mu, x, n_in, v, K)
+    G.assert_close(y, y_ref, "gemv")
+    y2 = G.gemv(dl, x, B.BTC_F32 if y_f32 else B.BTC_F16)
+    assert np.array_equal(y, y2), "two runs differ"
+
+
+def _full_size_gemv(G, oracle, case, n_sample=384):
+    B = G.B
+    say(f"gemv full {case}")
+    layer, x = S.make_case(**case)
+    dl = G.DeviceLayer(layer, oracle)
+    y = G.gemv(dl, x, B.BTC_F16)
+    rng = np.random.default_rng(1)
+    rows = np.unique(np.concatenate([[0, 1, layer.out - 2, layer.out - 1],
+                                     rng.choice(layer.out, size=min(n_sample, layer.out), replace=False)]))
+    y_ref = oracle.linear(dl.packed_host, dl.codebook_host, layer.alpha, layer.mu, x, layer.n_in, layer.v,
+                          layer.K, rows=rows)
+    G.assert_close(y[:, rows], y_ref, f"gemv {case}")
+    assert np.all(np.isfinite(y))
+
+
+@pytest.mark.parametrize("case", S.config_cases(0) + S.config_cases(2), ids=lambda c: f"{c['out']}x{c['n_in']}")
+def test_gemv_config_0_and_2_full_size(G, oracle, case):
+    _full_size_gemv(G, oracle, case)
+
+
+@pytest.mark.parametrize("case", S.config_cases(1), ids=lambda c: f"{c['out']}x{c['n_in']}b{c['batch']}")
+def test_gemv_config_1_full_size(G, oracle, case):
+    _full_size_gemv(G, oracle, case)
+
+
+@pytest.mark.parametrize("case", S.config_cases(4),
+                         ids=lambda c: f"{c['out']}x{c['n_in']}v{c['v']}K{c['K']}")
+def test_gemv_config_4_full_size(G, oracle, case):
+    _full_size_gemv(G, oracle, case, n_sample=192)
+
+
+def test_gemv_invariants_on_gpu(G, oracle):
+    """Full codebook and ones vector, evaluated by the HIP path itself."""
+    B = G.B
+    v, out, n_in = 10, 128, 1000
+    K = 1 << v
+    rng = np.random.default_rng(2)
+    Sg = np.where(rng.normal(size=(out, n_in)) >= 0, 1.0, -1.0)
+    bits = (Sg > 0).astype(np.int64).reshape(out, n_in // v, v)
+    idx = (bits << np.arange(v)).sum(axis=2).astype(np.int32)
+    layer = S.Layer(out, n_in, v, K, np.arange(K, dtype=np.uint32), idx,
+                    np.ones(out, np.float32), np.zeros(out, np.float32))
+    dl = G.DeviceLayer(layer, oracle)
+    xi = rng.integers(-4, 5, size=(1, n_in)).astype(np.float16)
+    y = G.gemv(dl, xi.view(np.uint16), B.BTC_F32)
+    assert np.array_equal(y, (xi.astype(np.float64) @ Sg.T))         # small integers: exact in fp32
+    ones = np.ones((1, n_in), np.float16)
+    y1 = G.gemv(dl, ones.view(np.uint16), B.BTC_F32)
+    assert np.array_equal(y1[0], Sg.sum(axis=1))
+
+
+# ------------------------------------------------------------------------- GEMM
+GEMM_SMALL = [
+    # out, in, v, K, M, x_dtype
+    (256, 640, 10, 256, 128, "bf16"), (300, 1000, 10, 256, 200, "bf16"), (130, 1283, 10, 512, 65, "bf16"),
+    (128, 5120, 10, 256, 256, "bf16"), (140, 810, 9, 1024, 130, "bf16"), (64, 700, 10, 128, 17, "f16"),
+    (100, 333, 4, 9, 33, "bf16"), (90, 512, 16, 7132, 40, "f16"), (70, 250, 20, 65536, 9, "bf16"),
+    (33, 640, 32, 2, 5, "bf16"), (50, 231, 7, 100, 3, "f16"), (1, 10, 10, 512, 1, "bf16"),
+]
+
+
+@pytest.mark.parametrize("out,n_in,v,K,M,xd", GEMM_SMALL)
+def test_gemm_small_full_compare(G, oracle, out, n_in, v, K, M, xd):
+    B = G.B
+    say(f"gemm small out={out} in={n_in} v={v} K={K} M={M} {xd}")
+    layer, x = S.make_case(9, out, n_in, v, K, M, x_dtype=xd)
+    dl = G.DeviceLayer(layer, oracle)
+    xk = B.BTC_BF16 if xd == "bf16" else B.BTC_F16
+    y_ref = oracle.linear(dl.packed_host, dl.codebook_host, layer.alpha, layer.mu, x, n_in, v, K, x_kind=xd)
+    for yd in (B.BTC_F32, B.BTC_BF16 if xd == "bf16" else B.BTC_F16):
+        y = G.gemm(dl, x, xk, yd)
+        if yd == B.BTC_BF16:       # bf16 output rounding alone is 2^-9 relative per element
+            rel = np.linalg.norm(y - y_ref) / np.linalg.norm(y_ref)
+            assert rel <= 4e-3
+        else:
+            G.assert_close(y, y_ref, "gemm")
+    y2 = G.gemm(dl, x, xk, B.BTC_F32)
+    y3 = G.gemm(dl, x, xk, B.BTC_F32)
+    assert np.array_equal(y2, y3), "two runs differ"
+
+
+@pytest.mark.parametrize("case", S.config_cases(3), ids=lambda c: f"{c['out']}x{c['n_in']}M{c['batch']}")
+def test_gemm_config_3_full_size(G, oracle, case):
+    B = G.B
+    say(f"gemm full {case}")
+    layer, x = S.make_case(**case)
+    dl = G.DeviceLayer(layer, oracle)
+    y = G.gemm(dl, x, B.BTC_BF16, B.BTC_F32)
+    assert np.all(np.isfinite(y))
+    rng = np.random.default_rng(3)
+    rows = np.unique(np.concatenate([[0, layer.out - 1], rng.choice(layer.out, size=96, replace=False)]))
+    y_ref = oracle.linear(dl.packed_host, dl.codebook_host, layer.alpha, layer.mu, x, layer.n_in, layer.v,
+                          layer.K, x_kind="bf16", rows=rows)
+    G.assert_close(y[:, rows], y_ref, f"gemm {case}")
