@@ -1,0 +1,260 @@
+#!/usr/bin/env python3
+"""Benchmark of the binary-codebook linear layer on one MI355X.
+
+Workload (BASELINE.json: "btc_gemv effective weight GB/s + us/call (13B shapes,
+0.8-bit); GEMM TFLOP/s"): the seven linear projections of a LLaMA-2-13B decoder
+layer (4 x 5120x5120, 2 x 13824x5120, 1 x 5120x13824) stored at v=10, K=256
+(8-bit indices, 0.8 bit/weight), Zipf(1.1) indices, batch-1 fp16 activations.
+
+One STEP = one decoder layer = 7 btc_gemv calls.  Consecutive steps walk
+through `--layers` distinct copies of the packed weights (40 copies = 1.27 GB,
+five times the 256 MB last-level cache), so every call streams its indices from
+HBM ("cold").  value = algorithmic bytes of a step / time of a step.  All
+inputs are resident in HBM before the timed region.  The launches of one
+sweep over all copies are captured once in a HIP graph (the calls still go
+through the C ABI, which only enqueues kernels) so that Python's per-call
+overhead is not what is timed; --mode stream times plain per-call launches.
+
+Also reported: prefill btc_gemm TFLOP/s on the same shapes (M = --gemm-m), a
+roofline object for the GEMV, and the CPU oracle timed on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+SHAPES_13B = [(5120, 5120, 4), (13824, 5120, 2), (5120, 13824, 1)]   # (out, in, count per layer)
+V, K = 10, 256
+
+
+def gemv_bytes(s, batch, y_bytes=2):
+    """Algorithmic bytes of one call: index stream + alpha, mu + x + y + codebook."""
+    return s.out * s.words_per_row * 4 + s.out * 8 + batch * s.in_ * 2 + batch * s.out * y_bytes + (1 << s.b) * 4
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--layers", type=int, default=40, help="distinct weight copies walked by consecutive steps")
+    ap.add_argument("--mode", choices=["graph", "stream"], default="graph")
+    ap.add_argument("--gemm-m", type=int, default=2048)
+    ap.add_argument("--gemm-iters", type=int, default=5)
+    ap.add_argument("--no-gemm", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (--gpus 1); nothing here uses a second GPU", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import btc_synth as S
+    import paper_2506_12040_amd as B
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    B.lib()  # raises if the HIP library was not built
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    # ---- one seeded layer per shape, packed on the GPU through btc_pack
+    t_setup = time.time()
+    protos = []
+    for (out, n_in, count) in SHAPES_13B:
+        layer, x = S.make_case(0, out, n_in, V, K, 1, dist="zipf")
+        s = B.btc_shape_init(out, n_in, V, K)
+        idx_d = torch.from_numpy(layer.idx).to(dev)
+        packed = torch.empty(out * s.words_per_row, dtype=torch.int32, device=dev)
+        ws = torch.zeros(64, dtype=torch.uint8, device=dev)
+        B.btc_pack(s, idx_d, packed, ws)
+        cb = np.zeros(1 << s.b, dtype=np.uint32)
+        cb[:K] = layer.codebook
+        protos.append(dict(s=s, layer=layer, count=count, packed=packed.view(out, s.words_per_row),
+                           codebook=torch.from_numpy(cb.view(np.int32)).to(dev),
+                           alpha=torch.from_numpy(layer.alpha).to(dev), mu=torch.from_numpy(layer.mu).to(dev),
+                           x=torch.from_numpy(x.view(np.int16)).to(dev), x_host=x))
+        del idx_d
+    # distinct copies: copy c of a matrix is the prototype with its rows rotated by a copy-specific offset
+    calls_per_layer = []
+    for L in range(args.layers):
+        calls = []
+        for p in protos:
+            for r in range(p["count"]):
+                shift = (L * 7 + r * 3 + 1) * 37 % p["s"].out
+                calls.append(dict(p=p, packed=torch.roll(p["packed"], shifts=shift, dims=0).contiguous(),
+                                  y=torch.empty(p["s"].out, dtype=torch.float16, device=dev)))
+        calls_per_layer.append(calls)
+    ws = torch.zeros(1 << 20, dtype=torch.uint8, device=dev)
+    n_calls = len(calls_per_layer[0])
+    step_bytes = sum(gemv_bytes(c["p"]["s"], 1) for c in calls_per_layer[0])
+    total_weight_bytes = step_bytes * args.layers
+    torch.cuda.synchronize()
+    t_setup = time.time() - t_setup
+
+    def run_layer(L):
+        for c in calls_per_layer[L]:
+            p = c["p"]
+            B.btc_gemv(p["s"], c["packed"], p["codebook"], p["alpha"], p["mu"], p["x"], 1, c["y"], B.BTC_F16, ws)
+
+    # ---- warmup
+    for i in range(max(args.warmup, 1)):
+        run_layer(i % args.layers)
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly `steps` layers
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    if args.mode == "graph":
+        full_sweeps, rest = divmod(args.steps, args.layers)
+        g_full = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g_full):
+            for L in range(args.layers):
+                run_layer(L)
+        g_rest = None
+        if rest:
+            g_rest = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g_rest):
+                for L in range(rest):
+                    run_layer(L)
+        g_full.replay()
+        torch.cuda.synchronize()
+        start.record()
+        for _ in range(full_sweeps):
+            g_full.replay()
+        if g_rest is not None:
+            g_rest.replay()
+        stop.record()
+    else:
+        torch.cuda.synchronize()
+        start.record()
+        for i in range(args.steps):
+            run_layer(i % args.layers)
+        stop.record()
+    torch.cuda.synchronize()
+    ms_total = start.elapsed_time(stop)
+    ms_per_step = ms_total / args.steps
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+    us_per_call = ms_per_step * 1e3 / n_calls
+    fp16_equiv = sum(2 * c["p"]["s"].out * c["p"]["s"].in_ for c in calls_per_layer[0]) / (ms_per_step * 1e-3) / 1e9
+
+    # per-shape timing (cold, rotating through the copies), events on the launch stream
+    per_shape = {}
+    for si, p in enumerate(protos):
+        mats = [c for calls in calls_per_layer for c in calls if c["p"] is p]
+        reps = max(1, 200 // len(mats))
+        gs = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gs):
+            for c in mats:
+                B.btc_gemv(p["s"], c["packed"], p["codebook"], p["alpha"], p["mu"], p["x"], 1, c["y"], B.BTC_F16, ws)
+        gs.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            gs.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / (reps * len(mats))
+        by = gemv_bytes(p["s"], 1)
+        per_shape[f"{p['s'].out}x{p['s'].in_}"] = dict(us_per_call=round(us, 3), bytes=by,
+                                                        eff_GBps=round(by / us / 1e3, 1),
+                                                        frac_hbm=round(by / us / 1e3 / HBM_PEAK_GBS, 4))
+
+    # ---- prefill GEMM on the same shapes
+    gemm = None
+    if not args.no_gemm:
+        M = args.gemm_m
+        gemm = {}
+        tot_flop, tot_ms = 0.0, 0.0
+        for p in protos:
+            s = p["s"]
+            rng = np.random.Generator(np.random.PCG64(0))
+            Xb = S.draw_x(rng, M, s.in_, "bf16")
+            X = torch.from_numpy(Xb.view(np.int16)).to(dev)
+            Y = torch.empty(M * s.out, dtype=torch.float32, device=dev)
+            wsg = torch.zeros(B.btc_workspace_bytes(s, M, True), dtype=torch.uint8, device=dev)
+            call = lambda: B.btc_gemm(s, p["packed"], p["codebook"], p["alpha"], p["mu"], X, B.BTC_BF16, M, Y,
+                                      B.BTC_F32, wsg)
+            call()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.gemm_iters):
+                call()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / args.gemm_iters
+            flop = 2.0 * M * s.out * s.in_
+            gemm[f"{s.out}x{s.in_}"] = dict(ms=round(ms, 4), tflops=round(flop / ms / 1e9, 1))
+            tot_flop += flop * p["count"]
+            tot_ms += ms * p["count"]
+            del X, Y
+        gemm_tflops = tot_flop / tot_ms / 1e9
+        gemm = dict(M=M, x_dtype="bf16", y_dtype="f32", per_shape=gemm, layer_tflops=round(gemm_tflops, 1),
+                    frac_mfma_peak=round(gemm_tflops / MFMA_BF16_PEAK_TFLOPS, 4))
+
+    # ---- CPU oracle on the host cores, bounded sample of the same workload
+    cpu = None
+    if not args.no_cpu:
+        import oracle
+        oracle.build()
+        threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        for p in protos:
+            p["packed_h"] = oracle.pack(p["layer"].idx, p["layer"].K)
+        t0 = time.time()
+        done_bytes, reps, cpu_s = 0, 0, 0.0
+        while time.time() - t0 < 10.0:
+            t1 = time.time()
+            for p in protos:
+                lay = p["layer"]
+                oracle.linear(p["packed_h"], lay.codebook, lay.alpha, lay.mu, p["x_host"], lay.n_in, lay.v, lay.K)
+                done_bytes += gemv_bytes(p["s"], 1)
+            reps += 1
+            cpu_s = time.time() - t1
+        cpu_elapsed = time.time() - t0
+        cpu = dict(value=round(done_bytes / cpu_elapsed / 1e9, 4), unit="GB/s", cores=threads, kind="oracle",
+                   sample=f"{reps} pass(es) over one matrix of each 13B shape (unpack + materialise fp64 + multiply), "
+                          f"{cpu_elapsed:.1f} s; last pass {cpu_s:.2f} s")
+
+    out = {
+        "metric": "btc_gemv effective weight GB/s (13B shapes, 0.8-bit, batch 1, cold)",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16 in / f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": "llama2-13b decoder-layer projections (4x5120x5120, 2x13824x5120, 1x5120x13824), "
+                               "v=10 K=256 (0.8 bit), Zipf(1.1) indices, batch-1 GEMV, "
+                               f"{args.layers} distinct weight copies ({total_weight_bytes / 1e9:.2f} GB) walked cold",
+                   "step": "one decoder layer = 7 btc_gemv calls", "launch": args.mode},
+        "us_per_call": round(us_per_call, 3),
+        "fp16_equivalent_GBps": round(fp16_equiv, 1),
+        "per_shape": per_shape,
+        "gemm": gemm,
+        "roofline": {"bound": "hbm", "achieved": round(value, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(value / HBM_PEAK_GBS, 4), "traffic": None,
+                     "note": "algorithmic bytes of the 7 calls of a step / event-timed duration of a step"},
+        "cpu_baseline": cpu,
+        "setup_s": round(t_setup, 1),
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
