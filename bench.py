@@ -95,7 +95,7 @@ def main():
                 calls.append(dict(p=p, packed=torch.roll(p["packed"], shifts=shift, dims=0).contiguous(),
                                   y=torch.empty(p["s"].out, dtype=torch.float16, device=dev)))
         calls_per_layer.append(calls)
-    ws = torch.zeros(1 << 20, dtype=torch.uint8, device=dev)
+    ws = torch.zeros(max(B.btc_workspace_bytes(p["s"], 1, False) for p in protos), dtype=torch.uint8, device=dev)
     n_calls = len(calls_per_layer[0])
     step_bytes = sum(gemv_bytes(c["p"]["s"], 1) for c in calls_per_layer[0])
     total_weight_bytes = step_bytes * args.layers

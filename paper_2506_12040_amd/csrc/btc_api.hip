@@ -48,6 +48,17 @@ size_t btc_packed_bytes(const btc_shape* s) {
   return (size_t)s->out * (size_t)s->words_per_row * sizeof(uint32_t);
 }
 
+size_t btc_workspace_bytes(const btc_shape* s, int32_t rows, int is_gemm) {
+  size_t need = 16;  // range-check flag of btc_pack
+  if (!s || rows <= 0) return need;
+  if (is_gemm) {
+    need += (((size_t)rows * sizeof(float)) + 15) & ~(size_t)15;  // fp32 row sums of X
+  } else if (btc::lut_engine_covers(btc::dims_of(*s))) {
+    need = btc::lut_workspace_bytes(*s);
+  }
+  return need;
+}
+
 const char* btc_status_str(btc_status st) {
   switch (st) {
     case BTC_OK: return "ok";

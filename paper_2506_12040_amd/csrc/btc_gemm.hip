@@ -184,12 +184,6 @@ static int gemm_chunks_per_tile(int v) {
 
 extern "C" {
 
-size_t btc_workspace_bytes(const btc_shape* s, int32_t rows, int is_gemm) {
-  size_t need = 16;
-  if (s && is_gemm && rows > 0) need += (((size_t)rows * sizeof(float)) + 15) & ~(size_t)15;
-  return need;
-}
-
 btc_status btc_gemm(void* stream, const btc_shape* s, const uint32_t* packed, const uint32_t* codebook,
                     const float* alpha, const float* mu, const void* X, btc_dtype x_dtype, int32_t M, void* Y,
                     btc_dtype y_dtype, void* workspace, size_t workspace_bytes) {

@@ -1,19 +1,12 @@
 // btc_gemv: argument checks and engine selection for the decode-time product.
 #include "btc_internal.h"
 
-namespace btc {
-btc_status gemv_generic(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
-                        const float* alpha, const float* mu, const void* x, int batch, void* y, int y_is_f32);
-}
-
 extern "C" {
 
 btc_status btc_gemv(void* stream, const btc_shape* s, const uint32_t* packed, const uint32_t* codebook,
                     const float* alpha, const float* mu, const void* x, int32_t batch, void* y, btc_dtype y_dtype,
                     void* workspace, size_t workspace_bytes) {
   using namespace btc;
-  (void)workspace;
-  (void)workspace_bytes;
   btc_status st = check_shape(s);
   if (st != BTC_OK) return st;
   if (!packed || !codebook || !alpha || !mu || !x || !y) return BTC_ERR_NULL;
@@ -22,8 +15,22 @@ btc_status btc_gemv(void* stream, const btc_shape* s, const uint32_t* packed, co
   if (!aligned16(packed) || !aligned16(codebook) || !aligned16(alpha) || !aligned16(mu) || !aligned16(x) ||
       !aligned16(y))
     return BTC_ERR_ALIGN;
-  return gemv_generic((hipStream_t)stream, dims_of(*s), packed, codebook, alpha, mu, x, batch, y,
-                      y_dtype == BTC_F32);
+  hipStream_t q = (hipStream_t)stream;
+  const Dims d = dims_of(*s);
+  const int y_is_f32 = y_dtype == BTC_F32;
+  if (!lut_engine_covers(d)) return gemv_generic(q, d, packed, codebook, alpha, mu, x, batch, y, y_is_f32);
+
+  if (!workspace || workspace_bytes < btc_workspace_bytes(s, batch, 0)) return BTC_ERR_WORKSPACE;
+  if (!aligned16(workspace)) return BTC_ERR_ALIGN;
+  // One pass of the table engine per activation row; the passes share the
+  // workspace, which is safe because they are ordered on the stream.
+  const size_t ysz = y_is_f32 ? 4 : 2;
+  for (int m = 0; m < batch; ++m) {
+    st = gemv_lut(q, d, packed, codebook, alpha, mu, (const char*)x + (size_t)m * d.in * 2,
+                  (char*)y + (size_t)m * d.out * ysz, y_is_f32, workspace);
+    if (st != BTC_OK) return st;
+  }
+  return BTC_OK;
 }
 
 }  // extern "C"

@@ -1,0 +1,366 @@
+// Batch-1 decode product by codebook lookup tables, for index widths 5..10.
+//
+// Appendix "Binary Codebook LUT-GEMM" turns  y_r = sum_j <x_j, C[I_rj]>  into
+// one table lookup and one addition per chunk: CBLUT_j[k] = <x_j, C_k> is
+// computed once per chunk column j and gathered by the indices of many rows.
+// This kernel keeps that idea and changes how it is carried out on CDNA4:
+//
+//  * A workgroup owns 64 consecutive chunk columns and R rows.  Its table
+//    T[k][c] = <x_c, C_k> (2^b x 64 fp16 entries) is produced by the matrix
+//    cores in one shot -- a (2^b x 16) +-1 matrix times a (16 x 64) block of
+//    activations -- instead of the two-stage segment tables of the paper,
+//    because MFMA builds 1024 entries per instruction while the vector ALU
+//    would need ~5 operations per entry.
+//  * Lane l of a wave owns row l of a 64-row tile and walks the 64 columns in
+//    the skewed order c = (l + t) mod 64.  At every step the 64 lanes address
+//    64 different columns, and the table is laid out so that a column fixes
+//    the LDS bank (dword c mod 32 of a 128-byte table row, half c / 32).
+//    Random indices therefore never collide on a bank, and every lane
+//    accumulates its own row: no cross-lane reduction at all.
+//  * The 64 b-bit indices of a row tile (2b words per row) are loaded
+//    coalesced, staged through LDS, and read back rotated by l chunks so that
+//    step t's index sits at the compile-time bit offset t*b of the lane's
+//    registers.
+//  * Column blocks are reduced across workgroups through fp32 partials in the
+//    workspace; the last workgroup to arrive for a row block adds them in a
+//    fixed order and applies  y = alpha * d + mu * sum(x)  (dequantisation step
+//    of Algorithm "Binary Transformation and Compression").  The result does
+//    not depend on arrival order.
+#include <hip/hip_fp16.h>
+
+#include "btc_internal.h"
+
+namespace btc {
+
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int kTileCols = 64;   // chunk columns per workgroup
+constexpr int kTileRows = 64;   // rows per wave tile
+
+// Workspace carve-up for the table engine (all offsets multiples of 256 bytes).
+struct LutWorkspace {
+  uint32_t* counter;  // [ceil(out/64)]   arrival counters, zero between calls
+  float* sx;          // [ceil(out/64)][n_ct]  per-column-block sum of x
+  float* partial;     // [n_ct][out]      per-column-block row sums
+};
+
+static inline size_t round256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+size_t lut_workspace_bytes(const btc_shape& s) {
+  const size_t n_ct = (s.nchunks + kTileCols - 1) / kTileCols;
+  const size_t n_rt = (s.out + kTileRows - 1) / kTileRows;
+  return round256(n_rt * 4) + round256(n_rt * n_ct * 4) + round256(n_ct * (size_t)s.out * 4);
+}
+
+static LutWorkspace carve(void* ws, const Dims& d) {
+  const size_t n_ct = (d.nchunks + kTileCols - 1) / kTileCols;
+  const size_t n_rt = (d.out + kTileRows - 1) / kTileRows;
+  char* p = (char*)ws;
+  LutWorkspace w;
+  w.counter = (uint32_t*)p;
+  p += round256(n_rt * 4);
+  w.sx = (float*)p;
+  p += round256(n_rt * n_ct * 4);
+  w.partial = (float*)p;
+  return w;
+}
+
+__device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi) {
+  const f16x2 h = {(_Float16)lo, (_Float16)hi};
+  return __builtin_bit_cast(uint32_t, h);
+}
+
+// Agent-scope relaxed accesses: they bypass the caches that are not coherent
+// across XCDs, so data written by one workgroup is what another one reads.
+__device__ __forceinline__ void store_agent(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float load_agent(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Two sign bits (t, t+1 of ~pattern) -> two fp16 values +-1.
+__device__ __forceinline__ uint32_t sign_pair(uint32_t npat, int t) {
+  return 0x3C003C00u | ((npat >> t) & 1u) << 15 | ((npat >> (t + 1)) & 1u) << 31;
+}
+
+// Order LDS writes before LDS reads of the SAME wave (different lanes): LDS
+// operations of one wave complete in issue order; wait for them and keep the
+// compiler from moving accesses across this point.
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int B, int NW, bool DUP>
+struct LutCfg {
+  static constexpr int kWordsPerTileRow = 2 * B;                       // 64 indices of B bits
+  static constexpr int kStageRow = (DUP ? 4 * B : 2 * B) + 1;          // words, odd stride
+  static constexpr int kTableBytes = (1 << B) * 128;
+  static constexpr int kStageBytes = NW * kTileRows * kStageRow * 4;
+  static constexpr int kLdsBytes = kTableBytes + kStageBytes;
+};
+
+template <int B, int NW, bool DUP>
+__global__ __launch_bounds__(NW * 64) void gemv_lut_kernel(Dims d, const uint32_t* __restrict__ packed,
+                                                           const uint32_t* __restrict__ codebook,
+                                                           const float* __restrict__ alpha,
+                                                           const float* __restrict__ mu,
+                                                           const __half* __restrict__ x, void* __restrict__ y,
+                                                           int y_is_f32, LutWorkspace ws, int n_ct, int n_rb, int RT) {
+  using Cfg = LutCfg<B, NW, DUP>;
+  constexpr int W2 = Cfg::kWordsPerTileRow;
+  constexpr int SR = Cfg::kStageRow;
+  extern __shared__ __align__(16) unsigned char smem[];
+  uint32_t* table = (uint32_t*)smem;                                   // [2^B][32] dwords of 2 x fp16
+  uint32_t* stage_all = (uint32_t*)(smem + Cfg::kTableBytes);
+  __shared__ int s_last;
+
+  // Workgroups are dealt round-robin to the 8 XCDs; give each XCD whole row
+  // blocks so that neighbouring column blocks of a row (which share HBM lines)
+  // meet in the same L2.
+  const int L = blockIdx.x;
+  const int xcd = L & 7, slot = L >> 3;
+  const int rb = (slot / n_ct) * 8 + xcd;
+  const int ct = slot % n_ct;
+  if (rb >= n_rb) return;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int j = lane & 31, h = lane >> 5;
+  uint32_t* stage = stage_all + wave * (kTileRows * SR);
+
+  // ---- first index tile: issue its loads now, they fly while the table is built.
+  // Coalesced: lane l fetches word (q*64 + l) of the 64 x 2B-word tile (clamped
+  // addresses; out-of-range words are replaced by zeros when staged).
+  const int words_left = d.wpr - ct * W2;                              // words of this column block inside a row
+  uint32_t ld[W2];
+  auto load_tile = [&](int row0) {
+#pragma unroll
+    for (int q = 0; q < W2; ++q) {
+      const int g = q * 64 + lane;
+      const int r = g / W2, w = g - r * W2;
+      const int rr = min(row0 + r, d.out - 1), ww = min(w, words_left - 1);
+      ld[q] = packed[(long long)rr * d.wpr + ct * W2 + ww];
+    }
+  };
+  load_tile((rb * RT * NW + wave) * kTileRows);
+
+  // ---- activations of this column block as MFMA B operands; their sum
+  const int KH = (d.v + 15) >> 4;                                      // 16 chunk elements per MFMA
+  uint4 bx[2][2];
+  float sx_lane = 0.f;
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb) {
+    const int chunk = ct * kTileCols + nb * 32 + j;
+#pragma unroll
+    for (int kh = 0; kh < 2; ++kh) {
+      // unconditional loads from a clamped address, then select: all loads of
+      // a lane are in flight together instead of one latency per element
+      const bool chunk_ok = kh < KH && chunk < d.nchunks;
+      uint16_t raw[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int t = kh * 16 + h * 8 + e;
+        const long long k = (long long)chunk * d.v + t;
+        const bool ok = chunk_ok && t < d.v && k < d.in;
+        raw[e] = __half_as_ushort(x[ok ? k : 0]);
+      }
+      uint32_t wv[4] = {0, 0, 0, 0};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int t = kh * 16 + h * 8 + e;
+        const long long k = (long long)chunk * d.v + t;
+        const bool ok = chunk_ok && t < d.v && k < d.in;
+        const uint16_t hv = ok ? raw[e] : (uint16_t)0;
+        sx_lane += __half2float(__ushort_as_half(hv));
+        wv[e >> 1] |= (uint32_t)hv << ((e & 1) * 16);
+      }
+      bx[nb][kh] = make_uint4(wv[0], wv[1], wv[2], wv[3]);
+    }
+  }
+  if (wave == 0) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) sx_lane += __shfl_xor(sx_lane, o, 64);
+    if (lane == 0) store_agent(&ws.sx[rb * n_ct + ct], sx_lane);
+  }
+
+  // ---- table build: 32 codewords x 64 columns per pair of MFMAs
+  for (int cg = wave; cg < (1 << B) / 32; cg += NW) {
+    const uint32_t npat = ~codebook[cg * 32 + j];
+    f32x16 d0, d1;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) d0[e] = d1[e] = 0.f;
+#pragma unroll
+    for (int kh = 0; kh < 2; ++kh) {
+      if (kh < KH) {
+        const int t0 = kh * 16 + h * 8;
+        const uint4 a = make_uint4(sign_pair(npat, t0), sign_pair(npat, t0 + 2), sign_pair(npat, t0 + 4),
+                                   sign_pair(npat, t0 + 6));
+        d0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
+                                                    __builtin_bit_cast(f16x8, bx[0][kh]), d0, 0, 0, 0);
+        d1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
+                                                    __builtin_bit_cast(f16x8, bx[1][kh]), d1, 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int code = cg * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
+      table[code * 32 + j] = pack_f16x2(d0[e], d1[e]);                 // columns j (low) and 32 + j (high)
+    }
+  }
+
+  // ---- per-lane constants of the skewed walk
+  // step t reads column c = (lane + t) & 63 -> byte offset 4 * (c & 31) + 2 * (c >> 5)
+  uint32_t colofs[64];
+#pragma unroll
+  for (int t = 0; t < 32; ++t) {
+    const uint32_t c = (uint32_t)(lane + t);
+    colofs[t] = ((c << 2) & 124u) | ((c >> 4) & 2u);
+    colofs[t + 32] = colofs[t] ^ 2u;
+  }
+  const int rot_bits = lane * B;
+  const int wr = rot_bits >> 5;
+  const uint32_t sh = rot_bits & 31;
+
+  __syncthreads();  // table complete
+
+  const char* table_bytes = (const char*)table;
+  for (int rt = 0; rt < RT; ++rt) {
+    const int row0 = ((rb * RT + rt) * NW + wave) * kTileRows;
+    // stage the tile row-major in this wave's LDS buffer
+#pragma unroll
+    for (int q = 0; q < W2; ++q) {
+      const int g = q * 64 + lane;
+      const int r = g / W2, w = g - r * W2;
+      const uint32_t val = (row0 + r < d.out && w < words_left) ? ld[q] : 0u;
+      stage[r * SR + w] = val;
+      if (DUP) stage[r * SR + W2 + w] = val;
+    }
+    if (rt + 1 < RT) load_tile(row0 + NW * kTileRows);  // next tile's loads fly during this tile's lookups
+    wave_lds_sync();
+    // read back rotated by `lane` chunks: R[i] = bits [32 i, 32 i + 32) of the rotated row
+    uint32_t Wd[W2 + 1];
+#pragma unroll
+    for (int i = 0; i <= W2; ++i) {
+      int w = wr + i;
+      if (!DUP) w = w >= W2 ? w - W2 : w;
+      Wd[i] = stage[lane * SR + w];
+    }
+    uint32_t R[W2];
+#pragma unroll
+    for (int i = 0; i < W2; ++i) R[i] = __builtin_amdgcn_alignbit(Wd[i + 1], Wd[i], sh);
+    wave_lds_sync();  // staging buffer may be overwritten by the next tile
+
+    float acc = 0.f;
+#pragma unroll
+    for (int t = 0; t < 64; t += 2) {
+      _Float16 e2[2];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int p = (t + u) * B, w = p >> 5, s = p & 31;
+        uint32_t code;
+        if (s + B <= 32) code = (R[w] >> s) & ((1u << B) - 1u);
+        else code = __builtin_amdgcn_alignbit(R[w + 1], R[w], s) & ((1u << B) - 1u);
+        e2[u] = *(const _Float16*)(table_bytes + ((code << 7) + colofs[t + u]));
+      }
+      const f16x2 pr = {e2[0], e2[1]};
+      const f16x2 one = {(_Float16)1.0f, (_Float16)1.0f};
+      acc = __builtin_amdgcn_fdot2(pr, one, acc, false);
+    }
+    const int row = row0 + lane;
+    if (row < d.out) store_agent(&ws.partial[(long long)ct * d.out + row], acc);
+  }
+
+  // ---- last workgroup of this row block adds the column blocks in order.
+  // Partials travel as agent-scope (cache-bypassing) stores and loads, so the
+  // only ordering needed is: my stores have completed before my arrival is
+  // counted.  Full agent-scope fences would write back and invalidate the
+  // whole L2 of the XCD, which costs tens of microseconds per workgroup.
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+  if (tid == 0) s_last = (atomicAdd(&ws.counter[rb], 1u) == (uint32_t)(n_ct - 1));
+  __syncthreads();
+  if (!s_last) return;
+  // sum of x: every thread adds the column-block sums in the same order
+  float* sx_buf = (float*)stage_all;  // staging space is free now
+  float sx = 0.f;
+  for (int c0 = 0; c0 < n_ct; c0 += NW * 64) {
+    __syncthreads();
+    if (c0 + tid < n_ct) sx_buf[tid] = load_agent(&ws.sx[rb * n_ct + c0 + tid]);
+    __syncthreads();
+    const int n = min(NW * 64, n_ct - c0);
+    for (int c = 0; c < n; ++c) sx += sx_buf[c];
+  }
+  const int rows_per_wg = RT * NW * kTileRows;
+  for (int r = tid; r < rows_per_wg; r += NW * 64) {
+    const int row = rb * rows_per_wg + r;
+    if (row >= d.out) break;
+    float dsum = 0.f;
+    int c = 0;
+    for (; c + 16 <= n_ct; c += 16) {
+      float p16[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) p16[u] = load_agent(&ws.partial[(long long)(c + u) * d.out + row]);
+#pragma unroll
+      for (int u = 0; u < 16; ++u) dsum += p16[u];
+    }
+    if (c < n_ct) {
+      float p16[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) p16[u] = load_agent(&ws.partial[(long long)min(c + u, n_ct - 1) * d.out + row]);
+#pragma unroll
+      for (int u = 0; u < 16; ++u) dsum += (c + u < n_ct) ? p16[u] : 0.f;
+    }
+    const float res = alpha[row] * dsum + mu[row] * sx;
+    if (y_is_f32) ((float*)y)[row] = res;
+    else ((__half*)y)[row] = __float2half_rn(res);
+  }
+  if (tid == 0) ws.counter[rb] = 0u;  // leave the counters zero for the next call
+}
+
+template <int B, int NW, bool DUP>
+static btc_status launch_lut(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
+                             const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, void* ws) {
+  using Cfg = LutCfg<B, NW, DUP>;
+  static_assert(Cfg::kLdsBytes <= 160 * 1024 - 64, "LDS budget");
+  static bool attr_set = false;  // one-time kernel attribute, not call state
+  if (!attr_set) {
+    if (hipFuncSetAttribute((const void*)gemv_lut_kernel<B, NW, DUP>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            Cfg::kLdsBytes) != hipSuccess)
+      return BTC_ERR_HIP;
+    attr_set = true;
+  }
+  const int n_ct = (d.nchunks + kTileCols - 1) / kTileCols;
+  const int tiles = (d.out + kTileRows - 1) / kTileRows;
+  // row tiles per wave: keep at least ~2 workgroups per CU when the matrix allows it
+  int RT = 1;
+  while (RT < 8 && (long long)((tiles + NW * RT * 2 - 1) / (NW * RT * 2)) * n_ct >= 512) RT *= 2;
+  const int n_rb = (tiles + NW * RT - 1) / (NW * RT);
+  const int grid = ((n_rb + 7) / 8) * 8 * n_ct;
+  gemv_lut_kernel<B, NW, DUP><<<grid, NW * 64, Cfg::kLdsBytes, q>>>(d, packed, codebook, alpha, mu, (const __half*)x,
+                                                                    y, y_is_f32, carve(ws, d), n_ct, n_rb, RT);
+  return launch_status();
+}
+
+bool lut_engine_covers(const Dims& d) { return d.b >= 5 && d.b <= 10; }
+
+// One activation row; `ws` must hold lut_workspace_bytes() bytes whose counter
+// area is zero (it is left zero).
+btc_status gemv_lut(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
+                    const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, void* ws) {
+  switch (d.b) {
+    case 5: return launch_lut<5, 4, true>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
+    case 6: return launch_lut<6, 4, true>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
+    case 7: return launch_lut<7, 4, true>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
+    case 8: return launch_lut<8, 4, true>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
+    case 9: return launch_lut<9, 8, true>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
+    case 10: return launch_lut<10, 4, false>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
+  }
+  return BTC_ERR_UNSUPPORTED;
+}
+
+}  // namespace btc

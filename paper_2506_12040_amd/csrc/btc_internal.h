@@ -22,6 +22,15 @@ inline Dims dims_of(const btc_shape& s) {
 // btc_shape_init (or was edited afterwards) is rejected before any launch.
 btc_status check_shape(const btc_shape* s);
 
+// Table engine of the decode product (btc_gemv_lut.hip).
+bool lut_engine_covers(const Dims& d);
+size_t lut_workspace_bytes(const btc_shape& s);
+btc_status gemv_lut(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
+                    const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, void* ws);
+// Fallback engine for every other setting (btc_gemv_generic.hip).
+btc_status gemv_generic(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
+                        const float* alpha, const float* mu, const void* x, int batch, void* y, int y_is_f32);
+
 inline btc_status launch_status() {
   return hipGetLastError() == hipSuccess ? BTC_OK : BTC_ERR_HIP;
 }
