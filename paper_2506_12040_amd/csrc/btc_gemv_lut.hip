@@ -26,6 +26,12 @@
 //    fixed order and applies  y = alpha * d + mu * sum(x)  (dequantisation step
 //    of Algorithm "Binary Transformation and Compression").  The result does
 //    not depend on arrival order.
+//
+// A decode call on a 13B-sized matrix lasts a few microseconds, so the serial
+// instruction count of a wave matters as much as throughput: global loads go
+// through buffer descriptors (hardware range check returns 0 outside the
+// matrix or the activation vector, which also realises the zero padding of
+// the last chunk), and LDS addresses are one per-lane register plus immediates.
 #include <hip/hip_fp16.h>
 
 #include "btc_internal.h"
@@ -38,6 +44,8 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr int kTileCols = 64;   // chunk columns per workgroup
 constexpr int kTileRows = 64;   // rows per wave tile
+constexpr uint32_t kOob = 0x80000000u;  // buffer offset that is always out of range (buffers are < 2 GiB)
+constexpr int kRsrcFlags = 0x00020000;  // raw buffer, 32-bit data format
 
 // Workspace carve-up for the table engine (all offsets multiples of 256 bytes).
 struct LutWorkspace {
@@ -81,9 +89,12 @@ __device__ __forceinline__ float load_agent(const float* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Two sign bits (t, t+1 of ~pattern) -> two fp16 values +-1.
-__device__ __forceinline__ uint32_t sign_pair(uint32_t npat, int t) {
-  return 0x3C003C00u | ((npat >> t) & 1u) << 15 | ((npat >> (t + 1)) & 1u) << 31;
+// Bits (2i, 2i+1) of n -> two fp16 values, bit set => -1, clear => +1.
+__device__ __forceinline__ uint32_t sign_pair(uint32_t n, int i) {
+  uint32_t r = 0x3C003C00u;
+  r = (r & ~0x8000u) | ((n << (15 - 2 * i)) & 0x8000u);
+  r = (r & ~0x80000000u) | ((n << (30 - 2 * i)) & 0x80000000u);
+  return r;
 }
 
 // Order LDS writes before LDS reads of the SAME wave (different lanes): LDS
@@ -98,14 +109,19 @@ __device__ __forceinline__ void wave_lds_sync() {
 
 template <int B, int NW, bool DUP>
 struct LutCfg {
-  static constexpr int kWordsPerTileRow = 2 * B;                       // 64 indices of B bits
-  static constexpr int kStageRow = (DUP ? 4 * B : 2 * B) + 1;          // words, odd stride
+  static constexpr int W2 = 2 * B;                       // words per tile row: 64 indices of B bits
+  static constexpr int RPI = 64 / W2;                    // tile rows fetched by one wave-wide load
+  static constexpr int NQ = (kTileRows + RPI - 1) / RPI; // loads per tile
+  static constexpr int kStageRows = NQ * RPI;            // >= 64
+  static constexpr int SR = (DUP ? 2 * W2 : W2) + 1;     // staged row stride in words (odd)
   static constexpr int kTableBytes = (1 << B) * 128;
-  static constexpr int kStageBytes = NW * kTileRows * kStageRow * 4;
+  static constexpr int kStageBytes = NW * kStageRows * SR * 4;
   static constexpr int kLdsBytes = kTableBytes + kStageBytes;
+  static constexpr int kGroups = (1 << B) / 32;          // 32-codeword groups
+  static_assert(kGroups % NW == 0, "codeword groups split evenly over the waves");
 };
 
-template <int B, int NW, bool DUP>
+template <int B, int NW, bool DUP, bool WIDE_V /* v > 16 */, bool X_DWORD /* v and in even */>
 __global__ __launch_bounds__(NW * 64) void gemv_lut_kernel(Dims d, const uint32_t* __restrict__ packed,
                                                            const uint32_t* __restrict__ codebook,
                                                            const float* __restrict__ alpha,
@@ -113,8 +129,8 @@ __global__ __launch_bounds__(NW * 64) void gemv_lut_kernel(Dims d, const uint32_
                                                            const __half* __restrict__ x, void* __restrict__ y,
                                                            int y_is_f32, LutWorkspace ws, int n_ct, int n_rb, int RT) {
   using Cfg = LutCfg<B, NW, DUP>;
-  constexpr int W2 = Cfg::kWordsPerTileRow;
-  constexpr int SR = Cfg::kStageRow;
+  constexpr int W2 = Cfg::W2, SR = Cfg::SR, RPI = Cfg::RPI, NQ = Cfg::NQ;
+  constexpr int KH = WIDE_V ? 2 : 1;
   extern __shared__ __align__(16) unsigned char smem[];
   uint32_t* table = (uint32_t*)smem;                                   // [2^B][32] dwords of 2 x fp16
   uint32_t* stage_all = (uint32_t*)(smem + Cfg::kTableBytes);
@@ -126,93 +142,65 @@ __global__ __launch_bounds__(NW * 64) void gemv_lut_kernel(Dims d, const uint32_
   const int L = blockIdx.x;
   const int xcd = L & 7, slot = L >> 3;
   const int rb = (slot / n_ct) * 8 + xcd;
-  const int ct = slot % n_ct;
+  const int ct = slot - (slot / n_ct) * n_ct;
   if (rb >= n_rb) return;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int j = lane & 31, h = lane >> 5;
-  uint32_t* stage = stage_all + wave * (kTileRows * SR);
+  uint32_t* stage = stage_all + wave * (Cfg::kStageRows * SR);
 
-  // ---- first index tile: issue its loads now, they fly while the table is built.
-  // Coalesced: lane l fetches word (q*64 + l) of the 64 x 2B-word tile (clamped
-  // addresses; out-of-range words are replaced by zeros when staged).
-  const int words_left = d.wpr - ct * W2;                              // words of this column block inside a row
-  uint32_t ld[W2];
+  // ---- index tiles: lane (lr, lw) fetches word lw of tile rows lr, lr+RPI, ...
+  const int lr = lane / W2, lw = lane - lr * W2;
+  const int words_left = d.wpr - ct * W2;                 // words of this column block inside a row
+  const bool lane_loads = lr < RPI;
+  const uint32_t tile_voff = (lane_loads && lw < words_left) ? (uint32_t)(lr * d.wpr + lw) * 4u : kOob;
+  const uint32_t q_stride = (uint32_t)(RPI * d.wpr) * 4u;
+  const uint32_t total_bytes = (uint32_t)d.out * (uint32_t)d.wpr * 4u;
+  uint32_t ld[NQ];
   auto load_tile = [&](int row0) {
+    // descriptor rebased to the tile, so that the range check sees the true distance to the end
+    const uint32_t base_off = ((uint32_t)row0 * (uint32_t)d.wpr + (uint32_t)(ct * W2)) * 4u;
+    const bool inside = row0 < d.out;
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)((const char*)packed + (inside ? base_off : 0u)), 0, inside ? (int)(total_bytes - base_off) : 0,
+        kRsrcFlags);
 #pragma unroll
-    for (int q = 0; q < W2; ++q) {
-      const int g = q * 64 + lane;
-      const int r = g / W2, w = g - r * W2;
-      const int rr = min(row0 + r, d.out - 1), ww = min(w, words_left - 1);
-      ld[q] = packed[(long long)rr * d.wpr + ct * W2 + ww];
-    }
+    for (int q = 0; q < NQ; ++q) ld[q] = __builtin_amdgcn_raw_buffer_load_b32(rs, tile_voff + q * q_stride, 0, 0);
   };
   load_tile((rb * RT * NW + wave) * kTileRows);
+  // this wave's share of the codebook (lane: codeword j of each of its 32-codeword groups)
+  uint32_t npat_all[Cfg::kGroups / NW];
+#pragma unroll
+  for (int it = 0; it < Cfg::kGroups / NW; ++it) npat_all[it] = ~codebook[(it * NW + wave) * 32 + j];
 
-  // ---- activations of this column block as MFMA B operands; their sum
-  const int KH = (d.v + 15) >> 4;                                      // 16 chunk elements per MFMA
-  uint4 bx[2][2];
-  float sx_lane = 0.f;
+  // ---- activations of this column block as MFMA B operands (lane: column j of
+  // block nb, elements 8h..8h+7 of the chunk); out-of-range elements read as 0
+  const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)x, 0, d.in * 2, kRsrcFlags);
+  uint4 bx[2][KH];
 #pragma unroll
   for (int nb = 0; nb < 2; ++nb) {
     const int chunk = ct * kTileCols + nb * 32 + j;
 #pragma unroll
-    for (int kh = 0; kh < 2; ++kh) {
-      // unconditional loads from a clamped address, then select: all loads of
-      // a lane are in flight together instead of one latency per element
-      const bool chunk_ok = kh < KH && chunk < d.nchunks;
-      uint16_t raw[8];
+    for (int kh = 0; kh < KH; ++kh) {
+      const int t0 = kh * 16 + h * 8;
+      const uint32_t e0 = (uint32_t)(chunk * d.v + t0) * 2u;   // byte offset of element t0 of the chunk
+      uint32_t wv[4];
+      if (X_DWORD) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int t = kh * 16 + h * 8 + e;
-        const long long k = (long long)chunk * d.v + t;
-        const bool ok = chunk_ok && t < d.v && k < d.in;
-        raw[e] = __half_as_ushort(x[ok ? k : 0]);
-      }
-      uint32_t wv[4] = {0, 0, 0, 0};
+        for (int i = 0; i < 4; ++i)
+          wv[i] = __builtin_amdgcn_raw_buffer_load_b32(rx, (t0 + 2 * i < d.v) ? e0 + 4u * i : kOob, 0, 0);
+      } else {
+        uint32_t hv[8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int t = kh * 16 + h * 8 + e;
-        const long long k = (long long)chunk * d.v + t;
-        const bool ok = chunk_ok && t < d.v && k < d.in;
-        const uint16_t hv = ok ? raw[e] : (uint16_t)0;
-        sx_lane += __half2float(__ushort_as_half(hv));
-        wv[e >> 1] |= (uint32_t)hv << ((e & 1) * 16);
+        for (int e = 0; e < 8; ++e)
+          hv[e] = __builtin_amdgcn_raw_buffer_load_b16(rx, (t0 + e < d.v) ? e0 + 2u * e : kOob, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) wv[i] = (hv[2 * i] & 0xFFFFu) | (hv[2 * i + 1] << 16);
       }
       bx[nb][kh] = make_uint4(wv[0], wv[1], wv[2], wv[3]);
     }
   }
-  if (wave == 0) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) sx_lane += __shfl_xor(sx_lane, o, 64);
-    if (lane == 0) store_agent(&ws.sx[rb * n_ct + ct], sx_lane);
-  }
-
-  // ---- table build: 32 codewords x 64 columns per pair of MFMAs
-  for (int cg = wave; cg < (1 << B) / 32; cg += NW) {
-    const uint32_t npat = ~codebook[cg * 32 + j];
-    f32x16 d0, d1;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) d0[e] = d1[e] = 0.f;
-#pragma unroll
-    for (int kh = 0; kh < 2; ++kh) {
-      if (kh < KH) {
-        const int t0 = kh * 16 + h * 8;
-        const uint4 a = make_uint4(sign_pair(npat, t0), sign_pair(npat, t0 + 2), sign_pair(npat, t0 + 4),
-                                   sign_pair(npat, t0 + 6));
-        d0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
-                                                    __builtin_bit_cast(f16x8, bx[0][kh]), d0, 0, 0, 0);
-        d1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
-                                                    __builtin_bit_cast(f16x8, bx[1][kh]), d1, 0, 0, 0);
-      }
-    }
-#pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      const int code = cg * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
-      table[code * 32 + j] = pack_f16x2(d0[e], d1[e]);                 // columns j (low) and 32 + j (high)
-    }
-  }
-
   // ---- per-lane constants of the skewed walk
   // step t reads column c = (lane + t) & 63 -> byte offset 4 * (c & 31) + 2 * (c >> 5)
   uint32_t colofs[64];
@@ -225,20 +213,62 @@ __global__ __launch_bounds__(NW * 64) void gemv_lut_kernel(Dims d, const uint32_
   const int rot_bits = lane * B;
   const int wr = rot_bits >> 5;
   const uint32_t sh = rot_bits & 31;
+  uint32_t* stage_wr = stage + lr * SR + lw;          // where this lane stages what it fetched
+  const uint32_t* stage_rd = stage + lane * SR + wr;  // where its own rotated row starts
+
+  if (wave == NW - 1) {  // one wave also adds the block's activations up
+    float sxl = 0.f;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int kh = 0; kh < KH; ++kh) {
+        const uint32_t w4[4] = {bx[nb][kh].x, bx[nb][kh].y, bx[nb][kh].z, bx[nb][kh].w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const f16x2 p = __builtin_bit_cast(f16x2, w4[i]);
+          sxl += (float)p[0];
+          sxl += (float)p[1];
+        }
+      }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) sxl += __shfl_xor(sxl, o, 64);
+    if (lane == 0) store_agent(&ws.sx[rb * n_ct + ct], sxl);
+  }
+
+  // ---- table build: 32 codewords x 64 columns per pair of MFMAs.
+  // D[i][jj]: lane holds column jj = lane % 32 and codewords i = 8 (e/4) + 4 h + e%4.
+  uint32_t* trow = table + (wave * 32 + 4 * h) * 32 + j;
+#pragma unroll
+  for (int it = 0; it < Cfg::kGroups / NW; ++it) {
+    const uint32_t npat = npat_all[it];
+    f32x16 d0, d1;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) d0[e] = d1[e] = 0.f;
+#pragma unroll
+    for (int kh = 0; kh < KH; ++kh) {
+      const uint32_t n = npat >> (kh * 16 + h * 8);
+      const uint4 a = make_uint4(sign_pair(n, 0), sign_pair(n, 1), sign_pair(n, 2), sign_pair(n, 3));
+      d0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, bx[0][kh]),
+                                                  d0, 0, 0, 0);
+      d1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, bx[1][kh]),
+                                                  d1, 0, 0, 0);
+    }
+#pragma unroll
+    for (int e = 0; e < 16; ++e)  // columns j (low half) and 32 + j (high half) of codeword row
+      trow[(it * NW * 32 + 8 * (e >> 2) + (e & 3)) * 32] = pack_f16x2(d0[e], d1[e]);
+  }
 
   __syncthreads();  // table complete
 
   const char* table_bytes = (const char*)table;
   for (int rt = 0; rt < RT; ++rt) {
     const int row0 = ((rb * RT + rt) * NW + wave) * kTileRows;
-    // stage the tile row-major in this wave's LDS buffer
+    if (lane_loads) {
 #pragma unroll
-    for (int q = 0; q < W2; ++q) {
-      const int g = q * 64 + lane;
-      const int r = g / W2, w = g - r * W2;
-      const uint32_t val = (row0 + r < d.out && w < words_left) ? ld[q] : 0u;
-      stage[r * SR + w] = val;
-      if (DUP) stage[r * SR + W2 + w] = val;
+      for (int q = 0; q < NQ; ++q) {
+        stage_wr[q * RPI * SR] = ld[q];
+        if (DUP) stage_wr[q * RPI * SR + W2] = ld[q];
+      }
     }
     if (rt + 1 < RT) load_tile(row0 + NW * kTileRows);  // next tile's loads fly during this tile's lookups
     wave_lds_sync();
@@ -246,9 +276,8 @@ __global__ __launch_bounds__(NW * 64) void gemv_lut_kernel(Dims d, const uint32_
     uint32_t Wd[W2 + 1];
 #pragma unroll
     for (int i = 0; i <= W2; ++i) {
-      int w = wr + i;
-      if (!DUP) w = w >= W2 ? w - W2 : w;
-      Wd[i] = stage[lane * SR + w];
+      if (DUP) Wd[i] = stage_rd[i];
+      else Wd[i] = stage[lane * SR + (wr + i >= W2 ? wr + i - W2 : wr + i)];
     }
     uint32_t R[W2];
 #pragma unroll
@@ -272,7 +301,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_lut_kernel(Dims d, const uint32_
       acc = __builtin_amdgcn_fdot2(pr, one, acc, false);
     }
     const int row = row0 + lane;
-    if (row < d.out) store_agent(&ws.partial[(long long)ct * d.out + row], acc);
+    if (row < d.out) store_agent(&ws.partial[ct * d.out + row], acc);
   }
 
   // ---- last workgroup of this row block adds the column blocks in order.
@@ -300,18 +329,10 @@ __global__ __launch_bounds__(NW * 64) void gemv_lut_kernel(Dims d, const uint32_
     const int row = rb * rows_per_wg + r;
     if (row >= d.out) break;
     float dsum = 0.f;
-    int c = 0;
-    for (; c + 16 <= n_ct; c += 16) {
+    for (int c = 0; c < n_ct; c += 16) {
       float p16[16];
 #pragma unroll
-      for (int u = 0; u < 16; ++u) p16[u] = load_agent(&ws.partial[(long long)(c + u) * d.out + row]);
-#pragma unroll
-      for (int u = 0; u < 16; ++u) dsum += p16[u];
-    }
-    if (c < n_ct) {
-      float p16[16];
-#pragma unroll
-      for (int u = 0; u < 16; ++u) p16[u] = load_agent(&ws.partial[(long long)min(c + u, n_ct - 1) * d.out + row]);
+      for (int u = 0; u < 16; ++u) p16[u] = load_agent(&ws.partial[min(c + u, n_ct - 1) * d.out + row]);
 #pragma unroll
       for (int u = 0; u < 16; ++u) dsum += (c + u < n_ct) ? p16[u] : 0.f;
     }
@@ -322,15 +343,15 @@ __global__ __launch_bounds__(NW * 64) void gemv_lut_kernel(Dims d, const uint32_
   if (tid == 0) ws.counter[rb] = 0u;  // leave the counters zero for the next call
 }
 
-template <int B, int NW, bool DUP>
-static btc_status launch_lut(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
-                             const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, void* ws) {
+template <int B, int NW, bool DUP, bool WIDE_V, bool X_DWORD>
+static btc_status launch_lut2(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
+                              const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, void* ws) {
   using Cfg = LutCfg<B, NW, DUP>;
   static_assert(Cfg::kLdsBytes <= 160 * 1024 - 64, "LDS budget");
   static bool attr_set = false;  // one-time kernel attribute, not call state
   if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)gemv_lut_kernel<B, NW, DUP>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            Cfg::kLdsBytes) != hipSuccess)
+    if (hipFuncSetAttribute((const void*)gemv_lut_kernel<B, NW, DUP, WIDE_V, X_DWORD>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes) != hipSuccess)
       return BTC_ERR_HIP;
     attr_set = true;
   }
@@ -341,20 +362,37 @@ static btc_status launch_lut(hipStream_t q, const Dims& d, const uint32_t* packe
   while (RT < 8 && (long long)((tiles + NW * RT * 2 - 1) / (NW * RT * 2)) * n_ct >= 512) RT *= 2;
   const int n_rb = (tiles + NW * RT - 1) / (NW * RT);
   const int grid = ((n_rb + 7) / 8) * 8 * n_ct;
-  gemv_lut_kernel<B, NW, DUP><<<grid, NW * 64, Cfg::kLdsBytes, q>>>(d, packed, codebook, alpha, mu, (const __half*)x,
-                                                                    y, y_is_f32, carve(ws, d), n_ct, n_rb, RT);
+  gemv_lut_kernel<B, NW, DUP, WIDE_V, X_DWORD><<<grid, NW * 64, Cfg::kLdsBytes, q>>>(
+      d, packed, codebook, alpha, mu, (const __half*)x, y, y_is_f32, carve(ws, d), n_ct, n_rb, RT);
   return launch_status();
 }
 
-bool lut_engine_covers(const Dims& d) { return d.b >= 5 && d.b <= 10; }
+template <int B, int NW, bool DUP>
+static btc_status launch_lut(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
+                             const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, void* ws) {
+  const bool xdw = (d.v % 2 == 0) && (d.in % 2 == 0);
+  if (d.v > 16) return launch_lut2<B, NW, DUP, true, false>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
+  if (xdw) return launch_lut2<B, NW, DUP, false, true>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
+  return launch_lut2<B, NW, DUP, false, false>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
+}
+
+// Index widths with a table that fits LDS, and buffers small enough for 32-bit
+// byte offsets with a spare always-out-of-range value.
+bool lut_engine_covers(const Dims& d) {
+  if (d.b < 5 || d.b > 10) return false;
+  if ((long long)d.out * d.wpr * 4 >= (1LL << 31)) return false;
+  if ((long long)d.in * 2 >= (1LL << 31) || (long long)d.nchunks * d.v * 2 >= (1LL << 31)) return false;
+  const long long n_ct = (d.nchunks + kTileCols - 1) / kTileCols;
+  return n_ct * d.out < (1LL << 29);
+}
 
 // One activation row; `ws` must hold lut_workspace_bytes() bytes whose counter
 // area is zero (it is left zero).
 btc_status gemv_lut(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
                     const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, void* ws) {
   switch (d.b) {
-    case 5: return launch_lut<5, 4, true>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
-    case 6: return launch_lut<6, 4, true>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
+    case 5: return launch_lut<5, 1, true>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
+    case 6: return launch_lut<6, 2, true>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
     case 7: return launch_lut<7, 4, true>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
     case 8: return launch_lut<8, 4, true>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
     case 9: return launch_lut<9, 8, true>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
