@@ -53,7 +53,7 @@ size_t btc_workspace_bytes(const btc_shape* s, int32_t rows, int is_gemm) {
   if (!s || rows <= 0) return need;
   if (is_gemm) {
     need += (((size_t)rows * sizeof(float)) + 15) & ~(size_t)15;  // fp32 row sums of X
-  } else if (btc::lut_engine_covers(btc::dims_of(*s))) {
+  } else if (btc::lut_engine_covers(btc::dims_of(*s))) {  // the table engine may be chosen
     need = btc::lut_workspace_bytes(*s);
   }
   return need;

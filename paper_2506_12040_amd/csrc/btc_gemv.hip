@@ -18,13 +18,24 @@ btc_status btc_gemv(void* stream, const btc_shape* s, const uint32_t* packed, co
   hipStream_t q = (hipStream_t)stream;
   const Dims d = dims_of(*s);
   const int y_is_f32 = y_dtype == BTC_F32;
+  const size_t ysz = y_is_f32 ? 4 : 2;
+  // Small matrices are bound by the chain of memory round trips: the register-resident engine has the
+  // shortest one.  Larger ones are bound by LDS and ALU throughput, where the table engine is lighter.
+  const bool small = (long long)d.out * d.wpr * 4 < (4LL << 20) || !lut_engine_covers(d);
+  if (small && expand_engine_covers(d)) {
+    for (int m = 0; m < batch; ++m) {
+      st = gemv_expand(q, d, packed, codebook, alpha, mu, (const char*)x + (size_t)m * d.in * 2,
+                       (char*)y + (size_t)m * d.out * ysz, y_is_f32);
+      if (st != BTC_OK) return st;
+    }
+    return BTC_OK;
+  }
   if (!lut_engine_covers(d)) return gemv_generic(q, d, packed, codebook, alpha, mu, x, batch, y, y_is_f32);
 
   if (!workspace || workspace_bytes < btc_workspace_bytes(s, batch, 0)) return BTC_ERR_WORKSPACE;
   if (!aligned16(workspace)) return BTC_ERR_ALIGN;
   // One pass of the table engine per activation row; the passes share the
   // workspace, which is safe because they are ordered on the stream.
-  const size_t ysz = y_is_f32 ? 4 : 2;
   for (int m = 0; m < batch; ++m) {
     st = gemv_lut(q, d, packed, codebook, alpha, mu, (const char*)x + (size_t)m * d.in * 2,
                   (char*)y + (size_t)m * d.out * ysz, y_is_f32, workspace);

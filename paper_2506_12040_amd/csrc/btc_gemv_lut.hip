@@ -48,10 +48,13 @@ constexpr uint32_t kOob = 0x80000000u;  // buffer offset that is always out of r
 constexpr int kRsrcFlags = 0x00020000;  // raw buffer, 32-bit data format
 
 // Workspace carve-up for the table engine (all offsets multiples of 256 bytes).
+// sx and partial hold 64-bit slots {fp32 value, tag}: tag 1 = written during
+// this call, 0 = empty.  The finalising workgroup empties what it consumes,
+// so the whole workspace is zero between calls.
 struct LutWorkspace {
-  uint32_t* counter;  // [ceil(out/64)]   arrival counters, zero between calls
-  float* sx;          // [ceil(out/64)][n_ct]  per-column-block sum of x
-  float* partial;     // [n_ct][out]      per-column-block row sums
+  uint32_t* counter;             // [ceil(out/64)]        arrival counters
+  unsigned long long* sx;        // [ceil(out/64)][n_ct]  per-column-block sum of x
+  unsigned long long* partial;   // [n_ct][out]           per-column-block row sums
 };
 
 static inline size_t round256(size_t n) { return (n + 255) & ~(size_t)255; }
@@ -59,7 +62,7 @@ static inline size_t round256(size_t n) { return (n + 255) & ~(size_t)255; }
 size_t lut_workspace_bytes(const btc_shape& s) {
   const size_t n_ct = (s.nchunks + kTileCols - 1) / kTileCols;
   const size_t n_rt = (s.out + kTileRows - 1) / kTileRows;
-  return round256(n_rt * 4) + round256(n_rt * n_ct * 4) + round256(n_ct * (size_t)s.out * 4);
+  return round256(n_rt * 4) + round256(n_rt * n_ct * 8) + round256(n_ct * (size_t)s.out * 8);
 }
 
 static LutWorkspace carve(void* ws, const Dims& d) {
@@ -69,9 +72,9 @@ static LutWorkspace carve(void* ws, const Dims& d) {
   LutWorkspace w;
   w.counter = (uint32_t*)p;
   p += round256(n_rt * 4);
-  w.sx = (float*)p;
-  p += round256(n_rt * n_ct * 4);
-  w.partial = (float*)p;
+  w.sx = (unsigned long long*)p;
+  p += round256(n_rt * n_ct * 8);
+  w.partial = (unsigned long long*)p;
   return w;
 }
 
@@ -82,11 +85,23 @@ __device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi) {
 
 // Agent-scope relaxed accesses: they bypass the caches that are not coherent
 // across XCDs, so data written by one workgroup is what another one reads.
-__device__ __forceinline__ void store_agent(float* p, float v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+__device__ __forceinline__ void store_slot(unsigned long long* p, float v) {
+  __hip_atomic_store(p, (1ull << 32) | (unsigned long long)__float_as_uint(v), __ATOMIC_RELAXED,
+                     __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ float load_agent(const float* p) {
+__device__ __forceinline__ void clear_slot(unsigned long long* p) {
+  __hip_atomic_store(p, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long load_slot(const unsigned long long* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Value of a slot whose store was issued before this workgroup learnt that it
+// is the last one: the store may still be in flight, so poll until the tag
+// shows up.  The bound only guards against a hang if a producer never ran.
+__device__ __forceinline__ float slot_value(const unsigned long long* p, unsigned long long first) {
+  unsigned long long v = first;
+  for (int spin = 0; (v >> 32) == 0 && spin < (1 << 22); ++spin) v = load_slot(p);
+  return __uint_as_float((uint32_t)v);
 }
 
 // Bits (2i, 2i+1) of n -> two fp16 values, bit set => -1, clear => +1.
@@ -232,7 +247,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_lut_kernel(Dims d, const uint32_
       }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) sxl += __shfl_xor(sxl, o, 64);
-    if (lane == 0) store_agent(&ws.sx[rb * n_ct + ct], sxl);
+    if (lane == 0) store_slot(&ws.sx[rb * n_ct + ct], sxl);
   }
 
   // ---- table build: 32 codewords x 64 columns per pair of MFMAs.
@@ -301,42 +316,60 @@ __global__ __launch_bounds__(NW * 64) void gemv_lut_kernel(Dims d, const uint32_
       acc = __builtin_amdgcn_fdot2(pr, one, acc, false);
     }
     const int row = row0 + lane;
-    if (row < d.out) store_agent(&ws.partial[ct * d.out + row], acc);
+    if (row < d.out) store_slot(&ws.partial[ct * d.out + row], acc);
   }
 
   // ---- last workgroup of this row block adds the column blocks in order.
-  // Partials travel as agent-scope (cache-bypassing) stores and loads, so the
-  // only ordering needed is: my stores have completed before my arrival is
-  // counted.  Full agent-scope fences would write back and invalidate the
-  // whole L2 of the XCD, which costs tens of microseconds per workgroup.
-  __builtin_amdgcn_s_waitcnt(0);
+  // Partials travel as agent-scope (cache-bypassing) 8-byte stores {value, tag}
+  // that are not waited for: arrival is counted as soon as they are issued, and
+  // the last workgroup polls the few slots whose store has not landed yet.
+  // (Full agent-scope fences would write back and invalidate the whole L2 of
+  // the XCD -- tens of microseconds per workgroup.)
   __syncthreads();
   if (tid == 0) s_last = (atomicAdd(&ws.counter[rb], 1u) == (uint32_t)(n_ct - 1));
   __syncthreads();
   if (!s_last) return;
   // sum of x: every thread adds the column-block sums in the same order
   float* sx_buf = (float*)stage_all;  // staging space is free now
+  const int rows_per_wg = RT * NW * kTileRows;
+  const int row_first = rb * rows_per_wg + tid;
+  unsigned long long p16[16];
+  if (row_first < d.out) {            // first batch of this thread's partials: in flight with the sx loads
+#pragma unroll
+    for (int u = 0; u < 16; ++u) p16[u] = load_slot(&ws.partial[min(u, n_ct - 1) * d.out + row_first]);
+  }
   float sx = 0.f;
   for (int c0 = 0; c0 < n_ct; c0 += NW * 64) {
     __syncthreads();
-    if (c0 + tid < n_ct) sx_buf[tid] = load_agent(&ws.sx[rb * n_ct + c0 + tid]);
+    if (c0 + tid < n_ct) {
+      unsigned long long* slot = &ws.sx[rb * n_ct + c0 + tid];
+      sx_buf[tid] = slot_value(slot, load_slot(slot));
+      clear_slot(slot);
+    }
     __syncthreads();
     const int n = min(NW * 64, n_ct - c0);
     for (int c = 0; c < n; ++c) sx += sx_buf[c];
   }
-  const int rows_per_wg = RT * NW * kTileRows;
   for (int r = tid; r < rows_per_wg; r += NW * 64) {
     const int row = rb * rows_per_wg + r;
     if (row >= d.out) break;
+    const float al = alpha[row], mm = mu[row];
     float dsum = 0.f;
     for (int c = 0; c < n_ct; c += 16) {
-      float p16[16];
+      if (r != tid || c != 0) {
 #pragma unroll
-      for (int u = 0; u < 16; ++u) p16[u] = load_agent(&ws.partial[min(c + u, n_ct - 1) * d.out + row]);
+        for (int u = 0; u < 16; ++u) p16[u] = load_slot(&ws.partial[min(c + u, n_ct - 1) * d.out + row]);
+      }
 #pragma unroll
-      for (int u = 0; u < 16; ++u) dsum += (c + u < n_ct) ? p16[u] : 0.f;
+      for (int u = 0; u < 16; ++u) {
+        if (c + u < n_ct) {
+          unsigned long long* slot = &ws.partial[(c + u) * d.out + row];
+          dsum += slot_value(slot, p16[u]);
+          clear_slot(slot);
+        }
+      }
     }
-    const float res = alpha[row] * dsum + mu[row] * sx;
+    const float res = al * dsum + mm * sx;
     if (y_is_f32) ((float*)y)[row] = res;
     else ((__half*)y)[row] = __float2half_rn(res);
   }

@@ -27,6 +27,10 @@ bool lut_engine_covers(const Dims& d);
 size_t lut_workspace_bytes(const btc_shape& s);
 btc_status gemv_lut(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
                     const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, void* ws);
+// Register-resident expansion engine for the tuned settings (btc_gemv_expand.hip).
+bool expand_engine_covers(const Dims& d);
+btc_status gemv_expand(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
+                       const float* alpha, const float* mu, const void* x, void* y, int y_is_f32);
 // Fallback engine for every other setting (btc_gemv_generic.hip).
 btc_status gemv_generic(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
                         const float* alpha, const float* mu, const void* x, int batch, void* y, int y_is_f32);
