@@ -1,0 +1,279 @@
+// Tuned prefill product for chunk length 10:  Y[M][out] = X[M][in] . W_hat^T.
+//
+// At many activation rows the layer is a dense contraction, so the index
+// tiles are decoded into +-1 16-bit tiles in LDS (exact in bf16 and fp16) and
+// contracted on the matrix cores with fp32 accumulation; alpha and mu are
+// applied afterwards in fp32 (Algorithm "Binary Transformation and
+// Compression": W_hat = alpha * B_hat + mu).
+//
+// Roles inside a workgroup (wave specialisation):
+//   * 4 contraction waves, stacked along M.  Wave w owns 64 activation rows
+//     and all BN = 32 NF weight rows of the workgroup: 2 x NF accumulators
+//     of MFMA 32x32x16.  Its A operand (activations) never touches LDS: lane
+//     (row, h) loads 16 consecutive elements straight from global memory and
+//     uses them as the k-slices {16h..16h+7} and {16h+8..16h+15} of a block of
+//     32 columns.  The B operand uses the same permutation of k inside the
+//     block, which costs nothing because it is only an LDS address.
+//   * 4 decoder waves.  A work item (row, half) turns 8 chunk indices of one
+//     weight row into 80 +-1 values of the next k-tile while the contraction
+//     waves work on the current one.  Decoding therefore overlaps the MFMAs
+//     in hardware (two waves per SIMD), and its cost is paid once per
+//     workgroup, not once per contraction wave.
+//   * one barrier per k-tile of 160 columns (16 chunks), two tile buffers.
+//
+// Workgroups are numbered so that all workgroups of one block of activation
+// rows land on the same XCD: its 4 MB L2 then keeps that block of X resident
+// while the weight-row blocks stream through.
+#include <hip/hip_bf16.h>
+#include <hip/hip_fp16.h>
+
+#include "btc_internal.h"
+
+namespace btc {
+namespace tiled {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int kV = 10;                  // chunk length this kernel is built for
+constexpr int kCH = 16;                 // chunks per k-tile
+constexpr int kKT = kV * kCH;           // 160 columns per k-tile = 5 blocks of 32
+constexpr int kRS = kKT + 8;            // LDS row stride in elements: 336 B, an odd multiple of 16 B
+constexpr int kBM = 256;                // activation rows per workgroup
+constexpr int kMW = 4;                  // contraction waves
+constexpr int kDW = 4;                  // decoder waves (8 waves per workgroup: 2 per SIMD, 256 registers each)
+constexpr uint32_t kOob = 0x80000000u;  // buffer offset that is always out of range
+constexpr int kRsrcFlags = 0x00020000;
+
+template <bool BF16>
+__device__ __forceinline__ f32x16 mfma32(const uint4& a, const uint4& b, const f32x16& c) {
+  if constexpr (BF16)
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+
+template <int NF, bool BF16>
+__global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
+    Dims d, const uint32_t* __restrict__ packed, const uint32_t* __restrict__ codebook,
+    const float* __restrict__ alpha, const float* __restrict__ mu, const uint16_t* __restrict__ X, int M,
+    void* __restrict__ Y, int y_dtype, const float* __restrict__ rowsum, int m_blocks, int n_blocks) {
+  constexpr int BN = 32 * NF;
+  extern __shared__ __align__(16) unsigned char smem[];
+  uint16_t* S = (uint16_t*)smem;                         // [2][BN][kRS]
+  uint32_t* cb = (uint32_t*)(S + 2 * BN * kRS);          // [2^b]
+
+  // ---- workgroup -> (m block, n block); consecutive ids go to consecutive XCDs
+  int mb, nb;
+  {
+    const int L = blockIdx.x;
+    if (m_blocks >= 8) {
+      const int xcd = L & 7, s = L >> 3;
+      const int per_xcd = (m_blocks + 7) >> 3;
+      mb = xcd + 8 * (s % per_xcd);
+      nb = s / per_xcd;
+    } else {
+      mb = L % m_blocks;
+      nb = L / m_blocks;
+    }
+    if (mb >= m_blocks || nb >= n_blocks) return;
+  }
+  const int m0 = mb * kBM, n0 = nb * BN;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int ntiles = (d.nchunks + kCH - 1) / kCH;
+
+  for (int k = tid; k < (1 << d.b); k += (kMW + kDW) * 64) cb[k] = codebook[k];
+  __syncthreads();
+
+  if (wave >= kMW) {
+    // =============================== decoder waves ===============================
+    const int did = tid - kMW * 64;                      // 0 .. 255
+    const uint32_t one2 = BF16 ? 0x3F803F80u : 0x3C003C00u;
+    for (int t = 0; t <= ntiles; ++t) {
+      if (t < ntiles) {
+        // work items (weight row r, half): 8 chunks = 80 values each, 64 NF items per tile
+        for (int item = did; item < 2 * BN; item += kDW * 64) {
+          const int r = item >> 1, half = item & 1;
+          const int n = n0 + r;
+          const uint32_t* prow = packed + (long long)min(n, d.out - 1) * d.wpr;
+          uint16_t* dst = S + (t & 1) * (BN * kRS) + r * kRS + half * (8 * kV);
+          const int j0 = t * kCH + half * 8;
+          uint32_t code[8];
+#pragma unroll
+          for (int c = 0; c < 8; ++c) {
+            const int j = j0 + c;
+            code[c] = (j < d.nchunks && n < d.out) ? field_at(prow, d.wpr, j * d.b, d.b) : 0xFFFFFFFFu;
+          }
+#pragma unroll
+          for (int c = 0; c < 8; ++c) {
+            uint32_t w[5];
+            if (code[c] != 0xFFFFFFFFu) {
+              const uint32_t npat = ~cb[code[c]];
+#pragma unroll
+              for (int p = 0; p < 5; ++p)
+                w[p] = one2 | ((npat << (15 - 2 * p)) & 0x8000u) | ((npat << (30 - 2 * p)) & 0x80000000u);
+            } else {
+#pragma unroll
+              for (int p = 0; p < 5; ++p) w[p] = 0u;     // beyond the matrix: zeros
+            }
+            uint32_t* o = (uint32_t*)(dst + c * kV);     // 20-byte chunks: 4-byte aligned
+#pragma unroll
+            for (int p = 0; p < 5; ++p) o[p] = w[p];
+          }
+        }
+      }
+      __syncthreads();                                   // tile t is complete; tile t-1 has been consumed
+    }
+    return;
+  }
+
+  // ================================= contraction waves =================================
+  const int h = lane >> 5, l32 = lane & 31;
+  f32x16 acc[2][NF];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int c = 0; c < NF; ++c)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[a][c][e] = 0.f;
+
+  // A operand: lane (row l32 of fragment a, h) reads X[m][k0 + 32 T + 16 h .. + 15]
+  const __amdgpu_buffer_rsrc_t rX =
+      __builtin_amdgcn_make_buffer_rsrc((void*)X, 0, (int)((long long)M * d.in * 2), kRsrcFlags);
+  uint32_t xoff[2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a) {
+    const int m = m0 + wave * 64 + a * 32 + l32;
+    xoff[a] = (m < M) ? (uint32_t)(((long long)m * d.in + 16 * h) * 2) : kOob;
+  }
+  auto load_a = [&](uint4 (&dst)[2][2], int k0) {        // k0: first column of a block of 32
+    const bool in_range = k0 + 16 * h + 16 <= d.in;      // `in` is a multiple of 16 for this kernel
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+      const uint32_t off = in_range ? xoff[a] + (uint32_t)k0 * 2u : kOob;
+      dst[a][0] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rX, off, 0, 0));
+      dst[a][1] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rX, off + 16u, 0, 0));
+    }
+  };
+
+  uint4 cur[2][2], nxt[2][2];                            // [fragment][k-slice]: block in use, block in flight
+  load_a(cur, 0);
+  __syncthreads();                                       // tile 0 decoded
+  const uint16_t* sbase = S + l32 * kRS + 16 * h;
+  for (int t = 0; t < ntiles; ++t) {
+    const uint16_t* st = sbase + (t & 1) * (BN * kRS);
+#pragma unroll
+    for (int T = 0; T < kKT / 32; ++T) {
+      // next block of activations (possibly the first block of the next tile)
+      load_a(nxt, t * kKT + (T + 1) * 32);
+#pragma unroll
+      for (int s = 0; s < 2; ++s) {
+        uint4 bfr[NF];
+#pragma unroll
+        for (int c = 0; c < NF; ++c) bfr[c] = *(const uint4*)(st + c * 32 * kRS + T * 32 + 8 * s);
+#pragma unroll
+        for (int c = 0; c < NF; ++c) {
+          acc[0][c] = mfma32<BF16>(cur[0][s], bfr[c], acc[0][c]);
+          acc[1][c] = mfma32<BF16>(cur[1][s], bfr[c], acc[1][c]);
+        }
+      }
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int s = 0; s < 2; ++s) cur[a][s] = nxt[a][s];
+    }
+    __syncthreads();                                     // tile t consumed; tile t+1 decoded
+  }
+
+  // ---- epilogue: lane holds weight row n (column of D), 16 activation rows per accumulator
+#pragma unroll
+  for (int c = 0; c < NF; ++c) {
+    const int n = n0 + c * 32 + l32;
+    if (n >= d.out) continue;
+    const float al = alpha[n], mn = mu[n];
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int m = m0 + wave * 64 + a * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
+        if (m >= M) continue;
+        const float r = al * acc[a][c][e] + mn * rowsum[m];
+        const long long o = (long long)m * d.out + n;
+        if (y_dtype == BTC_F32) ((float*)Y)[o] = r;
+        else if (y_dtype == BTC_BF16) ((__hip_bfloat16*)Y)[o] = __float2bfloat16(r);
+        else ((__half*)Y)[o] = __float2half_rn(r);
+      }
+    }
+  }
+}
+
+template <int NF>
+static size_t lds_bytes(int b) { return (size_t)2 * 32 * NF * kRS * 2 + ((size_t)4 << b); }
+
+template <int NF, bool BF16>
+static btc_status launch(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
+                         const float* alpha, const float* mu, const void* X, int M, void* Y, int y_dtype,
+                         const float* rowsum) {
+  static bool attr_set = false;  // one-time kernel attribute, not call state
+  if (!attr_set) {
+    if (hipFuncSetAttribute((const void*)gemm_tiled_kernel<NF, BF16>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            160 * 1024) != hipSuccess)
+      return BTC_ERR_HIP;
+    attr_set = true;
+  }
+  const int m_blocks = (M + kBM - 1) / kBM, n_blocks = (d.out + 32 * NF - 1) / (32 * NF);
+  int grid;
+  if (m_blocks >= 8) grid = 8 * ((m_blocks + 7) / 8) * n_blocks;
+  else grid = m_blocks * n_blocks;
+  gemm_tiled_kernel<NF, BF16><<<grid, (kMW + kDW) * 64, lds_bytes<NF>(d.b), q>>>(
+      d, packed, codebook, alpha, mu, (const uint16_t*)X, M, Y, y_dtype, rowsum, m_blocks, n_blocks);
+  return launch_status();
+}
+
+// Weight rows per workgroup (32 NF): the candidate that wastes the fewest CU
+// slots over whole rounds of 256 workgroups, larger NF on ties.
+static int pick_nf(const Dims& d, int M) {
+  const int m_blocks = (M + kBM - 1) / kBM;
+  int best = 4;
+  double best_eff = -1.0;
+  for (int nf = 4; nf <= 5; ++nf) {
+    const long long wgs = (long long)m_blocks * ((d.out + 32 * nf - 1) / (32 * nf));
+    const long long rounds = (wgs + 255) / 256;
+    const double useful = (double)M * d.out;
+    const double paid = (double)rounds * 256 * kBM * 32 * nf;
+    const double eff = useful / paid;
+    if (eff > best_eff + 1e-9 || (eff > best_eff - 1e-9 && nf > best)) {
+      best_eff = eff;
+      best = nf;
+    }
+  }
+  return best;
+}
+
+}  // namespace tiled
+
+bool gemm_tiled_covers(const Dims& d, int M) {
+  if (d.v != tiled::kV || d.b > 10) return false;
+  if (d.in % 16 != 0) return false;                           // 16-byte aligned, whole 16-element A loads
+  if ((long long)M * d.in * 2 >= (1LL << 31)) return false;   // 32-bit buffer offsets
+  return M >= 64;
+}
+
+btc_status gemm_tiled(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
+                      const float* alpha, const float* mu, const void* X, int is_bf16, int M, void* Y, int y_dtype,
+                      const float* rowsum) {
+  using namespace tiled;
+  const int nf = pick_nf(d, M);
+#define BTC_TILED_CASE(NFV)                                                                                         \
+  if (nf == NFV)                                                                                                    \
+    return is_bf16 ? launch<NFV, true>(q, d, packed, codebook, alpha, mu, X, M, Y, y_dtype, rowsum)                 \
+                   : launch<NFV, false>(q, d, packed, codebook, alpha, mu, X, M, Y, y_dtype, rowsum)
+  BTC_TILED_CASE(4);
+  BTC_TILED_CASE(5);
+#undef BTC_TILED_CASE
+  return BTC_ERR_UNSUPPORTED;
+}
+
+}  // namespace btc

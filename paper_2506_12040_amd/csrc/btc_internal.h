@@ -35,6 +35,15 @@ btc_status gemv_expand(hipStream_t q, const Dims& d, const uint32_t* packed, con
 btc_status gemv_generic(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
                         const float* alpha, const float* mu, const void* x, int batch, void* y, int y_is_f32);
 
+// Prefill kernels: the tuned tiling (btc_gemm_tiled.hip) and the generic one (btc_gemm_generic.hip).
+bool gemm_tiled_covers(const Dims& d, int M);
+btc_status gemm_tiled(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
+                      const float* alpha, const float* mu, const void* X, int is_bf16, int M, void* Y, int y_dtype,
+                      const float* rowsum);
+btc_status gemm_generic(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
+                        const float* alpha, const float* mu, const void* X, int is_bf16, int M, void* Y,
+                        int y_dtype, const float* rowsum);
+
 inline btc_status launch_status() {
   return hipGetLastError() == hipSuccess ? BTC_OK : BTC_ERR_HIP;
 }
