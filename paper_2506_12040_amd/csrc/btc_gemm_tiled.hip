@@ -27,6 +27,8 @@
 #include <hip/hip_bf16.h>
 #include <hip/hip_fp16.h>
 
+#include <type_traits>
+
 #include "btc_internal.h"
 
 namespace btc {
@@ -91,36 +93,68 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
     // =============================== decoder waves ===============================
     const int did = tid - kMW * 64;                      // 0 .. 255
     const uint32_t one2 = BF16 ? 0x3F803F80u : 0x3C003C00u;
+    // Work items (weight row r, half): 8 chunks = 80 values each, 64 NF items per tile;
+    // a thread owns items did and did + 256 (the second one only if it exists).
+    constexpr int NI = (2 * BN + kDW * 64 - 1) / (kDW * 64);
+    const uint32_t pk_bytes = (uint32_t)d.out * (uint32_t)d.wpr * 4u;
+    const __amdgpu_buffer_rsrc_t rP = __builtin_amdgcn_make_buffer_rsrc((void*)packed, 0, (int)pk_bytes, kRsrcFlags);
+    uint32_t W[NI][4];
+    // the 8 b-bit fields of an item start at bit (t*16 + half*8) * b of the row: at most 4 words
+    auto fetch = [&](int t) {
+#pragma unroll
+      for (int it = 0; it < NI; ++it) {
+        const int item = did + it * kDW * 64;
+        const int r = item >> 1, half = item & 1;
+        const int n = n0 + r;
+        const int w0 = ((t * kCH + half * 8) * d.b) >> 5;
+        const bool ok = item < 2 * BN && n < d.out;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const uint32_t off = (ok && w0 + u < d.wpr) ? ((uint32_t)n * (uint32_t)d.wpr + (uint32_t)(w0 + u)) * 4u : kOob;
+          W[it][u] = __builtin_amdgcn_raw_buffer_load_b32(rP, off, 0, 0);
+        }
+      }
+    };
+    fetch(0);
     for (int t = 0; t <= ntiles; ++t) {
       if (t < ntiles) {
-        // work items (weight row r, half): 8 chunks = 80 values each, 64 NF items per tile
-        for (int item = did; item < 2 * BN; item += kDW * 64) {
-          const int r = item >> 1, half = item & 1;
-          const int n = n0 + r;
-          const uint32_t* prow = packed + (long long)min(n, d.out - 1) * d.wpr;
-          uint16_t* dst = S + (t & 1) * (BN * kRS) + r * kRS + half * (8 * kV);
-          const int j0 = t * kCH + half * 8;
-          uint32_t code[8];
+        uint32_t A[NI][3];
 #pragma unroll
-          for (int c = 0; c < 8; ++c) {
-            const int j = j0 + c;
-            code[c] = (j < d.nchunks && n < d.out) ? field_at(prow, d.wpr, j * d.b, d.b) : 0xFFFFFFFFu;
-          }
+        for (int it = 0; it < NI; ++it) {                // align the window to the first field
+          const int half = (did + it * kDW * 64) & 1;
+          const uint32_t s0 = (uint32_t)((t * kCH + half * 8) * d.b) & 31u;
 #pragma unroll
-          for (int c = 0; c < 8; ++c) {
-            uint32_t w[5];
-            if (code[c] != 0xFFFFFFFFu) {
-              const uint32_t npat = ~cb[code[c]];
+          for (int u = 0; u < 3; ++u) A[it][u] = __builtin_amdgcn_alignbit(W[it][u + 1], W[it][u], s0);
+        }
+        if (t + 1 < ntiles) fetch(t + 1);                // next tile's words fly while this one is expanded
 #pragma unroll
-              for (int p = 0; p < 5; ++p)
-                w[p] = one2 | ((npat << (15 - 2 * p)) & 0x8000u) | ((npat << (30 - 2 * p)) & 0x80000000u);
-            } else {
+        for (int it = 0; it < NI; ++it) {
+          const int item = did + it * kDW * 64;
+          if (item < 2 * BN) {
+            const int r = item >> 1, half = item & 1;
+            const bool row_ok = n0 + r < d.out;
+            uint16_t* dst = S + (t & 1) * (BN * kRS) + r * kRS + half * (8 * kV);
+            const int j0 = t * kCH + half * 8;
+            const uint32_t mask = (1u << d.b) - 1u;
 #pragma unroll
-              for (int p = 0; p < 5; ++p) w[p] = 0u;     // beyond the matrix: zeros
+            for (int c = 0; c < 8; ++c) {
+              // field c sits at bit c*b of the aligned window (b <= 10: inside 3 words)
+              const uint32_t pos = (uint32_t)(c * d.b);
+              const uint32_t wlo = pos < 32 ? A[it][0] : (pos < 64 ? A[it][1] : A[it][2]);
+              const uint32_t whi = pos < 32 ? A[it][1] : A[it][2];
+              const uint32_t code = __builtin_amdgcn_alignbit(whi, wlo, pos & 31u) & mask;
+              uint32_t w[5];
+              const uint32_t npat = ~cb[code];
+              const bool ok = row_ok && j0 + c < d.nchunks;
+#pragma unroll
+              for (int p = 0; p < 5; ++p) {
+                const uint32_t v2 = one2 | ((npat << (15 - 2 * p)) & 0x8000u) | ((npat << (30 - 2 * p)) & 0x80000000u);
+                w[p] = ok ? v2 : 0u;                     // beyond the matrix: zeros
+              }
+              uint32_t* o = (uint32_t*)(dst + c * kV);   // 20-byte chunks: 4-byte aligned
+#pragma unroll
+              for (int p = 0; p < 5; ++p) o[p] = w[p];
             }
-            uint32_t* o = (uint32_t*)(dst + c * kV);     // 20-byte chunks: 4-byte aligned
-#pragma unroll
-            for (int p = 0; p < 5; ++p) o[p] = w[p];
           }
         }
       }
@@ -149,42 +183,57 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
     xoff[a] = (m < M) ? (uint32_t)(((long long)m * d.in + 16 * h) * 2) : kOob;
   }
   auto load_a = [&](uint4 (&dst)[2][2], int k0) {        // k0: first column of a block of 32
-    const bool in_range = k0 + 16 * h + 16 <= d.in;      // `in` is a multiple of 16 for this kernel
+    // `in` is a multiple of 16 for this kernel; past the end bit 31 of the offset is set (no branch)
+    const uint32_t past = (uint32_t)(k0 + 16 * h + 16 > d.in) << 31;
 #pragma unroll
     for (int a = 0; a < 2; ++a) {
-      const uint32_t off = in_range ? xoff[a] + (uint32_t)k0 * 2u : kOob;
+      const uint32_t off = (xoff[a] + (uint32_t)k0 * 2u) | past;
       dst[a][0] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rX, off, 0, 0));
       dst[a][1] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rX, off + 16u, 0, 0));
     }
   };
 
-  uint4 cur[2][2], nxt[2][2];                            // [fragment][k-slice]: block in use, block in flight
-  load_a(cur, 0);
+  // Software pipeline.  Activations: two register slots, the block after the one in use is
+  // in flight.  Pattern fragments: the NF fragments of the next k-slice are read from LDS
+  // while the 2 NF MFMAs of the current slice run.  Slots are compile-time (PAR = parity of
+  // the tile, 5 blocks per tile), so nothing is indexed dynamically.
+  constexpr int NB = kKT / 32;                           // blocks per k-tile
+  uint4 ablk[2][2][2];                                   // [slot][fragment][k-slice]
+  uint4 bfr[2][NF];                                      // [slot][fragment]
+  load_a(ablk[0], 0);
+  load_a(ablk[1], 32);
   __syncthreads();                                       // tile 0 decoded
   const uint16_t* sbase = S + l32 * kRS + 16 * h;
-  for (int t = 0; t < ntiles; ++t) {
-    const uint16_t* st = sbase + (t & 1) * (BN * kRS);
+  auto read_b = [&](uint4 (&dst)[NF], const uint16_t* st, int T, int s) {
 #pragma unroll
-    for (int T = 0; T < kKT / 32; ++T) {
-      // next block of activations (possibly the first block of the next tile)
-      load_a(nxt, t * kKT + (T + 1) * 32);
+    for (int c = 0; c < NF; ++c) dst[c] = *(const uint4*)(st + c * 32 * kRS + T * 32 + 8 * s);
+  };
+  auto tile = [&](int t, auto par) {
+    constexpr int PAR = decltype(par)::value;
+    const uint16_t* st = sbase + PAR * (BN * kRS);
+    read_b(bfr[0], st, 0, 0);
+#pragma unroll
+    for (int T = 0; T < NB; ++T) {
+      constexpr int dummy = 0;
+      (void)dummy;
+      const int aslot = (T + PAR * NB) & 1;
 #pragma unroll
       for (int s = 0; s < 2; ++s) {
-        uint4 bfr[NF];
-#pragma unroll
-        for (int c = 0; c < NF; ++c) bfr[c] = *(const uint4*)(st + c * 32 * kRS + T * 32 + 8 * s);
+        const int q = 2 * T + s;                         // slice number inside the tile
+        if (q + 1 < 2 * NB) read_b(bfr[(q + 1) & 1], st, (q + 1) >> 1, (q + 1) & 1);
 #pragma unroll
         for (int c = 0; c < NF; ++c) {
-          acc[0][c] = mfma32<BF16>(cur[0][s], bfr[c], acc[0][c]);
-          acc[1][c] = mfma32<BF16>(cur[1][s], bfr[c], acc[1][c]);
+          acc[0][c] = mfma32<BF16>(ablk[aslot][0][s], bfr[q & 1][c], acc[0][c]);
+          acc[1][c] = mfma32<BF16>(ablk[aslot][1][s], bfr[q & 1][c], acc[1][c]);
         }
       }
-#pragma unroll
-      for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int s = 0; s < 2; ++s) cur[a][s] = nxt[a][s];
+      load_a(ablk[aslot], t * kKT + (T + 2) * 32);       // two blocks ahead (zeros past the end)
     }
     __syncthreads();                                     // tile t consumed; tile t+1 decoded
+  };
+  for (int t = 0; t < ntiles; t += 2) {
+    tile(t, std::integral_constant<int, 0>{});
+    if (t + 1 < ntiles) tile(t + 1, std::integral_constant<int, 1>{});
   }
 
   // ---- epilogue: lane holds weight row n (column of D), 16 activation rows per accumulator
