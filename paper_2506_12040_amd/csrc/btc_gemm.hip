@@ -17,7 +17,10 @@ __device__ __forceinline__ float load_as_float(const uint16_t* p, bool bf16) {
   return __half2float(__ushort_as_half(h));
 }
 
-// rowsum[m] = sum_k X[m][k] in fp32, one wave per row, fixed order.
+// rowsum[m] = sum_k X[m][k] in fp32, one wave per row, fixed order: lane l adds
+// elements 8l..8l+7 of every block of 512 (16-byte loads), then the lanes are
+// added by a butterfly.  Rows whose length is not a multiple of 8 take the
+// element-wise path.
 __global__ __launch_bounds__(256) void rowsum_kernel(const uint16_t* __restrict__ X, int M, int in, int is_bf16,
                                                      float* __restrict__ rowsum) {
   const int lane = threadIdx.x & 63;
@@ -25,7 +28,24 @@ __global__ __launch_bounds__(256) void rowsum_kernel(const uint16_t* __restrict_
   if (m >= M) return;
   const uint16_t* row = X + (long long)m * in;
   float s = 0.f;
-  for (int k = lane; k < in; k += 64) s += load_as_float(row + k, is_bf16 != 0);
+  if ((in & 7) == 0) {
+    for (int k = lane * 8; k < in; k += 512) {
+      const uint4 v = *(const uint4*)(row + k);
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if (is_bf16) {
+          s += __uint_as_float(w[i] << 16);
+          s += __uint_as_float(w[i] & 0xFFFF0000u);
+        } else {
+          s += __half2float(__ushort_as_half((uint16_t)(w[i] & 0xFFFFu)));
+          s += __half2float(__ushort_as_half((uint16_t)(w[i] >> 16)));
+        }
+      }
+    }
+  } else {
+    for (int k = lane; k < in; k += 64) s += load_as_float(row + k, is_bf16 != 0);
+  }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
   if (lane == 0) rowsum[m] = s;

@@ -64,7 +64,7 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
   constexpr int BN = 32 * NF;
   extern __shared__ __align__(16) unsigned char smem[];
   uint16_t* S = (uint16_t*)smem;                         // [2][BN][kRS]
-  uint32_t* cb = (uint32_t*)(S + 2 * BN * kRS);          // [2^b]
+  uint32_t* E = (uint32_t*)(S + 2 * BN * kRS);           // [2^b][8]: codeword -> 5 dwords of +-1 pairs
 
   // ---- workgroup -> (m block, n block); consecutive ids go to consecutive XCDs
   int mb, nb;
@@ -86,13 +86,23 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int ntiles = (d.nchunks + kCH - 1) / kCH;
 
-  for (int k = tid; k < (1 << d.b); k += (kMW + kDW) * 64) cb[k] = codebook[k];
+  {
+    const uint32_t one2 = BF16 ? 0x3F803F80u : 0x3C003C00u;
+    for (int k = tid; k < (1 << d.b); k += (kMW + kDW) * 64) {
+      const uint32_t npat = ~codebook[k];
+      uint32_t e[5];
+#pragma unroll
+      for (int p = 0; p < 5; ++p)
+        e[p] = one2 | ((npat << (15 - 2 * p)) & 0x8000u) | ((npat << (30 - 2 * p)) & 0x80000000u);
+      *(uint4*)(E + 8 * k) = make_uint4(e[0], e[1], e[2], e[3]);
+      E[8 * k + 4] = e[4];
+    }
+  }
   __syncthreads();
 
   if (wave >= kMW) {
     // =============================== decoder waves ===============================
     const int did = tid - kMW * 64;                      // 0 .. 255
-    const uint32_t one2 = BF16 ? 0x3F803F80u : 0x3C003C00u;
     // Work items (weight row r, half): 8 chunks = 80 values each, 64 NF items per tile;
     // a thread owns items did and did + 256 (the second one only if it exists).
     constexpr int NI = (2 * BN + kDW * 64 - 1) / (kDW * 64);
@@ -143,13 +153,13 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
               const uint32_t wlo = pos < 32 ? A[it][0] : (pos < 64 ? A[it][1] : A[it][2]);
               const uint32_t whi = pos < 32 ? A[it][1] : A[it][2];
               const uint32_t code = __builtin_amdgcn_alignbit(whi, wlo, pos & 31u) & mask;
-              uint32_t w[5];
-              const uint32_t npat = ~cb[code];
               const bool ok = row_ok && j0 + c < d.nchunks;
+              const uint4 e4 = *(const uint4*)(E + 8 * code);
+              const uint32_t e5 = E[8 * code + 4];
+              uint32_t w[5] = {e4.x, e4.y, e4.z, e4.w, e5};
+              if (!ok) {                                 // beyond the matrix: zeros (rare, edge tiles only)
 #pragma unroll
-              for (int p = 0; p < 5; ++p) {
-                const uint32_t v2 = one2 | ((npat << (15 - 2 * p)) & 0x8000u) | ((npat << (30 - 2 * p)) & 0x80000000u);
-                w[p] = ok ? v2 : 0u;                     // beyond the matrix: zeros
+                for (int p = 0; p < 5; ++p) w[p] = 0u;
               }
               uint32_t* o = (uint32_t*)(dst + c * kV);   // 20-byte chunks: 4-byte aligned
 #pragma unroll
@@ -259,7 +269,7 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
 }
 
 template <int NF>
-static size_t lds_bytes(int b) { return (size_t)2 * 32 * NF * kRS * 2 + ((size_t)4 << b); }
+static size_t lds_bytes(int b) { return (size_t)2 * 32 * NF * kRS * 2 + ((size_t)32 << b); }
 
 template <int NF, bool BF16>
 static btc_status launch(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
