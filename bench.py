@@ -51,9 +51,11 @@ def main():
     ap.add_argument("--layers", type=int, default=40, help="distinct weight copies walked by consecutive steps")
     ap.add_argument("--mode", choices=["graph", "stream"], default="graph")
     ap.add_argument("--gemm-m", type=int, default=2048)
-    ap.add_argument("--gemm-iters", type=int, default=5)
+    ap.add_argument("--gemm-iters", type=int, default=10)
     ap.add_argument("--no-gemm", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run three 256 MiB device-to-device copies (reference for FETCH_SIZE/WRITE_SIZE) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); nothing here uses a second GPU", file=sys.stderr)
@@ -64,6 +66,15 @@ def main():
     import paper_2506_12040_amd as B
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
+    if args.copy_calibration:
+        a = torch.full((256 << 20,), 1, dtype=torch.uint8, device="cuda:0")
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes": 256 << 20, "copies": 3}))
+        return
     B.lib()  # raises if the HIP library was not built
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -170,38 +181,38 @@ def main():
                                                         eff_GBps=round(by / us / 1e3, 1),
                                                         frac_hbm=round(by / us / 1e3 / HBM_PEAK_GBS, 4))
 
-    # ---- prefill GEMM on the same shapes
+    # ---- prefill GEMM on the same shapes (btc_gemm = row-sum kernel + contraction kernel per call)
     gemm = None
     if not args.no_gemm:
-        M = args.gemm_m
         gemm = {}
-        tot_flop, tot_ms = 0.0, 0.0
-        for p in protos:
-            s = p["s"]
-            rng = np.random.Generator(np.random.PCG64(0))
-            Xb = S.draw_x(rng, M, s.in_, "bf16")
-            X = torch.from_numpy(Xb.view(np.int16)).to(dev)
-            Y = torch.empty(M * s.out, dtype=torch.float32, device=dev)
-            wsg = torch.zeros(B.btc_workspace_bytes(s, M, True), dtype=torch.uint8, device=dev)
-            call = lambda: B.btc_gemm(s, p["packed"], p["codebook"], p["alpha"], p["mu"], X, B.BTC_BF16, M, Y,
-                                      B.BTC_F32, wsg)
-            call()
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(args.gemm_iters):
+        for M in sorted({args.gemm_m, 512}, reverse=True):
+            per, tot_flop, tot_ms = {}, 0.0, 0.0
+            for p in protos:
+                s = p["s"]
+                rng = np.random.Generator(np.random.PCG64(0))
+                Xb = S.draw_x(rng, M, s.in_, "bf16")
+                X = torch.from_numpy(Xb.view(np.int16)).to(dev)
+                Y = torch.empty(M * s.out, dtype=torch.float32, device=dev)
+                wsg = torch.zeros(B.btc_workspace_bytes(s, M, True), dtype=torch.uint8, device=dev)
+                call = lambda: B.btc_gemm(s, p["packed"], p["codebook"], p["alpha"], p["mu"], X, B.BTC_BF16, M, Y,
+                                          B.BTC_F32, wsg)
                 call()
-            e1.record()
-            torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / args.gemm_iters
-            flop = 2.0 * M * s.out * s.in_
-            gemm[f"{s.out}x{s.in_}"] = dict(ms=round(ms, 4), tflops=round(flop / ms / 1e9, 1))
-            tot_flop += flop * p["count"]
-            tot_ms += ms * p["count"]
-            del X, Y
-        gemm_tflops = tot_flop / tot_ms / 1e9
-        gemm = dict(M=M, x_dtype="bf16", y_dtype="f32", per_shape=gemm, layer_tflops=round(gemm_tflops, 1),
-                    frac_mfma_peak=round(gemm_tflops / MFMA_BF16_PEAK_TFLOPS, 4))
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(args.gemm_iters):
+                    call()
+                e1.record()
+                torch.cuda.synchronize()
+                ms = e0.elapsed_time(e1) / args.gemm_iters
+                flop = 2.0 * M * s.out * s.in_
+                per[f"{s.out}x{s.in_}"] = dict(ms=round(ms, 4), tflops=round(flop / ms / 1e9, 1))
+                tot_flop += flop * p["count"]
+                tot_ms += ms * p["count"]
+                del X, Y
+            tf = tot_flop / tot_ms / 1e9
+            gemm[f"M{M}"] = dict(M=M, x_dtype="bf16", y_dtype="f32", per_shape=per, layer_tflops=round(tf, 1),
+                                 frac_mfma_peak=round(tf / MFMA_BF16_PEAK_TFLOPS, 4))
 
     # ---- CPU oracle on the host cores, bounded sample of the same workload
     cpu = None
@@ -250,6 +261,11 @@ def main():
         "roofline": {"bound": "hbm", "achieved": round(value, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(value / HBM_PEAK_GBS, 4), "traffic": None,
                      "note": "algorithmic bytes of the 7 calls of a step / event-timed duration of a step"},
+        "roofline_gemm": None if gemm is None else {
+            "bound": "mfma", "achieved": gemm[f"M{args.gemm_m}"]["layer_tflops"], "peak": MFMA_BF16_PEAK_TFLOPS,
+            "unit": "TFLOP/s", "frac": gemm[f"M{args.gemm_m}"]["frac_mfma_peak"], "traffic": None,
+            "note": f"2*M*out*in flop of the 7 projections at M={args.gemm_m} / event-timed btc_gemm calls "
+                    "(row-sum kernel included)"},
         "cpu_baseline": cpu,
         "setup_s": round(t_setup, 1),
     }
