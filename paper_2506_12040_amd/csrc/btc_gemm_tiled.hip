@@ -147,7 +147,11 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
             const int j0 = t * kCH + half * 8;
             const uint32_t mask = (1u << d.b) - 1u;
 #pragma unroll
-            for (int c = 0; c < 8; ++c) {
+            for (int cs = 0; cs < 8; ++cs) {
+              // The lanes of a wave walk their 8 chunks in different rotations: with a common
+              // order all rows would hit the same 8 LDS banks (the row stride is a multiple of
+              // 16 bytes), rotated they spread over all of them.
+              const int c = (cs + r + (r >> 3)) & 7;
               // field c sits at bit c*b of the aligned window (b <= 10: inside 3 words)
               const uint32_t pos = (uint32_t)(c * d.b);
               const uint32_t wlo = pos < 32 ? A[it][0] : (pos < 64 ? A[it][1] : A[it][2]);
@@ -174,6 +178,7 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
   }
 
   // ================================= contraction waves =================================
+  __builtin_amdgcn_s_setprio(2);                         // the matrix pipe is the bottleneck: issue these first
   const int h = lane >> 5, l32 = lane & 31;
   f32x16 acc[2][NF];
 #pragma unroll
@@ -246,26 +251,35 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
     if (t + 1 < ntiles) tile(t + 1, std::integral_constant<int, 1>{});
   }
 
-  // ---- epilogue: lane holds weight row n (column of D), 16 activation rows per accumulator
+  // ---- epilogue: lane holds weight row n (column of D), 16 activation rows per accumulator.
+  // The 32 row sums a lane needs are fetched first, all loads in flight together.
+  float rs[2][16];
 #pragma unroll
-  for (int c = 0; c < NF; ++c) {
-    const int n = n0 + c * 32 + l32;
-    if (n >= d.out) continue;
-    const float al = alpha[n], mn = mu[n];
+  for (int a = 0; a < 2; ++a)
 #pragma unroll
-    for (int a = 0; a < 2; ++a) {
+    for (int e = 0; e < 16; ++e) {
+      const int m = m0 + wave * 64 + a * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
+      rs[a][e] = rowsum[min(m, M - 1)];
+    }
+  auto store_all = [&](auto* Yt, auto cvt) {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int m = m0 + wave * 64 + a * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
-        if (m >= M) continue;
-        const float r = al * acc[a][c][e] + mn * rowsum[m];
-        const long long o = (long long)m * d.out + n;
-        if (y_dtype == BTC_F32) ((float*)Y)[o] = r;
-        else if (y_dtype == BTC_BF16) ((__hip_bfloat16*)Y)[o] = __float2bfloat16(r);
-        else ((__half*)Y)[o] = __float2half_rn(r);
+    for (int c = 0; c < NF; ++c) {
+      const int n = n0 + c * 32 + l32;
+      if (n >= d.out) continue;
+      const float al = alpha[n], mn = mu[n];
+#pragma unroll
+      for (int a = 0; a < 2; ++a) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int m = m0 + wave * 64 + a * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
+          if (m < M) Yt[(long long)m * d.out + n] = cvt(al * acc[a][c][e] + mn * rs[a][e]);
+        }
       }
     }
-  }
+  };
+  if (y_dtype == BTC_F32) store_all((float*)Y, [](float r) { return r; });
+  else if (y_dtype == BTC_BF16) store_all((__hip_bfloat16*)Y, [](float r) { return __float2bfloat16(r); });
+  else store_all((__half*)Y, [](float r) { return __float2half_rn(r); });
 }
 
 template <int NF>
