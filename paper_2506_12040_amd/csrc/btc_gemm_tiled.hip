@@ -305,20 +305,21 @@ static btc_status launch(hipStream_t q, const Dims& d, const uint32_t* packed, c
   return launch_status();
 }
 
-// Weight rows per workgroup (32 NF): the candidate that wastes the fewest CU
-// slots over whole rounds of 256 workgroups, larger NF on ties.
+// Weight rows per workgroup (32 NF).  One workgroup occupies a CU, so the kernel time is
+// rounds x (time of one workgroup), and a workgroup's time grows with NF (2 NF MFMAs per
+// k-slice) plus a part that does not (activation loads, decode, barriers: about two
+// fragments' worth).  Pick the NF with the smallest estimate; few activation rows
+// therefore get narrow workgroups that fill more CUs.
 static int pick_nf(const Dims& d, int M) {
   const int m_blocks = (M + kBM - 1) / kBM;
-  int best = 4;
-  double best_eff = -1.0;
-  for (int nf = 4; nf <= 5; ++nf) {
+  int best = 5;
+  double best_cost = 1e300;
+  for (int nf = 2; nf <= 5; ++nf) {
     const long long wgs = (long long)m_blocks * ((d.out + 32 * nf - 1) / (32 * nf));
     const long long rounds = (wgs + 255) / 256;
-    const double useful = (double)M * d.out;
-    const double paid = (double)rounds * 256 * kBM * 32 * nf;
-    const double eff = useful / paid;
-    if (eff > best_eff + 1e-9 || (eff > best_eff - 1e-9 && nf > best)) {
-      best_eff = eff;
+    const double cost = (double)rounds * (nf + 2.0);
+    if (cost < best_cost - 1e-9 || (cost < best_cost + 1e-9 && nf > best)) {
+      best_cost = cost;
       best = nf;
     }
   }
@@ -343,6 +344,8 @@ btc_status gemm_tiled(hipStream_t q, const Dims& d, const uint32_t* packed, cons
   if (nf == NFV)                                                                                                    \
     return is_bf16 ? launch<NFV, true>(q, d, packed, codebook, alpha, mu, X, M, Y, y_dtype, rowsum)                 \
                    : launch<NFV, false>(q, d, packed, codebook, alpha, mu, X, M, Y, y_dtype, rowsum)
+  BTC_TILED_CASE(2);
+  BTC_TILED_CASE(3);
   BTC_TILED_CASE(4);
   BTC_TILED_CASE(5);
 #undef BTC_TILED_CASE

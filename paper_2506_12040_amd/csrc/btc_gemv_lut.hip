@@ -52,7 +52,6 @@ constexpr int kRsrcFlags = 0x00020000;  // raw buffer, 32-bit data format
 // this call, 0 = empty.  The finalising workgroup empties what it consumes,
 // so the whole workspace is zero between calls.
 struct LutWorkspace {
-  uint32_t* counter;             // [ceil(out/64)]        arrival counters
   unsigned long long* sx;        // [ceil(out/64)][n_ct]  per-column-block sum of x
   unsigned long long* partial;   // [n_ct][out]           per-column-block row sums
 };
@@ -62,7 +61,7 @@ static inline size_t round256(size_t n) { return (n + 255) & ~(size_t)255; }
 size_t lut_workspace_bytes(const btc_shape& s) {
   const size_t n_ct = (s.nchunks + kTileCols - 1) / kTileCols;
   const size_t n_rt = (s.out + kTileRows - 1) / kTileRows;
-  return round256(n_rt * 4) + round256(n_rt * n_ct * 8) + round256(n_ct * (size_t)s.out * 8);
+  return round256(n_rt * n_ct * 8) + round256(n_ct * (size_t)s.out * 8);
 }
 
 static LutWorkspace carve(void* ws, const Dims& d) {
@@ -70,8 +69,6 @@ static LutWorkspace carve(void* ws, const Dims& d) {
   const size_t n_rt = (d.out + kTileRows - 1) / kTileRows;
   char* p = (char*)ws;
   LutWorkspace w;
-  w.counter = (uint32_t*)p;
-  p += round256(n_rt * 4);
   w.sx = (unsigned long long*)p;
   p += round256(n_rt * n_ct * 8);
   w.partial = (unsigned long long*)p;
@@ -95,13 +92,12 @@ __device__ __forceinline__ void clear_slot(unsigned long long* p) {
 __device__ __forceinline__ unsigned long long load_slot(const unsigned long long* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-// Value of a slot whose store was issued before this workgroup learnt that it
-// is the last one: the store may still be in flight, so poll until the tag
-// shows up.  The bound only guards against a hang if a producer never ran.
+// Value of a slot that another workgroup writes: poll until the tag shows up.
+// The bound only guards against a hang if a producer never ran (then NaN).
 __device__ __forceinline__ float slot_value(const unsigned long long* p, unsigned long long first) {
   unsigned long long v = first;
   for (int spin = 0; (v >> 32) == 0 && spin < (1 << 22); ++spin) v = load_slot(p);
-  return __uint_as_float((uint32_t)v);
+  return (v >> 32) != 0 ? __uint_as_float((uint32_t)v) : __uint_as_float(0x7FC00000u);
 }
 
 // Bits (2i, 2i+1) of n -> two fp16 values, bit set => -1, clear => +1.
@@ -149,7 +145,6 @@ __global__ __launch_bounds__(NW * 64) void gemv_lut_kernel(Dims d, const uint32_
   extern __shared__ __align__(16) unsigned char smem[];
   uint32_t* table = (uint32_t*)smem;                                   // [2^B][32] dwords of 2 x fp16
   uint32_t* stage_all = (uint32_t*)(smem + Cfg::kTableBytes);
-  __shared__ int s_last;
 
   // Workgroups are dealt round-robin to the 8 XCDs; give each XCD whole row
   // blocks so that neighbouring column blocks of a row (which share HBM lines)
@@ -319,16 +314,17 @@ __global__ __launch_bounds__(NW * 64) void gemv_lut_kernel(Dims d, const uint32_
     if (row < d.out) store_slot(&ws.partial[ct * d.out + row], acc);
   }
 
-  // ---- last workgroup of this row block adds the column blocks in order.
-  // Partials travel as agent-scope (cache-bypassing) 8-byte stores {value, tag}
-  // that are not waited for: arrival is counted as soon as they are issued, and
-  // the last workgroup polls the few slots whose store has not landed yet.
-  // (Full agent-scope fences would write back and invalidate the whole L2 of
-  // the XCD -- tens of microseconds per workgroup.)
-  __syncthreads();
-  if (tid == 0) s_last = (atomicAdd(&ws.counter[rb], 1u) == (uint32_t)(n_ct - 1));
-  __syncthreads();
-  if (!s_last) return;
+  // ---- the workgroup of the LAST column block of this row block adds the column blocks
+  // in order.  Partials travel as agent-scope (cache-bypassing) 8-byte stores {value, tag}
+  // that nobody waits for; the reducing workgroup polls each slot until its tag shows up.
+  // Why this cannot hang: producers never wait for anything, and the reducer has the
+  // highest workgroup id of its row block (same XCD, ids differ by multiples of 8), so the
+  // in-order dispatcher has already placed every producer when the reducer starts.  The
+  // poll is bounded all the same; a slot that never arrives yields NaN, not a hang.
+  // (An arrival counter would cost a device-scope atomic round trip per workgroup; full
+  // agent-scope fences would write back and invalidate the XCD's whole L2, tens of
+  // microseconds per workgroup.)
+  if (ct != n_ct - 1) return;
   // sum of x: every thread adds the column-block sums in the same order
   float* sx_buf = (float*)stage_all;  // staging space is free now
   const int rows_per_wg = RT * NW * kTileRows;
@@ -373,7 +369,6 @@ __global__ __launch_bounds__(NW * 64) void gemv_lut_kernel(Dims d, const uint32_
     if (y_is_f32) ((float*)y)[row] = res;
     else ((__half*)y)[row] = __float2half_rn(res);
   }
-  if (tid == 0) ws.counter[rb] = 0u;  // leave the counters zero for the next call
 }
 
 template <int B, int NW, bool DUP, bool WIDE_V, bool X_DWORD>
@@ -419,8 +414,7 @@ bool lut_engine_covers(const Dims& d) {
   return n_ct * d.out < (1LL << 29);
 }
 
-// One activation row; `ws` must hold lut_workspace_bytes() bytes whose counter
-// area is zero (it is left zero).
+// One activation row; `ws` must hold lut_workspace_bytes() zero bytes (it is left zero).
 btc_status gemv_lut(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
                     const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, void* ws) {
   switch (d.b) {
