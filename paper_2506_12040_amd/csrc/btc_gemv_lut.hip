@@ -5,7 +5,7 @@
 // computed once per chunk column j and gathered by the indices of many rows.
 // This kernel keeps that idea and changes how it is carried out on CDNA4:
 //
-//  * A workgroup owns 64 consecutive chunk columns and R rows.  Its table
+//  * A workgroup (16 waves) owns 64 consecutive chunk columns and R rows, 256 at a time.  Its table
 //    T[k][c] = <x_c, C_k> (2^b x 64 fp16 entries) is produced by the matrix
 //    cores in one shot -- a (2^b x 16) +-1 matrix times a (16 x 64) block of
 //    activations -- instead of the two-stage segment tables of the paper,
@@ -22,7 +22,7 @@
 //    step t's index sits at the compile-time bit offset t*b of the lane's
 //    registers.
 //  * Column blocks are reduced across workgroups through fp32 partials in the
-//    workspace; the last workgroup to arrive for a row block adds them in a
+//    workspace; the workgroup of the last column block adds them in a
 //    fixed order and applies  y = alpha * d + mu * sum(x)  (dequantisation step
 //    of Algorithm "Binary Transformation and Compression").  The result does
 //    not depend on arrival order.
@@ -118,33 +118,48 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <int B, int NW, bool DUP>
+constexpr int kRowTiles = 4;    // 64-row tiles a workgroup works on at once
+constexpr int kQuarters = 4;    // waves that share one row tile: each walks 16 of the 64 columns
+constexpr int kWaves = kRowTiles * kQuarters;
+
+template <int B, bool DUP>
 struct LutCfg {
   static constexpr int W2 = 2 * B;                       // words per tile row: 64 indices of B bits
   static constexpr int RPI = 64 / W2;                    // tile rows fetched by one wave-wide load
   static constexpr int NQ = (kTileRows + RPI - 1) / RPI; // loads per tile
-  static constexpr int kStageRows = NQ * RPI;            // >= 64
+  static constexpr int NQW = (NQ + kQuarters - 1) / kQuarters;  // loads per tile and wave
+  static constexpr int kStageRows = NQW * kQuarters * RPI;      // >= 64
   static constexpr int SR = (DUP ? 2 * W2 : W2) + 1;     // staged row stride in words (odd)
+  static constexpr int QW = (16 * B + 31) / 32;          // words holding a quarter's 16 indices
   static constexpr int kTableBytes = (1 << B) * 128;
-  static constexpr int kStageBytes = NW * kStageRows * SR * 4;
-  static constexpr int kLdsBytes = kTableBytes + kStageBytes;
+  static constexpr int kStageBytes = kRowTiles * kStageRows * SR * 4;
+  static constexpr int kRedBytes = kWaves * 64 * 4;
+  static constexpr int kLdsBytes = kTableBytes + kStageBytes + kRedBytes;
   static constexpr int kGroups = (1 << B) / 32;          // 32-codeword groups
-  static_assert(kGroups % NW == 0, "codeword groups split evenly over the waves");
+  static constexpr int kGroupsPerWave = (kGroups + kWaves - 1) / kWaves;
 };
 
-template <int B, int NW, bool DUP, bool WIDE_V /* v > 16 */, bool X_DWORD /* v and in even */>
-__global__ __launch_bounds__(NW * 64) void gemv_lut_kernel(Dims d, const uint32_t* __restrict__ packed,
-                                                           const uint32_t* __restrict__ codebook,
-                                                           const float* __restrict__ alpha,
-                                                           const float* __restrict__ mu,
-                                                           const __half* __restrict__ x, void* __restrict__ y,
-                                                           int y_is_f32, LutWorkspace ws, int n_ct, int n_rb, int RT) {
-  using Cfg = LutCfg<B, NW, DUP>;
-  constexpr int W2 = Cfg::W2, SR = Cfg::SR, RPI = Cfg::RPI, NQ = Cfg::NQ;
+// Wave w of the 16: row tile w / 4, column quarter w % 4.  The four waves of a row
+// tile split everything: the tile's loads, the 64-step walk (16 steps each, which is
+// just the original walk started at lane + 16 q) and -- through LDS -- the row sums.
+// Spreading a tile over four waves does not change the work, but it shortens the
+// serial instruction stream of every wave about fourfold, and at a few microseconds
+// per call that stream is what the latency consists of.
+template <int B, bool DUP, bool WIDE_V /* v > 16 */, bool X_DWORD /* v and in even */>
+__global__ __launch_bounds__(kWaves * 64) void gemv_lut_kernel(Dims d, const uint32_t* __restrict__ packed,
+                                                               const uint32_t* __restrict__ codebook,
+                                                               const float* __restrict__ alpha,
+                                                               const float* __restrict__ mu,
+                                                               const __half* __restrict__ x, void* __restrict__ y,
+                                                               int y_is_f32, LutWorkspace ws, int n_ct, int n_rb,
+                                                               int RT) {
+  using Cfg = LutCfg<B, DUP>;
+  constexpr int W2 = Cfg::W2, SR = Cfg::SR, RPI = Cfg::RPI, NQW = Cfg::NQW, QW = Cfg::QW;
   constexpr int KH = WIDE_V ? 2 : 1;
   extern __shared__ __align__(16) unsigned char smem[];
   uint32_t* table = (uint32_t*)smem;                                   // [2^B][32] dwords of 2 x fp16
   uint32_t* stage_all = (uint32_t*)(smem + Cfg::kTableBytes);
+  float* red = (float*)(smem + Cfg::kTableBytes + Cfg::kStageBytes);   // [16 waves][64]
 
   // Workgroups are dealt round-robin to the 8 XCDs; give each XCD whole row
   // blocks so that neighbouring column blocks of a row (which share HBM lines)
@@ -157,17 +172,19 @@ __global__ __launch_bounds__(NW * 64) void gemv_lut_kernel(Dims d, const uint32_
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wt = wave >> 2, qw = wave & 3;                             // row tile, column quarter
   const int j = lane & 31, h = lane >> 5;
-  uint32_t* stage = stage_all + wave * (Cfg::kStageRows * SR);
+  uint32_t* stage = stage_all + wt * (Cfg::kStageRows * SR);
 
-  // ---- index tiles: lane (lr, lw) fetches word lw of tile rows lr, lr+RPI, ...
+  // ---- index tiles: lane (lr, lw) fetches word lw of tile rows lr, lr+RPI, ...; the four waves
+  // of a row tile take every fourth load
   const int lr = lane / W2, lw = lane - lr * W2;
   const int words_left = d.wpr - ct * W2;                 // words of this column block inside a row
   const bool lane_loads = lr < RPI;
   const uint32_t tile_voff = (lane_loads && lw < words_left) ? (uint32_t)(lr * d.wpr + lw) * 4u : kOob;
   const uint32_t q_stride = (uint32_t)(RPI * d.wpr) * 4u;
   const uint32_t total_bytes = (uint32_t)d.out * (uint32_t)d.wpr * 4u;
-  uint32_t ld[NQ];
+  uint32_t ld[NQW];
   auto load_tile = [&](int row0) {
     // descriptor rebased to the tile, so that the range check sees the true distance to the end
     const uint32_t base_off = ((uint32_t)row0 * (uint32_t)d.wpr + (uint32_t)(ct * W2)) * 4u;
@@ -176,127 +193,134 @@ __global__ __launch_bounds__(NW * 64) void gemv_lut_kernel(Dims d, const uint32_
         (void*)((const char*)packed + (inside ? base_off : 0u)), 0, inside ? (int)(total_bytes - base_off) : 0,
         kRsrcFlags);
 #pragma unroll
-    for (int q = 0; q < NQ; ++q) ld[q] = __builtin_amdgcn_raw_buffer_load_b32(rs, tile_voff + q * q_stride, 0, 0);
+    for (int i = 0; i < NQW; ++i)   // loads q >= NQ fetch rows of the next tile or nothing; they are never used
+      ld[i] = __builtin_amdgcn_raw_buffer_load_b32(rs, tile_voff + (uint32_t)(i * kQuarters + qw) * q_stride, 0, 0);
   };
-  load_tile((rb * RT * NW + wave) * kTileRows);
-  // this wave's share of the codebook (lane: codeword j of each of its 32-codeword groups)
-  uint32_t npat_all[Cfg::kGroups / NW];
-#pragma unroll
-  for (int it = 0; it < Cfg::kGroups / NW; ++it) npat_all[it] = ~codebook[(it * NW + wave) * 32 + j];
+  load_tile((rb * RT * kRowTiles + wt) * kTileRows);
 
-  // ---- activations of this column block as MFMA B operands (lane: column j of
-  // block nb, elements 8h..8h+7 of the chunk); out-of-range elements read as 0
-  const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)x, 0, d.in * 2, kRsrcFlags);
+  // ---- table build, split over the waves by 32-codeword groups
+  const bool builds = wave < Cfg::kGroups;
+  uint32_t npat_all[Cfg::kGroupsPerWave];
   uint4 bx[2][KH];
+  if (builds) {
 #pragma unroll
-  for (int nb = 0; nb < 2; ++nb) {
-    const int chunk = ct * kTileCols + nb * 32 + j;
+    for (int it = 0; it < Cfg::kGroupsPerWave; ++it) npat_all[it] = ~codebook[(it * kWaves + wave) * 32 + j];
+    // activations of this column block as MFMA B operands (lane: column j of block nb,
+    // elements 8h..8h+7 of the chunk); out-of-range elements read as 0
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)x, 0, d.in * 2, kRsrcFlags);
 #pragma unroll
-    for (int kh = 0; kh < KH; ++kh) {
-      const int t0 = kh * 16 + h * 8;
-      const uint32_t e0 = (uint32_t)(chunk * d.v + t0) * 2u;   // byte offset of element t0 of the chunk
-      uint32_t wv[4];
-      if (X_DWORD) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-          wv[i] = __builtin_amdgcn_raw_buffer_load_b32(rx, (t0 + 2 * i < d.v) ? e0 + 4u * i : kOob, 0, 0);
-      } else {
-        uint32_t hv[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e)
-          hv[e] = __builtin_amdgcn_raw_buffer_load_b16(rx, (t0 + e < d.v) ? e0 + 2u * e : kOob, 0, 0);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) wv[i] = (hv[2 * i] & 0xFFFFu) | (hv[2 * i + 1] << 16);
-      }
-      bx[nb][kh] = make_uint4(wv[0], wv[1], wv[2], wv[3]);
-    }
-  }
-  // ---- per-lane constants of the skewed walk
-  // step t reads column c = (lane + t) & 63 -> byte offset 4 * (c & 31) + 2 * (c >> 5)
-  uint32_t colofs[64];
-#pragma unroll
-  for (int t = 0; t < 32; ++t) {
-    const uint32_t c = (uint32_t)(lane + t);
-    colofs[t] = ((c << 2) & 124u) | ((c >> 4) & 2u);
-    colofs[t + 32] = colofs[t] ^ 2u;
-  }
-  const int rot_bits = lane * B;
-  const int wr = rot_bits >> 5;
-  const uint32_t sh = rot_bits & 31;
-  uint32_t* stage_wr = stage + lr * SR + lw;          // where this lane stages what it fetched
-  const uint32_t* stage_rd = stage + lane * SR + wr;  // where its own rotated row starts
-
-  if (wave == NW - 1) {  // one wave also adds the block's activations up
-    float sxl = 0.f;
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
+    for (int nb = 0; nb < 2; ++nb) {
+      const int chunk = ct * kTileCols + nb * 32 + j;
 #pragma unroll
       for (int kh = 0; kh < KH; ++kh) {
-        const uint32_t w4[4] = {bx[nb][kh].x, bx[nb][kh].y, bx[nb][kh].z, bx[nb][kh].w};
+        const int t0 = kh * 16 + h * 8;
+        const uint32_t e0 = (uint32_t)(chunk * d.v + t0) * 2u;   // byte offset of element t0 of the chunk
+        uint32_t wv[4];
+        if (X_DWORD) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const f16x2 p = __builtin_bit_cast(f16x2, w4[i]);
-          sxl += (float)p[0];
-          sxl += (float)p[1];
+          for (int i = 0; i < 4; ++i)
+            wv[i] = __builtin_amdgcn_raw_buffer_load_b32(rx, (t0 + 2 * i < d.v) ? e0 + 4u * i : kOob, 0, 0);
+        } else {
+          uint32_t hv[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            hv[e] = __builtin_amdgcn_raw_buffer_load_b16(rx, (t0 + e < d.v) ? e0 + 2u * e : kOob, 0, 0);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) wv[i] = (hv[2 * i] & 0xFFFFu) | (hv[2 * i + 1] << 16);
         }
+        bx[nb][kh] = make_uint4(wv[0], wv[1], wv[2], wv[3]);
       }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) sxl += __shfl_xor(sxl, o, 64);
-    if (lane == 0) store_slot(&ws.sx[rb * n_ct + ct], sxl);
-  }
-
-  // ---- table build: 32 codewords x 64 columns per pair of MFMAs.
-  // D[i][jj]: lane holds column jj = lane % 32 and codewords i = 8 (e/4) + 4 h + e%4.
-  uint32_t* trow = table + (wave * 32 + 4 * h) * 32 + j;
-#pragma unroll
-  for (int it = 0; it < Cfg::kGroups / NW; ++it) {
-    const uint32_t npat = npat_all[it];
-    f32x16 d0, d1;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) d0[e] = d1[e] = 0.f;
-#pragma unroll
-    for (int kh = 0; kh < KH; ++kh) {
-      const uint32_t n = npat >> (kh * 16 + h * 8);
-      const uint4 a = make_uint4(sign_pair(n, 0), sign_pair(n, 1), sign_pair(n, 2), sign_pair(n, 3));
-      d0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, bx[0][kh]),
-                                                  d0, 0, 0, 0);
-      d1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, bx[1][kh]),
-                                                  d1, 0, 0, 0);
     }
-#pragma unroll
-    for (int e = 0; e < 16; ++e)  // columns j (low half) and 32 + j (high half) of codeword row
-      trow[(it * NW * 32 + 8 * (e >> 2) + (e & 3)) * 32] = pack_f16x2(d0[e], d1[e]);
   }
 
-  __syncthreads();  // table complete
+  // ---- per-lane constants of this wave's part of the skewed walk: it starts at virtual
+  // lane v0 = lane + 16 q; step i reads column c = (v0 + i) & 63 -> byte offset 4 (c & 31) + 2 (c >> 5)
+  const int v0 = (lane + 16 * qw) & 63;
+  uint32_t colofs[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const uint32_t c = (uint32_t)(v0 + i);
+    colofs[i] = ((c << 2) & 124u) | ((c >> 4) & 2u);
+  }
+  const int rot_bits = v0 * B;
+  const int wr = rot_bits >> 5;
+  const uint32_t sh = rot_bits & 31;
+  uint32_t* stage_wr = stage + (qw * RPI + lr) * SR + lw;  // where this lane stages what it fetched
+  const uint32_t* stage_rd = stage + lane * SR + wr;       // where its quarter of its rotated row starts
+
+  if (builds) {
+    if (wave == 0) {  // one wave also adds the block's activations up
+      float sxl = 0.f;
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int kh = 0; kh < KH; ++kh) {
+          const uint32_t w4[4] = {bx[nb][kh].x, bx[nb][kh].y, bx[nb][kh].z, bx[nb][kh].w};
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const f16x2 p = __builtin_bit_cast(f16x2, w4[i]);
+            sxl += (float)p[0];
+            sxl += (float)p[1];
+          }
+        }
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) sxl += __shfl_xor(sxl, o, 64);
+      if (lane == 0) store_slot(&ws.sx[rb * n_ct + ct], sxl);
+    }
+    // 32 codewords x 64 columns per pair of MFMAs.
+    // D[i][jj]: lane holds column jj = lane % 32 and codewords i = 8 (e/4) + 4 h + e%4.
+#pragma unroll
+    for (int it = 0; it < Cfg::kGroupsPerWave; ++it) {
+      const int cg = it * kWaves + wave;
+      if (cg < Cfg::kGroups) {
+        const uint32_t npat = npat_all[it];
+        f32x16 d0, d1;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) d0[e] = d1[e] = 0.f;
+#pragma unroll
+        for (int kh = 0; kh < KH; ++kh) {
+          const uint32_t n = npat >> (kh * 16 + h * 8);
+          const uint4 a = make_uint4(sign_pair(n, 0), sign_pair(n, 1), sign_pair(n, 2), sign_pair(n, 3));
+          d0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
+                                                      __builtin_bit_cast(f16x8, bx[0][kh]), d0, 0, 0, 0);
+          d1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
+                                                      __builtin_bit_cast(f16x8, bx[1][kh]), d1, 0, 0, 0);
+        }
+        uint32_t* trow = table + (cg * 32 + 4 * h) * 32 + j;
+#pragma unroll
+        for (int e = 0; e < 16; ++e)  // columns j (low half) and 32 + j (high half) of codeword row
+          trow[(8 * (e >> 2) + (e & 3)) * 32] = pack_f16x2(d0[e], d1[e]);
+      }
+    }
+  }
 
   const char* table_bytes = (const char*)table;
   for (int rt = 0; rt < RT; ++rt) {
-    const int row0 = ((rb * RT + rt) * NW + wave) * kTileRows;
+    const int row0 = ((rb * RT + rt) * kRowTiles + wt) * kTileRows;
     if (lane_loads) {
 #pragma unroll
-      for (int q = 0; q < NQ; ++q) {
-        stage_wr[q * RPI * SR] = ld[q];
-        if (DUP) stage_wr[q * RPI * SR + W2] = ld[q];
+      for (int i = 0; i < NQW; ++i) {
+        stage_wr[i * kQuarters * RPI * SR] = ld[i];
+        if (DUP) stage_wr[i * kQuarters * RPI * SR + W2] = ld[i];
       }
     }
-    if (rt + 1 < RT) load_tile(row0 + NW * kTileRows);  // next tile's loads fly during this tile's lookups
-    wave_lds_sync();
-    // read back rotated by `lane` chunks: R[i] = bits [32 i, 32 i + 32) of the rotated row
-    uint32_t Wd[W2 + 1];
+    if (rt + 1 < RT) load_tile(row0 + kRowTiles * kTileRows);  // next tile's loads fly during this tile's lookups
+    __syncthreads();  // tile staged by its four waves (first pass: the table is complete, too)
+    // read back this wave's quarter, rotated by v0 chunks: R[i] = bits [32 i, 32 i + 32)
+    uint32_t Wd[QW + 1];
 #pragma unroll
-    for (int i = 0; i <= W2; ++i) {
+    for (int i = 0; i <= QW; ++i) {
       if (DUP) Wd[i] = stage_rd[i];
       else Wd[i] = stage[lane * SR + (wr + i >= W2 ? wr + i - W2 : wr + i)];
     }
-    uint32_t R[W2];
+    uint32_t R[QW + 1];
 #pragma unroll
-    for (int i = 0; i < W2; ++i) R[i] = __builtin_amdgcn_alignbit(Wd[i + 1], Wd[i], sh);
-    wave_lds_sync();  // staging buffer may be overwritten by the next tile
+    for (int i = 0; i < QW; ++i) R[i] = __builtin_amdgcn_alignbit(Wd[i + 1], Wd[i], sh);
+    R[QW] = 0;
 
     float acc = 0.f;
 #pragma unroll
-    for (int t = 0; t < 64; t += 2) {
+    for (int t = 0; t < 16; t += 2) {
       _Float16 e2[2];
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
@@ -310,8 +334,14 @@ __global__ __launch_bounds__(NW * 64) void gemv_lut_kernel(Dims d, const uint32_
       const f16x2 one = {(_Float16)1.0f, (_Float16)1.0f};
       acc = __builtin_amdgcn_fdot2(pr, one, acc, false);
     }
-    const int row = row0 + lane;
-    if (row < d.out) store_slot(&ws.partial[ct * d.out + row], acc);
+    red[wave * 64 + lane] = acc;
+    __syncthreads();  // quarters of a row tile meet; the staging buffers are free again
+    if (qw == 0) {
+      const float* rp = red + (wt * kQuarters) * 64 + lane;
+      const float tot = ((rp[0] + rp[64]) + rp[128]) + rp[192];   // fixed order
+      const int row = row0 + lane;
+      if (row < d.out) store_slot(&ws.partial[ct * d.out + row], tot);
+    }
   }
 
   // ---- the workgroup of the LAST column block of this row block adds the column blocks
@@ -327,15 +357,16 @@ __global__ __launch_bounds__(NW * 64) void gemv_lut_kernel(Dims d, const uint32_
   if (ct != n_ct - 1) return;
   // sum of x: every thread adds the column-block sums in the same order
   float* sx_buf = (float*)stage_all;  // staging space is free now
-  const int rows_per_wg = RT * NW * kTileRows;
+  constexpr int NT = kWaves * 64;
+  const int rows_per_wg = RT * kRowTiles * kTileRows;
   const int row_first = rb * rows_per_wg + tid;
   unsigned long long p16[16];
-  if (row_first < d.out) {            // first batch of this thread's partials: in flight with the sx loads
+  if (tid < rows_per_wg && row_first < d.out) {  // first batch of this thread's partials: in flight with the sx loads
 #pragma unroll
     for (int u = 0; u < 16; ++u) p16[u] = load_slot(&ws.partial[min(u, n_ct - 1) * d.out + row_first]);
   }
   float sx = 0.f;
-  for (int c0 = 0; c0 < n_ct; c0 += NW * 64) {
+  for (int c0 = 0; c0 < n_ct; c0 += NT) {
     __syncthreads();
     if (c0 + tid < n_ct) {
       unsigned long long* slot = &ws.sx[rb * n_ct + c0 + tid];
@@ -343,10 +374,10 @@ __global__ __launch_bounds__(NW * 64) void gemv_lut_kernel(Dims d, const uint32_
       clear_slot(slot);
     }
     __syncthreads();
-    const int n = min(NW * 64, n_ct - c0);
+    const int n = min(NT, n_ct - c0);
     for (int c = 0; c < n; ++c) sx += sx_buf[c];
   }
-  for (int r = tid; r < rows_per_wg; r += NW * 64) {
+  for (int r = tid; r < rows_per_wg; r += NT) {
     const int row = rb * rows_per_wg + r;
     if (row >= d.out) break;
     const float al = alpha[row], mm = mu[row];
@@ -371,37 +402,37 @@ __global__ __launch_bounds__(NW * 64) void gemv_lut_kernel(Dims d, const uint32_
   }
 }
 
-template <int B, int NW, bool DUP, bool WIDE_V, bool X_DWORD>
+template <int B, bool DUP, bool WIDE_V, bool X_DWORD>
 static btc_status launch_lut2(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
                               const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, void* ws) {
-  using Cfg = LutCfg<B, NW, DUP>;
+  using Cfg = LutCfg<B, DUP>;
   static_assert(Cfg::kLdsBytes <= 160 * 1024 - 64, "LDS budget");
   static bool attr_set = false;  // one-time kernel attribute, not call state
   if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)gemv_lut_kernel<B, NW, DUP, WIDE_V, X_DWORD>,
+    if (hipFuncSetAttribute((const void*)gemv_lut_kernel<B, DUP, WIDE_V, X_DWORD>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes) != hipSuccess)
       return BTC_ERR_HIP;
     attr_set = true;
   }
   const int n_ct = (d.nchunks + kTileCols - 1) / kTileCols;
   const int tiles = (d.out + kTileRows - 1) / kTileRows;
-  // row tiles per wave: keep at least ~2 workgroups per CU when the matrix allows it
+  // row tiles per wave group, one after the other: 1 unless the grid would be far larger than the chip
   int RT = 1;
-  while (RT < 8 && (long long)((tiles + NW * RT * 2 - 1) / (NW * RT * 2)) * n_ct >= 512) RT *= 2;
-  const int n_rb = (tiles + NW * RT - 1) / (NW * RT);
+  while (RT < 8 && (long long)((tiles + kRowTiles * RT * 2 - 1) / (kRowTiles * RT * 2)) * n_ct >= 1024) RT *= 2;
+  const int n_rb = (tiles + kRowTiles * RT - 1) / (kRowTiles * RT);
   const int grid = ((n_rb + 7) / 8) * 8 * n_ct;
-  gemv_lut_kernel<B, NW, DUP, WIDE_V, X_DWORD><<<grid, NW * 64, Cfg::kLdsBytes, q>>>(
+  gemv_lut_kernel<B, DUP, WIDE_V, X_DWORD><<<grid, kWaves * 64, Cfg::kLdsBytes, q>>>(
       d, packed, codebook, alpha, mu, (const __half*)x, y, y_is_f32, carve(ws, d), n_ct, n_rb, RT);
   return launch_status();
 }
 
-template <int B, int NW, bool DUP>
+template <int B, bool DUP>
 static btc_status launch_lut(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
                              const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, void* ws) {
   const bool xdw = (d.v % 2 == 0) && (d.in % 2 == 0);
-  if (d.v > 16) return launch_lut2<B, NW, DUP, true, false>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
-  if (xdw) return launch_lut2<B, NW, DUP, false, true>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
-  return launch_lut2<B, NW, DUP, false, false>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
+  if (d.v > 16) return launch_lut2<B, DUP, true, false>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
+  if (xdw) return launch_lut2<B, DUP, false, true>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
+  return launch_lut2<B, DUP, false, false>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
 }
 
 // Index widths with a table that fits LDS, and buffers small enough for 32-bit
@@ -418,12 +449,12 @@ bool lut_engine_covers(const Dims& d) {
 btc_status gemv_lut(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
                     const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, void* ws) {
   switch (d.b) {
-    case 5: return launch_lut<5, 1, true>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
-    case 6: return launch_lut<6, 2, true>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
-    case 7: return launch_lut<7, 4, true>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
-    case 8: return launch_lut<8, 4, true>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
-    case 9: return launch_lut<9, 8, true>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
-    case 10: return launch_lut<10, 4, false>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
+    case 5: return launch_lut<5, true>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
+    case 6: return launch_lut<6, true>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
+    case 7: return launch_lut<7, true>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
+    case 8: return launch_lut<8, true>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
+    case 9: return launch_lut<9, true>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
+    case 10: return launch_lut<10, false>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
   }
   return BTC_ERR_UNSUPPORTED;
 }
