@@ -60,7 +60,7 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_expand_kernel(Dims d, const 
                                                                  const float* __restrict__ alpha,
                                                                  const float* __restrict__ mu,
                                                                  const __half* __restrict__ x, void* __restrict__ y,
-                                                                 int y_is_f32, int CS, int rows_per_group, int slot_dwords) {
+                                                                 int y_is_f32, int CS, int rows_per_group, int slot_dwords, int x_vec) {
   constexpr int F = 31 / B + 1;          // fields that can start inside one 32-bit word
   constexpr int VP = (V + 1) / 2;        // fp16 pairs per chunk
   static_assert(VP == 5, "the LDS entry is one 16-byte and one 4-byte read");
@@ -101,7 +101,26 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_expand_kernel(Dims d, const 
     }
   };
 #pragma unroll
-  for (int s = 0; s < kPD; ++s) load_row(s, row_begin + s);
+  for (int s = 0; s < kPD; ++s)
+    if (s < rows_per_group) load_row(s, row_begin + s);
+  // codewords this thread expands, and the scale and mean of the row it will finish: requested
+  // now, used after the row loop (a load issued there would add a memory round trip per call)
+  constexpr int KPT = ((1 << B) + kWaves * 64 - 1) / (kWaves * 64);
+  uint32_t cbv[KPT];
+#pragma unroll
+  for (int u = 0; u < KPT; ++u) cbv[u] = codebook[min(tid + u * kWaves * 64, (1 << B) - 1)];
+  int my_i, my_row;        // the finished row of this thread: row my_i of its group
+  if (CS > 1) {
+    const int g = tid % RG;
+    my_i = tid / RG;
+    my_row = my_i < rows_per_group ? (blockIdx.x * RG + g) * rows_per_group + my_i : d.out;
+  } else {
+    my_i = lane;
+    my_row = lane < rows_per_group ? row_begin + lane : d.out;
+  }
+  const bool my_ok = my_row < d.out;
+  const float my_alpha = my_ok ? alpha[my_row] : 0.f;
+  const float my_mu = my_ok ? mu[my_row] : 0.f;
 
   // ---- activations -> LDS, one 5-dword slot per chunk (pairs of fp16; element V of an odd-length
   // chunk is 0), one pad dword after every 4 slots so that lanes reading their slots spread over
@@ -109,8 +128,41 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_expand_kernel(Dims d, const 
   // so slots nchunks.. are all zero.  Each thread also adds up what it stages.
   const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)x, 0, d.in * 2, kRsrcFlags);
   float sx = 0.f;
-  {
-    const f16x2 one = {(_Float16)1.0f, (_Float16)1.0f};
+  const f16x2 one = {(_Float16)1.0f, (_Float16)1.0f};
+  if (V % 2 == 0 && x_vec) {
+    // A chunk of 10 fp16 is 5 dwords, so the slot layout is the activation vector itself: copy it
+    // 16 bytes at a time (groups of 4 dwords never straddle a pad, which follows every 20th dword).
+    const int n4 = (slot_dwords + 3) >> 2;
+    const int full4 = (d.in * 2) >> 4;                         // groups that lie entirely inside x
+    constexpr int U4 = 3;                                      // 16-byte loads in flight per thread
+    for (int base = tid; base < n4; base += kWaves * 64 * U4) {
+      uint4 val[U4];
+#pragma unroll
+      for (int u = 0; u < U4; ++u) {
+        const int g = base + u * kWaves * 64;
+        if (g < full4) {
+          val[u] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rx, (uint32_t)g * 16u, 0, 0));
+        } else {                                               // tail group or beyond: dwords past the end read 0
+          val[u].x = __builtin_amdgcn_raw_buffer_load_b32(rx, (uint32_t)g * 16u, 0, 0);
+          val[u].y = __builtin_amdgcn_raw_buffer_load_b32(rx, (uint32_t)g * 16u + 4u, 0, 0);
+          val[u].z = __builtin_amdgcn_raw_buffer_load_b32(rx, (uint32_t)g * 16u + 8u, 0, 0);
+          val[u].w = __builtin_amdgcn_raw_buffer_load_b32(rx, (uint32_t)g * 16u + 12u, 0, 0);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < U4; ++u) {
+        const int g = base + u * kWaves * 64;
+        if (g < n4) {
+          uint32_t* dst = xs + 4 * g + g / 5;
+          dst[0] = val[u].x; dst[1] = val[u].y; dst[2] = val[u].z; dst[3] = val[u].w;
+          sx = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, val[u].x), one, sx, false);
+          sx = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, val[u].y), one, sx, false);
+          sx = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, val[u].z), one, sx, false);
+          sx = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, val[u].w), one, sx, false);
+        }
+      }
+    }
+  } else {
     constexpr int U = 8;                                       // loads in flight per thread
     for (int base = tid; base < slot_dwords; base += kWaves * 64 * U) {
       uint32_t val[U];
@@ -136,13 +188,16 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_expand_kernel(Dims d, const 
         }
       }
     }
-    sx = wave_sum_to_lane63(sx);
-    if (lane == 63) red[wave] = sx;
   }
+  sx = wave_sum_to_lane63(sx);
+  if (lane == 63) red[wave] = sx;
   // ---- codebook -> +-1 fp16 pairs (bit set => +1).  Entries K..2^B-1 are read
   // too: the caller provides 2^B readable entries.
-  for (int k = tid; k < (1 << B); k += kWaves * 64) {
-    const uint32_t npat = ~codebook[k];
+#pragma unroll
+  for (int u = 0; u < KPT; ++u) {
+    const int k = tid + u * kWaves * 64;
+    if (k >= (1 << B)) break;
+    const uint32_t npat = ~cbv[u];
     uint32_t e[VP];
 #pragma unroll
     for (int p = 0; p < VP; ++p) e[p] = 0x3C003C00u | ((npat >> (2 * p)) & 1u) << 15 | ((npat >> (2 * p + 1)) & 1u) << 31;
@@ -210,29 +265,30 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_expand_kernel(Dims d, const 
         }
       }
       acc = wave_sum_to_lane63(acc);
-      if (lane == 63) {
-        if (CS > 1) {
-          rowpart[i * kWaves + wave] = acc;                  // column splits of a row meet in LDS after the loop
-        } else if (row < d.out) {
-          const float r = alpha[row] * acc + mu[row] * sx;
-          if (y_is_f32) ((float*)y)[row] = r;
-          else ((__half*)y)[row] = __float2half_rn(r);
-        }
-      }
+      if (lane == 63) rowpart[i * kWaves + wave] = acc;      // row sums (or column splits of them) meet in LDS
     }
   }
+  // ---- epilogue: thread (row my_i of its group) adds the column splits in a fixed order.  Without a
+  // column split the row sums were written by this very wave, so waiting for its own LDS writes is enough.
   if (CS > 1) {
     __syncthreads();
-    for (int t = tid; t < rows_per_group * RG; t += kWaves * 64) {
-      const int i = t / RG, g = t - i * RG;
-      const int row = (blockIdx.x * RG + g) * rows_per_group + i;
-      if (row >= d.out) continue;
-      float dsum = 0.f;
-      for (int c = 0; c < CS; ++c) dsum += rowpart[i * kWaves + g * CS + c];   // fixed order
-      const float r = alpha[row] * dsum + mu[row] * sx;
-      if (y_is_f32) ((float*)y)[row] = r;
-      else ((__half*)y)[row] = __float2half_rn(r);
+  } else {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
+  if (my_ok) {
+    float dsum = 0.f;
+    if (CS > 1) {
+      const int g = tid % RG;
+      for (int c = 0; c < CS; ++c) dsum += rowpart[my_i * kWaves + g * CS + c];
+    } else {
+      dsum = rowpart[my_i * kWaves + wave];
     }
+    const float r = my_alpha * dsum + my_mu * sx;
+    if (y_is_f32) ((float*)y)[my_row] = r;
+    else ((__half*)y)[my_row] = __float2half_rn(r);
   }
 }
 
@@ -260,8 +316,9 @@ static btc_status launch(hipStream_t q, const Dims& d, const uint32_t* packed, c
       return BTC_ERR_HIP;
     attr_set = true;
   }
+  const int x_vec = ((uintptr_t)x & 15) == 0;   // 16-byte loads of the activations
   gemv_expand_kernel<B, V, MB><<<grid, kWaves * 64, lds, q>>>(d, packed, codebook, alpha, mu, (const __half*)x, y,
-                                                             y_is_f32, CS, rpg, xw);
+                                                             y_is_f32, CS, rpg, xw, x_vec);
   return launch_status();
 }
 

@@ -145,7 +145,7 @@ struct LutCfg {
 // Spreading a tile over four waves does not change the work, but it shortens the
 // serial instruction stream of every wave about fourfold, and at a few microseconds
 // per call that stream is what the latency consists of.
-template <int B, bool DUP, bool WIDE_V /* v > 16 */, bool X_DWORD /* v and in even */>
+template <int B, bool DUP, bool WIDE_V /* v > 16 */, bool X_DWORD /* v and in even */, int D /* tiles in flight */>
 __global__ __launch_bounds__(kWaves * 64) void gemv_lut_kernel(Dims d, const uint32_t* __restrict__ packed,
                                                                const uint32_t* __restrict__ codebook,
                                                                const float* __restrict__ alpha,
@@ -173,6 +173,15 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_lut_kernel(Dims d, const uin
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wt = wave >> 2, qw = wave & 3;                             // row tile, column quarter
+  // The workgroup of the last column block finishes the rows; it asks for the scale and mean
+  // of its first rows now, so that the loads are not a round trip at the end of the call.
+  const int rows_per_wg = RT * kRowTiles * kTileRows;
+  const int row_first = rb * rows_per_wg + tid;
+  float al_first = 0.f, mu_first = 0.f;
+  if (ct == n_ct - 1 && tid < rows_per_wg && row_first < d.out) {
+    al_first = alpha[row_first];
+    mu_first = mu[row_first];
+  }
   const int j = lane & 31, h = lane >> 5;
   uint32_t* stage = stage_all + wt * (Cfg::kStageRows * SR);
 
@@ -184,8 +193,8 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_lut_kernel(Dims d, const uin
   const uint32_t tile_voff = (lane_loads && lw < words_left) ? (uint32_t)(lr * d.wpr + lw) * 4u : kOob;
   const uint32_t q_stride = (uint32_t)(RPI * d.wpr) * 4u;
   const uint32_t total_bytes = (uint32_t)d.out * (uint32_t)d.wpr * 4u;
-  uint32_t ld[NQW];
-  auto load_tile = [&](int row0) {
+  uint32_t ld[D][NQW];
+  auto load_tile = [&](int row0, uint32_t (&dst)[NQW]) {
     // descriptor rebased to the tile, so that the range check sees the true distance to the end
     const uint32_t base_off = ((uint32_t)row0 * (uint32_t)d.wpr + (uint32_t)(ct * W2)) * 4u;
     const bool inside = row0 < d.out;
@@ -194,9 +203,15 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_lut_kernel(Dims d, const uin
         kRsrcFlags);
 #pragma unroll
     for (int i = 0; i < NQW; ++i)   // loads q >= NQ fetch rows of the next tile or nothing; they are never used
-      ld[i] = __builtin_amdgcn_raw_buffer_load_b32(rs, tile_voff + (uint32_t)(i * kQuarters + qw) * q_stride, 0, 0);
+      dst[i] = __builtin_amdgcn_raw_buffer_load_b32(rs, tile_voff + (uint32_t)(i * kQuarters + qw) * q_stride, 0, 0);
   };
-  load_tile((rb * RT * kRowTiles + wt) * kTileRows);
+  // The first D tiles are requested before anything else.  HBM latency times bandwidth is
+  // several megabytes, so a workgroup that walks many tiles keeps D of them in flight.
+  const int first_row = (rb * RT * kRowTiles + wt) * kTileRows;
+  constexpr int kStep = kRowTiles * kTileRows;           // rows between successive tiles of a wave
+#pragma unroll
+  for (int u = 0; u < D; ++u)
+    if (u < RT) load_tile(first_row + u * kStep, ld[u]);
 
   // ---- table build, split over the waves by 32-codeword groups
   const bool builds = wave < Cfg::kGroups;
@@ -295,16 +310,20 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_lut_kernel(Dims d, const uin
   }
 
   const char* table_bytes = (const char*)table;
-  for (int rt = 0; rt < RT; ++rt) {
-    const int row0 = ((rb * RT + rt) * kRowTiles + wt) * kTileRows;
+  for (int rt0 = 0; rt0 < RT; rt0 += D) {
+#pragma unroll
+   for (int u = 0; u < D; ++u) {
+    const int rt = rt0 + u;
+    if (rt >= RT) break;
+    const int row0 = first_row + rt * kStep;
     if (lane_loads) {
 #pragma unroll
       for (int i = 0; i < NQW; ++i) {
-        stage_wr[i * kQuarters * RPI * SR] = ld[i];
-        if (DUP) stage_wr[i * kQuarters * RPI * SR + W2] = ld[i];
+        stage_wr[i * kQuarters * RPI * SR] = ld[u][i];
+        if (DUP) stage_wr[i * kQuarters * RPI * SR + W2] = ld[u][i];
       }
     }
-    if (rt + 1 < RT) load_tile(row0 + kRowTiles * kTileRows);  // next tile's loads fly during this tile's lookups
+    if (rt + D < RT) load_tile(row0 + D * kStep, ld[u]);  // keeps D tiles in flight
     __syncthreads();  // tile staged by its four waves (first pass: the table is complete, too)
     // read back this wave's quarter, rotated by v0 chunks: R[i] = bits [32 i, 32 i + 32)
     uint32_t Wd[QW + 1];
@@ -342,6 +361,7 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_lut_kernel(Dims d, const uin
       const int row = row0 + lane;
       if (row < d.out) store_slot(&ws.partial[ct * d.out + row], tot);
     }
+   }
   }
 
   // ---- the workgroup of the LAST column block of this row block adds the column blocks
@@ -358,8 +378,6 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_lut_kernel(Dims d, const uin
   // sum of x: every thread adds the column-block sums in the same order
   float* sx_buf = (float*)stage_all;  // staging space is free now
   constexpr int NT = kWaves * 64;
-  const int rows_per_wg = RT * kRowTiles * kTileRows;
-  const int row_first = rb * rows_per_wg + tid;
   unsigned long long p16[16];
   if (tid < rows_per_wg && row_first < d.out) {  // first batch of this thread's partials: in flight with the sx loads
 #pragma unroll
@@ -380,7 +398,7 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_lut_kernel(Dims d, const uin
   for (int r = tid; r < rows_per_wg; r += NT) {
     const int row = rb * rows_per_wg + r;
     if (row >= d.out) break;
-    const float al = alpha[row], mm = mu[row];
+    const float al = r == tid ? al_first : alpha[row], mm = r == tid ? mu_first : mu[row];
     float dsum = 0.f;
     for (int c = 0; c < n_ct; c += 16) {
       if (r != tid || c != 0) {
@@ -402,28 +420,60 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_lut_kernel(Dims d, const uin
   }
 }
 
-template <int B, bool DUP, bool WIDE_V, bool X_DWORD>
-static btc_status launch_lut2(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
-                              const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, void* ws) {
+constexpr int kDeep = 4;  // tiles in flight per wave when a workgroup walks several
+
+// Workgroups of this kernel that fit one XCD (32 compute units) at a time.
+static int xcd_slots(int lds_bytes) {
+  const int per_cu = (160 * 1024) / lds_bytes;
+  return 32 * (per_cu < 2 ? per_cu : 2);   // 2048 threads per compute unit: at most two such workgroups
+}
+
+template <int B, bool DUP, bool WIDE_V, bool X_DWORD, int D>
+static btc_status launch_lut3(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
+                              const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, void* ws,
+                              int n_ct, int n_rb, int RT) {
   using Cfg = LutCfg<B, DUP>;
   static_assert(Cfg::kLdsBytes <= 160 * 1024 - 64, "LDS budget");
   static bool attr_set = false;  // one-time kernel attribute, not call state
   if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)gemv_lut_kernel<B, DUP, WIDE_V, X_DWORD>,
+    if (hipFuncSetAttribute((const void*)gemv_lut_kernel<B, DUP, WIDE_V, X_DWORD, D>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes) != hipSuccess)
       return BTC_ERR_HIP;
     attr_set = true;
   }
-  const int n_ct = (d.nchunks + kTileCols - 1) / kTileCols;
-  const int tiles = (d.out + kTileRows - 1) / kTileRows;
-  // row tiles per wave group, one after the other: 1 unless the grid would be far larger than the chip
-  int RT = 1;
-  while (RT < 8 && (long long)((tiles + kRowTiles * RT * 2 - 1) / (kRowTiles * RT * 2)) * n_ct >= 1024) RT *= 2;
-  const int n_rb = (tiles + kRowTiles * RT - 1) / (kRowTiles * RT);
   const int grid = ((n_rb + 7) / 8) * 8 * n_ct;
-  gemv_lut_kernel<B, DUP, WIDE_V, X_DWORD><<<grid, kWaves * 64, Cfg::kLdsBytes, q>>>(
+  gemv_lut_kernel<B, DUP, WIDE_V, X_DWORD, D><<<grid, kWaves * 64, Cfg::kLdsBytes, q>>>(
       d, packed, codebook, alpha, mu, (const __half*)x, y, y_is_f32, carve(ws, d), n_ct, n_rb, RT);
   return launch_status();
+}
+
+template <int B, bool DUP, bool WIDE_V, bool X_DWORD>
+static btc_status launch_lut2(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
+                              const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, void* ws) {
+  using Cfg = LutCfg<B, DUP>;
+  const int n_ct = (d.nchunks + kTileCols - 1) / kTileCols;
+  const int tiles = (d.out + kTileRows - 1) / kTileRows;
+  // Row blocks (256 rows) per workgroup.  One, as long as the grid is at most two rounds of
+  // resident workgroups: everything is then requested from memory at the start, which is what
+  // a call of a few microseconds needs.  Two beyond that (measured: fewer table builds, and
+  // more does not help because a row block costs a workgroup about as much as a build).  With
+  // 10-bit indices the 128 KB table is expensive enough to build once per resident workgroup:
+  // then the row blocks are dealt to as many workgroups as stay resident, whole row blocks per XCD.
+  const int blocks = (tiles + kRowTiles - 1) / kRowTiles;
+  const int slots_xcd = xcd_slots(Cfg::kLdsBytes);
+  int RT = 1;
+  if (Cfg::kTableBytes >= 128 * 1024) {
+    const int rb_xcd = slots_xcd / n_ct;
+    const int rb_fit = 8 * (rb_xcd > 0 ? rb_xcd : 1);
+    RT = (blocks + rb_fit - 1) / rb_fit;
+  } else if ((long long)blocks * n_ct > 2LL * 8 * slots_xcd) {
+    RT = 2;
+  }
+  const int n_rb = (blocks + RT - 1) / RT;
+  if (RT == 1)
+    return launch_lut3<B, DUP, WIDE_V, X_DWORD, 1>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws, n_ct, n_rb, RT);
+  return launch_lut3<B, DUP, WIDE_V, X_DWORD, kDeep>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws, n_ct, n_rb,
+                                                     RT);
 }
 
 template <int B, bool DUP>
