@@ -56,11 +56,42 @@ __device__ __forceinline__ f32x16 mfma32(const uint4& a, const uint4& b, const f
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
 }
 
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+
+// acc + lo + hi of a packed pair of 16-bit floats
+template <bool BF16>
+__device__ __forceinline__ float pair_sum(uint32_t w, float acc) {
+  if constexpr (BF16) {
+    const bf16x2 one = {(__bf16)1.0f, (__bf16)1.0f};
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), one, acc, false);
+  } else {
+    const f16x2 one = {(_Float16)1.0f, (_Float16)1.0f};
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, w), one, acc, false);
+  }
+}
+
+__device__ __forceinline__ uint32_t bf16_bits(float v) {
+  return (uint32_t)__builtin_bit_cast(uint16_t, __float2bfloat16(v));
+}
+__device__ __forceinline__ uint32_t f16_bits(float v) {
+  return (uint32_t)__builtin_bit_cast(uint16_t, __float2half_rn(v));
+}
+
+// LDS traffic inside one wave (writes by some lanes, reads by others): LDS operations of a
+// wave complete in order, so waiting for them is enough; the fences pin the compiler.
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 template <int NF, bool BF16>
 __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
     Dims d, const uint32_t* __restrict__ packed, const uint32_t* __restrict__ codebook,
     const float* __restrict__ alpha, const float* __restrict__ mu, const uint16_t* __restrict__ X, int M,
-    void* __restrict__ Y, int y_dtype, const float* __restrict__ rowsum, int m_blocks, int n_blocks) {
+    void* __restrict__ Y, int y_dtype, int m_blocks, int n_blocks) {
   constexpr int BN = 32 * NF;
   extern __shared__ __align__(16) unsigned char smem[];
   uint16_t* S = (uint16_t*)smem;                         // [2][BN][kRS]
@@ -86,7 +117,9 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int ntiles = (d.nchunks + kCH - 1) / kCH;
 
-  {
+  // Codeword table: built by all threads, but only after each role has put its first global
+  // loads in flight (the table needs a round trip of its own for the codebook).
+  auto build_table = [&]() {
     const uint32_t one2 = BF16 ? 0x3F803F80u : 0x3C003C00u;
     for (int k = tid; k < (1 << d.b); k += (kMW + kDW) * 64) {
       const uint32_t npat = ~codebook[k];
@@ -97,8 +130,8 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
       *(uint4*)(E + 8 * k) = make_uint4(e[0], e[1], e[2], e[3]);
       E[8 * k + 4] = e[4];
     }
-  }
-  __syncthreads();
+    __syncthreads();
+  };
 
   if (wave >= kMW) {
     // =============================== decoder waves ===============================
@@ -109,6 +142,7 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
     const uint32_t pk_bytes = (uint32_t)d.out * (uint32_t)d.wpr * 4u;
     const __amdgpu_buffer_rsrc_t rP = __builtin_amdgcn_make_buffer_rsrc((void*)packed, 0, (int)pk_bytes, kRsrcFlags);
     uint32_t W[NI][4];
+    const bool pair_loads = d.b == 8 && (d.wpr & 1) == 0;   // two-word loads stay 8-byte aligned
     // the 8 b-bit fields of an item start at bit (t*16 + half*8) * b of the row: at most 4 words
     auto fetch = [&](int t) {
 #pragma unroll
@@ -118,14 +152,23 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
         const int n = n0 + r;
         const int w0 = ((t * kCH + half * 8) * d.b) >> 5;
         const bool ok = item < 2 * BN && n < d.out;
+        if (pair_loads) {
+          // 8-bit indices: the 8 fields of an item are exactly two words, fetched by one load.
+          // (Every lane access costs the L1 a cycle, and the L1 access rate bounds this kernel.)
+          const uint32_t off = (ok && w0 + 1 < d.wpr) ? ((uint32_t)n * (uint32_t)d.wpr + (uint32_t)w0) * 4u : kOob;
+          const uint2 w2 = __builtin_bit_cast(uint2, __builtin_amdgcn_raw_buffer_load_b64(rP, off, 0, 0));
+          W[it][0] = w2.x; W[it][1] = w2.y; W[it][2] = 0u; W[it][3] = 0u;
+        } else {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const uint32_t off = (ok && w0 + u < d.wpr) ? ((uint32_t)n * (uint32_t)d.wpr + (uint32_t)(w0 + u)) * 4u : kOob;
-          W[it][u] = __builtin_amdgcn_raw_buffer_load_b32(rP, off, 0, 0);
+          for (int u = 0; u < 4; ++u) {
+            const uint32_t off = (ok && w0 + u < d.wpr) ? ((uint32_t)n * (uint32_t)d.wpr + (uint32_t)(w0 + u)) * 4u : kOob;
+            W[it][u] = __builtin_amdgcn_raw_buffer_load_b32(rP, off, 0, 0);
+          }
         }
       }
     };
     fetch(0);
+    build_table();
     for (int t = 0; t <= ntiles; ++t) {
       if (t < ntiles) {
         uint32_t A[NI][3];
@@ -191,95 +234,162 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
   // A operand: lane (row l32 of fragment a, h) reads X[m][k0 + 32 T + 16 h .. + 15]
   const __amdgpu_buffer_rsrc_t rX =
       __builtin_amdgcn_make_buffer_rsrc((void*)X, 0, (int)((long long)M * d.in * 2), kRsrcFlags);
-  uint32_t xoff[2];
-#pragma unroll
-  for (int a = 0; a < 2; ++a) {
-    const int m = m0 + wave * 64 + a * 32 + l32;
-    xoff[a] = (m < M) ? (uint32_t)(((long long)m * d.in + 16 * h) * 2) : kOob;
-  }
+  // Rows m >= M need no test of their own: X is row-major, so they lie past the end of the
+  // buffer and the hardware range check returns zeros for them.
+  const uint32_t xoff0 = (uint32_t)(((long long)(m0 + wave * 64 + l32) * d.in + 16 * h) * 2);
+  const uint32_t xstep = (uint32_t)(32LL * d.in * 2);    // second fragment: 32 rows further
   auto load_a = [&](uint4 (&dst)[2][2], int k0) {        // k0: first column of a block of 32
-    // `in` is a multiple of 16 for this kernel; past the end bit 31 of the offset is set (no branch)
+    // `in` is a multiple of 16 for this kernel; past the end of a row bit 31 of the offset is set
     const uint32_t past = (uint32_t)(k0 + 16 * h + 16 > d.in) << 31;
 #pragma unroll
     for (int a = 0; a < 2; ++a) {
-      const uint32_t off = (xoff[a] + (uint32_t)k0 * 2u) | past;
+      const uint32_t off = (xoff0 + (uint32_t)a * xstep + (uint32_t)k0 * 2u) | past;
       dst[a][0] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rX, off, 0, 0));
       dst[a][1] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rX, off + 16u, 0, 0));
     }
   };
 
-  // Software pipeline.  Activations: two register slots, the block after the one in use is
-  // in flight.  Pattern fragments: the NF fragments of the next k-slice are read from LDS
-  // while the 2 NF MFMAs of the current slice run.  Slots are compile-time (PAR = parity of
-  // the tile, 5 blocks per tile), so nothing is indexed dynamically.
+  // Software pipeline.  Activations: kAS register slots, a block is requested kAS - 1 blocks
+  // (about a microsecond of MFMA time) before its use, because the loads come from L2 or
+  // beyond.  Pattern fragments: one register set; fragment c of the next k-slice is read from
+  // LDS right after the two MFMAs that use fragment c of the current slice have been issued,
+  // a whole slice of MFMAs before it is needed.  Slots are compile-time (a tile has 5 blocks,
+  // so the slot pattern repeats every kAS tiles and the buffer parity every 2: 6 tile bodies).
   constexpr int NB = kKT / 32;                           // blocks per k-tile
-  uint4 ablk[2][2][2];                                   // [slot][fragment][k-slice]
-  uint4 bfr[2][NF];                                      // [slot][fragment]
-  load_a(ablk[0], 0);
-  load_a(ablk[1], 32);
+  constexpr int kAS = 3;
+  uint4 ablk[kAS][2][2];                                 // [slot][fragment][k-slice]
+  uint4 bfr[NF];
+  float rsum[2] = {0.f, 0.f};                            // this lane's half of the row sums of its two rows
+#pragma unroll
+  for (int i = 0; i < kAS; ++i) load_a(ablk[i], 32 * i);
+  build_table();
   __syncthreads();                                       // tile 0 decoded
   const uint16_t* sbase = S + l32 * kRS + 16 * h;
-  auto read_b = [&](uint4 (&dst)[NF], const uint16_t* st, int T, int s) {
-#pragma unroll
-    for (int c = 0; c < NF; ++c) dst[c] = *(const uint4*)(st + c * 32 * kRS + T * 32 + 8 * s);
-  };
-  auto tile = [&](int t, auto par) {
-    constexpr int PAR = decltype(par)::value;
+  auto tile = [&](int t, auto variant) {
+    constexpr int PAR = decltype(variant)::value & 1;    // tile buffer
+    constexpr int PH = decltype(variant)::value % kAS;   // phase of the slot pattern
     const uint16_t* st = sbase + PAR * (BN * kRS);
-    read_b(bfr[0], st, 0, 0);
+#pragma unroll
+    for (int c = 0; c < NF; ++c) bfr[c] = *(const uint4*)(st + c * 32 * kRS);
 #pragma unroll
     for (int T = 0; T < NB; ++T) {
       constexpr int dummy = 0;
       (void)dummy;
-      const int aslot = (T + PAR * NB) & 1;
+      const int aslot = (NB * PH + T) % kAS;
 #pragma unroll
       for (int s = 0; s < 2; ++s) {
         const int q = 2 * T + s;                         // slice number inside the tile
-        if (q + 1 < 2 * NB) read_b(bfr[(q + 1) & 1], st, (q + 1) >> 1, (q + 1) & 1);
 #pragma unroll
         for (int c = 0; c < NF; ++c) {
-          acc[0][c] = mfma32<BF16>(ablk[aslot][0][s], bfr[q & 1][c], acc[0][c]);
-          acc[1][c] = mfma32<BF16>(ablk[aslot][1][s], bfr[q & 1][c], acc[1][c]);
+          acc[0][c] = mfma32<BF16>(ablk[aslot][0][s], bfr[c], acc[0][c]);
+          acc[1][c] = mfma32<BF16>(ablk[aslot][1][s], bfr[c], acc[1][c]);
+          if (q + 1 < 2 * NB) bfr[c] = *(const uint4*)(st + c * 32 * kRS + ((q + 1) >> 1) * 32 + 8 * ((q + 1) & 1));
         }
       }
-      load_a(ablk[aslot], t * kKT + (T + 2) * 32);       // two blocks ahead (zeros past the end)
+      // row sums of the activations (for the mu term) from the block just used: 16 packed dot
+      // products per lane, issued in the shadow of the MFMAs.  The scheduler must not move them
+      // (or the refill of the slot) to the top of the tile: they would wait there for loads
+      // that were meant to stay in flight.
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+          rsum[a] = pair_sum<BF16>(ablk[aslot][a][s].x, rsum[a]);
+          rsum[a] = pair_sum<BF16>(ablk[aslot][a][s].y, rsum[a]);
+          rsum[a] = pair_sum<BF16>(ablk[aslot][a][s].z, rsum[a]);
+          rsum[a] = pair_sum<BF16>(ablk[aslot][a][s].w, rsum[a]);
+        }
+      load_a(ablk[aslot], t * kKT + (T + kAS) * 32);     // kAS blocks ahead (zeros past the end)
+      __builtin_amdgcn_sched_barrier(0);
     }
     __syncthreads();                                     // tile t consumed; tile t+1 decoded
   };
-  for (int t = 0; t < ntiles; t += 2) {
+  for (int t = 0; t < ntiles; t += 6) {
     tile(t, std::integral_constant<int, 0>{});
     if (t + 1 < ntiles) tile(t + 1, std::integral_constant<int, 1>{});
+    if (t + 2 < ntiles) tile(t + 2, std::integral_constant<int, 2>{});
+    if (t + 3 < ntiles) tile(t + 3, std::integral_constant<int, 3>{});
+    if (t + 4 < ntiles) tile(t + 4, std::integral_constant<int, 4>{});
+    if (t + 5 < ntiles) tile(t + 5, std::integral_constant<int, 5>{});
   }
 
-  // ---- epilogue: lane holds weight row n (column of D), 16 activation rows per accumulator.
-  // The 32 row sums a lane needs are fetched first, all loads in flight together.
-  float rs[2][16];
+  // ---- epilogue.  After the last barrier the tile buffers are free; each wave uses a part of
+  // them to turn its accumulators (lane = weight row n, 16 activation rows per register set)
+  // into rows of Y, so that a lane stores 4 consecutive outputs at once.
+  constexpr int TS = BN + 4;                                   // floats per staged row
+  float* Tw = (float*)smem + wave * (32 * TS);                 // 32 rows x BN of this wave
+  float* rsb = (float*)smem + kMW * (32 * TS) + wave * 64;     // its 64 row sums
+  float al[NF], mn[NF];
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int c = 0; c < NF; ++c) {
+    const int n = n0 + c * 32 + l32;
+    al[c] = n < d.out ? alpha[n] : 0.f;
+    mn[c] = n < d.out ? mu[n] : 0.f;
+  }
+  // row sums: the two halves of a row meet, then every lane picks up the 32 it needs
 #pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      const int m = m0 + wave * 64 + a * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
-      rs[a][e] = rowsum[min(m, M - 1)];
+  for (int a = 0; a < 2; ++a) rsum[a] += __shfl_xor(rsum[a], 32, 64);
+  if (h == 0) {
+    rsb[l32] = rsum[0];
+    rsb[32 + l32] = rsum[1];
+  }
+  wave_lds_sync();
+  const bool vec = (d.out & 3) == 0;                           // 4 outputs of a row are aligned and inside
+#pragma unroll
+  for (int a = 0; a < 2; ++a) {
+    const int mrow0 = m0 + wave * 64 + a * 32;
+    float rs[16];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const float4 v = *(const float4*)(rsb + a * 32 + 8 * g + 4 * h);
+      rs[4 * g + 0] = v.x; rs[4 * g + 1] = v.y; rs[4 * g + 2] = v.z; rs[4 * g + 3] = v.w;
     }
-  auto store_all = [&](auto* Yt, auto cvt) {
+    if (vec) {
 #pragma unroll
-    for (int c = 0; c < NF; ++c) {
-      const int n = n0 + c * 32 + l32;
-      if (n >= d.out) continue;
-      const float al = alpha[n], mn = mu[n];
+      for (int c = 0; c < NF; ++c)
 #pragma unroll
-      for (int a = 0; a < 2; ++a) {
+        for (int e = 0; e < 16; ++e)
+          Tw[(8 * (e >> 2) + 4 * h + (e & 3)) * TS + c * 32 + l32] = al[c] * acc[a][c][e] + mn[c] * rs[e];
+      wave_lds_sync();
+#pragma unroll 4
+      for (int i = 0; i < BN / 8; ++i) {
+        const int idx = i * 64 + lane;
+        const int r = idx / (BN / 4), c4 = idx - r * (BN / 4);
+        const float4 v = *(const float4*)(Tw + r * TS + 4 * c4);
+        const int m = mrow0 + r, n = n0 + 4 * c4;
+        if (m < M && n < d.out) {
+          const long long o = (long long)m * d.out + n;
+          if (y_dtype == BTC_F32) {
+            *(float4*)((float*)Y + o) = v;
+          } else if (y_dtype == BTC_BF16) {
+            *(uint2*)((uint16_t*)Y + o) = make_uint2(bf16_bits(v.x) | (bf16_bits(v.y) << 16),
+                                                     bf16_bits(v.z) | (bf16_bits(v.w) << 16));
+          } else {
+            *(uint2*)((uint16_t*)Y + o) = make_uint2(f16_bits(v.x) | (f16_bits(v.y) << 16),
+                                                     f16_bits(v.z) | (f16_bits(v.w) << 16));
+          }
+        }
+      }
+      wave_lds_sync();                                         // before the second half overwrites the rows
+    } else {
+#pragma unroll
+      for (int c = 0; c < NF; ++c) {
+        const int n = n0 + c * 32 + l32;
+        if (n >= d.out) continue;
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          const int m = m0 + wave * 64 + a * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
-          if (m < M) Yt[(long long)m * d.out + n] = cvt(al * acc[a][c][e] + mn * rs[a][e]);
+          const int m = mrow0 + 8 * (e >> 2) + 4 * h + (e & 3);
+          if (m >= M) continue;
+          const float r = al[c] * acc[a][c][e] + mn[c] * rs[e];
+          const long long o = (long long)m * d.out + n;
+          if (y_dtype == BTC_F32) ((float*)Y)[o] = r;
+          else if (y_dtype == BTC_BF16) ((__hip_bfloat16*)Y)[o] = __float2bfloat16(r);
+          else ((__half*)Y)[o] = __float2half_rn(r);
         }
       }
     }
-  };
-  if (y_dtype == BTC_F32) store_all((float*)Y, [](float r) { return r; });
-  else if (y_dtype == BTC_BF16) store_all((__hip_bfloat16*)Y, [](float r) { return __float2bfloat16(r); });
-  else store_all((__half*)Y, [](float r) { return __float2half_rn(r); });
+  }
 }
 
 template <int NF>
@@ -287,8 +397,7 @@ static size_t lds_bytes(int b) { return (size_t)2 * 32 * NF * kRS * 2 + ((size_t
 
 template <int NF, bool BF16>
 static btc_status launch(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
-                         const float* alpha, const float* mu, const void* X, int M, void* Y, int y_dtype,
-                         const float* rowsum) {
+                         const float* alpha, const float* mu, const void* X, int M, void* Y, int y_dtype) {
   static bool attr_set = false;  // one-time kernel attribute, not call state
   if (!attr_set) {
     if (hipFuncSetAttribute((const void*)gemm_tiled_kernel<NF, BF16>, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -301,7 +410,7 @@ static btc_status launch(hipStream_t q, const Dims& d, const uint32_t* packed, c
   if (m_blocks >= 8) grid = 8 * ((m_blocks + 7) / 8) * n_blocks;
   else grid = m_blocks * n_blocks;
   gemm_tiled_kernel<NF, BF16><<<grid, (kMW + kDW) * 64, lds_bytes<NF>(d.b), q>>>(
-      d, packed, codebook, alpha, mu, (const uint16_t*)X, M, Y, y_dtype, rowsum, m_blocks, n_blocks);
+      d, packed, codebook, alpha, mu, (const uint16_t*)X, M, Y, y_dtype, m_blocks, n_blocks);
   return launch_status();
 }
 
@@ -336,14 +445,13 @@ bool gemm_tiled_covers(const Dims& d, int M) {
 }
 
 btc_status gemm_tiled(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
-                      const float* alpha, const float* mu, const void* X, int is_bf16, int M, void* Y, int y_dtype,
-                      const float* rowsum) {
+                      const float* alpha, const float* mu, const void* X, int is_bf16, int M, void* Y, int y_dtype) {
   using namespace tiled;
   const int nf = pick_nf(d, M);
 #define BTC_TILED_CASE(NFV)                                                                                         \
   if (nf == NFV)                                                                                                    \
-    return is_bf16 ? launch<NFV, true>(q, d, packed, codebook, alpha, mu, X, M, Y, y_dtype, rowsum)                 \
-                   : launch<NFV, false>(q, d, packed, codebook, alpha, mu, X, M, Y, y_dtype, rowsum)
+    return is_bf16 ? launch<NFV, true>(q, d, packed, codebook, alpha, mu, X, M, Y, y_dtype)                         \
+                   : launch<NFV, false>(q, d, packed, codebook, alpha, mu, X, M, Y, y_dtype)
   BTC_TILED_CASE(2);
   BTC_TILED_CASE(3);
   BTC_TILED_CASE(4);
