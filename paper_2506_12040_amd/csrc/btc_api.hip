@@ -1,6 +1,8 @@
 // Host-side entry points that touch no device memory: shape arithmetic,
 // byte counts, status strings.  (Storage format: Section "Compression
 // Analysis" -- ceil(log2 c) index bits per length-v vector.)
+#include <algorithm>
+
 #include "btc_internal.h"
 
 namespace btc {
@@ -51,12 +53,15 @@ size_t btc_packed_bytes(const btc_shape* s) {
 size_t btc_workspace_bytes(const btc_shape* s, int32_t rows, int is_gemm) {
   size_t need = 16;  // range-check flag of btc_pack
   if (!s || rows <= 0) return need;
+  const btc::Dims d = btc::dims_of(*s);
   if (is_gemm) {
     need += (((size_t)rows * sizeof(float)) + 15) & ~(size_t)15;  // fp32 row sums of X
-  } else if (btc::lut_engine_covers(btc::dims_of(*s))) {  // the table engine may be chosen
+  } else if (btc::lut_engine_covers(d)) {  // the table engine may be chosen
     need = btc::lut_workspace_bytes(*s);
   }
-  return need;
+  // partial sums of a call that the tiled contraction kernel splits along k
+  if (btc::gemm_tiled_covers(d, rows)) need = std::max(need, btc::gemm_tiled_workspace_bytes(d, rows));
+  return (need + 255) & ~(size_t)255;
 }
 
 const char* btc_status_str(btc_status st) {

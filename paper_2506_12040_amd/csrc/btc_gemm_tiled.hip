@@ -91,16 +91,19 @@ template <int NF, bool BF16>
 __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
     Dims d, const uint32_t* __restrict__ packed, const uint32_t* __restrict__ codebook,
     const float* __restrict__ alpha, const float* __restrict__ mu, const uint16_t* __restrict__ X, int M,
-    void* __restrict__ Y, int y_dtype, int m_blocks, int n_blocks) {
+    void* __restrict__ Y, int y_dtype, int m_blocks, int n_blocks, int tiles_per_split, float* __restrict__ part,
+    float* __restrict__ rpart) {
   constexpr int BN = 32 * NF;
   extern __shared__ __align__(16) unsigned char smem[];
   uint16_t* S = (uint16_t*)smem;                         // [2][BN][kRS]
   uint32_t* E = (uint32_t*)(S + 2 * BN * kRS);           // [2^b][8]: codeword -> 5 dwords of +-1 pairs
 
   // ---- workgroup -> (m block, n block); consecutive ids go to consecutive XCDs
-  int mb, nb;
+  int mb, nb, sp;                                       // activation-row block, weight-row block, k split
   {
-    const int L = blockIdx.x;
+    const int per_split = m_blocks >= 8 ? 8 * ((m_blocks + 7) >> 3) * n_blocks : m_blocks * n_blocks;
+    sp = blockIdx.x / per_split;
+    const int L = blockIdx.x - sp * per_split;
     if (m_blocks >= 8) {
       const int xcd = L & 7, s = L >> 3;
       const int per_xcd = (m_blocks + 7) >> 3;
@@ -116,6 +119,9 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int ntiles = (d.nchunks + kCH - 1) / kCH;
+  // this workgroup's share of the k-tiles (the host makes every split non-empty)
+  const int t_begin = sp * tiles_per_split;
+  const int nt = min(ntiles, t_begin + tiles_per_split) - t_begin;
 
   // Codeword table: built by all threads, but only after each role has put its first global
   // loads in flight (the table needs a round trip of its own for the codebook).
@@ -167,10 +173,11 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
         }
       }
     };
-    fetch(0);
+    fetch(t_begin);
     build_table();
-    for (int t = 0; t <= ntiles; ++t) {
-      if (t < ntiles) {
+    for (int lt = 0; lt <= nt; ++lt) {
+      const int t = t_begin + lt;
+      if (lt < nt) {
         uint32_t A[NI][3];
 #pragma unroll
         for (int it = 0; it < NI; ++it) {                // align the window to the first field
@@ -179,14 +186,14 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
 #pragma unroll
           for (int u = 0; u < 3; ++u) A[it][u] = __builtin_amdgcn_alignbit(W[it][u + 1], W[it][u], s0);
         }
-        if (t + 1 < ntiles) fetch(t + 1);                // next tile's words fly while this one is expanded
+        if (lt + 1 < nt) fetch(t + 1);                   // next tile's words fly while this one is expanded
 #pragma unroll
         for (int it = 0; it < NI; ++it) {
           const int item = did + it * kDW * 64;
           if (item < 2 * BN) {
             const int r = item >> 1, half = item & 1;
             const bool row_ok = n0 + r < d.out;
-            uint16_t* dst = S + (t & 1) * (BN * kRS) + r * kRS + half * (8 * kV);
+            uint16_t* dst = S + (lt & 1) * (BN * kRS) + r * kRS + half * (8 * kV);
             const int j0 = t * kCH + half * 8;
             const uint32_t mask = (1u << d.b) - 1u;
 #pragma unroll
@@ -221,6 +228,12 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
   }
 
   // ================================= contraction waves =================================
+  if (m0 + wave * 64 >= M) {                             // no activation rows for this wave: keep the barriers only
+    build_table();
+    __syncthreads();
+    for (int lt = 0; lt < nt; ++lt) __syncthreads();
+    return;
+  }
   __builtin_amdgcn_s_setprio(2);                         // the matrix pipe is the bottleneck: issue these first
   const int h = lane >> 5, l32 = lane & 31;
   f32x16 acc[2][NF];
@@ -261,7 +274,7 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
   uint4 bfr[NF];
   float rsum[2] = {0.f, 0.f};                            // this lane's half of the row sums of its two rows
 #pragma unroll
-  for (int i = 0; i < kAS; ++i) load_a(ablk[i], 32 * i);
+  for (int i = 0; i < kAS; ++i) load_a(ablk[i], t_begin * kKT + 32 * i);
   build_table();
   __syncthreads();                                       // tile 0 decoded
   const uint16_t* sbase = S + l32 * kRS + 16 * h;
@@ -305,13 +318,14 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
     }
     __syncthreads();                                     // tile t consumed; tile t+1 decoded
   };
-  for (int t = 0; t < ntiles; t += 6) {
+  for (int lt = 0; lt < nt; lt += 6) {                   // the tile body's variant follows the local tile number
+    const int t = t_begin + lt;
     tile(t, std::integral_constant<int, 0>{});
-    if (t + 1 < ntiles) tile(t + 1, std::integral_constant<int, 1>{});
-    if (t + 2 < ntiles) tile(t + 2, std::integral_constant<int, 2>{});
-    if (t + 3 < ntiles) tile(t + 3, std::integral_constant<int, 3>{});
-    if (t + 4 < ntiles) tile(t + 4, std::integral_constant<int, 4>{});
-    if (t + 5 < ntiles) tile(t + 5, std::integral_constant<int, 5>{});
+    if (lt + 1 < nt) tile(t + 1, std::integral_constant<int, 1>{});
+    if (lt + 2 < nt) tile(t + 2, std::integral_constant<int, 2>{});
+    if (lt + 3 < nt) tile(t + 3, std::integral_constant<int, 3>{});
+    if (lt + 4 < nt) tile(t + 4, std::integral_constant<int, 4>{});
+    if (lt + 5 < nt) tile(t + 5, std::integral_constant<int, 5>{});
   }
 
   // ---- epilogue.  After the last barrier the tile buffers are free; each wave uses a part of
@@ -320,12 +334,20 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
   constexpr int TS = BN + 4;                                   // floats per staged row
   float* Tw = (float*)smem + wave * (32 * TS);                 // 32 rows x BN of this wave
   float* rsb = (float*)smem + kMW * (32 * TS) + wave * 64;     // its 64 row sums
+  // With a k split the workgroup leaves its raw sums (and, from the first weight-row block,
+  // its share of the activation row sums) in the workspace; a second kernel adds the splits
+  // and applies alpha and mu.
+  const bool split = part != nullptr;
+  if (split) {
+    Y = part + (size_t)sp * M * d.out;
+    y_dtype = BTC_F32;
+  }
   float al[NF], mn[NF];
 #pragma unroll
   for (int c = 0; c < NF; ++c) {
     const int n = n0 + c * 32 + l32;
-    al[c] = n < d.out ? alpha[n] : 0.f;
-    mn[c] = n < d.out ? mu[n] : 0.f;
+    al[c] = split ? 1.f : (n < d.out ? alpha[n] : 0.f);
+    mn[c] = split ? 0.f : (n < d.out ? mu[n] : 0.f);
   }
   // row sums: the two halves of a row meet, then every lane picks up the 32 it needs
 #pragma unroll
@@ -333,6 +355,13 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
   if (h == 0) {
     rsb[l32] = rsum[0];
     rsb[32 + l32] = rsum[1];
+    if (split && nb == 0) {
+#pragma unroll
+      for (int a = 0; a < 2; ++a) {
+        const int m = m0 + wave * 64 + a * 32 + l32;
+        if (m < M) rpart[(size_t)sp * M + m] = rsum[a];
+      }
+    }
   }
   wave_lds_sync();
   const bool vec = (d.out & 3) == 0;                           // 4 outputs of a row are aligned and inside
@@ -395,9 +424,95 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
 template <int NF>
 static size_t lds_bytes(int b) { return (size_t)2 * 32 * NF * kRS * 2 + ((size_t)32 << b); }
 
+// Second pass of a k-split call:  Y = alpha * (sum of the splits' raw sums) + mu * (sum of their
+// activation row sums), in split order.
+__global__ __launch_bounds__(256) void split_reduce_kernel(const float* __restrict__ part,
+                                                           const float* __restrict__ rpart,
+                                                           const float* __restrict__ alpha,
+                                                           const float* __restrict__ mu, int M, int out, int splits,
+                                                           void* __restrict__ Y, int y_dtype) {
+  const long long total = (long long)M * out;
+  const bool vec = (out & 3) == 0;
+  const long long i0 = ((long long)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i0 >= total) return;
+  const int lanes = vec ? 4 : (int)min(4LL, total - i0);
+  float v[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int sp = 0; sp < splits; ++sp) {
+    const float* p = part + (size_t)sp * total + i0;
+    if (vec) {
+      const float4 t = *(const float4*)p;
+      v[0] += t.x; v[1] += t.y; v[2] += t.z; v[3] += t.w;
+    } else {
+      for (int u = 0; u < lanes; ++u) v[u] += p[u];
+    }
+  }
+  float r[4];
+  for (int u = 0; u < lanes; ++u) {
+    const long long i = i0 + u;
+    const int m = (int)(i / out), n = (int)(i - (long long)m * out);
+    float rs = 0.f;
+    for (int sp = 0; sp < splits; ++sp) rs += rpart[(size_t)sp * M + m];
+    r[u] = alpha[n] * v[u] + mu[n] * rs;
+  }
+  if (vec && y_dtype == BTC_F32) {
+    *(float4*)((float*)Y + i0) = make_float4(r[0], r[1], r[2], r[3]);
+  } else if (vec && y_dtype == BTC_BF16) {
+    *(uint2*)((uint16_t*)Y + i0) =
+        make_uint2(bf16_bits(r[0]) | (bf16_bits(r[1]) << 16), bf16_bits(r[2]) | (bf16_bits(r[3]) << 16));
+  } else if (vec) {
+    *(uint2*)((uint16_t*)Y + i0) =
+        make_uint2(f16_bits(r[0]) | (f16_bits(r[1]) << 16), f16_bits(r[2]) | (f16_bits(r[3]) << 16));
+  } else {
+    for (int u = 0; u < lanes; ++u) {
+      if (y_dtype == BTC_F32) ((float*)Y)[i0 + u] = r[u];
+      else if (y_dtype == BTC_BF16) ((__hip_bfloat16*)Y)[i0 + u] = __float2bfloat16(r[u]);
+      else ((__half*)Y)[i0 + u] = __float2half_rn(r[u]);
+    }
+  }
+}
+
+struct Plan {
+  int nf;               // weight rows per workgroup / 32
+  int splits;           // workgroups that share one output tile along k
+  int tiles_per_split;
+  double est_us;        // modelled duration of the call
+};
+
+// Tile width and k split.  A workgroup occupies a compute unit, so the kernel lasts about
+//   rounds x (k-tiles per workgroup) x (time per k-tile) + a fixed part,
+// all fitted to measurements (microseconds): a k-tile costs 0.15 + 0.17 NF + 0.45 per contraction
+// wave that has activation rows (their loads, one L1 access per lane and 16 bytes, bound the
+// kernel; the NF term is the decode); prologue and epilogue cost 10 + 2 NF.  Wide tiles win
+// unless they leave compute units idle; then the k-tiles of an output tile are dealt to several
+// workgroups, which costs a second pass over the partial sums.
+static Plan make_plan(const Dims& d, int M) {
+  const int m_blocks = (M + kBM - 1) / kBM;
+  const int ntiles = (d.nchunks + kCH - 1) / kCH;
+  const int waves = (min(M, kBM) + 63) / 64;
+  Plan best{5, 1, ntiles, 0.0};
+  double best_cost = 1e300;
+  for (int nf = 2; nf <= 5; ++nf) {
+    const double t_tile = 0.15 + 0.17 * nf + 0.45 * waves;
+    const long long tiles_out = (long long)m_blocks * ((d.out + 32 * nf - 1) / (32 * nf));
+    for (int sp = 1; sp <= 8; ++sp) {
+      const int tps = (ntiles + sp - 1) / sp;
+      if (sp > 1 && (tps < 4 || (sp - 1) * tps >= ntiles)) continue;   // short or empty splits
+      const long long rounds = (tiles_out * sp + 255) / 256;
+      double cost = (double)rounds * tps * t_tile + 10.0 + 2.0 * nf;
+      if (sp > 1) cost += 2.0 + (double)sp * M * d.out * 4.0 / 3.0e6;   // second pass over the partials
+      if (cost < best_cost) {
+        best_cost = cost;
+        best = Plan{nf, sp, tps, cost};
+      }
+    }
+  }
+  return best;
+}
+
 template <int NF, bool BF16>
 static btc_status launch(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
-                         const float* alpha, const float* mu, const void* X, int M, void* Y, int y_dtype) {
+                         const float* alpha, const float* mu, const void* X, int M, void* Y, int y_dtype,
+                         const Plan& plan, void* workspace) {
   static bool attr_set = false;  // one-time kernel attribute, not call state
   if (!attr_set) {
     if (hipFuncSetAttribute((const void*)gemm_tiled_kernel<NF, BF16>, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -409,30 +524,21 @@ static btc_status launch(hipStream_t q, const Dims& d, const uint32_t* packed, c
   int grid;
   if (m_blocks >= 8) grid = 8 * ((m_blocks + 7) / 8) * n_blocks;
   else grid = m_blocks * n_blocks;
-  gemm_tiled_kernel<NF, BF16><<<grid, (kMW + kDW) * 64, lds_bytes<NF>(d.b), q>>>(
-      d, packed, codebook, alpha, mu, (const uint16_t*)X, M, Y, y_dtype, m_blocks, n_blocks);
-  return launch_status();
-}
-
-// Weight rows per workgroup (32 NF).  One workgroup occupies a CU, so the kernel time is
-// rounds x (time of one workgroup), and a workgroup's time grows with NF (2 NF MFMAs per
-// k-slice) plus a part that does not (activation loads, decode, barriers: about two
-// fragments' worth).  Pick the NF with the smallest estimate; few activation rows
-// therefore get narrow workgroups that fill more CUs.
-static int pick_nf(const Dims& d, int M) {
-  const int m_blocks = (M + kBM - 1) / kBM;
-  int best = 5;
-  double best_cost = 1e300;
-  for (int nf = 2; nf <= 5; ++nf) {
-    const long long wgs = (long long)m_blocks * ((d.out + 32 * nf - 1) / (32 * nf));
-    const long long rounds = (wgs + 255) / 256;
-    const double cost = (double)rounds * (nf + 2.0);
-    if (cost < best_cost - 1e-9 || (cost < best_cost + 1e-9 && nf > best)) {
-      best_cost = cost;
-      best = nf;
-    }
+  float* part = nullptr;
+  float* rpart = nullptr;
+  if (plan.splits > 1) {
+    part = (float*)workspace;
+    rpart = part + (size_t)plan.splits * M * d.out;
   }
-  return best;
+  gemm_tiled_kernel<NF, BF16><<<grid * plan.splits, (kMW + kDW) * 64, lds_bytes<NF>(d.b), q>>>(
+      d, packed, codebook, alpha, mu, (const uint16_t*)X, M, Y, y_dtype, m_blocks, n_blocks, plan.tiles_per_split,
+      part, rpart);
+  btc_status st = launch_status();
+  if (st != BTC_OK || plan.splits == 1) return st;
+  const long long quads = ((long long)M * d.out + 3) / 4;
+  split_reduce_kernel<<<(unsigned)((quads + 255) / 256), 256, 0, q>>>(part, rpart, alpha, mu, M, d.out, plan.splits, Y,
+                                                                     y_dtype);
+  return launch_status();
 }
 
 }  // namespace tiled
@@ -441,17 +547,27 @@ bool gemm_tiled_covers(const Dims& d, int M) {
   if (d.v != tiled::kV || d.b > 10) return false;
   if (d.in % 16 != 0) return false;                           // 16-byte aligned, whole 16-element A loads
   if ((long long)M * d.in * 2 >= (1LL << 31)) return false;   // 32-bit buffer offsets
-  return M >= 64;
+  return M >= 1;
+}
+
+double gemm_tiled_estimate_us(const Dims& d, int M) { return tiled::make_plan(d, M).est_us; }
+
+size_t gemm_tiled_workspace_bytes(const Dims& d, int M) {
+  const tiled::Plan plan = tiled::make_plan(d, M);
+  if (plan.splits == 1) return 0;
+  return (size_t)plan.splits * M * ((size_t)d.out + 1) * sizeof(float);
 }
 
 btc_status gemm_tiled(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
-                      const float* alpha, const float* mu, const void* X, int is_bf16, int M, void* Y, int y_dtype) {
+                      const float* alpha, const float* mu, const void* X, int is_bf16, int M, void* Y, int y_dtype,
+                      void* workspace, size_t workspace_bytes) {
   using namespace tiled;
-  const int nf = pick_nf(d, M);
+  const Plan plan = make_plan(d, M);
+  if (plan.splits > 1 && (!workspace || workspace_bytes < gemm_tiled_workspace_bytes(d, M))) return BTC_ERR_WORKSPACE;
 #define BTC_TILED_CASE(NFV)                                                                                         \
-  if (nf == NFV)                                                                                                    \
-    return is_bf16 ? launch<NFV, true>(q, d, packed, codebook, alpha, mu, X, M, Y, y_dtype)                         \
-                   : launch<NFV, false>(q, d, packed, codebook, alpha, mu, X, M, Y, y_dtype)
+  if (plan.nf == NFV)                                                                                               \
+    return is_bf16 ? launch<NFV, true>(q, d, packed, codebook, alpha, mu, X, M, Y, y_dtype, plan, workspace)        \
+                   : launch<NFV, false>(q, d, packed, codebook, alpha, mu, X, M, Y, y_dtype, plan, workspace)
   BTC_TILED_CASE(2);
   BTC_TILED_CASE(3);
   BTC_TILED_CASE(4);

@@ -1,6 +1,12 @@
 // btc_gemv: argument checks and engine selection for the decode-time product.
 #include "btc_internal.h"
 
+// Rough duration in microseconds of one decode pass over the matrix for a single activation
+// row (a fixed chain of round trips plus streaming time; fitted to measurements on 7B-shaped
+// layers).  Compared with the tiled contraction kernel's own estimate to decide whether a
+// batch is served by one pass per row or by one pass of that kernel for all rows.
+static double row_pass_us(const btc::Dims& d) { return 3.5 + 1.8e-6 * (double)d.out * d.wpr * 4; }
+
 extern "C" {
 
 btc_status btc_gemv(void* stream, const btc_shape* s, const uint32_t* packed, const uint32_t* codebook,
@@ -19,6 +25,14 @@ btc_status btc_gemv(void* stream, const btc_shape* s, const uint32_t* packed, co
   const Dims d = dims_of(*s);
   const int y_is_f32 = y_dtype == BTC_F32;
   const size_t ysz = y_is_f32 ? 4 : 2;
+  // Several activation rows: decoding the indices is the cost, and the matrix cores take up to 32
+  // rows for the price of one, so the call goes to the tiled contraction kernel (each index is
+  // decoded once for the whole batch) instead of one decode pass per row.
+  if (batch > 1 && gemm_tiled_covers(d, batch) && batch * row_pass_us(d) > gemm_tiled_estimate_us(d, batch)) {
+    if (gemm_tiled_workspace_bytes(d, batch) > 0 && workspace && !aligned16(workspace)) return BTC_ERR_ALIGN;
+    return gemm_tiled(q, d, packed, codebook, alpha, mu, x, /*is_bf16=*/0, batch, y, (int)y_dtype, workspace,
+                      workspace_bytes);
+  }
   // Small matrices are bound by the chain of memory round trips: the register-resident engine has the
   // shortest one.  Larger ones are bound by LDS and ALU throughput, where the table engine is lighter.
   const bool small = (long long)d.out * d.wpr * 4 < (4LL << 20) || !lut_engine_covers(d);
