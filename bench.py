@@ -15,8 +15,10 @@ sweep over all copies are captured once in a HIP graph (the calls still go
 through the C ABI, which only enqueues kernels) so that Python's per-call
 overhead is not what is timed; --mode stream times plain per-call launches.
 
-Also reported: prefill btc_gemm TFLOP/s on the same shapes (M = --gemm-m), a
-roofline object for the GEMV, and the CPU oracle timed on the host cores.
+Also reported: prefill btc_gemm TFLOP/s on the same shapes (M = --gemm-m and
+512), decode timings of the 7B shapes at batch 1/4/16 and of a 70B-shaped
+layer at 1.11/0.9/0.7 bit, a roofline object for the GEMV, and the CPU oracle
+timed on the host cores.
 """
 from __future__ import annotations
 
@@ -54,6 +56,7 @@ def main():
     ap.add_argument("--gemm-iters", type=int, default=10)
     ap.add_argument("--no-gemm", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-other", action="store_true", help="skip the 7B (batch 1/4/16) and 70B decode sweeps")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run three 256 MiB device-to-device copies (reference for FETCH_SIZE/WRITE_SIZE) and exit")
     args = ap.parse_args()
@@ -181,7 +184,85 @@ def main():
                                                         eff_GBps=round(by / us / 1e3, 1),
                                                         frac_hbm=round(by / us / 1e3 / HBM_PEAK_GBS, 4))
 
-    # ---- prefill GEMM on the same shapes (btc_gemm = row-sum kernel + contraction kernel per call)
+    # ---- the other decode configurations of the benchmark spec (timing only; random index words of the
+    # right shape, >= 1 GiB of distinct copies per shape so that every call streams from HBM)
+    other = None
+    if not args.no_other:
+        other = {}
+
+        def time_gemv(out_, in_, v_, K_, batch, reps_target=120):
+            s2 = B.btc_shape_init(out_, in_, v_, K_)
+            nbytes = out_ * s2.words_per_row * 4
+            ncopies = int(min(64, max(8, -(-(1 << 30) // nbytes))))
+            proto = torch.randint(0, 2**31 - 1, (out_, s2.words_per_row), dtype=torch.int32, device=dev)
+            copies = [torch.roll(proto, shifts=(i * 37 + 1) % out_, dims=0).contiguous() for i in range(ncopies)]
+            cb2 = torch.randint(0, 1 << v_, (1 << s2.b,), dtype=torch.int32, device=dev)
+            al2 = torch.rand(out_, device=dev) * 0.02
+            mu2 = torch.rand(out_, device=dev) * 0.002
+            x2 = torch.randn(batch, in_, device=dev).half()
+            y2 = torch.empty(batch, out_, dtype=torch.float16, device=dev)
+            ws2 = torch.zeros(B.btc_workspace_bytes(s2, batch, False), dtype=torch.uint8, device=dev)
+            for c in copies:
+                B.btc_gemv(s2, c, cb2, al2, mu2, x2, batch, y2, B.BTC_F16, ws2)
+            torch.cuda.synchronize()
+            g2 = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g2):
+                for c in copies:
+                    B.btc_gemv(s2, c, cb2, al2, mu2, x2, batch, y2, B.BTC_F16, ws2)
+            g2.replay()
+            torch.cuda.synchronize()
+            reps = max(1, reps_target // ncopies)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                g2.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / (reps * ncopies)
+            by = gemv_bytes(s2, batch)
+            del copies, proto
+            return dict(us_per_call=round(us, 2), eff_GBps=round(by / us / 1e3, 1),
+                        frac_hbm=round(by / us / 1e3 / HBM_PEAK_GBS, 4))
+
+        seven = {}
+        for (o, i) in [(4096, 4096), (11008, 4096), (4096, 11008)]:
+            seven[f"{o}x{i}"] = {f"batch{b}": time_gemv(o, i, 10, 512, b) for b in (1, 4, 16)}
+        other["llama2-7b v=10 K=512 (0.9 bit)"] = seven
+        for (v_, K_, tag) in [(9, 1024, "1.11 bit"), (10, 512, "0.9 bit"), (10, 128, "0.7 bit")]:
+            per, layer_us, layer_bytes = {}, 0.0, 0
+            for (o, i, cnt) in [(8192, 8192, 2), (1024, 8192, 2), (28672, 8192, 2), (8192, 28672, 1)]:
+                r = time_gemv(o, i, v_, K_, 1, reps_target=60)
+                per[f"{o}x{i}"] = r
+                layer_us += cnt * r["us_per_call"]
+                layer_bytes += cnt * gemv_bytes(B.btc_shape_init(o, i, v_, K_), 1)
+            other[f"llama2-70b v={v_} K={K_} ({tag})"] = dict(
+                per_shape=per, layer_us=round(layer_us, 1), layer_eff_GBps=round(layer_bytes / layer_us / 1e3, 1),
+                layer_frac_hbm=round(layer_bytes / layer_us / 1e3 / HBM_PEAK_GBS, 4))
+        # independent projections (q, k, v of one layer) on three streams, one graph per stream
+        p0 = protos[0]
+        mats = [c for calls in calls_per_layer for c in calls if c["p"] is p0][:120]
+        streams = [torch.cuda.Stream() for _ in range(3)]
+        graphs = []
+        wss = [torch.zeros_like(ws) for _ in streams]
+        for si, stq in enumerate(streams):
+            gq = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gq, stream=stq):
+                for c in mats[si::3]:
+                    B.btc_gemv(p0["s"], c["packed"], p0["codebook"], p0["alpha"], p0["mu"], p0["x"], 1, c["y"],
+                               B.BTC_F16, wss[si])
+            graphs.append(gq)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(10):
+            for gq, stq in zip(graphs, streams):
+                with torch.cuda.stream(stq):
+                    gq.replay()
+        torch.cuda.synchronize()
+        other["three_streams_5120x5120"] = dict(
+            us_per_call=round((time.perf_counter() - t0) * 1e6 / (10 * len(mats)), 2),
+            note="independent calls (as q, k, v of one layer) replayed from one graph per stream; host-timed")
+
+    # ---- prefill GEMM on the same shapes (btc_gemm = one contraction kernel per call, plus a second pass when the call is split along k)
     gemm = None
     if not args.no_gemm:
         gemm = {}
@@ -258,6 +339,7 @@ def main():
         "fp16_equivalent_GBps": round(fp16_equiv, 1),
         "per_shape": per_shape,
         "gemm": gemm,
+        "other_decode_configs": other,
         "roofline": {"bound": "hbm", "achieved": round(value, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(value / HBM_PEAK_GBS, 4), "traffic": None,
                      "note": "algorithmic bytes of the 7 calls of a step / event-timed duration of a step"},
@@ -265,7 +347,7 @@ def main():
             "bound": "mfma", "achieved": gemm[f"M{args.gemm_m}"]["layer_tflops"], "peak": MFMA_BF16_PEAK_TFLOPS,
             "unit": "TFLOP/s", "frac": gemm[f"M{args.gemm_m}"]["frac_mfma_peak"], "traffic": None,
             "note": f"2*M*out*in flop of the 7 projections at M={args.gemm_m} / event-timed btc_gemm calls "
-                    "(row-sum kernel included)"},
+                    "(whole calls)"},
         "cpu_baseline": cpu,
         "setup_s": round(t_setup, 1),
     }
