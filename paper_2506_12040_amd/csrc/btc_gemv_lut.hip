@@ -178,7 +178,7 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_lut_kernel(Dims d, const uin
   const int rows_per_wg = RT * kRowTiles * kTileRows;
   const int row_first = rb * rows_per_wg + tid;
   float al_first = 0.f, mu_first = 0.f;
-  if (ct == n_ct - 1 && tid < rows_per_wg && row_first < d.out) {
+  if (D == 1 && ct == n_ct - 1 && tid < 256 && row_first < d.out) {   // the threads that will store the rows
     al_first = alpha[row_first];
     mu_first = mu[row_first];
   }
@@ -375,14 +375,37 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_lut_kernel(Dims d, const uin
   // agent-scope fences would write back and invalidate the XCD's whole L2, tens of
   // microseconds per workgroup.)
   if (ct != n_ct - 1) return;
-  // sum of x: every thread adds the column-block sums in the same order
+  // Four threads share a row: thread (part, r) fetches the column blocks part, part + 4, ... of
+  // row r, all in flight at once, and adds them in increasing order; the four sums then meet in
+  // LDS and are added in a fixed order too, so the result does not depend on timing.
   float* sx_buf = (float*)stage_all;  // staging space is free now
+  float* comb = red;                  // [4][256], free after the last barrier of the main loop
   constexpr int NT = kWaves * 64;
-  unsigned long long p16[16];
-  if (tid < rows_per_wg && row_first < d.out) {  // first batch of this thread's partials: in flight with the sx loads
+  constexpr int kPB = 12;             // slots per thread and batch: 48 column blocks per batch
+  const int part = tid >> 8, rr = tid & 255;
+  unsigned long long pb[kPB];
+  auto fetch_slots = [&](int row, int c0) {
 #pragma unroll
-    for (int u = 0; u < 16; ++u) p16[u] = load_slot(&ws.partial[min(u, n_ct - 1) * d.out + row_first]);
+    for (int u = 0; u < kPB; ++u)   // the guard is uniform in a wave (part is), so no lane issues idle loads
+      if (c0 + 4 * u < n_ct) pb[u] = load_slot(&ws.partial[(c0 + 4 * u) * d.out + row]);
+  };
+  auto add_slots = [&](int row, int c0, float acc) {
+#pragma unroll
+    for (int u = 0; u < kPB; ++u) {
+      const int c = c0 + 4 * u;
+      if (c < n_ct) {
+        unsigned long long* slot = &ws.partial[c * d.out + row];
+        acc += slot_value(slot, pb[u]);
+        clear_slot(slot);
+      }
+    }
+    return acc;
+  };
+  if (D == 1) {  // first batch: in flight with the sx loads
+    const int row = rb * rows_per_wg + rr;
+    if (row < d.out) fetch_slots(row, part);
   }
+  // sum of x: every thread adds the column-block sums in the same order
   float sx = 0.f;
   for (int c0 = 0; c0 < n_ct; c0 += NT) {
     __syncthreads();
@@ -395,28 +418,49 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_lut_kernel(Dims d, const uin
     const int n = min(NT, n_ct - c0);
     for (int c = 0; c < n; ++c) sx += sx_buf[c];
   }
-  for (int r = tid; r < rows_per_wg; r += NT) {
-    const int row = rb * rows_per_wg + r;
-    if (row >= d.out) break;
-    const float al = r == tid ? al_first : alpha[row], mm = r == tid ? mu_first : mu[row];
+  if (D == 1) {   // one block of 256 rows per workgroup
+    const int row = rb * rows_per_wg + rr;
+    const bool ok = row < d.out;
     float dsum = 0.f;
-    for (int c = 0; c < n_ct; c += 16) {
-      if (r != tid || c != 0) {
-#pragma unroll
-        for (int u = 0; u < 16; ++u) p16[u] = load_slot(&ws.partial[min(c + u, n_ct - 1) * d.out + row]);
-      }
-#pragma unroll
-      for (int u = 0; u < 16; ++u) {
-        if (c + u < n_ct) {
-          unsigned long long* slot = &ws.partial[(c + u) * d.out + row];
-          dsum += slot_value(slot, p16[u]);
-          clear_slot(slot);
-        }
+    if (ok) {
+      for (int c0 = part; c0 < n_ct; c0 += 4 * kPB) {
+        if (c0 != part) fetch_slots(row, c0);
+        dsum = add_slots(row, c0, dsum);
       }
     }
-    const float res = al * dsum + mm * sx;
-    if (y_is_f32) ((float*)y)[row] = res;
-    else ((__half*)y)[row] = __float2half_rn(res);
+    comb[part * 256 + rr] = dsum;
+    __syncthreads();
+    if (part == 0 && ok) {
+      const float tot = ((comb[rr] + comb[256 + rr]) + comb[512 + rr]) + comb[768 + rr];
+      const float res = al_first * tot + mu_first * sx;
+      if (y_is_f32) ((float*)y)[row] = res;
+      else ((__half*)y)[row] = __float2half_rn(res);
+    }
+  } else {
+    // Several row blocks per workgroup: a thread per row keeps more rows in flight at once than
+    // four threads per row would, and the rows outnumber the threads anyway.
+    for (int r = tid; r < rows_per_wg; r += NT) {
+      const int row = rb * rows_per_wg + r;
+      if (row >= d.out) break;
+      const float al = alpha[row], mm = mu[row];
+      float dsum = 0.f;
+      for (int c = 0; c < n_ct; c += 16) {
+        unsigned long long p16[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) p16[u] = load_slot(&ws.partial[min(c + u, n_ct - 1) * d.out + row]);
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+          if (c + u < n_ct) {
+            unsigned long long* slot = &ws.partial[(c + u) * d.out + row];
+            dsum += slot_value(slot, p16[u]);
+            clear_slot(slot);
+          }
+        }
+      }
+      const float res = al * dsum + mm * sx;
+      if (y_is_f32) ((float*)y)[row] = res;
+      else ((__half*)y)[row] = __float2half_rn(res);
+    }
   }
 }
 
