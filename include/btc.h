@@ -69,7 +69,15 @@ size_t btc_packed_bytes(const btc_shape* s);
 
 /* Host. Bytes of workspace the call would need: rows = batch for btc_gemv
  * (is_gemm = 0), rows = M for btc_gemm (is_gemm != 0).  Always >= 16 so that
- * one buffer serves btc_pack too. */
+ * one buffer serves btc_pack too.
+ * The workspace is device memory owned by the caller, 16-byte aligned.  It
+ * must be ZERO-FILLED before its first use by btc_gemv; every btc_gemv call
+ * leaves it zero again (partial sums travel between workgroups in tagged
+ * slots whose empty state is 0), so one buffer serves any number of calls
+ * that are ordered on a stream.  Calls that may overlap in time (different
+ * streams) need a buffer each: sharing one is a data race.  btc_gemm writes
+ * scratch values there and needs no particular contents; give it a buffer of
+ * its own, or zero the buffer again before the next btc_gemv. */
 size_t btc_workspace_bytes(const btc_shape* s, int32_t rows, int is_gemm);
 
 /* Index matrix -> bit stream (Compression Analysis; storage format of the
@@ -95,8 +103,11 @@ btc_status btc_unpack(void* stream, const btc_shape* s, const uint32_t* packed, 
  *   alpha,mu : float [out]
  *   x        : fp16 [batch][in], batch 1..16
  *   y        : [batch][out] of y_dtype (BTC_F16 or BTC_F32, round to nearest even)
+ *   workspace: btc_workspace_bytes(s, batch, 0) bytes, see there (zero-filled)
  * Accumulates in fp32.  A stored index >= K reads codebook[index] inside the
- * 2^b-entry table. */
+ * 2^b-entry table.  Enqueues and returns.  Errors: BTC_ERR_NULL, _SHAPE,
+ * _UNSUPPORTED (batch outside 1..16, y_dtype), _ALIGN, _WORKSPACE (missing
+ * or too small for the engine chosen), _HIP (launch failed). */
 btc_status btc_gemv(void* stream, const btc_shape* s, const uint32_t* packed,
                     const uint32_t* codebook, const float* alpha, const float* mu,
                     const void* x, int32_t batch, void* y, btc_dtype y_dtype,

@@ -56,11 +56,14 @@ size_t btc_workspace_bytes(const btc_shape* s, int32_t rows, int is_gemm) {
   const btc::Dims d = btc::dims_of(*s);
   if (is_gemm) {
     need += (((size_t)rows * sizeof(float)) + 15) & ~(size_t)15;  // fp32 row sums of X
-  } else if (btc::lut_engine_covers(d)) {  // the table engine may be chosen
-    need = btc::lut_workspace_bytes(*s);
+    // partial sums of a call that the tiled contraction kernel splits along k
+    if (btc::gemm_tiled_covers(d, rows)) need = std::max(need, btc::gemm_tiled_workspace_bytes(d, rows));
+  } else {
+    // the table engine's slots (zero between calls), then the partial sums of a batched call
+    // that goes to the tiled contraction kernel and is split along k
+    need = btc::gemv_table_region_bytes(d);
+    if (rows > 1 && btc::gemm_tiled_covers(d, rows)) need += btc::gemm_tiled_workspace_bytes(d, rows);
   }
-  // partial sums of a call that the tiled contraction kernel splits along k
-  if (btc::gemm_tiled_covers(d, rows)) need = std::max(need, btc::gemm_tiled_workspace_bytes(d, rows));
   return (need + 255) & ~(size_t)255;
 }
 

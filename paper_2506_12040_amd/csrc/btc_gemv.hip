@@ -29,9 +29,16 @@ btc_status btc_gemv(void* stream, const btc_shape* s, const uint32_t* packed, co
   // rows for the price of one, so the call goes to the tiled contraction kernel (each index is
   // decoded once for the whole batch) instead of one decode pass per row.
   if (batch > 1 && gemm_tiled_covers(d, batch) && batch * row_pass_us(d) > gemm_tiled_estimate_us(d, batch)) {
-    if (gemm_tiled_workspace_bytes(d, batch) > 0 && workspace && !aligned16(workspace)) return BTC_ERR_ALIGN;
-    return gemm_tiled(q, d, packed, codebook, alpha, mu, x, /*is_bf16=*/0, batch, y, (int)y_dtype, workspace,
-                      workspace_bytes);
+    // A k-split call leaves partial sums behind; they go after the region whose zero state the
+    // table engine relies on, so that one workspace serves calls of any batch size.
+    const size_t off = gemv_table_region_bytes(d);
+    const size_t need = gemm_tiled_workspace_bytes(d, batch);
+    if (need > 0) {
+      if (!workspace || workspace_bytes < off + need) return BTC_ERR_WORKSPACE;
+      if (!aligned16(workspace)) return BTC_ERR_ALIGN;
+    }
+    return gemm_tiled(q, d, packed, codebook, alpha, mu, x, /*is_bf16=*/0, batch, y, (int)y_dtype,
+                      need > 0 ? (char*)workspace + off : nullptr, need);
   }
   // Small matrices are bound by the chain of memory round trips: the register-resident engine has the
   // shortest one.  Larger ones are bound by LDS and ALU throughput, where the table engine is lighter.

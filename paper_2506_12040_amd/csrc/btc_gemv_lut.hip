@@ -64,6 +64,13 @@ size_t lut_workspace_bytes(const btc_shape& s) {
   return round256(n_rt * n_ct * 8) + round256(n_ct * (size_t)s.out * 8);
 }
 
+size_t gemv_table_region_bytes(const Dims& d) {
+  if (!lut_engine_covers(d)) return 256;
+  const size_t n_ct = (d.nchunks + kTileCols - 1) / kTileCols;
+  const size_t n_rt = (d.out + kTileRows - 1) / kTileRows;
+  return round256(n_rt * n_ct * 8) + round256(n_ct * (size_t)d.out * 8);
+}
+
 static LutWorkspace carve(void* ws, const Dims& d) {
   const size_t n_ct = (d.nchunks + kTileCols - 1) / kTileCols;
   const size_t n_rt = (d.out + kTileRows - 1) / kTileRows;

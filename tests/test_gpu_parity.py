@@ -127,6 +127,34 @@ def test_gemv_config_4_full_size(G, oracle, case):
     _full_size_gemv(G, oracle, case, n_sample=192)
 
 
+def test_gemv_calls_share_one_workspace(G, oracle):
+    """One workspace, zero-filled once, serves calls of different shapes and batch sizes in a row:
+    the table engine must find (and leave) its slots empty whatever ran before."""
+    import torch
+    B = G.B
+    cases = [(700, 3008, 10, 64, 1), (700, 3008, 10, 64, 16), (300, 7008, 10, 64, 1), (9000, 4096, 10, 512, 16),
+             (9000, 4096, 10, 512, 1), (700, 3008, 10, 64, 4), (300, 7008, 10, 64, 1)]
+    layers = {}
+    need = 16
+    for (out, n_in, v, K, batch) in cases:
+        if (out, n_in, K) not in layers:
+            layer, _ = S.make_case(11, out, n_in, v, K, 1)
+            layers[(out, n_in, K)] = (layer, G.DeviceLayer(layer, oracle))
+        need = max(need, B.btc_workspace_bytes(layers[(out, n_in, K)][1].shape, batch, False))
+    ws = torch.zeros(need, dtype=torch.uint8, device="cuda")
+    rng = np.random.Generator(np.random.PCG64(5))
+    for (out, n_in, v, K, batch) in cases:
+        say(f"shared workspace: out={out} in={n_in} K={K} batch={batch}")
+        layer, dl = layers[(out, n_in, K)]
+        x = S.draw_x(rng, batch, n_in, "f16")
+        y = G.GuardedOutput(batch, out, torch.float16)
+        B.btc_gemv(dl.shape, dl.packed, dl.codebook, dl.alpha, dl.mu, G.dev(x), batch, y.payload, B.BTC_F16, ws)
+        y.check_guards()
+        rows = np.unique(np.concatenate([[0, out - 1], rng.choice(out, size=min(256, out), replace=False)]))
+        y_ref = oracle.linear(dl.packed_host, dl.codebook_host, layer.alpha, layer.mu, x, n_in, v, K, rows=rows)
+        G.assert_close(y.numpy()[:, rows], y_ref, f"shared workspace {out}x{n_in} batch {batch}")
+
+
 def test_gemv_invariants_on_gpu(G, oracle):
     """Full codebook and ones vector, evaluated by the HIP path itself."""
     B = G.B
