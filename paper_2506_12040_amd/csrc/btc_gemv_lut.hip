@@ -471,6 +471,261 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_lut_kernel(Dims d, const uin
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// Streaming variant for matrices of tens of megabytes (used for 9-bit indices).
+//
+// The kernel above is built for calls that last a few microseconds: it spends instructions
+// (a quarter tile per wave, two workgroup barriers per tile) to shorten every wave's serial
+// stream.  On a large matrix the same engine is bound by instruction issue, so here the
+// trade is reversed: a wave owns a whole 64 x 64 tile (64 lookups per staged tile instead of
+// 16, no workgroup barrier after the table is built, wave-private staging), workgroups stay
+// resident and build their table once, and each wave keeps two tiles in flight from memory.
+// Table, lookup order, partial-sum slots and the finishing workgroup are the same as above.
+constexpr int kStreamWaves = 12;
+
+template <int B>
+struct StreamCfg {
+  static constexpr int W2 = 2 * B;                       // words per tile row: 64 indices of B bits
+  static constexpr int RPI = 64 / W2;                    // tile rows fetched by one wave-wide load
+  static constexpr int NQ = (kTileRows + RPI - 1) / RPI; // loads per tile
+  static constexpr int kStageRows = NQ * RPI;            // >= 64
+  static constexpr int SR = W2 + 1;                      // staged row stride in words (odd)
+  static constexpr int kTableBytes = (1 << B) * 128;
+  static constexpr int kStageBytes = kStreamWaves * kStageRows * SR * 4;
+  static constexpr int kLdsBytes = kTableBytes + kStageBytes + 1024;   // + sums of x of the column blocks
+  static constexpr int kGroups = (1 << B) / 32;
+};
+
+template <int B, bool WIDE_V, bool X_DWORD>
+__global__ __launch_bounds__(kStreamWaves * 64) void gemv_lut_stream_kernel(
+    Dims d, const uint32_t* __restrict__ packed, const uint32_t* __restrict__ codebook,
+    const float* __restrict__ alpha, const float* __restrict__ mu, const __half* __restrict__ x,
+    void* __restrict__ y, int y_is_f32, LutWorkspace ws, int n_ct, int n_rb, int tiles_per_wg) {
+  using Cfg = StreamCfg<B>;
+  constexpr int W2 = Cfg::W2, SR = Cfg::SR, RPI = Cfg::RPI, NQ = Cfg::NQ;
+  constexpr int KH = WIDE_V ? 2 : 1;
+  extern __shared__ __align__(16) unsigned char smem[];
+  uint32_t* table = (uint32_t*)smem;                                   // [2^B][32] dwords of 2 x fp16
+  uint32_t* stage_all = (uint32_t*)(smem + Cfg::kTableBytes);
+  float* sx_buf = (float*)(smem + Cfg::kTableBytes + Cfg::kStageBytes);
+
+  // Same XCD-aware numbering as above, with one more workgroup per row block: number n_ct has
+  // no column block; it only finishes the rows (below).
+  const int L = blockIdx.x;
+  const int xcd = L & 7, slot = L >> 3;
+  const int rb = (slot / (n_ct + 1)) * 8 + xcd;
+  const int ct = slot - (slot / (n_ct + 1)) * (n_ct + 1);
+  if (rb >= n_rb) return;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int j = lane & 31, h = lane >> 5;
+  uint32_t* stage = stage_all + wave * (Cfg::kStageRows * SR);
+  const int tile_first = rb * tiles_per_wg;                            // this workgroup's 64-row tiles
+  const int n_tiles_all = (d.out + kTileRows - 1) / kTileRows;
+  const int tile_end = min(tile_first + tiles_per_wg, n_tiles_all);
+
+  // ---- index tiles: lane (lr, lw) fetches word lw of tile rows lr, lr + RPI, ...
+  const int lr = lane / W2, lw = lane - lr * W2;
+  const int words_left = d.wpr - ct * W2;
+  const bool lane_loads = lr < RPI;
+  const uint32_t tile_voff = (lane_loads && lw < words_left) ? (uint32_t)(lr * d.wpr + lw) * 4u : kOob;
+  const uint32_t q_stride = (uint32_t)(RPI * d.wpr) * 4u;
+  const uint32_t total_bytes = (uint32_t)d.out * (uint32_t)d.wpr * 4u;
+  uint32_t ld[2][NQ];
+  auto load_tile = [&](int tile, uint32_t (&dst)[NQ]) {
+    const int row0 = tile * kTileRows;
+    const bool inside = tile < tile_end;                               // tiles of other workgroups are not fetched
+    const uint32_t base_off = inside ? ((uint32_t)row0 * (uint32_t)d.wpr + (uint32_t)(ct * W2)) * 4u : 0u;
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)((const char*)packed + base_off), 0, inside ? (int)(total_bytes - base_off) : 0, kRsrcFlags);
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) dst[i] = __builtin_amdgcn_raw_buffer_load_b32(rs, tile_voff + (uint32_t)i * q_stride, 0, 0);
+  };
+  if (ct == n_ct) {
+    // ---- The finishing workgroup.  It has the highest workgroup id of its row block, so the
+    // in-order dispatcher has placed every producer of the block before it; producers never
+    // wait, hence the polls below end (they are bounded all the same: NaN, not a hang).  It
+    // starts polling at once and follows the producers tile by tile, so that at the end of
+    // the call only the last tiles' round trip is left.
+    constexpr int NT = kStreamWaves * 64;
+    float sx = 0.f;
+    for (int c0 = 0; c0 < n_ct; c0 += 256) {
+      __syncthreads();
+      if (tid < 256 && c0 + tid < n_ct) {
+        unsigned long long* sl = &ws.sx[rb * n_ct + c0 + tid];
+        sx_buf[tid] = slot_value(sl, load_slot(sl));
+        clear_slot(sl);
+      }
+      __syncthreads();
+      const int n = min(256, n_ct - c0);
+      for (int c = 0; c < n; ++c) sx += sx_buf[c];
+    }
+    const int row_begin = tile_first * kTileRows, row_end = min(tile_end * kTileRows, d.out);
+    for (int row = row_begin + tid; row < row_end; row += NT) {
+      const float al = alpha[row], mm = mu[row];
+      float dsum = 0.f;
+      for (int c = 0; c < n_ct; c += 16) {
+        unsigned long long p16[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u)
+          if (c + u < n_ct) p16[u] = load_slot(&ws.partial[(c + u) * d.out + row]);
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+          if (c + u < n_ct) {
+            unsigned long long* sl = &ws.partial[(c + u) * d.out + row];
+            dsum += slot_value(sl, p16[u]);
+            clear_slot(sl);
+          }
+        }
+      }
+      const float res = al * dsum + mm * sx;
+      if (y_is_f32) ((float*)y)[row] = res;
+      else ((__half*)y)[row] = __float2half_rn(res);
+    }
+    return;
+  }
+
+  // ---- activations first (the table needs them, and loads return in order), then the first
+  // two index tiles of this wave; the table build is split over the waves by 32-codeword
+  // groups as in the kernel above
+  {
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)x, 0, d.in * 2, kRsrcFlags);
+    uint4 bx[2][KH];
+    if (wave >= Cfg::kGroups) {
+      load_tile(tile_first + wave, ld[0]);
+    } else {
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb) {
+        const int chunk = ct * kTileCols + nb * 32 + j;
+#pragma unroll
+        for (int kh = 0; kh < KH; ++kh) {
+          const int t0 = kh * 16 + h * 8;
+          const uint32_t e0 = (uint32_t)(chunk * d.v + t0) * 2u;
+          uint32_t wv[4];
+          if (X_DWORD) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              wv[i] = __builtin_amdgcn_raw_buffer_load_b32(rx, (t0 + 2 * i < d.v) ? e0 + 4u * i : kOob, 0, 0);
+          } else {
+            uint32_t hv[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+              hv[e] = __builtin_amdgcn_raw_buffer_load_b16(rx, (t0 + e < d.v) ? e0 + 2u * e : kOob, 0, 0);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) wv[i] = (hv[2 * i] & 0xFFFFu) | (hv[2 * i + 1] << 16);
+          }
+          bx[nb][kh] = make_uint4(wv[0], wv[1], wv[2], wv[3]);
+        }
+      }
+      load_tile(tile_first + wave, ld[0]);   // the second tile is requested after the barrier: issuing it here
+                                             // would hold this wave in the (saturated) memory queue while
+                                             // the whole workgroup waits for its part of the table
+      if (wave == 0) {  // one wave also adds the block's activations up
+        float sxl = 0.f;
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+          for (int kh = 0; kh < KH; ++kh) {
+            const uint32_t w4[4] = {bx[nb][kh].x, bx[nb][kh].y, bx[nb][kh].z, bx[nb][kh].w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const f16x2 p = __builtin_bit_cast(f16x2, w4[i]);
+              sxl += (float)p[0];
+              sxl += (float)p[1];
+            }
+          }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) sxl += __shfl_xor(sxl, o, 64);
+        if (lane == 0) store_slot(&ws.sx[rb * n_ct + ct], sxl);
+      }
+      for (int cg = wave; cg < Cfg::kGroups; cg += kStreamWaves) {
+        const uint32_t npat = ~codebook[cg * 32 + j];
+        f32x16 d0, d1;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) d0[e] = d1[e] = 0.f;
+#pragma unroll
+        for (int kh = 0; kh < KH; ++kh) {
+          const uint32_t n = npat >> (kh * 16 + h * 8);
+          const uint4 a = make_uint4(sign_pair(n, 0), sign_pair(n, 1), sign_pair(n, 2), sign_pair(n, 3));
+          d0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
+                                                      __builtin_bit_cast(f16x8, bx[0][kh]), d0, 0, 0, 0);
+          d1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
+                                                      __builtin_bit_cast(f16x8, bx[1][kh]), d1, 0, 0, 0);
+        }
+        uint32_t* trow = table + (cg * 32 + 4 * h) * 32 + j;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) trow[(8 * (e >> 2) + (e & 3)) * 32] = pack_f16x2(d0[e], d1[e]);
+      }
+    }
+  }
+
+  // ---- per-lane constants of the skewed walk: step i reads column c = (lane + i) & 63
+  // (column c + 32 shares the dword of column c and sits in its other half: steps 32..63 reuse
+  // the offsets of steps 0..31 with bit 1 flipped, which halves the registers held)
+  uint32_t colofs[32];
+#pragma unroll
+  for (int i = 0; i < 32; ++i) {
+    const uint32_t c = (uint32_t)(lane + i);
+    colofs[i] = ((c << 2) & 124u) | ((c >> 4) & 2u);
+  }
+  const int rot_bits = lane * B;
+  const int wr = rot_bits >> 5;
+  const uint32_t sh = rot_bits & 31;
+  uint32_t* stage_wr = stage + lr * SR + lw;
+  const uint32_t* rd_a = stage + lane * SR + wr;       // word i of the rotated row: rd_a[i], or
+  const uint32_t* rd_b = rd_a - W2;                    // rd_b[i] once wr + i has run past the row's end
+  __syncthreads();                                     // the table is complete
+  load_tile(tile_first + wave + kStreamWaves, ld[1]);
+
+  const char* table_bytes = (const char*)table;
+  auto one_tile = [&](int tile, uint32_t (&cur)[NQ]) {
+    if (lane_loads) {
+#pragma unroll
+      for (int i = 0; i < NQ; ++i) stage_wr[i * RPI * SR] = cur[i];
+    }
+    load_tile(tile + 2 * kStreamWaves, cur);            // two tiles ahead, into the registers just staged
+    wave_lds_sync();
+    uint32_t Wd[W2];
+#pragma unroll
+    for (int i = 0; i < W2; ++i) {
+      // lanes l >= ceil(32 (W2 - i) / B) have wrapped around at word i
+      constexpr int dummy = 0;
+      (void)dummy;
+      const int first_wrapped = (32 * (W2 - i) + B - 1) / B;
+      Wd[i] = (lane >= first_wrapped ? rd_b : rd_a)[i];
+    }
+    wave_lds_sync();                                    // staging area free for the next tile
+    uint32_t R[W2 + 1];
+#pragma unroll
+    for (int i = 0; i < W2; ++i) R[i] = __builtin_amdgcn_alignbit(Wd[(i + 1) % W2], Wd[i], sh);
+    R[W2] = 0;
+    float acc = 0.f;
+#pragma unroll
+    for (int t = 0; t < 64; t += 2) {
+      _Float16 e2[2];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int p = (t + u) * B, w = p >> 5, s = p & 31;
+        uint32_t code;
+        if (s + B <= 32) code = (R[w] >> s) & ((1u << B) - 1u);
+        else code = __builtin_amdgcn_alignbit(R[w + 1], R[w], s) & ((1u << B) - 1u);
+        const uint32_t at = (code << 7) | colofs[(t + u) & 31];
+        e2[u] = *(const _Float16*)(table_bytes + (t + u < 32 ? at : at ^ 2u));
+      }
+      const f16x2 pr = {e2[0], e2[1]};
+      const f16x2 one = {(_Float16)1.0f, (_Float16)1.0f};
+      acc = __builtin_amdgcn_fdot2(pr, one, acc, false);
+    }
+    const int row = tile * kTileRows + lane;
+    if (row < d.out) store_slot(&ws.partial[ct * d.out + row], acc);
+  };
+  for (int tile = tile_first + wave; tile < tile_end; tile += 2 * kStreamWaves) {
+    one_tile(tile, ld[0]);
+    if (tile + kStreamWaves < tile_end) one_tile(tile + kStreamWaves, ld[1]);
+  }
+}
+
 constexpr int kDeep = 4;  // tiles in flight per wave when a workgroup walks several
 
 // Workgroups of this kernel that fit one XCD (32 compute units) at a time.
@@ -527,9 +782,68 @@ static btc_status launch_lut2(hipStream_t q, const Dims& d, const uint32_t* pack
                                                      RT);
 }
 
+// Streaming variant: applicable when a whole row block's column blocks fit one XCD at one
+// workgroup per compute unit, and every wave gets at least two tiles.
+template <int B>
+static bool stream_applies(const Dims& d, int* n_rb_out, int* tiles_per_wg_out) {
+  // Measured on 28672 x 8192: with 9-bit indices (64 KB table, one workgroup per compute unit either
+  // way) the streaming kernel takes 21.8 us against 27.0; with 8 bits and fewer the kernel above
+  // fits two workgroups per compute unit and wins (17.1 against 20.0 us); the 128 KB table of 10-bit
+  // indices leaves no room for 12 staging areas.
+  if (B != 9) return false;
+  const int n_ct = (d.nchunks + kTileCols - 1) / kTileCols;
+  const int tiles = (d.out + kTileRows - 1) / kTileRows;
+  if (n_ct + 1 > 32) return false;
+  const int n_rb = 8 * (32 / (n_ct + 1));                   // n_ct producers and one finishing workgroup per row block
+  const int tiles_per_wg = (tiles + n_rb - 1) / n_rb;
+  if (tiles_per_wg < 2 * kStreamWaves) return false;
+  *n_rb_out = (tiles + tiles_per_wg - 1) / tiles_per_wg;
+  *tiles_per_wg_out = tiles_per_wg;
+  return true;
+}
+
+template <int B, bool WIDE_V, bool X_DWORD>
+static btc_status launch_stream2(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
+                                 const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, void* ws,
+                                 int n_rb, int tiles_per_wg) {
+  using Cfg = StreamCfg<B>;
+  static_assert(Cfg::kLdsBytes <= 160 * 1024 - 64, "LDS budget");
+  static bool attr_set = false;  // one-time kernel attribute, not call state
+  if (!attr_set) {
+    if (hipFuncSetAttribute((const void*)gemv_lut_stream_kernel<B, WIDE_V, X_DWORD>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes) != hipSuccess)
+      return BTC_ERR_HIP;
+    attr_set = true;
+  }
+  const int n_ct = (d.nchunks + kTileCols - 1) / kTileCols;
+  const int grid = ((n_rb + 7) / 8) * 8 * (n_ct + 1);
+  gemv_lut_stream_kernel<B, WIDE_V, X_DWORD><<<grid, kStreamWaves * 64, Cfg::kLdsBytes, q>>>(
+      d, packed, codebook, alpha, mu, (const __half*)x, y, y_is_f32, carve(ws, d), n_ct, n_rb, tiles_per_wg);
+  return launch_status();
+}
+
+template <int B>
+static btc_status launch_stream(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
+                                const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, void* ws,
+                                int n_rb, int tiles_per_wg) {
+  if constexpr (B <= 9) {
+    const bool xdw = (d.v % 2 == 0) && (d.in % 2 == 0);
+    if (d.v > 16)
+      return launch_stream2<B, true, false>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws, n_rb, tiles_per_wg);
+    if (xdw)
+      return launch_stream2<B, false, true>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws, n_rb, tiles_per_wg);
+    return launch_stream2<B, false, false>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws, n_rb, tiles_per_wg);
+  } else {
+    return BTC_ERR_UNSUPPORTED;
+  }
+}
+
 template <int B, bool DUP>
 static btc_status launch_lut(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
                              const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, void* ws) {
+  int n_rb, tiles_per_wg;
+  if (stream_applies<B>(d, &n_rb, &tiles_per_wg))
+    return launch_stream<B>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws, n_rb, tiles_per_wg);
   const bool xdw = (d.v % 2 == 0) && (d.in % 2 == 0);
   if (d.v > 16) return launch_lut2<B, DUP, true, false>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
   if (xdw) return launch_lut2<B, DUP, false, true>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws);
