@@ -125,6 +125,86 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// ---- pieces of the table build shared by both kernels of this file ------------------------
+
+// Activations of column block ct as MFMA B operands: lane (j = lane % 32, h = lane / 32) gets
+// elements 8 h .. 8 h + 7 (and 16 + 8 h .. for chunks longer than 16) of chunk columns j and
+// 32 + j.  Elements outside the chunk or past the end of x read as 0, which also realises the
+// zero padding of the last chunk.
+template <bool WIDE_V, bool X_DWORD>
+__device__ __forceinline__ void load_block_activations(const __half* x, const Dims& d, int ct, int j, int h,
+                                                       uint4 (&bx)[2][WIDE_V ? 2 : 1]) {
+  constexpr int KH = WIDE_V ? 2 : 1;
+  const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)x, 0, d.in * 2, kRsrcFlags);
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb) {
+    const int chunk = ct * kTileCols + nb * 32 + j;
+#pragma unroll
+    for (int kh = 0; kh < KH; ++kh) {
+      const int t0 = kh * 16 + h * 8;
+      const uint32_t e0 = (uint32_t)(chunk * d.v + t0) * 2u;   // byte offset of element t0 of the chunk
+      uint32_t wv[4];
+      if (X_DWORD) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          wv[i] = __builtin_amdgcn_raw_buffer_load_b32(rx, (t0 + 2 * i < d.v) ? e0 + 4u * i : kOob, 0, 0);
+      } else {
+        uint32_t hv[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          hv[e] = __builtin_amdgcn_raw_buffer_load_b16(rx, (t0 + e < d.v) ? e0 + 2u * e : kOob, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) wv[i] = (hv[2 * i] & 0xFFFFu) | (hv[2 * i + 1] << 16);
+      }
+      bx[nb][kh] = make_uint4(wv[0], wv[1], wv[2], wv[3]);
+    }
+  }
+}
+
+// Sum of the block's activations over the whole wave (every element is held by exactly one lane).
+template <int KH>
+__device__ __forceinline__ float block_activation_sum(const uint4 (&bx)[2][KH]) {
+  float sxl = 0.f;
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+    for (int kh = 0; kh < KH; ++kh) {
+      const uint32_t w4[4] = {bx[nb][kh].x, bx[nb][kh].y, bx[nb][kh].z, bx[nb][kh].w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const f16x2 p = __builtin_bit_cast(f16x2, w4[i]);
+        sxl += (float)p[0];
+        sxl += (float)p[1];
+      }
+    }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) sxl += __shfl_xor(sxl, o, 64);
+  return sxl;
+}
+
+// Table rows of the 32 codewords of group cg: 32 codewords x 64 columns per pair of MFMAs.
+// D[i][jj]: lane holds column jj = lane % 32 and codewords i = 8 (e/4) + 4 h + e%4; columns j (low
+// half) and 32 + j (high half) of a codeword row share a dword.  npat = ~codeword of lane j.
+template <int KH>
+__device__ __forceinline__ void build_table_group(uint32_t* table, int cg, uint32_t npat, const uint4 (&bx)[2][KH],
+                                                  int j, int h) {
+  f32x16 d0, d1;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) d0[e] = d1[e] = 0.f;
+#pragma unroll
+  for (int kh = 0; kh < KH; ++kh) {
+    const uint32_t n = npat >> (kh * 16 + h * 8);
+    const uint4 a = make_uint4(sign_pair(n, 0), sign_pair(n, 1), sign_pair(n, 2), sign_pair(n, 3));
+    d0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, bx[0][kh]), d0,
+                                                0, 0, 0);
+    d1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, bx[1][kh]), d1,
+                                                0, 0, 0);
+  }
+  uint32_t* trow = table + (cg * 32 + 4 * h) * 32 + j;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) trow[(8 * (e >> 2) + (e & 3)) * 32] = pack_f16x2(d0[e], d1[e]);
+}
+
 constexpr int kRowTiles = 4;    // 64-row tiles a workgroup works on at once
 constexpr int kQuarters = 4;    // waves that share one row tile: each walks 16 of the 64 columns
 constexpr int kWaves = kRowTiles * kQuarters;
@@ -227,32 +307,7 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_lut_kernel(Dims d, const uin
   if (builds) {
 #pragma unroll
     for (int it = 0; it < Cfg::kGroupsPerWave; ++it) npat_all[it] = ~codebook[(it * kWaves + wave) * 32 + j];
-    // activations of this column block as MFMA B operands (lane: column j of block nb,
-    // elements 8h..8h+7 of the chunk); out-of-range elements read as 0
-    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)x, 0, d.in * 2, kRsrcFlags);
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-      const int chunk = ct * kTileCols + nb * 32 + j;
-#pragma unroll
-      for (int kh = 0; kh < KH; ++kh) {
-        const int t0 = kh * 16 + h * 8;
-        const uint32_t e0 = (uint32_t)(chunk * d.v + t0) * 2u;   // byte offset of element t0 of the chunk
-        uint32_t wv[4];
-        if (X_DWORD) {
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            wv[i] = __builtin_amdgcn_raw_buffer_load_b32(rx, (t0 + 2 * i < d.v) ? e0 + 4u * i : kOob, 0, 0);
-        } else {
-          uint32_t hv[8];
-#pragma unroll
-          for (int e = 0; e < 8; ++e)
-            hv[e] = __builtin_amdgcn_raw_buffer_load_b16(rx, (t0 + e < d.v) ? e0 + 2u * e : kOob, 0, 0);
-#pragma unroll
-          for (int i = 0; i < 4; ++i) wv[i] = (hv[2 * i] & 0xFFFFu) | (hv[2 * i + 1] << 16);
-        }
-        bx[nb][kh] = make_uint4(wv[0], wv[1], wv[2], wv[3]);
-      }
-    }
+    load_block_activations<WIDE_V, X_DWORD>(x, d, ct, j, h, bx);
   }
 
   // ---- per-lane constants of this wave's part of the skewed walk: it starts at virtual
@@ -272,47 +327,13 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_lut_kernel(Dims d, const uin
 
   if (builds) {
     if (wave == 0) {  // one wave also adds the block's activations up
-      float sxl = 0.f;
-#pragma unroll
-      for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-        for (int kh = 0; kh < KH; ++kh) {
-          const uint32_t w4[4] = {bx[nb][kh].x, bx[nb][kh].y, bx[nb][kh].z, bx[nb][kh].w};
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const f16x2 p = __builtin_bit_cast(f16x2, w4[i]);
-            sxl += (float)p[0];
-            sxl += (float)p[1];
-          }
-        }
-#pragma unroll
-      for (int o = 32; o > 0; o >>= 1) sxl += __shfl_xor(sxl, o, 64);
+      const float sxl = block_activation_sum<KH>(bx);
       if (lane == 0) store_slot(&ws.sx[rb * n_ct + ct], sxl);
     }
-    // 32 codewords x 64 columns per pair of MFMAs.
-    // D[i][jj]: lane holds column jj = lane % 32 and codewords i = 8 (e/4) + 4 h + e%4.
 #pragma unroll
     for (int it = 0; it < Cfg::kGroupsPerWave; ++it) {
       const int cg = it * kWaves + wave;
-      if (cg < Cfg::kGroups) {
-        const uint32_t npat = npat_all[it];
-        f32x16 d0, d1;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) d0[e] = d1[e] = 0.f;
-#pragma unroll
-        for (int kh = 0; kh < KH; ++kh) {
-          const uint32_t n = npat >> (kh * 16 + h * 8);
-          const uint4 a = make_uint4(sign_pair(n, 0), sign_pair(n, 1), sign_pair(n, 2), sign_pair(n, 3));
-          d0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
-                                                      __builtin_bit_cast(f16x8, bx[0][kh]), d0, 0, 0, 0);
-          d1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
-                                                      __builtin_bit_cast(f16x8, bx[1][kh]), d1, 0, 0, 0);
-        }
-        uint32_t* trow = table + (cg * 32 + 4 * h) * 32 + j;
-#pragma unroll
-        for (int e = 0; e < 16; ++e)  // columns j (low half) and 32 + j (high half) of codeword row
-          trow[(8 * (e >> 2) + (e & 3)) * 32] = pack_f16x2(d0[e], d1[e]);
-      }
+      if (cg < Cfg::kGroups) build_table_group<KH>(table, cg, npat_all[it], bx, j, h);
     }
   }
 
@@ -590,73 +611,20 @@ __global__ __launch_bounds__(kStreamWaves * 64) void gemv_lut_stream_kernel(
   // two index tiles of this wave; the table build is split over the waves by 32-codeword
   // groups as in the kernel above
   {
-    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)x, 0, d.in * 2, kRsrcFlags);
     uint4 bx[2][KH];
     if (wave >= Cfg::kGroups) {
       load_tile(tile_first + wave, ld[0]);
     } else {
-#pragma unroll
-      for (int nb = 0; nb < 2; ++nb) {
-        const int chunk = ct * kTileCols + nb * 32 + j;
-#pragma unroll
-        for (int kh = 0; kh < KH; ++kh) {
-          const int t0 = kh * 16 + h * 8;
-          const uint32_t e0 = (uint32_t)(chunk * d.v + t0) * 2u;
-          uint32_t wv[4];
-          if (X_DWORD) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-              wv[i] = __builtin_amdgcn_raw_buffer_load_b32(rx, (t0 + 2 * i < d.v) ? e0 + 4u * i : kOob, 0, 0);
-          } else {
-            uint32_t hv[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-              hv[e] = __builtin_amdgcn_raw_buffer_load_b16(rx, (t0 + e < d.v) ? e0 + 2u * e : kOob, 0, 0);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) wv[i] = (hv[2 * i] & 0xFFFFu) | (hv[2 * i + 1] << 16);
-          }
-          bx[nb][kh] = make_uint4(wv[0], wv[1], wv[2], wv[3]);
-        }
-      }
+      load_block_activations<WIDE_V, X_DWORD>(x, d, ct, j, h, bx);
       load_tile(tile_first + wave, ld[0]);   // the second tile is requested after the barrier: issuing it here
                                              // would hold this wave in the (saturated) memory queue while
                                              // the whole workgroup waits for its part of the table
       if (wave == 0) {  // one wave also adds the block's activations up
-        float sxl = 0.f;
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-          for (int kh = 0; kh < KH; ++kh) {
-            const uint32_t w4[4] = {bx[nb][kh].x, bx[nb][kh].y, bx[nb][kh].z, bx[nb][kh].w};
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              const f16x2 p = __builtin_bit_cast(f16x2, w4[i]);
-              sxl += (float)p[0];
-              sxl += (float)p[1];
-            }
-          }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) sxl += __shfl_xor(sxl, o, 64);
+        const float sxl = block_activation_sum<KH>(bx);
         if (lane == 0) store_slot(&ws.sx[rb * n_ct + ct], sxl);
       }
-      for (int cg = wave; cg < Cfg::kGroups; cg += kStreamWaves) {
-        const uint32_t npat = ~codebook[cg * 32 + j];
-        f32x16 d0, d1;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) d0[e] = d1[e] = 0.f;
-#pragma unroll
-        for (int kh = 0; kh < KH; ++kh) {
-          const uint32_t n = npat >> (kh * 16 + h * 8);
-          const uint4 a = make_uint4(sign_pair(n, 0), sign_pair(n, 1), sign_pair(n, 2), sign_pair(n, 3));
-          d0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
-                                                      __builtin_bit_cast(f16x8, bx[0][kh]), d0, 0, 0, 0);
-          d1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
-                                                      __builtin_bit_cast(f16x8, bx[1][kh]), d1, 0, 0, 0);
-        }
-        uint32_t* trow = table + (cg * 32 + 4 * h) * 32 + j;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) trow[(8 * (e >> 2) + (e & 3)) * 32] = pack_f16x2(d0[e], d1[e]);
-      }
+      for (int cg = wave; cg < Cfg::kGroups; cg += kStreamWaves)
+        build_table_group<KH>(table, cg, ~codebook[cg * 32 + j], bx, j, h);
     }
   }
 
