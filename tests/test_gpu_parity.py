@@ -127,6 +127,12 @@ def test_gemv_config_4_full_size(G, oracle, case):
     _full_size_gemv(G, oracle, case, n_sample=192)
 
 
+def test_gemv_large_ragged_streaming(G, oracle):
+    """A matrix large enough for the streaming kernel of the table engine (9-bit indices), with a
+    ragged last row tile and a ragged last column block."""
+    _full_size_gemv(G, oracle, dict(seed=3, out=28700, n_in=8190, v=10, K=512, batch=1), n_sample=192)
+
+
 def test_gemv_calls_share_one_workspace(G, oracle):
     """One workspace, zero-filled once, serves calls of different shapes and batch sizes in a row:
     the table engine must find (and leave) its slots empty whatever ran before."""
@@ -182,6 +188,10 @@ GEMM_SMALL = [
     (128, 5120, 10, 256, 256, "bf16"), (140, 810, 9, 1024, 130, "bf16"), (64, 700, 10, 128, 17, "f16"),
     (100, 333, 4, 9, 33, "bf16"), (90, 512, 16, 7132, 40, "f16"), (70, 250, 20, 65536, 9, "bf16"),
     (33, 640, 32, 2, 5, "bf16"), (50, 231, 7, 100, 3, "f16"), (1, 10, 10, 512, 1, "bf16"),
+    # tiled kernel (v = 10, in % 16 == 0): ragged M and out, out % 4 != 0 (scalar epilogue), every index
+    # width it has a table for, long rows with few outputs (k split), more than one block of activation rows
+    (301, 1600, 10, 256, 300, "bf16"), (300, 5136, 10, 512, 100, "f16"), (97, 2080, 10, 1024, 70, "bf16"),
+    (512, 1616, 10, 128, 513, "bf16"), (2100, 800, 10, 256, 64, "bf16"), (45, 4000, 10, 64, 2, "f16"),
 ]
 
 
