@@ -47,6 +47,7 @@ constexpr int kMW = 4;                  // contraction waves
 constexpr int kDW = 4;                  // decoder waves (8 waves per workgroup: 2 per SIMD, 256 registers each)
 constexpr uint32_t kOob = 0x80000000u;  // buffer offset that is always out of range
 constexpr int kRsrcFlags = 0x00020000;
+constexpr int kAStage = 2 * 32 * 64;     // bytes of a contraction wave's private activation slots in LDS
 
 template <bool BF16>
 __device__ __forceinline__ f32x16 mfma32(const uint4& a, const uint4& b, const f32x16& c) {
@@ -244,43 +245,94 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[a][c][e] = 0.f;
 
-  // A operand: lane (row l32 of fragment a, h) reads X[m][k0 + 32 T + 16 h .. + 15]
+  // A operand (activations), 64 rows per wave in two fragments of 32.
+  // An MFMA lane holds 8 consecutive elements of ONE row, so loading the operand straight from
+  // memory makes every lane touch a cache line of its own, and the vector L1 -- about one lane
+  // access per cycle -- is what bounds this kernel.  Passing everything through LDS instead
+  // trades that for LDS waits of the single contraction wave per SIMD.  So the load is split:
+  //   fragment 0 (rows 0..31): lane (row l32, h) reads X[m][k0 + 16 h .. + 15] straight into
+  //     registers, three blocks of 32 columns in flight;
+  //   fragment 1 (rows 32..63): fetched coalesced -- four consecutive lanes read the 64 bytes a
+  //     row has in a block -- parked in a wave-private LDS slot and read back in MFMA layout.
+  //     Only this wave touches the slot, so no barrier is involved (LDS operations of a wave
+  //     complete in order).  The four 16-byte pieces of a row are stored at position
+  //     piece ^ ((row / 2) % 4): the read-back of 8 consecutive rows then hits 8 bank groups.
   const __amdgpu_buffer_rsrc_t rX =
       __builtin_amdgcn_make_buffer_rsrc((void*)X, 0, (int)((long long)M * d.in * 2), kRsrcFlags);
   // Rows m >= M need no test of their own: X is row-major, so they lie past the end of the
   // buffer and the hardware range check returns zeros for them.
   const uint32_t xoff0 = (uint32_t)(((long long)(m0 + wave * 64 + l32) * d.in + 16 * h) * 2);
-  const uint32_t xstep = (uint32_t)(32LL * d.in * 2);    // second fragment: 32 rows further
-  auto load_a = [&](uint4 (&dst)[2][2], int k0) {        // k0: first column of a block of 32
-    // `in` is a multiple of 16 for this kernel; past the end of a row bit 31 of the offset is set
-    const uint32_t past = (uint32_t)(k0 + 16 * h + 16 > d.in) << 31;
+  const int k_lim = min(d.in, (t_begin + nt) * kKT);     // columns of this workgroup's share end here
+  auto load_direct = [&](uint4 (&dst)[2], int k0) {      // k0: first column of a block of 32
+    // `in` is a multiple of 16 for this kernel; past the end of the row (or of this workgroup's share of
+    // it: those blocks are requested by the pipeline but never used) bit 31 of the offset is set
+    const uint32_t past = (uint32_t)(k0 + 16 * h + 16 > k_lim) << 31;
+    const uint32_t off = (xoff0 + (uint32_t)k0 * 2u) | past;
+    dst[0] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rX, off, 0, 0));
+    dst[1] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rX, off + 16u, 0, 0));
+  };
+  unsigned char* AS = smem + 2 * BN * kRS * 2 + ((size_t)32 << d.b) + wave * kAStage;   // [2][32 rows][64 B]
+  const int lrow = lane >> 2, lq = lane & 3;
+  const int lpiece = lq ^ ((lrow >> 1) & 3);             // the piece this lane fetches (parked at position lq)
+  const uint32_t goff0 = (uint32_t)(((long long)(m0 + wave * 64 + 32 + lrow) * d.in + 8 * lpiece) * 2);
+  const uint32_t gstep = (uint32_t)(16LL * d.in * 2);    // load j covers rows 32 + 16 j + lane / 4
+  auto load_stage = [&](uint4 (&dst)[2], int k0) {
+    const uint32_t past = (uint32_t)(k0 + 8 * lpiece + 8 > k_lim) << 31;
 #pragma unroll
-    for (int a = 0; a < 2; ++a) {
-      const uint32_t off = (xoff0 + (uint32_t)a * xstep + (uint32_t)k0 * 2u) | past;
-      dst[a][0] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rX, off, 0, 0));
-      dst[a][1] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rX, off + 16u, 0, 0));
+    for (int j = 0; j < 2; ++j) {
+      const uint32_t off = (goff0 + (uint32_t)j * gstep + (uint32_t)k0 * 2u) | past;
+      dst[j] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rX, off, 0, 0));
     }
   };
-
-  // Software pipeline.  Activations: kAS register slots, a block is requested kAS - 1 blocks
-  // (about a microsecond of MFMA time) before its use, because the loads come from L2 or
-  // beyond.  Pattern fragments: one register set; fragment c of the next k-slice is read from
-  // LDS right after the two MFMAs that use fragment c of the current slice have been issued,
-  // a whole slice of MFMAs before it is needed.  Slots are compile-time (a tile has 5 blocks,
-  // so the slot pattern repeats every kAS tiles and the buffer parity every 2: 6 tile bodies).
-  constexpr int NB = kKT / 32;                           // blocks per k-tile
-  constexpr int kAS = 3;
-  uint4 ablk[kAS][2][2];                                 // [slot][fragment][k-slice]
-  uint4 bfr[NF];
-  float rsum[2] = {0.f, 0.f};                            // this lane's half of the row sums of its two rows
+  auto park = [&](int slot, const uint4 (&src)[2]) {
 #pragma unroll
-  for (int i = 0; i < kAS; ++i) load_a(ablk[i], t_begin * kKT + 32 * i);
+    for (int j = 0; j < 2; ++j) *(uint4*)(AS + slot * 2048 + j * 1024 + lane * 16) = src[j];
+  };
+  const int rsw = (l32 >> 1) & 3;
+  const unsigned char* ard0 = AS + l32 * 64 + 16 * ((2 * h) ^ rsw);       // k-slice 0: elements 16 h .. + 7
+  const unsigned char* ard1 = AS + l32 * 64 + 16 * ((2 * h + 1) ^ rsw);   // k-slice 1: elements 16 h + 8 .. + 15
+
+  // Software pipeline.  Fragment 0: kAS register slots, a block is requested kAS - 1 blocks
+  // before its use (a third slot does not fit the 256 registers next to 160 accumulators and
+  // measured no faster when it did).  Fragment 1: two register stages in
+  // flight from memory (requested three blocks ahead), two LDS slots (the block in use and the
+  // next), two fragment registers (the k-slice in use and the next).  Pattern fragments: one
+  // register set; fragment c of the next k-slice is read from LDS right after the two MFMAs
+  // that use fragment c of the current slice have been issued.  Slots are compile-time: a tile
+  // has 5 blocks, so register slot, LDS slot, stage and tile buffer all follow the parity of the
+  // tile's first block: 2 tile bodies.
+  constexpr int NB = kKT / 32;                           // blocks per k-tile
+  constexpr int kAS = 2;
+  uint4 ad[kAS][2];                                      // fragment 0: [slot][k-slice]
+  uint4 stg[2][2];                                       // fragment 1: [stage][load]
+  uint4 afr[2];                                          // fragment 1: [k-slice]
+  uint4 bfr[NF];
+  float rsum0 = 0.f;                                     // row l32, this lane's half of the columns
+  float rs2[2] = {0.f, 0.f};                             // row 32 + 16 j + lane / 4, this lane's piece
+  const int kb = t_begin * kKT;                          // first column of this workgroup's share
+#pragma unroll
+  for (int i = 0; i < kAS; ++i) load_direct(ad[i], kb + 32 * i);
+  load_stage(stg[0], kb);
+  load_stage(stg[1], kb + 32);
   build_table();
+  auto add_rows2 = [&](const uint4 (&src)[2]) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      rs2[j] = pair_sum<BF16>(src[j].x, rs2[j]);
+      rs2[j] = pair_sum<BF16>(src[j].y, rs2[j]);
+      rs2[j] = pair_sum<BF16>(src[j].z, rs2[j]);
+      rs2[j] = pair_sum<BF16>(src[j].w, rs2[j]);
+    }
+  };
+  park(0, stg[0]);
+  add_rows2(stg[0]);
+  load_stage(stg[0], kb + 64);
+  afr[0] = *(const uint4*)ard0;
   __syncthreads();                                       // tile 0 decoded
   const uint16_t* sbase = S + l32 * kRS + 16 * h;
   auto tile = [&](int t, auto variant) {
-    constexpr int PAR = decltype(variant)::value & 1;    // tile buffer
-    constexpr int PH = decltype(variant)::value % kAS;   // phase of the slot pattern
+    constexpr int PAR = decltype(variant)::value & 1;    // tile buffer; parity of the tile's first block
+    constexpr int PH = decltype(variant)::value % kAS;   // phase of the register-slot pattern
     const uint16_t* st = sbase + PAR * (BN * kRS);
 #pragma unroll
     for (int c = 0; c < NF; ++c) bfr[c] = *(const uint4*)(st + c * 32 * kRS);
@@ -289,43 +341,46 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
       constexpr int dummy = 0;
       (void)dummy;
       const int aslot = (NB * PH + T) % kAS;
+      const int bp = (PAR + T) & 1;                      // parity of this block
+      // Fragment 1 of the NEXT block moves from its register stage to the other LDS slot and
+      // the stage is refilled with the block three further on.  The scheduler must not move
+      // this (or the refills below) to the top of the tile: it would wait there for loads that
+      // are meant to stay in flight.
+      __builtin_amdgcn_sched_barrier(0);
+      park(bp ^ 1, stg[bp ^ 1]);
+      add_rows2(stg[bp ^ 1]);                            // (zeros beyond this workgroup's share)
+      load_stage(stg[bp ^ 1], t * kKT + (T + 3) * 32);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int s = 0; s < 2; ++s) {
         const int q = 2 * T + s;                         // slice number inside the tile
+        if (s == 0) afr[1] = *(const uint4*)(ard1 + bp * 2048);          // next slice: same block
+        else afr[0] = *(const uint4*)(ard0 + (bp ^ 1) * 2048);           //   first slice of the next block
 #pragma unroll
         for (int c = 0; c < NF; ++c) {
-          acc[0][c] = mfma32<BF16>(ablk[aslot][0][s], bfr[c], acc[0][c]);
-          acc[1][c] = mfma32<BF16>(ablk[aslot][1][s], bfr[c], acc[1][c]);
+          acc[0][c] = mfma32<BF16>(ad[aslot][s], bfr[c], acc[0][c]);
+          acc[1][c] = mfma32<BF16>(afr[s], bfr[c], acc[1][c]);
           if (q + 1 < 2 * NB) bfr[c] = *(const uint4*)(st + c * 32 * kRS + ((q + 1) >> 1) * 32 + 8 * ((q + 1) & 1));
         }
       }
-      // row sums of the activations (for the mu term) from the block just used: 16 packed dot
-      // products per lane, issued in the shadow of the MFMAs.  The scheduler must not move them
-      // (or the refill of the slot) to the top of the tile: they would wait there for loads
-      // that were meant to stay in flight.
+      // row sums of fragment 0 from the block just used, then its slot is refilled
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int s = 0; s < 2; ++s) {
-          rsum[a] = pair_sum<BF16>(ablk[aslot][a][s].x, rsum[a]);
-          rsum[a] = pair_sum<BF16>(ablk[aslot][a][s].y, rsum[a]);
-          rsum[a] = pair_sum<BF16>(ablk[aslot][a][s].z, rsum[a]);
-          rsum[a] = pair_sum<BF16>(ablk[aslot][a][s].w, rsum[a]);
-        }
-      load_a(ablk[aslot], t * kKT + (T + kAS) * 32);     // kAS blocks ahead (zeros past the end)
+      for (int s = 0; s < 2; ++s) {
+        rsum0 = pair_sum<BF16>(ad[aslot][s].x, rsum0);
+        rsum0 = pair_sum<BF16>(ad[aslot][s].y, rsum0);
+        rsum0 = pair_sum<BF16>(ad[aslot][s].z, rsum0);
+        rsum0 = pair_sum<BF16>(ad[aslot][s].w, rsum0);
+      }
+      load_direct(ad[aslot], t * kKT + (T + kAS) * 32);  // kAS blocks ahead (zeros past the end)
       __builtin_amdgcn_sched_barrier(0);
     }
     __syncthreads();                                     // tile t consumed; tile t+1 decoded
   };
-  for (int lt = 0; lt < nt; lt += 6) {                   // the tile body's variant follows the local tile number
+  for (int lt = 0; lt < nt; lt += 2) {                   // the tile body's variant follows the local tile number
     const int t = t_begin + lt;
     tile(t, std::integral_constant<int, 0>{});
     if (lt + 1 < nt) tile(t + 1, std::integral_constant<int, 1>{});
-    if (lt + 2 < nt) tile(t + 2, std::integral_constant<int, 2>{});
-    if (lt + 3 < nt) tile(t + 3, std::integral_constant<int, 3>{});
-    if (lt + 4 < nt) tile(t + 4, std::integral_constant<int, 4>{});
-    if (lt + 5 < nt) tile(t + 5, std::integral_constant<int, 5>{});
   }
 
   // ---- epilogue.  After the last barrier the tile buffers are free; each wave uses a part of
@@ -349,18 +404,25 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
     al[c] = split ? 1.f : (n < d.out ? alpha[n] : 0.f);
     mn[c] = split ? 0.f : (n < d.out ? mu[n] : 0.f);
   }
-  // row sums: the two halves of a row meet, then every lane picks up the 32 it needs
+  // row sums: the lanes that shared a row add up (two halves of fragment 0, four pieces of
+  // fragment 1), then every lane picks up the 32 sums it needs
+  rsum0 += __shfl_xor(rsum0, 32, 64);
 #pragma unroll
-  for (int a = 0; a < 2; ++a) rsum[a] += __shfl_xor(rsum[a], 32, 64);
+  for (int j = 0; j < 2; ++j) {
+    rs2[j] += __shfl_xor(rs2[j], 1, 64);
+    rs2[j] += __shfl_xor(rs2[j], 2, 64);
+  }
   if (h == 0) {
-    rsb[l32] = rsum[0];
-    rsb[32 + l32] = rsum[1];
-    if (split && nb == 0) {
+    rsb[l32] = rsum0;
+    const int m = m0 + wave * 64 + l32;
+    if (split && nb == 0 && m < M) rpart[(size_t)sp * M + m] = rsum0;
+  }
+  if (lq == 0) {
 #pragma unroll
-      for (int a = 0; a < 2; ++a) {
-        const int m = m0 + wave * 64 + a * 32 + l32;
-        if (m < M) rpart[(size_t)sp * M + m] = rsum[a];
-      }
+    for (int j = 0; j < 2; ++j) {
+      rsb[32 + 16 * j + lrow] = rs2[j];
+      const int m = m0 + wave * 64 + 32 + 16 * j + lrow;
+      if (split && nb == 0 && m < M) rpart[(size_t)sp * M + m] = rs2[j];
     }
   }
   wave_lds_sync();
@@ -422,7 +484,7 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
 }
 
 template <int NF>
-static size_t lds_bytes(int b) { return (size_t)2 * 32 * NF * kRS * 2 + ((size_t)32 << b); }
+static size_t lds_bytes(int b) { return (size_t)2 * 32 * NF * kRS * 2 + ((size_t)32 << b) + kMW * kAStage; }
 
 // Second pass of a k-split call:  Y = alpha * (sum of the splits' raw sums) + mu * (sum of their
 // activation row sums), in split order.
