@@ -35,6 +35,9 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+# HBM bytes of one step (7 calls) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
+# 256 MiB copy (profiles/gemv_13b_hbm_traffic.md): 37.1 MB fetched + 5.5 MB written.
+HBM_TRAFFIC_PER_STEP = 42.6e6
 
 SHAPES_13B = [(5120, 5120, 4), (13824, 5120, 2), (5120, 13824, 1)]   # (out, in, count per layer)
 V, K = 10, 256
@@ -341,8 +344,11 @@ def main():
         "gemm": gemm,
         "other_decode_configs": other,
         "roofline": {"bound": "hbm", "achieved": round(value, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(value / HBM_PEAK_GBS, 4), "traffic": None,
-                     "note": "algorithmic bytes of the 7 calls of a step / event-timed duration of a step"},
+                     "frac": round(value / HBM_PEAK_GBS, 4), "traffic": HBM_TRAFFIC_PER_STEP,
+                     "note": "algorithmic bytes of the 7 calls of a step / event-timed duration of a step; "
+                             "traffic = HBM bytes per step (fetched + written) from the rocprofv3 counter runs "
+                             "summarised in profiles/gemv_13b_hbm_traffic.md, algorithmic bytes per step "
+                             f"{step_bytes}"},
         "roofline_gemm": None if gemm is None else {
             "bound": "mfma", "achieved": gemm[f"M{args.gemm_m}"]["layer_tflops"], "peak": MFMA_BF16_PEAK_TFLOPS,
             "unit": "TFLOP/s", "frac": gemm[f"M{args.gemm_m}"]["frac_mfma_peak"], "traffic": None,
