@@ -727,12 +727,13 @@ static btc_status launch_lut2(hipStream_t q, const Dims& d, const uint32_t* pack
   using Cfg = LutCfg<B, DUP>;
   const int n_ct = (d.nchunks + kTileCols - 1) / kTileCols;
   const int tiles = (d.out + kTileRows - 1) / kTileRows;
-  // Row blocks (256 rows) per workgroup.  One, as long as the grid is at most two rounds of
-  // resident workgroups: everything is then requested from memory at the start, which is what
-  // a call of a few microseconds needs.  Two beyond that (measured: fewer table builds, and
-  // more does not help because a row block costs a workgroup about as much as a build).  With
-  // 10-bit indices the 128 KB table is expensive enough to build once per resident workgroup:
-  // then the row blocks are dealt to as many workgroups as stay resident, whole row blocks per XCD.
+  // Row blocks (256 rows) per workgroup.  One, as long as all workgroups are resident at once:
+  // everything is then requested from memory at the start, which is what a call of a few
+  // microseconds needs.  Two beyond that (measured on 7B- to 70B-sized matrices: a second round of
+  // workgroups costs more than a second row block, and more than two does not help because a row
+  // block costs a workgroup about as much as a table build).  With 10-bit indices the 128 KB
+  // table is expensive enough to build once per resident workgroup: then the row blocks are dealt
+  // to as many workgroups as stay resident, whole row blocks per XCD.
   const int blocks = (tiles + kRowTiles - 1) / kRowTiles;
   const int slots_xcd = xcd_slots(Cfg::kLdsBytes);
   int RT = 1;
@@ -740,7 +741,7 @@ static btc_status launch_lut2(hipStream_t q, const Dims& d, const uint32_t* pack
     const int rb_xcd = slots_xcd / n_ct;
     const int rb_fit = 8 * (rb_xcd > 0 ? rb_xcd : 1);
     RT = (blocks + rb_fit - 1) / rb_fit;
-  } else if ((long long)blocks * n_ct > 2LL * 8 * slots_xcd) {
+  } else if ((long long)blocks * n_ct > 8LL * slots_xcd) {
     RT = 2;
   }
   const int n_rb = (blocks + RT - 1) / RT;
