@@ -74,7 +74,8 @@ btc_status btc_gemm(void* stream, const btc_shape* s, const uint32_t* packed, co
   float* rowsum = (float*)((char*)workspace + 16);
   const int is_bf16 = x_dtype == BTC_BF16;
   if (gemm_tiled_covers(d, M))   // adds the activation rows up itself
-    return gemm_tiled(q, d, packed, codebook, alpha, mu, X, is_bf16, M, Y, (int)y_dtype, workspace, workspace_bytes);
+    return gemm_tiled(q, d, packed, codebook, alpha, mu, X, is_bf16, M, Y, (int)y_dtype, workspace, workspace_bytes,
+                      /*clear_workspace=*/0);
   rowsum_kernel<<<(M + 3) / 4, 256, 0, q>>>((const uint16_t*)X, M, d.in, is_bf16, rowsum);
   return gemm_generic(q, d, packed, codebook, alpha, mu, X, is_bf16, M, Y, (int)y_dtype, rowsum);
 }

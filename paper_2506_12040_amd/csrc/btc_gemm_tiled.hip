@@ -389,8 +389,8 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
   constexpr int TS = BN + 4;                                   // floats per staged row
   float* Tw = (float*)smem + wave * (32 * TS);                 // 32 rows x BN of this wave
   float* rsb = (float*)smem + kMW * (32 * TS) + wave * 64;     // its 64 row sums
-  // With a k split the workgroup leaves its raw sums (and, from the first weight-row block,
-  // its share of the activation row sums) in the workspace; a second kernel adds the splits
+  // With a k split the workgroup leaves its raw sums and its share of the activation row sums
+  // (one copy per weight-row block) in the workspace; a second kernel adds the splits
   // and applies alpha and mu.
   const bool split = part != nullptr;
   if (split) {
@@ -415,14 +415,14 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
   if (h == 0) {
     rsb[l32] = rsum0;
     const int m = m0 + wave * 64 + l32;
-    if (split && nb == 0 && m < M) rpart[(size_t)sp * M + m] = rsum0;
+    if (split && m < M) rpart[((size_t)sp * n_blocks + nb) * M + m] = rsum0;
   }
   if (lq == 0) {
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       rsb[32 + 16 * j + lrow] = rs2[j];
       const int m = m0 + wave * 64 + 32 + 16 * j + lrow;
-      if (split && nb == 0 && m < M) rpart[(size_t)sp * M + m] = rs2[j];
+      if (split && m < M) rpart[((size_t)sp * n_blocks + nb) * M + m] = rs2[j];
     }
   }
   wave_lds_sync();
@@ -487,49 +487,60 @@ template <int NF>
 static size_t lds_bytes(int b) { return (size_t)2 * 32 * NF * kRS * 2 + ((size_t)32 << b) + kMW * kAStage; }
 
 // Second pass of a k-split call:  Y = alpha * (sum of the splits' raw sums) + mu * (sum of their
-// activation row sums), in split order.
-__global__ __launch_bounds__(256) void split_reduce_kernel(const float* __restrict__ part,
-                                                           const float* __restrict__ rpart,
-                                                           const float* __restrict__ alpha,
-                                                           const float* __restrict__ mu, int M, int out, int splits,
-                                                           void* __restrict__ Y, int y_dtype) {
-  const long long total = (long long)M * out;
-  const bool vec = (out & 3) == 0;
-  const long long i0 = ((long long)blockIdx.x * 256 + threadIdx.x) * 4;
-  if (i0 >= total) return;
-  const int lanes = vec ? 4 : (int)min(4LL, total - i0);
-  float v[4] = {0.f, 0.f, 0.f, 0.f};
-  for (int sp = 0; sp < splits; ++sp) {
-    const float* p = part + (size_t)sp * total + i0;
-    if (vec) {
-      const float4 t = *(const float4*)p;
-      v[0] += t.x; v[1] += t.y; v[2] += t.z; v[3] += t.w;
-    } else {
-      for (int u = 0; u < lanes; ++u) v[u] += p[u];
+// activation row sums), in split order.  One small workgroup per (weight-row block, activation
+// row): it is the only reader of that block's partial sums and of that block's copy of the row
+// sums, so with `clear` it can hand the workspace back zero-filled (the decode entry point
+// promises that to its callers) without a race.
+__global__ __launch_bounds__(64) void split_reduce_kernel(float* __restrict__ part, float* __restrict__ rpart,
+                                                          const float* __restrict__ alpha,
+                                                          const float* __restrict__ mu, int M, int out, int bn,
+                                                          int splits, void* __restrict__ Y, int y_dtype, int clear) {
+  const int nb = blockIdx.x, m = blockIdx.y, tid = threadIdx.x;
+  const int n_blocks = gridDim.x;
+  const size_t total = (size_t)M * out;
+  float rs = 0.f;
+  for (int sp = 0; sp < splits; ++sp) rs += rpart[((size_t)sp * n_blocks + nb) * M + m];
+  const size_t row = (size_t)m * out;
+  const int n_begin = nb * bn, n_end = min(out, n_begin + bn);
+  if ((out & 3) == 0) {
+    for (int n = n_begin + 4 * tid; n < n_end; n += 4 * 64) {
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      for (int sp = 0; sp < splits; ++sp) {
+        float4* p = (float4*)(part + (size_t)sp * total + row + n);
+        const float4 t = *p;
+        v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
+        if (clear) *p = make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+      const float4 al = *(const float4*)(alpha + n), mn = *(const float4*)(mu + n);
+      const float r0 = al.x * v.x + mn.x * rs, r1 = al.y * v.y + mn.y * rs, r2 = al.z * v.z + mn.z * rs,
+                  r3 = al.w * v.w + mn.w * rs;
+      if (y_dtype == BTC_F32) {
+        *(float4*)((float*)Y + row + n) = make_float4(r0, r1, r2, r3);
+      } else if (y_dtype == BTC_BF16) {
+        *(uint2*)((uint16_t*)Y + row + n) =
+            make_uint2(bf16_bits(r0) | (bf16_bits(r1) << 16), bf16_bits(r2) | (bf16_bits(r3) << 16));
+      } else {
+        *(uint2*)((uint16_t*)Y + row + n) =
+            make_uint2(f16_bits(r0) | (f16_bits(r1) << 16), f16_bits(r2) | (f16_bits(r3) << 16));
+      }
     }
-  }
-  float r[4];
-  for (int u = 0; u < lanes; ++u) {
-    const long long i = i0 + u;
-    const int m = (int)(i / out), n = (int)(i - (long long)m * out);
-    float rs = 0.f;
-    for (int sp = 0; sp < splits; ++sp) rs += rpart[(size_t)sp * M + m];
-    r[u] = alpha[n] * v[u] + mu[n] * rs;
-  }
-  if (vec && y_dtype == BTC_F32) {
-    *(float4*)((float*)Y + i0) = make_float4(r[0], r[1], r[2], r[3]);
-  } else if (vec && y_dtype == BTC_BF16) {
-    *(uint2*)((uint16_t*)Y + i0) =
-        make_uint2(bf16_bits(r[0]) | (bf16_bits(r[1]) << 16), bf16_bits(r[2]) | (bf16_bits(r[3]) << 16));
-  } else if (vec) {
-    *(uint2*)((uint16_t*)Y + i0) =
-        make_uint2(f16_bits(r[0]) | (f16_bits(r[1]) << 16), f16_bits(r[2]) | (f16_bits(r[3]) << 16));
   } else {
-    for (int u = 0; u < lanes; ++u) {
-      if (y_dtype == BTC_F32) ((float*)Y)[i0 + u] = r[u];
-      else if (y_dtype == BTC_BF16) ((__hip_bfloat16*)Y)[i0 + u] = __float2bfloat16(r[u]);
-      else ((__half*)Y)[i0 + u] = __float2half_rn(r[u]);
+    for (int n = n_begin + tid; n < n_end; n += 64) {
+      float v = 0.f;
+      for (int sp = 0; sp < splits; ++sp) {
+        float* p = part + (size_t)sp * total + row + n;
+        v += *p;
+        if (clear) *p = 0.f;
+      }
+      const float r = alpha[n] * v + mu[n] * rs;
+      if (y_dtype == BTC_F32) ((float*)Y)[row + n] = r;
+      else if (y_dtype == BTC_BF16) ((__hip_bfloat16*)Y)[row + n] = __float2bfloat16(r);
+      else ((__half*)Y)[row + n] = __float2half_rn(r);
     }
+  }
+  if (clear) {
+    __syncthreads();   // every thread has read the row sum
+    if (tid < splits) rpart[((size_t)tid * n_blocks + nb) * M + m] = 0.f;
   }
 }
 
@@ -558,7 +569,7 @@ static Plan make_plan(const Dims& d, int M) {
     const long long tiles_out = (long long)m_blocks * ((d.out + 32 * nf - 1) / (32 * nf));
     for (int sp = 1; sp <= 8; ++sp) {
       const int tps = (ntiles + sp - 1) / sp;
-      if (sp > 1 && (tps < 4 || (sp - 1) * tps >= ntiles)) continue;   // short or empty splits
+      if (sp > 1 && (tps < 4 || (sp - 1) * tps >= ntiles || M > 65535)) continue;   // short or empty splits; grid limit of the second pass
       const long long rounds = (tiles_out * sp + 255) / 256;
       double cost = (double)rounds * tps * t_tile + 10.0 + 2.0 * nf;
       if (sp > 1) cost += 2.0 + (double)sp * M * d.out * 4.0 / 3.0e6;   // second pass over the partials
@@ -574,7 +585,7 @@ static Plan make_plan(const Dims& d, int M) {
 template <int NF, bool BF16>
 static btc_status launch(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
                          const float* alpha, const float* mu, const void* X, int M, void* Y, int y_dtype,
-                         const Plan& plan, void* workspace) {
+                         const Plan& plan, void* workspace, int clear_workspace) {
   static bool attr_set = false;  // one-time kernel attribute, not call state
   if (!attr_set) {
     if (hipFuncSetAttribute((const void*)gemm_tiled_kernel<NF, BF16>, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -597,9 +608,8 @@ static btc_status launch(hipStream_t q, const Dims& d, const uint32_t* packed, c
       part, rpart);
   btc_status st = launch_status();
   if (st != BTC_OK || plan.splits == 1) return st;
-  const long long quads = ((long long)M * d.out + 3) / 4;
-  split_reduce_kernel<<<(unsigned)((quads + 255) / 256), 256, 0, q>>>(part, rpart, alpha, mu, M, d.out, plan.splits, Y,
-                                                                     y_dtype);
+  split_reduce_kernel<<<dim3(n_blocks, M), 64, 0, q>>>(part, rpart, alpha, mu, M, d.out, 32 * NF, plan.splits, Y, y_dtype,
+                                                      clear_workspace);
   return launch_status();
 }
 
@@ -617,19 +627,22 @@ double gemm_tiled_estimate_us(const Dims& d, int M) { return tiled::make_plan(d,
 size_t gemm_tiled_workspace_bytes(const Dims& d, int M) {
   const tiled::Plan plan = tiled::make_plan(d, M);
   if (plan.splits == 1) return 0;
-  return (size_t)plan.splits * M * ((size_t)d.out + 1) * sizeof(float);
+  const size_t n_blocks = (d.out + 32 * plan.nf - 1) / (32 * plan.nf);
+  return (size_t)plan.splits * M * ((size_t)d.out + n_blocks) * sizeof(float);
 }
 
 btc_status gemm_tiled(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
                       const float* alpha, const float* mu, const void* X, int is_bf16, int M, void* Y, int y_dtype,
-                      void* workspace, size_t workspace_bytes) {
+                      void* workspace, size_t workspace_bytes, int clear_workspace) {
   using namespace tiled;
   const Plan plan = make_plan(d, M);
   if (plan.splits > 1 && (!workspace || workspace_bytes < gemm_tiled_workspace_bytes(d, M))) return BTC_ERR_WORKSPACE;
 #define BTC_TILED_CASE(NFV)                                                                                         \
   if (plan.nf == NFV)                                                                                               \
-    return is_bf16 ? launch<NFV, true>(q, d, packed, codebook, alpha, mu, X, M, Y, y_dtype, plan, workspace)        \
-                   : launch<NFV, false>(q, d, packed, codebook, alpha, mu, X, M, Y, y_dtype, plan, workspace)
+    return is_bf16 ? launch<NFV, true>(q, d, packed, codebook, alpha, mu, X, M, Y, y_dtype, plan, workspace,       \
+                                      clear_workspace)                                                          \
+                   : launch<NFV, false>(q, d, packed, codebook, alpha, mu, X, M, Y, y_dtype, plan, workspace,      \
+                                       clear_workspace)
   BTC_TILED_CASE(2);
   BTC_TILED_CASE(3);
   BTC_TILED_CASE(4);

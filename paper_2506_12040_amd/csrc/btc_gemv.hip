@@ -29,8 +29,9 @@ btc_status btc_gemv(void* stream, const btc_shape* s, const uint32_t* packed, co
   // rows for the price of one, so the call goes to the tiled contraction kernel (each index is
   // decoded once for the whole batch) instead of one decode pass per row.
   if (batch > 1 && gemm_tiled_covers(d, batch) && batch * row_pass_us(d) > gemm_tiled_estimate_us(d, batch)) {
-    // A k-split call leaves partial sums behind; they go after the region whose zero state the
-    // table engine relies on, so that one workspace serves calls of any batch size.
+    // A k-split call parks partial sums in the workspace (after the table engine's slots of this
+    // shape) and zeroes them again in its second pass, so that one zero-filled workspace serves
+    // any sequence of calls, whatever their shapes and batch sizes.
     const size_t off = gemv_table_region_bytes(d);
     const size_t need = gemm_tiled_workspace_bytes(d, batch);
     if (need > 0) {
@@ -38,11 +39,12 @@ btc_status btc_gemv(void* stream, const btc_shape* s, const uint32_t* packed, co
       if (!aligned16(workspace)) return BTC_ERR_ALIGN;
     }
     return gemm_tiled(q, d, packed, codebook, alpha, mu, x, /*is_bf16=*/0, batch, y, (int)y_dtype,
-                      need > 0 ? (char*)workspace + off : nullptr, need);
+                      need > 0 ? (char*)workspace + off : nullptr, need, /*clear_workspace=*/1);
   }
   // Small matrices are bound by the chain of memory round trips: the register-resident engine has the
-  // shortest one.  Larger ones are bound by LDS and ALU throughput, where the table engine is lighter.
-  const bool small = (long long)d.out * d.wpr * 4 < (4LL << 20) || !lut_engine_covers(d);
+  // shortest one.  Larger ones are bound by LDS and ALU throughput, where the table engine is lighter
+  // (measured crossover: 4096 x 4096 at 0.7-0.9 bit is faster expanded, 5120 x 5120 is faster looked up).
+  const bool small = (long long)d.out * d.wpr * 4 < (2LL << 20) || !lut_engine_covers(d);
   if (small && expand_engine_covers(d)) {
     for (int m = 0; m < batch; ++m) {
       st = gemv_expand(q, d, packed, codebook, alpha, mu, (const char*)x + (size_t)m * d.in * 2,

@@ -239,7 +239,7 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_lut_kernel(Dims d, const uin
                                                                const float* __restrict__ mu,
                                                                const __half* __restrict__ x, void* __restrict__ y,
                                                                int y_is_f32, LutWorkspace ws, int n_ct, int n_rb,
-                                                               int RT) {
+                                                               int RT, int fin) {
   using Cfg = LutCfg<B, DUP>;
   constexpr int W2 = Cfg::W2, SR = Cfg::SR, RPI = Cfg::RPI, NQW = Cfg::NQW, QW = Cfg::QW;
   constexpr int KH = WIDE_V ? 2 : 1;
@@ -253,8 +253,9 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_lut_kernel(Dims d, const uin
   // meet in the same L2.
   const int L = blockIdx.x;
   const int xcd = L & 7, slot = L >> 3;
-  const int rb = (slot / n_ct) * 8 + xcd;
-  const int ct = slot - (slot / n_ct) * n_ct;
+  const int n_cols = n_ct + fin;                         // with fin, workgroup n_ct of a row block only finishes rows
+  const int rb = (slot / n_cols) * 8 + xcd;
+  const int ct = slot - (slot / n_cols) * n_cols;
   if (rb >= n_rb) return;
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -265,10 +266,18 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_lut_kernel(Dims d, const uin
   const int rows_per_wg = RT * kRowTiles * kTileRows;
   const int row_first = rb * rows_per_wg + tid;
   float al_first = 0.f, mu_first = 0.f;
-  if (D == 1 && ct == n_ct - 1 && tid < 256 && row_first < d.out) {   // the threads that will store the rows
+  if (D == 1 && ct == n_ct - 1 + fin && tid < 256 && row_first < d.out) {   // the threads that will store the rows
     al_first = alpha[row_first];
     mu_first = mu[row_first];
   }
+  // Finishing a row block: add the column blocks' partial sums in order, scale, store (details
+  // at the end of the kernel).  Done by the workgroup of the last column block after its own
+  // lookups or, with `fin`, by an extra workgroup that does nothing else and therefore polls
+  // from the start: the call then ends one poll after the last partial sum lands instead of a
+  // production phase plus polls later.  The extra workgroup costs a residency slot, so the host
+  // asks for it only when every workgroup of the grid is resident at once anyway.
+  const bool finisher = fin && ct == n_ct;
+  auto produce = [&]() {
   const int j = lane & 31, h = lane >> 5;
   uint32_t* stage = stage_all + wt * (Cfg::kStageRows * SR);
 
@@ -402,7 +411,11 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_lut_kernel(Dims d, const uin
   // (An arrival counter would cost a device-scope atomic round trip per workgroup; full
   // agent-scope fences would write back and invalidate the XCD's whole L2, tens of
   // microseconds per workgroup.)
-  if (ct != n_ct - 1) return;
+  };
+  if (!finisher) {
+    produce();
+    if (fin || ct != n_ct - 1) return;
+  }
   // Four threads share a row: thread (part, r) fetches the column blocks part, part + 4, ... of
   // row r, all in flight at once, and adds them in increasing order; the four sums then meet in
   // LDS and are added in a fixed order too, so the result does not depend on timing.
@@ -705,7 +718,7 @@ static int xcd_slots(int lds_bytes) {
 template <int B, bool DUP, bool WIDE_V, bool X_DWORD, int D>
 static btc_status launch_lut3(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
                               const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, void* ws,
-                              int n_ct, int n_rb, int RT) {
+                              int n_ct, int n_rb, int RT, int fin) {
   using Cfg = LutCfg<B, DUP>;
   static_assert(Cfg::kLdsBytes <= 160 * 1024 - 64, "LDS budget");
   static bool attr_set = false;  // one-time kernel attribute, not call state
@@ -715,9 +728,9 @@ static btc_status launch_lut3(hipStream_t q, const Dims& d, const uint32_t* pack
       return BTC_ERR_HIP;
     attr_set = true;
   }
-  const int grid = ((n_rb + 7) / 8) * 8 * n_ct;
+  const int grid = ((n_rb + 7) / 8) * 8 * (n_ct + fin);
   gemv_lut_kernel<B, DUP, WIDE_V, X_DWORD, D><<<grid, kWaves * 64, Cfg::kLdsBytes, q>>>(
-      d, packed, codebook, alpha, mu, (const __half*)x, y, y_is_f32, carve(ws, d), n_ct, n_rb, RT);
+      d, packed, codebook, alpha, mu, (const __half*)x, y, y_is_f32, carve(ws, d), n_ct, n_rb, RT, fin);
   return launch_status();
 }
 
@@ -745,10 +758,13 @@ static btc_status launch_lut2(hipStream_t q, const Dims& d, const uint32_t* pack
     RT = 2;
   }
   const int n_rb = (blocks + RT - 1) / RT;
+  // an extra finishing workgroup per row block, if the grid is still resident at once with it
+  const int fin = RT == 1 && (long long)blocks * (n_ct + 1) <= 8LL * slots_xcd;
   if (RT == 1)
-    return launch_lut3<B, DUP, WIDE_V, X_DWORD, 1>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws, n_ct, n_rb, RT);
+    return launch_lut3<B, DUP, WIDE_V, X_DWORD, 1>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws, n_ct, n_rb, RT,
+                                                   fin);
   return launch_lut3<B, DUP, WIDE_V, X_DWORD, kDeep>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, ws, n_ct, n_rb,
-                                                     RT);
+                                                     RT, fin);
 }
 
 // Streaming variant: applicable when a whole row block's column blocks fit one XCD at one

@@ -39,7 +39,7 @@ btc_status gemv_generic(hipStream_t q, const Dims& d, const uint32_t* packed, co
 bool gemm_tiled_covers(const Dims& d, int M);
 btc_status gemm_tiled(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
                       const float* alpha, const float* mu, const void* X, int is_bf16, int M, void* Y, int y_dtype,
-                      void* workspace, size_t workspace_bytes);
+                      void* workspace, size_t workspace_bytes, int clear_workspace);
 size_t gemm_tiled_workspace_bytes(const Dims& d, int M);   // 0 unless the call is split along k
 double gemm_tiled_estimate_us(const Dims& d, int M);       // rough duration, for engine selection
 // Leading part of a btc_gemv workspace that must stay zero between calls (the table engine's slots).

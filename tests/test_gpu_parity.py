@@ -156,6 +156,7 @@ def test_gemv_calls_share_one_workspace(G, oracle):
         y = G.GuardedOutput(batch, out, torch.float16)
         B.btc_gemv(dl.shape, dl.packed, dl.codebook, dl.alpha, dl.mu, G.dev(x), batch, y.payload, B.BTC_F16, ws)
         y.check_guards()
+        assert int(ws.count_nonzero()) == 0, "btc_gemv did not hand the workspace back zero-filled"
         rows = np.unique(np.concatenate([[0, out - 1], rng.choice(out, size=min(256, out), replace=False)]))
         y_ref = oracle.linear(dl.packed_host, dl.codebook_host, layer.alpha, layer.mu, x, n_in, v, K, rows=rows)
         G.assert_close(y.numpy()[:, rows], y_ref, f"shared workspace {out}x{n_in} batch {batch}")
