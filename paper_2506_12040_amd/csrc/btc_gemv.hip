@@ -43,8 +43,10 @@ btc_status btc_gemv(void* stream, const btc_shape* s, const uint32_t* packed, co
   }
   // Small matrices are bound by the chain of memory round trips: the register-resident engine has the
   // shortest one.  Larger ones are bound by LDS and ALU throughput, where the table engine is lighter
-  // (measured crossover: 4096 x 4096 at 0.7-0.9 bit is faster expanded, 5120 x 5120 is faster looked up).
-  const bool small = (long long)d.out * d.wpr * 4 < (2LL << 20) || !lut_engine_covers(d);
+  // Measured crossover: 4096 x 4096 (1.5-1.9 MB) is faster expanded; at 5120 x 5120 (2.3-2.6 MB) the two
+  // are within 0.5 us of each other -- expansion ahead on clustered (Zipf) indices, whose repeated table
+  // reads LDS serves as broadcasts, the table engine ahead on uniform ones; from 4 MB on the table engine.
+  const bool small = (long long)d.out * d.wpr * 4 < (3LL << 20) || !lut_engine_covers(d);
   if (small && expand_engine_covers(d)) {
     for (int m = 0; m < batch; ++m) {
       st = gemv_expand(q, d, packed, codebook, alpha, mu, (const char*)x + (size_t)m * d.in * 2,
