@@ -265,6 +265,63 @@ def main():
             us_per_call=round((time.perf_counter() - t0) * 1e6 / (10 * len(mats)), 2),
             note="independent calls (as q, k, v of one layer) replayed from one graph per stream; host-timed")
 
+        # The paper's own latency comparison: its MLP layer 8192 x 28672 against the dense fp16
+        # product of the stock PyTorch build, for M = batch x sequence length (Section 5.3).  Here: torch's
+        # fp16/bf16 matmul on this GPU (a library call, timed the same way: cold, rotating copies).
+        def time_dense(out_, in_, M, dt):
+            ncopies = 3                                    # 3 x 470 MB: more than the last-level cache holds
+            Ws = [torch.randn(out_, in_, device=dev, dtype=dt) for _ in range(ncopies)]
+            xd = torch.randn(M, in_, device=dev, dtype=dt)
+            for w in Ws:
+                torch.matmul(xd, w.t())
+            torch.cuda.synchronize()
+            reps = 8 if M <= 16 else 2
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                for w in Ws:
+                    torch.matmul(xd, w.t())
+            e1.record()
+            torch.cuda.synchronize()
+            del Ws
+            return e0.elapsed_time(e1) * 1e3 / (reps * ncopies)
+
+        def time_gemm(out_, in_, v_, K_, M):
+            s2 = B.btc_shape_init(out_, in_, v_, K_)
+            pk = torch.randint(0, 2**31 - 1, (out_, s2.words_per_row), dtype=torch.int32, device=dev)
+            cb2 = torch.randint(0, 1 << v_, (1 << s2.b,), dtype=torch.int32, device=dev)
+            al2 = torch.rand(out_, device=dev) * 0.02
+            mu2 = torch.rand(out_, device=dev) * 0.002
+            X2 = torch.randn(M, in_, device=dev).bfloat16()
+            Y2 = torch.empty(M, out_, dtype=torch.bfloat16, device=dev)
+            ws2 = torch.zeros(B.btc_workspace_bytes(s2, M, True), dtype=torch.uint8, device=dev)
+            f = lambda: B.btc_gemm(s2, pk, cb2, al2, mu2, X2, B.BTC_BF16, M, Y2, B.BTC_BF16, ws2)
+            f()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(4):
+                f()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) * 1e3 / 4
+
+        mlp = {}
+        o_, i_ = 8192, 28672
+        for M in (1, 16):
+            dense_us = time_dense(o_, i_, M, torch.float16)
+            row = {"torch_fp16_us": round(dense_us, 1)}
+            for (v_, K_, tag) in [(10, 512, "0.9 bit"), (10, 256, "0.8 bit"), (10, 128, "0.7 bit")]:
+                us = time_gemv(o_, i_, v_, K_, M, reps_target=40)["us_per_call"]
+                row[tag] = dict(us=us, speedup_over_fp16=round(dense_us / us, 2))
+            mlp[f"M{M}"] = row
+        dense_us = time_dense(o_, i_, 2048, torch.bfloat16)
+        us = time_gemm(o_, i_, 10, 256, 2048)
+        mlp["M2048"] = {"torch_bf16_us": round(dense_us, 1),
+                        "0.8 bit": dict(us=round(us, 1), speedup_over_bf16=round(dense_us / us, 2),
+                                        tflops=round(2.0 * 2048 * o_ * i_ / us / 1e6, 1))}
+        other["mlp_8192x28672_vs_dense_torch"] = mlp
+
     # ---- prefill GEMM on the same shapes (btc_gemm = one contraction kernel per call, plus a second pass when the call is split along k)
     gemm = None
     if not args.no_gemm:

@@ -62,7 +62,10 @@ size_t btc_workspace_bytes(const btc_shape* s, int32_t rows, int is_gemm) {
     // the table engine's slots (zero between calls), then the partial sums of a batched call
     // that goes to the tiled contraction kernel and is split along k
     need = btc::gemv_table_region_bytes(d);
-    if (rows > 1 && btc::gemm_tiled_covers(d, rows)) need += btc::gemm_tiled_workspace_bytes(d, rows);
+    size_t extra = 0;
+    if (rows > 1 && btc::gemm_tiled_covers(d, rows)) extra = btc::gemm_tiled_workspace_bytes(d, rows);
+    if (btc::gemv_mfma_covers(d, rows)) extra = std::max(extra, btc::gemv_mfma_workspace_bytes(d, rows));
+    need += extra;
   }
   return (need + 255) & ~(size_t)255;
 }

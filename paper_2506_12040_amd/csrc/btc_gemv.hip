@@ -25,6 +25,15 @@ btc_status btc_gemv(void* stream, const btc_shape* s, const uint32_t* packed, co
   const Dims d = dims_of(*s);
   const int y_is_f32 = y_dtype == BTC_F32;
   const size_t ysz = y_is_f32 ? 4 : 2;
+  // A few activation rows on a supported setting: one pass of the matrix-core engine serves them all
+  // (unless the matrix is so small that a pass per row is still quicker).
+  if (gemv_mfma_covers(d, batch) && batch * row_pass_us(d) > gemv_mfma_estimate_us(d)) {
+    const size_t off = gemv_table_region_bytes(d);
+    const size_t need = gemv_mfma_workspace_bytes(d, batch);
+    if (!workspace || workspace_bytes < off + need) return BTC_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return BTC_ERR_ALIGN;
+    return gemv_mfma(q, d, packed, codebook, alpha, mu, x, batch, y, y_is_f32, (char*)workspace + off);
+  }
   // Several activation rows: decoding the indices is the cost, and the matrix cores take up to 32
   // rows for the price of one, so the call goes to the tiled contraction kernel (each index is
   // decoded once for the whole batch) instead of one decode pass per row.

@@ -1,0 +1,451 @@
+// Decode product for a few activation rows at once (btc_gemv with 2..16 rows), chunk length 10.
+//
+// With several activation rows the cost of a call is the decoding of the indices, which does
+// not depend on the number of rows, so all rows are served by one pass over the index stream.
+// The +-1 patterns go straight from a table in LDS into the A operand of the matrix cores
+// (MFMA 16x16x32, fp16 in, fp32 accumulate): 16 weight rows x 32 contraction positions per
+// instruction, the activation rows (padded to 16) are the B operand.  Nothing is written back to
+// LDS and no lane expands a pattern with ALU work: a table entry IS the operand.
+//
+// The contraction index inside one MFMA may be permuted freely as long as both operands use
+// the same permutation.  A chunk has 10 values, an operand register group 8, so the chunks of
+// a "super-group" of 64 consecutive chunks are dealt out as follows.  Lane (i, q) -- weight
+// row i = lane % 16, group q = lane / 16 -- owns the 16 chunks 16 q .. 16 q + 15 of the
+// super-group.  MFMA u (u = 0..15) contracts values 0..7 of chunk 16 q + u in group q; tail
+// MFMA t (t = 0..3) contracts values 8 and 9 of the chunks 16 q + 4 t .. + 3.  20 MFMAs cover the
+// 640 columns without padding.  A lane therefore needs, per chunk, one 16-byte table read
+// (values 0..7) and one 4-byte read (values 8, 9), and its 16 indices are one contiguous
+// piece of 16 b bits of the row's stream: one 16-byte load (plus one word for b > 8).
+//
+// Tables: the 16-byte entries are replicated (16 copies for b <= 8) so that the 16 lanes that
+// the LDS serves together read from 16 different bank groups whatever their indices are.
+// Activations: staged once per workgroup in operand order, X8[chunk][row] (16 bytes, the row
+// position rotated by the chunk number so that both the staging writes and the operand reads
+// spread over the banks) and X2[chunk][row] (4 bytes).
+//
+// Work split: a workgroup owns 128 R weight rows (8 waves x R blocks of 16) and up to 4
+// super-groups of columns; the column tiles of a row leave fp32 partial sums in the workspace
+// and a second, small kernel adds them, applies alpha and mu (Algorithm "Binary Transformation
+// and Compression": W_hat = alpha * B_hat + mu) and clears what it has read.
+#include <hip/hip_fp16.h>
+
+#include <type_traits>
+#include <utility>
+
+#include "btc_internal.h"
+
+namespace btc {
+namespace skinny {
+
+// f(integral_constant<int, I>) for I = Begin .. End - 1, fully unrolled
+template <int Begin, int End, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (Begin < End) {
+    f(std::integral_constant<int, Begin>{});
+    static_for<Begin + 1, End>(f);
+  }
+}
+
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+constexpr int kV = 10;                  // chunk length this kernel is built for
+constexpr int kWaves = 8;
+constexpr int kSG = 64;                 // chunks per super-group
+constexpr int kMaxSG = 6;               // super-groups of activations a workgroup stages
+constexpr int kAhead = 3;               // index words are requested this many super-groups ahead of their use
+constexpr int kReduceCols = 256;        // outputs per block of the second pass
+constexpr uint32_t kOob = 0x80000000u;  // buffer offset that is always out of range
+constexpr int kRsrcFlags = 0x00020000;
+
+template <int B>
+struct Cfg {
+  static constexpr int kNW = B <= 8 ? 4 : 5;                              // index words per lane and super-group
+  static constexpr int kK2 = 1 << B;
+  static constexpr int kRep = (2048 >> B) > 16 ? 16 : (2048 >> B);        // copies of a 16-byte entry
+  static constexpr int kE8Bytes = kK2 * kRep * 16;                        // <= 32 KB
+  static constexpr int kT2Bytes = kK2 * 4;
+};
+
+constexpr int lds_bytes(int e8, int t2, int nsg) { return e8 + t2 + nsg * kSG * (256 + 64); }
+
+// position (in words) of the 4-byte tail of (chunk c, activation row j): inside a block of 4 chunks
+// (64 words = every bank once) the 16-word slot of a chunk is rotated by c / 16, so that the four
+// lane groups of a wave, whose chunks are 16 apart, read from different banks.
+__device__ __forceinline__ int x2_word(int c, int j) { return (c >> 2) * 64 + (((c & 3) + (c >> 4)) & 3) * 16 + j; }
+
+__device__ __forceinline__ float pair_sum(uint32_t w, float acc) {
+  const f16x2 one = {(_Float16)1.0f, (_Float16)1.0f};
+  return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, w), one, acc, false);
+}
+
+__device__ __forceinline__ f32x4 mfma16(const uint4& a, const uint4& b, const f32x4& c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+
+template <int B, int R>
+__global__ __launch_bounds__(kWaves * 64) void gemv_mfma_kernel(
+    Dims d, const uint32_t* __restrict__ packed, const uint32_t* __restrict__ codebook,
+    const uint16_t* __restrict__ x, int batch, int n_ct, int nsg, int n_rb, float* __restrict__ part,
+    float* __restrict__ xpart) {
+  using C = Cfg<B>;
+  constexpr int NW = C::kNW;
+  extern __shared__ __align__(16) unsigned char smem[];
+  unsigned char* E8 = smem;                                      // [code][copy] x 16 B: values 0..7 as +-1 fp16
+  uint32_t* T2 = (uint32_t*)(smem + C::kE8Bytes);                // [code]: values 8, 9
+  unsigned char* X8 = smem + C::kE8Bytes + C::kT2Bytes;          // [chunk][16 rows] x 16 B
+  uint32_t* X2 = (uint32_t*)(X8 + nsg * kSG * 256);              // [chunk][16 rows] x 4 B
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int i = lane & 15, q = lane >> 4;
+  const int ct = blockIdx.x % n_ct, rt = blockIdx.x / n_ct;
+  const int sgs = (d.nchunks + kSG - 1) / kSG;
+  const int my_nsg = min(nsg, sgs - ct * nsg);                   // >= 1: the host sizes n_ct so
+  const int c0 = ct * nsg * kSG;                                 // first chunk of this column tile
+  const int row_base = (rt * kWaves + wave) * (R * 16);
+
+  // ---- every global load of the prologue is issued before anything waits: codebook, this
+  // tile's activations, then the index words super-group by super-group.  Loads return in
+  // order, so the tables can be built and the activations staged while the index words are
+  // still arriving, and the contraction of a super-group starts as soon as its words are
+  // there while the later ones stream in.
+  constexpr int NC = (C::kK2 + kWaves * 64 - 1) / (kWaves * 64);
+  uint32_t cw[NC];
+#pragma unroll
+  for (int k = 0; k < NC; ++k) {
+    const int code = tid + k * kWaves * 64;
+    cw[k] = code < C::kK2 ? codebook[code] : 0u;
+  }
+  // activations: wave w stages rows w and w + 8, a lane takes 16-byte pieces of a row
+  constexpr int NS = (kMaxSG * (kSG * kV / 8) + 63) / 64;        // pieces per lane and row
+  const int nseg = my_nsg * (kSG * kV / 8);
+  const int k0 = c0 * kV;
+  uint4 xv[2][NS];
+  {
+    const __amdgpu_buffer_rsrc_t rX =
+        __builtin_amdgcn_make_buffer_rsrc((void*)x, 0, (int)((long long)batch * d.in * 2), kRsrcFlags);
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj) {
+      const int j = wave + jj * kWaves;
+      const uint32_t rowoff = (uint32_t)j * (uint32_t)d.in * 2u;
+#pragma unroll
+      for (int m = 0; m < NS; ++m) {
+        const int seg = lane + 64 * m;
+        const int k = k0 + 8 * seg;
+        const uint32_t off = (j < batch && seg < nseg && k < d.in) ? rowoff + (uint32_t)k * 2u : kOob;
+        xv[jj][m] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rX, off, 0, 0));
+      }
+    }
+  }
+  const __amdgpu_buffer_rsrc_t rP =
+      __builtin_amdgcn_make_buffer_rsrc((void*)packed, 0, (int)((uint32_t)d.out * (uint32_t)d.wpr * 4u), kRsrcFlags);
+  uint32_t W[kMaxSG][R][NW];
+  auto load_words = [&](auto sg_c) {
+    constexpr int sg = decltype(sg_c)::value;
+    const int cs = c0 + sg * kSG;
+    const int w0 = ((cs + 16 * q) * B) >> 5;
+    // does every lane's window of NW words lie inside its row?  (uniform; false only in the last
+    // super-group of a row, where words are fetched one by one and those past the row read as zero)
+    const bool inside = (((cs + kSG) * B + 31) >> 5) <= d.wpr;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int n = row_base + r * 16 + i;
+      const bool row_ok = sg < my_nsg && n < d.out;
+      if (inside) {
+        const uint32_t off = row_ok ? ((uint32_t)n * (uint32_t)d.wpr + (uint32_t)w0) * 4u : kOob;
+        const uint4 v = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rP, off, 0, 0));
+        W[sg][r][0] = v.x; W[sg][r][1] = v.y; W[sg][r][2] = v.z; W[sg][r][3] = v.w;
+        if constexpr (NW == 5) W[sg][r][4] = __builtin_amdgcn_raw_buffer_load_b32(rP, off + 16u, 0, 0);
+      } else {
+#pragma unroll
+        for (int k = 0; k < NW; ++k) {
+          const uint32_t off =
+              (row_ok && w0 + k < d.wpr) ? ((uint32_t)n * (uint32_t)d.wpr + (uint32_t)(w0 + k)) * 4u : kOob;
+          W[sg][r][k] = __builtin_amdgcn_raw_buffer_load_b32(rP, off, 0, 0);
+        }
+      }
+    }
+  };
+  static_for<0, kAhead>([&](auto sg_c) { load_words(sg_c); });
+
+  // ---- pattern tables: a thread writes all copies of its entries
+#pragma unroll
+  for (int k = 0; k < NC; ++k) {
+    const int code = tid + k * kWaves * 64;
+    if (code < C::kK2) {
+      const uint32_t npat = ~cw[k];
+      uint32_t p[5];
+#pragma unroll
+      for (int m = 0; m < 5; ++m)
+        p[m] = 0x3C003C00u | ((npat << (15 - 2 * m)) & 0x8000u) | ((npat << (30 - 2 * m)) & 0x80000000u);
+#pragma unroll
+      for (int c = 0; c < C::kRep; ++c) *(uint4*)(E8 + (code * C::kRep + c) * 16) = make_uint4(p[0], p[1], p[2], p[3]);
+      T2[code] = p[4];
+    }
+  }
+
+  // ---- activations into operand order.  Columns past the end of a row are staged as zeros,
+  // which is what makes the padding of the last chunk and the chunks past the end of the row
+  // contribute nothing (a piece that straddles the end of its row is masked pair by pair; rows
+  // have an even number of columns here).
+  {
+    auto put = [&](int j, int p, uint32_t w) {                   // pair p of the tile (values 2p, 2p+1) of row j
+      const int c = (int)(((uint32_t)p * 52429u) >> 18);         // p / 5 for p < 2^16
+      const int s = p - 5 * c;
+      if (k0 + 2 * p >= d.in) w = 0u;
+      if (s < 4) ((uint32_t*)X8)[(c * 16 + ((j + c) & 15)) * 4 + s] = w;
+      else X2[x2_word(c, j)] = w;
+    };
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj) {
+      const int j = wave + jj * kWaves;
+#pragma unroll
+      for (int m = 0; m < NS; ++m) {
+        const int seg = lane + 64 * m;
+        if (j < batch && seg < nseg) {
+          put(j, 4 * seg + 0, xv[jj][m].x); put(j, 4 * seg + 1, xv[jj][m].y);
+          put(j, 4 * seg + 2, xv[jj][m].z); put(j, 4 * seg + 3, xv[jj][m].w);
+        }
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- sums of the activation rows over this column tile (for the mu term), once per tile:
+  // the workgroups of the first row tile leave one copy per block of the second pass
+  if (rt == 0) {
+    for (int j = wave; j < batch; j += kWaves) {
+      float s = 0.f;
+      for (int c = lane; c < my_nsg * kSG; c += 64) {
+        const uint4 v = *(const uint4*)(X8 + (c * 16 + ((j + c) & 15)) * 16);
+        s = pair_sum(v.x, s); s = pair_sum(v.y, s); s = pair_sum(v.z, s); s = pair_sum(v.w, s);
+        s = pair_sum(X2[x2_word(c, j)], s);
+      }
+#pragma unroll
+      for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
+      if (lane < n_rb) xpart[((size_t)lane * n_ct + ct) * 16 + j] = s;
+      for (int nb = 64 + lane; nb < n_rb; nb += 64) xpart[((size_t)nb * n_ct + ct) * 16 + j] = s;
+    }
+  }
+
+  // ---- contraction
+  f32x4 acc[R][2];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    acc[r][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+    acc[r][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  const uint32_t shift = (uint32_t)(16 * q * B) & 31u;           // where the lane's first index starts in its window
+  const unsigned char* e8_lane = E8 + (i & (C::kRep - 1)) * 16;
+  static_for<0, kMaxSG>([&](auto sg_c) {
+    constexpr int sg = decltype(sg_c)::value;
+    if constexpr (sg + kAhead < kMaxSG) {
+      if (sg + kAhead < my_nsg) load_words(std::integral_constant<int, sg + kAhead>{});
+    }
+    if (sg < my_nsg) {
+      // the lane's 16 indices, aligned to bit 0 of Wn
+      uint32_t Wn[R][NW];
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+#pragma unroll
+        for (int k = 0; k + 1 < NW; ++k) Wn[r][k] = __builtin_amdgcn_alignbit(W[sg][r][k + 1], W[sg][r][k], shift);
+        Wn[r][NW - 1] = W[sg][r][NW - 1] >> shift;
+      }
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        uint4 b8[4], b2;
+        uint32_t b2w[4];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          const int cl = sg * kSG + 16 * q + 4 * t + w;          // chunk number inside the tile
+          b8[w] = *(const uint4*)(X8 + (cl * 16 + ((i + 4 * t + w) & 15)) * 16);
+          b2w[w] = X2[x2_word(cl, i)];
+        }
+        b2 = make_uint4(b2w[0], b2w[1], b2w[2], b2w[3]);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+          uint4 a8[4];
+          uint32_t a2w[4];
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            constexpr uint32_t mask = (1u << B) - 1u;
+            const int pos = (4 * t + w) * B;                     // compile-time after unrolling
+            const int wi = pos >> 5, sh = pos & 31;
+            uint32_t code;
+            if (sh + B <= 32) code = (Wn[r][wi] >> sh) & mask;
+            else code = __builtin_amdgcn_alignbit(Wn[r][wi + 1 < NW ? wi + 1 : wi], Wn[r][wi], (uint32_t)sh) & mask;
+            a8[w] = *(const uint4*)(e8_lane + code * (C::kRep * 16));
+            a2w[w] = T2[code];
+          }
+          acc[r][0] = mfma16(a8[0], b8[0], acc[r][0]);
+          acc[r][1] = mfma16(a8[1], b8[1], acc[r][1]);
+          acc[r][0] = mfma16(a8[2], b8[2], acc[r][0]);
+          acc[r][1] = mfma16(a8[3], b8[3], acc[r][1]);
+          acc[r][0] = mfma16(make_uint4(a2w[0], a2w[1], a2w[2], a2w[3]), b2, acc[r][0]);
+        }
+      }
+    }
+  });
+
+  // ---- partial sums: lane (j, q) holds the weight rows 4 q .. 4 q + 3 of each block for activation row j
+  if (i < batch) {
+    float* dst = part + ((size_t)ct * batch + i) * d.out;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int n = row_base + r * 16 + 4 * q;
+      const f32x4 v = acc[r][0] + acc[r][1];
+      if ((d.out & 3) == 0) {
+        if (n < d.out) *(float4*)(dst + n) = make_float4(v[0], v[1], v[2], v[3]);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (n + e < d.out) dst[n + e] = v[e];
+      }
+    }
+  }
+}
+
+// Second pass: y[j][n] = alpha[n] * (sum of the column tiles' partial sums) + mu[n] * (sum of row j).
+// A block owns kReduceCols outputs of one activation row and its own copies of the row sums, so
+// it can clear what it has read without a race.
+__global__ __launch_bounds__(64) void skinny_reduce_kernel(const float* __restrict__ alpha, const float* __restrict__ mu,
+                                                            float* __restrict__ part, float* __restrict__ xpart, int out,
+                                                            int batch, int n_ct, void* __restrict__ y, int y_is_f32) {
+  const int nb = blockIdx.x, j = blockIdx.y, tid = threadIdx.x;
+  float xs = 0.f;
+  for (int ct = 0; ct < n_ct; ++ct) xs += xpart[((size_t)nb * n_ct + ct) * 16 + j];
+  const int n_end = min(out, (nb + 1) * kReduceCols);
+  const size_t yrow = (size_t)j * out;
+  if ((out & 3) == 0) {
+    const int n = nb * kReduceCols + 4 * tid;
+    if (n < n_end) {
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 4
+      for (int ct = 0; ct < n_ct; ++ct) {
+        float4* p = (float4*)(part + ((size_t)ct * batch + j) * out + n);
+        const float4 t = *p;
+        v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
+        *p = make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+      const float4 al = *(const float4*)(alpha + n), mn = *(const float4*)(mu + n);
+      const float r0 = al.x * v.x + mn.x * xs, r1 = al.y * v.y + mn.y * xs, r2 = al.z * v.z + mn.z * xs,
+                  r3 = al.w * v.w + mn.w * xs;
+      if (y_is_f32) {
+        *(float4*)((float*)y + yrow + n) = make_float4(r0, r1, r2, r3);
+      } else {
+        const __half2 h0 = __floats2half2_rn(r0, r1), h1 = __floats2half2_rn(r2, r3);
+        *(uint2*)((uint16_t*)y + yrow + n) =
+            make_uint2(__builtin_bit_cast(uint32_t, h0), __builtin_bit_cast(uint32_t, h1));
+      }
+    }
+  } else {
+    for (int n = nb * kReduceCols + tid; n < n_end; n += 64) {
+      float v = 0.f;
+      for (int ct = 0; ct < n_ct; ++ct) {
+        float* p = part + ((size_t)ct * batch + j) * out + n;
+        v += *p;
+        *p = 0.f;
+      }
+      const float r = alpha[n] * v + mu[n] * xs;
+      if (y_is_f32) ((float*)y)[yrow + n] = r;
+      else ((__half*)y)[yrow + n] = __float2half_rn(r);
+    }
+  }
+  __syncthreads();   // every thread has read the row sums
+  for (int ct = tid; ct < n_ct; ct += 64) xpart[((size_t)nb * n_ct + ct) * 16 + j] = 0.f;
+}
+
+struct Plan {
+  int R;        // blocks of 16 weight rows per wave
+  int nsg;      // super-groups per column tile
+  int n_ct;     // column tiles
+  int n_rt;     // row tiles
+  double est_us;
+};
+
+// Tile shape: the kernel lasts about rounds x (fixed + R nsg unit), one workgroup per compute unit;
+// fixed = tables and staging, unit = one block of 16 rows x 64 chunks on each of the 8 waves.
+static Plan make_plan(const Dims& d) {
+  const int sgs = (d.nchunks + kSG - 1) / kSG;
+  Plan best{0, 0, 0, 0, 1e30};
+  for (int R = 1; R <= 2; R *= 2)
+    for (int nsg = 1; nsg <= kMaxSG; ++nsg) {
+      const int n_ct = (sgs + nsg - 1) / nsg;
+      const int n_rt = (d.out + kWaves * R * 16 - 1) / (kWaves * R * 16);
+      const double rounds = (double)(((long long)n_ct * n_rt + 255) / 256);
+      const double t = rounds * (2.0 + 0.9 * R * nsg) + 0.15 * n_ct;   // + the second pass reading n_ct partial sums
+      if (t < best.est_us) best = Plan{R, nsg, n_ct, n_rt, t};
+    }
+  best.est_us += 6.0;   // two launches
+  return best;
+}
+
+template <int B, int R>
+static btc_status launch2(hipStream_t q, const Dims& d, const Plan& pl, const uint32_t* packed, const uint32_t* codebook,
+                          const void* x, int batch, float* part, float* xpart, int n_rb) {
+  using C = Cfg<B>;
+  static_assert(lds_bytes(C::kE8Bytes, C::kT2Bytes, kMaxSG) <= 160 * 1024 - 64, "LDS budget");
+  static bool attr_set = false;  // one-time kernel attribute, not call state
+  if (!attr_set) {
+    if (hipFuncSetAttribute((const void*)gemv_mfma_kernel<B, R>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            lds_bytes(C::kE8Bytes, C::kT2Bytes, kMaxSG)) != hipSuccess)
+      return BTC_ERR_HIP;
+    attr_set = true;
+  }
+  gemv_mfma_kernel<B, R><<<pl.n_ct * pl.n_rt, kWaves * 64, lds_bytes(C::kE8Bytes, C::kT2Bytes, pl.nsg), q>>>(
+      d, packed, codebook, (const uint16_t*)x, batch, pl.n_ct, pl.nsg, n_rb, part, xpart);
+  return launch_status();
+}
+
+template <int B>
+static btc_status launch1(hipStream_t q, const Dims& d, const Plan& pl, const uint32_t* packed, const uint32_t* codebook,
+                          const void* x, int batch, float* part, float* xpart, int n_rb) {
+  switch (pl.R) {
+    case 1: return launch2<B, 1>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb);
+    default: return launch2<B, 2>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb);
+  }
+}
+
+}  // namespace skinny
+
+bool gemv_mfma_covers(const Dims& d, int batch) {
+  return batch >= 2 && batch <= 16 && d.v == skinny::kV && d.b >= 7 && d.b <= 10 && (d.in & 1) == 0 &&
+         (long long)d.out * d.wpr * 4 < (1LL << 31) && (long long)batch * d.in * 2 < (1LL << 31);
+}
+
+static size_t xpart_bytes(const Dims& d, const skinny::Plan& pl) {
+  const int n_rb = (d.out + skinny::kReduceCols - 1) / skinny::kReduceCols;
+  return (size_t)n_rb * pl.n_ct * 16 * sizeof(float);
+}
+
+size_t gemv_mfma_workspace_bytes(const Dims& d, int batch) {
+  const skinny::Plan pl = skinny::make_plan(d);
+  return xpart_bytes(d, pl) + (size_t)pl.n_ct * batch * d.out * sizeof(float);
+}
+
+// Measured: about 11 us of launches, prologue and second pass plus 1 us per MB of index stream.
+double gemv_mfma_estimate_us(const Dims& d) { return 11.0 + 1.0e-6 * (double)d.out * d.wpr * 4; }
+
+btc_status gemv_mfma(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook, const float* alpha,
+                     const float* mu, const void* x, int batch, void* y, int y_is_f32, void* workspace) {
+  using namespace skinny;
+  const Plan pl = make_plan(d);
+  const int n_rb = (d.out + kReduceCols - 1) / kReduceCols;
+  float* xpart = (float*)workspace;
+  float* part = (float*)((char*)workspace + xpart_bytes(d, pl));
+  btc_status st;
+  switch (d.b) {
+    case 7: st = launch1<7>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb); break;
+    case 8: st = launch1<8>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb); break;
+    case 9: st = launch1<9>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb); break;
+    case 10: st = launch1<10>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb); break;
+    default: return BTC_ERR_UNSUPPORTED;
+  }
+  if (st != BTC_OK) return st;
+  skinny_reduce_kernel<<<dim3(n_rb, batch), 64, 0, q>>>(alpha, mu, part, xpart, d.out, batch, pl.n_ct, y, y_is_f32);
+  return launch_status();
+}
+
+}  // namespace btc

@@ -79,6 +79,12 @@ GEMV_SMALL = [
     (50, 333, 4, 9, 1, "uniform"), (31, 260, 8, 85, 2, "uniform"), (20, 250, 20, 65536, 1, "uniform"),
     (9, 640, 32, 2, 1, "uniform"), (1, 10, 10, 512, 1, "uniform"), (5, 3, 10, 4, 1, "uniform"),
     (40, 330, 16, 7132, 4, "uniform"), (64, 96, 12, 777, 16, "uniform"),
+    # 2..16 rows on the matrix-core engine (v = 10, 7..10 index bits): every index width, rows that are
+    # not 16-byte aligned, ragged last chunk, out not a multiple of 4 / below one block of 16, several
+    # row and column tiles
+    (300, 4096, 10, 128, 2, "uniform"), (131, 6408, 10, 256, 7, "zipf"), (77, 2570, 10, 1024, 16, "uniform"),
+    (260, 1234, 10, 512, 3, "uniform"), (13, 648, 10, 256, 15, "uniform"), (1030, 10240, 10, 256, 4, "uniform"),
+    (523, 5128, 10, 100, 9, "uniform"),
 ]
 
 
