@@ -25,9 +25,16 @@ btc_status btc_gemv(void* stream, const btc_shape* s, const uint32_t* packed, co
   const Dims d = dims_of(*s);
   const int y_is_f32 = y_dtype == BTC_F32;
   const size_t ysz = y_is_f32 ? 4 : 2;
-  // A few activation rows on a supported setting: one pass of the matrix-core engine serves them all
-  // (unless the matrix is so small that a pass per row is still quicker).
-  if (gemv_mfma_covers(d, batch) && batch * row_pass_us(d) > gemv_mfma_estimate_us(d)) {
+  // Several activation rows on a supported setting: one pass of the matrix-core engine serves them all
+  // (unless the matrix is so small that a pass per row is still quicker).  A single row goes there
+  // too when the matrix is large and so wide that the table engine cannot use its streaming kernel
+  // (measured on 8192 x 28672: 22.7 against 29.9 us at 9 index bits, 23.2 against 38.8 us at 10).
+  bool use_mfma = false;
+  if (gemv_mfma_covers(d, batch)) {
+    if (batch == 1) use_mfma = d.b >= 9 && d.nchunks >= 2048 && (long long)d.out * d.wpr * 4 >= (16LL << 20);
+    else use_mfma = batch * row_pass_us(d) > gemv_mfma_estimate_us(d, batch);
+  }
+  if (use_mfma) {
     const size_t off = gemv_table_region_bytes(d);
     const size_t need = gemv_mfma_workspace_bytes(d, batch);
     if (!workspace || workspace_bytes < off + need) return BTC_ERR_WORKSPACE;

@@ -1,32 +1,37 @@
-// Decode product for a few activation rows at once (btc_gemv with 2..16 rows), chunk length 10.
+// Decode product on the matrix cores: btc_gemv for 2..16 activation rows (and for one row on
+// large, very wide matrices), chunk length 10, 7..10 index bits.
 //
 // With several activation rows the cost of a call is the decoding of the indices, which does
 // not depend on the number of rows, so all rows are served by one pass over the index stream.
-// The +-1 patterns go straight from a table in LDS into the A operand of the matrix cores
-// (MFMA 16x16x32, fp16 in, fp32 accumulate): 16 weight rows x 32 contraction positions per
-// instruction, the activation rows (padded to 16) are the B operand.  Nothing is written back to
-// LDS and no lane expands a pattern with ALU work: a table entry IS the operand.
+// The +-1 patterns go straight from a table in LDS into the A operand of MFMA 16x16x32 (fp16
+// in, fp32 accumulate): 16 weight rows x 32 contraction positions per instruction; the
+// activation rows (padded to 16) are the B operand.  Nothing is written back to LDS and no lane
+// expands a pattern with ALU work: a table entry IS the operand.
 //
 // The contraction index inside one MFMA may be permuted freely as long as both operands use
 // the same permutation.  A chunk has 10 values, an operand register group 8, so the chunks of
 // a "super-group" of 64 consecutive chunks are dealt out as follows.  Lane (i, q) -- weight
 // row i = lane % 16, group q = lane / 16 -- owns the 16 chunks 16 q .. 16 q + 15 of the
 // super-group.  MFMA u (u = 0..15) contracts values 0..7 of chunk 16 q + u in group q; tail
-// MFMA t (t = 0..3) contracts values 8 and 9 of the chunks 16 q + 4 t .. + 3.  20 MFMAs cover the
-// 640 columns without padding.  A lane therefore needs, per chunk, one 16-byte table read
-// (values 0..7) and one 4-byte read (values 8, 9), and its 16 indices are one contiguous
-// piece of 16 b bits of the row's stream: one 16-byte load (plus one word for b > 8).
+// MFMA t (t = 0..3) contracts values 8 and 9 of the chunks 16 q + 4 t .. + 3.  20 MFMAs cover
+// the 640 columns without padding.  Per chunk a lane needs one 16-byte table read: the entry
+// holds values 0..7 as +-1.0, and the signs of values 8 and 9 ride in the lowest mantissa bit
+// of values 0 and 1, from where two ALU operations turn them into a +-1.0 pair (a third clears
+// them, so the entry is exact when it is used).  A lane's 16 indices are one contiguous piece
+// of 16 b bits of its row's stream: one 16-byte load (plus one word for b > 8).
 //
-// Tables: the 16-byte entries are replicated (16 copies for b <= 8) so that the 16 lanes that
-// the LDS serves together read from 16 different bank groups whatever their indices are.
+// Tables: the entries are replicated (16 copies for b <= 8, 8 for b = 9, 4 for b = 10: 64 KB)
+// so that the 16 lanes that the LDS serves together read from different bank groups whatever
+// their indices are (always for b <= 8, mostly otherwise).
 // Activations: staged once per workgroup in operand order, X8[chunk][row] (16 bytes, the row
-// position rotated by the chunk number so that both the staging writes and the operand reads
+// position XORed with the chunk number so that both the staging writes and the operand reads
 // spread over the banks) and X2[chunk][row] (4 bytes).
 //
-// Work split: a workgroup owns 128 R weight rows (8 waves x R blocks of 16) and up to 4
-// super-groups of columns; the column tiles of a row leave fp32 partial sums in the workspace
-// and a second, small kernel adds them, applies alpha and mu (Algorithm "Binary Transformation
-// and Compression": W_hat = alpha * B_hat + mu) and clears what it has read.
+// Work split: a workgroup (16 waves) owns 256 R weight rows (R blocks of 16 per wave) and up
+// to 4 super-groups of columns; the index words of a super-group are requested while the
+// previous one is contracted.  The column tiles of a row leave fp32 partial sums in the
+// workspace and a second, small kernel adds them, applies alpha and mu (Algorithm "Binary
+// Transformation and Compression": W_hat = alpha * B_hat + mu) and clears what it has read.
 #include <hip/hip_fp16.h>
 
 #include <type_traits>
@@ -49,13 +54,14 @@ __device__ __forceinline__ void static_for(F&& f) {
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int kV = 10;                  // chunk length this kernel is built for
-constexpr int kWaves = 8;
+constexpr int kWaves = 16;               // 1024 threads: one workgroup per compute unit, 128 registers per lane
 constexpr int kSG = 64;                 // chunks per super-group
-constexpr int kMaxSG = 6;               // super-groups of activations a workgroup stages
-constexpr int kAhead = 3;               // index words are requested this many super-groups ahead of their use
 constexpr int kReduceCols = 256;        // outputs per block of the second pass
+constexpr int kMaxSG = 4;               // super-groups of activations a workgroup stages
+constexpr int kAhead = 1;               // index words are requested this many super-groups ahead of their use
 constexpr uint32_t kOob = 0x80000000u;  // buffer offset that is always out of range
 constexpr int kRsrcFlags = 0x00020000;
 
@@ -63,12 +69,11 @@ template <int B>
 struct Cfg {
   static constexpr int kNW = B <= 8 ? 4 : 5;                              // index words per lane and super-group
   static constexpr int kK2 = 1 << B;
-  static constexpr int kRep = (2048 >> B) > 16 ? 16 : (2048 >> B);        // copies of a 16-byte entry
-  static constexpr int kE8Bytes = kK2 * kRep * 16;                        // <= 32 KB
-  static constexpr int kT2Bytes = kK2 * 4;
+  static constexpr int kRep = (4096 >> B) > 16 ? 16 : (4096 >> B);        // copies of a 16-byte entry
+  static constexpr int kE8Bytes = kK2 * kRep * 16;                        // <= 64 KB
 };
 
-constexpr int lds_bytes(int e8, int t2, int nsg) { return e8 + t2 + nsg * kSG * (256 + 64); }
+constexpr int lds_bytes(int e8, int nsg) { return e8 + nsg * kSG * (256 + 64); }
 
 // position (in words) of the 4-byte tail of (chunk c, activation row j): inside a block of 4 chunks
 // (64 words = every bank once) the 16-word slot of a chunk is rotated by c / 16, so that the four
@@ -92,9 +97,8 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_mfma_kernel(
   using C = Cfg<B>;
   constexpr int NW = C::kNW;
   extern __shared__ __align__(16) unsigned char smem[];
-  unsigned char* E8 = smem;                                      // [code][copy] x 16 B: values 0..7 as +-1 fp16
-  uint32_t* T2 = (uint32_t*)(smem + C::kE8Bytes);                // [code]: values 8, 9
-  unsigned char* X8 = smem + C::kE8Bytes + C::kT2Bytes;          // [chunk][16 rows] x 16 B
+  unsigned char* E8 = smem;                                      // [code][copy] x 16 B: values 0..7 as +-1 fp16 (+ 2 flag bits)
+  unsigned char* X8 = smem + C::kE8Bytes;                        // [chunk][16 rows] x 16 B
   uint32_t* X2 = (uint32_t*)(X8 + nsg * kSG * 256);              // [chunk][16 rows] x 4 B
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -118,25 +122,21 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_mfma_kernel(
     const int code = tid + k * kWaves * 64;
     cw[k] = code < C::kK2 ? codebook[code] : 0u;
   }
-  // activations: wave w stages rows w and w + 8, a lane takes 16-byte pieces of a row
+  // activations: wave w stages row w, a lane takes 16-byte pieces of it
   constexpr int NS = (kMaxSG * (kSG * kV / 8) + 63) / 64;        // pieces per lane and row
   const int nseg = my_nsg * (kSG * kV / 8);
   const int k0 = c0 * kV;
-  uint4 xv[2][NS];
+  uint4 xv[NS];
   {
     const __amdgpu_buffer_rsrc_t rX =
         __builtin_amdgcn_make_buffer_rsrc((void*)x, 0, (int)((long long)batch * d.in * 2), kRsrcFlags);
+    const uint32_t rowoff = (uint32_t)wave * (uint32_t)d.in * 2u;
 #pragma unroll
-    for (int jj = 0; jj < 2; ++jj) {
-      const int j = wave + jj * kWaves;
-      const uint32_t rowoff = (uint32_t)j * (uint32_t)d.in * 2u;
-#pragma unroll
-      for (int m = 0; m < NS; ++m) {
-        const int seg = lane + 64 * m;
-        const int k = k0 + 8 * seg;
-        const uint32_t off = (j < batch && seg < nseg && k < d.in) ? rowoff + (uint32_t)k * 2u : kOob;
-        xv[jj][m] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rX, off, 0, 0));
-      }
+    for (int m = 0; m < NS; ++m) {
+      const int seg = lane + 64 * m;
+      const int k = k0 + 8 * seg;
+      const uint32_t off = (wave < batch && seg < nseg && k < d.in) ? rowoff + (uint32_t)k * 2u : kOob;
+      xv[m] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rX, off, 0, 0));
     }
   }
   const __amdgpu_buffer_rsrc_t rP =
@@ -168,7 +168,6 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_mfma_kernel(
       }
     }
   };
-  static_for<0, kAhead>([&](auto sg_c) { load_words(sg_c); });
 
   // ---- pattern tables: a thread writes all copies of its entries
 #pragma unroll
@@ -176,13 +175,15 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_mfma_kernel(
     const int code = tid + k * kWaves * 64;
     if (code < C::kK2) {
       const uint32_t npat = ~cw[k];
-      uint32_t p[5];
+      uint32_t p[4];
 #pragma unroll
-      for (int m = 0; m < 5; ++m)
+      for (int m = 0; m < 4; ++m)
         p[m] = 0x3C003C00u | ((npat << (15 - 2 * m)) & 0x8000u) | ((npat << (30 - 2 * m)) & 0x80000000u);
+      // the signs of values 8 and 9 ride in the lowest mantissa bit of values 0 and 1; the reader
+      // moves them into a +-1 pair of its own and clears them before the entry is used
+      p[0] |= ((npat >> 8) & 1u) | (((npat >> 9) & 1u) << 16);
 #pragma unroll
       for (int c = 0; c < C::kRep; ++c) *(uint4*)(E8 + (code * C::kRep + c) * 16) = make_uint4(p[0], p[1], p[2], p[3]);
-      T2[code] = p[4];
     }
   }
 
@@ -195,39 +196,34 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_mfma_kernel(
       const int c = (int)(((uint32_t)p * 52429u) >> 18);         // p / 5 for p < 2^16
       const int s = p - 5 * c;
       if (k0 + 2 * p >= d.in) w = 0u;
-      if (s < 4) ((uint32_t*)X8)[(c * 16 + ((j + c) & 15)) * 4 + s] = w;
+      if (s < 4) ((uint32_t*)X8)[(c * 16 + (j ^ (c & 15))) * 4 + s] = w;
       else X2[x2_word(c, j)] = w;
     };
 #pragma unroll
-    for (int jj = 0; jj < 2; ++jj) {
-      const int j = wave + jj * kWaves;
-#pragma unroll
-      for (int m = 0; m < NS; ++m) {
-        const int seg = lane + 64 * m;
-        if (j < batch && seg < nseg) {
-          put(j, 4 * seg + 0, xv[jj][m].x); put(j, 4 * seg + 1, xv[jj][m].y);
-          put(j, 4 * seg + 2, xv[jj][m].z); put(j, 4 * seg + 3, xv[jj][m].w);
-        }
+    for (int m = 0; m < NS; ++m) {
+      const int seg = lane + 64 * m;
+      if (wave < batch && seg < nseg) {
+        put(wave, 4 * seg + 0, xv[m].x); put(wave, 4 * seg + 1, xv[m].y);
+        put(wave, 4 * seg + 2, xv[m].z); put(wave, 4 * seg + 3, xv[m].w);
       }
     }
   }
+  static_for<0, kAhead>([&](auto sg_c) { load_words(sg_c); });
   __syncthreads();
 
   // ---- sums of the activation rows over this column tile (for the mu term), once per tile:
   // the workgroups of the first row tile leave one copy per block of the second pass
-  if (rt == 0) {
-    for (int j = wave; j < batch; j += kWaves) {
-      float s = 0.f;
-      for (int c = lane; c < my_nsg * kSG; c += 64) {
-        const uint4 v = *(const uint4*)(X8 + (c * 16 + ((j + c) & 15)) * 16);
-        s = pair_sum(v.x, s); s = pair_sum(v.y, s); s = pair_sum(v.z, s); s = pair_sum(v.w, s);
-        s = pair_sum(X2[x2_word(c, j)], s);
-      }
-#pragma unroll
-      for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
-      if (lane < n_rb) xpart[((size_t)lane * n_ct + ct) * 16 + j] = s;
-      for (int nb = 64 + lane; nb < n_rb; nb += 64) xpart[((size_t)nb * n_ct + ct) * 16 + j] = s;
+  if (rt == 0 && wave < batch) {
+    const int j = wave;
+    float s = 0.f;
+    for (int c = lane; c < my_nsg * kSG; c += 64) {
+      const uint4 v = *(const uint4*)(X8 + (c * 16 + (j ^ (c & 15))) * 16);
+      s = pair_sum(v.x, s); s = pair_sum(v.y, s); s = pair_sum(v.z, s); s = pair_sum(v.w, s);
+      s = pair_sum(X2[x2_word(c, j)], s);
     }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
+    for (int nb = lane; nb < n_rb; nb += 64) xpart[((size_t)nb * n_ct + ct) * 16 + j] = s;
   }
 
   // ---- contraction
@@ -238,7 +234,16 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_mfma_kernel(
     acc[r][1] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
   const uint32_t shift = (uint32_t)(16 * q * B) & 31u;           // where the lane's first index starts in its window
-  const unsigned char* e8_lane = E8 + (i & (C::kRep - 1)) * 16;
+  typedef __attribute__((address_space(3))) const u32x4* lds_u4;
+  const uint32_t e8_lane32 = (uint32_t)(uintptr_t)(lds_u4)(const u32x4*)(E8 + (i & (C::kRep - 1)) * 16);   // LDS address of the lane's copy of entry 0
+  // Lane-dependent parts of the operand addresses, so that the loops add constants only: chunk
+  // cl = 64 sg + 16 q + u sits at X8 + 256 cl + 16 (i ^ u) and at word x2_word(cl, i) of X2.
+  const uint32_t x8_lane = (uint32_t)(q * 4096 + i * 16);
+  const uint32_t* x2_lane[4];
+#pragma unroll
+  for (int w = 0; w < 4; ++w) x2_lane[w] = X2 + q * 256 + ((w + q) & 3) * 16 + i;
+  uint32_t one2;                                                 // 1.0 | 1.0 in a scalar register: an instruction takes one literal only
+  asm volatile("s_mov_b32 %0, 0x3c003c00" : "=s"(one2));
   static_for<0, kMaxSG>([&](auto sg_c) {
     constexpr int sg = decltype(sg_c)::value;
     if constexpr (sg + kAhead < kMaxSG) {
@@ -253,39 +258,55 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_mfma_kernel(
         for (int k = 0; k + 1 < NW; ++k) Wn[r][k] = __builtin_amdgcn_alignbit(W[sg][r][k + 1], W[sg][r][k], shift);
         Wn[r][NW - 1] = W[sg][r][NW - 1] >> shift;
       }
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
+      static_for<0, 4>([&](auto t_c) {
+        constexpr int t = decltype(t_c)::value;
         uint4 b8[4], b2;
         uint32_t b2w[4];
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          const int cl = sg * kSG + 16 * q + 4 * t + w;          // chunk number inside the tile
-          b8[w] = *(const uint4*)(X8 + (cl * 16 + ((i + 4 * t + w) & 15)) * 16);
-          b2w[w] = X2[x2_word(cl, i)];
-        }
+        static_for<0, 4>([&](auto w_c) {
+          constexpr int w = decltype(w_c)::value;
+          constexpr int u = 4 * t + w;
+          b8[w] = *(const uint4*)(X8 + ((x8_lane ^ (uint32_t)(u * 16)) + (uint32_t)((sg * kSG + u) * 256)));
+          b2w[w] = x2_lane[w][(16 * sg + t) * 64];
+        });
         b2 = make_uint4(b2w[0], b2w[1], b2w[2], b2w[3]);
+        // all table reads of this step first (R x 4 independent reads in flight), then the
+        // fix-ups, then the matrix instructions
+        uint4 a8[R][4];
+        uint32_t a2w[R][4];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-          uint4 a8[4];
-          uint32_t a2w[4];
+          static_for<0, 4>([&](auto w_c) {
+            constexpr int w = decltype(w_c)::value;
+            constexpr int pos = (4 * t + w) * B;
+            constexpr int wi = pos >> 5, sh = pos & 31;
+            uint32_t src = Wn[r][wi];
+            if constexpr (sh + B > 32) src = __builtin_amdgcn_alignbit(Wn[r][wi + 1 < NW ? wi + 1 : wi], Wn[r][wi], (uint32_t)sh);
+            // code = bits [sh, sh + B) of src; entry address = lane base + code * (copies * 16)
+            uint32_t code, addr;
+            asm("v_bfe_u32 %0, %1, %2, %3" : "=v"(code) : "v"(src), "n"(sh + B > 32 ? 0 : sh), "n"(B));
+            asm("v_lshl_add_u32 %0, %1, %2, %3" : "=v"(addr) : "v"(code), "n"(B <= 8 ? 8 : B == 9 ? 7 : 6), "v"(e8_lane32));
+            a8[r][w] = __builtin_bit_cast(uint4, *(lds_u4)(uintptr_t)addr);
+          });
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
 #pragma unroll
           for (int w = 0; w < 4; ++w) {
-            constexpr uint32_t mask = (1u << B) - 1u;
-            const int pos = (4 * t + w) * B;                     // compile-time after unrolling
-            const int wi = pos >> 5, sh = pos & 31;
-            uint32_t code;
-            if (sh + B <= 32) code = (Wn[r][wi] >> sh) & mask;
-            else code = __builtin_amdgcn_alignbit(Wn[r][wi + 1 < NW ? wi + 1 : wi], Wn[r][wi], (uint32_t)sh) & mask;
-            a8[w] = *(const uint4*)(e8_lane + code * (C::kRep * 16));
-            a2w[w] = T2[code];
+            uint32_t flags;
+            asm("v_and_b32 %0, 0x10001, %1" : "=v"(flags) : "v"(a8[r][w].x));
+            asm("v_lshl_or_b32 %0, %1, 15, %2" : "=v"(a2w[r][w]) : "v"(flags), "s"(one2));
+            a8[r][w].x &= 0xFFFEFFFEu;
           }
-          acc[r][0] = mfma16(a8[0], b8[0], acc[r][0]);
-          acc[r][1] = mfma16(a8[1], b8[1], acc[r][1]);
-          acc[r][0] = mfma16(a8[2], b8[2], acc[r][0]);
-          acc[r][1] = mfma16(a8[3], b8[3], acc[r][1]);
-          acc[r][0] = mfma16(make_uint4(a2w[0], a2w[1], a2w[2], a2w[3]), b2, acc[r][0]);
         }
-      }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+          acc[r][0] = mfma16(a8[r][0], b8[0], acc[r][0]);
+          acc[r][1] = mfma16(a8[r][1], b8[1], acc[r][1]);
+          acc[r][0] = mfma16(a8[r][2], b8[2], acc[r][0]);
+          acc[r][1] = mfma16(a8[r][3], b8[3], acc[r][1]);
+          acc[r][0] = mfma16(make_uint4(a2w[r][0], a2w[r][1], a2w[r][2], a2w[r][3]), b2, acc[r][0]);
+        }
+      });
     }
   });
 
@@ -309,27 +330,55 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_mfma_kernel(
 
 // Second pass: y[j][n] = alpha[n] * (sum of the column tiles' partial sums) + mu[n] * (sum of row j).
 // A block owns kReduceCols outputs of one activation row and its own copies of the row sums, so
-// it can clear what it has read without a race.
-__global__ __launch_bounds__(64) void skinny_reduce_kernel(const float* __restrict__ alpha, const float* __restrict__ mu,
+// it can clear what it has read without a race.  Its four waves share the column tiles (wave g
+// takes tiles g, g + 4, ...), each lane four consecutive outputs; wave 0 adds the four results.
+// (A finishing workgroup inside the first kernel instead of this pass was tried: partial sums
+// that cross XCDs inside one kernel need agent-scope accesses or cache write-backs, and both
+// cost more than the second launch.)
+__global__ __launch_bounds__(256) void skinny_reduce_kernel(const float* __restrict__ alpha, const float* __restrict__ mu,
                                                             float* __restrict__ part, float* __restrict__ xpart, int out,
                                                             int batch, int n_ct, void* __restrict__ y, int y_is_f32) {
-  const int nb = blockIdx.x, j = blockIdx.y, tid = threadIdx.x;
-  float xs = 0.f;
-  for (int ct = 0; ct < n_ct; ++ct) xs += xpart[((size_t)nb * n_ct + ct) * 16 + j];
+  __shared__ float4 red[3][64];
+  const int nb = blockIdx.x, j = blockIdx.y, tid = threadIdx.x, lane = tid & 63, g = tid >> 6;
   const int n_end = min(out, (nb + 1) * kReduceCols);
   const size_t yrow = (size_t)j * out;
+  float xs = 0.f;
+  if (g == 0) {                                      // the row sum: one tile per lane, then across the wave
+    for (int ct = lane; ct < n_ct; ct += 64) xs += xpart[((size_t)nb * n_ct + ct) * 16 + j];
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) xs += __shfl_xor(xs, o, 64);
+  }
   if ((out & 3) == 0) {
-    const int n = nb * kReduceCols + 4 * tid;
-    if (n < n_end) {
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll 4
-      for (int ct = 0; ct < n_ct; ++ct) {
-        float4* p = (float4*)(part + ((size_t)ct * batch + j) * out + n);
-        const float4 t = *p;
-        v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
-        *p = make_float4(0.f, 0.f, 0.f, 0.f);
+    const int n = nb * kReduceCols + 4 * lane;
+    const bool ok = n < n_end;
+    float4 al = make_float4(0.f, 0.f, 0.f, 0.f), mn = al, v = al;
+    if (ok && g == 0) {
+      al = *(const float4*)(alpha + n);
+      mn = *(const float4*)(mu + n);
+    }
+    if (ok) {
+      float4* p0 = (float4*)(part + (size_t)j * out + n);
+      const size_t step = (size_t)batch * out / 4;   // float4s between consecutive column tiles
+      for (int ct = g; ct < n_ct; ct += 16) {        // four tiles of this wave at a time: loads first, then clears
+        float4 t[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          t[u] = ct + 4 * u < n_ct ? p0[(size_t)(ct + 4 * u) * step] : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          v.x += t[u].x; v.y += t[u].y; v.z += t[u].z; v.w += t[u].w;
+          if (ct + 4 * u < n_ct) p0[(size_t)(ct + 4 * u) * step] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
       }
-      const float4 al = *(const float4*)(alpha + n), mn = *(const float4*)(mu + n);
+    }
+    if (g > 0) red[g - 1][lane] = v;
+    __syncthreads();
+    if (g == 0 && ok) {
+#pragma unroll
+      for (int u = 0; u < 3; ++u) {
+        const float4 t = red[u][lane];
+        v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
+      }
       const float r0 = al.x * v.x + mn.x * xs, r1 = al.y * v.y + mn.y * xs, r2 = al.z * v.z + mn.z * xs,
                   r3 = al.w * v.w + mn.w * xs;
       if (y_is_f32) {
@@ -341,20 +390,23 @@ __global__ __launch_bounds__(64) void skinny_reduce_kernel(const float* __restri
       }
     }
   } else {
-    for (int n = nb * kReduceCols + tid; n < n_end; n += 64) {
-      float v = 0.f;
-      for (int ct = 0; ct < n_ct; ++ct) {
-        float* p = part + ((size_t)ct * batch + j) * out + n;
-        v += *p;
-        *p = 0.f;
+    if (g == 0) {
+      for (int n = nb * kReduceCols + lane; n < n_end; n += 64) {
+        float v = 0.f;
+        for (int ct = 0; ct < n_ct; ++ct) {
+          float* p = part + ((size_t)ct * batch + j) * out + n;
+          v += *p;
+          *p = 0.f;
+        }
+        const float r = alpha[n] * v + mu[n] * xs;
+        if (y_is_f32) ((float*)y)[yrow + n] = r;
+        else ((__half*)y)[yrow + n] = __float2half_rn(r);
       }
-      const float r = alpha[n] * v + mu[n] * xs;
-      if (y_is_f32) ((float*)y)[yrow + n] = r;
-      else ((__half*)y)[yrow + n] = __float2half_rn(r);
     }
   }
-  __syncthreads();   // every thread has read the row sums
-  for (int ct = tid; ct < n_ct; ct += 64) xpart[((size_t)nb * n_ct + ct) * 16 + j] = 0.f;
+  // the row sums are read by wave 0 only, which clears them afterwards
+  if (g == 0)
+    for (int ct = lane; ct < n_ct; ct += 64) xpart[((size_t)nb * n_ct + ct) * 16 + j] = 0.f;
 }
 
 struct Plan {
@@ -378,7 +430,6 @@ static Plan make_plan(const Dims& d) {
       const double t = rounds * (2.0 + 0.9 * R * nsg) + 0.15 * n_ct;   // + the second pass reading n_ct partial sums
       if (t < best.est_us) best = Plan{R, nsg, n_ct, n_rt, t};
     }
-  best.est_us += 6.0;   // two launches
   return best;
 }
 
@@ -386,15 +437,15 @@ template <int B, int R>
 static btc_status launch2(hipStream_t q, const Dims& d, const Plan& pl, const uint32_t* packed, const uint32_t* codebook,
                           const void* x, int batch, float* part, float* xpart, int n_rb) {
   using C = Cfg<B>;
-  static_assert(lds_bytes(C::kE8Bytes, C::kT2Bytes, kMaxSG) <= 160 * 1024 - 64, "LDS budget");
+  static_assert(lds_bytes(C::kE8Bytes, kMaxSG) <= 160 * 1024 - 64, "LDS budget");
   static bool attr_set = false;  // one-time kernel attribute, not call state
   if (!attr_set) {
     if (hipFuncSetAttribute((const void*)gemv_mfma_kernel<B, R>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            lds_bytes(C::kE8Bytes, C::kT2Bytes, kMaxSG)) != hipSuccess)
+                            lds_bytes(C::kE8Bytes, kMaxSG)) != hipSuccess)
       return BTC_ERR_HIP;
     attr_set = true;
   }
-  gemv_mfma_kernel<B, R><<<pl.n_ct * pl.n_rt, kWaves * 64, lds_bytes(C::kE8Bytes, C::kT2Bytes, pl.nsg), q>>>(
+  gemv_mfma_kernel<B, R><<<pl.n_ct * pl.n_rt, kWaves * 64, lds_bytes(C::kE8Bytes, pl.nsg), q>>>(
       d, packed, codebook, (const uint16_t*)x, batch, pl.n_ct, pl.nsg, n_rb, part, xpart);
   return launch_status();
 }
@@ -411,10 +462,11 @@ static btc_status launch1(hipStream_t q, const Dims& d, const Plan& pl, const ui
 }  // namespace skinny
 
 bool gemv_mfma_covers(const Dims& d, int batch) {
-  return batch >= 2 && batch <= 16 && d.v == skinny::kV && d.b >= 7 && d.b <= 10 && (d.in & 1) == 0 &&
+  return batch >= 1 && batch <= 16 && d.v == skinny::kV && d.b >= 7 && d.b <= 10 && (d.in & 1) == 0 &&
          (long long)d.out * d.wpr * 4 < (1LL << 31) && (long long)batch * d.in * 2 < (1LL << 31);
 }
 
+// Workspace of a call: the row sums (one copy per block of the second pass), then the partial sums.
 static size_t xpart_bytes(const Dims& d, const skinny::Plan& pl) {
   const int n_rb = (d.out + skinny::kReduceCols - 1) / skinny::kReduceCols;
   return (size_t)n_rb * pl.n_ct * 16 * sizeof(float);
@@ -425,8 +477,12 @@ size_t gemv_mfma_workspace_bytes(const Dims& d, int batch) {
   return xpart_bytes(d, pl) + (size_t)pl.n_ct * batch * d.out * sizeof(float);
 }
 
-// Measured: about 11 us of launches, prologue and second pass plus 1 us per MB of index stream.
-double gemv_mfma_estimate_us(const Dims& d) { return 11.0 + 1.0e-6 * (double)d.out * d.wpr * 4; }
+// Fitted to measurements on 2 .. 26 MB matrices: launches, prologue and second pass, plus the
+// index stream, plus what grows with the number of activation rows (staging, partial sums).
+double gemv_mfma_estimate_us(const Dims& d, int batch) {
+  const double bytes = (double)d.out * d.wpr * 4;
+  return 8.4 + 0.47e-6 * bytes + batch / 16.0 * (1.8 + 0.13e-6 * bytes);
+}
 
 btc_status gemv_mfma(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook, const float* alpha,
                      const float* mu, const void* x, int batch, void* y, int y_is_f32, void* workspace) {
@@ -444,7 +500,7 @@ btc_status gemv_mfma(hipStream_t q, const Dims& d, const uint32_t* packed, const
     default: return BTC_ERR_UNSUPPORTED;
   }
   if (st != BTC_OK) return st;
-  skinny_reduce_kernel<<<dim3(n_rb, batch), 64, 0, q>>>(alpha, mu, part, xpart, d.out, batch, pl.n_ct, y, y_is_f32);
+  skinny_reduce_kernel<<<dim3(n_rb, batch), 256, 0, q>>>(alpha, mu, part, xpart, d.out, batch, pl.n_ct, y, y_is_f32);
   return launch_status();
 }
 

@@ -35,11 +35,11 @@ btc_status gemv_expand(hipStream_t q, const Dims& d, const uint32_t* packed, con
 btc_status gemv_generic(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
                         const float* alpha, const float* mu, const void* x, int batch, void* y, int y_is_f32);
 
-// Matrix-core engine for 2..16 activation rows (btc_gemv_mfma.hip): one pass over the index
+// Matrix-core engine for 1..16 activation rows (btc_gemv_mfma.hip): one pass over the index
 // stream for all rows, then a small second pass over partial sums parked in the workspace.
 bool gemv_mfma_covers(const Dims& d, int batch);
 size_t gemv_mfma_workspace_bytes(const Dims& d, int batch);
-double gemv_mfma_estimate_us(const Dims& d);       // rough duration, for engine selection
+double gemv_mfma_estimate_us(const Dims& d, int batch);   // rough duration, for engine selection
 btc_status gemv_mfma(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
                      const float* alpha, const float* mu, const void* x, int batch, void* y, int y_is_f32,
                      void* workspace);
