@@ -1,5 +1,6 @@
 // Decode product on the matrix cores: btc_gemv for 2..16 activation rows (and for one row on
-// large, very wide matrices), chunk length 10, 7..10 index bits.
+// large, very wide matrices), chunk lengths 10 and 9, 7..10 index bits.  (The text describes chunk
+// length 10; with 9 the second tail slot of a chunk is a zero in both operands.)
 //
 // With several activation rows the cost of a call is the decoding of the indices, which does
 // not depend on the number of rows, so all rows are served by one pass over the index stream.
@@ -56,7 +57,6 @@ typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
-constexpr int kV = 10;                  // chunk length this kernel is built for
 constexpr int kWaves = 16;               // 1024 threads: one workgroup per compute unit, 128 registers per lane
 constexpr int kSG = 64;                 // chunks per super-group
 constexpr int kReduceCols = 256;        // outputs per block of the second pass
@@ -89,7 +89,7 @@ __device__ __forceinline__ f32x4 mfma16(const uint4& a, const uint4& b, const f3
   return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
 }
 
-template <int B, int R>
+template <int V, int B, int R>
 __global__ __launch_bounds__(kWaves * 64) void gemv_mfma_kernel(
     Dims d, const uint32_t* __restrict__ packed, const uint32_t* __restrict__ codebook,
     const uint16_t* __restrict__ x, int batch, int n_ct, int nsg, int n_rb, float* __restrict__ part,
@@ -123,9 +123,10 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_mfma_kernel(
     cw[k] = code < C::kK2 ? codebook[code] : 0u;
   }
   // activations: wave w stages row w, a lane takes 16-byte pieces of it
-  constexpr int NS = (kMaxSG * (kSG * kV / 8) + 63) / 64;        // pieces per lane and row
-  const int nseg = my_nsg * (kSG * kV / 8);
-  const int k0 = c0 * kV;
+  static_assert(V == 9 || V == 10, "chunk lengths 9 (one tail value) and 10 (two)");
+  constexpr int NS = (kMaxSG * (kSG * V / 8) + 63) / 64;         // pieces per lane and row
+  const int nseg = my_nsg * (kSG * V / 8);
+  const int k0 = c0 * V;
   uint4 xv[NS];
   {
     const __amdgpu_buffer_rsrc_t rX =
@@ -181,7 +182,7 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_mfma_kernel(
         p[m] = 0x3C003C00u | ((npat << (15 - 2 * m)) & 0x8000u) | ((npat << (30 - 2 * m)) & 0x80000000u);
       // the signs of values 8 and 9 ride in the lowest mantissa bit of values 0 and 1; the reader
       // moves them into a +-1 pair of its own and clears them before the entry is used
-      p[0] |= ((npat >> 8) & 1u) | (((npat >> 9) & 1u) << 16);
+      p[0] |= ((npat >> 8) & 1u) | (V == 10 ? ((npat >> 9) & 1u) << 16 : 0u);
 #pragma unroll
       for (int c = 0; c < C::kRep; ++c) *(uint4*)(E8 + (code * C::kRep + c) * 16) = make_uint4(p[0], p[1], p[2], p[3]);
     }
@@ -189,22 +190,45 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_mfma_kernel(
 
   // ---- activations into operand order.  Columns past the end of a row are staged as zeros,
   // which is what makes the padding of the last chunk and the chunks past the end of the row
-  // contribute nothing (a piece that straddles the end of its row is masked pair by pair; rows
-  // have an even number of columns here).
-  {
-    auto put = [&](int j, int p, uint32_t w) {                   // pair p of the tile (values 2p, 2p+1) of row j
-      const int c = (int)(((uint32_t)p * 52429u) >> 18);         // p / 5 for p < 2^16
-      const int s = p - 5 * c;
-      if (k0 + 2 * p >= d.in) w = 0u;
-      if (s < 4) ((uint32_t*)X8)[(c * 16 + (j ^ (c & 15))) * 4 + s] = w;
-      else X2[x2_word(c, j)] = w;
-    };
+  // contribute nothing.  Chunk length 10: pair by pair (a pair never straddles a chunk; rows have
+  // an even number of columns here).  Chunk length 9: value by value; the second tail slot is zero
+  // (and so is the table's).
+  if (wave < batch) {
+    const int j = wave;
+    if constexpr (V == 10) {
+      auto put = [&](int p, uint32_t w) {                        // pair p of the tile: values 2p, 2p+1
+        const int c = (int)(((uint32_t)p * 52429u) >> 18);       // p / 5 for p < 2^16
+        const int s = p - 5 * c;
+        if (k0 + 2 * p >= d.in) w = 0u;
+        if (s < 4) ((uint32_t*)X8)[(c * 16 + (j ^ (c & 15))) * 4 + s] = w;
+        else X2[x2_word(c, j)] = w;
+      };
 #pragma unroll
-    for (int m = 0; m < NS; ++m) {
-      const int seg = lane + 64 * m;
-      if (wave < batch && seg < nseg) {
-        put(wave, 4 * seg + 0, xv[m].x); put(wave, 4 * seg + 1, xv[m].y);
-        put(wave, 4 * seg + 2, xv[m].z); put(wave, 4 * seg + 3, xv[m].w);
+      for (int m = 0; m < NS; ++m) {
+        const int seg = lane + 64 * m;
+        if (seg < nseg) {
+          put(4 * seg + 0, xv[m].x); put(4 * seg + 1, xv[m].y);
+          put(4 * seg + 2, xv[m].z); put(4 * seg + 3, xv[m].w);
+        }
+      }
+    } else {
+      auto put = [&](int e, uint32_t h) {                        // value e of the tile (16 bits)
+        const int c = e / V, t = e - V * c;
+        if (k0 + e >= d.in) h = 0u;
+        if (t < 8) ((uint16_t*)X8)[(c * 16 + (j ^ (c & 15))) * 8 + t] = (uint16_t)h;
+        else X2[x2_word(c, j)] = h;
+      };
+#pragma unroll
+      for (int m = 0; m < NS; ++m) {
+        const int seg = lane + 64 * m;
+        if (seg < nseg) {
+          const uint32_t w[4] = {xv[m].x, xv[m].y, xv[m].z, xv[m].w};
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            put(8 * seg + 2 * u, w[u] & 0xFFFFu);
+            put(8 * seg + 2 * u + 1, w[u] >> 16);
+          }
+        }
       }
     }
   }
@@ -243,7 +267,8 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_mfma_kernel(
 #pragma unroll
   for (int w = 0; w < 4; ++w) x2_lane[w] = X2 + q * 256 + ((w + q) & 3) * 16 + i;
   uint32_t one2;                                                 // 1.0 | 1.0 in a scalar register: an instruction takes one literal only
-  asm volatile("s_mov_b32 %0, 0x3c003c00" : "=s"(one2));
+  if constexpr (V == 10) asm volatile("s_mov_b32 %0, 0x3c003c00" : "=s"(one2));
+  else asm volatile("s_mov_b32 %0, 0x00003c00" : "=s"(one2));   // chunk length 9: the second tail slot is 0.0
   static_for<0, kMaxSG>([&](auto sg_c) {
     constexpr int sg = decltype(sg_c)::value;
     if constexpr (sg + kAhead < kMaxSG) {
@@ -433,36 +458,36 @@ static Plan make_plan(const Dims& d) {
   return best;
 }
 
-template <int B, int R>
+template <int V, int B, int R>
 static btc_status launch2(hipStream_t q, const Dims& d, const Plan& pl, const uint32_t* packed, const uint32_t* codebook,
                           const void* x, int batch, float* part, float* xpart, int n_rb) {
   using C = Cfg<B>;
   static_assert(lds_bytes(C::kE8Bytes, kMaxSG) <= 160 * 1024 - 64, "LDS budget");
   static bool attr_set = false;  // one-time kernel attribute, not call state
   if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)gemv_mfma_kernel<B, R>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    if (hipFuncSetAttribute((const void*)gemv_mfma_kernel<V, B, R>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             lds_bytes(C::kE8Bytes, kMaxSG)) != hipSuccess)
       return BTC_ERR_HIP;
     attr_set = true;
   }
-  gemv_mfma_kernel<B, R><<<pl.n_ct * pl.n_rt, kWaves * 64, lds_bytes(C::kE8Bytes, pl.nsg), q>>>(
+  gemv_mfma_kernel<V, B, R><<<pl.n_ct * pl.n_rt, kWaves * 64, lds_bytes(C::kE8Bytes, pl.nsg), q>>>(
       d, packed, codebook, (const uint16_t*)x, batch, pl.n_ct, pl.nsg, n_rb, part, xpart);
   return launch_status();
 }
 
-template <int B>
+template <int V, int B>
 static btc_status launch1(hipStream_t q, const Dims& d, const Plan& pl, const uint32_t* packed, const uint32_t* codebook,
                           const void* x, int batch, float* part, float* xpart, int n_rb) {
   switch (pl.R) {
-    case 1: return launch2<B, 1>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb);
-    default: return launch2<B, 2>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb);
+    case 1: return launch2<V, B, 1>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb);
+    default: return launch2<V, B, 2>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb);
   }
 }
 
 }  // namespace skinny
 
 bool gemv_mfma_covers(const Dims& d, int batch) {
-  return batch >= 1 && batch <= 16 && d.v == skinny::kV && d.b >= 7 && d.b <= 10 && (d.in & 1) == 0 &&
+  return batch >= 1 && batch <= 16 && (d.v == 9 || d.v == 10) && d.b >= 7 && d.b <= 10 && (d.in & 1) == 0 &&
          (long long)d.out * d.wpr * 4 < (1LL << 31) && (long long)batch * d.in * 2 < (1LL << 31);
 }
 
@@ -492,11 +517,15 @@ btc_status gemv_mfma(hipStream_t q, const Dims& d, const uint32_t* packed, const
   float* xpart = (float*)workspace;
   float* part = (float*)((char*)workspace + xpart_bytes(d, pl));
   btc_status st;
-  switch (d.b) {
-    case 7: st = launch1<7>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb); break;
-    case 8: st = launch1<8>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb); break;
-    case 9: st = launch1<9>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb); break;
-    case 10: st = launch1<10>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb); break;
+  switch (d.v * 16 + d.b) {
+    case 10 * 16 + 7: st = launch1<10, 7>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb); break;
+    case 10 * 16 + 8: st = launch1<10, 8>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb); break;
+    case 10 * 16 + 9: st = launch1<10, 9>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb); break;
+    case 10 * 16 + 10: st = launch1<10, 10>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb); break;
+    case 9 * 16 + 7: st = launch1<9, 7>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb); break;
+    case 9 * 16 + 8: st = launch1<9, 8>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb); break;
+    case 9 * 16 + 9: st = launch1<9, 9>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb); break;
+    case 9 * 16 + 10: st = launch1<9, 10>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb); break;
     default: return BTC_ERR_UNSUPPORTED;
   }
   if (st != BTC_OK) return st;

@@ -85,6 +85,9 @@ GEMV_SMALL = [
     (300, 4096, 10, 128, 2, "uniform"), (131, 6408, 10, 256, 7, "zipf"), (77, 2570, 10, 1024, 16, "uniform"),
     (260, 1234, 10, 512, 3, "uniform"), (13, 648, 10, 256, 15, "uniform"), (1030, 10240, 10, 256, 4, "uniform"),
     (523, 5128, 10, 100, 9, "uniform"),
+    # the same engine at chunk length 9 (one tail value per chunk)
+    (200, 8192, 9, 1024, 4, "uniform"), (77, 2700, 9, 512, 16, "uniform"), (130, 1000, 9, 256, 3, "zipf"),
+    (300, 5770, 9, 128, 2, "uniform"),
 ]
 
 
