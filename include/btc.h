@@ -73,7 +73,9 @@ size_t btc_packed_bytes(const btc_shape* s);
  * The workspace is device memory owned by the caller, 16-byte aligned.  It
  * must be ZERO-FILLED before its first use by btc_gemv; every btc_gemv call
  * leaves it zero again (partial sums travel between workgroups in tagged
- * slots whose empty state is 0), so one buffer serves any number of calls
+ * slots whose empty state is 0; a call with several activation rows parks
+ * fp32 partial sums behind them and zeroes them in its second pass), so one
+ * buffer serves any number of calls
  * that are ordered on a stream.  Calls that may overlap in time (different
  * streams) need a buffer each: sharing one is a data race.  btc_gemm writes
  * scratch values there and needs no particular contents; give it a buffer of
