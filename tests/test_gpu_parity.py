@@ -79,15 +79,15 @@ GEMV_SMALL = [
     (50, 333, 4, 9, 1, "uniform"), (31, 260, 8, 85, 2, "uniform"), (20, 250, 20, 65536, 1, "uniform"),
     (9, 640, 32, 2, 1, "uniform"), (1, 10, 10, 512, 1, "uniform"), (5, 3, 10, 4, 1, "uniform"),
     (40, 330, 16, 7132, 4, "uniform"), (64, 96, 12, 777, 16, "uniform"),
-    # 2..16 rows on the matrix-core engine (v = 10, 7..10 index bits): every index width, rows that are
-    # not 16-byte aligned, ragged last chunk, out not a multiple of 4 / below one block of 16, several
-    # row and column tiles
-    (300, 4096, 10, 128, 2, "uniform"), (131, 6408, 10, 256, 7, "zipf"), (77, 2570, 10, 1024, 16, "uniform"),
+    # 3..16 rows on the matrix-core engine (v = 10, 7..10 index bits; with 2 rows matrices this small
+    # still take one pass per row): every index width, rows that are not 16-byte aligned, ragged last
+    # chunk, out not a multiple of 4 / below one block of 16, several row and column tiles
+    (300, 4096, 10, 128, 6, "uniform"), (131, 6408, 10, 256, 7, "zipf"), (77, 2570, 10, 1024, 16, "uniform"),
     (260, 1234, 10, 512, 3, "uniform"), (13, 648, 10, 256, 15, "uniform"), (1030, 10240, 10, 256, 4, "uniform"),
     (523, 5128, 10, 100, 9, "uniform"),
     # the same engine at chunk length 9 (one tail value per chunk)
     (200, 8192, 9, 1024, 4, "uniform"), (77, 2700, 9, 512, 16, "uniform"), (130, 1000, 9, 256, 3, "zipf"),
-    (300, 5770, 9, 128, 2, "uniform"),
+    (300, 5770, 9, 128, 5, "uniform"),
 ]
 
 
@@ -140,6 +140,12 @@ def test_gemv_large_ragged_streaming(G, oracle):
     """A matrix large enough for the streaming kernel of the table engine (9-bit indices), with a
     ragged last row tile and a ragged last column block."""
     _full_size_gemv(G, oracle, dict(seed=3, out=28700, n_in=8190, v=10, K=512, batch=1), n_sample=192)
+
+
+def test_gemv_wide_single_row_on_matrix_cores(G, oracle):
+    """A single activation row on a large, very wide matrix takes the matrix-core engine; here with
+    ragged row tiles, a ragged last chunk and rows of the stream that are not 16-byte aligned."""
+    _full_size_gemv(G, oracle, dict(seed=4, out=9001, n_in=28666, v=10, K=512, batch=1), n_sample=160)
 
 
 def test_gemv_calls_share_one_workspace(G, oracle):
