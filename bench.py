@@ -315,11 +315,12 @@ def main():
                 us = time_gemv(o_, i_, v_, K_, M, reps_target=40)["us_per_call"]
                 row[tag] = dict(us=us, speedup_over_fp16=round(dense_us / us, 2))
             mlp[f"M{M}"] = row
-        dense_us = time_dense(o_, i_, 2048, torch.bfloat16)
-        us = time_gemm(o_, i_, 10, 256, 2048)
-        mlp["M2048"] = {"torch_bf16_us": round(dense_us, 1),
-                        "0.8 bit": dict(us=round(us, 1), speedup_over_bf16=round(dense_us / us, 2),
-                                        tflops=round(2.0 * 2048 * o_ * i_ / us / 1e6, 1))}
+        for M in (32, 64, 128, 256, 512, 2048):            # btc_gemm, bf16 activations
+            dense_us = time_dense(o_, i_, M, torch.bfloat16)
+            us = time_gemm(o_, i_, 10, 256, M)
+            mlp[f"M{M}"] = {"torch_bf16_us": round(dense_us, 1),
+                            "0.8 bit": dict(us=round(us, 1), speedup_over_bf16=round(dense_us / us, 2),
+                                            tflops=round(2.0 * M * o_ * i_ / us / 1e6, 1))}
         other["mlp_8192x28672_vs_dense_torch"] = mlp
 
     # ---- prefill GEMM on the same shapes (btc_gemm = one contraction kernel per call, plus a second pass when the call is split along k)

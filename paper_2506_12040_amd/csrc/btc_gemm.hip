@@ -73,6 +73,21 @@ btc_status btc_gemm(void* stream, const btc_shape* s, const uint32_t* packed, co
   const Dims d = dims_of(*s);
   float* rowsum = (float*)((char*)workspace + 16);
   const int is_bf16 = x_dtype == BTC_BF16;
+  // Few activation rows: decoding dominates, and the decode engine of btc_gemv (table entries
+  // that are matrix-core operands, 16 rows per pass) is several times quicker than a 256-row tile
+  // that is mostly empty.  Up to 48 rows are served in blocks of 16.
+  if (M <= 48 && gemv_mfma_covers(d, M < 16 ? M : 16) &&
+      ((M + 15) / 16) * gemv_mfma_estimate_us(d, M < 16 ? M : 16) <
+          (gemm_tiled_covers(d, M) ? gemm_tiled_estimate_us(d, M) : 1e30)) {
+    const size_t xsz = 2, ysz = y_dtype == BTC_F32 ? 4 : 2;
+    for (int m0 = 0; m0 < M; m0 += 16) {
+      const int rows = M - m0 < 16 ? M - m0 : 16;
+      st = gemv_mfma(q, d, packed, codebook, alpha, mu, (const char*)X + (size_t)m0 * d.in * xsz, is_bf16, rows,
+                     (char*)Y + (size_t)m0 * d.out * ysz, (int)y_dtype, workspace);
+      if (st != BTC_OK) return st;
+    }
+    return BTC_OK;
+  }
   if (gemm_tiled_covers(d, M))   // adds the activation rows up itself
     return gemm_tiled(q, d, packed, codebook, alpha, mu, X, is_bf16, M, Y, (int)y_dtype, workspace, workspace_bytes,
                       /*clear_workspace=*/0);

@@ -39,7 +39,7 @@ btc_status btc_gemv(void* stream, const btc_shape* s, const uint32_t* packed, co
     const size_t need = gemv_mfma_workspace_bytes(d, batch);
     if (!workspace || workspace_bytes < off + need) return BTC_ERR_WORKSPACE;
     if (!aligned16(workspace)) return BTC_ERR_ALIGN;
-    return gemv_mfma(q, d, packed, codebook, alpha, mu, x, batch, y, y_is_f32, (char*)workspace + off);
+    return gemv_mfma(q, d, packed, codebook, alpha, mu, x, /*is_bf16=*/0, batch, y, (int)y_dtype, (char*)workspace + off);
   }
   // Several activation rows: decoding the indices is the cost, and the matrix cores take up to 32
   // rows for the price of one, so the call goes to the tiled contraction kernel (each index is

@@ -33,6 +33,7 @@
 // previous one is contracted.  The column tiles of a row leave fp32 partial sums in the
 // workspace and a second, small kernel adds them, applies alpha and mu (Algorithm "Binary
 // Transformation and Compression": W_hat = alpha * B_hat + mu) and clears what it has read.
+#include <hip/hip_bf16.h>
 #include <hip/hip_fp16.h>
 
 #include <type_traits>
@@ -54,6 +55,8 @@ __device__ __forceinline__ void static_for(F&& f) {
 
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
@@ -80,16 +83,31 @@ constexpr int lds_bytes(int e8, int nsg) { return e8 + nsg * kSG * (256 + 64); }
 // lane groups of a wave, whose chunks are 16 apart, read from different banks.
 __device__ __forceinline__ int x2_word(int c, int j) { return (c >> 2) * 64 + (((c & 3) + (c >> 4)) & 3) * 16 + j; }
 
+// acc + lo + hi of a packed pair of 16-bit floats
+template <bool BF16>
 __device__ __forceinline__ float pair_sum(uint32_t w, float acc) {
-  const f16x2 one = {(_Float16)1.0f, (_Float16)1.0f};
-  return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, w), one, acc, false);
+  if constexpr (BF16) {
+    const bf16x2 one = {(__bf16)1.0f, (__bf16)1.0f};
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), one, acc, false);
+  } else {
+    const f16x2 one = {(_Float16)1.0f, (_Float16)1.0f};
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, w), one, acc, false);
+  }
 }
 
+__device__ __forceinline__ uint32_t bf16_bits(float v) {
+  return (uint32_t)__builtin_bit_cast(uint16_t, __float2bfloat16(v));
+}
+
+template <bool BF16>
 __device__ __forceinline__ f32x4 mfma16(const uint4& a, const uint4& b, const f32x4& c) {
-  return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+  if constexpr (BF16)
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
 }
 
-template <int V, int B, int R>
+template <int V, int B, int R, bool BF16>
 __global__ __launch_bounds__(kWaves * 64) void gemv_mfma_kernel(
     Dims d, const uint32_t* __restrict__ packed, const uint32_t* __restrict__ codebook,
     const uint16_t* __restrict__ x, int batch, int n_ct, int nsg, int n_rb, float* __restrict__ part,
@@ -179,7 +197,7 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_mfma_kernel(
       uint32_t p[4];
 #pragma unroll
       for (int m = 0; m < 4; ++m)
-        p[m] = 0x3C003C00u | ((npat << (15 - 2 * m)) & 0x8000u) | ((npat << (30 - 2 * m)) & 0x80000000u);
+        p[m] = (BF16 ? 0x3F803F80u : 0x3C003C00u) | ((npat << (15 - 2 * m)) & 0x8000u) | ((npat << (30 - 2 * m)) & 0x80000000u);
       // the signs of values 8 and 9 ride in the lowest mantissa bit of values 0 and 1; the reader
       // moves them into a +-1 pair of its own and clears them before the entry is used
       p[0] |= ((npat >> 8) & 1u) | (V == 10 ? ((npat >> 9) & 1u) << 16 : 0u);
@@ -242,8 +260,8 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_mfma_kernel(
     float s = 0.f;
     for (int c = lane; c < my_nsg * kSG; c += 64) {
       const uint4 v = *(const uint4*)(X8 + (c * 16 + (j ^ (c & 15))) * 16);
-      s = pair_sum(v.x, s); s = pair_sum(v.y, s); s = pair_sum(v.z, s); s = pair_sum(v.w, s);
-      s = pair_sum(X2[x2_word(c, j)], s);
+      s = pair_sum<BF16>(v.x, s); s = pair_sum<BF16>(v.y, s); s = pair_sum<BF16>(v.z, s); s = pair_sum<BF16>(v.w, s);
+      s = pair_sum<BF16>(X2[x2_word(c, j)], s);
     }
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
@@ -267,8 +285,14 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_mfma_kernel(
 #pragma unroll
   for (int w = 0; w < 4; ++w) x2_lane[w] = X2 + q * 256 + ((w + q) & 3) * 16 + i;
   uint32_t one2;                                                 // 1.0 | 1.0 in a scalar register: an instruction takes one literal only
-  if constexpr (V == 10) asm volatile("s_mov_b32 %0, 0x3c003c00" : "=s"(one2));
-  else asm volatile("s_mov_b32 %0, 0x00003c00" : "=s"(one2));   // chunk length 9: the second tail slot is 0.0
+  // (chunk length 9: the second tail slot is 0.0)
+  if constexpr (BF16) {
+    if constexpr (V == 10) asm volatile("s_mov_b32 %0, 0x3f803f80" : "=s"(one2));
+    else asm volatile("s_mov_b32 %0, 0x00003f80" : "=s"(one2));
+  } else {
+    if constexpr (V == 10) asm volatile("s_mov_b32 %0, 0x3c003c00" : "=s"(one2));
+    else asm volatile("s_mov_b32 %0, 0x00003c00" : "=s"(one2));
+  }
   static_for<0, kMaxSG>([&](auto sg_c) {
     constexpr int sg = decltype(sg_c)::value;
     if constexpr (sg + kAhead < kMaxSG) {
@@ -325,11 +349,11 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_mfma_kernel(
         }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-          acc[r][0] = mfma16(a8[r][0], b8[0], acc[r][0]);
-          acc[r][1] = mfma16(a8[r][1], b8[1], acc[r][1]);
-          acc[r][0] = mfma16(a8[r][2], b8[2], acc[r][0]);
-          acc[r][1] = mfma16(a8[r][3], b8[3], acc[r][1]);
-          acc[r][0] = mfma16(make_uint4(a2w[r][0], a2w[r][1], a2w[r][2], a2w[r][3]), b2, acc[r][0]);
+          acc[r][0] = mfma16<BF16>(a8[r][0], b8[0], acc[r][0]);
+          acc[r][1] = mfma16<BF16>(a8[r][1], b8[1], acc[r][1]);
+          acc[r][0] = mfma16<BF16>(a8[r][2], b8[2], acc[r][0]);
+          acc[r][1] = mfma16<BF16>(a8[r][3], b8[3], acc[r][1]);
+          acc[r][0] = mfma16<BF16>(make_uint4(a2w[r][0], a2w[r][1], a2w[r][2], a2w[r][3]), b2, acc[r][0]);
         }
       });
     }
@@ -362,7 +386,7 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_mfma_kernel(
 // cost more than the second launch.)
 __global__ __launch_bounds__(256) void skinny_reduce_kernel(const float* __restrict__ alpha, const float* __restrict__ mu,
                                                             float* __restrict__ part, float* __restrict__ xpart, int out,
-                                                            int batch, int n_ct, void* __restrict__ y, int y_is_f32) {
+                                                            int batch, int n_ct, void* __restrict__ y, int y_dtype) {
   __shared__ float4 red[3][64];
   const int nb = blockIdx.x, j = blockIdx.y, tid = threadIdx.x, lane = tid & 63, g = tid >> 6;
   const int n_end = min(out, (nb + 1) * kReduceCols);
@@ -406,8 +430,11 @@ __global__ __launch_bounds__(256) void skinny_reduce_kernel(const float* __restr
       }
       const float r0 = al.x * v.x + mn.x * xs, r1 = al.y * v.y + mn.y * xs, r2 = al.z * v.z + mn.z * xs,
                   r3 = al.w * v.w + mn.w * xs;
-      if (y_is_f32) {
+      if (y_dtype == BTC_F32) {
         *(float4*)((float*)y + yrow + n) = make_float4(r0, r1, r2, r3);
+      } else if (y_dtype == BTC_BF16) {
+        *(uint2*)((uint16_t*)y + yrow + n) =
+            make_uint2(bf16_bits(r0) | (bf16_bits(r1) << 16), bf16_bits(r2) | (bf16_bits(r3) << 16));
       } else {
         const __half2 h0 = __floats2half2_rn(r0, r1), h1 = __floats2half2_rn(r2, r3);
         *(uint2*)((uint16_t*)y + yrow + n) =
@@ -424,7 +451,8 @@ __global__ __launch_bounds__(256) void skinny_reduce_kernel(const float* __restr
           *p = 0.f;
         }
         const float r = alpha[n] * v + mu[n] * xs;
-        if (y_is_f32) ((float*)y)[yrow + n] = r;
+        if (y_dtype == BTC_F32) ((float*)y)[yrow + n] = r;
+        else if (y_dtype == BTC_BF16) ((__hip_bfloat16*)y)[yrow + n] = __float2bfloat16(r);
         else ((__half*)y)[yrow + n] = __float2half_rn(r);
       }
     }
@@ -458,30 +486,32 @@ static Plan make_plan(const Dims& d) {
   return best;
 }
 
-template <int V, int B, int R>
+template <int V, int B, int R, bool BF16>
 static btc_status launch2(hipStream_t q, const Dims& d, const Plan& pl, const uint32_t* packed, const uint32_t* codebook,
                           const void* x, int batch, float* part, float* xpart, int n_rb) {
   using C = Cfg<B>;
   static_assert(lds_bytes(C::kE8Bytes, kMaxSG) <= 160 * 1024 - 64, "LDS budget");
   static bool attr_set = false;  // one-time kernel attribute, not call state
   if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)gemv_mfma_kernel<V, B, R>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    if (hipFuncSetAttribute((const void*)gemv_mfma_kernel<V, B, R, BF16>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             lds_bytes(C::kE8Bytes, kMaxSG)) != hipSuccess)
       return BTC_ERR_HIP;
     attr_set = true;
   }
-  gemv_mfma_kernel<V, B, R><<<pl.n_ct * pl.n_rt, kWaves * 64, lds_bytes(C::kE8Bytes, pl.nsg), q>>>(
+  gemv_mfma_kernel<V, B, R, BF16><<<pl.n_ct * pl.n_rt, kWaves * 64, lds_bytes(C::kE8Bytes, pl.nsg), q>>>(
       d, packed, codebook, (const uint16_t*)x, batch, pl.n_ct, pl.nsg, n_rb, part, xpart);
   return launch_status();
 }
 
 template <int V, int B>
 static btc_status launch1(hipStream_t q, const Dims& d, const Plan& pl, const uint32_t* packed, const uint32_t* codebook,
-                          const void* x, int batch, float* part, float* xpart, int n_rb) {
-  switch (pl.R) {
-    case 1: return launch2<V, B, 1>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb);
-    default: return launch2<V, B, 2>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb);
+                          const void* x, int is_bf16, int batch, float* part, float* xpart, int n_rb) {
+  if (is_bf16) {
+    if (pl.R == 1) return launch2<V, B, 1, true>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb);
+    return launch2<V, B, 2, true>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb);
   }
+  if (pl.R == 1) return launch2<V, B, 1, false>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb);
+  return launch2<V, B, 2, false>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb);
 }
 
 }  // namespace skinny
@@ -510,7 +540,7 @@ double gemv_mfma_estimate_us(const Dims& d, int batch) {
 }
 
 btc_status gemv_mfma(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook, const float* alpha,
-                     const float* mu, const void* x, int batch, void* y, int y_is_f32, void* workspace) {
+                     const float* mu, const void* x, int is_bf16, int batch, void* y, int y_dtype, void* workspace) {
   using namespace skinny;
   const Plan pl = make_plan(d);
   const int n_rb = (d.out + kReduceCols - 1) / kReduceCols;
@@ -518,18 +548,18 @@ btc_status gemv_mfma(hipStream_t q, const Dims& d, const uint32_t* packed, const
   float* part = (float*)((char*)workspace + xpart_bytes(d, pl));
   btc_status st;
   switch (d.v * 16 + d.b) {
-    case 10 * 16 + 7: st = launch1<10, 7>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb); break;
-    case 10 * 16 + 8: st = launch1<10, 8>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb); break;
-    case 10 * 16 + 9: st = launch1<10, 9>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb); break;
-    case 10 * 16 + 10: st = launch1<10, 10>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb); break;
-    case 9 * 16 + 7: st = launch1<9, 7>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb); break;
-    case 9 * 16 + 8: st = launch1<9, 8>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb); break;
-    case 9 * 16 + 9: st = launch1<9, 9>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb); break;
-    case 9 * 16 + 10: st = launch1<9, 10>(q, d, pl, packed, codebook, x, batch, part, xpart, n_rb); break;
+    case 10 * 16 + 7: st = launch1<10, 7>(q, d, pl, packed, codebook, x, is_bf16, batch, part, xpart, n_rb); break;
+    case 10 * 16 + 8: st = launch1<10, 8>(q, d, pl, packed, codebook, x, is_bf16, batch, part, xpart, n_rb); break;
+    case 10 * 16 + 9: st = launch1<10, 9>(q, d, pl, packed, codebook, x, is_bf16, batch, part, xpart, n_rb); break;
+    case 10 * 16 + 10: st = launch1<10, 10>(q, d, pl, packed, codebook, x, is_bf16, batch, part, xpart, n_rb); break;
+    case 9 * 16 + 7: st = launch1<9, 7>(q, d, pl, packed, codebook, x, is_bf16, batch, part, xpart, n_rb); break;
+    case 9 * 16 + 8: st = launch1<9, 8>(q, d, pl, packed, codebook, x, is_bf16, batch, part, xpart, n_rb); break;
+    case 9 * 16 + 9: st = launch1<9, 9>(q, d, pl, packed, codebook, x, is_bf16, batch, part, xpart, n_rb); break;
+    case 9 * 16 + 10: st = launch1<9, 10>(q, d, pl, packed, codebook, x, is_bf16, batch, part, xpart, n_rb); break;
     default: return BTC_ERR_UNSUPPORTED;
   }
   if (st != BTC_OK) return st;
-  skinny_reduce_kernel<<<dim3(n_rb, batch), 256, 0, q>>>(alpha, mu, part, xpart, d.out, batch, pl.n_ct, y, y_is_f32);
+  skinny_reduce_kernel<<<dim3(n_rb, batch), 256, 0, q>>>(alpha, mu, part, xpart, d.out, batch, pl.n_ct, y, y_dtype);
   return launch_status();
 }
 

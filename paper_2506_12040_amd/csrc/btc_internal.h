@@ -41,8 +41,8 @@ bool gemv_mfma_covers(const Dims& d, int batch);
 size_t gemv_mfma_workspace_bytes(const Dims& d, int batch);
 double gemv_mfma_estimate_us(const Dims& d, int batch);   // rough duration, for engine selection
 btc_status gemv_mfma(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
-                     const float* alpha, const float* mu, const void* x, int batch, void* y, int y_is_f32,
-                     void* workspace);
+                     const float* alpha, const float* mu, const void* x, int is_bf16, int batch, void* y,
+                     int y_dtype, void* workspace);
 
 // Prefill kernels: the tuned tiling (btc_gemm_tiled.hip) and the generic one (btc_gemm_generic.hip).
 bool gemm_tiled_covers(const Dims& d, int M);
