@@ -75,8 +75,8 @@ btc_status btc_gemm(void* stream, const btc_shape* s, const uint32_t* packed, co
   const int is_bf16 = x_dtype == BTC_BF16;
   // Few activation rows: decoding dominates, and the decode engine of btc_gemv (table entries
   // that are matrix-core operands, 16 rows per pass) is several times quicker than a 256-row tile
-  // that is mostly empty.  Up to 48 rows are served in blocks of 16.
-  if (M <= 48 && gemv_mfma_covers(d, M < 16 ? M : 16) &&
+  // that is mostly empty.  Up to 64 rows are served in blocks of 16.
+  if (M <= 64 && gemv_mfma_covers(d, M < 16 ? M : 16) &&
       ((M + 15) / 16) * gemv_mfma_estimate_us(d, M < 16 ? M : 16) <
           (gemm_tiled_covers(d, M) ? gemm_tiled_estimate_us(d, M) : 1e30)) {
     const size_t xsz = 2, ysz = y_dtype == BTC_F32 ? 4 : 2;

@@ -208,10 +208,10 @@ GEMM_SMALL = [
     # width it has a table for, long rows with few outputs (k split), more than one block of activation rows
     (301, 1600, 10, 256, 300, "bf16"), (300, 5136, 10, 512, 100, "f16"), (97, 2080, 10, 1024, 70, "bf16"),
     (512, 1616, 10, 128, 513, "bf16"), (2100, 800, 10, 256, 64, "bf16"), (45, 4000, 10, 64, 2, "f16"),
-    # up to 48 rows: served by the decode engine of btc_gemv in blocks of 16 (bf16 and fp16 operands, chunk
+    # up to 64 rows: served by the decode engine of btc_gemv in blocks of 16 (bf16 and fp16 operands, chunk
     # lengths 10 and 9, a last block of one row, rows of X that are not 16-byte aligned)
     (140, 810, 9, 1024, 33, "bf16"), (300, 5136, 10, 512, 12, "f16"), (97, 2080, 10, 1024, 30, "bf16"),
-    (523, 1002, 10, 256, 48, "bf16"), (13, 648, 10, 100, 16, "bf16"),
+    (523, 1002, 10, 256, 49, "bf16"), (13, 648, 10, 100, 16, "bf16"),
 ]
 
 
