@@ -29,6 +29,11 @@ btc_status btc_gemv(void* stream, const btc_shape* s, const uint32_t* packed, co
   // (unless the matrix is so small that a pass per row is still quicker).  A single row goes there
   // too when the matrix is large and so wide that the table engine cannot use its streaming kernel
   // (measured on 8192 x 28672: 22.7 against 29.9 us at 9 index bits, 23.2 against 38.8 us at 10).
+  // One row, 9 or 10 index bits, a wide matrix with few enough rows: the single-kernel variant of the
+  // matrix-core engine (measured on 4096 x 11008 at 9 bits: 8.6 us against 11.4 for the table engine; at 7 or
+  // 8 bits, or with many rows, the other engines stay ahead).
+  if (batch == 1 && d.b >= 9 && d.nchunks >= 1024 && d.out <= 6144 && gemv_mfma_one_covers(d))
+    return gemv_mfma_one(q, d, packed, codebook, alpha, mu, x, y, y_is_f32);
   bool use_mfma = false;
   if (gemv_mfma_covers(d, batch)) {
     if (batch == 1) use_mfma = d.b >= 9 && d.nchunks >= 2048 && (long long)d.out * d.wpr * 4 >= (16LL << 20);

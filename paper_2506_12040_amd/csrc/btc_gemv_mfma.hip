@@ -462,6 +462,240 @@ __global__ __launch_bounds__(256) void skinny_reduce_kernel(const float* __restr
     for (int ct = lane; ct < n_ct; ct += 64) xpart[((size_t)nb * n_ct + ct) * 16 + j] = 0.f;
 }
 
+// ---------------------------------------------------------------------------------------------
+// One activation row, one kernel: the same operand scheme with a workgroup of 8 waves that owns
+// 16 weight rows over ALL columns.  Wave w takes the super-groups w, w + 8, ... (the sums of the
+// eight waves meet in LDS), so no partial sum leaves the workgroup and the call is a single
+// launch whose chain is: every load issued at once, one wait, table and staging, a handful of
+// MFMAs per wave, 16 outputs.  The activation row (20 bytes per chunk) and a 32 KB table fit
+// two to three workgroups per compute unit.  All 16 columns of the B operand read the same
+// activation row (one LDS address per lane group: a broadcast), so every column of the result
+// is the answer and column 0 is taken.
+constexpr int kOneWaves = 8;
+constexpr int kOneIters = 8;            // super-groups per wave at most: in <= 8 * 8 * 640 columns (chunk length 10)
+constexpr int kOnePieces = 8;           // 16-byte pieces of the activation row per thread at most
+
+template <int B>
+struct OneCfg {
+  static constexpr int kRep = (2048 >> B) > 16 ? 16 : (2048 >> B);        // copies of a 16-byte entry: 32 KB
+  static constexpr int kE8Bytes = (1 << B) * kRep * 16;
+};
+
+constexpr int one_lds_bytes(int e8, int sgs) { return e8 + sgs * kSG * 20 + kOneWaves * 16 * 4 * 4 + 64; }
+
+template <int V, int B, int R>
+__global__ __launch_bounds__(kOneWaves * 64) void gemv_mfma_one_kernel(
+    Dims d, const uint32_t* __restrict__ packed, const uint32_t* __restrict__ codebook,
+    const float* __restrict__ alpha, const float* __restrict__ mu, const uint16_t* __restrict__ x,
+    void* __restrict__ y, int y_is_f32) {
+  static_assert(V == 9 || V == 10, "chunk lengths 9 and 10");
+  using C = OneCfg<B>;
+  constexpr int NW = Cfg<B>::kNW;
+  constexpr int K2 = 1 << B;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int sgs = (d.nchunks + kSG - 1) / kSG;
+  unsigned char* E8 = smem;                                      // [code][copy] x 16 B
+  unsigned char* X8 = smem + C::kE8Bytes;                        // [chunk] x 16 B: values 0..7
+  uint32_t* X2 = (uint32_t*)(X8 + sgs * kSG * 16);               // [chunk] x 4 B: values 8, 9
+  float* red = (float*)(X2 + sgs * kSG);                         // [wave][16 R rows]
+  float* xs_w = red + kOneWaves * 16 * R;                            // [wave]: partial sums of the activation row
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int i = lane & 15, q = lane >> 4;
+  const int n0 = blockIdx.x * (16 * R);                          // first weight row of the workgroup
+
+  // ---- every global load first
+  constexpr int NC = (K2 + kOneWaves * 64 - 1) / (kOneWaves * 64);
+  uint32_t cw[NC];
+#pragma unroll
+  for (int k = 0; k < NC; ++k) {
+    const int code = tid + k * kOneWaves * 64;
+    cw[k] = code < K2 ? codebook[code] : 0u;
+  }
+  const __amdgpu_buffer_rsrc_t rX = __builtin_amdgcn_make_buffer_rsrc((void*)x, 0, d.in * 2, kRsrcFlags);
+  uint4 xv[kOnePieces];
+#pragma unroll
+  for (int m = 0; m < kOnePieces; ++m) {
+    const int k = 8 * (tid + m * kOneWaves * 64);
+    xv[m] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rX, k < d.in ? (uint32_t)k * 2u : kOob, 0, 0));
+  }
+  const __amdgpu_buffer_rsrc_t rP =
+      __builtin_amdgcn_make_buffer_rsrc((void*)packed, 0, (int)((uint32_t)d.out * (uint32_t)d.wpr * 4u), kRsrcFlags);
+  uint32_t W[kOneIters][R][NW];
+#pragma unroll
+  for (int it = 0; it < kOneIters; ++it) {
+    const int sg = wave + it * kOneWaves;
+    const int cs = sg * kSG;
+    const int w0 = ((cs + 16 * q) * B) >> 5;
+    const bool inside = (((cs + kSG) * B + 31) >> 5) <= d.wpr;   // uniform: the whole window of every lane lies in its row
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int n = n0 + 16 * r + i;
+      const bool row_ok = sg < sgs && n < d.out;
+      if (inside) {
+        const uint32_t off = row_ok ? ((uint32_t)n * (uint32_t)d.wpr + (uint32_t)w0) * 4u : kOob;
+        const uint4 v = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rP, off, 0, 0));
+        W[it][r][0] = v.x; W[it][r][1] = v.y; W[it][r][2] = v.z; W[it][r][3] = v.w;
+        if constexpr (NW == 5) W[it][r][4] = __builtin_amdgcn_raw_buffer_load_b32(rP, off + 16u, 0, 0);
+      } else {
+#pragma unroll
+        for (int k = 0; k < NW; ++k) {
+          const uint32_t off =
+              (row_ok && w0 + k < d.wpr) ? ((uint32_t)n * (uint32_t)d.wpr + (uint32_t)(w0 + k)) * 4u : kOob;
+          W[it][r][k] = __builtin_amdgcn_raw_buffer_load_b32(rP, off, 0, 0);
+        }
+      }
+    }
+  }
+  const float my_alpha = (tid < 16 * R && n0 + tid < d.out) ? alpha[n0 + tid] : 0.f;
+  const float my_mu = (tid < 16 * R && n0 + tid < d.out) ? mu[n0 + tid] : 0.f;
+
+  // ---- table
+#pragma unroll
+  for (int k = 0; k < NC; ++k) {
+    const int code = tid + k * kOneWaves * 64;
+    if (code < K2) {
+      const uint32_t npat = ~cw[k];
+      uint32_t p[4];
+#pragma unroll
+      for (int m = 0; m < 4; ++m)
+        p[m] = 0x3C003C00u | ((npat << (15 - 2 * m)) & 0x8000u) | ((npat << (30 - 2 * m)) & 0x80000000u);
+      p[0] |= ((npat >> 8) & 1u) | (V == 10 ? ((npat >> 9) & 1u) << 16 : 0u);
+#pragma unroll
+      for (int c = 0; c < C::kRep; ++c) *(uint4*)(E8 + (code * C::kRep + c) * 16) = make_uint4(p[0], p[1], p[2], p[3]);
+    }
+  }
+  // ---- the activation row into operand order (zeros past its end), and its sum
+  float xsum = 0.f;
+  {
+    const int n_vals = sgs * kSG * V;                            // slots of the staged row
+#pragma unroll
+    for (int m = 0; m < kOnePieces; ++m) {
+      const int k = 8 * (tid + m * kOneWaves * 64);
+      if (k < n_vals) {
+        const uint32_t w[4] = {xv[m].x, xv[m].y, xv[m].z, xv[m].w};
+        if constexpr (V == 10) {
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const int p = k / 2 + u;                             // pair p: values 2p, 2p+1 (never straddles a chunk)
+            const uint32_t wv = 2 * p < d.in ? w[u] : 0u;        // `in` is even here
+            xsum = pair_sum<false>(wv, xsum);
+            const int c = (int)(((uint32_t)p * 52429u) >> 18), sl = p - 5 * c;
+            if (sl < 4) ((uint32_t*)X8)[c * 4 + sl] = wv;
+            else X2[c] = wv;
+          }
+        } else {
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            const int e = k + u;
+            uint32_t h = (u & 1) ? w[u >> 1] >> 16 : w[u >> 1] & 0xFFFFu;
+            if (e >= d.in) h = 0u;
+            xsum = pair_sum<false>(h, xsum);
+            const int c = e / V, t = e - V * c;
+            if (t < 8) ((uint16_t*)X8)[c * 8 + t] = (uint16_t)h;
+            else X2[c] = h;
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) xsum += __shfl_xor(xsum, o, 64);
+    if (lane == 0) xs_w[wave] = xsum;
+  }
+  __syncthreads();
+
+  // ---- contraction: this wave's super-groups
+  f32x4 acc[R][2];
+#pragma unroll
+  for (int r = 0; r < R; ++r) acc[r][0] = acc[r][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const uint32_t shift = (uint32_t)(16 * q * B) & 31u;
+  typedef __attribute__((address_space(3))) const u32x4* lds_u4;
+  const uint32_t e8_lane32 = (uint32_t)(uintptr_t)(lds_u4)(const u32x4*)(E8 + (i & (C::kRep - 1)) * 16);
+  uint32_t one2;
+  if constexpr (V == 10) asm volatile("s_mov_b32 %0, 0x3c003c00" : "=s"(one2));
+  else asm volatile("s_mov_b32 %0, 0x00003c00" : "=s"(one2));
+  static_for<0, kOneIters>([&](auto it_c) {
+    constexpr int it = decltype(it_c)::value;
+    const int sg = wave + it * kOneWaves;
+    if (sg < sgs) {
+      uint32_t Wn[R][NW];
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+#pragma unroll
+        for (int k = 0; k + 1 < NW; ++k) Wn[r][k] = __builtin_amdgcn_alignbit(W[it][r][k + 1], W[it][r][k], shift);
+        Wn[r][NW - 1] = W[it][r][NW - 1] >> shift;
+      }
+      const unsigned char* xb8 = X8 + (sg * kSG + 16 * q) * 16;  // the lane group's 16 chunks (the same for all 16 columns)
+      const uint32_t* xb2 = X2 + sg * kSG + 16 * q;
+      static_for<0, 4>([&](auto t_c) {
+        constexpr int t = decltype(t_c)::value;
+        uint4 a8[R][4], b8[4];
+        uint32_t a2w[R][4];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) b8[w] = *(const uint4*)(xb8 + (4 * t + w) * 16);
+        const uint4 b2 = *(const uint4*)(xb2 + 4 * t);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+          static_for<0, 4>([&](auto w_c) {
+            constexpr int w = decltype(w_c)::value;
+            constexpr int pos = (4 * t + w) * B;
+            constexpr int wi = pos >> 5, sh = pos & 31;
+            uint32_t src = Wn[r][wi];
+            if constexpr (sh + B > 32) src = __builtin_amdgcn_alignbit(Wn[r][wi + 1 < NW ? wi + 1 : wi], Wn[r][wi], (uint32_t)sh);
+            uint32_t code, addr;
+            asm("v_bfe_u32 %0, %1, %2, %3" : "=v"(code) : "v"(src), "n"(sh + B > 32 ? 0 : sh), "n"(B));
+            asm("v_lshl_add_u32 %0, %1, %2, %3" : "=v"(addr) : "v"(code), "n"(B <= 7 ? 8 : B == 8 ? 7 : B == 9 ? 6 : 5), "v"(e8_lane32));
+            a8[r][w] = __builtin_bit_cast(uint4, *(lds_u4)(uintptr_t)addr);
+          });
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            uint32_t flags;
+            asm("v_and_b32 %0, 0x10001, %1" : "=v"(flags) : "v"(a8[r][w].x));
+            asm("v_lshl_or_b32 %0, %1, 15, %2" : "=v"(a2w[r][w]) : "v"(flags), "s"(one2));
+            a8[r][w].x &= 0xFFFEFFFEu;
+          }
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+          acc[r][0] = mfma16<false>(a8[r][0], b8[0], acc[r][0]);
+          acc[r][1] = mfma16<false>(a8[r][1], b8[1], acc[r][1]);
+          acc[r][0] = mfma16<false>(a8[r][2], b8[2], acc[r][0]);
+          acc[r][1] = mfma16<false>(a8[r][3], b8[3], acc[r][1]);
+          acc[r][0] = mfma16<false>(make_uint4(a2w[r][0], a2w[r][1], a2w[r][2], a2w[r][3]), b2, acc[r][0]);
+        }
+      });
+    }
+  });
+
+  // ---- the eight waves' sums meet in LDS; 16 threads finish the 16 rows
+  if (i == 0) {
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const f32x4 v = acc[r][0] + acc[r][1];                     // column 0: weight rows 4 q .. 4 q + 3 of block r
+      *(float4*)(red + (wave * R + r) * 16 + 4 * q) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+  }
+  __syncthreads();
+  if (tid < 16 * R) {
+    float sum = 0.f, sx = 0.f;
+#pragma unroll
+    for (int w = 0; w < kOneWaves; ++w) {
+      sum += red[w * 16 * R + tid];
+      sx += xs_w[w];
+    }
+    const int nn = n0 + tid;
+    if (nn < d.out) {
+      const float r = my_alpha * sum + my_mu * sx;
+      if (y_is_f32) ((float*)y)[nn] = r;
+      else ((__half*)y)[nn] = __float2half_rn(r);
+    }
+  }
+}
+
 struct Plan {
   int R;        // blocks of 16 weight rows per wave
   int nsg;      // super-groups per column tile
@@ -515,6 +749,58 @@ static btc_status launch1(hipStream_t q, const Dims& d, const Plan& pl, const ui
 }
 
 }  // namespace skinny
+
+// Single-row, single-kernel variant: the staged row and the table must fit LDS with room for a
+// second workgroup, a wave takes at most kOneIters super-groups, and the threads' 16-byte pieces
+// must cover every staged slot.
+bool gemv_mfma_one_covers(const Dims& d) {
+  const int sgs = (d.nchunks + skinny::kSG - 1) / skinny::kSG;
+  return (d.v == 9 || d.v == 10) && d.b >= 7 && d.b <= 10 && (d.in & 1) == 0 &&
+         sgs <= skinny::kOneWaves * skinny::kOneIters &&
+         sgs * skinny::kSG * d.v <= 8 * skinny::kOnePieces * skinny::kOneWaves * 64 &&
+         skinny::one_lds_bytes(32 << 10, sgs) <= 80 * 1024 && (long long)d.out * d.wpr * 4 < (1LL << 31);
+}
+
+template <int V, int B, int R>
+static btc_status launch_one2(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
+                              const float* alpha, const float* mu, const void* x, void* y, int y_is_f32) {
+  using namespace skinny;
+  const int sgs = (d.nchunks + kSG - 1) / kSG;
+  const int lds = one_lds_bytes(OneCfg<B>::kE8Bytes, sgs);
+  static bool attr_set = false;  // one-time kernel attribute, not call state
+  if (!attr_set) {
+    if (hipFuncSetAttribute((const void*)gemv_mfma_one_kernel<V, B, R>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            80 * 1024) != hipSuccess)
+      return BTC_ERR_HIP;
+    attr_set = true;
+  }
+  gemv_mfma_one_kernel<V, B, R><<<(d.out + 16 * R - 1) / (16 * R), kOneWaves * 64, lds, q>>>(d, packed, codebook, alpha, mu,
+                                                                           (const uint16_t*)x, y, y_is_f32);
+  return launch_status();
+}
+
+// Rows per workgroup: the kernel is written for R blocks of 16, but 16 rows is what the matrices
+// it is chosen for want (measured on 4096 x 11008: 8.6 us with 16 rows, 11.3 with 32, 17.8 with 64).
+template <int V, int B>
+static btc_status launch_one(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
+                             const float* alpha, const float* mu, const void* x, void* y, int y_is_f32) {
+  return launch_one2<V, B, 1>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32);
+}
+
+btc_status gemv_mfma_one(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
+                         const float* alpha, const float* mu, const void* x, void* y, int y_is_f32) {
+  switch (d.v * 16 + d.b) {
+    case 10 * 16 + 7: return launch_one<10, 7>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32);
+    case 10 * 16 + 8: return launch_one<10, 8>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32);
+    case 10 * 16 + 9: return launch_one<10, 9>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32);
+    case 10 * 16 + 10: return launch_one<10, 10>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32);
+    case 9 * 16 + 7: return launch_one<9, 7>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32);
+    case 9 * 16 + 8: return launch_one<9, 8>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32);
+    case 9 * 16 + 9: return launch_one<9, 9>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32);
+    case 9 * 16 + 10: return launch_one<9, 10>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32);
+    default: return BTC_ERR_UNSUPPORTED;
+  }
+}
 
 bool gemv_mfma_covers(const Dims& d, int batch) {
   return batch >= 1 && batch <= 16 && (d.v == 9 || d.v == 10) && d.b >= 7 && d.b <= 10 && (d.in & 1) == 0 &&

@@ -44,6 +44,11 @@ btc_status gemv_mfma(hipStream_t q, const Dims& d, const uint32_t* packed, const
                      const float* alpha, const float* mu, const void* x, int is_bf16, int batch, void* y,
                      int y_dtype, void* workspace);
 
+// The same operand scheme for one activation row in a single kernel (16 weight rows per workgroup).
+bool gemv_mfma_one_covers(const Dims& d);
+btc_status gemv_mfma_one(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
+                         const float* alpha, const float* mu, const void* x, void* y, int y_is_f32);
+
 // Prefill kernels: the tuned tiling (btc_gemm_tiled.hip) and the generic one (btc_gemm_generic.hip).
 bool gemm_tiled_covers(const Dims& d, int M);
 btc_status gemm_tiled(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,

@@ -85,6 +85,10 @@ GEMV_SMALL = [
     (300, 4096, 10, 128, 6, "uniform"), (131, 6408, 10, 256, 7, "zipf"), (77, 2570, 10, 1024, 16, "uniform"),
     (260, 1234, 10, 512, 3, "uniform"), (13, 648, 10, 256, 15, "uniform"), (1030, 10240, 10, 256, 4, "uniform"),
     (523, 5128, 10, 100, 9, "uniform"),
+    # one row on wide matrices with 9 or 10 index bits: the single-kernel variant (ragged rows and columns,
+    # rows of the stream that are not 16-byte aligned, chunk length 9)
+    (70, 13824, 10, 512, 1, "uniform"), (130, 11006, 10, 512, 1, "zipf"), (200, 12006, 9, 1024, 1, "uniform"),
+    (1, 10250, 10, 1024, 1, "uniform"),
     # the same engine at chunk length 9 (one tail value per chunk)
     (200, 8192, 9, 1024, 4, "uniform"), (77, 2700, 9, 512, 16, "uniform"), (130, 1000, 9, 256, 3, "zipf"),
     (300, 5770, 9, 128, 5, "uniform"),
