@@ -58,6 +58,7 @@ size_t btc_workspace_bytes(const btc_shape* s, int32_t rows, int is_gemm) {
     need += (((size_t)rows * sizeof(float)) + 15) & ~(size_t)15;  // fp32 row sums of X
     // partial sums of a call that the tiled contraction kernel splits along k
     if (btc::gemm_tiled_covers(d, rows)) need = std::max(need, btc::gemm_tiled_workspace_bytes(d, rows));
+    if (btc::gemm_rows_covers(d, rows)) need = std::max(need, btc::gemm_rows_workspace_bytes(d, rows));
     // a call with few rows may go to the decode engine, 16 rows at a time
     if (rows <= 64 && btc::gemv_mfma_covers(d, rows < 16 ? rows : 16))
       need = std::max(need, btc::gemv_mfma_workspace_bytes(d, rows < 16 ? rows : 16));

@@ -73,6 +73,11 @@ btc_status btc_gemm(void* stream, const btc_shape* s, const uint32_t* packed, co
   const Dims d = dims_of(*s);
   float* rowsum = (float*)((char*)workspace + 16);
   const int is_bf16 = x_dtype == BTC_BF16;
+  // 17..64 activation rows: the same operand scheme with two or four blocks of activation rows
+  // per table read, one pass over the index stream.
+  if (gemm_rows_covers(d, M) &&
+      gemm_rows_estimate_us(d, M) < (gemm_tiled_covers(d, M) ? gemm_tiled_estimate_us(d, M) : 1e30))
+    return gemm_rows(q, d, packed, codebook, alpha, mu, X, is_bf16, M, Y, (int)y_dtype, workspace);
   // Few activation rows: decoding dominates, and the decode engine of btc_gemv (table entries
   // that are matrix-core operands, 16 rows per pass) is several times quicker than a 256-row tile
   // that is mostly empty.  Up to 64 rows are served in blocks of 16.

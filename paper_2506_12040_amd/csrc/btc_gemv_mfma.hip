@@ -33,79 +33,10 @@
 // previous one is contracted.  The column tiles of a row leave fp32 partial sums in the
 // workspace and a second, small kernel adds them, applies alpha and mu (Algorithm "Binary
 // Transformation and Compression": W_hat = alpha * B_hat + mu) and clears what it has read.
-#include <hip/hip_bf16.h>
-#include <hip/hip_fp16.h>
-
-#include <type_traits>
-#include <utility>
-
-#include "btc_internal.h"
+#include "btc_mfma_decode.h"
 
 namespace btc {
 namespace skinny {
-
-// f(integral_constant<int, I>) for I = Begin .. End - 1, fully unrolled
-template <int Begin, int End, class F>
-__device__ __forceinline__ void static_for(F&& f) {
-  if constexpr (Begin < End) {
-    f(std::integral_constant<int, Begin>{});
-    static_for<Begin + 1, End>(f);
-  }
-}
-
-typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
-typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-
-constexpr int kWaves = 16;               // 1024 threads: one workgroup per compute unit, 128 registers per lane
-constexpr int kSG = 64;                 // chunks per super-group
-constexpr int kReduceCols = 256;        // outputs per block of the second pass
-constexpr int kMaxSG = 4;               // super-groups of activations a workgroup stages
-constexpr int kAhead = 1;               // index words are requested this many super-groups ahead of their use
-constexpr uint32_t kOob = 0x80000000u;  // buffer offset that is always out of range
-constexpr int kRsrcFlags = 0x00020000;
-
-template <int B>
-struct Cfg {
-  static constexpr int kNW = B <= 8 ? 4 : 5;                              // index words per lane and super-group
-  static constexpr int kK2 = 1 << B;
-  static constexpr int kRep = (4096 >> B) > 16 ? 16 : (4096 >> B);        // copies of a 16-byte entry
-  static constexpr int kE8Bytes = kK2 * kRep * 16;                        // <= 64 KB
-};
-
-constexpr int lds_bytes(int e8, int nsg) { return e8 + nsg * kSG * (256 + 64); }
-
-// position (in words) of the 4-byte tail of (chunk c, activation row j): inside a block of 4 chunks
-// (64 words = every bank once) the 16-word slot of a chunk is rotated by c / 16, so that the four
-// lane groups of a wave, whose chunks are 16 apart, read from different banks.
-__device__ __forceinline__ int x2_word(int c, int j) { return (c >> 2) * 64 + (((c & 3) + (c >> 4)) & 3) * 16 + j; }
-
-// acc + lo + hi of a packed pair of 16-bit floats
-template <bool BF16>
-__device__ __forceinline__ float pair_sum(uint32_t w, float acc) {
-  if constexpr (BF16) {
-    const bf16x2 one = {(__bf16)1.0f, (__bf16)1.0f};
-    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), one, acc, false);
-  } else {
-    const f16x2 one = {(_Float16)1.0f, (_Float16)1.0f};
-    return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, w), one, acc, false);
-  }
-}
-
-__device__ __forceinline__ uint32_t bf16_bits(float v) {
-  return (uint32_t)__builtin_bit_cast(uint16_t, __float2bfloat16(v));
-}
-
-template <bool BF16>
-__device__ __forceinline__ f32x4 mfma16(const uint4& a, const uint4& b, const f32x4& c) {
-  if constexpr (BF16)
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-  else
-    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
-}
 
 template <int V, int B, int R, bool BF16>
 __global__ __launch_bounds__(kWaves * 64) void gemv_mfma_kernel(
@@ -386,14 +317,14 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_mfma_kernel(
 // cost more than the second launch.)
 __global__ __launch_bounds__(256) void skinny_reduce_kernel(const float* __restrict__ alpha, const float* __restrict__ mu,
                                                             float* __restrict__ part, float* __restrict__ xpart, int out,
-                                                            int batch, int n_ct, void* __restrict__ y, int y_dtype) {
+                                                            int batch, int n_ct, int xstride, void* __restrict__ y, int y_dtype) {
   __shared__ float4 red[3][64];
   const int nb = blockIdx.x, j = blockIdx.y, tid = threadIdx.x, lane = tid & 63, g = tid >> 6;
   const int n_end = min(out, (nb + 1) * kReduceCols);
   const size_t yrow = (size_t)j * out;
   float xs = 0.f;
   if (g == 0) {                                      // the row sum: one tile per lane, then across the wave
-    for (int ct = lane; ct < n_ct; ct += 64) xs += xpart[((size_t)nb * n_ct + ct) * 16 + j];
+    for (int ct = lane; ct < n_ct; ct += 64) xs += xpart[((size_t)nb * n_ct + ct) * xstride + j];
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) xs += __shfl_xor(xs, o, 64);
   }
@@ -459,7 +390,7 @@ __global__ __launch_bounds__(256) void skinny_reduce_kernel(const float* __restr
   }
   // the row sums are read by wave 0 only, which clears them afterwards
   if (g == 0)
-    for (int ct = lane; ct < n_ct; ct += 64) xpart[((size_t)nb * n_ct + ct) * 16 + j] = 0.f;
+    for (int ct = lane; ct < n_ct; ct += 64) xpart[((size_t)nb * n_ct + ct) * xstride + j] = 0.f;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -825,6 +756,14 @@ double gemv_mfma_estimate_us(const Dims& d, int batch) {
   return 8.4 + 0.47e-6 * bytes + batch / 16.0 * (1.8 + 0.13e-6 * bytes);
 }
 
+btc_status skinny_reduce(hipStream_t q, const float* alpha, const float* mu, float* part, float* xpart, int out,
+                         int rows, int n_ct, int xstride, void* y, int y_dtype) {
+  const int n_rb = (out + skinny::kReduceCols - 1) / skinny::kReduceCols;
+  skinny::skinny_reduce_kernel<<<dim3(n_rb, rows), 256, 0, q>>>(alpha, mu, part, xpart, out, rows, n_ct, xstride, y,
+                                                               y_dtype);
+  return launch_status();
+}
+
 btc_status gemv_mfma(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook, const float* alpha,
                      const float* mu, const void* x, int is_bf16, int batch, void* y, int y_dtype, void* workspace) {
   using namespace skinny;
@@ -845,8 +784,7 @@ btc_status gemv_mfma(hipStream_t q, const Dims& d, const uint32_t* packed, const
     default: return BTC_ERR_UNSUPPORTED;
   }
   if (st != BTC_OK) return st;
-  skinny_reduce_kernel<<<dim3(n_rb, batch), 256, 0, q>>>(alpha, mu, part, xpart, d.out, batch, pl.n_ct, y, y_dtype);
-  return launch_status();
+  return skinny_reduce(q, alpha, mu, part, xpart, d.out, batch, pl.n_ct, 16, y, y_dtype);
 }
 
 }  // namespace btc

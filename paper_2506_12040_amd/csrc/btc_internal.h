@@ -44,6 +44,20 @@ btc_status gemv_mfma(hipStream_t q, const Dims& d, const uint32_t* packed, const
                      const float* alpha, const float* mu, const void* x, int is_bf16, int batch, void* y,
                      int y_dtype, void* workspace);
 
+// Second pass of the engines above and below: y = alpha * (sum of `n_ct` partial-sum planes
+// [n_ct][rows][out]) + mu * (sum of `n_ct` row-sum entries, one copy of [n_ct][xstride] per block of
+// 256 outputs); clears what it reads.
+btc_status skinny_reduce(hipStream_t q, const float* alpha, const float* mu, float* part, float* xpart, int out,
+                         int rows, int n_ct, int xstride, void* y, int y_dtype);
+// 17..64 activation rows on the same operand scheme (btc_gemm_rows.hip): a workgroup keeps its
+// accumulators while it walks its share of the columns, restaging the activations per super-group.
+bool gemm_rows_covers(const Dims& d, int M);
+size_t gemm_rows_workspace_bytes(const Dims& d, int M);
+double gemm_rows_estimate_us(const Dims& d, int M);
+btc_status gemm_rows(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
+                     const float* alpha, const float* mu, const void* X, int is_bf16, int M, void* Y, int y_dtype,
+                     void* workspace);
+
 // The same operand scheme for one activation row in a single kernel (16 weight rows per workgroup).
 bool gemv_mfma_one_covers(const Dims& d);
 btc_status gemv_mfma_one(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,

@@ -216,6 +216,10 @@ GEMM_SMALL = [
     # lengths 10 and 9, a last block of one row, rows of X that are not 16-byte aligned)
     (140, 810, 9, 1024, 33, "bf16"), (300, 5136, 10, 512, 12, "f16"), (97, 2080, 10, 1024, 30, "bf16"),
     (523, 1002, 10, 256, 49, "bf16"), (13, 648, 10, 100, 16, "bf16"),
+    # 17..64 rows at chunk length 10: two or four blocks of activation rows per table read; several row
+    # tiles and column shares, ragged everything, every index width
+    (700, 5128, 10, 512, 33, "bf16"), (1030, 2570, 10, 256, 64, "f16"), (300, 13824, 10, 128, 17, "bf16"),
+    (261, 2082, 10, 1024, 32, "f16"), (77, 650, 10, 512, 63, "bf16"),
 ]
 
 
