@@ -23,7 +23,6 @@ constexpr int kRWaves = 8;
 constexpr int kRR = 2;                  // blocks of 16 weight rows per wave
 constexpr int kRowsPerWg = kRWaves * kRR * 16;
 constexpr int kV = 10;
-constexpr int kPiecesPerRow = kSG * kV / 8;   // 16-byte pieces of one activation row per super-group
 
 template <int B, int NB>
 constexpr int rows_lds_bytes() { return Cfg<B>::kE8Bytes + NB * kSG * (256 + 64); }
@@ -37,12 +36,12 @@ __global__ __launch_bounds__(kRWaves * 64) void gemm_rows_kernel(
   constexpr int NW = C::kNW;
   constexpr int R = kRR;
   constexpr int TPR = kRWaves * 64 / (16 * NB);                  // threads that stage one activation row
-  constexpr int NP = kPiecesPerRow / TPR;                        // pieces per thread and super-group
-  static_assert(kPiecesPerRow % TPR == 0, "pieces divide evenly among the threads of a row");
+  constexpr int NCH = kSG / TPR;                                 // chunks per thread and super-group
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* E8 = smem;                                      // [code][copy] x 16 B
   unsigned char* X8 = smem + C::kE8Bytes;                        // [block][chunk][16 rows] x 16 B
-  uint32_t* X2 = (uint32_t*)(X8 + NB * kSG * 256);               // [block][chunk][16 rows] x 4 B
+  uint32_t* X2 = (uint32_t*)(X8 + NB * kSG * 256);               // [block][chunk / 4][16 rows][chunk % 4] x 4 B: the tails
+                                                                 // of the four chunks of a tail MFMA are one 16-byte read
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -59,30 +58,38 @@ __global__ __launch_bounds__(kRWaves * 64) void gemm_rows_kernel(
   const __amdgpu_buffer_rsrc_t rX =
       __builtin_amdgcn_make_buffer_rsrc((void*)X, 0, (int)((long long)M * d.in * 2), kRsrcFlags);
   const uint32_t xrow = (uint32_t)my_row * (uint32_t)d.in * 2u;
-  uint4 xv[NP];
+  // A thread stages whole chunks (20 bytes: one 16-byte and one 4-byte load, both only 4-byte
+  // aligned), so a chunk goes to LDS with one 16-byte and one 4-byte write and no index arithmetic
+  // beyond its chunk number.
+  uint4 xv[NCH];
+  uint32_t xt[NCH];
   auto load_x = [&](int sg) {
 #pragma unroll
-    for (int m = 0; m < NP; ++m) {
-      const int k = sg * (kSG * kV) + 8 * (my_sub + TPR * m);
+    for (int m = 0; m < NCH; ++m) {
+      const int k = (sg * kSG + my_sub + TPR * m) * kV;
       const uint32_t off = (my_row < M && k < d.in) ? xrow + (uint32_t)k * 2u : kOob;
       xv[m] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rX, off, 0, 0));
+      xt[m] = __builtin_amdgcn_raw_buffer_load_b32(rX, off + 16u, 0, 0);
     }
   };
   float xsum = 0.f;
-  auto put_x = [&](int sg) {                                     // xv -> operand order (zeros past the end of a row)
+  auto put_x = [&](int sg) {                                     // operand order; zeros past the end of a row
     if (my_row < M) {
+      const bool ragged = (sg + 1) * (kSG * kV) > d.in;          // uniform: this super-group reaches past the row's end
 #pragma unroll
-      for (int m = 0; m < NP; ++m) {
-        const uint32_t w[4] = {xv[m].x, xv[m].y, xv[m].z, xv[m].w};
+      for (int m = 0; m < NCH; ++m) {
+        const int c = my_sub + TPR * m;
+        uint32_t w[5] = {xv[m].x, xv[m].y, xv[m].z, xv[m].w, xt[m]};
+        if (ragged) {
+          const int k = (sg * kSG + c) * kV;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int p = 4 * (my_sub + TPR * m) + u;              // pair p of the super-group: values 2p, 2p+1
-          const uint32_t wv = sg * (kSG * kV) + 2 * p < d.in ? w[u] : 0u;   // `in` is even here
-          xsum = pair_sum<BF16>(wv, xsum);
-          const int c = (int)(((uint32_t)p * 52429u) >> 18), sl = p - 5 * c;
-          if (sl < 4) ((uint32_t*)X8)[my_nb * (kSG * 64) + (c * 16 + (my_j ^ (c & 15))) * 4 + sl] = wv;
-          else X2[my_nb * (kSG * 16) + x2_word(c, my_j)] = wv;
+          for (int u = 0; u < 5; ++u)
+            if (k + 2 * u >= d.in) w[u] = 0u;                    // `in` is even here
         }
+#pragma unroll
+        for (int u = 0; u < 5; ++u) xsum = pair_sum<BF16>(w[u], xsum);
+        *(uint4*)(X8 + my_nb * (kSG * 256) + (c * 16 + (my_j ^ (c & 15))) * 16) = make_uint4(w[0], w[1], w[2], w[3]);
+        X2[my_nb * (kSG * 16) + ((c >> 2) * 16 + my_j) * 4 + (c & 3)] = w[4];
       }
     }
   };
@@ -153,9 +160,7 @@ __global__ __launch_bounds__(kRWaves * 64) void gemm_rows_kernel(
   typedef __attribute__((address_space(3))) const u32x4* lds_u4;
   const uint32_t e8_lane32 = (uint32_t)(uintptr_t)(lds_u4)(const u32x4*)(E8 + (i & (C::kRep - 1)) * 16);
   const uint32_t x8_lane = (uint32_t)(q * 4096 + i * 16);
-  const uint32_t* x2_lane[4];
-#pragma unroll
-  for (int w = 0; w < 4; ++w) x2_lane[w] = X2 + q * 256 + ((w + q) & 3) * 16 + i;
+  const uint32_t* x2_lane = X2 + (q * 64 + i) * 4;               // tails of chunks 16 q + 4 t .. + 3: + 64 t words
   uint32_t one2;
   if constexpr (BF16) asm volatile("s_mov_b32 %0, 0x3f803f80" : "=s"(one2));
   else asm volatile("s_mov_b32 %0, 0x3c003c00" : "=s"(one2));
@@ -202,14 +207,12 @@ __global__ __launch_bounds__(kRWaves * 64) void gemm_rows_kernel(
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
         uint4 b8[4];
-        uint32_t b2w[4];
         static_for<0, 4>([&](auto w_c) {
           constexpr int w = decltype(w_c)::value;
           constexpr int u = 4 * t + w;
           b8[w] = *(const uint4*)(X8 + nb * (kSG * 256) + ((x8_lane ^ (uint32_t)(u * 16)) + (uint32_t)(u * 256)));
-          b2w[w] = x2_lane[w][nb * (kSG * 16) + t * 64];
         });
-        const uint4 b2 = make_uint4(b2w[0], b2w[1], b2w[2], b2w[3]);
+        const uint4 b2 = *(const uint4*)(x2_lane + nb * (kSG * 16) + t * 64);
 #pragma unroll
         for (int w = 0; w < 4; ++w)
 #pragma unroll
@@ -218,7 +221,6 @@ __global__ __launch_bounds__(kRWaves * 64) void gemm_rows_kernel(
         for (int r = 0; r < R; ++r)
           acc[r][nb] = mfma16<BF16>(make_uint4(a2w[r][0], a2w[r][1], a2w[r][2], a2w[r][3]), b2, acc[r][nb]);
       }
-      __builtin_amdgcn_sched_barrier(0);                         // keeps the next step's operands from piling up in registers
     });
     if (more) {
       __syncthreads();                                           // everybody is done with super-group sg
