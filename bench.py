@@ -37,7 +37,7 @@ HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes of one step (7 calls) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
 # 256 MiB copy (profiles/gemv_13b_hbm_traffic.md): 37.1 MB fetched + 5.5 MB written.
-HBM_TRAFFIC_PER_STEP = 42.6e6
+HBM_TRAFFIC_PER_STEP = 45.2e6
 
 SHAPES_13B = [(5120, 5120, 4), (13824, 5120, 2), (5120, 13824, 1)]   # (out, in, count per layer)
 V, K = 10, 256
