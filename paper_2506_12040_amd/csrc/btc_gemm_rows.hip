@@ -1,11 +1,10 @@
 // 17..64 activation rows (small-M btc_gemm), chunk length 10, 7..10 index bits: the operand scheme
 // of the decode engine (a table entry in LDS IS the A operand of MFMA 16x16x32, chunk-aligned
 // permutation of the contraction index: see btc_gemv_mfma.hip), with NB = 2 or 4 blocks of 16
-// activation rows as B operands.  An A operand read from the table is used for NB MFMAs, a B
-// operand for the two weight-row blocks of the wave.
+// activation rows as B operands.  An A operand read from the table is used for NB MFMAs.
 //
-// A workgroup of 8 waves owns 256 weight rows (2 blocks of 16 per wave) and a share of the
-// columns, which it walks super-group by super-group (64 chunks) with its accumulators in
+// A workgroup of 16 waves owns 256 weight rows (one block of 16 per wave; two blocks per wave
+// on 8 waves measured the same) and a share of the columns, which it walks super-group by super-group (64 chunks) with its accumulators in
 // registers: the activations of one super-group (16 NB rows x 640 columns, in operand order) are
 // staged in LDS, contracted, and replaced by the next ones, whose global loads were issued a
 // whole super-group earlier; the index words of the next super-group are in flight meanwhile.
@@ -19,8 +18,8 @@ namespace rows {
 
 using namespace skinny;   // operand types, table geometry, layout helpers
 
-constexpr int kRWaves = 8;
-constexpr int kRR = 2;                  // blocks of 16 weight rows per wave
+constexpr int kRWaves = 16;
+constexpr int kRR = 1;                  // blocks of 16 weight rows per wave
 constexpr int kRowsPerWg = kRWaves * kRR * 16;
 constexpr int kV = 10;
 
@@ -35,8 +34,8 @@ __global__ __launch_bounds__(kRWaves * 64) void gemm_rows_kernel(
   using C = Cfg<B>;
   constexpr int NW = C::kNW;
   constexpr int R = kRR;
-  constexpr int TPR = kRWaves * 64 / (16 * NB);                  // threads that stage one activation row
-  constexpr int NCH = kSG / TPR;                                 // chunks per thread and super-group
+  constexpr int TPR = 16;                                        // staging tasks (threads) per activation row
+  static_assert(kRWaves * 64 >= 16 * NB * TPR, "one staging task per thread at most");
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* E8 = smem;                                      // [code][copy] x 16 B
   unsigned char* X8 = smem + C::kE8Bytes;                        // [block][chunk][16 rows] x 16 B
@@ -55,42 +54,45 @@ __global__ __launch_bounds__(kRWaves * 64) void gemm_rows_kernel(
   // staging role: activation row my_row, pieces my_sub, my_sub + TPR, ...
   const int my_row = tid / TPR, my_sub = tid % TPR;
   const int my_nb = my_row >> 4, my_j = my_row & 15;
+  const bool stager = my_row < M && my_row < 16 * NB;
   const __amdgpu_buffer_rsrc_t rX =
       __builtin_amdgcn_make_buffer_rsrc((void*)X, 0, (int)((long long)M * d.in * 2), kRsrcFlags);
   const uint32_t xrow = (uint32_t)my_row * (uint32_t)d.in * 2u;
-  // A thread stages whole chunks (20 bytes: one 16-byte and one 4-byte load, both only 4-byte
-  // aligned), so a chunk goes to LDS with one 16-byte and one 4-byte write and no index arithmetic
-  // beyond its chunk number.
-  uint4 xv[NCH];
-  uint32_t xt[NCH];
+  // A staging task is four consecutive chunks of one activation row: 80 bytes = five 16-byte
+  // loads (rows are only 4-byte aligned, which such loads allow), whose 20 words map to
+  // (chunk, slot) at compile time -- no index arithmetic, one 16-byte and one 4-byte LDS
+  // write per chunk.  16 tasks per row and super-group; the first 256 NB threads take one each.
+  uint4 xv[5];
   auto load_x = [&](int sg) {
+    const int k = (sg * kSG + 4 * my_sub) * kV;
 #pragma unroll
-    for (int m = 0; m < NCH; ++m) {
-      const int k = (sg * kSG + my_sub + TPR * m) * kV;
-      const uint32_t off = (my_row < M && k < d.in) ? xrow + (uint32_t)k * 2u : kOob;
+    for (int m = 0; m < 5; ++m) {
+      const uint32_t off = (stager && k + 8 * m < d.in) ? xrow + (uint32_t)(k + 8 * m) * 2u : kOob;
       xv[m] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rX, off, 0, 0));
-      xt[m] = __builtin_amdgcn_raw_buffer_load_b32(rX, off + 16u, 0, 0);
     }
   };
   float xsum = 0.f;
   auto put_x = [&](int sg) {                                     // operand order; zeros past the end of a row
-    if (my_row < M) {
+    if (stager) {
       const bool ragged = (sg + 1) * (kSG * kV) > d.in;          // uniform: this super-group reaches past the row's end
+      uint32_t w[20] = {xv[0].x, xv[0].y, xv[0].z, xv[0].w, xv[1].x, xv[1].y, xv[1].z, xv[1].w, xv[2].x, xv[2].y,
+                        xv[2].z, xv[2].w, xv[3].x, xv[3].y, xv[3].z, xv[3].w, xv[4].x, xv[4].y, xv[4].z, xv[4].w};
+      if (ragged) {
+        const int k = (sg * kSG + 4 * my_sub) * kV;
 #pragma unroll
-      for (int m = 0; m < NCH; ++m) {
-        const int c = my_sub + TPR * m;
-        uint32_t w[5] = {xv[m].x, xv[m].y, xv[m].z, xv[m].w, xt[m]};
-        if (ragged) {
-          const int k = (sg * kSG + c) * kV;
-#pragma unroll
-          for (int u = 0; u < 5; ++u)
-            if (k + 2 * u >= d.in) w[u] = 0u;                    // `in` is even here
-        }
-#pragma unroll
-        for (int u = 0; u < 5; ++u) xsum = pair_sum<BF16>(w[u], xsum);
-        *(uint4*)(X8 + my_nb * (kSG * 256) + (c * 16 + (my_j ^ (c & 15))) * 16) = make_uint4(w[0], w[1], w[2], w[3]);
-        X2[my_nb * (kSG * 16) + ((c >> 2) * 16 + my_j) * 4 + (c & 3)] = w[4];
+        for (int u = 0; u < 20; ++u)
+          if (k + 2 * u >= d.in) w[u] = 0u;                      // `in` is even here
       }
+#pragma unroll
+      for (int u = 0; u < 20; ++u) xsum = pair_sum<BF16>(w[u], xsum);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int c = 4 * my_sub + e;
+        *(uint4*)(X8 + my_nb * (kSG * 256) + (c * 16 + (my_j ^ (c & 15))) * 16) =
+            make_uint4(w[5 * e], w[5 * e + 1], w[5 * e + 2], w[5 * e + 3]);
+      }
+      // the four tails of the task are the 16 bytes that a tail MFMA reads for this row
+      *(uint4*)(X2 + my_nb * (kSG * 16) + (my_sub * 16 + my_j) * 4) = make_uint4(w[4], w[9], w[14], w[19]);
     }
   };
   const __amdgpu_buffer_rsrc_t rP =
@@ -259,7 +261,7 @@ __global__ __launch_bounds__(kRWaves * 64) void gemm_rows_kernel(
   // row add up; the workgroups of the first row tile leave one copy per block of the second pass
 #pragma unroll
   for (int o = TPR / 2; o >= 1; o >>= 1) xsum += __shfl_xor(xsum, o, 64);
-  if (rt == 0 && my_row < M)
+  if (rt == 0 && stager)
     for (int nbr = my_sub; nbr < n_rb; nbr += TPR) xpart[((size_t)nbr * n_cs + cs) * 64 + my_row] = xsum;
 }
 
