@@ -29,7 +29,7 @@ constexpr int rows_lds_bytes() { return Cfg<B>::kE8Bytes + NB * kSG * (256 + 64)
 template <int B, int NB, bool BF16>
 __global__ __launch_bounds__(kRWaves * 64) void gemm_rows_kernel(
     Dims d, const uint32_t* __restrict__ packed, const uint32_t* __restrict__ codebook,
-    const uint16_t* __restrict__ X, int M, int n_cs, int sg_per_cs, int n_rb, float* __restrict__ part,
+    const uint16_t* __restrict__ X, int M, int n_cs, int n_rt, int sg_per_cs, int n_rb, float* __restrict__ part,
     float* __restrict__ xpart) {
   using C = Cfg<B>;
   constexpr int NW = C::kNW;
@@ -45,7 +45,14 @@ __global__ __launch_bounds__(kRWaves * 64) void gemm_rows_kernel(
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int i = lane & 15, q = lane >> 4;
-  const int cs = blockIdx.x % n_cs, rt = blockIdx.x / n_cs;
+  // Workgroups are dealt round-robin to the 8 XCDs; each XCD gets a contiguous eighth of the
+  // (row tile, column share) pairs, so the shares of a row tile mostly meet in one L2, which
+  // serves the cache lines that neighbouring shares have in common.
+  const int tiles = n_cs * n_rt, xcd = blockIdx.x & 7;
+  const int first = (int)((long long)tiles * xcd >> 3), last = (int)((long long)tiles * (xcd + 1) >> 3);
+  const int flat = first + (blockIdx.x >> 3);
+  if (flat >= last) return;                                      // the grid is padded to 8 x ceil(tiles / 8)
+  const int cs = flat % n_cs, rt = flat / n_cs;
   const int sgs = (d.nchunks + kSG - 1) / kSG;
   const int sg_begin = cs * sg_per_cs;
   const int sg_end = min(sgs, sg_begin + sg_per_cs);             // > sg_begin: the host sizes n_cs so
@@ -296,8 +303,8 @@ static btc_status launch_rows(hipStream_t q, const Dims& d, const RowsPlan& pl, 
       return BTC_ERR_HIP;
     attr_set = true;
   }
-  gemm_rows_kernel<B, NB, BF16><<<pl.n_rt * pl.n_cs, kRWaves * 64, rows_lds_bytes<B, NB>(), q>>>(
-      d, packed, codebook, (const uint16_t*)X, M, pl.n_cs, pl.sg_per_cs, n_rb, part, xpart);
+  gemm_rows_kernel<B, NB, BF16><<<(pl.n_rt * pl.n_cs + 7) / 8 * 8, kRWaves * 64, rows_lds_bytes<B, NB>(), q>>>(
+      d, packed, codebook, (const uint16_t*)X, M, pl.n_cs, pl.n_rt, pl.sg_per_cs, n_rb, part, xpart);
   return launch_status();
 }
 
