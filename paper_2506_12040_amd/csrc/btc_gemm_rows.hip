@@ -151,7 +151,8 @@ __global__ __launch_bounds__(kRWaves * 64) void gemm_rows_kernel(
       // the signs of values 8 and 9 ride in the lowest mantissa bit of values 0 and 1
       p[0] |= ((npat >> 8) & 1u) | (((npat >> 9) & 1u) << 16);
 #pragma unroll
-      for (int c = 0; c < C::kRep; ++c) *(uint4*)(E8 + (code * C::kRep + c) * 16) = make_uint4(p[0], p[1], p[2], p[3]);
+      for (int c = 0; c < C::kRep; ++c)   // copies in an order rotated by the code: neighbouring threads write different bank groups
+        *(uint4*)(E8 + (code * C::kRep + ((c + code) & (C::kRep - 1))) * 16) = make_uint4(p[0], p[1], p[2], p[3]);
     }
   }
   put_x(sg_begin);

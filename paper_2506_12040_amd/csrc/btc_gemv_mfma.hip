@@ -141,7 +141,8 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_mfma_kernel(
       // moves them into a +-1 pair of its own and clears them before the entry is used
       p[0] |= ((npat >> 8) & 1u) | (V == 10 ? ((npat >> 9) & 1u) << 16 : 0u);
 #pragma unroll
-      for (int c = 0; c < C::kRep; ++c) *(uint4*)(E8 + (code * C::kRep + c) * 16) = make_uint4(p[0], p[1], p[2], p[3]);
+      for (int c = 0; c < C::kRep; ++c)   // copies in an order rotated by the code: neighbouring threads write different bank groups
+        *(uint4*)(E8 + (code * C::kRep + ((c + code) & (C::kRep - 1))) * 16) = make_uint4(p[0], p[1], p[2], p[3]);
     }
   }
 
@@ -502,7 +503,8 @@ __global__ __launch_bounds__(kOneWaves * 64) void gemv_mfma_one_kernel(
         p[m] = 0x3C003C00u | ((npat << (15 - 2 * m)) & 0x8000u) | ((npat << (30 - 2 * m)) & 0x80000000u);
       p[0] |= ((npat >> 8) & 1u) | (V == 10 ? ((npat >> 9) & 1u) << 16 : 0u);
 #pragma unroll
-      for (int c = 0; c < C::kRep; ++c) *(uint4*)(E8 + (code * C::kRep + c) * 16) = make_uint4(p[0], p[1], p[2], p[3]);
+      for (int c = 0; c < C::kRep; ++c)   // copies in an order rotated by the code: neighbouring threads write different bank groups
+        *(uint4*)(E8 + (code * C::kRep + ((c + code) & (C::kRep - 1))) * 16) = make_uint4(p[0], p[1], p[2], p[3]);
     }
   }
   // ---- the activation row into operand order (zeros past its end), and its sum
