@@ -1,0 +1,59 @@
+"""GPU parity on seeded random shapes: the engines that feed table entries straight into matrix-core
+operands (2..16 activation rows, one row on wide matrices, btc_gemm with up to 64 rows) against the CPU
+oracle on sampled output rows.  Shapes are drawn so that ragged row tiles, ragged last chunks, activation rows
+that are not 16-byte aligned and every supported index width come up; the tolerances are those of the other
+parity tests."""
+import numpy as np
+import pytest
+
+import btc_synth as S
+
+pytestmark = pytest.mark.gpu
+
+K_OF = {10: [100, 128, 200, 256, 300, 512, 700, 1024], 9: [128, 256, 512]}
+
+
+def _cases(seed, n):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        v = 10 if rng.random() < 0.75 else 9
+        K = int(rng.choice(K_OF[v]))
+        out = int(rng.integers(1, 3000))
+        n_in = 2 * int(rng.integers(300, 9000))
+        mode = int(rng.integers(0, 4))
+        s = int(rng.integers(1, 1000))
+        if mode == 0:      # several rows on the decode engine
+            cases.append(("gemv", s, out, n_in, v, K, int(rng.integers(3, 17)), "f16"))
+        elif mode == 1:    # btc_gemm with few rows
+            cases.append(("gemm", s, out, n_in, v, K, int(rng.integers(1, 65)), "bf16" if rng.random() < 0.6 else "f16"))
+        elif mode == 2:    # one row, wide matrix, 9 or 10 index bits
+            Kw = int(rng.choice([300, 512, 700, 1024] if v == 10 else [300, 512]))
+            cases.append(("gemv", s, int(rng.integers(1, 2000)), 2 * int(rng.integers(5200, 12000)), v, Kw, 1, "f16"))
+        else:              # two rows
+            cases.append(("gemv", s, out, n_in, v, K, 2, "f16"))
+    return cases
+
+
+@pytest.fixture(scope="module")
+def G():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import gpu_util
+    return gpu_util
+
+
+@pytest.mark.parametrize("kind,seed,out,n_in,v,K,rows,xd", _cases(20250612, 28))
+def test_random_shape(G, oracle, kind, seed, out, n_in, v, K, rows, xd):
+    B = G.B
+    print(f"random {kind} seed={seed} out={out} in={n_in} v={v} K={K} rows={rows} {xd}", flush=True)
+    layer, x = S.make_case(seed, out, n_in, v, K, rows, x_dtype=xd)
+    dl = G.DeviceLayer(layer, oracle)
+    rng = np.random.default_rng(seed)
+    sel = np.unique(np.concatenate([[0, out - 1], rng.choice(out, size=min(96, out), replace=False)]))
+    y_ref = oracle.linear(dl.packed_host, dl.codebook_host, layer.alpha, layer.mu, x, n_in, v, K, rows=sel, x_kind=xd)
+    if kind == "gemv":
+        y = G.gemv(dl, x, B.BTC_F32)
+    else:
+        y = G.gemm(dl, x, B.BTC_BF16 if xd == "bf16" else B.BTC_F16, B.BTC_F32)
+    G.assert_close(y[:, sel], y_ref, f"{kind} {out}x{n_in} v{v} K{K} rows={rows} {xd}")
