@@ -36,7 +36,10 @@ btc_status btc_gemv(void* stream, const btc_shape* s, const uint32_t* packed, co
     return gemv_mfma_one(q, d, packed, codebook, alpha, mu, x, y, y_is_f32);
   bool use_mfma = false;
   if (gemv_mfma_covers(d, batch)) {
-    if (batch == 1) use_mfma = d.b >= 9 && d.nchunks >= 2048 && (long long)d.out * d.wpr * 4 >= (16LL << 20);
+    const long long bytes = (long long)d.out * d.wpr * 4;
+    if (batch == 1)   // also every large matrix with 10-bit indices, where the table engine's 128 KB table
+                      // allows one workgroup per compute unit only (28672 x 8192: 25.8 against 29.6 us)
+      use_mfma = (d.b >= 9 && d.nchunks >= 2048 && bytes >= (16LL << 20)) || (d.b == 10 && bytes >= (8LL << 20));
     else use_mfma = batch * row_pass_us(d) > gemv_mfma_estimate_us(d, batch);
   }
   if (use_mfma) {
