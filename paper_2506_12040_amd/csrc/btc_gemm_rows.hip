@@ -24,7 +24,7 @@ constexpr int kRowsPerWg = kRWaves * kRR * 16;
 constexpr int kV = 10;
 
 template <int B, int NB>
-constexpr int rows_lds_bytes() { return Cfg<B>::kE8Bytes + NB * kSG * (256 + 64); }
+constexpr int rows_lds_bytes() { return Cfg<B>::kE8Bytes + (NB == 2 ? 2 : 1) * NB * kSG * (256 + 64); }
 
 template <int B, int NB, bool BF16>
 __global__ __launch_bounds__(kRWaves * 64) void gemm_rows_kernel(
@@ -38,6 +38,11 @@ __global__ __launch_bounds__(kRWaves * 64) void gemm_rows_kernel(
   static_assert(kRWaves * 64 >= 16 * NB * TPR, "one staging task per thread at most");
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* E8 = smem;                                      // [code][copy] x 16 B
+  // Staged activations of one super-group; with two blocks of activation rows there is room for
+  // two such buffers, which lets the next super-group be staged while this one is contracted
+  // (one barrier per super-group instead of two).
+  constexpr bool DB = NB == 2;
+  constexpr int kXBuf = NB * kSG * (256 + 64);                   // bytes of one buffer
   unsigned char* X8 = smem + C::kE8Bytes;                        // [block][chunk][16 rows] x 16 B
   uint32_t* X2 = (uint32_t*)(X8 + NB * kSG * 256);               // [block][chunk / 4][16 rows][chunk % 4] x 4 B: the tails
                                                                  // of the four chunks of a tail MFMA are one 16-byte read
@@ -80,6 +85,7 @@ __global__ __launch_bounds__(kRWaves * 64) void gemm_rows_kernel(
   };
   float xsum = 0.f;
   auto put_x = [&](int sg) {                                     // operand order; zeros past the end of a row
+    const int xb = DB ? ((sg - sg_begin) & 1) * kXBuf : 0;       // byte offset of the buffer of super-group sg
     if (stager) {
       const bool ragged = (sg + 1) * (kSG * kV) > d.in;          // uniform: this super-group reaches past the row's end
       uint32_t w[20] = {xv[0].x, xv[0].y, xv[0].z, xv[0].w, xv[1].x, xv[1].y, xv[1].z, xv[1].w, xv[2].x, xv[2].y,
@@ -95,11 +101,11 @@ __global__ __launch_bounds__(kRWaves * 64) void gemm_rows_kernel(
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const int c = 4 * my_sub + e;
-        *(uint4*)(X8 + my_nb * (kSG * 256) + (c * 16 + (my_j ^ (c & 15))) * 16) =
+        *(uint4*)(X8 + xb + my_nb * (kSG * 256) + (c * 16 + (my_j ^ (c & 15))) * 16) =
             make_uint4(w[5 * e], w[5 * e + 1], w[5 * e + 2], w[5 * e + 3]);
       }
       // the four tails of the task are the 16 bytes that a tail MFMA reads for this row
-      *(uint4*)(X2 + my_nb * (kSG * 16) + (my_sub * 16 + my_j) * 4) = make_uint4(w[4], w[9], w[14], w[19]);
+      *(uint4*)((unsigned char*)X2 + xb + (my_nb * (kSG * 16) + (my_sub * 16 + my_j) * 4) * 4) = make_uint4(w[4], w[9], w[14], w[19]);
     }
   };
   const __amdgpu_buffer_rsrc_t rP =
@@ -177,7 +183,12 @@ __global__ __launch_bounds__(kRWaves * 64) void gemm_rows_kernel(
 
   for (int sg = sg_begin; sg < sg_end; ++sg) {
     const bool more = sg + 1 < sg_end;
+    const int xb = DB ? ((sg - sg_begin) & 1) * kXBuf : 0;
     if (more) load_w(sg + 1, Wx);
+    if (DB && more) {                                            // stage the next super-group into the other buffer
+      put_x(sg + 1);
+      if (sg + 2 < sg_end) load_x(sg + 2);
+    }
     // ---- contraction of super-group sg
     uint32_t Wn[R][NW];
 #pragma unroll
@@ -220,9 +231,9 @@ __global__ __launch_bounds__(kRWaves * 64) void gemm_rows_kernel(
         static_for<0, 4>([&](auto w_c) {
           constexpr int w = decltype(w_c)::value;
           constexpr int u = 4 * t + w;
-          b8[w] = *(const uint4*)(X8 + nb * (kSG * 256) + ((x8_lane ^ (uint32_t)(u * 16)) + (uint32_t)(u * 256)));
+          b8[w] = *(const uint4*)(X8 + xb + nb * (kSG * 256) + ((x8_lane ^ (uint32_t)(u * 16)) + (uint32_t)(u * 256)));
         });
-        const uint4 b2 = *(const uint4*)(x2_lane + nb * (kSG * 16) + t * 64);
+        const uint4 b2 = *(const uint4*)((const unsigned char*)x2_lane + xb + (nb * (kSG * 16) + t * 64) * 4);
 #pragma unroll
         for (int w = 0; w < 4; ++w)
 #pragma unroll
@@ -233,10 +244,13 @@ __global__ __launch_bounds__(kRWaves * 64) void gemm_rows_kernel(
       }
     });
     if (more) {
-      __syncthreads();                                           // everybody is done with super-group sg
-      put_x(sg + 1);
-      if (sg + 2 < sg_end) load_x(sg + 2);
-      __syncthreads();
+      __syncthreads();                                           // everybody is done with super-group sg (and, with two
+                                                                 // buffers, has staged its part of the next one)
+      if (!DB) {
+        put_x(sg + 1);
+        if (sg + 2 < sg_end) load_x(sg + 2);
+        __syncthreads();
+      }
 #pragma unroll
       for (int r = 0; r < R; ++r)
 #pragma unroll
