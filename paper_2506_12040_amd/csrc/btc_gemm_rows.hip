@@ -1,6 +1,6 @@
 // 17..64 activation rows (small-M btc_gemm), chunk length 10, 7..10 index bits: the operand scheme
 // of the decode engine (a table entry in LDS IS the A operand of MFMA 16x16x32, chunk-aligned
-// permutation of the contraction index: see btc_gemv_mfma.hip), with NB = 2 or 4 blocks of 16
+// permutation of the contraction index: see btc_gemv_mfma.hip), with NB = 2, 3 or 4 blocks of 16
 // activation rows as B operands.  An A operand read from the table is used for NB MFMAs.
 //
 // A workgroup of 16 waves owns 256 weight rows (one block of 16 per wave; two blocks per wave
@@ -288,7 +288,7 @@ __global__ __launch_bounds__(kRWaves * 64) void gemm_rows_kernel(
 }
 
 struct RowsPlan {
-  int nb;          // blocks of 16 activation rows: 2 or 4
+  int nb;          // blocks of 16 activation rows: 2, 3 or 4
   int n_rt;        // row tiles (256 weight rows)
   int n_cs;        // column shares
   int sg_per_cs;
@@ -297,7 +297,7 @@ struct RowsPlan {
 static RowsPlan make_rows_plan(const Dims& d, int M) {
   const int sgs = (d.nchunks + kSG - 1) / kSG;
   RowsPlan p;
-  p.nb = M <= 32 ? 2 : 4;
+  p.nb = M <= 32 ? 2 : M <= 48 ? 3 : 4;
   p.n_rt = (d.out + kRowsPerWg - 1) / kRowsPerWg;
   int n_cs = (256 + p.n_rt - 1) / p.n_rt;                        // about one workgroup per compute unit
   if (n_cs > sgs) n_cs = sgs;
@@ -331,6 +331,10 @@ static btc_status launch_rows_b(hipStream_t q, const Dims& d, const RowsPlan& pl
     if (is_bf16) return launch_rows<B, 2, true>(q, d, pl, packed, codebook, X, M, part, xpart, n_rb);
     return launch_rows<B, 2, false>(q, d, pl, packed, codebook, X, M, part, xpart, n_rb);
   }
+  if (pl.nb == 3) {
+    if (is_bf16) return launch_rows<B, 3, true>(q, d, pl, packed, codebook, X, M, part, xpart, n_rb);
+    return launch_rows<B, 3, false>(q, d, pl, packed, codebook, X, M, part, xpart, n_rb);
+  }
   if (is_bf16) return launch_rows<B, 4, true>(q, d, pl, packed, codebook, X, M, part, xpart, n_rb);
   return launch_rows<B, 4, false>(q, d, pl, packed, codebook, X, M, part, xpart, n_rb);
 }
@@ -356,7 +360,7 @@ size_t gemm_rows_workspace_bytes(const Dims& d, int M) {
 // stream; what grows with the number of activation rows).
 double gemm_rows_estimate_us(const Dims& d, int M) {
   const double bytes = (double)d.out * d.wpr * 4;
-  return M <= 32 ? 14.3 + 0.87e-6 * bytes : 21.2 + 1.45e-6 * bytes;
+  return M <= 32 ? 12.3 + 0.7e-6 * bytes : M <= 48 ? 13.9 + 1.07e-6 * bytes : 15.4 + 1.48e-6 * bytes;
 }
 
 btc_status gemm_rows(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook, const float* alpha,
