@@ -315,7 +315,7 @@ def main():
                 us = time_gemv(o_, i_, v_, K_, M, reps_target=40)["us_per_call"]
                 row[tag] = dict(us=us, speedup_over_fp16=round(dense_us / us, 2))
             mlp[f"M{M}"] = row
-        for M in (32, 64, 128, 256, 512, 2048):            # btc_gemm, bf16 activations
+        for M in (32, 64, 96, 128, 256, 512, 2048):        # btc_gemm, bf16 activations
             dense_us = time_dense(o_, i_, M, torch.bfloat16)
             us = time_gemm(o_, i_, 10, 256, M)
             mlp[f"M{M}"] = {"torch_bf16_us": round(dense_us, 1),

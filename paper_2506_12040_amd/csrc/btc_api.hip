@@ -59,6 +59,10 @@ size_t btc_workspace_bytes(const btc_shape* s, int32_t rows, int is_gemm) {
     // partial sums of a call that the tiled contraction kernel splits along k
     if (btc::gemm_tiled_covers(d, rows)) need = std::max(need, btc::gemm_tiled_workspace_bytes(d, rows));
     if (btc::gemm_rows_covers(d, rows)) need = std::max(need, btc::gemm_rows_workspace_bytes(d, rows));
+    if (rows > 64 && rows <= 128 && btc::gemm_rows_covers(d, 64)) {   // may run as 64 rows + the rest
+      need = std::max(need, btc::gemm_rows_workspace_bytes(d, 64));
+      if (btc::gemv_mfma_covers(d, 16)) need = std::max(need, btc::gemv_mfma_workspace_bytes(d, 16));
+    }
     // a call with few rows may go to the decode engine, 16 rows at a time
     if (rows <= 64 && btc::gemv_mfma_covers(d, rows < 16 ? rows : 16))
       need = std::max(need, btc::gemv_mfma_workspace_bytes(d, rows < 16 ? rows : 16));

@@ -78,6 +78,24 @@ btc_status btc_gemm(void* stream, const btc_shape* s, const uint32_t* packed, co
   if (gemm_rows_covers(d, M) &&
       gemm_rows_estimate_us(d, M) < (gemm_tiled_covers(d, M) ? gemm_tiled_estimate_us(d, M) : 1e30))
     return gemm_rows(q, d, packed, codebook, alpha, mu, X, is_bf16, M, Y, (int)y_dtype, workspace);
+  // 65..128 rows on a large matrix (6 MB of indices or more): two passes of that kernel (64 rows, then
+  // the rest) still beat a 256-row tile that is half empty (8192 x 28672, M = 96: 77 against 118 us); the
+  // estimates decide.
+  if (M > 64 && M <= 128 && (long long)d.out * d.wpr * 4 >= (6LL << 20) && gemm_rows_covers(d, 64) &&
+      gemm_tiled_covers(d, M)) {
+    const int rest = M - 64;
+    const double est = gemm_rows_estimate_us(d, 64) +
+                       (rest >= 17 ? gemm_rows_estimate_us(d, rest) : gemv_mfma_estimate_us(d, rest));
+    if (1.1 * est < gemm_tiled_estimate_us(d, M)) {
+      const size_t ysz = y_dtype == BTC_F32 ? 4 : 2;
+      st = gemm_rows(q, d, packed, codebook, alpha, mu, X, is_bf16, 64, Y, (int)y_dtype, workspace);
+      if (st != BTC_OK) return st;
+      const void* X2 = (const char*)X + (size_t)64 * d.in * 2;
+      void* Y2 = (char*)Y + (size_t)64 * d.out * ysz;
+      if (rest >= 17) return gemm_rows(q, d, packed, codebook, alpha, mu, X2, is_bf16, rest, Y2, (int)y_dtype, workspace);
+      return gemv_mfma(q, d, packed, codebook, alpha, mu, X2, is_bf16, rest, Y2, (int)y_dtype, workspace);
+    }
+  }
   // Few activation rows: decoding dominates, and the decode engine of btc_gemv (table entries
   // that are matrix-core operands, 16 rows per pass) is several times quicker than a 256-row tile
   // that is mostly empty.  Up to 64 rows are served in blocks of 16.

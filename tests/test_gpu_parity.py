@@ -220,6 +220,8 @@ GEMM_SMALL = [
     # tiles and column shares, ragged everything, every index width
     (700, 5128, 10, 512, 33, "bf16"), (1030, 2570, 10, 256, 64, "f16"), (300, 13824, 10, 128, 17, "bf16"),
     (261, 2082, 10, 1024, 32, "f16"), (77, 650, 10, 512, 63, "bf16"),
+    # 65..128 rows on a matrix of more than 6 MB: 64 rows, then the rest (again that kernel, or the decode engine)
+    (5200, 12800, 10, 512, 70, "bf16"), (5200, 12800, 10, 512, 100, "f16"),
 ]
 
 
