@@ -1,6 +1,8 @@
-"""GPU parity on seeded random shapes: the engines that feed table entries straight into matrix-core
-operands (2..16 activation rows, one row on wide matrices, btc_gemm with up to 64 rows) against the CPU
-oracle on sampled output rows.  Shapes are drawn so that ragged row tiles, ragged last chunks, activation rows
+"""GPU parity on seeded random shapes against the CPU oracle on sampled output rows.  First set: the engines
+that feed table entries straight into matrix-core operands (2..16 activation rows, one row on wide matrices,
+btc_gemm with up to 64 rows).  Second set: every other route -- 65..128 rows on large matrices, the tiled
+kernel at any M, one row with arbitrary chunk length and codebook size, btc_gemm on settings only the generic
+kernel covers.  Shapes are drawn so that ragged row tiles, ragged last chunks, activation rows
 that are not 16-byte aligned and every supported index width come up; the tolerances are those of the other
 parity tests."""
 import numpy as np
@@ -35,6 +37,31 @@ def _cases(seed, n):
     return cases
 
 
+def _wide_cases(seed, n):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        mode = int(rng.integers(0, 4))
+        s = int(rng.integers(1, 1000))
+        xd = "bf16" if rng.random() < 0.6 else "f16"
+        if mode == 0:      # 65..128 rows, 6 MB of indices or more
+            cases.append(("gemm", s, int(rng.integers(3000, 8200)), 16 * int(rng.integers(400, 1000)), 10,
+                          int(rng.choice([128, 256, 512, 1024])), int(rng.integers(65, 129)), xd))
+        elif mode == 1:    # tiled kernel, ragged M and out
+            cases.append(("gemm", s, int(rng.integers(1, 3000)), 16 * int(rng.integers(40, 600)), 10,
+                          int(rng.choice([100, 256, 512, 1024])), int(rng.integers(129, 700)), xd))
+        elif mode == 2:    # one row, any chunk length and codebook size
+            v = int(rng.choice([4, 7, 8, 9, 10, 12, 16]))
+            K = int(rng.integers(2, min(2 ** v, 4096) + 1))
+            cases.append(("gemv", s, int(rng.integers(1, 9000)), int(rng.integers(20, 15000)), v, K, 1, "f16"))
+        else:              # btc_gemm outside the tuned settings
+            v = int(rng.choice([4, 8, 9, 12]))
+            K = int(rng.integers(2, min(2 ** v, 2048) + 1))
+            cases.append(("gemm", s, int(rng.integers(1, 1500)), int(rng.integers(20, 4000)), v, K,
+                          int(rng.integers(1, 200)), "bf16"))
+    return cases
+
+
 @pytest.fixture(scope="module")
 def G():
     import torch
@@ -43,7 +70,7 @@ def G():
     return gpu_util
 
 
-@pytest.mark.parametrize("kind,seed,out,n_in,v,K,rows,xd", _cases(20250612, 28))
+@pytest.mark.parametrize("kind,seed,out,n_in,v,K,rows,xd", _cases(20250612, 28) + _wide_cases(20250613, 24))
 def test_random_shape(G, oracle, kind, seed, out, n_in, v, K, rows, xd):
     B = G.B
     print(f"random {kind} seed={seed} out={out} in={n_in} v={v} K={K} rows={rows} {xd}", flush=True)
