@@ -183,3 +183,21 @@ def config_cases(cfg: int) -> list[dict]:
     for c in cases:
         c.setdefault("seed", 0)
     return cases
+
+
+def draw_transform(seed: int, n1: int, n2: int, perturb: float = 0.02):
+    """A synthetic transformation pair for an activation row of n1*n2 channels: sign bits of the diagonal
+    sign matrix (uint32[ceil(n/32)], bit k set => sigma_k = +1, unused tail bits zero) and the two
+    Kronecker factors P1 [n1][n1], P2 [n2][n2] (float32, row-major).  The factors stand in for learned
+    invertible matrices: a random orthogonal matrix (QR of a Gaussian one) plus N(0, perturb) noise."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    n = n1 * n2
+    sigma = rng.integers(0, 2, size=n, dtype=np.uint32)
+    bits = np.zeros((n + 31) // 32, dtype=np.uint32)
+    for k in np.nonzero(sigma)[0]:
+        bits[k >> 5] |= np.uint32(1) << np.uint32(k & 31)
+    factors = []
+    for m in (n1, n2):
+        q, _ = np.linalg.qr(rng.standard_normal((m, m)))
+        factors.append((q + perturb * rng.standard_normal((m, m))).astype(np.float32))
+    return bits, factors[0], factors[1]

@@ -60,6 +60,8 @@ def lib() -> ctypes.CDLL:
                                              c_vp, c_long, c_vp]
         L.btc_oracle_matmul.restype = None
         L.btc_oracle_matmul.argtypes = [c_vp, c_long, c_long, c_vp, c_long, c_vp]
+        L.btc_oracle_transform.restype = None
+        L.btc_oracle_transform.argtypes = [c_vp, c_long, c_long, c_long, c_vp, c_vp, c_vp, c_vp]
         _lib = L
     return _lib
 
@@ -170,3 +172,17 @@ def linear(packed, codebook, alpha, mu, x_bits, n_in: int, v: int, K: int,
     W = materialise(packed, codebook, alpha, mu, n_in, v, K, rows)
     X = widen(np.atleast_2d(x_bits), x_kind)
     return matmul(W, X)
+
+
+def transform(x_bits, sign_bits, P1, P2, x_kind: str = "f16") -> np.ndarray:
+    """The online activation transform X <- X . diag(sigma) . (P1 kron P2); returns float64 [M][n1*n2]."""
+    X = widen(np.atleast_2d(x_bits), x_kind)
+    P1 = _c(P1, np.float32)
+    P2 = _c(P2, np.float32)
+    n1, n2 = P1.shape[0], P2.shape[0]
+    assert P1.shape == (n1, n1) and P2.shape == (n2, n2) and X.shape[1] == n1 * n2
+    sign_bits = _c(sign_bits, np.uint32)
+    assert sign_bits.shape == ((n1 * n2 + 31) // 32,)
+    Y = np.empty(X.shape, dtype=np.float64)
+    lib().btc_oracle_transform(_p(X), X.shape[0], n1, n2, _p(sign_bits), _p(P1), _p(P2), _p(Y))
+    return Y

@@ -24,6 +24,12 @@
 // Columns k >= in do not exist: surplus positions of the last chunk's pattern
 // are never touched.
 //
+// Also here: the online activation transform that sits in front of the layer
+// at inference (section "Learnable Transformation"): X <- X T, T = D P with
+// D = diag(sigma), sigma_k = +-1, and P = P1 (x) P2 a Kronecker product.  It
+// is written out as the definition too: the n x n matrix T is formed entry by
+// entry and the activation row multiplied with it (pins: tests/test_transform_pins.py).
+//
 // Pins (tests/test_oracle_pins.py): brute force from a byte view of the
 // stream, full-codebook dense sign matrix, ones vector -> popcount integers,
 // linearity, affine split in (alpha, mu), XNOR-popcount closed form for +-1
@@ -176,6 +182,37 @@ void btc_oracle_matmul(const double* W, long nrows, long in,
       for (long k = 0; k < in; ++k) acc += w[k] * x[k];
       Y[m * nrows + r] = acc;
     }
+  }
+}
+
+// Online activation transform, section "Learnable Transformation" (transformation
+// pair T = D P, P = P1 (x) P2) and "Integration into Transformer Architecture"
+// (X <- X T):
+//   T[i][j] = sigma_i * P1[i1][j1] * P2[i2][j2],  i = i1*n2 + i2,  j = j1*n2 + j2
+//   Y[m][j] = sum_i X[m][i] * T[i][j]
+// sigma_i = +1 where bit (i & 31) of sign_bits[i >> 5] is set, else -1 (the
+// same sign<->bit map as the codebook).  X is fp64 [M][n] (already widened),
+// P1 is fp32 [n1][n1], P2 is fp32 [n2][n2], both row-major; Y fp64 [M][n].
+// T is formed one column at a time (n doubles), never blocked or factored.
+void btc_oracle_transform(const double* X, long M, long n1, long n2, const uint32_t* sign_bits,
+                          const float* P1, const float* P2, double* Y) {
+  const long n = n1 * n2;
+#pragma omp parallel for schedule(static)
+  for (long j = 0; j < n; ++j) {
+    const long j1 = j / n2, j2 = j % n2;
+    double* col = new double[n];
+    for (long i = 0; i < n; ++i) {
+      const long i1 = i / n2, i2 = i % n2;
+      const double sigma = ((sign_bits[i >> 5] >> (i & 31)) & 1u) ? 1.0 : -1.0;
+      col[i] = sigma * ((double)P1[i1 * n1 + j1] * (double)P2[i2 * n2 + j2]);
+    }
+    for (long m = 0; m < M; ++m) {
+      const double* x = X + m * n;
+      double acc = 0.0;
+      for (long i = 0; i < n; ++i) acc += x[i] * col[i];
+      Y[m * n + j] = acc;
+    }
+    delete[] col;
   }
 }
 
