@@ -126,6 +126,25 @@ btc_status btc_gemm(void* stream, const btc_shape* s, const uint32_t* packed,
                     const void* X, btc_dtype x_dtype, int32_t M, void* Y, btc_dtype y_dtype,
                     void* workspace, size_t workspace_bytes);
 
+/* Online activation transform in front of the layer (section "Learnable
+ * Transformation": transformation pair T = D P, D = diag(sigma) a diagonal sign
+ * matrix, P = P1 (x) P2 a Kronecker product; "Integration into Transformer
+ * Architecture": X <- X T at inference, the weights hold T^-1):
+ *   Y[m][j1*n2 + j2] = sum_{i1,i2} sigma[i] * X[m][i] * P1[i1][j1] * P2[i2][j2],  i = i1*n2 + i2
+ *   X         : [M][n1*n2] of x_dtype (BTC_F16 or BTC_BF16), M >= 1
+ *   sign_bits : uint32 [ceil(n1*n2 / 32)], bit (i & 31) of word (i >> 5) set => sigma[i] = +1,
+ *               clear => -1 (the sign<->bit map of the codebook)
+ *   P1, P2    : float [n1][n1], [n2][n2], row-major; n1 <= 128, n2 <= 256
+ *   Y         : [M][n1*n2] of y_dtype (BTC_F16, BTC_BF16 or BTC_F32; round to nearest even)
+ * All pointers are device memory owned by the caller, 16-byte aligned; X and Y
+ * must not overlap.  fp32 accumulation in a fixed order (deterministic).  No
+ * workspace.  Enqueues and returns.  Errors: BTC_ERR_NULL, _SHAPE (non-positive
+ * sizes), _UNSUPPORTED (n1, n2 or a dtype outside the ranges above, X == Y),
+ * _ALIGN, _HIP (launch failed). */
+btc_status btc_transform(void* stream, const void* X, btc_dtype x_dtype, int32_t M, int32_t n1,
+                         int32_t n2, const uint32_t* sign_bits, const float* P1, const float* P2,
+                         void* Y, btc_dtype y_dtype);
+
 /* Host. Static string for a status code. */
 const char* btc_status_str(btc_status st);
 

@@ -55,6 +55,8 @@ def lib() -> ctypes.CDLL:
         L.btc_gemv.argtypes = [vp, sp, vp, vp, vp, vp, vp, i32, vp, ctypes.c_int, vp, sz]
         L.btc_gemm.restype = ctypes.c_int
         L.btc_gemm.argtypes = [vp, sp, vp, vp, vp, vp, vp, ctypes.c_int, i32, vp, ctypes.c_int, vp, sz]
+        L.btc_transform.restype = ctypes.c_int
+        L.btc_transform.argtypes = [vp, vp, ctypes.c_int, i32, i32, i32, vp, vp, vp, vp, ctypes.c_int]
         L.btc_status_str.restype = ctypes.c_char_p
         L.btc_status_str.argtypes = [ctypes.c_int]
         _lib = L
@@ -128,3 +130,8 @@ def btc_gemm(s: btc_shape, packed, codebook, alpha, mu, X, x_dtype: int, M: int,
     wb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
     _check(lib().btc_gemm(_stream(stream), ctypes.byref(s), _ptr(packed), _ptr(codebook), _ptr(alpha), _ptr(mu),
                           _ptr(X), x_dtype, M, _ptr(Y), y_dtype, _ptr(workspace), wb), "btc_gemm")
+
+
+def btc_transform(X, x_dtype: int, M: int, n1: int, n2: int, sign_bits, P1, P2, Y, y_dtype: int, stream=None) -> None:
+    _check(lib().btc_transform(_stream(stream), _ptr(X), x_dtype, M, n1, n2, _ptr(sign_bits), _ptr(P1), _ptr(P2),
+                               _ptr(Y), y_dtype), "btc_transform")

@@ -98,6 +98,14 @@ def test_argument_checks_need_no_gpu(B):
     assert L.btc_pack(None, sp, None, fake, fake, 16) == E.BTC_ERR_NULL
     assert L.btc_unpack(None, sp, fake, odd) == E.BTC_ERR_ALIGN
     assert L.btc_unpack(None, None, fake, fake) == E.BTC_ERR_NULL
+    assert L.btc_transform(None, None, E.BTC_F16, 1, 4, 4, fake, fake, fake, fake, E.BTC_F16) == E.BTC_ERR_NULL
+    other = ctypes.c_void_p(0x2000)
+    assert L.btc_transform(None, fake, E.BTC_F16, 0, 4, 4, fake, fake, fake, other, E.BTC_F16) == E.BTC_ERR_SHAPE
+    assert L.btc_transform(None, fake, E.BTC_F16, 1, 129, 4, fake, fake, fake, other, E.BTC_F16) == E.BTC_ERR_UNSUPPORTED
+    assert L.btc_transform(None, fake, E.BTC_F16, 1, 4, 257, fake, fake, fake, other, E.BTC_F16) == E.BTC_ERR_UNSUPPORTED
+    assert L.btc_transform(None, fake, E.BTC_F32, 1, 4, 4, fake, fake, fake, other, E.BTC_F16) == E.BTC_ERR_UNSUPPORTED
+    assert L.btc_transform(None, fake, E.BTC_F16, 1, 4, 4, fake, fake, fake, fake, E.BTC_F16) == E.BTC_ERR_UNSUPPORTED
+    assert L.btc_transform(None, fake, E.BTC_F16, 1, 4, 4, fake, odd, fake, other, E.BTC_F16) == E.BTC_ERR_ALIGN
     t = B.btc_shape_init(64, 100, 10, 512)
     t.words_per_row += 1                 # a shape edited after btc_shape_init
     assert L.btc_unpack(None, ctypes.byref(t), fake, fake) == E.BTC_ERR_SHAPE
