@@ -13,10 +13,13 @@
 // kCB columns j2 of ALL rows j1 is computed by one workgroup without help from any other:
 //   stage 1:  Y1[i1][jj] = sum_i2 sigma x[i1 n2 + i2] P2[i2][j0 + jj]      (n1 x kCB values)
 //   stage 2:  Z[j1][jj]  = sum_i1 P1[i1][j1] Y1[i1][jj]
-// The workgroup keeps P1, its slice of P2 and the sign bits in LDS and walks over the rows of
-// X dealt to it; a row is staged with its signs applied (a flip of the sign bit: exact).
-// fp32 accumulation in ascending i2, then ascending i1: deterministic.  One activation row
-// (decode) is n2 / kCB workgroups whose chain is: loads, stage 1, stage 2, store.
+// The workgroup keeps P1 and its slice of P2 in LDS and walks over the rows of X dealt to it; a
+// row is staged with its signs applied (a flip of the sign bit: exact).  fp32 accumulation in a
+// fixed order: deterministic.  Two shapes of the same kernel: for a few rows (decode) the call is
+// a chain of latencies, so a workgroup has 1024 threads and every dot product of both stages is
+// cut into KS = 4 pieces whose sums meet in LDS; for many rows (prefill) 256 threads, whole dot
+// products, four columns per thread, and the rows are dealt to about five workgroups per compute
+// unit.  Every global load of a phase is issued before the first one is used.
 #include <hip/hip_fp16.h>
 
 #include "btc_internal.h"
@@ -31,18 +34,18 @@ constexpr int kMaxN2 = 256;
 
 struct Layout {                // byte offsets into dynamic LDS
   int rs;                      // staged row stride in 16-bit elements (even; rs / 2 odd: rows start in different banks)
-  int p1, p2, y1, sg, total;
+  int p1, p2, y1, part, total;
 };
 
-static Layout layout_of(int n1, int n2) {
+static Layout layout_of(int n1, int n2, int KS) {
   Layout L;
   L.rs = 2 * (((n2 + 1) / 2) | 1);
   auto up16 = [](int b) { return (b + 15) & ~15; };
   L.p1 = up16(n1 * L.rs * 2);
   L.p2 = L.p1 + up16(n1 * n1 * 4);
-  L.y1 = L.p2 + up16(n2 * kCB * 4);
-  L.sg = L.y1 + up16(n1 * kCB * 4);
-  L.total = L.sg + up16(((n1 * n2 + 31) / 32) * 4);
+  L.y1 = L.p2 + up16((n2 + KS) * kCB * 4);
+  L.part = L.y1 + up16(n1 * kCB * 4);
+  L.total = L.part + (KS > 1 ? up16(KS * n1 * kCB * 4) : 0);
   return L;
 }
 
@@ -64,78 +67,190 @@ __device__ __forceinline__ void store_out(void* Y, size_t at, float v, int y_dty
   }
 }
 
-template <bool BF16>
-__global__ __launch_bounds__(kThreads) void transform_kernel(const uint16_t* __restrict__ X, int M, int n1, int n2,
-                                                            const uint32_t* __restrict__ sign_bits,
-                                                            const float* __restrict__ P1,
-                                                            const float* __restrict__ P2, void* __restrict__ Y,
-                                                            int y_dtype, Layout L) {
+// KS: pieces per dot product (threads = 256 KS); CPI: columns per work item.
+template <bool BF16, int KS, int CPI>
+__global__ __launch_bounds__(kThreads * KS) void transform_kernel(const uint16_t* __restrict__ X, int M, int n1, int n2,
+                                                                 const uint32_t* __restrict__ sign_bits,
+                                                                 const float* __restrict__ P1,
+                                                                 const float* __restrict__ P2, void* __restrict__ Y,
+                                                                 int y_dtype, Layout L) {
+  constexpr int T = kThreads * KS;
+  constexpr int IPR = kCB / CPI;             // work items per row index
   extern __shared__ __align__(16) unsigned char smem[];
   uint16_t* xs = (uint16_t*)smem;
   float* p1s = (float*)(smem + L.p1);
-  float* p2s = (float*)(smem + L.p2);
-  float* y1 = (float*)(smem + L.y1);
-  uint32_t* sg = (uint32_t*)(smem + L.sg);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  float* p2s = (float*)(smem + L.p2);        // row i2 at i2 * kCB + (i2 / len2) * kCB: a pad per piece, against bank conflicts
+  float* y1 = (float*)(smem + L.y1);         // [n1][kCB]
+  float* part = (float*)(smem + L.part);     // [KS][n1][kCB] partial sums of either stage (KS > 1)
+  const int tid = threadIdx.x;
   const int n = n1 * n2;
   const int j0 = blockIdx.x * kCB;
   const int ncol = min(kCB, n2 - j0);
+  const int len2 = (((n2 + KS - 1) / KS) + 1) & ~1;   // piece of a stage-1 dot product (even)
+  const int len1 = (n1 + KS - 1) / KS;                // piece of a stage-2 dot product
+  const float rcp_n2 = 1.0f / (float)n2;
+  const bool x_vec = (n2 & 7) == 0;          // a group of 8 channels stays inside one row of the n1 x n2 view, and
+                                             // rows of X start 16-byte aligned
 
-  // ---- once per workgroup: P1, columns j0 .. j0 + kCB - 1 of P2 (zero past the last column), sign words
-  for (int t = tid; t < n1 * n1; t += kThreads) p1s[t] = P1[t];
-  for (int t = tid; t < n2 * kCB; t += kThreads) {
-    const int i2 = t / kCB, jj = t - i2 * kCB;
-    p2s[t] = jj < ncol ? P2[(size_t)i2 * n2 + j0 + jj] : 0.f;
-  }
-  for (int t = tid; t < (n + 31) / 32; t += kThreads) sg[t] = sign_bits[t];
-
-  const int items = n1 * (kCB / 2);          // an item: one row index and a pair of columns
-  for (int m = blockIdx.y; m < M; m += gridDim.y) {
-    __syncthreads();                         // sign words are there; the previous row's readers are done
-    // ---- row m with its signs applied -> LDS, one wave per row i1 of the n1 x n2 view
+  // A row of X with its signs applied -> LDS (row i1 of the n1 x n2 view at xs + i1 * rs).
+  auto stage_x = [&](int m) {
     const uint16_t* xrow = X + (size_t)m * n;
-    for (int i1 = wave; i1 < n1; i1 += kThreads / 64) {
-      for (int i2 = lane; i2 < n2; i2 += 64) {
-        const int k = i1 * n2 + i2;
-        const uint32_t plus = (sg[k >> 5] >> (k & 31)) & 1u;
+    if (x_vec) {
+      constexpr int U = 4;
+      const int groups = n >> 3;
+      for (int base = tid; base < groups; base += T * U) {
+        uint4 v[U];
+        uint32_t sw[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int g = base + u * T;
+          if (g < groups) {
+            v[u] = *(const uint4*)(xrow + 8 * g);
+            sw[u] = sign_bits[g >> 2];
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int g = base + u * T;
+          if (g < groups) {
+            const int k = 8 * g;
+            const int i1 = (int)(((float)k + 0.5f) * rcp_n2);     // exact for k < 2^20
+            const int i2 = k - i1 * n2;
+            const uint32_t minus = ~(sw[u] >> (k & 31)) & 0xFFu;    // bit e set: channel k + e is flipped
+            uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              w[e] ^= (((minus >> (2 * e)) & 1u) << 15) | (((minus >> (2 * e + 1)) & 1u) << 31);
+            uint32_t* dst = (uint32_t*)(xs + i1 * L.rs + i2);       // 4-byte aligned (rs and i2 are even)
+            dst[0] = w[0]; dst[1] = w[1]; dst[2] = w[2]; dst[3] = w[3];
+          }
+        }
+      }
+    } else {
+      for (int k = tid; k < n; k += T) {
+        const int i1 = (int)(((float)k + 0.5f) * rcp_n2);
+        const int i2 = k - i1 * n2;
+        const uint32_t plus = (sign_bits[k >> 5] >> (k & 31)) & 1u;
         xs[i1 * L.rs + i2] = (uint16_t)(xrow[k] ^ (plus ? 0u : 0x8000u));
       }
     }
-    __syncthreads();
-    // ---- stage 1
-    for (int it = tid; it < items; it += kThreads) {
-      const int i1 = it >> 2, jp = (it & 3) * 2;
-      const uint16_t* xr = xs + i1 * L.rs;
-      float a0 = 0.f, a1 = 0.f;
-      int i2 = 0;
-      for (; i2 + 1 < n2; i2 += 2) {
-        const uint32_t pr = *(const uint32_t*)(xr + i2);
-        const float x0 = widen<BF16>(pr & 0xFFFFu), x1 = widen<BF16>(pr >> 16);
-        const float2 p = *(const float2*)(p2s + i2 * kCB + jp);
-        const float2 q = *(const float2*)(p2s + (i2 + 1) * kCB + jp);
-        a0 = fmaf(x0, p.x, a0); a1 = fmaf(x0, p.y, a1);
-        a0 = fmaf(x1, q.x, a0); a1 = fmaf(x1, q.y, a1);
-      }
-      if (i2 < n2) {
-        const float x0 = widen<BF16>(xr[i2]);
-        const float2 p = *(const float2*)(p2s + i2 * kCB + jp);
-        a0 = fmaf(x0, p.x, a0); a1 = fmaf(x0, p.y, a1);
-      }
-      *(float2*)(y1 + i1 * kCB + jp) = make_float2(a0, a1);
+  };
+
+  // ---- the first row's activations are requested first, then the factors (once per workgroup)
+  stage_x(blockIdx.y);
+  if ((n2 & 3) == 0) {                       // columns j0 .. j0 + 7 of a row of P2 are two aligned 16-byte pieces
+    for (int t = tid; t < 2 * n2; t += T) {
+      const int i2 = t >> 1, h = t & 1;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (j0 + 4 * h < n2) v = *(const float4*)(P2 + (size_t)i2 * n2 + j0 + 4 * h);
+      *(float4*)(p2s + i2 * kCB + (i2 / len2) * kCB + 4 * h) = v;
+    }
+  } else {
+    for (int t = tid; t < n2 * kCB; t += T) {
+      const int i2 = t / kCB, jj = t - i2 * kCB;
+      p2s[i2 * kCB + (i2 / len2) * kCB + jj] = jj < ncol ? P2[(size_t)i2 * n2 + j0 + jj] : 0.f;
+    }
+  }
+  if (((n1 * n1) & 3) == 0) {
+    constexpr int U = 4;
+    const int quads = (n1 * n1) >> 2;
+    for (int base = tid; base < quads; base += T * U) {
+      float4 v[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (base + u * T < quads) v[u] = *(const float4*)(P1 + 4 * (size_t)(base + u * T));
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (base + u * T < quads) *(float4*)(p1s + 4 * (base + u * T)) = v[u];
+    }
+  } else {
+    for (int t = tid; t < n1 * n1; t += T) p1s[t] = P1[t];
+  }
+
+  const int items = n1 * IPR * KS;           // item = (row index, group of CPI columns, piece)
+  for (int m = blockIdx.y; m < M; m += gridDim.y) {
+    if (m != (int)blockIdx.y) {
+      __syncthreads();                       // the previous row's readers are done
+      stage_x(m);
     }
     __syncthreads();
-    // ---- stage 2 and the store
-    for (int it = tid; it < items; it += kThreads) {
-      const int j1 = it >> 2, jp = (it & 3) * 2;
-      float a0 = 0.f, a1 = 0.f;
-      for (int i1 = 0; i1 < n1; ++i1) {
-        const float p = p1s[i1 * n1 + j1];
-        const float2 yv = *(const float2*)(y1 + i1 * kCB + jp);
-        a0 = fmaf(p, yv.x, a0); a1 = fmaf(p, yv.y, a1);
+    // ---- stage 1: piece ks of  Y1[i1][c0 .. c0 + CPI - 1]
+    for (int it = tid; it < items; it += T) {
+      const int ks = it % KS, rest = it / KS;
+      const int c0 = (rest % IPR) * CPI, i1 = rest / IPR;
+      const uint16_t* xr = xs + i1 * L.rs;
+      const float* pc = p2s + ks * kCB + c0;
+      const int lo = ks * len2, hi = min(n2, lo + len2);
+      float a[CPI];
+#pragma unroll
+      for (int c = 0; c < CPI; ++c) a[c] = 0.f;
+      int i2 = lo;
+      for (; i2 + 1 < hi; i2 += 2) {
+        const uint32_t pr = *(const uint32_t*)(xr + i2);
+        const float x0 = widen<BF16>(pr & 0xFFFFu), x1 = widen<BF16>(pr >> 16);
+        float p[CPI], q[CPI];
+        if constexpr (CPI == 4) {
+          const float4 pv = *(const float4*)(pc + i2 * kCB), qv = *(const float4*)(pc + (i2 + 1) * kCB);
+          p[0] = pv.x; p[1] = pv.y; p[2] = pv.z; p[3] = pv.w;
+          q[0] = qv.x; q[1] = qv.y; q[2] = qv.z; q[3] = qv.w;
+        } else {
+          const float2 pv = *(const float2*)(pc + i2 * kCB), qv = *(const float2*)(pc + (i2 + 1) * kCB);
+          p[0] = pv.x; p[1] = pv.y; q[0] = qv.x; q[1] = qv.y;
+        }
+#pragma unroll
+        for (int c = 0; c < CPI; ++c) a[c] = fmaf(x1, q[c], fmaf(x0, p[c], a[c]));
       }
-      const size_t at = (size_t)m * n + (size_t)j1 * n2 + j0 + jp;
-      if (jp < ncol) store_out(Y, at, a0, y_dtype);
-      if (jp + 1 < ncol) store_out(Y, at + 1, a1, y_dtype);
+      if (i2 < hi) {
+        const float x0 = widen<BF16>(xr[i2]);
+#pragma unroll
+        for (int c = 0; c < CPI; ++c) a[c] = fmaf(x0, pc[i2 * kCB + c], a[c]);
+      }
+      float* dst = (KS > 1 ? part + ks * n1 * kCB : y1) + i1 * kCB + c0;
+#pragma unroll
+      for (int c = 0; c < CPI; ++c) dst[c] = a[c];
+    }
+    __syncthreads();
+    if constexpr (KS > 1) {                  // the pieces of a dot product are added in ascending order
+      for (int t = tid; t < n1 * kCB; t += T) {
+        float sum = part[t];
+#pragma unroll
+        for (int k = 1; k < KS; ++k) sum += part[k * n1 * kCB + t];
+        y1[t] = sum;
+      }
+      __syncthreads();
+    }
+    // ---- stage 2: piece ks of  Z[j1][c0 .. c0 + CPI - 1]
+    for (int it = tid; it < items; it += T) {
+      const int rest = it % (n1 * IPR), ks = it / (n1 * IPR);     // neighbouring lanes: neighbouring j1
+      const int j1 = rest % n1, c0 = (rest / n1) * CPI;
+      const int lo = ks * len1, hi = min(n1, lo + len1);
+      float a[CPI];
+#pragma unroll
+      for (int c = 0; c < CPI; ++c) a[c] = 0.f;
+      for (int i1 = lo; i1 < hi; ++i1) {
+        const float p = p1s[i1 * n1 + j1];
+#pragma unroll
+        for (int c = 0; c < CPI; ++c) a[c] = fmaf(p, y1[i1 * kCB + c0 + c], a[c]);
+      }
+      if constexpr (KS > 1) {
+#pragma unroll
+        for (int c = 0; c < CPI; ++c) part[ks * n1 * kCB + j1 * kCB + c0 + c] = a[c];
+      } else {
+        const size_t at = (size_t)m * n + (size_t)j1 * n2 + j0 + c0;
+#pragma unroll
+        for (int c = 0; c < CPI; ++c)
+          if (c0 + c < ncol) store_out(Y, at + c, a[c], y_dtype);
+      }
+    }
+    if constexpr (KS > 1) {
+      __syncthreads();
+      for (int t = tid; t < n1 * kCB; t += T) {
+        float sum = part[t];
+#pragma unroll
+        for (int k = 1; k < KS; ++k) sum += part[k * n1 * kCB + t];
+        const int j1 = t / kCB, jj = t - j1 * kCB;
+        if (jj < ncol) store_out(Y, (size_t)m * n + (size_t)j1 * n2 + j0 + jj, sum, y_dtype);
+      }
     }
   }
 }
@@ -157,27 +272,36 @@ btc_status btc_transform(void* stream, const void* X, btc_dtype x_dtype, int32_t
   if ((long long)M * n1 * n2 >= (1LL << 40)) return BTC_ERR_SHAPE;
   if (!aligned16(X) || !aligned16(sign_bits) || !aligned16(P1) || !aligned16(P2) || !aligned16(Y)) return BTC_ERR_ALIGN;
   if (X == Y) return BTC_ERR_UNSUPPORTED;    // workgroups read whole rows that others write slices of
-  const Layout L = layout_of(n1, n2);
   const int n_cb = (n2 + kCB - 1) / kCB;
-  int gy = 1280 / n_cb;                      // about five workgroups per compute unit share the rows
+  // A few rows: one workgroup of 1024 threads per (column block, row), dot products cut in four.
+  // Many rows: 256 threads, and the rows are dealt to about five workgroups per compute unit.
+  const bool few = (long long)M * n_cb <= 512;
+  const int KS = few ? 4 : 1;
+  const Layout L = layout_of(n1, n2, KS);
+  if (L.total > 160 * 1024 - 256) return BTC_ERR_UNSUPPORTED;
+  int gy = few ? M : 1280 / n_cb;
   if (gy < 1) gy = 1;
   if (gy > M) gy = M;
   hipStream_t q = (hipStream_t)stream;
-  static bool attr_set[2] = {false, false};  // one-time kernel attributes, not call state
-  const int bf = x_dtype == BTC_BF16;
-  if (!attr_set[bf]) {
-    const void* fn = bf ? (const void*)transform_kernel<true> : (const void*)transform_kernel<false>;
-    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256) != hipSuccess)
-      return BTC_ERR_HIP;
-    attr_set[bf] = true;
+  static bool attr_set = false;              // one-time kernel attributes, not call state
+  if (!attr_set) {
+    const void* fns[4] = {(const void*)transform_kernel<false, 4, 2>, (const void*)transform_kernel<true, 4, 2>,
+                          (const void*)transform_kernel<false, 1, 4>, (const void*)transform_kernel<true, 1, 4>};
+    for (const void* fn : fns)
+      if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256) != hipSuccess)
+        return BTC_ERR_HIP;
+    attr_set = true;
   }
+  const bool bf = x_dtype == BTC_BF16;
   const dim3 grid(n_cb, gy);
-  if (bf)
-    transform_kernel<true><<<grid, kThreads, L.total, q>>>((const uint16_t*)X, M, n1, n2, sign_bits, P1, P2, Y,
-                                                           (int)y_dtype, L);
-  else
-    transform_kernel<false><<<grid, kThreads, L.total, q>>>((const uint16_t*)X, M, n1, n2, sign_bits, P1, P2, Y,
-                                                            (int)y_dtype, L);
+  const uint16_t* Xp = (const uint16_t*)X;
+  if (few) {
+    if (bf) transform_kernel<true, 4, 2><<<grid, kThreads * 4, L.total, q>>>(Xp, M, n1, n2, sign_bits, P1, P2, Y, (int)y_dtype, L);
+    else transform_kernel<false, 4, 2><<<grid, kThreads * 4, L.total, q>>>(Xp, M, n1, n2, sign_bits, P1, P2, Y, (int)y_dtype, L);
+  } else {
+    if (bf) transform_kernel<true, 1, 4><<<grid, kThreads, L.total, q>>>(Xp, M, n1, n2, sign_bits, P1, P2, Y, (int)y_dtype, L);
+    else transform_kernel<false, 1, 4><<<grid, kThreads, L.total, q>>>(Xp, M, n1, n2, sign_bits, P1, P2, Y, (int)y_dtype, L);
+  }
   return launch_status();
 }
 
