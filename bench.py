@@ -35,6 +35,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+FP32_VALU_PEAK_TFLOPS = 157.3     # 256 compute units x 128 fp32 lanes x 2 flop x 2.4 GHz
 # HBM bytes of one step (7 calls) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
 # 256 MiB copy (profiles/gemv_13b_hbm_traffic.md): 37.1 MB fetched + 5.5 MB written.
 HBM_TRAFFIC_PER_STEP = 45.2e6
@@ -59,6 +60,7 @@ def main():
     ap.add_argument("--gemm-iters", type=int, default=10)
     ap.add_argument("--no-gemm", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-transform", action="store_true", help="skip the btc_transform timings")
     ap.add_argument("--no-other", action="store_true", help="skip the 7B (batch 1/4/16) and 70B decode sweeps")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run three 256 MiB device-to-device copies (reference for FETCH_SIZE/WRITE_SIZE) and exit")
@@ -356,6 +358,49 @@ def main():
             gemm[f"M{M}"] = dict(M=M, x_dtype="bf16", y_dtype="f32", per_shape=per, layer_tflops=round(tf, 1),
                                  frac_mfma_peak=round(tf / MFMA_BF16_PEAK_TFLOPS, 4))
 
+    # ---- the online activation transform in front of the layer (btc_transform), on the two input widths of
+    # the 13B layer: decode rows from a captured graph of 20 launches, prefill rows event-timed
+    transform = None
+    if not args.no_transform:
+        transform = {}
+        for (n1, n2) in [(64, 80), (108, 128)]:
+            n = n1 * n2
+            bits, P1, P2 = S.draw_transform(0, n1, n2)
+            bits_d = torch.from_numpy(bits.view(np.int32)).to(dev)
+            P1_d, P2_d = torch.from_numpy(P1).to(dev), torch.from_numpy(P2).to(dev)
+            row = {}
+            for (M, kind) in [(1, "f16"), (16, "f16"), (2048, "bf16")]:
+                tdt, bdt = (torch.float16, B.BTC_F16) if kind == "f16" else (torch.bfloat16, B.BTC_BF16)
+                X = torch.from_numpy(S.draw_x(np.random.Generator(np.random.PCG64(1)), M, n, kind).view(np.int16)).to(dev)
+                Y = torch.empty(M * n, dtype=tdt, device=dev)
+                call = lambda: B.btc_transform(X, bdt, M, n1, n2, bits_d, P1_d, P2_d, Y, bdt)
+                call()
+                torch.cuda.synchronize()
+                reps = 20 if M <= 16 else 5
+                if M <= 16:
+                    g = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g):
+                        for _ in range(reps):
+                            call()
+                    run = g.replay
+                else:
+                    def run():
+                        for _ in range(reps):
+                            call()
+                run()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(5):
+                    run()
+                e1.record()
+                torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / (5 * reps)
+                flop = 2.0 * M * n * (n1 + n2)
+                row[f"M{M}"] = dict(us=round(us, 2), tflops=round(flop / us / 1e6, 2),
+                                    frac_fp32_alu_peak=round(flop / us / 1e6 / FP32_VALU_PEAK_TFLOPS, 4))
+            transform[f"n={n} ({n1}x{n2})"] = row
+
     # ---- CPU oracle on the host cores, bounded sample of the same workload
     cpu = None
     if not args.no_cpu:
@@ -412,6 +457,7 @@ def main():
             "unit": "TFLOP/s", "frac": gemm[f"M{args.gemm_m}"]["frac_mfma_peak"], "traffic": None,
             "note": f"2*M*out*in flop of the 7 projections at M={args.gemm_m} / event-timed btc_gemm calls "
                     "(whole calls)"},
+        "transform": transform,
         "cpu_baseline": cpu,
         "setup_s": round(t_setup, 1),
     }

@@ -275,11 +275,14 @@ btc_status btc_transform(void* stream, const void* X, btc_dtype x_dtype, int32_t
   const int n_cb = (n2 + kCB - 1) / kCB;
   // A few rows: one workgroup of 1024 threads per (column block, row), dot products cut in four.
   // Many rows: 256 threads, and the rows are dealt to about five workgroups per compute unit.
+  // Large factors leave room for one workgroup per compute unit only: then the 1024-thread shape serves
+  // many rows too (16 waves per compute unit instead of 4).
   const bool few = (long long)M * n_cb <= 512;
-  const int KS = few ? 4 : 1;
+  const bool big = layout_of(n1, n2, 1).total > 48 * 1024;
+  const int KS = (few || big) ? 4 : 1;
   const Layout L = layout_of(n1, n2, KS);
   if (L.total > 160 * 1024 - 256) return BTC_ERR_UNSUPPORTED;
-  int gy = few ? M : 1280 / n_cb;
+  int gy = few ? M : big ? 256 / n_cb : 1280 / n_cb;
   if (gy < 1) gy = 1;
   if (gy > M) gy = M;
   hipStream_t q = (hipStream_t)stream;
@@ -295,7 +298,7 @@ btc_status btc_transform(void* stream, const void* X, btc_dtype x_dtype, int32_t
   const bool bf = x_dtype == BTC_BF16;
   const dim3 grid(n_cb, gy);
   const uint16_t* Xp = (const uint16_t*)X;
-  if (few) {
+  if (KS == 4) {
     if (bf) transform_kernel<true, 4, 2><<<grid, kThreads * 4, L.total, q>>>(Xp, M, n1, n2, sign_bits, P1, P2, Y, (int)y_dtype, L);
     else transform_kernel<false, 4, 2><<<grid, kThreads * 4, L.total, q>>>(Xp, M, n1, n2, sign_bits, P1, P2, Y, (int)y_dtype, L);
   } else {
