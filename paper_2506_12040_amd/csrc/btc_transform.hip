@@ -93,7 +93,7 @@ __global__ __launch_bounds__(kThreads * KS) void transform_kernel(const uint16_t
                                              // rows of X start 16-byte aligned
 
   // A row of X with its signs applied -> LDS (row i1 of the n1 x n2 view at xs + i1 * rs).
-  auto stage_x = [&](int m) {
+  auto stage_x = [&](int m) __attribute__((always_inline)) {
     const uint16_t* xrow = X + (size_t)m * n;
     if (x_vec) {
       constexpr int U = 4;
@@ -103,11 +103,9 @@ __global__ __launch_bounds__(kThreads * KS) void transform_kernel(const uint16_t
         uint32_t sw[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-          const int g = base + u * T;
-          if (g < groups) {
-            v[u] = *(const uint4*)(xrow + 8 * g);
-            sw[u] = sign_bits[g >> 2];
-          }
+          const int g = min(base + u * T, groups - 1);            // past the end: a valid group, not stored
+          v[u] = *(const uint4*)(xrow + 8 * g);
+          sw[u] = sign_bits[g >> 2];
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -157,8 +155,7 @@ __global__ __launch_bounds__(kThreads * KS) void transform_kernel(const uint16_t
     for (int base = tid; base < quads; base += T * U) {
       float4 v[U];
 #pragma unroll
-      for (int u = 0; u < U; ++u)
-        if (base + u * T < quads) v[u] = *(const float4*)(P1 + 4 * (size_t)(base + u * T));
+      for (int u = 0; u < U; ++u) v[u] = *(const float4*)(P1 + 4 * (size_t)min(base + u * T, quads - 1));
 #pragma unroll
       for (int u = 0; u < U; ++u)
         if (base + u * T < quads) *(float4*)(p1s + 4 * (base + u * T)) = v[u];
@@ -255,6 +252,191 @@ __global__ __launch_bounds__(kThreads * KS) void transform_kernel(const uint16_t
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// Many rows of bf16 activations (prefill): the two stages are small dense contractions and
+// run on the matrix cores (MFMA 32x32x16 bf16, fp32 accumulate).  A wave owns one row of X
+// and one block of 32 columns j2:
+//   stage 1:  D1[i1][j2] = sum_i2 (sigma x)[i1][i2] P2[i2][j2]    A = the row itself, read from
+//             global memory in operand layout (16 bytes per lane, signs applied in registers);
+//             B = P2 from LDS
+//   stage 2:  Z[j1][j2]  = sum_i1 P1[i1][j1] D1[i1][j2]           A = P1^T from LDS; B = D1 as it
+//             sits in the accumulators: a lane of D1 holds column j2 = lane % 32 and the 16 rows
+//             8 (e / 4) + 4 (lane / 32) + e % 4, which is a valid B operand once the contraction
+//             index of a 16-row step is permuted the same way in A -- P1^T is staged in that order.
+// The fp32 factors and the fp32 D1 enter as sums of three bf16 numbers (24 bits); products whose
+// weight is below 2^-24 are dropped, so the result has the accuracy of the fp32 kernel above.
+// The activations are bf16 already and enter exactly.
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+__device__ __forceinline__ uint32_t bf16_rne(float v) {      // finite v; an infinity stays one
+  const uint32_t u = __float_as_uint(v);
+  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+// v = p0 + p1 + p2 up to 2^-24 relative, each a bf16 bit pattern
+__device__ __forceinline__ void split3(float v, uint32_t& p0, uint32_t& p1, uint32_t& p2) {
+  p0 = bf16_rne(v);
+  float r = v - __uint_as_float(p0 << 16);
+  p1 = bf16_rne(r);
+  r -= __uint_as_float(p1 << 16);
+  p2 = bf16_rne(r);
+}
+
+__device__ __forceinline__ f32x16 mfma32(const uint4& a, const uint4& b, const f32x16& c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+// IT = ceil(n1 / 32): blocks of 32 rows i1 (and of 32 rows j1).  Needs n2 % 16 == 0.
+template <int IT>
+__global__ __launch_bounds__(kThreads) void transform_mfma_kernel(const uint16_t* __restrict__ X, int M, int n1, int n2,
+                                                                 const uint32_t* __restrict__ sign_bits,
+                                                                 const float* __restrict__ P1,
+                                                                 const float* __restrict__ P2, void* __restrict__ Y,
+                                                                 int y_dtype, int p2_bytes) {
+  constexpr int KS1 = 2 * IT;                // 16-row steps of stage 2
+  extern __shared__ __align__(16) unsigned char smem[];
+  uint4* P2op = (uint4*)smem;                // [step][part][lane]: B operands of stage 1
+  uint4* P1op = (uint4*)(smem + p2_bytes);   // [block j1][step][part][lane]: A operands of stage 2
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, h = lane >> 5;
+  const int n = n1 * n2, KS2 = n2 >> 4;
+  const int j2 = blockIdx.x * 32 + l32;
+
+  for (int it = tid; it < KS2 * 64; it += kThreads) {
+    const int ks = it >> 6, ln = it & 63, c = blockIdx.x * 32 + (ln & 31), hh = ln >> 5;
+    uint32_t q[3][8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int i2 = 16 * ks + 8 * hh + e;
+      split3(c < n2 ? P2[(size_t)i2 * n2 + c] : 0.f, q[0][e], q[1][e], q[2][e]);
+    }
+#pragma unroll
+    for (int p = 0; p < 3; ++p)
+      P2op[(ks * 3 + p) * 64 + ln] = make_uint4(q[p][0] | q[p][1] << 16, q[p][2] | q[p][3] << 16,
+                                               q[p][4] | q[p][5] << 16, q[p][6] | q[p][7] << 16);
+  }
+  for (int it = tid; it < IT * KS1 * 64; it += kThreads) {
+    const int ln = it & 63, ks = (it >> 6) % KS1, jt = (it >> 6) / KS1;
+    const int j1 = jt * 32 + (ln & 31), hh = ln >> 5;
+    uint32_t q[3][8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int i1 = 16 * ks + 8 * (e >> 2) + 4 * hh + (e & 3);   // the row of D1 that element e of a lane's step holds
+      split3((i1 < n1 && j1 < n1) ? P1[(size_t)i1 * n1 + j1] : 0.f, q[0][e], q[1][e], q[2][e]);
+    }
+#pragma unroll
+    for (int p = 0; p < 3; ++p)
+      P1op[((jt * KS1 + ks) * 3 + p) * 64 + ln] = make_uint4(q[p][0] | q[p][1] << 16, q[p][2] | q[p][3] << 16,
+                                                            q[p][4] | q[p][5] << 16, q[p][6] | q[p][7] << 16);
+  }
+  __syncthreads();
+
+  const uint8_t* sign_bytes = (const uint8_t*)sign_bits;   // byte k / 8 holds the bits of channels k .. k + 7
+  for (int m = blockIdx.y * 4 + wave; m < M; m += 4 * gridDim.y) {
+    const uint16_t* xrow = X + (size_t)m * n;
+    auto load_a = [&](int ks, uint4 (&a)[IT], uint32_t (&sg)[IT]) {
+#pragma unroll
+      for (int it = 0; it < IT; ++it) {
+        const int i1 = it * 32 + l32;
+        a[it] = make_uint4(0u, 0u, 0u, 0u);
+        sg[it] = 0xFFu;
+        if (i1 < n1) {
+          const int k = i1 * n2 + 16 * ks + 8 * h;
+          a[it] = *(const uint4*)(xrow + k);
+          sg[it] = sign_bytes[k >> 3];
+        }
+      }
+    };
+    f32x16 d1[IT];
+#pragma unroll
+    for (int it = 0; it < IT; ++it)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) d1[it][e] = 0.f;
+    uint4 a_cur[IT], a_nxt[IT];
+    uint32_t s_cur[IT], s_nxt[IT];
+    load_a(0, a_cur, s_cur);
+    for (int ks = 0; ks < KS2; ++ks) {
+      if (ks + 1 < KS2) load_a(ks + 1, a_nxt, s_nxt);
+      const uint4 b0 = P2op[(ks * 3 + 0) * 64 + lane], b1 = P2op[(ks * 3 + 1) * 64 + lane],
+                  b2 = P2op[(ks * 3 + 2) * 64 + lane];
+#pragma unroll
+      for (int it = 0; it < IT; ++it) {
+        const uint32_t minus = ~s_cur[it] & 0xFFu;           // bit e set: element e changes sign
+        uint4 a = a_cur[it];
+        a.x ^= ((minus & 1u) << 15) | ((minus & 2u) << 30);
+        a.y ^= ((minus & 4u) << 13) | ((minus & 8u) << 28);
+        a.z ^= ((minus & 16u) << 11) | ((minus & 32u) << 26);
+        a.w ^= ((minus & 64u) << 9) | ((minus & 128u) << 24);
+        d1[it] = mfma32(a, b0, d1[it]);
+        d1[it] = mfma32(a, b1, d1[it]);
+        d1[it] = mfma32(a, b2, d1[it]);
+      }
+#pragma unroll
+      for (int it = 0; it < IT; ++it) { a_cur[it] = a_nxt[it]; s_cur[it] = s_nxt[it]; }
+    }
+    // D1 as three bf16 parts, in B-operand form: step s of block it takes elements 8 s .. 8 s + 7
+    uint4 yb[IT][2][3];
+#pragma unroll
+    for (int it = 0; it < IT; ++it)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        uint32_t q[3][8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) split3(d1[it][8 * s2 + e], q[0][e], q[1][e], q[2][e]);
+#pragma unroll
+        for (int p = 0; p < 3; ++p)
+          yb[it][s2][p] = make_uint4(q[p][0] | q[p][1] << 16, q[p][2] | q[p][3] << 16, q[p][4] | q[p][5] << 16,
+                                     q[p][6] | q[p][7] << 16);
+      }
+    for (int jt = 0; jt < IT; ++jt) {
+      f32x16 z;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) z[e] = 0.f;
+#pragma unroll
+      for (int it = 0; it < IT; ++it)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          const uint4* ap = P1op + ((jt * KS1 + 2 * it + s2) * 3) * 64 + lane;
+          const uint4 a0 = ap[0], a1 = ap[64], a2 = ap[128];
+          z = mfma32(a2, yb[it][s2][0], z);                  // small terms first
+          z = mfma32(a1, yb[it][s2][1], z);
+          z = mfma32(a0, yb[it][s2][2], z);
+          z = mfma32(a1, yb[it][s2][0], z);
+          z = mfma32(a0, yb[it][s2][1], z);
+          z = mfma32(a0, yb[it][s2][0], z);
+        }
+      if (j2 < n2) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int j1 = jt * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
+          if (j1 < n1) store_out(Y, (size_t)m * n + (size_t)j1 * n2 + j2, z[e], y_dtype);
+        }
+      }
+    }
+  }
+}
+
+template <int IT>
+static btc_status launch_mfma(hipStream_t q, const uint16_t* X, int M, int n1, int n2, const uint32_t* sign_bits,
+                              const float* P1, const float* P2, void* Y, int y_dtype) {
+  const int p2_bytes = (n2 >> 4) * 3 * 1024;
+  const int lds = p2_bytes + IT * 2 * IT * 3 * 1024;
+  static bool attr_set = false;              // one-time kernel attribute, not call state
+  if (!attr_set) {
+    if (hipFuncSetAttribute((const void*)transform_mfma_kernel<IT>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            160 * 1024 - 256) != hipSuccess)
+      return BTC_ERR_HIP;
+    attr_set = true;
+  }
+  const int gx = (n2 + 31) / 32;
+  int gy = 512 / gx;                         // about two workgroups per compute unit; a wave walks the rows dealt to it
+  if (gy > (M + 3) / 4) gy = (M + 3) / 4;
+  if (gy < 1) gy = 1;
+  transform_mfma_kernel<IT><<<dim3(gx, gy), kThreads, lds, q>>>(X, M, n1, n2, sign_bits, P1, P2, Y, y_dtype, p2_bytes);
+  return launch_status();
+}
+
 }  // namespace transform
 }  // namespace btc
 
@@ -272,6 +454,16 @@ btc_status btc_transform(void* stream, const void* X, btc_dtype x_dtype, int32_t
   if ((long long)M * n1 * n2 >= (1LL << 40)) return BTC_ERR_SHAPE;
   if (!aligned16(X) || !aligned16(sign_bits) || !aligned16(P1) || !aligned16(P2) || !aligned16(Y)) return BTC_ERR_ALIGN;
   if (X == Y) return BTC_ERR_UNSUPPORTED;    // workgroups read whole rows that others write slices of
+  hipStream_t q = (hipStream_t)stream;
+  if (x_dtype == BTC_BF16 && (n2 & 15) == 0 && M >= 64) {    // prefill on the matrix cores
+    const uint16_t* Xm = (const uint16_t*)X;
+    switch ((n1 + 31) / 32) {
+      case 1: return launch_mfma<1>(q, Xm, M, n1, n2, sign_bits, P1, P2, Y, (int)y_dtype);
+      case 2: return launch_mfma<2>(q, Xm, M, n1, n2, sign_bits, P1, P2, Y, (int)y_dtype);
+      case 3: return launch_mfma<3>(q, Xm, M, n1, n2, sign_bits, P1, P2, Y, (int)y_dtype);
+      default: return launch_mfma<4>(q, Xm, M, n1, n2, sign_bits, P1, P2, Y, (int)y_dtype);
+    }
+  }
   const int n_cb = (n2 + kCB - 1) / kCB;
   // A few rows: one workgroup of 1024 threads per (column block, row), dot products cut in four.
   // Many rows: 256 threads, and the rows are dealt to about five workgroups per compute unit.
@@ -285,7 +477,6 @@ btc_status btc_transform(void* stream, const void* X, btc_dtype x_dtype, int32_t
   int gy = few ? M : big ? 256 / n_cb : 1280 / n_cb;
   if (gy < 1) gy = 1;
   if (gy > M) gy = M;
-  hipStream_t q = (hipStream_t)stream;
   static bool attr_set = false;              // one-time kernel attributes, not call state
   if (!attr_set) {
     const void* fns[4] = {(const void*)transform_kernel<false, 4, 2>, (const void*)transform_kernel<true, 4, 2>,
