@@ -60,10 +60,8 @@ __device__ __forceinline__ void store_out(void* Y, size_t at, float v, int y_dty
     ((float*)Y)[at] = v;
   } else if (y_dtype == BTC_F16) {
     ((__half*)Y)[at] = __float2half_rn(v);
-  } else {                                   // bf16, round to nearest even (NaN stays NaN)
-    const uint32_t u = __float_as_uint(v);
-    const uint32_t r = (u & 0x7FFFFFFFu) > 0x7F800000u ? (u | 0x00400000u) : u + 0x7FFFu + ((u >> 16) & 1u);
-    ((uint16_t*)Y)[at] = (uint16_t)(r >> 16);
+  } else {                                   // bf16, round to nearest even
+    ((__bf16*)Y)[at] = (__bf16)v;
   }
 }
 
@@ -269,9 +267,9 @@ __global__ __launch_bounds__(kThreads * KS) void transform_kernel(const uint16_t
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-__device__ __forceinline__ uint32_t bf16_rne(float v) {      // finite v; an infinity stays one
-  const uint32_t u = __float_as_uint(v);
-  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+// float -> bf16 bit pattern, round to nearest even (the hardware conversion of gfx950)
+__device__ __forceinline__ uint32_t bf16_rne(float v) {
+  return (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)v);
 }
 
 // v = p0 + p1 + p2 up to 2^-24 relative, each a bf16 bit pattern
@@ -333,47 +331,60 @@ __global__ __launch_bounds__(kThreads) void transform_mfma_kernel(const uint16_t
   __syncthreads();
 
   const uint8_t* sign_bytes = (const uint8_t*)sign_bits;   // byte k / 8 holds the bits of channels k .. k + 7
-  for (int m = blockIdx.y * 4 + wave; m < M; m += 4 * gridDim.y) {
-    const uint16_t* xrow = X + (size_t)m * n;
-    auto load_a = [&](int ks, uint4 (&a)[IT], uint32_t (&sg)[IT]) {
+  // A operands of stage 1 come straight from global memory, PD steps ahead: slot u of the ring holds step
+  // ks0 + u of the current chunk of PD steps; once used it is refilled with step ks0 + PD + u of the same row
+  // or, in a row's last chunk, with step u of the wave's next row, whose first loads thus fly during stage 2.
+  constexpr int PD = IT <= 2 ? 4 : 2;
+  const int stride = 4 * gridDim.y;
+  auto load_a = [&](int mm, int ks, uint4 (&a)[IT], uint32_t (&sg)[IT]) __attribute__((always_inline)) {
+    const uint16_t* xrow = X + (size_t)mm * n;
 #pragma unroll
-      for (int it = 0; it < IT; ++it) {
-        const int i1 = it * 32 + l32;
-        a[it] = make_uint4(0u, 0u, 0u, 0u);
-        sg[it] = 0xFFu;
-        if (i1 < n1) {
-          const int k = i1 * n2 + 16 * ks + 8 * h;
-          a[it] = *(const uint4*)(xrow + k);
-          sg[it] = sign_bytes[k >> 3];
-        }
-      }
-    };
+    for (int it = 0; it < IT; ++it) {
+      const int i1 = min(it * 32 + l32, n1 - 1);               // rows past the end: a valid row, zeroed below
+      const int k = i1 * n2 + 16 * ks + 8 * h;
+      a[it] = *(const uint4*)(xrow + k);
+      sg[it] = sign_bytes[k >> 3];
+    }
+  };
+  uint4 ring[PD][IT];
+  uint32_t rsg[PD][IT];
+  const int m_first = blockIdx.y * 4 + wave;
+  if (m_first < M) {
+#pragma unroll
+    for (int u = 0; u < PD; ++u)
+      if (u < KS2) load_a(m_first, u, ring[u], rsg[u]);
+  }
+  for (int m = m_first; m < M; m += stride) {
     f32x16 d1[IT];
 #pragma unroll
     for (int it = 0; it < IT; ++it)
 #pragma unroll
       for (int e = 0; e < 16; ++e) d1[it][e] = 0.f;
-    uint4 a_cur[IT], a_nxt[IT];
-    uint32_t s_cur[IT], s_nxt[IT];
-    load_a(0, a_cur, s_cur);
-    for (int ks = 0; ks < KS2; ++ks) {
-      if (ks + 1 < KS2) load_a(ks + 1, a_nxt, s_nxt);
-      const uint4 b0 = P2op[(ks * 3 + 0) * 64 + lane], b1 = P2op[(ks * 3 + 1) * 64 + lane],
-                  b2 = P2op[(ks * 3 + 2) * 64 + lane];
+    for (int ks0 = 0; ks0 < KS2; ks0 += PD) {
+      const bool last_chunk = ks0 + PD >= KS2;
 #pragma unroll
-      for (int it = 0; it < IT; ++it) {
-        const uint32_t minus = ~s_cur[it] & 0xFFu;           // bit e set: element e changes sign
-        uint4 a = a_cur[it];
-        a.x ^= ((minus & 1u) << 15) | ((minus & 2u) << 30);
-        a.y ^= ((minus & 4u) << 13) | ((minus & 8u) << 28);
-        a.z ^= ((minus & 16u) << 11) | ((minus & 32u) << 26);
-        a.w ^= ((minus & 64u) << 9) | ((minus & 128u) << 24);
-        d1[it] = mfma32(a, b0, d1[it]);
-        d1[it] = mfma32(a, b1, d1[it]);
-        d1[it] = mfma32(a, b2, d1[it]);
+      for (int u = 0; u < PD; ++u) {
+        const int ks = ks0 + u;
+        if (ks < KS2) {
+          const uint4 b0 = P2op[(ks * 3 + 0) * 64 + lane], b1 = P2op[(ks * 3 + 1) * 64 + lane],
+                      b2 = P2op[(ks * 3 + 2) * 64 + lane];
+#pragma unroll
+          for (int it = 0; it < IT; ++it) {
+            const uint32_t minus = ~rsg[u][it] & 0xFFu;          // bit e set: element e changes sign
+            uint4 a = ring[u][it];
+            a.x ^= ((minus & 1u) << 15) | ((minus & 2u) << 30);
+            a.y ^= ((minus & 4u) << 13) | ((minus & 8u) << 28);
+            a.z ^= ((minus & 16u) << 11) | ((minus & 32u) << 26);
+            a.w ^= ((minus & 64u) << 9) | ((minus & 128u) << 24);
+            if (it * 32 + l32 >= n1) a = make_uint4(0u, 0u, 0u, 0u);
+            d1[it] = mfma32(a, b0, d1[it]);
+            d1[it] = mfma32(a, b1, d1[it]);
+            d1[it] = mfma32(a, b2, d1[it]);
+          }
+        }
+        if (ks + PD < KS2) load_a(m, ks + PD, ring[u], rsg[u]);
+        else if (last_chunk && u < KS2 && m + stride < M) load_a(m + stride, u, ring[u], rsg[u]);
       }
-#pragma unroll
-      for (int it = 0; it < IT; ++it) { a_cur[it] = a_nxt[it]; s_cur[it] = s_nxt[it]; }
     }
     // D1 as three bf16 parts, in B-operand form: step s of block it takes elements 8 s .. 8 s + 7
     uint4 yb[IT][2][3];
