@@ -22,6 +22,8 @@
 // unit.  Every global load of a phase is issued before the first one is used.
 #include <hip/hip_fp16.h>
 
+#include <type_traits>
+
 #include "btc_internal.h"
 
 namespace btc {
@@ -417,12 +419,20 @@ __global__ __launch_bounds__(kThreads) void transform_mfma_kernel(const uint16_t
           z = mfma32(a0, yb[it][s2][1], z);
           z = mfma32(a0, yb[it][s2][0], z);
         }
-      if (j2 < n2) {
+      if (j2 < n2) {                                           // one branch on the output type per tile, not per element
+        const size_t at0 = (size_t)m * n + (size_t)(jt * 32 + 4 * h) * n2 + j2;
+        const int rows_left = n1 - (jt * 32 + 4 * h);            // rows 8 (e / 4) + e % 4 below this count exist
+        auto store_tile = [&](auto* out) __attribute__((always_inline)) {
+          typedef typename std::remove_pointer<decltype(out)>::type T;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int j1 = jt * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
-          if (j1 < n1) store_out(Y, (size_t)m * n + (size_t)j1 * n2 + j2, z[e], y_dtype);
-        }
+          for (int e = 0; e < 16; ++e) {
+            const int r = 8 * (e >> 2) + (e & 3);
+            if (r < rows_left) out[at0 + (size_t)(r * n2)] = (T)z[e];
+          }
+        };
+        if (y_dtype == BTC_BF16) store_tile((__bf16*)Y);
+        else if (y_dtype == BTC_F32) store_tile((float*)Y);
+        else store_tile((_Float16*)Y);
       }
     }
   }
