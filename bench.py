@@ -35,7 +35,6 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
-FP32_VALU_PEAK_TFLOPS = 157.3     # 256 compute units x 128 fp32 lanes x 2 flop x 2.4 GHz
 # HBM bytes of one step (7 calls) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
 # 256 MiB copy (profiles/gemv_13b_hbm_traffic.md): 37.1 MB fetched + 5.5 MB written.
 HBM_TRAFFIC_PER_STEP = 45.2e6
@@ -397,8 +396,10 @@ def main():
                 torch.cuda.synchronize()
                 us = e0.elapsed_time(e1) * 1e3 / (5 * reps)
                 flop = 2.0 * M * n * (n1 + n2)
+                nbytes = 2.0 * M * n * 2 + 4.0 * (n1 * n1 + n2 * n2) + n / 8
                 row[f"M{M}"] = dict(us=round(us, 2), tflops=round(flop / us / 1e6, 2),
-                                    frac_fp32_alu_peak=round(flop / us / 1e6 / FP32_VALU_PEAK_TFLOPS, 4))
+                                    GBps=round(nbytes / us / 1e3, 1), frac_hbm=round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4),
+                                    engine="fp32 vector ALU" if M <= 16 else "bf16 matrix cores, 3-part operands")
             transform[f"n={n} ({n1}x{n2})"] = row
 
     # ---- CPU oracle on the host cores, bounded sample of the same workload
