@@ -83,3 +83,25 @@ def test_transform_identity_and_signs_exact(G, oracle):
     xb = S.draw_x(np.random.default_rng(8), M, n1 * n2, "f16")
     y = _run(G, xb, "f16", bits, np.eye(n1, dtype=np.float32), np.eye(n2, dtype=np.float32), B.BTC_F16)
     assert np.array_equal(y, oracle.transform(xb, bits, np.eye(n1, dtype=np.float32), np.eye(n2, dtype=np.float32)))
+
+
+# The matrix-core path (bf16 activations, n2 a multiple of 16, 64 rows or more): ragged blocks of 32 rows i1 / j1
+# (108 = 3 x 32 + 12, 33 = 32 + 1), a last block of 32 columns that is half empty (48, 80, 16), fewer steps than the
+# prefetch depth (n2 = 16, 32), every block count 1..4, rows that do not divide among the waves.
+MFMA_CASES = [(108, 128, 100, "f32"), (128, 224, 70, "f32"), (40, 16, 200, "f32"), (33, 48, 130, "bf16"),
+              (96, 32, 64, "f16"), (64, 80, 257, "f32"), (20, 96, 65, "f32"), (128, 256, 66, "bf16")]
+
+
+@pytest.mark.parametrize("n1,n2,M,yd", MFMA_CASES)
+def test_transform_matrix_core_path_sampled_rows(G, oracle, n1, n2, M, yd):
+    B = G.B
+    print(f"transform (matrix cores) n1={n1} n2={n2} M={M} bf16->{yd}", flush=True)
+    y_dtype = {"f32": B.BTC_F32, "f16": B.BTC_F16, "bf16": B.BTC_BF16}[yd]
+    bits, P1, P2 = S.draw_transform(300 + n1 + n2, n1, n2)
+    xb = S.draw_x(np.random.default_rng(n1 + n2 + M), M, n1 * n2, "bf16")
+    y = _run(G, xb, "bf16", bits, P1, P2, y_dtype)
+    rows = np.unique(np.array([0, 1, 2, 3, 4, M // 2, M - 5, M - 4, M - 3, M - 2, M - 1]))
+    if n1 * n2 > 8192:
+        rows = rows[[0, 3, len(rows) // 2, -1]]          # the oracle forms n x n entries per row
+    _check(y[rows], oracle.transform(xb[rows], bits, P1, P2, "bf16"), y_dtype, B, (n1, n2, M, yd))
+    assert np.isfinite(y).all()
