@@ -62,6 +62,8 @@ def lib() -> ctypes.CDLL:
         L.btc_oracle_matmul.argtypes = [c_vp, c_long, c_long, c_vp, c_long, c_vp]
         L.btc_oracle_transform.restype = None
         L.btc_oracle_transform.argtypes = [c_vp, c_long, c_long, c_long, c_vp, c_vp, c_vp, c_vp]
+        L.btc_oracle_assign.restype = None
+        L.btc_oracle_assign.argtypes = [c_vp, c_long, c_int, c_vp, c_long, c_vp, c_vp]
         _lib = L
     return _lib
 
@@ -186,3 +188,13 @@ def transform(x_bits, sign_bits, P1, P2, x_kind: str = "f16") -> np.ndarray:
     Y = np.empty(X.shape, dtype=np.float64)
     lib().btc_oracle_transform(_p(X), X.shape[0], n1, n2, _p(sign_bits), _p(P1), _p(P2), _p(Y))
     return Y
+
+
+def assign(vectors, v: int, codebook):
+    """E-step: nearest centroid of every v-bit sign pattern; returns (z int32[N], squared distance int32[N])."""
+    vectors = _c(vectors, np.uint32)
+    codebook = _c(codebook, np.uint32)
+    z = np.empty(vectors.shape[0], dtype=np.int32)
+    d2 = np.empty(vectors.shape[0], dtype=np.int32)
+    lib().btc_oracle_assign(_p(vectors), vectors.shape[0], int(v), _p(codebook), codebook.shape[0], _p(z), _p(d2))
+    return z, d2

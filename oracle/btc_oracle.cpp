@@ -216,4 +216,34 @@ void btc_oracle_transform(const double* X, long M, long n1, long n2, const uint3
   }
 }
 
+// E-step of the binary codebook clustering (section "Binary Codebook Compression", step
+// "E-step Assignment"): z_i = argmin_k || b_i - c_k ||_2^2 over +-1 vectors of length v, a vector
+// identical to a centroid being assigned to it (distance 0 is the minimum, so the rule is the
+// argmin itself).  Written from the definition: elements are expanded to +-1 integers and the
+// squared differences are summed.  Among equally near centroids the lowest index wins (the paper
+// leaves ties open).  Bit t of a pattern is element t (set => +1); bits >= v are ignored.
+// dist2[i] receives the squared distance to the chosen centroid (may be null).
+void btc_oracle_assign(const uint32_t* vectors, long N, int v, const uint32_t* codebook, long K,
+                       int32_t* z, int32_t* dist2) {
+#pragma omp parallel for schedule(static)
+  for (long i = 0; i < N; ++i) {
+    long best_k = -1;
+    int best = 0;
+    for (long k = 0; k < K; ++k) {
+      int d2 = 0;
+      for (int t = 0; t < v; ++t) {
+        const int b = ((vectors[i] >> t) & 1u) ? 1 : -1;
+        const int c = ((codebook[k] >> t) & 1u) ? 1 : -1;
+        d2 += (b - c) * (b - c);
+      }
+      if (best_k < 0 || d2 < best) {
+        best = d2;
+        best_k = k;
+      }
+    }
+    z[i] = (int32_t)best_k;
+    if (dist2) dist2[i] = best;
+  }
+}
+
 }  // extern "C"
