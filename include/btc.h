@@ -145,6 +145,22 @@ btc_status btc_transform(void* stream, const void* X, btc_dtype x_dtype, int32_t
                          int32_t n2, const uint32_t* sign_bits, const float* P1, const float* P2,
                          void* Y, btc_dtype y_dtype);
 
+/* E-step of the binary codebook clustering (section "Flash and Accurate Binary
+ * Codebook", step "E-step Assignment": z_i = argmin_k ||b_i - c_k||^2, which for
+ * +-1 vectors is 4 * POPCNT(b_i xor c_k); a vector identical to a centroid goes to
+ * it).  Offline step that produces the index matrix btc_pack stores.
+ *   vectors  : uint32 [N], bit t of entry i = element t of vector i (1 => +1), t < v;
+ *              bits >= v are ignored
+ *   codebook : uint32 [K] centroids in the same form, K 1..65536; v 1..32
+ *   z        : int32 [N], index of the nearest centroid; among equally near ones
+ *              (duplicates included) the lowest index
+ *   dist2    : int32 [N] squared distance to it (4 * Hamming distance), or NULL
+ * Device pointers owned by the caller, 16-byte aligned.  Integer arithmetic, exact.
+ * Enqueues and returns.  Errors: BTC_ERR_NULL, _SHAPE (N <= 0), _UNSUPPORTED
+ * (v or K out of range), _ALIGN, _HIP. */
+btc_status btc_assign(void* stream, const uint32_t* vectors, int64_t N, int32_t v,
+                      const uint32_t* codebook, int32_t K, int32_t* z, int32_t* dist2);
+
 /* Host. Static string for a status code. */
 const char* btc_status_str(btc_status st);
 

@@ -57,6 +57,8 @@ def lib() -> ctypes.CDLL:
         L.btc_gemm.argtypes = [vp, sp, vp, vp, vp, vp, vp, ctypes.c_int, i32, vp, ctypes.c_int, vp, sz]
         L.btc_transform.restype = ctypes.c_int
         L.btc_transform.argtypes = [vp, vp, ctypes.c_int, i32, i32, i32, vp, vp, vp, vp, ctypes.c_int]
+        L.btc_assign.restype = ctypes.c_int
+        L.btc_assign.argtypes = [vp, vp, ctypes.c_int64, i32, vp, i32, vp, vp]
         L.btc_status_str.restype = ctypes.c_char_p
         L.btc_status_str.argtypes = [ctypes.c_int]
         _lib = L
@@ -135,3 +137,8 @@ def btc_gemm(s: btc_shape, packed, codebook, alpha, mu, X, x_dtype: int, M: int,
 def btc_transform(X, x_dtype: int, M: int, n1: int, n2: int, sign_bits, P1, P2, Y, y_dtype: int, stream=None) -> None:
     _check(lib().btc_transform(_stream(stream), _ptr(X), x_dtype, M, n1, n2, _ptr(sign_bits), _ptr(P1), _ptr(P2),
                                _ptr(Y), y_dtype), "btc_transform")
+
+
+def btc_assign(vectors, N: int, v: int, codebook, K: int, z, dist2=None, stream=None) -> None:
+    _check(lib().btc_assign(_stream(stream), _ptr(vectors), N, v, _ptr(codebook), K, _ptr(z), _ptr(dist2)),
+           "btc_assign")

@@ -106,6 +106,11 @@ def test_argument_checks_need_no_gpu(B):
     assert L.btc_transform(None, fake, E.BTC_F32, 1, 4, 4, fake, fake, fake, other, E.BTC_F16) == E.BTC_ERR_UNSUPPORTED
     assert L.btc_transform(None, fake, E.BTC_F16, 1, 4, 4, fake, fake, fake, fake, E.BTC_F16) == E.BTC_ERR_UNSUPPORTED
     assert L.btc_transform(None, fake, E.BTC_F16, 1, 4, 4, fake, odd, fake, other, E.BTC_F16) == E.BTC_ERR_ALIGN
+    assert L.btc_assign(None, None, 8, 10, fake, 4, fake, None) == E.BTC_ERR_NULL
+    assert L.btc_assign(None, fake, 0, 10, fake, 4, fake, None) == E.BTC_ERR_SHAPE
+    assert L.btc_assign(None, fake, 8, 33, fake, 4, fake, None) == E.BTC_ERR_UNSUPPORTED
+    assert L.btc_assign(None, fake, 8, 10, fake, 65537, fake, None) == E.BTC_ERR_UNSUPPORTED
+    assert L.btc_assign(None, fake, 8, 10, fake, 4, odd, None) == E.BTC_ERR_ALIGN
     t = B.btc_shape_init(64, 100, 10, 512)
     t.words_per_row += 1                 # a shape edited after btc_shape_init
     assert L.btc_unpack(None, ctypes.byref(t), fake, fake) == E.BTC_ERR_SHAPE
