@@ -47,7 +47,9 @@ def _run(G, vec, v, cb, want_dist=True):
 
 
 CASES = [(1, 10, 256), (1023, 10, 256), (100001, 10, 512), (5000, 9, 1024), (4097, 4, 5), (3000, 16, 4096),
-         (2000, 20, 65536), (777, 32, 100), (2048, 10, 1), (50000, 10, 128), (1025, 1, 2)]
+         (2000, 20, 65536), (777, 32, 100), (2048, 10, 1), (50000, 10, 128), (1025, 1, 2),
+         # many short vectors: the route that assigns the 2^v patterns once and looks the vectors up
+         (262147, 12, 1000), (65536, 10, 256), (65535, 10, 256), (40001, 9, 1024), (300, 2, 3)]
 
 
 @pytest.mark.parametrize("N,v,K", CASES)
