@@ -402,6 +402,39 @@ def main():
                                     engine="fp32 vector ALU" if M <= 16 else "bf16 matrix cores, 3-part operands")
             transform[f"n={n} ({n1}x{n2})"] = row
 
+    # ---- E-step of the codebook clustering (btc_assign): the length-10 vectors of a 5120 x 5120 and of a
+    # 13824 x 5120 sign matrix against 256 centroids; a setting with long vectors (no pattern table)
+    assign = None
+    if not args.no_transform:
+        assign = {}
+        for (tag, N, v_, K_) in [("5120x5120 v=10 K=256", 5120 * 512, 10, 256), ("13824x5120 v=10 K=256", 13824 * 512, 10, 256),
+                                 ("4096x4096 v=16 K=4096", 4096 * 256, 16, 4096)]:
+            g = torch.Generator(device=dev)
+            g.manual_seed(0)
+            vec = torch.randint(0, 2 ** v_, (N,), dtype=torch.int32, device=dev, generator=g)
+            cbk = torch.randint(0, 2 ** v_, (K_,), dtype=torch.int32, device=dev, generator=g)
+            zz = torch.empty(N, dtype=torch.int32, device=dev)
+            dd = torch.empty(N, dtype=torch.int32, device=dev)
+            call = lambda: B.btc_assign(vec, N, v_, cbk, K_, zz, dd)
+            call()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(5):
+                call()
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / 5
+            table = v_ <= 12 and N >= (64 << v_)
+            row = dict(us=round(us, 1), vectors_per_s=round(N / us * 1e6, -6), GBps=round(12.0 * N / us / 1e3, 1))
+            if table:
+                row.update(route="pattern table in LDS", frac_hbm=round(12.0 * N / us / 1e3 / HBM_PEAK_GBS, 4))
+            else:   # xor, bit count, shift-or, minimum per (vector, centroid) pair on 256 x 64 lanes at 2.4 GHz
+                row.update(route="all pairs", lane_ops_per_s=round(4.0 * N * K_ / us * 1e6, -9),
+                           frac_alu=round(4.0 * N * K_ / us * 1e6 / 39.3e12, 4))
+            assign[tag] = row
+            del vec, zz, dd
+
     # ---- CPU oracle on the host cores, bounded sample of the same workload
     cpu = None
     if not args.no_cpu:
@@ -459,6 +492,7 @@ def main():
             "note": f"2*M*out*in flop of the 7 projections at M={args.gemm_m} / event-timed btc_gemm calls "
                     "(whole calls)"},
         "transform": transform,
+        "assign": assign,
         "cpu_baseline": cpu,
         "setup_s": round(t_setup, 1),
     }
