@@ -64,6 +64,8 @@ def lib() -> ctypes.CDLL:
         L.btc_oracle_transform.argtypes = [c_vp, c_long, c_long, c_long, c_vp, c_vp, c_vp, c_vp]
         L.btc_oracle_assign.restype = None
         L.btc_oracle_assign.argtypes = [c_vp, c_long, c_int, c_vp, c_long, c_vp, c_vp]
+        L.btc_oracle_update.restype = c_int
+        L.btc_oracle_update.argtypes = [c_vp, c_vp, c_long, c_int, c_vp, c_long]
         _lib = L
     return _lib
 
@@ -198,3 +200,13 @@ def assign(vectors, v: int, codebook):
     d2 = np.empty(vectors.shape[0], dtype=np.int32)
     lib().btc_oracle_assign(_p(vectors), vectors.shape[0], int(v), _p(codebook), codebook.shape[0], _p(z), _p(d2))
     return z, d2
+
+
+def update(vectors, z, v: int, codebook) -> np.ndarray:
+    """M-step: majority vote per cluster; returns the new codebook (empty clusters keep their centroid)."""
+    vectors = _c(vectors, np.uint32)
+    z = _c(z, np.int32)
+    new = np.array(codebook, dtype=np.uint32, copy=True)
+    if lib().btc_oracle_update(_p(vectors), _p(z), vectors.shape[0], int(v), _p(new), new.shape[0]) != 0:
+        raise ValueError("assignment outside [0, K)")
+    return new

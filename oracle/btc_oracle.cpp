@@ -246,4 +246,31 @@ void btc_oracle_assign(const uint32_t* vectors, long N, int v, const uint32_t* c
   }
 }
 
+// M-step of the binary codebook clustering (section "Flash and Accurate Binary Codebook", step
+// "M-step Centroid Update"; the loop over clusters in the algorithm of appendix "Binary Codebook
+// Optimization"): for every cluster k with at least one assigned vector, the centroid becomes the
+// sign of the dimension-wise mean of its vectors, a zero mean giving +1; an empty cluster keeps its
+// centroid.  Written from the definition: the +-1 elements are summed as integers per cluster and
+// dimension.  Bits >= v of a new centroid are zero; an unchanged centroid is left as it was.
+// z[i] outside [0, K) is an error (returns -1, nothing written).
+int btc_oracle_update(const uint32_t* vectors, const int32_t* z, long N, int v, uint32_t* codebook, long K) {
+  for (long i = 0; i < N; ++i)
+    if (z[i] < 0 || z[i] >= K) return -1;
+  for (long k = 0; k < K; ++k) {
+    long size = 0;
+    long sum[32] = {0};
+    for (long i = 0; i < N; ++i) {
+      if (z[i] != k) continue;
+      ++size;
+      for (int t = 0; t < v; ++t) sum[t] += ((vectors[i] >> t) & 1u) ? 1 : -1;
+    }
+    if (size == 0) continue;
+    uint32_t c = 0;
+    for (int t = 0; t < v; ++t)
+      if (sum[t] >= 0) c |= 1u << t;           // sign(mean), sign(0) = +1
+    codebook[k] = c;
+  }
+  return 0;
+}
+
 }  // extern "C"

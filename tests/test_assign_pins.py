@@ -71,3 +71,59 @@ def test_brute_force_in_pure_python(oracle):
             if best is None or d < best[0]:
                 best = (d, k)
         assert (d2[i], z[i]) == best
+
+
+# ---- M-step: c_k = sign(mean of the vectors assigned to k), sign(0) = +1, empty clusters unchanged
+
+def test_update_majority_vote_against_numpy(oracle):
+    rng = np.random.default_rng(10)
+    for (v, K, N) in [(10, 16, 500), (9, 40, 300), (4, 3, 50), (20, 7, 200), (32, 5, 90)]:
+        vec = rng.integers(0, 1 << 32, size=N, dtype=np.uint64).astype(np.uint32) & np.uint32((1 << v) - 1 if v < 32 else 0xFFFFFFFF)
+        z = rng.integers(0, K, size=N).astype(np.int32)
+        z[z == K - 1] = 0                                        # the last cluster stays empty
+        old = rng.integers(0, 1 << min(v, 31), size=K).astype(np.uint32)
+        new = oracle.update(vec, z, v, old)
+        signs = np.where((vec[:, None] >> np.arange(v, dtype=np.uint32)[None, :]) & 1, 1, -1)   # N x v of +-1
+        for k in range(K):
+            member = signs[z == k]
+            if len(member) == 0:
+                assert new[k] == old[k]
+                continue
+            mean = member.mean(axis=0)
+            want = sum(1 << t for t in range(v) if mean[t] >= 0)
+            assert int(new[k]) == want
+
+
+def test_update_ties_give_plus_one_and_single_member_is_copied(oracle):
+    vec = np.array([0b0011, 0b0101, 0b1111, 0b1000], dtype=np.uint32)
+    z = np.array([0, 0, 1, 2], dtype=np.int32)
+    new = oracle.update(vec, z, 4, np.zeros(4, dtype=np.uint32) + 9)
+    # cluster 0: elements (+,+) (+,-) (-,+) (-,-): sums 2, 0, 0, -2 -> 0111; clusters 1, 2: their only member; 3: empty
+    assert new.tolist() == [0b0111, 0b1111, 0b1000, 9]
+
+
+def test_update_is_a_fixed_point_after_assigning_exact_copies(oracle):
+    rng = np.random.default_rng(11)
+    cb = S.draw_codebook(rng, 10, 64)
+    vec = cb[rng.integers(0, 64, size=1000)]
+    z, d2 = oracle.assign(vec, 10, cb)
+    assert not d2.any() and np.array_equal(oracle.update(vec, z, 10, cb), cb)
+
+
+def test_update_never_increases_the_total_distance(oracle):
+    """One E-step / M-step round of the clustering cannot raise the summed distance (each centroid moves to the
+    per-dimension majority, which minimises the Hamming distance to its members)."""
+    rng = np.random.default_rng(12)
+    cb = S.draw_codebook(rng, 10, 32)
+    vec = rng.integers(0, 1 << 10, size=4000).astype(np.uint32)
+    z, d2 = oracle.assign(vec, 10, cb)
+    new = oracle.update(vec, z, 10, cb)
+    after = np.array([bin(int(a) ^ int(new[k])).count("1") for a, k in zip(vec, z)]) * 4
+    assert after.sum() <= d2.sum()
+    z2, d3 = oracle.assign(vec, 10, new)
+    assert d3.sum() <= after.sum()
+
+
+def test_update_rejects_assignments_out_of_range(oracle):
+    with pytest.raises(ValueError):
+        oracle.update(np.zeros(3, dtype=np.uint32), np.array([0, 5, 1], dtype=np.int32), 4, np.zeros(4, dtype=np.uint32))
