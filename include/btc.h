@@ -161,6 +161,30 @@ btc_status btc_transform(void* stream, const void* X, btc_dtype x_dtype, int32_t
 btc_status btc_assign(void* stream, const uint32_t* vectors, int64_t N, int32_t v,
                       const uint32_t* codebook, int32_t K, int32_t* z, int32_t* dist2);
 
+/* Host. Bytes of workspace btc_update needs: K * (v + 1) 32-bit counters and an
+ * error flag.  0 for v or K out of range. */
+size_t btc_update_workspace_bytes(int32_t v, int32_t K);
+
+/* M-step of the binary codebook clustering (section "Flash and Accurate Binary
+ * Codebook", step "M-step Centroid Update"; algorithm of appendix "Binary Codebook
+ * Optimization"): for every cluster k with at least one member,
+ *   codebook[k] element t = +1  iff  sum over the members of element t >= 0
+ * (the sign of the mean, a zero mean giving +1); bits >= v of a new centroid are 0.
+ * A cluster without members keeps its centroid.
+ *   vectors  : uint32 [N] sign patterns (bit t = element t, 1 => +1; bits >= v ignored)
+ *   z        : int32 [N] cluster of each vector, every entry in [0, K)
+ *   codebook : uint32 [K], read and overwritten;  v 1..32, K 1..65536, N < 2^31
+ *   workspace: btc_update_workspace_bytes(v, K) bytes, ZERO-FILLED before its first
+ *              use; every call leaves it zero again
+ * Device pointers owned by the caller, 16-byte aligned.  Integer arithmetic, exact,
+ * independent of the order of the atomic additions.  This call WAITS for the stream
+ * (like btc_pack): an entry of z outside [0, K) gives BTC_ERR_INDEX_RANGE and leaves
+ * the codebook unchanged.  Other errors: BTC_ERR_NULL, _SHAPE (N <= 0),
+ * _UNSUPPORTED, _WORKSPACE, _ALIGN, _HIP. */
+btc_status btc_update(void* stream, const uint32_t* vectors, const int32_t* z, int64_t N,
+                      int32_t v, uint32_t* codebook, int32_t K, void* workspace,
+                      size_t workspace_bytes);
+
 /* Host. Static string for a status code. */
 const char* btc_status_str(btc_status st);
 

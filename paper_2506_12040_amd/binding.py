@@ -59,6 +59,10 @@ def lib() -> ctypes.CDLL:
         L.btc_transform.argtypes = [vp, vp, ctypes.c_int, i32, i32, i32, vp, vp, vp, vp, ctypes.c_int]
         L.btc_assign.restype = ctypes.c_int
         L.btc_assign.argtypes = [vp, vp, ctypes.c_int64, i32, vp, i32, vp, vp]
+        L.btc_update_workspace_bytes.restype = sz
+        L.btc_update_workspace_bytes.argtypes = [i32, i32]
+        L.btc_update.restype = ctypes.c_int
+        L.btc_update.argtypes = [vp, vp, vp, ctypes.c_int64, i32, vp, i32, vp, sz]
         L.btc_status_str.restype = ctypes.c_char_p
         L.btc_status_str.argtypes = [ctypes.c_int]
         _lib = L
@@ -142,3 +146,14 @@ def btc_transform(X, x_dtype: int, M: int, n1: int, n2: int, sign_bits, P1, P2, 
 def btc_assign(vectors, N: int, v: int, codebook, K: int, z, dist2=None, stream=None) -> None:
     _check(lib().btc_assign(_stream(stream), _ptr(vectors), N, v, _ptr(codebook), K, _ptr(z), _ptr(dist2)),
            "btc_assign")
+
+
+def btc_update_workspace_bytes(v: int, K: int) -> int:
+    return lib().btc_update_workspace_bytes(v, K)
+
+
+def btc_update(vectors, z, N: int, v: int, codebook, K: int, workspace, stream=None,
+               workspace_bytes: Optional[int] = None) -> None:
+    wb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
+    _check(lib().btc_update(_stream(stream), _ptr(vectors), _ptr(z), N, v, _ptr(codebook), K, _ptr(workspace), wb),
+           "btc_update")

@@ -111,6 +111,12 @@ def test_argument_checks_need_no_gpu(B):
     assert L.btc_assign(None, fake, 8, 33, fake, 4, fake, None) == E.BTC_ERR_UNSUPPORTED
     assert L.btc_assign(None, fake, 8, 10, fake, 65537, fake, None) == E.BTC_ERR_UNSUPPORTED
     assert L.btc_assign(None, fake, 8, 10, fake, 4, odd, None) == E.BTC_ERR_ALIGN
+    assert L.btc_update_workspace_bytes(10, 256) == 256 * 11 * 4 + 16 and L.btc_update_workspace_bytes(33, 4) == 0
+    assert L.btc_update(None, fake, None, 8, 10, fake, 4, fake, 1 << 20) == E.BTC_ERR_NULL
+    assert L.btc_update(None, fake, fake, 0, 10, fake, 4, fake, 1 << 20) == E.BTC_ERR_SHAPE
+    assert L.btc_update(None, fake, fake, 8, 0, fake, 4, fake, 1 << 20) == E.BTC_ERR_UNSUPPORTED
+    assert L.btc_update(None, fake, fake, 8, 10, fake, 4, fake, 8) == E.BTC_ERR_WORKSPACE
+    assert L.btc_update(None, fake, fake, 8, 10, odd, 4, fake, 1 << 20) == E.BTC_ERR_ALIGN
     t = B.btc_shape_init(64, 100, 10, 512)
     t.words_per_row += 1                 # a shape edited after btc_shape_init
     assert L.btc_unpack(None, ctypes.byref(t), fake, fake) == E.BTC_ERR_SHAPE

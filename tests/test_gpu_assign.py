@@ -82,3 +82,71 @@ def test_assign_13b_matrix_full_size(G, oracle):
     z, d2 = _run(G, vec, 10, cb)
     z_ref, d_ref = oracle.assign(vec, 10, cb)
     assert np.array_equal(z, z_ref) and np.array_equal(d2, d_ref)
+
+
+# ---- M-step (btc_update): majority vote per cluster, bit-exact
+
+def _update(G, vec, z, v, cb, ws=None):
+    import torch
+    B = G.B
+    K = cb.shape[0]
+    if ws is None:
+        ws = torch.zeros(B.btc_update_workspace_bytes(v, K), dtype=torch.uint8, device="cuda")
+    cbd = G.dev(cb.copy())
+    B.btc_update(G.dev(vec), G.dev(z.astype(np.int32)), vec.shape[0], v, cbd, K, ws)
+    torch.cuda.synchronize()
+    assert not bool(ws.any()), "workspace not handed back zero-filled"
+    return cbd.cpu().numpy().view(np.uint32), ws
+
+
+UPDATE_CASES = [(1, 10, 256), (5000, 10, 256), (100001, 10, 512), (30000, 9, 1024), (4097, 4, 5), (60000, 16, 4096),
+                (3000, 20, 65536), (777, 32, 100), (2048, 10, 1), (1025, 1, 2), (400000, 10, 1400)]
+
+
+@pytest.mark.parametrize("N,v,K", UPDATE_CASES)
+def test_update_matches_oracle(G, oracle, N, v, K):
+    print(f"update N={N} v={v} K={K}", flush=True)
+    rng = np.random.default_rng(N + 7 * v + K)
+    cb = (rng.integers(0, 1 << 32, size=K, dtype=np.uint64) & np.uint64((1 << v) - 1)).astype(np.uint32)
+    vec = _vectors(rng, N, v, cb)
+    z = rng.integers(0, K, size=N).astype(np.int32)
+    if K > 2:
+        z[z == K // 2] = 0                                   # an empty cluster keeps its centroid
+    new, _ = _update(G, vec, z, v, cb)
+    assert np.array_equal(new, oracle.update(vec, z, v, cb))
+
+
+def test_one_clustering_round_on_the_gpu(G, oracle):
+    """E-step then M-step on the GPU, twice through one workspace, against the oracle's round."""
+    import torch
+    rng = np.random.default_rng(21)
+    v, K, N = 10, 256, 200000
+    cb = S.draw_codebook(rng, v, K)
+    vec = _vectors(rng, N, v, cb)
+    ws = None
+    cb_ref = cb
+    for _ in range(2):
+        z, _ = _run(G, vec, v, cb_ref)
+        z_ref, _ = oracle.assign(vec, v, cb_ref)
+        assert np.array_equal(z, z_ref)
+        new, ws = _update(G, vec, z, v, cb_ref, ws)
+        cb_ref = oracle.update(vec, z_ref, v, cb_ref)
+        assert np.array_equal(new, cb_ref)
+
+
+def test_update_rejects_an_assignment_out_of_range(G):
+    import torch
+    B = G.B
+    rng = np.random.default_rng(22)
+    v, K, N = 10, 64, 5000
+    cb = S.draw_codebook(rng, v, K)
+    vec = rng.integers(0, 1 << v, size=N).astype(np.uint32)
+    z = rng.integers(0, K, size=N).astype(np.int32)
+    z[1234] = K
+    ws = torch.zeros(B.btc_update_workspace_bytes(v, K), dtype=torch.uint8, device="cuda")
+    cbd = G.dev(cb.copy())
+    with pytest.raises(B.BtcError) as e:
+        B.btc_update(G.dev(vec), G.dev(z), N, v, cbd, K, ws)
+    assert e.value.status == B.binding.BTC_ERR_INDEX_RANGE
+    torch.cuda.synchronize()
+    assert np.array_equal(cbd.cpu().numpy().view(np.uint32), cb) and not bool(ws.any())
