@@ -432,6 +432,15 @@ def main():
             else:   # xor, bit count, shift-or, minimum per (vector, centroid) pair on 256 x 64 lanes at 2.4 GHz
                 row.update(route="all pairs", lane_ops_per_s=round(4.0 * N * K_ / us * 1e6, -9),
                            frac_alu=round(4.0 * N * K_ / us * 1e6 / 39.3e12, 4))
+            # the M-step on the assignment just computed (the call waits for the stream: host round trip included)
+            wsu = torch.zeros(B.btc_update_workspace_bytes(v_, K_), dtype=torch.uint8, device=dev)
+            cb2 = cbk.clone()
+            upd = lambda: B.btc_update(vec, zz, N, v_, cb2, K_, wsu)
+            upd()
+            t0 = time.perf_counter()
+            for _ in range(5):
+                upd()
+            row["update_us"] = round((time.perf_counter() - t0) / 5 * 1e6, 1)
             assign[tag] = row
             del vec, zz, dd
 
