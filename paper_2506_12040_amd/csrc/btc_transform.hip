@@ -15,11 +15,12 @@
 //   stage 2:  Z[j1][jj]  = sum_i1 P1[i1][j1] Y1[i1][jj]
 // The workgroup keeps P1 and its slice of P2 in LDS and walks over the rows of X dealt to it; a
 // row is staged with its signs applied (a flip of the sign bit: exact).  fp32 accumulation in a
-// fixed order: deterministic.  Two shapes of the same kernel: for a few rows (decode) the call is
+// fixed order: deterministic.  Two shapes of this kernel: for a few rows (decode) the call is
 // a chain of latencies, so a workgroup has 1024 threads and every dot product of both stages is
-// cut into KS = 4 pieces whose sums meet in LDS; for many rows (prefill) 256 threads, whole dot
-// products, four columns per thread, and the rows are dealt to about five workgroups per compute
-// unit.  Every global load of a phase is issued before the first one is used.
+// cut into KS = 4 pieces whose sums meet in LDS; for many rows 256 threads, whole dot products,
+// four columns per thread, and the rows are dealt to about five workgroups per compute unit.
+// Every global load of a phase is issued before the first one is used.  Many rows of bf16
+// activations (prefill) take the matrix-core kernel further down instead.
 #include <hip/hip_fp16.h>
 
 #include <type_traits>
