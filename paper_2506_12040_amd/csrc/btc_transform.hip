@@ -425,10 +425,15 @@ __global__ __launch_bounds__(kThreads) void transform_mfma_kernel(const uint16_t
         const int rows_left = n1 - (jt * 32 + 4 * h);            // rows 8 (e / 4) + e % 4 below this count exist
         auto store_tile = [&](auto* out) __attribute__((always_inline)) {
           typedef typename std::remove_pointer<decltype(out)>::type T;
+          if ((jt + 1) * 32 <= n1) {                              // a whole block of rows (uniform): no per-element test
 #pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const int r = 8 * (e >> 2) + (e & 3);
-            if (r < rows_left) out[at0 + (size_t)(r * n2)] = (T)z[e];
+            for (int e = 0; e < 16; ++e) out[at0 + (size_t)((8 * (e >> 2) + (e & 3)) * n2)] = (T)z[e];
+          } else {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+              const int r = 8 * (e >> 2) + (e & 3);
+              if (r < rows_left) out[at0 + (size_t)(r * n2)] = (T)z[e];
+            }
           }
         };
         if (y_dtype == BTC_BF16) store_tile((__bf16*)Y);
