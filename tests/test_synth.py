@@ -63,3 +63,22 @@ def test_config_tables():
     assert len(S.config_cases(0)) == 1 and len(S.config_cases(1)) == 9
     assert len(S.config_cases(2)) == 3 and len(S.config_cases(3)) == 6 and len(S.config_cases(4)) == 12
     assert all(c["seed"] == 0 for k in range(5) for c in S.config_cases(k))
+
+
+def test_transform_pair_is_seeded_and_well_formed():
+    bits, P1, P2 = S.draw_transform(3, 6, 10)
+    bits2, Q1, Q2 = S.draw_transform(3, 6, 10)
+    assert np.array_equal(bits, bits2) and np.array_equal(P1, Q1) and np.array_equal(P2, Q2)
+    assert bits.dtype == np.uint32 and bits.shape == (2,) and (int(bits[1]) >> (60 - 32)) == 0   # tail bits zero
+    assert P1.shape == (6, 6) and P2.shape == (10, 10) and P1.dtype == np.float32
+    for P in (P1, P2):                                       # near-orthogonal, hence invertible and well conditioned
+        assert np.linalg.cond(P.astype(np.float64)) < 2.0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in r.stderr
