@@ -17,7 +17,8 @@
 // row is staged with its signs applied (a flip of the sign bit: exact).  fp32 accumulation in a
 // fixed order: deterministic.  Two shapes of this kernel: for a few rows (decode) the call is
 // a chain of latencies, so a workgroup has 1024 threads and every dot product of both stages is
-// cut into KS = 4 pieces whose sums meet in LDS; for many rows 256 threads, whole dot products,
+// cut into KS = 4 pieces held by neighbouring lanes, whose sums meet by two cross-lane additions;
+// for many rows 256 threads, whole dot products,
 // four columns per thread, and the rows are dealt to about five workgroups per compute unit.
 // Every global load of a phase is issued before the first one is used.  Many rows of bf16
 // activations (prefill) take the matrix-core kernel further down instead.
@@ -37,7 +38,7 @@ constexpr int kMaxN2 = 256;
 
 struct Layout {                // byte offsets into dynamic LDS
   int rs;                      // staged row stride in 16-bit elements (even; rs / 2 odd: rows start in different banks)
-  int p1, p2, y1, part, total;
+  int p1, p2, y1, total;
 };
 
 static Layout layout_of(int n1, int n2, int KS) {
@@ -45,10 +46,9 @@ static Layout layout_of(int n1, int n2, int KS) {
   L.rs = 2 * (((n2 + 1) / 2) | 1);
   auto up16 = [](int b) { return (b + 15) & ~15; };
   L.p1 = up16(n1 * L.rs * 2);
-  L.p2 = L.p1 + up16(n1 * n1 * 4);
+  L.p2 = L.p1 + up16((n1 * n1 + KS * 32) * 4);                // up to 31 words of padding per piece, here and in Y1
   L.y1 = L.p2 + up16((n2 + KS) * kCB * 4);
-  L.part = L.y1 + up16(n1 * kCB * 4);
-  L.total = L.part + (KS > 1 ? up16(KS * n1 * kCB * 4) : 0);
+  L.total = L.y1 + up16((n1 * kCB + KS * 32) * 4);
   return L;
 }
 
@@ -81,15 +81,30 @@ __global__ __launch_bounds__(kThreads * KS) void transform_kernel(const uint16_t
   uint16_t* xs = (uint16_t*)smem;
   float* p1s = (float*)(smem + L.p1);
   float* p2s = (float*)(smem + L.p2);        // row i2 at i2 * kCB + (i2 / len2) * kCB: a pad per piece, against bank conflicts
-  float* y1 = (float*)(smem + L.y1);         // [n1][kCB]
-  float* part = (float*)(smem + L.part);     // [KS][n1][kCB] partial sums of either stage (KS > 1)
+  float* y1 = (float*)(smem + L.y1);         // [n1][kCB], row i1 at i1 * kCB + (i1 / len1) * pady
   const int tid = threadIdx.x;
   const int n = n1 * n2;
   const int j0 = blockIdx.x * kCB;
   const int ncol = min(kCB, n2 - j0);
   const int len2 = (((n2 + KS - 1) / KS) + 1) & ~1;   // piece of a stage-1 dot product (even)
   const int len1 = (n1 + KS - 1) / KS;                // piece of a stage-2 dot product
-  const float rcp_n2 = 1.0f / (float)n2;
+  const float rcp_n2 = 1.0f / (float)n2, rcp_n1 = 1.0f / (float)n1, rcp_len1 = 1.0f / (float)len1;
+  // The KS lanes that hold the pieces of one dot product are neighbours (a quad): their sums meet by two
+  // cross-lane additions, ((p0 + p1) + (p2 + p3)), and the lane of piece 0 keeps the result.  The rows of P1 and
+  // of Y1 that belong to piece ks are shifted by a few words, so that the four lanes of a quad, which read the same
+  // column of different pieces, hit different banks: the start of piece ks is 8 ks words (mod 32) after that of
+  // piece 0, whatever the sizes.
+  const int pad1 = (8 - len1 * n1) & 31, pady = (8 - len1 * kCB) & 31;
+  auto quad_sum = [](float a) __attribute__((always_inline)) {
+    if constexpr (KS == 4) {
+      a += __shfl_xor(a, 1, 64);
+      a += __shfl_xor(a, 2, 64);
+    }
+    return a;
+  };
+  auto piece_of = [&](int i1) __attribute__((always_inline)) {
+    return KS > 1 ? (int)(((float)i1 + 0.5f) * rcp_len1) : 0;  // i1 / len1, exact for these sizes
+  };
   const bool x_vec = (n2 & 7) == 0;          // a group of 8 channels stays inside one row of the n1 x n2 view, and
                                              // rows of X start 16-byte aligned
 
@@ -150,7 +165,7 @@ __global__ __launch_bounds__(kThreads * KS) void transform_kernel(const uint16_t
       p2s[i2 * kCB + (i2 / len2) * kCB + jj] = jj < ncol ? P2[(size_t)i2 * n2 + j0 + jj] : 0.f;
     }
   }
-  if (((n1 * n1) & 3) == 0) {
+  if ((n1 & 3) == 0) {                       // four consecutive elements stay inside one row of P1
     constexpr int U = 4;
     const int quads = (n1 * n1) >> 2;
     for (int base = tid; base < quads; base += T * U) {
@@ -158,11 +173,19 @@ __global__ __launch_bounds__(kThreads * KS) void transform_kernel(const uint16_t
 #pragma unroll
       for (int u = 0; u < U; ++u) v[u] = *(const float4*)(P1 + 4 * (size_t)min(base + u * T, quads - 1));
 #pragma unroll
-      for (int u = 0; u < U; ++u)
-        if (base + u * T < quads) *(float4*)(p1s + 4 * (base + u * T)) = v[u];
+      for (int u = 0; u < U; ++u) {
+        const int qd = base + u * T;
+        if (qd < quads) {
+          const int i1 = (int)(((float)(4 * qd) + 0.5f) * rcp_n1);
+          *(float4*)(p1s + 4 * qd + piece_of(i1) * pad1) = v[u];   // pad1 is a multiple of 4 here
+        }
+      }
     }
   } else {
-    for (int t = tid; t < n1 * n1; t += T) p1s[t] = P1[t];
+    for (int t = tid; t < n1 * n1; t += T) {
+      const int i1 = (int)(((float)t + 0.5f) * rcp_n1);
+      p1s[t + piece_of(i1) * pad1] = P1[t];
+    }
   }
 
   const int items = n1 * IPR * KS;           // item = (row index, group of CPI columns, piece)
@@ -203,51 +226,37 @@ __global__ __launch_bounds__(kThreads * KS) void transform_kernel(const uint16_t
 #pragma unroll
         for (int c = 0; c < CPI; ++c) a[c] = fmaf(x0, pc[i2 * kCB + c], a[c]);
       }
-      float* dst = (KS > 1 ? part + ks * n1 * kCB : y1) + i1 * kCB + c0;
 #pragma unroll
-      for (int c = 0; c < CPI; ++c) dst[c] = a[c];
+      for (int c = 0; c < CPI; ++c) a[c] = quad_sum(a[c]);
+      if (ks == 0) {
+        float* dst = y1 + i1 * kCB + piece_of(i1) * pady + c0;
+#pragma unroll
+        for (int c = 0; c < CPI; ++c) dst[c] = a[c];
+      }
     }
     __syncthreads();
-    if constexpr (KS > 1) {                  // the pieces of a dot product are added in ascending order
-      for (int t = tid; t < n1 * kCB; t += T) {
-        float sum = part[t];
-#pragma unroll
-        for (int k = 1; k < KS; ++k) sum += part[k * n1 * kCB + t];
-        y1[t] = sum;
-      }
-      __syncthreads();
-    }
-    // ---- stage 2: piece ks of  Z[j1][c0 .. c0 + CPI - 1]
+    // ---- stage 2: piece ks of  Z[j1][c0 .. c0 + CPI - 1]; a wave's lanes: 16 neighbouring j1 x KS pieces
     for (int it = tid; it < items; it += T) {
-      const int rest = it % (n1 * IPR), ks = it / (n1 * IPR);     // neighbouring lanes: neighbouring j1
+      const int ks = it % KS, rest = it / KS;
       const int j1 = rest % n1, c0 = (rest / n1) * CPI;
       const int lo = ks * len1, hi = min(n1, lo + len1);
+      const float* pc = p1s + ks * pad1 + j1;
+      const float* yc = y1 + ks * pady + c0;
       float a[CPI];
 #pragma unroll
       for (int c = 0; c < CPI; ++c) a[c] = 0.f;
       for (int i1 = lo; i1 < hi; ++i1) {
-        const float p = p1s[i1 * n1 + j1];
+        const float p = pc[i1 * n1];
 #pragma unroll
-        for (int c = 0; c < CPI; ++c) a[c] = fmaf(p, y1[i1 * kCB + c0 + c], a[c]);
+        for (int c = 0; c < CPI; ++c) a[c] = fmaf(p, yc[i1 * kCB + c], a[c]);
       }
-      if constexpr (KS > 1) {
 #pragma unroll
-        for (int c = 0; c < CPI; ++c) part[ks * n1 * kCB + j1 * kCB + c0 + c] = a[c];
-      } else {
+      for (int c = 0; c < CPI; ++c) a[c] = quad_sum(a[c]);
+      if (ks == 0) {
         const size_t at = (size_t)m * n + (size_t)j1 * n2 + j0 + c0;
 #pragma unroll
         for (int c = 0; c < CPI; ++c)
           if (c0 + c < ncol) store_out(Y, at + c, a[c], y_dtype);
-      }
-    }
-    if constexpr (KS > 1) {
-      __syncthreads();
-      for (int t = tid; t < n1 * kCB; t += T) {
-        float sum = part[t];
-#pragma unroll
-        for (int k = 1; k < KS; ++k) sum += part[k * n1 * kCB + t];
-        const int j1 = t / kCB, jj = t - j1 * kCB;
-        if (jj < ncol) store_out(Y, (size_t)m * n + (size_t)j1 * n2 + j0 + jj, sum, y_dtype);
       }
     }
   }
@@ -498,7 +507,8 @@ btc_status btc_transform(void* stream, const void* X, btc_dtype x_dtype, int32_t
   // many rows too (16 waves per compute unit instead of 4).
   const bool few = (long long)M * n_cb <= 512;
   const bool big = layout_of(n1, n2, 1).total > 48 * 1024;
-  const int KS = (few || big) ? 4 : 1;
+  int KS = (few || big) ? 4 : 1;
+  if (KS == 4 && layout_of(n1, n2, 4).total > 160 * 1024 - 256) KS = 1;   // the largest factors: no room for the pads
   const Layout L = layout_of(n1, n2, KS);
   if (L.total > 160 * 1024 - 256) return BTC_ERR_UNSUPPORTED;
   int gy = few ? M : big ? 256 / n_cb : 1280 / n_cb;
