@@ -32,7 +32,7 @@ namespace btc {
 namespace transform {
 
 constexpr int kThreads = 256;
-constexpr int kCB = 8;         // columns of P2 per workgroup
+constexpr int kCB = 8;         // columns of P2 per workgroup (4 when a call has very few rows: more workgroups)
 constexpr int kMaxN1 = 128;
 constexpr int kMaxN2 = 256;
 
@@ -41,7 +41,7 @@ struct Layout {                // byte offsets into dynamic LDS
   int p1, p2, y1, total;
 };
 
-static Layout layout_of(int n1, int n2, int KS) {
+static Layout layout_of(int n1, int n2, int KS, int kCB = 8) {
   Layout L;
   L.rs = 2 * (((n2 + 1) / 2) | 1);
   auto up16 = [](int b) { return (b + 15) & ~15; };
@@ -68,14 +68,15 @@ __device__ __forceinline__ void store_out(void* Y, size_t at, float v, int y_dty
   }
 }
 
-// KS: pieces per dot product (threads = 256 KS); CPI: columns per work item.
-template <bool BF16, int KS, int CPI>
+// KS: pieces per dot product (threads = 256 KS); CPI: columns per work item; CB: columns per workgroup.
+template <bool BF16, int KS, int CPI, int CB>
 __global__ __launch_bounds__(kThreads * KS) void transform_kernel(const uint16_t* __restrict__ X, int M, int n1, int n2,
                                                                  const uint32_t* __restrict__ sign_bits,
                                                                  const float* __restrict__ P1,
                                                                  const float* __restrict__ P2, void* __restrict__ Y,
                                                                  int y_dtype, Layout L) {
   constexpr int T = kThreads * KS;
+  constexpr int kCB = CB;
   constexpr int IPR = kCB / CPI;             // work items per row index
   extern __shared__ __align__(16) unsigned char smem[];
   uint16_t* xs = (uint16_t*)smem;
@@ -152,9 +153,10 @@ __global__ __launch_bounds__(kThreads * KS) void transform_kernel(const uint16_t
 
   // ---- the first row's activations are requested first, then the factors (once per workgroup)
   stage_x(blockIdx.y);
-  if ((n2 & 3) == 0) {                       // columns j0 .. j0 + 7 of a row of P2 are two aligned 16-byte pieces
-    for (int t = tid; t < 2 * n2; t += T) {
-      const int i2 = t >> 1, h = t & 1;
+  if ((n2 & 3) == 0) {                       // columns j0 .. j0 + kCB - 1 of a row of P2 are aligned 16-byte pieces
+    constexpr int PR = kCB / 4;
+    for (int t = tid; t < PR * n2; t += T) {
+      const int i2 = t / PR, h = t % PR;
       float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
       if (j0 + 4 * h < n2) v = *(const float4*)(P2 + (size_t)i2 * n2 + j0 + 4 * h);
       *(float4*)(p2s + i2 * kCB + (i2 / len2) * kCB + 4 * h) = v;
@@ -500,7 +502,7 @@ btc_status btc_transform(void* stream, const void* X, btc_dtype x_dtype, int32_t
       default: return launch_mfma<4>(q, Xm, M, n1, n2, sign_bits, P1, P2, Y, (int)y_dtype);
     }
   }
-  const int n_cb = (n2 + kCB - 1) / kCB;
+  int n_cb = (n2 + kCB - 1) / kCB;
   // A few rows: one workgroup of 1024 threads per (column block, row), dot products cut in four.
   // Many rows: 256 threads, and the rows are dealt to about five workgroups per compute unit.
   // Large factors leave room for one workgroup per compute unit only: then the 1024-thread shape serves
@@ -509,15 +511,19 @@ btc_status btc_transform(void* stream, const void* X, btc_dtype x_dtype, int32_t
   const bool big = layout_of(n1, n2, 1).total > 48 * 1024;
   int KS = (few || big) ? 4 : 1;
   if (KS == 4 && layout_of(n1, n2, 4).total > 160 * 1024 - 256) KS = 1;   // the largest factors: no room for the pads
-  const Layout L = layout_of(n1, n2, KS);
+  // Very few rows: blocks of 4 columns, i.e. twice the workgroups, each with half the arithmetic.
+  const int cb = (KS == 4 && few && (long long)M * n_cb <= 128 && n2 >= 8) ? 4 : kCB;
+  if (cb == 4) n_cb = (n2 + 3) / 4;
+  const Layout L = layout_of(n1, n2, KS, cb);
   if (L.total > 160 * 1024 - 256) return BTC_ERR_UNSUPPORTED;
   int gy = few ? M : big ? 256 / n_cb : 1280 / n_cb;
   if (gy < 1) gy = 1;
   if (gy > M) gy = M;
   static bool attr_set = false;              // one-time kernel attributes, not call state
   if (!attr_set) {
-    const void* fns[4] = {(const void*)transform_kernel<false, 4, 2>, (const void*)transform_kernel<true, 4, 2>,
-                          (const void*)transform_kernel<false, 1, 4>, (const void*)transform_kernel<true, 1, 4>};
+    const void* fns[6] = {(const void*)transform_kernel<false, 4, 2, 8>, (const void*)transform_kernel<true, 4, 2, 8>,
+                          (const void*)transform_kernel<false, 4, 2, 4>, (const void*)transform_kernel<true, 4, 2, 4>,
+                          (const void*)transform_kernel<false, 1, 4, 8>, (const void*)transform_kernel<true, 1, 4, 8>};
     for (const void* fn : fns)
       if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256) != hipSuccess)
         return BTC_ERR_HIP;
@@ -526,12 +532,15 @@ btc_status btc_transform(void* stream, const void* X, btc_dtype x_dtype, int32_t
   const bool bf = x_dtype == BTC_BF16;
   const dim3 grid(n_cb, gy);
   const uint16_t* Xp = (const uint16_t*)X;
-  if (KS == 4) {
-    if (bf) transform_kernel<true, 4, 2><<<grid, kThreads * 4, L.total, q>>>(Xp, M, n1, n2, sign_bits, P1, P2, Y, (int)y_dtype, L);
-    else transform_kernel<false, 4, 2><<<grid, kThreads * 4, L.total, q>>>(Xp, M, n1, n2, sign_bits, P1, P2, Y, (int)y_dtype, L);
+  if (KS == 4 && cb == 4) {
+    if (bf) transform_kernel<true, 4, 2, 4><<<grid, kThreads * 4, L.total, q>>>(Xp, M, n1, n2, sign_bits, P1, P2, Y, (int)y_dtype, L);
+    else transform_kernel<false, 4, 2, 4><<<grid, kThreads * 4, L.total, q>>>(Xp, M, n1, n2, sign_bits, P1, P2, Y, (int)y_dtype, L);
+  } else if (KS == 4) {
+    if (bf) transform_kernel<true, 4, 2, 8><<<grid, kThreads * 4, L.total, q>>>(Xp, M, n1, n2, sign_bits, P1, P2, Y, (int)y_dtype, L);
+    else transform_kernel<false, 4, 2, 8><<<grid, kThreads * 4, L.total, q>>>(Xp, M, n1, n2, sign_bits, P1, P2, Y, (int)y_dtype, L);
   } else {
-    if (bf) transform_kernel<true, 1, 4><<<grid, kThreads, L.total, q>>>(Xp, M, n1, n2, sign_bits, P1, P2, Y, (int)y_dtype, L);
-    else transform_kernel<false, 1, 4><<<grid, kThreads, L.total, q>>>(Xp, M, n1, n2, sign_bits, P1, P2, Y, (int)y_dtype, L);
+    if (bf) transform_kernel<true, 1, 4, 8><<<grid, kThreads, L.total, q>>>(Xp, M, n1, n2, sign_bits, P1, P2, Y, (int)y_dtype, L);
+    else transform_kernel<false, 1, 4, 8><<<grid, kThreads, L.total, q>>>(Xp, M, n1, n2, sign_bits, P1, P2, Y, (int)y_dtype, L);
   }
   return launch_status();
 }
