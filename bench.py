@@ -401,6 +401,38 @@ def main():
                                     GBps=round(nbytes / us / 1e3, 1), frac_hbm=round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4),
                                     engine="fp32 vector ALU" if M <= 16 else "bf16 matrix cores, 3-part operands")
             transform[f"n={n} ({n1}x{n2})"] = row
+        # one decoder layer at decode with its four transforms in place (the inputs of q/k/v, of o, of gate/up
+        # and of down), cold weights, one graph over all layer copies: what the transform adds to the headline step
+        tr = {}
+        for (n1, n2) in [(64, 80), (108, 128)]:
+            bits, P1, P2 = S.draw_transform(0, n1, n2)
+            tr[n1 * n2] = (n1, n2, torch.from_numpy(bits.view(np.int32)).to(dev), torch.from_numpy(P1).to(dev),
+                           torch.from_numpy(P2).to(dev), torch.empty(n1 * n2, dtype=torch.float16, device=dev))
+
+        def run_layer_t(L):
+            for ci, c in enumerate(calls_per_layer[L]):
+                p = c["p"]
+                n1, n2, bd, p1d, p2d, xt = tr[p["s"].in_]
+                if ci in (0, 3, 4, 6):
+                    B.btc_transform(p["x"], B.BTC_F16, 1, n1, n2, bd, p1d, p2d, xt, B.BTC_F16)
+                B.btc_gemv(p["s"], c["packed"], p["codebook"], p["alpha"], p["mu"], xt, 1, c["y"], B.BTC_F16, ws)
+
+        run_layer_t(0)
+        torch.cuda.synchronize()
+        gt = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gt):
+            for L in range(args.layers):
+                run_layer_t(L)
+        gt.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            gt.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        transform["decoder_layer_decode_with_4_transforms_us"] = round(e0.elapsed_time(e1) * 1e3 / (5 * args.layers), 2)
+        transform["decoder_layer_decode_without_us"] = round(ms_per_step * 1e3, 2)
 
     # ---- E-step of the codebook clustering (btc_assign): the length-10 vectors of a 5120 x 5120 and of a
     # 13824 x 5120 sign matrix against 256 centroids; a setting with long vectors (no pattern table)
