@@ -16,13 +16,20 @@
  *     comment says "host".  The library allocates no device memory and keeps
  *     no state between calls; scratch space is the caller's `workspace`.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *     Compute calls enqueue work and return; only btc_pack waits (see there).
+ *     Compute calls enqueue work and return; only btc_pack and btc_update
+ *     wait, to return the result of a range check (see there).
  *   - Array pointers must be 16-byte aligned (BTC_ERR_ALIGN otherwise).
- *   - Errors are returned, never thrown; on an error nothing was enqueued.
+ *   - Errors are returned, never thrown; on an argument error nothing was
+ *     enqueued.
  *   - Matrices are row-major.  Activations are X[rows][in], outputs
  *     Y[rows][out] (Y = X W^T, Section "Integration into Transformer
  *     Architecture").  A row of X has exactly `in` elements; positions
  *     in .. nchunks*v-1 of the last chunk are logical zeros and are never read.
+ *
+ * Besides the layer itself (btc_pack, btc_unpack, btc_gemv, btc_gemm) the
+ * library holds the step in front of it at inference, btc_transform (the online
+ * activation transform), and one round of the offline codebook clustering that
+ * produces the indices, btc_assign and btc_update.
  */
 #ifndef BTC_H_
 #define BTC_H_
