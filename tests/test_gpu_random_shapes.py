@@ -2,7 +2,7 @@
 that feed table entries straight into matrix-core operands (2..16 activation rows, one row on wide matrices,
 btc_gemm with up to 64 rows).  Second set: every other route -- 65..128 rows on large matrices, the tiled
 kernel at any M, one row with arbitrary chunk length and codebook size, btc_gemm on settings only the generic
-kernel covers.  Shapes are drawn so that ragged row tiles, ragged last chunks, activation rows
+kernel covers.  Third set: btc_transform, btc_assign and btc_update on random sizes.  Shapes are drawn so that ragged row tiles, ragged last chunks, activation rows
 that are not 16-byte aligned and every supported index width come up; the tolerances are those of the other
 parity tests."""
 import numpy as np
@@ -84,3 +84,66 @@ def test_random_shape(G, oracle, kind, seed, out, n_in, v, K, rows, xd):
     else:
         y = G.gemm(dl, x, B.BTC_BF16 if xd == "bf16" else B.BTC_F16, B.BTC_F32)
     G.assert_close(y[:, sel], y_ref, f"{kind} {out}x{n_in} v{v} K{K} rows={rows} {xd}")
+
+
+def _aux_cases(seed, n):
+    """Seeded random calls of btc_transform, btc_assign and btc_update."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        s = int(rng.integers(1, 100000))
+        if rng.random() < 0.4:
+            n2 = int(rng.choice([int(rng.integers(1, 257)), 16 * int(rng.integers(1, 17)), 8 * int(rng.integers(1, 33))]))
+            cases.append(("transform", s, int(rng.integers(1, 129)), n2, int(rng.choice([1, 2, 5, 16, 40, 64, 65, 100, 300])),
+                          "bf16" if rng.random() < 0.6 else "f16", str(rng.choice(["f32", "f16", "bf16"]))))
+        else:
+            K = int(rng.choice([1, 2, 3, 17, 128, 256, 512, 1000, 1024, 4096, 20000]))
+            N = int(rng.choice([1, 3, 255, 1024, 4099, 70001, 300007])) if K <= 4096 else int(rng.choice([1, 1000, 5003]))
+            cases.append(("cluster", s, N, int(rng.choice([1, 2, 4, 7, 9, 10, 11, 12, 13, 16, 20, 32])), K, "", ""))
+    return cases
+
+
+@pytest.mark.parametrize("kind,seed,a,b,c,xd,yd", _aux_cases(20250614, 40))
+def test_random_transform_and_clustering_calls(G, oracle, kind, seed, a, b, c, xd, yd):
+    import torch
+    B = G.B
+    rng = np.random.default_rng(seed)
+    print(f"random {kind} seed={seed} {a} {b} {c} {xd} {yd}", flush=True)
+    if kind == "transform":
+        n1, n2, M = a, b, c
+        y_dtype = {"f32": B.BTC_F32, "f16": B.BTC_F16, "bf16": B.BTC_BF16}[yd]
+        bits, P1, P2 = S.draw_transform(seed, n1, n2)
+        xb = S.draw_x(rng, M, n1 * n2, xd)
+        out = G.GuardedOutput(M, n1 * n2, {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[yd])
+        B.btc_transform(G.dev(xb), B.BTC_BF16 if xd == "bf16" else B.BTC_F16, M, n1, n2, G.dev(bits), G.dev(P1), G.dev(P2),
+                        out.payload, y_dtype)
+        out.check_guards()
+        y = out.numpy()
+        rows = np.unique(rng.integers(0, M, size=min(M, 4 if n1 * n2 > 4000 else 16)))
+        ref = oracle.transform(xb[rows], bits, P1, P2, xd)
+        rel = np.linalg.norm(y[rows] - ref) / np.linalg.norm(ref)
+        mabs = np.max(np.abs(y[rows] - ref)) / np.max(np.abs(ref))
+        tol = (1e-5, 1e-5) if yd == "f32" else (2e-3, 1e-2)
+        assert rel <= tol[0] and mabs <= tol[1] and np.isfinite(y).all(), (rel, mabs)
+        return
+    N, v, K = a, b, c
+    mask = np.uint32((1 << v) - 1 if v < 32 else 0xFFFFFFFF)
+    cb = (rng.integers(0, 1 << 32, size=K, dtype=np.uint64).astype(np.uint32)) & mask
+    vec = rng.integers(0, 1 << 32, size=N, dtype=np.uint64).astype(np.uint32)
+    if rng.random() < 0.5:      # near the centroids, junk above bit v
+        vec = (cb[rng.integers(0, K, size=N)] ^ (np.uint32(1) << rng.integers(0, v, size=N).astype(np.uint32))) | (vec & ~mask)
+    z = G.GuardedOutput(1, N, torch.int32)
+    d = G.GuardedOutput(1, N, torch.int32)
+    B.btc_assign(G.dev(vec), N, v, G.dev(cb), K, z.payload, d.payload)
+    z.check_guards()
+    d.check_guards()
+    z_ref, d_ref = oracle.assign(vec, v, cb)
+    assert np.array_equal(z.payload.cpu().numpy(), z_ref) and np.array_equal(d.payload.cpu().numpy(), d_ref)
+    if N * K <= 4e8:
+        zz = z_ref if rng.random() < 0.5 else rng.integers(0, K, size=N).astype(np.int32)
+        ws = torch.zeros(B.btc_update_workspace_bytes(v, K), dtype=torch.uint8, device="cuda")
+        cbd = G.dev(cb.copy())
+        B.btc_update(G.dev(vec), G.dev(zz), N, v, cbd, K, ws)
+        torch.cuda.synchronize()
+        assert not bool(ws.any())
+        assert np.array_equal(cbd.cpu().numpy().view(np.uint32), oracle.update(vec, zz, v, cb))
