@@ -6,11 +6,15 @@
 // Element t of the new centroid is +1 iff  2 * (members with element t = +1) >= members.  So the
 // call counts, per cluster, its members and the +1s of every element: v + 1 counters per cluster
 // in the caller's workspace.  Pass 1: a workgroup adds up its share of the vectors in an LDS copy
-// of the counters when they fit (K (v + 1) <= 16128; one LDS atomic per set bit and one per vector)
-// and then adds its non-zero counters to the workspace; otherwise the atomics go to the workspace
-// directly.  Pass 2: one thread per cluster forms the centroid and clears its counters, so the
+// of the counters (one LDS atomic per set bit and one per vector) and then adds its non-zero
+// counters to the workspace.  When the counters of all clusters do not fit LDS (more than 16128)
+// the clusters are cut into ranges that do, and every range gets its own workgroups, which read all
+// the vectors and count only those of their range: re-reading 8 bytes per vector is far cheaper
+// than atomics that go to memory.  Pass 2: one thread per cluster forms the centroid and clears its counters, so the
 // workspace is left zero-filled for the next call.  Integer sums: the result does not depend on the
 // order of the atomics.
+#include <algorithm>
+
 #include "btc_internal.h"
 
 namespace btc {
@@ -21,15 +25,14 @@ constexpr int kMaxLdsCounters = 16128;   // 63 KB
 
 __global__ __launch_bounds__(kThreads) void count_kernel(const uint32_t* __restrict__ vectors, const int32_t* __restrict__ z,
                                                         long long N, int v, int K, uint32_t* __restrict__ counts,
-                                                        int use_lds, uint32_t* __restrict__ bad) {
-  extern __shared__ uint32_t local[];                          // [K][v + 1] when use_lds
+                                                        int KR, uint32_t* __restrict__ bad) {
+  extern __shared__ uint32_t local[];                          // [KR][v + 1]: clusters k0 .. k0 + KR - 1
   const int W = v + 1;
   const int tid = threadIdx.x;
-  if (use_lds) {
-    for (int t = tid; t < K * W; t += kThreads) local[t] = 0u;
-    __syncthreads();
-  }
-  uint32_t* dst = use_lds ? local : counts;
+  const int k0 = blockIdx.y * KR;
+  const int kn = min(KR, K - k0);
+  for (int t = tid; t < kn * W; t += kThreads) local[t] = 0u;
+  __syncthreads();
   const long long step = (long long)gridDim.x * kThreads;
   for (long long i = (long long)blockIdx.x * kThreads + tid; i < N; i += step) {
     const int k = z[i];
@@ -37,8 +40,9 @@ __global__ __launch_bounds__(kThreads) void count_kernel(const uint32_t* __restr
       *bad = 1u;
       continue;
     }
+    if (k < k0 || k >= k0 + kn) continue;                      // another range's cluster
     uint32_t b = vectors[i] & (v >= 32 ? 0xFFFFFFFFu : ((1u << v) - 1u));
-    uint32_t* row = dst + (size_t)k * W;
+    uint32_t* row = local + (size_t)(k - k0) * W;
     atomicAdd(row + v, 1u);
     while (b) {
       const int t = __builtin_ctz(b);
@@ -46,12 +50,10 @@ __global__ __launch_bounds__(kThreads) void count_kernel(const uint32_t* __restr
       atomicAdd(row + t, 1u);
     }
   }
-  if (use_lds) {
-    __syncthreads();
-    for (int t = tid; t < K * W; t += kThreads) {
-      const uint32_t c = local[t];
-      if (c) atomicAdd(counts + t, c);
-    }
+  __syncthreads();
+  for (int t = tid; t < kn * W; t += kThreads) {
+    const uint32_t c = local[t];
+    if (c) atomicAdd(counts + (size_t)k0 * W + t, c);
   }
 }
 
@@ -97,10 +99,14 @@ btc_status btc_update(void* stream, const uint32_t* vectors, const int32_t* z, i
   uint32_t* counts = (uint32_t*)workspace;
   const size_t n_counters = (size_t)K * (size_t)(v + 1);
   uint32_t* bad = counts + ((n_counters + 3) & ~(size_t)3);
-  const int use_lds = n_counters <= (size_t)kMaxLdsCounters;
+  const int KR = std::min(K, kMaxLdsCounters / (v + 1));       // clusters per range (>= 488)
+  const int ranges = (K + KR - 1) / KR;
   long long want = (N + kThreads - 1) / kThreads;
-  const unsigned grid = (unsigned)(want < 512 ? want : 512);
-  count_kernel<<<grid, kThreads, use_lds ? n_counters * 4 : 0, q>>>(vectors, z, (long long)N, v, K, counts, use_lds, bad);
+  long long gx = 512 / ranges;                                 // about two workgroups per compute unit in all
+  if (gx < 1) gx = 1;
+  if (gx > want) gx = want;
+  count_kernel<<<dim3((unsigned)gx, (unsigned)ranges), kThreads, (size_t)KR * (v + 1) * 4, q>>>(vectors, z, (long long)N, v, K,
+                                                                                              counts, KR, bad);
   if (launch_status() != BTC_OK) return BTC_ERR_HIP;
   vote_kernel<<<(K + 255) / 256, 256, 0, q>>>(counts, v, K, codebook, bad);
   if (launch_status() != BTC_OK) return BTC_ERR_HIP;
