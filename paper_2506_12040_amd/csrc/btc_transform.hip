@@ -299,14 +299,29 @@ __device__ __forceinline__ f32x16 mfma32(const uint4& a, const uint4& b, const f
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
+// f(integral_constant<int, I>) for I = Begin .. End - 1, fully unrolled
+template <int Begin, int End, class F>
+__device__ __forceinline__ void static_for_it(F&& f) {
+  if constexpr (Begin < End) {
+    f(std::integral_constant<int, Begin>{});
+    static_for_it<Begin + 1, End>(f);
+  }
+}
+
 // IT = ceil(n1 / 32): blocks of 32 rows i1 (and of 32 rows j1).  Needs n2 % 16 == 0.
+// waves per workgroup: with three or four blocks the operands of P1 fill most of LDS (one workgroup per compute
+// unit), so the workgroup is made twice as large to keep two waves per SIMD
 template <int IT>
-__global__ __launch_bounds__(kThreads) void transform_mfma_kernel(const uint16_t* __restrict__ X, int M, int n1, int n2,
+constexpr int mfma_waves() { return IT <= 2 ? 4 : 8; }
+
+template <int IT>
+__global__ __launch_bounds__(64 * mfma_waves<IT>()) void transform_mfma_kernel(const uint16_t* __restrict__ X, int M, int n1, int n2,
                                                                  const uint32_t* __restrict__ sign_bits,
                                                                  const float* __restrict__ P1,
                                                                  const float* __restrict__ P2, void* __restrict__ Y,
                                                                  int y_dtype, int p2_bytes) {
   constexpr int KS1 = 2 * IT;                // 16-row steps of stage 2
+  constexpr int NWV = mfma_waves<IT>(), NT = 64 * NWV;
   extern __shared__ __align__(16) unsigned char smem[];
   uint4* P2op = (uint4*)smem;                // [step][part][lane]: B operands of stage 1
   uint4* P1op = (uint4*)(smem + p2_bytes);   // [block j1][step][part][lane]: A operands of stage 2
@@ -315,7 +330,7 @@ __global__ __launch_bounds__(kThreads) void transform_mfma_kernel(const uint16_t
   const int n = n1 * n2, KS2 = n2 >> 4;
   const int j2 = blockIdx.x * 32 + l32;
 
-  for (int it = tid; it < KS2 * 64; it += kThreads) {
+  for (int it = tid; it < KS2 * 64; it += NT) {
     const int ks = it >> 6, ln = it & 63, c = blockIdx.x * 32 + (ln & 31), hh = ln >> 5;
     uint32_t q[3][8];
 #pragma unroll
@@ -328,7 +343,7 @@ __global__ __launch_bounds__(kThreads) void transform_mfma_kernel(const uint16_t
       P2op[(ks * 3 + p) * 64 + ln] = make_uint4(q[p][0] | q[p][1] << 16, q[p][2] | q[p][3] << 16,
                                                q[p][4] | q[p][5] << 16, q[p][6] | q[p][7] << 16);
   }
-  for (int it = tid; it < IT * KS1 * 64; it += kThreads) {
+  for (int it = tid; it < IT * KS1 * 64; it += NT) {
     const int ln = it & 63, ks = (it >> 6) % KS1, jt = (it >> 6) / KS1;
     const int j1 = jt * 32 + (ln & 31), hh = ln >> 5;
     uint32_t q[3][8];
@@ -345,92 +360,91 @@ __global__ __launch_bounds__(kThreads) void transform_mfma_kernel(const uint16_t
   __syncthreads();
 
   const uint8_t* sign_bytes = (const uint8_t*)sign_bits;   // byte k / 8 holds the bits of channels k .. k + 7
-  // A operands of stage 1 come straight from global memory, PD steps ahead: slot u of the ring holds step
-  // ks0 + u of the current chunk of PD steps; once used it is refilled with step ks0 + PD + u of the same row
-  // or, in a row's last chunk, with step u of the wave's next row, whose first loads thus fly during stage 2.
-  constexpr int PD = IT <= 2 ? 4 : 2;
-  const int stride = 4 * gridDim.y;
-  auto load_a = [&](int mm, int ks, uint4 (&a)[IT], uint32_t (&sg)[IT]) __attribute__((always_inline)) {
-    const uint16_t* xrow = X + (size_t)mm * n;
-#pragma unroll
-    for (int it = 0; it < IT; ++it) {
-      const int i1 = min(it * 32 + l32, n1 - 1);               // rows past the end: a valid row, zeroed below
-      const int k = i1 * n2 + 16 * ks + 8 * h;
-      a[it] = *(const uint4*)(xrow + k);
-      sg[it] = sign_bytes[k >> 3];
-    }
+  // One block of 32 rows i1 at a time: its stage 1 (all steps over i2), the split of its 32 x 32 result, and its
+  // share of stage 2 for every block j1 -- so only one block of the intermediate is alive, next to the IT
+  // accumulators of the output.  A operands of stage 1 come straight from global memory, PD steps ahead: slot u of
+  // the ring holds step ks0 + u of the current chunk of PD steps; once used it is refilled with step ks0 + PD + u
+  // of the same block or, in a block's last chunk, with step u of the next block (of the wave's next row after
+  // the last block), so the loads always fly during the arithmetic of the block before.
+  constexpr int PD = 4;
+  const int stride = NWV * gridDim.y;
+  auto load_a = [&](int mm, int it, int ks, uint4& a, uint32_t& sg) __attribute__((always_inline)) {
+    const int i1 = min(it * 32 + l32, n1 - 1);                 // rows past the end: a valid row, zeroed below
+    const int k = i1 * n2 + 16 * ks + 8 * h;
+    a = *(const uint4*)(X + (size_t)mm * n + k);
+    sg = sign_bytes[k >> 3];
   };
-  uint4 ring[PD][IT];
-  uint32_t rsg[PD][IT];
-  const int m_first = blockIdx.y * 4 + wave;
+  uint4 ring[PD];
+  uint32_t rsg[PD];
+  const int m_first = blockIdx.y * NWV + wave;
   if (m_first < M) {
 #pragma unroll
     for (int u = 0; u < PD; ++u)
-      if (u < KS2) load_a(m_first, u, ring[u], rsg[u]);
+      if (u < KS2) load_a(m_first, 0, u, ring[u], rsg[u]);
   }
   for (int m = m_first; m < M; m += stride) {
-    f32x16 d1[IT];
+    f32x16 z[IT];
 #pragma unroll
-    for (int it = 0; it < IT; ++it)
+    for (int jt = 0; jt < IT; ++jt)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) d1[it][e] = 0.f;
-    for (int ks0 = 0; ks0 < KS2; ks0 += PD) {
-      const bool last_chunk = ks0 + PD >= KS2;
+      for (int e = 0; e < 16; ++e) z[jt][e] = 0.f;
+    static_for_it<0, IT>([&](auto it_c) {
+      constexpr int it = decltype(it_c)::value;
+      f32x16 d1;
 #pragma unroll
-      for (int u = 0; u < PD; ++u) {
-        const int ks = ks0 + u;
-        if (ks < KS2) {
-          const uint4 b0 = P2op[(ks * 3 + 0) * 64 + lane], b1 = P2op[(ks * 3 + 1) * 64 + lane],
-                      b2 = P2op[(ks * 3 + 2) * 64 + lane];
+      for (int e = 0; e < 16; ++e) d1[e] = 0.f;
+      const bool row_ok = it * 32 + l32 < n1;
+      for (int ks0 = 0; ks0 < KS2; ks0 += PD) {
+        const bool last_chunk = ks0 + PD >= KS2;
 #pragma unroll
-          for (int it = 0; it < IT; ++it) {
-            const uint32_t minus = ~rsg[u][it] & 0xFFu;          // bit e set: element e changes sign
-            uint4 a = ring[u][it];
+        for (int u = 0; u < PD; ++u) {
+          const int ks = ks0 + u;
+          if (ks < KS2) {
+            const uint32_t minus = ~rsg[u] & 0xFFu;              // bit e set: element e changes sign
+            uint4 a = ring[u];
             a.x ^= ((minus & 1u) << 15) | ((minus & 2u) << 30);
             a.y ^= ((minus & 4u) << 13) | ((minus & 8u) << 28);
             a.z ^= ((minus & 16u) << 11) | ((minus & 32u) << 26);
             a.w ^= ((minus & 64u) << 9) | ((minus & 128u) << 24);
-            if (it * 32 + l32 >= n1) a = make_uint4(0u, 0u, 0u, 0u);
-            d1[it] = mfma32(a, b0, d1[it]);
-            d1[it] = mfma32(a, b1, d1[it]);
-            d1[it] = mfma32(a, b2, d1[it]);
+            if (!row_ok) a = make_uint4(0u, 0u, 0u, 0u);
+            d1 = mfma32(a, P2op[(ks * 3 + 0) * 64 + lane], d1);
+            d1 = mfma32(a, P2op[(ks * 3 + 1) * 64 + lane], d1);
+            d1 = mfma32(a, P2op[(ks * 3 + 2) * 64 + lane], d1);
+          }
+          if (ks + PD < KS2) {
+            load_a(m, it, ks + PD, ring[u], rsg[u]);
+          } else if (last_chunk && u < KS2) {
+            if (it + 1 < IT) load_a(m, it + 1, u, ring[u], rsg[u]);
+            else if (m + stride < M) load_a(m + stride, 0, u, ring[u], rsg[u]);
           }
         }
-        if (ks + PD < KS2) load_a(m, ks + PD, ring[u], rsg[u]);
-        else if (last_chunk && u < KS2 && m + stride < M) load_a(m + stride, u, ring[u], rsg[u]);
       }
-    }
-    // D1 as three bf16 parts, in B-operand form: step s of block it takes elements 8 s .. 8 s + 7
-    uint4 yb[IT][2][3];
-#pragma unroll
-    for (int it = 0; it < IT; ++it)
+      // the block as three bf16 parts, in B-operand form: step s2 takes elements 8 s2 .. 8 s2 + 7
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {
         uint32_t q[3][8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) split3(d1[it][8 * s2 + e], q[0][e], q[1][e], q[2][e]);
+        for (int e = 0; e < 8; ++e) split3(d1[8 * s2 + e], q[0][e], q[1][e], q[2][e]);
+        uint4 y[3];
 #pragma unroll
         for (int p = 0; p < 3; ++p)
-          yb[it][s2][p] = make_uint4(q[p][0] | q[p][1] << 16, q[p][2] | q[p][3] << 16, q[p][4] | q[p][5] << 16,
-                                     q[p][6] | q[p][7] << 16);
-      }
-    for (int jt = 0; jt < IT; ++jt) {
-      f32x16 z;
+          y[p] = make_uint4(q[p][0] | q[p][1] << 16, q[p][2] | q[p][3] << 16, q[p][4] | q[p][5] << 16, q[p][6] | q[p][7] << 16);
 #pragma unroll
-      for (int e = 0; e < 16; ++e) z[e] = 0.f;
-#pragma unroll
-      for (int it = 0; it < IT; ++it)
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
+        for (int jt = 0; jt < IT; ++jt) {
           const uint4* ap = P1op + ((jt * KS1 + 2 * it + s2) * 3) * 64 + lane;
           const uint4 a0 = ap[0], a1 = ap[64], a2 = ap[128];
-          z = mfma32(a2, yb[it][s2][0], z);                  // small terms first
-          z = mfma32(a1, yb[it][s2][1], z);
-          z = mfma32(a0, yb[it][s2][2], z);
-          z = mfma32(a1, yb[it][s2][0], z);
-          z = mfma32(a0, yb[it][s2][1], z);
-          z = mfma32(a0, yb[it][s2][0], z);
+          z[jt] = mfma32(a2, y[0], z[jt]);                       // small terms first
+          z[jt] = mfma32(a1, y[1], z[jt]);
+          z[jt] = mfma32(a0, y[2], z[jt]);
+          z[jt] = mfma32(a1, y[0], z[jt]);
+          z[jt] = mfma32(a0, y[1], z[jt]);
+          z[jt] = mfma32(a0, y[0], z[jt]);
         }
+      }
+    });
+    static_for_it<0, IT>([&](auto jt_c) {
+      constexpr int jt = decltype(jt_c)::value;
+      const f32x16& zt = z[jt];
       if (j2 < n2) {                                           // one branch on the output type per tile, not per element
         const size_t at0 = (size_t)m * n + (size_t)(jt * 32 + 4 * h) * n2 + j2;
         const int rows_left = n1 - (jt * 32 + 4 * h);            // rows 8 (e / 4) + e % 4 below this count exist
@@ -438,12 +452,12 @@ __global__ __launch_bounds__(kThreads) void transform_mfma_kernel(const uint16_t
           typedef typename std::remove_pointer<decltype(out)>::type T;
           if ((jt + 1) * 32 <= n1) {                              // a whole block of rows (uniform): no per-element test
 #pragma unroll
-            for (int e = 0; e < 16; ++e) out[at0 + (size_t)((8 * (e >> 2) + (e & 3)) * n2)] = (T)z[e];
+            for (int e = 0; e < 16; ++e) out[at0 + (size_t)((8 * (e >> 2) + (e & 3)) * n2)] = (T)zt[e];
           } else {
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
               const int r = 8 * (e >> 2) + (e & 3);
-              if (r < rows_left) out[at0 + (size_t)(r * n2)] = (T)z[e];
+              if (r < rows_left) out[at0 + (size_t)(r * n2)] = (T)zt[e];
             }
           }
         };
@@ -451,7 +465,7 @@ __global__ __launch_bounds__(kThreads) void transform_mfma_kernel(const uint16_t
         else if (y_dtype == BTC_F32) store_tile((float*)Y);
         else store_tile((_Float16*)Y);
       }
-    }
+    });
   }
 }
 
@@ -468,10 +482,11 @@ static btc_status launch_mfma(hipStream_t q, const uint16_t* X, int M, int n1, i
     attr_set = true;
   }
   const int gx = (n2 + 31) / 32;
-  int gy = 512 / gx;                         // about two workgroups per compute unit; a wave walks the rows dealt to it
-  if (gy > (M + 3) / 4) gy = (M + 3) / 4;
+  constexpr int NWV = mfma_waves<IT>();
+  int gy = (IT <= 2 ? 768 : 256) / gx;       // as many workgroups as stay resident; a wave walks the rows dealt to it
+  if (gy > (M + NWV - 1) / NWV) gy = (M + NWV - 1) / NWV;
   if (gy < 1) gy = 1;
-  transform_mfma_kernel<IT><<<dim3(gx, gy), kThreads, lds, q>>>(X, M, n1, n2, sign_bits, P1, P2, Y, y_dtype, p2_bytes);
+  transform_mfma_kernel<IT><<<dim3(gx, gy), 64 * NWV, lds, q>>>(X, M, n1, n2, sign_bits, P1, P2, Y, y_dtype, p2_bytes);
   return launch_status();
 }
 
