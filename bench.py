@@ -399,7 +399,7 @@ def main():
                 nbytes = 2.0 * M * n * 2 + 4.0 * (n1 * n1 + n2 * n2) + n / 8
                 row[f"M{M}"] = dict(us=round(us, 2), tflops=round(flop / us / 1e6, 2),
                                     GBps=round(nbytes / us / 1e3, 1), frac_hbm=round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4),
-                                    engine="fp32 vector ALU" if M <= 16 else "bf16 matrix cores, 3-part operands")
+                                    engine="fp32 vector ALU" if M <= 16 else "bf16 matrix cores, 2-part operands (16-bit output)")
             transform[f"n={n} ({n1}x{n2})"] = row
         # one decoder layer at decode with its four transforms in place (the inputs of q/k/v, of o, of gate/up
         # and of down), cold weights, one graph over all layer copies: what the transform adds to the headline step
