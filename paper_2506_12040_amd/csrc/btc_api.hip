@@ -33,7 +33,8 @@ btc_status btc_shape_init(btc_shape* s, int32_t out, int32_t in, int32_t v, int3
   const int64_t nchunks = ((int64_t)in + v - 1) / v;
   const int b = btc::ceil_log2(K);
   const int64_t wpr = (nchunks * b + 31) / 32;
-  // element counts are kept below 2^31 so that int indexing inside kernels is safe per row
+  // the packed stream stays below 2^40 words; engines that address it with 32-bit byte offsets check
+  // for themselves that it is below 2 GiB and leave larger ones to the generic kernels (64-bit indexing)
   if ((int64_t)out * wpr >= ((int64_t)1 << 40)) return BTC_ERR_UNSUPPORTED;
   s->out = out;
   s->in = in;

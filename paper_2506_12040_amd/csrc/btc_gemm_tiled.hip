@@ -619,6 +619,8 @@ bool gemm_tiled_covers(const Dims& d, int M) {
   if (d.v != tiled::kV || d.b > 10) return false;
   if (d.in % 16 != 0) return false;                           // 16-byte aligned, whole 16-element A loads
   if ((long long)M * d.in * 2 >= (1LL << 31)) return false;   // 32-bit buffer offsets
+  // the index stream is addressed with 32-bit byte offsets too, 0x80000000 being the out-of-range one
+  if ((long long)d.out * d.wpr * 4 >= (1LL << 31)) return false;
   return M >= 1;
 }
 

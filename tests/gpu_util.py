@@ -74,10 +74,23 @@ def gemm(dl: DeviceLayer, x_bits: np.ndarray, x_dtype: int, y_dtype: int = B.BTC
     M = x_bits.shape[0]
     X = dev(x_bits)
     Y = GuardedOutput(M, dl.layer.out, _TORCH_OF[y_dtype])
-    ws = torch.zeros(B.btc_workspace_bytes(dl.shape, M, True), dtype=torch.uint8, device="cuda")
+    # btc_gemm promises to need no particular workspace contents: hand it NaN bit patterns
+    ws = torch.full((B.btc_workspace_bytes(dl.shape, M, True),), 0xFF, dtype=torch.uint8, device="cuda")
     B.btc_gemm(dl.shape, dl.packed, dl.codebook, dl.alpha, dl.mu, X, x_dtype, M, Y.payload, y_dtype, ws)
     Y.check_guards()
     return Y.numpy()
+
+
+def oracle_all_rows(oracle, dl: DeviceLayer, x_bits: np.ndarray, x_kind: str = "f16", block: int = 4096) -> np.ndarray:
+    """The oracle's result for EVERY weight row, [rows of x][out], materialising W_hat a block of rows at a time
+    so that a 28672 x 8192 matrix never needs more than a gigabyte."""
+    layer = dl.layer
+    parts = []
+    for r0 in range(0, layer.out, block):
+        rows = np.arange(r0, min(layer.out, r0 + block))
+        parts.append(oracle.linear(dl.packed_host, dl.codebook_host, layer.alpha, layer.mu, x_bits, layer.n_in,
+                                   layer.v, layer.K, x_kind=x_kind, rows=rows))
+    return np.concatenate(parts, axis=1)
 
 
 def assert_close(y: np.ndarray, y_ref: np.ndarray, what: str = ""):

@@ -109,19 +109,14 @@ def test_gemv_small_full_compare(G, oracle, out, n_in, v, K, batch, dist, y_f32)
     assert np.array_equal(y, y2), "two runs differ"
 
 
-def _full_size_gemv(G, oracle, case, n_sample=384):
+def _full_size_gemv(G, oracle, case):
+    """Every output of the call is compared with the oracle (no sampling)."""
     B = G.B
     say(f"gemv full {case}")
     layer, x = S.make_case(**case)
     dl = G.DeviceLayer(layer, oracle)
     y = G.gemv(dl, x, B.BTC_F16)
-    rng = np.random.default_rng(1)
-    rows = np.unique(np.concatenate([[0, 1, layer.out - 2, layer.out - 1],
-                                     rng.choice(layer.out, size=min(n_sample, layer.out), replace=False)]))
-    y_ref = oracle.linear(dl.packed_host, dl.codebook_host, layer.alpha, layer.mu, x, layer.n_in, layer.v,
-                          layer.K, rows=rows)
-    G.assert_close(y[:, rows], y_ref, f"gemv {case}")
-    assert np.all(np.isfinite(y))
+    G.assert_close(y, G.oracle_all_rows(oracle, dl, x), f"gemv {case}")
 
 
 @pytest.mark.parametrize("case", S.config_cases(0) + S.config_cases(2), ids=lambda c: f"{c['out']}x{c['n_in']}")
@@ -137,19 +132,19 @@ def test_gemv_config_1_full_size(G, oracle, case):
 @pytest.mark.parametrize("case", S.config_cases(4),
                          ids=lambda c: f"{c['out']}x{c['n_in']}v{c['v']}K{c['K']}")
 def test_gemv_config_4_full_size(G, oracle, case):
-    _full_size_gemv(G, oracle, case, n_sample=192)
+    _full_size_gemv(G, oracle, case)
 
 
 def test_gemv_large_ragged_streaming(G, oracle):
     """A matrix large enough for the streaming kernel of the table engine (9-bit indices), with a
     ragged last row tile and a ragged last column block."""
-    _full_size_gemv(G, oracle, dict(seed=3, out=28700, n_in=8190, v=10, K=512, batch=1), n_sample=192)
+    _full_size_gemv(G, oracle, dict(seed=3, out=28700, n_in=8190, v=10, K=512, batch=1))
 
 
 def test_gemv_wide_single_row_on_matrix_cores(G, oracle):
     """A single activation row on a large, very wide matrix takes the matrix-core engine; here with
     ragged row tiles, a ragged last chunk and rows of the stream that are not 16-byte aligned."""
-    _full_size_gemv(G, oracle, dict(seed=4, out=9001, n_in=28666, v=10, K=512, batch=1), n_sample=160)
+    _full_size_gemv(G, oracle, dict(seed=4, out=9001, n_in=28666, v=10, K=512, batch=1))
 
 
 def test_gemv_calls_share_one_workspace(G, oracle):
@@ -176,9 +171,7 @@ def test_gemv_calls_share_one_workspace(G, oracle):
         B.btc_gemv(dl.shape, dl.packed, dl.codebook, dl.alpha, dl.mu, G.dev(x), batch, y.payload, B.BTC_F16, ws)
         y.check_guards()
         assert int(ws.count_nonzero()) == 0, "btc_gemv did not hand the workspace back zero-filled"
-        rows = np.unique(np.concatenate([[0, out - 1], rng.choice(out, size=min(256, out), replace=False)]))
-        y_ref = oracle.linear(dl.packed_host, dl.codebook_host, layer.alpha, layer.mu, x, n_in, v, K, rows=rows)
-        G.assert_close(y.numpy()[:, rows], y_ref, f"shared workspace {out}x{n_in} batch {batch}")
+        G.assert_close(y.numpy(), G.oracle_all_rows(oracle, dl, x), f"shared workspace {out}x{n_in} batch {batch}")
 
 
 def test_gemv_invariants_on_gpu(G, oracle):
@@ -235,11 +228,10 @@ def test_gemm_small_full_compare(G, oracle, out, n_in, v, K, M, xd):
     y_ref = oracle.linear(dl.packed_host, dl.codebook_host, layer.alpha, layer.mu, x, n_in, v, K, x_kind=xd)
     for yd in (B.BTC_F32, B.BTC_BF16 if xd == "bf16" else B.BTC_F16):
         y = G.gemm(dl, x, xk, yd)
-        if yd == B.BTC_BF16:       # bf16 output rounding alone is 2^-9 relative per element
-            rel = np.linalg.norm(y - y_ref) / np.linalg.norm(y_ref)
-            assert rel <= 4e-3
-        else:
-            G.assert_close(y, y_ref, "gemm")
+        # bf16 output included: rounding to 8 significant bits is at most 2^-8 relative per element
+        # (3.9e-3 < 1e-2 on the largest one) and 2^-8 / sqrt(7) = 1.5e-3 in the L2 ratio for significands
+        # spread evenly over [1, 2) -- inside the bar that every other output type is held to
+        G.assert_close(y, y_ref, "gemm")
     y2 = G.gemm(dl, x, xk, B.BTC_F32)
     y3 = G.gemm(dl, x, xk, B.BTC_F32)
     assert np.array_equal(y2, y3), "two runs differ"
@@ -253,8 +245,16 @@ def test_gemm_config_3_full_size(G, oracle, case):
     dl = G.DeviceLayer(layer, oracle)
     y = G.gemm(dl, x, B.BTC_BF16, B.BTC_F32)
     assert np.all(np.isfinite(y))
+    M = x.shape[0]
+    # (1) every weight row, for a band of activation rows that touches every block of 256 activation rows
+    # (first, last and two inner rows of each block)
+    band = np.unique(np.concatenate([[b0, b0 + 37, b0 + 130, min(b0 + 255, M - 1)] for b0 in range(0, M, 256)]))
+    band = band[band < M]
+    y_band = G.oracle_all_rows(oracle, dl, x[band], "bf16")
+    G.assert_close(y[band], y_band, f"gemm {case}, all weight rows of {len(band)} activation rows")
+    # (2) every activation row, for sampled weight rows
     rng = np.random.default_rng(3)
     rows = np.unique(np.concatenate([[0, layer.out - 1], rng.choice(layer.out, size=96, replace=False)]))
     y_ref = oracle.linear(dl.packed_host, dl.codebook_host, layer.alpha, layer.mu, x, layer.n_in, layer.v,
                           layer.K, x_kind="bf16", rows=rows)
-    G.assert_close(y[:, rows], y_ref, f"gemm {case}")
+    G.assert_close(y[:, rows], y_ref, f"gemm {case}, sampled weight rows")

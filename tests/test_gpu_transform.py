@@ -61,16 +61,16 @@ def test_transform_matches_oracle(G, oracle, n1, n2, M, kind, yd):
 
 @pytest.mark.parametrize("kind,yd", [("bf16", "bf16"), ("f16", "f32")])
 def test_transform_prefill_size_sampled_rows(G, oracle, kind, yd):
-    """2048 rows of 5120 channels (the prefill size of the benchmark): the oracle recomputes sampled rows, which
-    are independent of one another; every other row is compared with a dense fp64 product on the host that
-    uses the factored form (valid because the factored form is pinned to the definition on the CPU)."""
+    """2048 rows of 5120 channels (the prefill size of the benchmark).  The oracle forms the n x n matrix T per
+    call, so it recomputes rows spread over the blocks of rows the kernel deals to its waves (rows are independent
+    of one another); the remaining rows are only checked to be finite."""
     B = G.B
     n1, n2, M = 64, 80, 2048
     y_dtype = {"f32": B.BTC_F32, "bf16": B.BTC_BF16}[yd]
     bits, P1, P2 = S.draw_transform(77, n1, n2)
     xb = S.draw_x(np.random.default_rng(4), M, n1 * n2, kind)
     y = _run(G, xb, kind, bits, P1, P2, y_dtype)
-    rows = np.array([0, 1, 511, 1024, 2047])
+    rows = np.unique(np.concatenate([[0, 1, 2046, 2047], np.arange(5, 2048, 97)]))
     _check(y[rows], oracle.transform(xb[rows], bits, P1, P2, kind), y_dtype, B, "sampled rows")
     assert np.isfinite(y).all()
 
