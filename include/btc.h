@@ -122,6 +122,26 @@ btc_status btc_gemv(void* stream, const btc_shape* s, const uint32_t* packed,
                     const void* x, int32_t batch, void* y, btc_dtype y_dtype,
                     void* workspace, size_t workspace_bytes);
 
+/* Test and measurement hook: btc_gemv through ONE chosen engine, so that each engine can be checked against the
+ * oracle and timed against the others on any shape (the engines are different ways of carrying out the same
+ * blockwise sum of appendix "Binary Codebook LUT-GEMM").  Same arguments, results and errors as btc_gemv;
+ * BTC_ENGINE_AUTO is btc_gemv itself; an engine that does not cover the shape or batch size returns
+ * BTC_ERR_UNSUPPORTED and enqueues nothing. */
+enum {
+  BTC_ENGINE_AUTO = 0,
+  BTC_ENGINE_EXPAND = 1,    /* codebook expanded to +-1 pairs, activations in registers            */
+  BTC_ENGINE_LUT = 2,       /* per-column tables of partial dot products (the paper's scheme)      */
+  BTC_ENGINE_MFMA_ONE = 3,  /* fp16 matrix cores, one activation row, one kernel                   */
+  BTC_ENGINE_MFMA = 4,      /* fp16 matrix cores, up to 16 activation rows, two kernels            */
+  BTC_ENGINE_TILED = 5,     /* the prefill kernel on a few rows                                    */
+  BTC_ENGINE_GENERIC = 6,   /* any chunk length and index width                                    */
+  BTC_ENGINE_FP4 = 7        /* 4-bit matrix cores: weights as E2M1, activations as E5M2 pieces     */
+};
+btc_status btc_gemv_engine(void* stream, const btc_shape* s, const uint32_t* packed,
+                           const uint32_t* codebook, const float* alpha, const float* mu,
+                           const void* x, int32_t batch, void* y, btc_dtype y_dtype,
+                           void* workspace, size_t workspace_bytes, int32_t engine);
+
 /* Prefill product for many activation rows; same definition as btc_gemv with
  *   X : [M][in] of x_dtype (BTC_BF16 or BTC_F16), M >= 1
  *   Y : [M][out] of y_dtype (BTC_F32, BTC_BF16 or BTC_F16)

@@ -16,6 +16,8 @@ BTC_OK = 0
 BTC_ERR_NULL, BTC_ERR_SHAPE, BTC_ERR_UNSUPPORTED, BTC_ERR_ALIGN = -1, -2, -3, -4
 BTC_ERR_INDEX_RANGE, BTC_ERR_HIP, BTC_ERR_WORKSPACE = -5, -6, -7
 BTC_F16, BTC_BF16, BTC_F32 = 0, 1, 2
+(BTC_ENGINE_AUTO, BTC_ENGINE_EXPAND, BTC_ENGINE_LUT, BTC_ENGINE_MFMA_ONE, BTC_ENGINE_MFMA, BTC_ENGINE_TILED,
+ BTC_ENGINE_GENERIC, BTC_ENGINE_FP4) = range(8)
 
 
 class btc_shape(ctypes.Structure):
@@ -53,6 +55,8 @@ def lib() -> ctypes.CDLL:
         L.btc_unpack.argtypes = [vp, sp, vp, vp]
         L.btc_gemv.restype = ctypes.c_int
         L.btc_gemv.argtypes = [vp, sp, vp, vp, vp, vp, vp, i32, vp, ctypes.c_int, vp, sz]
+        L.btc_gemv_engine.restype = ctypes.c_int
+        L.btc_gemv_engine.argtypes = [vp, sp, vp, vp, vp, vp, vp, i32, vp, ctypes.c_int, vp, sz, i32]
         L.btc_gemm.restype = ctypes.c_int
         L.btc_gemm.argtypes = [vp, sp, vp, vp, vp, vp, vp, ctypes.c_int, i32, vp, ctypes.c_int, vp, sz]
         L.btc_transform.restype = ctypes.c_int
@@ -129,6 +133,13 @@ def btc_gemv(s: btc_shape, packed, codebook, alpha, mu, x, batch: int, y, y_dtyp
     wb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
     _check(lib().btc_gemv(_stream(stream), ctypes.byref(s), _ptr(packed), _ptr(codebook), _ptr(alpha), _ptr(mu),
                           _ptr(x), batch, _ptr(y), y_dtype, _ptr(workspace), wb), "btc_gemv")
+
+
+def btc_gemv_engine(s: btc_shape, packed, codebook, alpha, mu, x, batch: int, y, y_dtype: int, engine: int,
+                    workspace=None, stream=None, workspace_bytes: Optional[int] = None) -> None:
+    wb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
+    _check(lib().btc_gemv_engine(_stream(stream), ctypes.byref(s), _ptr(packed), _ptr(codebook), _ptr(alpha), _ptr(mu),
+                                 _ptr(x), batch, _ptr(y), y_dtype, _ptr(workspace), wb, engine), "btc_gemv_engine")
 
 
 def btc_gemm(s: btc_shape, packed, codebook, alpha, mu, X, x_dtype: int, M: int, Y, y_dtype: int,
