@@ -29,6 +29,13 @@ static btc_status gemv_dispatch(int engine, void* stream, const btc_shape* s, co
   const long long bytes = (long long)d.out * d.wpr * 4;
 
   if (engine == BTC_ENGINE_AUTO) {
+    // One activation row on the tuned settings (v = 9, 10; 7..10 index bits; rows of at most 15360 weights): the
+    // engine on the 4-bit matrix cores.  Measured against the engines below on every LLaMA-2 7B / 13B / 70B
+    // projection shape it covers, at 0.7 .. 1.11 bit: ahead on all of them (5.6 against 6.0 us on 5120 x 5120,
+    // 7.0 against 11.5 on 8192 x 8192, 14.1 against 21.6 on 28672 x 8192), level on matrices below 2 MB.
+    if (batch == 1 && gemv_fp4_covers(d))
+      engine = BTC_ENGINE_FP4;
+    else
     // One row, 9 or 10 index bits, a wide matrix with few enough rows: the single-kernel variant of the
     // matrix-core engine (measured on 4096 x 11008 at 9 bits: 8.6 us against 11.4 for the table engine; at 7 or
     // 8 bits, or with many rows, the other engines stay ahead).

@@ -13,23 +13,28 @@
 // accumulation.  The paper's kernel trades multiplications for table lookups of partial dot products
 // because its hardware has no such instruction; here the lookup that remains is the codebook itself:
 //
-//  * The codebook is expanded once per workgroup into LDS entries of v nibbles (one 8-byte entry per
-//    codeword, replicated so that the 16 lanes the LDS serves together read 16 different banks whatever
-//    their indices).  A chunk costs one 8-byte LDS read; three chunks (v = 9, 10) are merged by four
-//    shift-or operations into the 128-bit A operand of a lane.  No per-column table is ever built.
-//  * The contraction index of an MFMA may be permuted freely as long as both operands agree.  Lane
-//    (row r, k block q) of wave w owns a contiguous run of G*T chunks of row r ("strand" 4w + q), G =
-//    floor(32 / v) chunks per operand and T instructions per row block, so its index bits are one
-//    contiguous piece of the row's stream: a few 16-byte loads, one funnel shift to normalise, and every
-//    field sits at a compile-time position.  The B operands follow the same permutation; they depend on x
-//    only, are built once per workgroup (through an LDS staging area, in operand layout) and then live
-//    in registers for all row blocks the workgroup walks.  One activation row fills 4 of the 16 B
-//    columns, so one set of B registers serves FOUR steps: columns 4c..4c+3 hold the pieces of step
-//    4 tt + c, step 4 tt + c accumulates into accumulator c, and only columns 4c..4c+3 of accumulator c
-//    are kept at the end (the other columns are products with another step's activations).
-//  * A workgroup owns whole rows: its W waves split the columns, their sixteen-row partial sums meet in
-//    LDS (one barrier per row block, double-buffered) and one wave applies alpha, mu * sum(x) and stores.
-//    No workspace, no traffic between workgroups, one launch, deterministic.
+//  * The codebook is expanded once per workgroup into LDS entries of nibbles (one 8-byte entry per
+//    codeword: elements 0..7 in the low word, the remaining v - 8 in the high word; every entry is
+//    replicated so that the 16 lanes the LDS serves together read 16 different bank pairs whatever their
+//    indices).  A chunk costs one 8-byte LDS read.  The contraction index of an MFMA may be permuted freely
+//    as long as both operands agree, so a lane's 128-bit A operand is laid out for cheapness: words 0..2
+//    ARE the low words of its three chunks, word 3 collects the three short tails (two shift-or operations).
+//    No per-column table is ever built.
+//  * Lane (row r, k block q) of column wave cw owns a contiguous run of G*T chunks of row r ("strand"
+//    4 cw + q), G = floor(32 / v) chunks per operand and T instructions per row block, so its index bits
+//    are one contiguous piece of the row's stream and every field sits at a compile-time position after one
+//    funnel shift.  The pieces of the 16 rows are fetched by neighbouring lanes from neighbouring
+//    addresses (16 bytes each) and handed to their owners through a wave-private LDS area.
+//  * The B operands follow the same permutation; they depend on x only, are built once per workgroup (in
+//    LDS, in operand layout) and then live in registers.  One activation row fills 4 of the 16 B columns,
+//    so one set of eight B registers serves FOUR steps: columns 4c..4c+3 hold the pieces of step 4 tt + c,
+//    that step accumulates into accumulator c, and only columns 4c..4c+3 of accumulator c are kept at the
+//    end (the other columns are products with another step's activations).  That keeps the kernel below
+//    128 registers: four waves per SIMD, which is what hides the LDS and memory latencies here.
+//  * A workgroup owns whole rows: eight column waves split the columns of a row block, their sixteen-row
+//    partial sums meet in LDS and one wave applies alpha, mu * sum(x) and stores.  Two such teams of eight
+//    waves work on two row blocks at a time and share the table, the B operands and one barrier per step
+//    of the row loop.  No workspace, no traffic between workgroups, one launch, deterministic.
 //  * Index words are requested three row blocks ahead; a row block is 16 whole rows of the stream, so
 //    the matrix is read front to back in large contiguous pieces.
 #include <hip/hip_fp16.h>
@@ -49,13 +54,15 @@ typedef __attribute__((address_space(3))) unsigned long long lds_u64;
 
 constexpr uint32_t kOob = 0x80000000u;   // buffer offset that is always out of range (buffers are < 2 GiB)
 constexpr int kRsrcFlags = 0x00020000;   // raw buffer, 32-bit data format
-constexpr int kPD = 4;                   // row blocks in flight per wave (the row loop is unrolled by this)
-constexpr int kSetBytes = 512;           // staged B operand of one step: 4 pieces x 4 k blocks x 32 bytes
+constexpr int kCW = 8;                   // column waves per team
+constexpr int kPD = 2;                   // row blocks in flight per wave in registers (a third one sits in LDS)
+constexpr int kSetBytes = 2048;          // B operands of four steps: 16 columns x 4 k blocks x 32 bytes
 
-template <int V, int B, int T, int W>
+template <int V, int B, int T, int TEAMS>
 struct Cfg {
-  static constexpr int G = 32 / V;                          // chunks per 128-bit operand of a lane
-  static constexpr int EW = 4 * V;                          // bits of a table entry
+  static constexpr int W = kCW * TEAMS;                     // waves per workgroup
+  static constexpr int G = 3;                               // chunks per 128-bit operand of a lane
+  static constexpr int TAIL = V - 8;                        // elements of a chunk in the high word of its entry
   static constexpr int L = G * T;                           // chunks per strand
   static constexpr int ND = (L * B + 31) / 32 + 1;          // index words a lane needs per row block
   // index words of a wave's four strands inside one row, fetched as 16-byte pieces by LPR lanes per row
@@ -63,16 +70,18 @@ struct Cfg {
   static constexpr int LPR = (NW + 3) / 4;
   static constexpr int RPI = 64 / LPR;                      // rows per load instruction
   static constexpr int NLD = (16 + RPI - 1) / RPI;          // load instructions per row block
-  static constexpr int S = 4 * LPR + 4;                     // staged row stride in words
-  static constexpr int C = (B == 8) ? 32 : (B <= 9) ? 16 : (B == 10 ? 8 : (B == 11 ? 4 : (B == 12 ? 2 : 1)));  // table copies
-  static constexpr int LOG2C = C == 32 ? 5 : C == 16 ? 4 : (C == 8 ? 3 : (C == 4 ? 2 : (C == 2 ? 1 : 0)));
+  static constexpr int S = 4 * ((LPR + 1) | 1);             // staged row stride in words: an odd number of 16-byte
+                                                            // pieces, so that the 16 rows start in 16 different banks
+  static constexpr int C = (B <= 8) ? 32 : (B == 9) ? 16 : 8;   // table copies (32: no two lanes of a wave share a bank pair)
+  static constexpr int LOG2C = C == 32 ? 5 : (C == 16 ? 4 : 3);
   static constexpr int kTableBytes = (1 << B) * C * 8;
-  static constexpr int kRedBytes = (4 * W * 16 * 4 + W * 4 + 15) & ~15;
-  static constexpr int kIdxBytes = W * 2 * 16 * S * 4;      // two staged row blocks per wave
-  static constexpr int kStageBytes = W * T * kSetBytes;
+  static constexpr int kRedBytes = (2 * W * 16 * 4 + W * 4 + 15) & ~15;
+  static constexpr int kIdxBytes = W * 16 * S * 4;          // one staged row block per wave
+  static constexpr int NSET = (T + 3) / 4;                  // B register sets
+  static constexpr int kStageBytes = kCW * NSET * kSetBytes;
   static constexpr int kLdsBytes = kTableBytes + kRedBytes + kIdxBytes + kStageBytes;
-  static constexpr int kWavesPerEu = (T <= 5 && kLdsBytes <= 80 * 1024 - 64) ? 2 * W / 4 : W / 4;
-  static_assert(V >= 5 && V <= 16, "one 8-byte entry per codeword");
+  static_assert(V == 9 || V == 10, "three chunks per operand, tails of one or two elements");
+  static_assert(B >= 7 && B <= 10, "table of at most 64 KB");
   static_assert(LPR <= 32, "at least two rows per load instruction");
 };
 
@@ -81,6 +90,12 @@ __device__ __forceinline__ float dpp_xor1(float v) {
 }
 __device__ __forceinline__ float dpp_xor2(float v) {
   return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float dpp_ror4(float v) {   // rotate right by 4 inside a row of 16 lanes
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x124, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float dpp_ror8(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x128, 0xF, 0xF, true));
 }
 // Sum over the 64 lanes, valid in lane 63.
 __device__ __forceinline__ float wave_sum_to_lane63(float v) {
@@ -101,13 +116,16 @@ __device__ __forceinline__ void wave_lds_order() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// Codeword (bit t = element t, 1 => +1) -> V nibbles, 0x2 = +1.0 and 0xA = -1.0 in E2M1.
+// Codeword (bit t = element t, 1 => +1) -> nibbles 0x2 = +1.0, 0xA = -1.0 (E2M1): elements 0..7 in the low
+// word, elements 8..V-1 in the low bits of the high word.
 template <int V>
 __device__ __forceinline__ unsigned long long expand_codeword(uint32_t c) {
-  unsigned long long e = 0;
+  uint32_t lo = 0, hi = 0;
 #pragma unroll
-  for (int t = 0; t < V; ++t) e |= (unsigned long long)(((c >> t) & 1u) ? 0x2u : 0xAu) << (4 * t);
-  return e;
+  for (int t = 0; t < 8; ++t) lo |= (((c >> t) & 1u) ? 0x2u : 0xAu) << (4 * t);
+#pragma unroll
+  for (int t = 8; t < V; ++t) hi |= (((c >> t) & 1u) ? 0x2u : 0xAu) << (4 * (t - 8));
+  return ((unsigned long long)hi << 32) | lo;
 }
 
 #ifdef BTC_FP4_STAMPS
@@ -121,68 +139,103 @@ __device__ unsigned long long g_stamps[4 * 64];
 #define STAMP(i)
 #endif
 
-template <int V, int B, int T, int W>
-__global__ __launch_bounds__(W * 64, (Cfg<V, B, T, W>::kWavesPerEu)) void gemv_fp4_kernel(
+// Slot e (0..31) of a lane's operand at step t holds element (chunk c, position u) of its three chunks:
+// e < 24: c = e / 8, u = e % 8;  24 <= e < 24 + 3 TAIL: c = (e - 24) / TAIL, u = 8 + (e - 24) % TAIL;  else padding.
+// The same order is used for the activations on the B side.
+
+template <int V, int B, int T, int TEAMS>
+__global__ __launch_bounds__(kCW * TEAMS * 64) void gemv_fp4_kernel(
     Dims d, const uint32_t* __restrict__ packed, const uint32_t* __restrict__ codebook,
     const float* __restrict__ alpha, const float* __restrict__ mu, const __half* __restrict__ x,
     void* __restrict__ y, int y_is_f32, int n_rb, int x_dword) {
-  using K = Cfg<V, B, T, W>;
-  constexpr int G = K::G, EW = K::EW, ND = K::ND, C = K::C, L = K::L;
+  using K = Cfg<V, B, T, TEAMS>;
+  constexpr int W = K::W, G = K::G, TAIL = K::TAIL, ND = K::ND, C = K::C, L = K::L;
   constexpr int LPR = K::LPR, RPI = K::RPI, NLD = K::NLD, S = K::S;
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned long long* table = (unsigned long long*)smem;                       // [2^B][C], at LDS offset 0
-  float* red = (float*)(smem + K::kTableBytes);                                // [2 phases][2 row blocks][W][16]
-  float* sxp = red + 4 * W * 16;                                               // [W]
-  uint32_t* idx_all = (uint32_t*)(smem + K::kTableBytes + K::kRedBytes);       // [W][2 row blocks][16][S]
-  unsigned char* bstage_all = smem + K::kTableBytes + K::kRedBytes + K::kIdxBytes;  // [W][T][512]
+  float* red = (float*)(smem + K::kTableBytes);                                // [2 phases][W][16]
+  float* sxp = red + 2 * W * 16;                                               // [W]
+  uint32_t* idx_all = (uint32_t*)(smem + K::kTableBytes + K::kRedBytes);       // [W][16][S]
+  unsigned char* bstage_all = smem + K::kTableBytes + K::kRedBytes + K::kIdxBytes;  // [kCW][NSET][2048]
 
   const int tid = threadIdx.x, lane = tid & 63;
   STAMP(0);
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int cw = wave & (kCW - 1), team = wave / kCW;        // column wave, team
   const int r = lane & 15, q = lane >> 4;
-  const int stride = gridDim.x;
+  const int stride = gridDim.x;                              // row blocks between successive ones of a team slot
 
-  // ---- small loads first (their data is needed first): codewords, this wave's activations.
+  // ---- small loads first (their data is needed first): codewords, then this wave's share of the activations.
   // An item is 16 consecutive B bytes of one step: (step t, strand qa, half h) = slots e = 16 h .. 16 h + 15
-  // of strand qa, which are the CONSECUTIVE elements (chunk0(qa) + G t) * V + e of x for e < G * V (the
-  // G chunks of a step follow one another in x) and padding above.  Slot k = 32 qa + e of an instruction
-  // sits in B lane k block q' = 2 (qa & 1) + (e >> 4) at byte 16 (qa >> 1) + (e & 15).
+  // of strand qa.  Slot k = 32 qa + e of an instruction sits in B lane k block q' = 2 (qa & 1) + (e >> 4) at
+  // byte 16 (qa >> 1) + (e & 15).  The two teams share the B operands: team h prepares the items of half h.
   constexpr int KPT = ((1 << B) + W * 64 - 1) / (W * 64);
-  uint32_t cw[KPT];
+  uint32_t cwd[KPT];
 #pragma unroll
-  for (int i = 0; i < KPT; ++i) cw[i] = codebook[min(tid + i * W * 64, (1 << B) - 1)];
-  unsigned char* bstage = bstage_all + wave * (T * kSetBytes);
+  for (int i = 0; i < KPT; ++i) cwd[i] = codebook[min(tid + i * W * 64, (1 << B) - 1)];
+  unsigned char* bstage = bstage_all + cw * (K::NSET * kSetBytes);
   const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)x, 0, d.in * 2, kRsrcFlags);
-  constexpr int n_items = 8 * T;
+  constexpr int n_items = (TEAMS == 2 ? 4 : 8) * T;
   constexpr int NI = (n_items + 63) / 64;
-  uint32_t hx[NI][8];                                      // 16 fp16 values per item
+  uint32_t hx[NI][8];                                      // 16 fp16 values per item, in slot order
 #pragma unroll
   for (int ii = 0; ii < NI; ++ii) {
     const int item = lane + 64 * ii;
-    const int t = item >> 3, qa = (item >> 1) & 3, h = item & 1;
-    const uint32_t x0 = (uint32_t)((wave * 4 + qa) * L + G * t) * V + 16u * h;   // first element of the item
+    const int t = TEAMS == 2 ? item >> 2 : item >> 3;
+    const int qa = TEAMS == 2 ? item & 3 : (item >> 1) & 3;
+    const int h = TEAMS == 2 ? team : item & 1;
+    const uint32_t xb = (uint32_t)((cw * 4 + qa) * L + G * t) * V;   // first element of the step's three chunks
     const bool live = item < n_items;
-    if (x_dword) {        // x0 is even: two 16-byte loads (4-byte aligned), range-checked word by word
+    // half 0: chunk 0 elements 0..7, chunk 1 elements 0..7; half 1: chunk 2 elements 0..7, then the tails
+    const uint32_t run0 = h == 0 ? xb : xb + 2u * V;
+    if (x_dword) {        // V and `in` even: every pair of elements is one aligned word
+      const auto a4 = __builtin_amdgcn_raw_buffer_load_b128(rx, live ? run0 * 2u : kOob, 0, 0);
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const auto v4 = __builtin_amdgcn_raw_buffer_load_b128(rx, live ? (x0 + 8u * i) * 2u : kOob, 0, 0);
+      for (int k = 0; k < 4; ++k) hx[ii][k] = a4[k];
+      if (h == 0 || TEAMS == 1) {
+        const auto b4 = __builtin_amdgcn_raw_buffer_load_b128(rx, (live && h == 0) ? (xb + V) * 2u : kOob, 0, 0);
 #pragma unroll
-        for (int k = 0; k < 4; ++k) hx[ii][4 * i + k] = (16 * h + 8 * i + 2 * k < G * V) ? v4[k] : 0u;   // padding slots
+        for (int k = 0; k < 4; ++k) hx[ii][4 + k] = b4[k];
+      }
+      if (h == 1 || TEAMS == 1) {
+        if constexpr (TAIL == 2) {
+          uint32_t tl[3];
+#pragma unroll
+          for (int c = 0; c < 3; ++c)
+            tl[c] = __builtin_amdgcn_raw_buffer_load_b32(rx, (live && h == 1) ? (xb + c * V + 8u) * 2u : kOob, 0, 0);
+          if (h == 1) {
+            hx[ii][4] = tl[0];
+            hx[ii][5] = tl[1];
+            hx[ii][6] = tl[2];
+            hx[ii][7] = 0u;
+          }
+        }
       }
     } else {
+      uint32_t hv[16];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const uint32_t lo = __builtin_amdgcn_raw_buffer_load_b16(rx, (live && 16 * h + 2 * i < G * V) ? (x0 + 2u * i) * 2u : kOob, 0, 0);
-        const uint32_t hi = __builtin_amdgcn_raw_buffer_load_b16(rx, (live && 16 * h + 2 * i + 1 < G * V) ? (x0 + 2u * i + 1) * 2u : kOob, 0, 0);
-        hx[ii][i] = (lo & 0xFFFFu) | (hi << 16);
+      for (int e = 0; e < 16; ++e) {
+        // element of x in slot 16 h + e
+        uint32_t xe;
+        bool pad = false;
+        if (e < 8) xe = run0 + e;
+        else if (h == 0) xe = xb + V + (e - 8);
+        else {
+          const int k = e - 8;                 // tail slot
+          pad = k >= 3 * TAIL;
+          xe = xb + (uint32_t)(k / TAIL) * V + 8u + (uint32_t)(k % TAIL);
+        }
+        hv[e] = __builtin_amdgcn_raw_buffer_load_b16(rx, (live && !pad) ? xe * 2u : kOob, 0, 0) & 0xFFFFu;
       }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) hx[ii][k] = hv[2 * k] | (hv[2 * k + 1] << 16);
     }
   }
 
   // ---- index words.  The wave's four strands are one contiguous piece of every row: LPR lanes fetch it as
   // 16-byte pieces (neighbouring lanes read neighbouring addresses), RPI rows per instruction; the pieces go
   // through a wave-private LDS area from which lane (row r, strand q) reads its own run of words.
-  const uint32_t wbit0 = (uint32_t)(wave * 4 * L) * B;       // first bit of the wave's piece inside a row
+  const uint32_t wbit0 = (uint32_t)(cw * 4 * L) * B;         // first bit of the wave's piece inside a row
   const int wd0 = (int)(wbit0 >> 5);
   const int lrow = lane / LPR, lpc = lane - lrow * LPR;
   const uint32_t row_bytes = (uint32_t)d.wpr * 4u;
@@ -202,40 +255,51 @@ __global__ __launch_bounds__(W * 64, (Cfg<V, B, T, W>::kWavesPerEu)) void gemv_f
       dst[j] = make_uint4(v4[0], v4[1], v4[2], v4[3]);
     }
   };
-  uint32_t* idx_stage = idx_all + wave * (2 * 16 * S);
-  auto stage_block = [&](int parity, const uint4 (&src)[NLD]) {
+  uint32_t* idx_stage = idx_all + wave * (16 * S);
+  auto stage_block = [&](const uint4 (&src)[NLD]) {
 #pragma unroll
     for (int j = 0; j < NLD; ++j) {
       const int rr = j * RPI + lrow;
-      if (lrow < RPI && rr < 16) *(uint4*)(idx_stage + (parity * 16 + rr) * S + 4 * lpc) = src[j];
+      if (lrow < RPI && rr < 16) *(uint4*)(idx_stage + rr * S + 4 * lpc) = src[j];
     }
   };
-#pragma unroll
-  for (int u = 0; u < kPD; ++u) load_block(blockIdx.x + u * stride, D[u]);
+  // this wave's row blocks: blockIdx.x + (TEAMS * i + team) * stride, i = 0, 1, ...
+  const int rb_first = blockIdx.x + team * stride, rb_step = TEAMS * stride;
+  // Only the first row block is requested now: all waves of all workgroups get their first words within the
+  // first burst, instead of queueing behind the later row blocks of the waves that happened to issue first.
+  uint4 D0[NLD];
+  load_block(rb_first, D0);
   STAMP(1);
 
   // ---- codebook -> table of nibble patterns, every entry C times.  Thread k writes its entry's copies in
   // the order k, k + 1, ... (mod C): at every step the 16 threads of consecutive entries write 16 different
-  // bank pairs, although an entry's copies are 128 bytes apart from the next entry's.
+  // bank pairs, although an entry's copies are 128 bytes or more apart from the next entry's.
 #pragma unroll
   for (int i = 0; i < KPT; ++i) {
     const int k = tid + i * W * 64;
     if (k < (1 << B)) {
-      const unsigned long long ent = expand_codeword<V>(cw[i]);
+      const unsigned long long ent = expand_codeword<V>(cwd[i]);
 #pragma unroll
       for (int c = 0; c < C; ++c) table[k * C + ((c + k) & (C - 1))] = ent;
     }
   }
   STAMP(2);
 
+  if (T & 3) {   // B columns of steps that do not exist must not hold junk (the two teams share the clearing)
+    uint4* z = (uint4*)(bstage + (K::NSET - 1) * kSetBytes + (T & 3) * 512) + team * ((4 - (T & 3)) * 32 / TEAMS);
+    for (int i = lane; i < (4 - (T & 3)) * 32 / TEAMS; i += 64) z[i] = make_uint4(0, 0, 0, 0);
+  }
   // ---- activations -> four E5M2 pieces each (the top byte of an fp16 IS an E5M2 number; subtracting it
   // leaves at most 8 significant bits, exactly), written in B-operand layout: 16 bytes per item and piece
   float sx_lane = 0.f;
 #pragma unroll
   for (int ii = 0; ii < NI; ++ii) {
     const int item = lane + 64 * ii;
-    const int t = item >> 3, qa = (item >> 1) & 3, h = item & 1;
-    unsigned char* dst = bstage + t * kSetBytes + (2 * (qa & 1) + h) * 32 + 16 * (qa >> 1);
+    const int t = TEAMS == 2 ? item >> 2 : item >> 3;
+    const int qa = TEAMS == 2 ? item & 3 : (item >> 1) & 3;
+    const int h = TEAMS == 2 ? team : item & 1;
+    // piece n of step t is column 4 (t % 4) + n of set t / 4
+    unsigned char* dst = bstage + (t >> 2) * kSetBytes + (t & 3) * 512 + (2 * (qa & 1) + h) * 32 + 16 * (qa >> 1);
     uint32_t res[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -248,7 +312,7 @@ __global__ __launch_bounds__(W * 64, (Cfg<V, B, T, W>::kWavesPerEu)) void gemv_f
       for (int n = 0; n < 4; ++n) {
         uint32_t o4[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j)   // bytes 1 and 3 of two dwords: the pieces of four consecutive elements
+        for (int j = 0; j < 4; ++j)   // bytes 1 and 3 of two dwords: the pieces of four consecutive slots
           o4[j] = __builtin_amdgcn_perm(res[2 * j + 1], res[2 * j], 0x07050301u);
         *(uint4*)(dst + n * 128) = make_uint4(o4[0], o4[1], o4[2], o4[3]);
         if (n < 3) {
@@ -262,30 +326,15 @@ __global__ __launch_bounds__(W * 64, (Cfg<V, B, T, W>::kWavesPerEu)) void gemv_f
     }
   }
   STAMP(5);
-  // sum of this wave's activations (every element belongs to exactly one item)
+  // sum of this wave's share of the activations (every element belongs to exactly one item)
   sx_lane = wave_sum_to_lane63(sx_lane);
   if (lane == 63) sxp[wave] = sx_lane;
-  wave_lds_order();
-
-  // ---- B operands of this wave: lane (column n, k block q) of set t holds piece n of step t for n < 4
-  // and zeros in the other columns
-  i32x8 Bq[T];
+  // the next row blocks are requested, the first one's index words go to LDS
 #pragma unroll
-  for (int t = 0; t < T; ++t) {
-    Bq[t] = i32x8{0, 0, 0, 0, 0, 0, 0, 0};
-    if (r < 4) {
-      const uint4* src = (const uint4*)(bstage + t * kSetBytes + r * 128 + q * 32);
-      const uint4 lo = src[0], hi = src[1];
-      Bq[t] = i32x8{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
-    }
-  }
-  // the first pair of row blocks: index words -> LDS, registers refilled with the third pair's
-  stage_block(0, D[0]);
-  stage_block(1, D[1]);
-  load_block(blockIdx.x + 4 * stride, D[0]);
-  load_block(blockIdx.x + 5 * stride, D[1]);
+  for (int u = 0; u < kPD; ++u) load_block(rb_first + (u + 1) * rb_step, D[u]);
+  stage_block(D0);
   STAMP(6);
-  __syncthreads();   // table complete, sums of x stored
+  __syncthreads();   // table complete, B operands staged, sums of x stored
   STAMP(7);
   float sx = 0.f;
 #pragma unroll
@@ -296,98 +345,77 @@ __global__ __launch_bounds__(W * 64, (Cfg<V, B, T, W>::kWavesPerEu)) void gemv_f
   const uint32_t s0 = lbit & 31u;
   const uint32_t* my_words = idx_stage + r * S + (lbit >> 5);
   const uint32_t lane_copy = (uint32_t)(lane & (C - 1)) * 8u;   // this lane's copy of every table entry
-  // ---- the row loop: two row blocks at a time (their instruction streams interleave, so one hides the
-  // other's LDS latency; the B registers serve both), one barrier per pair
-  int it = 0;
-  for (int rb0 = blockIdx.x; rb0 < n_rb; rb0 += 4 * stride) {
+  // B operands: lane (column n = r, k block q) of set tt holds piece n % 4 of step 4 tt + n / 4
+  i32x8 Bq[K::NSET];
 #pragma unroll
-    for (int pp = 0; pp < 2; ++pp) {
-      const int rbA = rb0 + 2 * pp * stride, rbB = rbA + stride;     // rbB may be past the end: zeros, not stored
-      if (rbA >= n_rb) break;
-      // the waves that will finish the two row blocks ask for their scales now
-      const int fwA = it % W, fwB = (it + 1) % W;
-      const int my_rb = wave == fwA ? rbA : rbB;
-      const int my_row = my_rb * 16 + lane;
-      const bool finishes = (wave == fwA || wave == fwB) && lane < 16 && my_rb < n_rb && my_row < d.out;
+  for (int tt = 0; tt < K::NSET; ++tt) {
+    const uint4* src = (const uint4*)(bstage + tt * kSetBytes + r * 128 + q * 32);
+    const uint4 lo = src[0], hi = src[1];
+    Bq[tt] = i32x8{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+  }
+
+  int it = 0;
+  for (int rb0 = rb_first; rb0 < n_rb + (TEAMS - 1) * stride; rb0 += kPD * rb_step) {
+#pragma unroll
+    for (int u = 0; u < kPD; ++u) {
+      const int rb = rb0 + u * rb_step;                      // may be past the end (second team): zeros, not stored
+      if (rb - team * stride >= n_rb) break;                 // the same for both teams: they share the barriers
+      // the wave that will finish this row block asks for its scales now
+      const int fw = (it + team * (W / 2 + 1)) % W;          // rotates; the two teams' finishers differ
+      const int my_row = rb * 16 + lane;
+      const bool finishes = wave == fw && lane < 16 && rb < n_rb && my_row < d.out;
       float al = 0.f, mm = 0.f;
       if (finishes) {
         al = alpha[my_row];
         mm = mu[my_row];
       }
-      // both row blocks' words from LDS; then the next pair's words take their place (LDS operations of a
-      // wave complete in order) and the registers are refilled with the pair after that
+      // this row block's words from LDS; then the next one's take their place (LDS operations of a wave
+      // complete in order) and the registers are refilled with the one after those in flight
       wave_lds_order();
-      uint32_t Wd[2][ND + 1];
+      uint32_t Wd[ND + 1];
 #pragma unroll
-      for (int h = 0; h < 2; ++h)
-#pragma unroll
-        for (int i = 0; i <= ND; ++i) Wd[h][i] = my_words[h * 16 * S + i];
-      if (it < 4) STAMP(40 + 3 * it);
+      for (int i = 0; i <= ND; ++i) Wd[i] = my_words[i];
       wave_lds_order();
-      stage_block(0, D[2 * (pp ^ 1)]);
-      stage_block(1, D[2 * (pp ^ 1) + 1]);
-      if (it < 4) STAMP(41 + 3 * it);
-      load_block(rbA + 6 * stride, D[2 * (pp ^ 1)]);
-      load_block(rbA + 7 * stride, D[2 * (pp ^ 1) + 1]);
-      if (it < 16) STAMP(13 + 3 * it);
-      uint32_t R[2][ND];     // normalised: bit 0 is the first bit of the lane's run
+      stage_block(D[u]);
+      load_block(rb + (kPD + 1) * rb_step, D[u]);
+      uint32_t R[ND];     // normalised: bit 0 is the first bit of the lane's run
 #pragma unroll
-      for (int h = 0; h < 2; ++h)
-#pragma unroll
-        for (int i = 0; i < ND; ++i) R[h][i] = __builtin_amdgcn_alignbit(Wd[h][i + 1], Wd[h][i], s0);
-      if (it < 16) STAMP(8 + 3 * it);
+      for (int i = 0; i < ND; ++i) R[i] = __builtin_amdgcn_alignbit(Wd[i + 1], Wd[i], s0);
+      if (it < 8) STAMP(8 + 5 * it);
 
-      // The step loop, software-pipelined by hand: the table reads of step t + 1 (both row blocks) are issued
-      // before the entries of step t are merged and contracted, so an LDS round trip is covered by a step's
-      // worth of arithmetic.  (Left to itself the compiler waits for every group of three reads.)
-      f32x4 acc[2][2] = {{{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}}, {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}}};
-      unsigned long long E[2][2][G];   // [pipeline stage][row block][chunk]
-      auto issue = [&](int t, unsigned long long (&dst)[2][G]) {
+      // The step loop, software-pipelined by hand: the LDS reads of step t + 1 (three table entries, the
+      // B operand) are issued before the entries of step t are merged and contracted, so an LDS round trip
+      // is covered by a step's worth of arithmetic.  (Left to itself the compiler waits for every read.)
+      f32x4 acc[4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+      unsigned long long E[2][G];   // [pipeline stage][chunk]
+      auto issue = [&](int t, unsigned long long (&dst)[G]) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-          for (int g = 0; g < G; ++g) {
-            const int pos = (t * G + g) * B, w = pos >> 5, sb = pos & 31;
-            uint32_t ofs;
-            if (B == 8 && C == 32) {
-              // byte-aligned indices, one table copy per lane pair of banks: offset = index << 8 | copy,
-              // assembled by one byte permute
-              ofs = __builtin_amdgcn_perm(R[h][w], lane_copy, 0x0C0C0000u | ((4u + (sb >> 3)) << 8));
-            } else {
-              // table offset of the entry = index << SH | copy: the field is extracted already shifted
-              constexpr int SH = 3 + K::LOG2C;
-              constexpr uint32_t mask = ((1u << B) - 1u) << SH;
-              uint32_t sh;
-              if (sb + B <= 32) sh = sb >= SH ? R[h][w] >> (sb - SH) : R[h][w] << (SH - sb);
-              else sh = sb >= SH ? __builtin_amdgcn_alignbit(R[h][w + 1], R[h][w], sb - SH)
-                                 : __builtin_amdgcn_alignbit(R[h][w + 1], R[h][w], sb) << SH;
-              ofs = (sh & mask) | lane_copy;
-            }
-            // the table starts at LDS address 0 (this kernel has no static LDS), so the offset IS the address
-            dst[h][g] = *(const lds_u64*)(uintptr_t)ofs;
+        for (int g = 0; g < G; ++g) {
+          const int pos = (t * G + g) * B, w = pos >> 5, sb = pos & 31;
+          uint32_t ofs;
+          if (B == 8) {
+            // byte-aligned indices, 32 copies: offset = index << 8 | copy, assembled by one byte permute
+            ofs = __builtin_amdgcn_perm(R[w], lane_copy, 0x0C0C0000u | ((4u + (sb >> 3)) << 8));
+          } else {
+            // table offset of the entry = index << SH | copy: the field is extracted already shifted
+            constexpr int SH = 3 + K::LOG2C;
+            constexpr uint32_t mask = ((1u << B) - 1u) << SH;
+            uint32_t sh;
+            if (sb + B <= 32) sh = sb >= SH ? R[w] >> (sb - SH) : R[w] << (SH - sb);
+            else sh = sb >= SH ? __builtin_amdgcn_alignbit(R[w + 1], R[w], sb - SH)
+                               : __builtin_amdgcn_alignbit(R[w + 1], R[w], sb) << SH;
+            ofs = (sh & mask) | lane_copy;
           }
-      };
-      auto consume = [&](int t, const unsigned long long (&src)[2][G]) {
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          uint32_t A[4] = {0u, 0u, 0u, 0u};
-#pragma unroll
-          for (int g = 0; g < G; ++g) {
-            const uint32_t lo = (uint32_t)src[h][g], hi = (uint32_t)(src[h][g] >> 32);
-            const int bit = g * EW, w0 = bit >> 5, ss = bit & 31;
-            if (ss == 0) {
-              A[w0] |= lo;
-              if (EW > 32) A[w0 + 1] |= hi;
-            } else {
-              A[w0] |= lo << ss;
-              if (EW + ss > 32) A[w0 + 1] |= __builtin_amdgcn_alignbit(hi, lo, 32 - ss);
-              if (EW + ss > 64) A[w0 + 2] |= hi >> (32 - ss);
-            }
-          }
-          const i32x8 Av = {(int)A[0], (int)A[1], (int)A[2], (int)A[3], 0, 0, 0, 0};
-          acc[h][t & 1] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(Av, Bq[t], acc[h][t & 1], 4 /* A: E2M1 */,
-                                                                           1 /* B: E5M2 */, 0, 0, 0, 0);
+          // the table starts at LDS address 0 (this kernel has no static LDS), so the offset IS the address
+          dst[g] = *(const lds_u64*)(uintptr_t)ofs;
         }
+      };
+      auto consume = [&](int t, const unsigned long long (&src)[G]) {
+        const uint32_t t0 = (uint32_t)(src[0] >> 32), t1 = (uint32_t)(src[1] >> 32), t2 = (uint32_t)(src[2] >> 32);
+        const uint32_t tails = t0 | (t1 << (4 * TAIL)) | (t2 << (8 * TAIL));
+        const i32x8 Av = {(int)(uint32_t)src[0], (int)(uint32_t)src[1], (int)(uint32_t)src[2], (int)tails, 0, 0, 0, 0};
+        acc[t & 3] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(Av, Bq[t >> 2], acc[t & 3], 4 /* A: E2M1 */,
+                                                                      1 /* B: E5M2 */, 0, 0, 0, 0);
       };
       issue(0, E[0]);
 #pragma unroll
@@ -398,36 +426,42 @@ __global__ __launch_bounds__(W * 64, (Cfg<V, B, T, W>::kWavesPerEu)) void gemv_f
         consume(t, E[t & 1]);
       }
       __builtin_amdgcn_sched_barrier(0);
-      if (it < 16) STAMP(9 + 3 * it);
-      // columns 0..3 hold the four pieces' sums, the other columns are zero: add the quad, lane 0 of a row
-      // group stores its four rows
-      float* rbuf = red + pp * (2 * W * 16);
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        float s4[4];
+      if (it < 8) STAMP(9 + 5 * it);
+      // Column n of accumulator c is valid for n / 4 == c; a row's sum is the sum of its 16 valid entries.
+      // Register i of a lane belongs to row 4 q + i.  The four registers are reduced over the 16 lanes of a
+      // row group together: after two select-and-add steps lane n holds the quad sum of register n % 4,
+      // after two rotations by 4 and 8 the sum over all 16 lanes.
+      float v4[4];
+      {
+        const int cls = r >> 2;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          float v = acc[h][0][i] + acc[h][1][i];
-          v += dpp_xor1(v);
-          v += dpp_xor2(v);
-          s4[i] = v;
+          const float a01 = cls & 1 ? acc[1][i] : acc[0][i];
+          const float a23 = cls & 1 ? acc[3][i] : acc[2][i];
+          v4[i] = cls & 2 ? a23 : a01;
         }
-        if (r == 0) *(float4*)(rbuf + h * (W * 16) + wave * 16 + 4 * q) = make_float4(s4[0], s4[1], s4[2], s4[3]);
       }
-      if (it < 16) STAMP(10 + 3 * it);
+      const bool odd = r & 1, up = r & 2;
+      const float w01 = (odd ? v4[1] : v4[0]) + dpp_xor1(odd ? v4[0] : v4[1]);
+      const float w23 = (odd ? v4[3] : v4[2]) + dpp_xor1(odd ? v4[2] : v4[3]);
+      float z = (up ? w23 : w01) + dpp_xor2(up ? w01 : w23);
+      z += dpp_ror4(z);
+      z += dpp_ror8(z);                                      // lane n: the sum of row 4 q + n % 4
+      float* rbuf = red + (it & 1) * (W * 16) + team * (kCW * 16);
+      if (r < 4) rbuf[cw * 16 + 4 * q + r] = z;
+      if (it < 8) STAMP(10 + 5 * it);
       __syncthreads();
-      if (it < 16) STAMP(11 + 3 * it);
+      if (it < 8) STAMP(11 + 5 * it);
       if (finishes) {
-        const float* fb = rbuf + (wave == fwA ? 0 : W * 16);
         float tot = 0.f;
 #pragma unroll
-        for (int w = 0; w < W; ++w) tot += fb[w * 16 + lane];
+        for (int w = 0; w < kCW; ++w) tot += rbuf[w * 16 + lane];
         const float res = al * tot + mm * sx;
         if (y_is_f32) ((float*)y)[my_row] = res;
         else ((__half*)y)[my_row] = __float2half_rn(res);
       }
-      if (it < 16) STAMP(12 + 3 * it);
-      it += 2;
+      if (it < 8) STAMP(12 + 5 * it);
+      ++it;
     }
   }
   STAMP(63);
@@ -435,37 +469,32 @@ __global__ __launch_bounds__(W * 64, (Cfg<V, B, T, W>::kWavesPerEu)) void gemv_f
 
 constexpr int kLdsMax = 160 * 1024 - 64;
 
-template <int V, int B, int T, int W>
+template <int V, int B, int T, int TEAMS>
 static btc_status launch3(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
-                          const float* alpha, const float* mu, const void* x, void* y, int y_is_f32) {
-  using K = Cfg<V, B, T, W>;
-  if constexpr (K::kLdsBytes > kLdsMax) {
-    return BTC_ERR_UNSUPPORTED;
-  } else {
-    static bool attr_set = false;   // one-time kernel attribute, not call state
-    if (!attr_set) {
-      if (hipFuncSetAttribute((const void*)gemv_fp4_kernel<V, B, T, W>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              K::kLdsBytes) != hipSuccess)
-        return BTC_ERR_HIP;
-      attr_set = true;
-    }
-    const int n_rb = (d.out + 15) / 16;
-    const int per_cu = K::kWavesPerEu * 4 / W;           // workgroups resident per compute unit (registers, LDS)
-    const int slots = 256 * per_cu;
-    const int grid = n_rb < slots ? n_rb : slots;        // workgroup i walks row blocks i, i + grid, ...
-    const int x_dword = (V % 2 == 0) && (d.in % 2 == 0);
-    gemv_fp4_kernel<V, B, T, W><<<grid, W * 64, K::kLdsBytes, q>>>(d, packed, codebook, alpha, mu, (const __half*)x,
-                                                                          y, y_is_f32, n_rb, x_dword);
-    return launch_status();
+                          const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, bool dry) {
+  using K = Cfg<V, B, T, TEAMS>;
+  static_assert(K::kLdsBytes <= kLdsMax, "LDS budget");
+  if (dry) return BTC_OK;         // only asked whether a kernel exists for this setting
+  static bool attr_set = false;   // one-time kernel attribute, not call state
+  if (!attr_set) {
+    if (hipFuncSetAttribute((const void*)gemv_fp4_kernel<V, B, T, TEAMS>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            K::kLdsBytes) != hipSuccess)
+      return BTC_ERR_HIP;
+    attr_set = true;
   }
+  const int n_rb = (d.out + 15) / 16;
+  const int slots = 256 * TEAMS;                         // one workgroup per compute unit, TEAMS row blocks at a time
+  const int grid = n_rb < slots ? (n_rb + TEAMS - 1) / TEAMS : 256;
+  const int x_dword = (V % 2 == 0) && (d.in % 2 == 0);
+  gemv_fp4_kernel<V, B, T, TEAMS><<<grid, K::W * 64, K::kLdsBytes, q>>>(d, packed, codebook, alpha, mu, (const __half*)x,
+                                                                          y, y_is_f32, n_rb, x_dword);
+  return launch_status();
 }
 
-// Steps per row block: the 4 W strands of a workgroup must cover the row.  Instantiated for a few step counts; a
+// Steps per row block: the 32 strands of a team must cover the row.  Instantiated for a few step counts; a
 // strand that is longer than needed reads zeros for the activations past the end of the row.
-constexpr int kW = 8;
 static int steps_for(const Dims& d) {
-  const int G = 32 / d.v;
-  const int need = (d.nchunks + kW * 4 * G - 1) / (kW * 4 * G);
+  const int need = (d.nchunks + kCW * 4 * 3 - 1) / (kCW * 4 * 3);
   static const int have[] = {3, 4, 5, 6, 8, 9, 10, 12, 15, 16};
   for (int t : have) if (need <= t) return t;
   return 0;
@@ -473,9 +502,16 @@ static int steps_for(const Dims& d) {
 
 template <int V, int B>
 static btc_status launch2(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
-                          const float* alpha, const float* mu, const void* x, void* y, int y_is_f32) {
-#define BTC_FP4_CASE(TT) \
-  case TT: return launch3<V, B, TT, kW>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32);
+                          const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, bool dry) {
+  // two teams whenever table, staging areas and B operands of 16 waves fit the LDS
+#define BTC_FP4_CASE(TT)                                                                             \
+  case TT:                                                                                           \
+    if constexpr (Cfg<V, B, TT, 2>::kLdsBytes <= kLdsMax)                                            \
+      return launch3<V, B, TT, 2>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry);           \
+    else if constexpr (Cfg<V, B, TT, 1>::kLdsBytes <= kLdsMax)                                       \
+      return launch3<V, B, TT, 1>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry);           \
+    else                                                                                             \
+      return BTC_ERR_UNSUPPORTED;
   switch (steps_for(d)) {
     BTC_FP4_CASE(3) BTC_FP4_CASE(4) BTC_FP4_CASE(5) BTC_FP4_CASE(6) BTC_FP4_CASE(8) BTC_FP4_CASE(9)
     BTC_FP4_CASE(10) BTC_FP4_CASE(12) BTC_FP4_CASE(15) BTC_FP4_CASE(16)
@@ -486,12 +522,12 @@ static btc_status launch2(hipStream_t q, const Dims& d, const uint32_t* packed, 
 
 template <int V>
 static btc_status launch1(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
-                          const float* alpha, const float* mu, const void* x, void* y, int y_is_f32) {
+                          const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, bool dry) {
   switch (d.b) {
-    case 7: return launch2<V, 7>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32);
-    case 8: return launch2<V, 8>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32);
-    case 9: return launch2<V, 9>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32);
-    case 10: return launch2<V, 10>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32);
+    case 7: return launch2<V, 7>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry);
+    case 8: return launch2<V, 8>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry);
+    case 9: return launch2<V, 9>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry);
+    case 10: return launch2<V, 10>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry);
   }
   return BTC_ERR_UNSUPPORTED;
 }
@@ -504,19 +540,23 @@ extern "C" int btc_debug_fp4_stamps(unsigned long long* host, int n) {
 }
 #endif
 
+static btc_status fp4_dispatch(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
+                               const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, bool dry) {
+  if (d.v != 9 && d.v != 10) return BTC_ERR_UNSUPPORTED;
+  if (d.b < 7 || d.b > 10) return BTC_ERR_UNSUPPORTED;
+  if ((long long)d.out * d.wpr * 4 >= (1LL << 31)) return BTC_ERR_UNSUPPORTED;     // 32-bit byte offsets
+  if ((long long)d.nchunks * d.v * 2 >= (1LL << 31)) return BTC_ERR_UNSUPPORTED;
+  if (d.v == 9) return fp4::launch1<9>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry);
+  return fp4::launch1<10>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry);
+}
+
 bool gemv_fp4_covers(const Dims& d) {
-  if (d.v != 9 && d.v != 10) return false;
-  if (d.b < 7 || d.b > 10) return false;
-  if ((long long)d.out * d.wpr * 4 >= (1LL << 31)) return false;
-  if ((long long)d.nchunks * d.v * 2 >= (1LL << 31)) return false;
-  return fp4::steps_for(d) != 0;    // table (at most 64 KB) + staging (at most 64 KB) always fit
+  return fp4_dispatch(nullptr, d, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0, /*dry=*/true) == BTC_OK;
 }
 
 btc_status gemv_fp4(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
                     const float* alpha, const float* mu, const void* x, void* y, int y_is_f32) {
-  if (!gemv_fp4_covers(d)) return BTC_ERR_UNSUPPORTED;
-  if (d.v == 9) return fp4::launch1<9>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32);
-  return fp4::launch1<10>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32);
+  return fp4_dispatch(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, /*dry=*/false);
 }
 
 }  // namespace btc
