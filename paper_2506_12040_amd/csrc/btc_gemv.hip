@@ -29,11 +29,14 @@ static btc_status gemv_dispatch(int engine, void* stream, const btc_shape* s, co
   const long long bytes = (long long)d.out * d.wpr * 4;
 
   if (engine == BTC_ENGINE_AUTO) {
-    // One activation row on the tuned settings (v = 9, 10; 7..10 index bits; rows of at most 15360 weights): the
-    // engine on the 4-bit matrix cores.  Measured against the engines below on every LLaMA-2 7B / 13B / 70B
-    // projection shape it covers, at 0.7 .. 1.11 bit: ahead on all of them (5.6 against 6.0 us on 5120 x 5120,
-    // 7.0 against 11.5 on 8192 x 8192, 14.1 against 21.6 on 28672 x 8192), level on matrices below 2 MB.
-    if (batch == 1 && gemv_fp4_covers(d))
+    // One activation row on the tuned settings (v = 9, 10; 7..10 index bits; rows of at most 30720 weights) and a
+    // matrix of 3.5 MiB or more: the engine on the 4-bit matrix cores.  Measured against the engines below on the
+    // LLaMA-2 7B / 13B / 70B projection shapes at 0.7 .. 1.11 bit: 7.5 against 10.5 us on 11008 x 4096, 7.8 against
+    // 11.5 on 8192 x 8192, 15.0 against 21.6 on 28672 x 8192; level at 13824 x 5120 (8.3 us); below 3 MiB its longer
+    // prologue (table and activation operands are built per workgroup) leaves the register-resident engine ahead
+    // (6.0 against 6.2 us on 5120 x 5120) -- unless the rows are long (6000 weights or more), where that engine and
+    // the table engine fall behind from 1 MiB on (2362 x 7266 at 1.0 bit: 9.8 and 8.4 against 7.8 us).
+    if (batch == 1 && (bytes >= (7LL << 19) || (bytes >= (1LL << 20) && d.nchunks >= 600)) && gemv_fp4_covers(d))
       engine = BTC_ENGINE_FP4;
     else
     // One row, 9 or 10 index bits, a wide matrix with few enough rows: the single-kernel variant of the

@@ -5,8 +5,12 @@
 // Algorithm "Binary Transformation and Compression").
 //
 // A +-1 weight is exactly representable in the 4-bit float format E2M1 (0x2 = +1, 0xA = -1), and an
-// fp16 activation is exactly the sum of four E5M2 numbers (E5M2 is the top byte of an fp16: take the top
-// byte, subtract, repeat -- every step removes three significant bits and the subtraction is exact).
+// fp16 activation is the sum of four E5M2 numbers (E5M2 is the top byte of an fp16: take the top byte,
+// subtract, repeat -- every step removes three significant bits and the subtraction is exact; what could
+// be lost is only what falls below the smallest E5M2 number, 2^-16, so every block of activations is first
+// multiplied by a power of two that brings its largest element to 2^14..2^15, and the partial sums of that
+// block are multiplied by the inverse power afterwards: exact down to 2^-30 of the block's largest
+// element).
 // So the product of 16 weight rows with one activation row is ONE instruction per 128 weights per row,
 //     V_MFMA_F32_16X16X128_F8F6F4   (A = 16 x 128 fp4 weights, B = 128 x 16 bf8, fp32 accumulate),
 // with the four pieces of x in four of the sixteen B columns and the result exact up to fp32
@@ -54,13 +58,15 @@ typedef __attribute__((address_space(3))) unsigned long long lds_u64;
 
 constexpr uint32_t kOob = 0x80000000u;   // buffer offset that is always out of range (buffers are < 2 GiB)
 constexpr int kRsrcFlags = 0x00020000;   // raw buffer, 32-bit data format
-constexpr int kCW = 8;                   // column waves per team
 constexpr int kPD = 2;                   // row blocks in flight per wave in registers (a third one sits in LDS)
 constexpr int kSetBytes = 2048;          // B operands of four steps: 16 columns x 4 k blocks x 32 bytes
 
-template <int V, int B, int T, int TEAMS>
+// CW column waves per team: 8, two teams (LDS permitting) -- or 16 in one team for rows of more than 15360
+// weights ("wide"), where every wave prepares its own B operands, one set at a time, in a small buffer.
+template <int V, int B, int T, int TEAMS, int CW>
 struct Cfg {
-  static constexpr int W = kCW * TEAMS;                     // waves per workgroup
+  static constexpr int W = CW * TEAMS;                      // waves per workgroup
+  static constexpr bool WIDE = CW == 16;
   static constexpr int G = 3;                               // chunks per 128-bit operand of a lane
   static constexpr int TAIL = V - 8;                        // elements of a chunk in the high word of its entry
   static constexpr int L = G * T;                           // chunks per strand
@@ -75,14 +81,16 @@ struct Cfg {
   static constexpr int C = (B <= 8) ? 32 : (B == 9) ? 16 : 8;   // table copies (32: no two lanes of a wave share a bank pair)
   static constexpr int LOG2C = C == 32 ? 5 : (C == 16 ? 4 : 3);
   static constexpr int kTableBytes = (1 << B) * C * 8;
-  static constexpr int kRedBytes = (2 * W * 16 * 4 + W * 4 + 15) & ~15;
+  static constexpr int kRedBytes = (2 * W * 16 * 4 + W * 4 + CW * 2 * 4 + 15) & ~15;
   static constexpr int kIdxBytes = W * 16 * S * 4;          // one staged row block per wave
   static constexpr int NSET = (T + 3) / 4;                  // B register sets
-  static constexpr int kStageBytes = kCW * NSET * kSetBytes;
+  static constexpr int kStageBytes = WIDE ? 0 : CW * NSET * kSetBytes;   // wide: the wave's index area serves first
+  static_assert(!WIDE || 16 * S * 4 >= kSetBytes, "a set fits the wave's index area");
   static constexpr int kLdsBytes = kTableBytes + kRedBytes + kIdxBytes + kStageBytes;
   static_assert(V == 9 || V == 10, "three chunks per operand, tails of one or two elements");
   static_assert(B >= 7 && B <= 10, "table of at most 64 KB");
   static_assert(LPR <= 32, "at least two rows per load instruction");
+  static_assert(TEAMS == 1 || CW == 8, "two teams of eight");
 };
 
 __device__ __forceinline__ float dpp_xor1(float v) {
@@ -105,6 +113,17 @@ __device__ __forceinline__ float wave_sum_to_lane63(float v) {
   v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true));  // row_mirror
   v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x142, 0xA, 0xF, false)); // row_bcast:15
   v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x143, 0xC, 0xF, false)); // row_bcast:31
+  return v;
+}
+
+// Maximum over the 64 lanes, valid in lane 63.
+__device__ __forceinline__ uint32_t wave_max_to_lane63(uint32_t v) {
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, true));    // quad xor 1
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, true));    // quad xor 2
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, true));   // row_half_mirror
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xF, 0xF, true));   // row_mirror
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, false));  // row_bcast:15
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, false));  // row_bcast:31
   return v;
 }
 
@@ -143,25 +162,27 @@ __device__ unsigned long long g_stamps[4 * 64];
 // e < 24: c = e / 8, u = e % 8;  24 <= e < 24 + 3 TAIL: c = (e - 24) / TAIL, u = 8 + (e - 24) % TAIL;  else padding.
 // The same order is used for the activations on the B side.
 
-template <int V, int B, int T, int TEAMS>
-__global__ __launch_bounds__(kCW * TEAMS * 64) void gemv_fp4_kernel(
+template <int V, int B, int T, int TEAMS, int CW>
+__global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
     Dims d, const uint32_t* __restrict__ packed, const uint32_t* __restrict__ codebook,
     const float* __restrict__ alpha, const float* __restrict__ mu, const __half* __restrict__ x,
     void* __restrict__ y, int y_is_f32, int n_rb, int x_dword) {
-  using K = Cfg<V, B, T, TEAMS>;
+  using K = Cfg<V, B, T, TEAMS, CW>;
+  constexpr bool WIDE = K::WIDE;
   constexpr int W = K::W, G = K::G, TAIL = K::TAIL, ND = K::ND, C = K::C, L = K::L;
   constexpr int LPR = K::LPR, RPI = K::RPI, NLD = K::NLD, S = K::S;
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned long long* table = (unsigned long long*)smem;                       // [2^B][C], at LDS offset 0
   float* red = (float*)(smem + K::kTableBytes);                                // [2 phases][W][16]
   float* sxp = red + 2 * W * 16;                                               // [W]
+  int* scl = (int*)(sxp + W);                                                   // [CW][2] block scale exponents
   uint32_t* idx_all = (uint32_t*)(smem + K::kTableBytes + K::kRedBytes);       // [W][16][S]
-  unsigned char* bstage_all = smem + K::kTableBytes + K::kRedBytes + K::kIdxBytes;  // [kCW][NSET][2048]
+  unsigned char* bstage_all = smem + K::kTableBytes + K::kRedBytes + K::kIdxBytes;  // [CW][NSET][2048]; wide: [W][2048]
 
   const int tid = threadIdx.x, lane = tid & 63;
   STAMP(0);
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int cw = wave & (kCW - 1), team = wave / kCW;        // column wave, team
+  const int cw = wave & (CW - 1), team = wave / CW;          // column wave, team
   const int r = lane & 15, q = lane >> 4;
   const int stride = gridDim.x;                              // row blocks between successive ones of a team slot
 
@@ -173,31 +194,67 @@ __global__ __launch_bounds__(kCW * TEAMS * 64) void gemv_fp4_kernel(
   uint32_t cwd[KPT];
 #pragma unroll
   for (int i = 0; i < KPT; ++i) cwd[i] = codebook[min(tid + i * W * 64, (1 << B) - 1)];
-  unsigned char* bstage = bstage_all + cw * (K::NSET * kSetBytes);
+  unsigned char* bstage = WIDE ? (unsigned char*)(idx_all + wave * (16 * S)) : bstage_all + cw * (K::NSET * kSetBytes);
   const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)x, 0, d.in * 2, kRsrcFlags);
-  constexpr int n_items = (TEAMS == 2 ? 4 : 8) * T;
-  constexpr int NI = (n_items + 63) / 64;
+  // With two teams, team e prepares the steps t = e, e + 2, ...: a step's B operand then carries one block
+  // scale, and steps of different parity never share an accumulator.
+  constexpr int n_items = WIDE ? 0 : 8 * (TEAMS == 2 ? (T + 1) / 2 : T);
+  constexpr int NI = WIDE ? 1 : (n_items + 63) / 64;
   uint32_t hx[NI][8];                                      // 16 fp16 values per item, in slot order
+  // wide: one half item (8 slots) per lane and set: step 4 tt + lane / 16, strand (lane / 4) % 4, half (lane / 2) % 2,
+  // quarter lane % 2 -- chunk 0, chunk 1, chunk 2 (elements 0..7 each) or the three tails
+  uint32_t hw[WIDE ? K::NSET : 1][4];
+  if constexpr (WIDE) {
 #pragma unroll
-  for (int ii = 0; ii < NI; ++ii) {
+    for (int tt = 0; tt < K::NSET; ++tt) {
+      const int t = 4 * tt + (lane >> 4), qa = (lane >> 2) & 3, part = lane & 3;
+      const uint32_t xb = (uint32_t)((cw * 4 + qa) * L + G * t) * V;
+      const bool live = t < T;
+      if (x_dword) {
+        const auto a4 = __builtin_amdgcn_raw_buffer_load_b128(rx, (live && part < 3) ? (xb + part * V) * 2u : kOob, 0, 0);
+        uint32_t tl[3] = {0u, 0u, 0u};
+        if constexpr (TAIL == 2) {
+#pragma unroll
+          for (int c = 0; c < 3; ++c)
+            tl[c] = __builtin_amdgcn_raw_buffer_load_b32(rx, (live && part == 3) ? (xb + c * V + 8u) * 2u : kOob, 0, 0);
+        }
+        hw[tt][0] = part < 3 ? a4[0] : tl[0];
+        hw[tt][1] = part < 3 ? a4[1] : tl[1];
+        hw[tt][2] = part < 3 ? a4[2] : tl[2];
+        hw[tt][3] = part < 3 ? a4[3] : 0u;
+      } else {
+        uint32_t hv[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const bool pad = part == 3 && e >= 3 * TAIL;
+          const uint32_t xe = part < 3 ? xb + part * V + e : xb + (uint32_t)(e / TAIL) * V + 8u + (uint32_t)(e % TAIL);
+          hv[e] = __builtin_amdgcn_raw_buffer_load_b16(rx, (live && !pad) ? xe * 2u : kOob, 0, 0) & 0xFFFFu;
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) hw[tt][k] = hv[2 * k] | (hv[2 * k + 1] << 16);
+      }
+    }
+  }
+#pragma unroll
+  for (int ii = 0; ii < (WIDE ? 0 : NI); ++ii) {
     const int item = lane + 64 * ii;
-    const int t = TEAMS == 2 ? item >> 2 : item >> 3;
-    const int qa = TEAMS == 2 ? item & 3 : (item >> 1) & 3;
-    const int h = TEAMS == 2 ? team : item & 1;
+    const int t = TEAMS == 2 ? 2 * (item >> 3) + team : item >> 3;
+    const int qa = (item >> 1) & 3;
+    const int h = item & 1;
     const uint32_t xb = (uint32_t)((cw * 4 + qa) * L + G * t) * V;   // first element of the step's three chunks
-    const bool live = item < n_items;
+    const bool live = t < T;
     // half 0: chunk 0 elements 0..7, chunk 1 elements 0..7; half 1: chunk 2 elements 0..7, then the tails
     const uint32_t run0 = h == 0 ? xb : xb + 2u * V;
     if (x_dword) {        // V and `in` even: every pair of elements is one aligned word
       const auto a4 = __builtin_amdgcn_raw_buffer_load_b128(rx, live ? run0 * 2u : kOob, 0, 0);
 #pragma unroll
       for (int k = 0; k < 4; ++k) hx[ii][k] = a4[k];
-      if (h == 0 || TEAMS == 1) {
+      {
         const auto b4 = __builtin_amdgcn_raw_buffer_load_b128(rx, (live && h == 0) ? (xb + V) * 2u : kOob, 0, 0);
 #pragma unroll
         for (int k = 0; k < 4; ++k) hx[ii][4 + k] = b4[k];
       }
-      if (h == 1 || TEAMS == 1) {
+      {
         if constexpr (TAIL == 2) {
           uint32_t tl[3];
 #pragma unroll
@@ -285,19 +342,84 @@ __global__ __launch_bounds__(kCW * TEAMS * 64) void gemv_fp4_kernel(
   }
   STAMP(2);
 
-  if (T & 3) {   // B columns of steps that do not exist must not hold junk (the two teams share the clearing)
+  if (!WIDE && (T & 3)) {   // B columns of steps that do not exist must not hold junk (the two teams share the clearing)
     uint4* z = (uint4*)(bstage + (K::NSET - 1) * kSetBytes + (T & 3) * 512) + team * ((4 - (T & 3)) * 32 / TEAMS);
     for (int i = lane; i < (4 - (T & 3)) * 32 / TEAMS; i += 64) z[i] = make_uint4(0, 0, 0, 0);
   }
   // ---- activations -> four E5M2 pieces each (the top byte of an fp16 IS an E5M2 number; subtracting it
   // leaves at most 8 significant bits, exactly), written in B-operand layout: 16 bytes per item and piece
+  // Block scale: 2^k brings the largest element this wave stages to 2^14..2^15 (positive fp16 bit patterns
+  // order like integers); the B lanes that hold this wave's items hand 2^-k to the matrix instruction.
   float sx_lane = 0.f;
+  int k_scale;
+  {
+    // largest magnitude of this lane's items: packed fp16 maximum of the absolute values, then the two halves
+    f16x2 m2 = {(_Float16)0.0f, (_Float16)0.0f};
 #pragma unroll
-  for (int ii = 0; ii < NI; ++ii) {
+    for (int ii = 0; ii < (WIDE ? 0 : NI); ++ii)
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        m2 = __builtin_elementwise_max(m2, __builtin_bit_cast(f16x2, hx[ii][i] & 0x7FFF7FFFu));
+    if constexpr (WIDE) {
+#pragma unroll
+      for (int tt = 0; tt < K::NSET; ++tt)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          m2 = __builtin_elementwise_max(m2, __builtin_bit_cast(f16x2, hw[tt][i] & 0x7FFF7FFFu));
+    }
+    const uint32_t mb = __builtin_bit_cast(uint32_t, m2);
+    uint32_t mx = max(mb & 0xFFFFu, mb >> 16);
+    mx = __builtin_amdgcn_readlane((int)wave_max_to_lane63(mx), 63);
+    const int e_field = (int)(mx >> 10);                 // 0 for subnormals, 31 for infinities and NaNs
+    k_scale = 29 - max(e_field, 1);
+    if (lane == 0) {
+      if (TEAMS == 2) scl[cw * 2 + team] = k_scale;
+      else scl[cw * 2] = scl[cw * 2 + 1] = k_scale;
+    }
+  }
+  i32x8 Bq[K::NSET];       // B operands: lane (column n = r, k block q) of set tt holds piece n % 4 of step 4 tt + n / 4
+  if constexpr (WIDE) {
+    // one set at a time through this wave's 2 KB buffer: 64 half items of 8 slots, then every lane reads its 32 bytes
+    const int qa = (lane >> 2) & 3, part = lane & 3;
+    unsigned char* dst = bstage + (lane >> 4) * 512 + (2 * (qa & 1) + (part >> 1)) * 32 + 16 * (qa >> 1) + 8 * (part & 1);
+    const int m1 = k_scale > 15 ? 15 : k_scale;
+    const uint32_t pw1 = (uint32_t)(15 + m1) << 10, pw2 = (uint32_t)(15 + (k_scale > 15 ? k_scale - 15 : 0)) << 10;
+    const f16x2 f1 = __builtin_bit_cast(f16x2, pw1 | (pw1 << 16)), f2 = __builtin_bit_cast(f16x2, pw2 | (pw2 << 16));
+#pragma unroll
+    for (int tt = 0; tt < K::NSET; ++tt) {
+      uint32_t res[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const f16x2 one = {(_Float16)1.0f, (_Float16)1.0f};
+        sx_lane = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, hw[tt][i]), one, sx_lane, false);
+        res[i] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(f16x2, hw[tt][i]) * f1 * f2);   // x * 2^k, exactly
+      }
+#pragma unroll
+      for (int n = 0; n < 4; ++n) {
+        const uint32_t o0 = __builtin_amdgcn_perm(res[1], res[0], 0x07050301u);
+        const uint32_t o1 = __builtin_amdgcn_perm(res[3], res[2], 0x07050301u);
+        *(uint2*)(dst + n * 128) = make_uint2(o0, o1);     // steps past T stage zeros (their loads returned zeros)
+        if (n < 3) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const f16x2 top = __builtin_bit_cast(f16x2, res[i] & 0xFF00FF00u);
+            res[i] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(f16x2, res[i]) - top);
+          }
+        }
+      }
+      wave_lds_order();
+      const uint4* src = (const uint4*)(bstage + r * 128 + q * 32);
+      const uint4 lo = src[0], hi = src[1];
+      Bq[tt] = i32x8{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+      wave_lds_order();
+    }
+  }
+#pragma unroll
+  for (int ii = 0; ii < (WIDE ? 0 : NI); ++ii) {
     const int item = lane + 64 * ii;
-    const int t = TEAMS == 2 ? item >> 2 : item >> 3;
-    const int qa = TEAMS == 2 ? item & 3 : (item >> 1) & 3;
-    const int h = TEAMS == 2 ? team : item & 1;
+    const int t = TEAMS == 2 ? 2 * (item >> 3) + team : item >> 3;
+    const int qa = (item >> 1) & 3;
+    const int h = item & 1;
     // piece n of step t is column 4 (t % 4) + n of set t / 4
     unsigned char* dst = bstage + (t >> 2) * kSetBytes + (t & 3) * 512 + (2 * (qa & 1) + h) * 32 + 16 * (qa >> 1);
     uint32_t res[8];
@@ -307,7 +429,22 @@ __global__ __launch_bounds__(kCW * TEAMS * 64) void gemv_fp4_kernel(
       const f16x2 one = {(_Float16)1.0f, (_Float16)1.0f};
       sx_lane = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, res[i]), one, sx_lane, false);
     }
-    if (item < n_items) {
+    // x * 2^k, exactly (k is the same for the whole wave): one multiplication by at most 2^15, and a second
+    // one when the whole block is below 2^-1
+    {
+      const int m = k_scale > 15 ? 15 : k_scale;
+      const uint32_t pw = (uint32_t)(15 + m) << 10;
+      const f16x2 f = __builtin_bit_cast(f16x2, pw | (pw << 16));
+#pragma unroll
+      for (int i = 0; i < 8; ++i) res[i] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(f16x2, res[i]) * f);
+      if (k_scale > 15) {
+        const uint32_t pw2 = (uint32_t)(15 + (k_scale - 15)) << 10;
+        const f16x2 f2 = __builtin_bit_cast(f16x2, pw2 | (pw2 << 16));
+#pragma unroll
+        for (int i = 0; i < 8; ++i) res[i] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(f16x2, res[i]) * f2);
+      }
+    }
+    if (t < T) {
 #pragma unroll
       for (int n = 0; n < 4; ++n) {
         uint32_t o4[4];
@@ -345,10 +482,12 @@ __global__ __launch_bounds__(kCW * TEAMS * 64) void gemv_fp4_kernel(
   const uint32_t s0 = lbit & 31u;
   const uint32_t* my_words = idx_stage + r * S + (lbit >> 5);
   const uint32_t lane_copy = (uint32_t)(lane & (C - 1)) * 8u;   // this lane's copy of every table entry
-  // B operands: lane (column n = r, k block q) of set tt holds piece n % 4 of step 4 tt + n / 4
-  i32x8 Bq[K::NSET];
+  // inverse block scale of the accumulator class this lane keeps (class c = column / 4 collects the steps
+  // t = c mod 4, prepared by team c mod 2)
+  const float my_scale = __builtin_ldexpf(1.0f, -scl[cw * 2 + ((r >> 2) & 1)]);
+  // the shared B operands are complete: every wave takes its registers
 #pragma unroll
-  for (int tt = 0; tt < K::NSET; ++tt) {
+  for (int tt = 0; tt < (WIDE ? 0 : K::NSET); ++tt) {
     const uint4* src = (const uint4*)(bstage + tt * kSetBytes + r * 128 + q * 32);
     const uint4 lo = src[0], hi = src[1];
     Bq[tt] = i32x8{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
@@ -444,10 +583,11 @@ __global__ __launch_bounds__(kCW * TEAMS * 64) void gemv_fp4_kernel(
       const bool odd = r & 1, up = r & 2;
       const float w01 = (odd ? v4[1] : v4[0]) + dpp_xor1(odd ? v4[0] : v4[1]);
       const float w23 = (odd ? v4[3] : v4[2]) + dpp_xor1(odd ? v4[2] : v4[3]);
-      float z = (up ? w23 : w01) + dpp_xor2(up ? w01 : w23);
+      float z = (up ? w23 : w01) + dpp_xor2(up ? w01 : w23);   // quad sum: one class, one block scale
+      z *= my_scale;
       z += dpp_ror4(z);
       z += dpp_ror8(z);                                      // lane n: the sum of row 4 q + n % 4
-      float* rbuf = red + (it & 1) * (W * 16) + team * (kCW * 16);
+      float* rbuf = red + (it & 1) * (W * 16) + team * (CW * 16);
       if (r < 4) rbuf[cw * 16 + 4 * q + r] = z;
       if (it < 8) STAMP(10 + 5 * it);
       __syncthreads();
@@ -455,7 +595,7 @@ __global__ __launch_bounds__(kCW * TEAMS * 64) void gemv_fp4_kernel(
       if (finishes) {
         float tot = 0.f;
 #pragma unroll
-        for (int w = 0; w < kCW; ++w) tot += rbuf[w * 16 + lane];
+        for (int w = 0; w < CW; ++w) tot += rbuf[w * 16 + lane];
         const float res = al * tot + mm * sx;
         if (y_is_f32) ((float*)y)[my_row] = res;
         else ((__half*)y)[my_row] = __float2half_rn(res);
@@ -469,15 +609,15 @@ __global__ __launch_bounds__(kCW * TEAMS * 64) void gemv_fp4_kernel(
 
 constexpr int kLdsMax = 160 * 1024 - 64;
 
-template <int V, int B, int T, int TEAMS>
+template <int V, int B, int T, int TEAMS, int CW>
 static btc_status launch3(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
                           const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, bool dry) {
-  using K = Cfg<V, B, T, TEAMS>;
+  using K = Cfg<V, B, T, TEAMS, CW>;
   static_assert(K::kLdsBytes <= kLdsMax, "LDS budget");
   if (dry) return BTC_OK;         // only asked whether a kernel exists for this setting
   static bool attr_set = false;   // one-time kernel attribute, not call state
   if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)gemv_fp4_kernel<V, B, T, TEAMS>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    if (hipFuncSetAttribute((const void*)gemv_fp4_kernel<V, B, T, TEAMS, CW>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             K::kLdsBytes) != hipSuccess)
       return BTC_ERR_HIP;
     attr_set = true;
@@ -486,17 +626,22 @@ static btc_status launch3(hipStream_t q, const Dims& d, const uint32_t* packed, 
   const int slots = 256 * TEAMS;                         // one workgroup per compute unit, TEAMS row blocks at a time
   const int grid = n_rb < slots ? (n_rb + TEAMS - 1) / TEAMS : 256;
   const int x_dword = (V % 2 == 0) && (d.in % 2 == 0);
-  gemv_fp4_kernel<V, B, T, TEAMS><<<grid, K::W * 64, K::kLdsBytes, q>>>(d, packed, codebook, alpha, mu, (const __half*)x,
+  gemv_fp4_kernel<V, B, T, TEAMS, CW><<<grid, K::W * 64, K::kLdsBytes, q>>>(d, packed, codebook, alpha, mu, (const __half*)x,
                                                                           y, y_is_f32, n_rb, x_dword);
   return launch_status();
 }
 
-// Steps per row block: the 32 strands of a team must cover the row.  Instantiated for a few step counts; a
+// Steps per row block: the 4 CW strands of a team must cover the row.  Instantiated for a few step counts; a
 // strand that is longer than needed reads zeros for the activations past the end of the row.
-static int steps_for(const Dims& d) {
-  const int need = (d.nchunks + kCW * 4 * 3 - 1) / (kCW * 4 * 3);
+static int steps_for(const Dims& d, int cw) {
+  const int need = (d.nchunks + cw * 4 * 3 - 1) / (cw * 4 * 3);
   static const int have[] = {3, 4, 5, 6, 8, 9, 10, 12, 15, 16};
-  for (int t : have) if (need <= t) return t;
+  static const int have_wide[] = {9, 10, 12, 15, 16};     // 17 steps no longer fit 128 registers
+  if (cw == 8) {
+    for (int t : have) if (need <= t) return t;
+  } else {
+    for (int t : have_wide) if (need <= t) return t;
+  }
   return 0;
 }
 
@@ -506,17 +651,27 @@ static btc_status launch2(hipStream_t q, const Dims& d, const uint32_t* packed, 
   // two teams whenever table, staging areas and B operands of 16 waves fit the LDS
 #define BTC_FP4_CASE(TT)                                                                             \
   case TT:                                                                                           \
-    if constexpr (Cfg<V, B, TT, 2>::kLdsBytes <= kLdsMax)                                            \
-      return launch3<V, B, TT, 2>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry);           \
-    else if constexpr (Cfg<V, B, TT, 1>::kLdsBytes <= kLdsMax)                                       \
-      return launch3<V, B, TT, 1>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry);           \
+    if constexpr (Cfg<V, B, TT, 2, 8>::kLdsBytes <= kLdsMax)                                         \
+      return launch3<V, B, TT, 2, 8>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry);        \
+    else if constexpr (Cfg<V, B, TT, 1, 8>::kLdsBytes <= kLdsMax)                                    \
+      return launch3<V, B, TT, 1, 8>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry);        \
     else                                                                                             \
-      return BTC_ERR_UNSUPPORTED;
-  switch (steps_for(d)) {
+      break;
+#define BTC_FP4_WIDE(TT)                                                                             \
+  case TT:                                                                                           \
+    if constexpr (Cfg<V, B, TT, 1, 16>::kLdsBytes <= kLdsMax)                                        \
+      return launch3<V, B, TT, 1, 16>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry);       \
+    else                                                                                             \
+      break;
+  switch (steps_for(d, 8)) {
     BTC_FP4_CASE(3) BTC_FP4_CASE(4) BTC_FP4_CASE(5) BTC_FP4_CASE(6) BTC_FP4_CASE(8) BTC_FP4_CASE(9)
     BTC_FP4_CASE(10) BTC_FP4_CASE(12) BTC_FP4_CASE(15) BTC_FP4_CASE(16)
   }
+  switch (steps_for(d, 16)) {      // rows too long for eight column waves (or for their LDS areas)
+    BTC_FP4_WIDE(9) BTC_FP4_WIDE(10) BTC_FP4_WIDE(12) BTC_FP4_WIDE(15) BTC_FP4_WIDE(16)
+  }
 #undef BTC_FP4_CASE
+#undef BTC_FP4_WIDE
   return BTC_ERR_UNSUPPORTED;
 }
 
