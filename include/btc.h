@@ -122,6 +122,19 @@ btc_status btc_gemv(void* stream, const btc_shape* s, const uint32_t* packed,
                     const void* x, int32_t batch, void* y, btc_dtype y_dtype,
                     void* workspace, size_t workspace_bytes);
 
+/* btc_gemv for callers that cannot allocate or pass device scratch memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments (without the workspace), same kernels, same
+ * results and errors as btc_gemv.  Whatever btc_gemv would park in the caller's workspace goes to a static
+ * device array of 8 MiB inside the library (one copy per GPU, held until the process ends; its address is looked
+ * up on the first call on a device).  The call allocates nothing, on the host or the device.  A call whose engine
+ * needs more than 8 MiB returns BTC_ERR_WORKSPACE and enqueues nothing (use btc_gemv with a workspace of
+ * btc_workspace_bytes(s, batch, 0) bytes).  All calls on one GPU share the array: the part a call uses is cleared by
+ * a small kernel at its start, calls ordered on one stream are safe, calls that may overlap in time (different
+ * streams) race on it. */
+btc_status btc_gemv_static(void* stream, const btc_shape* s, const uint32_t* packed,
+                           const uint32_t* codebook, const float* alpha, const float* mu,
+                           const void* x, int32_t batch, void* y, btc_dtype y_dtype);
+
 /* Test and measurement hook: btc_gemv through ONE chosen engine, so that each engine can be checked against the
  * oracle and timed against the others on any shape (the engines are different ways of carrying out the same
  * blockwise sum of appendix "Binary Codebook LUT-GEMM").  Same arguments, results and errors as btc_gemv;

@@ -55,6 +55,8 @@ def lib() -> ctypes.CDLL:
         L.btc_unpack.argtypes = [vp, sp, vp, vp]
         L.btc_gemv.restype = ctypes.c_int
         L.btc_gemv.argtypes = [vp, sp, vp, vp, vp, vp, vp, i32, vp, ctypes.c_int, vp, sz]
+        L.btc_gemv_static.restype = ctypes.c_int
+        L.btc_gemv_static.argtypes = [vp, sp, vp, vp, vp, vp, vp, i32, vp, ctypes.c_int]
         L.btc_gemv_engine.restype = ctypes.c_int
         L.btc_gemv_engine.argtypes = [vp, sp, vp, vp, vp, vp, vp, i32, vp, ctypes.c_int, vp, sz, i32]
         L.btc_gemm.restype = ctypes.c_int
@@ -133,6 +135,11 @@ def btc_gemv(s: btc_shape, packed, codebook, alpha, mu, x, batch: int, y, y_dtyp
     wb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
     _check(lib().btc_gemv(_stream(stream), ctypes.byref(s), _ptr(packed), _ptr(codebook), _ptr(alpha), _ptr(mu),
                           _ptr(x), batch, _ptr(y), y_dtype, _ptr(workspace), wb), "btc_gemv")
+
+
+def btc_gemv_static(s: btc_shape, packed, codebook, alpha, mu, x, batch: int, y, y_dtype: int, stream=None) -> None:
+    _check(lib().btc_gemv_static(_stream(stream), ctypes.byref(s), _ptr(packed), _ptr(codebook), _ptr(alpha), _ptr(mu),
+                                 _ptr(x), batch, _ptr(y), y_dtype), "btc_gemv_static")
 
 
 def btc_gemv_engine(s: btc_shape, packed, codebook, alpha, mu, x, batch: int, y, y_dtype: int, engine: int,

@@ -1,4 +1,6 @@
 // btc_gemv: argument checks and engine selection for the decode-time product.
+#include <mutex>
+
 #include "btc_internal.h"
 
 // Rough duration in microseconds of one decode pass over the matrix for a single activation
@@ -9,26 +11,11 @@ static double row_pass_us(const btc::Dims& d) { return 3.5 + 1.8e-6 * (double)d.
 
 namespace btc {
 
-// One decode call through a chosen engine (engine = BTC_ENGINE_AUTO: the dispatcher's own choice).  A forced
-// engine that does not cover the shape or the batch returns BTC_ERR_UNSUPPORTED.
-static btc_status gemv_dispatch(int engine, void* stream, const btc_shape* s, const uint32_t* packed,
-                                const uint32_t* codebook, const float* alpha, const float* mu, const void* x,
-                                int32_t batch, void* y, btc_dtype y_dtype, void* workspace, size_t workspace_bytes) {
-  btc_status st = check_shape(s);
-  if (st != BTC_OK) return st;
-  if (!packed || !codebook || !alpha || !mu || !x || !y) return BTC_ERR_NULL;
-  if (batch < 1 || batch > 16) return BTC_ERR_UNSUPPORTED;
-  if (y_dtype != BTC_F16 && y_dtype != BTC_F32) return BTC_ERR_UNSUPPORTED;
-  if (!aligned16(packed) || !aligned16(codebook) || !aligned16(alpha) || !aligned16(mu) || !aligned16(x) ||
-      !aligned16(y))
-    return BTC_ERR_ALIGN;
-  hipStream_t q = (hipStream_t)stream;
-  const Dims d = dims_of(*s);
-  const int y_is_f32 = y_dtype == BTC_F32;
-  const size_t ysz = y_is_f32 ? 4 : 2;
+// The dispatcher's choice of engine for a shape and a number of activation rows.
+static int choose_engine(const Dims& d, int batch) {
   const long long bytes = (long long)d.out * d.wpr * 4;
-
-  if (engine == BTC_ENGINE_AUTO) {
+  int engine = BTC_ENGINE_AUTO;
+  {
     // One activation row on the tuned settings (v = 9, 10; 7..10 index bits; rows of at most 30720 weights) and a
     // matrix of 3.5 MiB or more: the engine on the 4-bit matrix cores.  Measured against the engines below on the
     // LLaMA-2 7B / 13B / 70B projection shapes at 0.7 .. 1.11 bit: 7.5 against 10.5 us on 11008 x 4096, 7.8 against
@@ -63,6 +50,34 @@ static btc_status gemv_dispatch(int engine, void* stream, const btc_shape* s, co
     else
       engine = BTC_ENGINE_GENERIC;
   }
+
+  return engine;
+}
+
+// Whether an engine parks anything in the caller's workspace.
+static bool engine_uses_workspace(int engine) {
+  return engine == BTC_ENGINE_LUT || engine == BTC_ENGINE_MFMA || engine == BTC_ENGINE_TILED;
+}
+
+// One decode call through a chosen engine (engine = BTC_ENGINE_AUTO: the dispatcher's own choice).  A forced
+// engine that does not cover the shape or the batch returns BTC_ERR_UNSUPPORTED.
+static btc_status gemv_dispatch(int engine, void* stream, const btc_shape* s, const uint32_t* packed,
+                                const uint32_t* codebook, const float* alpha, const float* mu, const void* x,
+                                int32_t batch, void* y, btc_dtype y_dtype, void* workspace, size_t workspace_bytes) {
+  btc_status st = check_shape(s);
+  if (st != BTC_OK) return st;
+  if (!packed || !codebook || !alpha || !mu || !x || !y) return BTC_ERR_NULL;
+  if (batch < 1 || batch > 16) return BTC_ERR_UNSUPPORTED;
+  if (y_dtype != BTC_F16 && y_dtype != BTC_F32) return BTC_ERR_UNSUPPORTED;
+  if (!aligned16(packed) || !aligned16(codebook) || !aligned16(alpha) || !aligned16(mu) || !aligned16(x) ||
+      !aligned16(y))
+    return BTC_ERR_ALIGN;
+  hipStream_t q = (hipStream_t)stream;
+  const Dims d = dims_of(*s);
+  const int y_is_f32 = y_dtype == BTC_F32;
+  const size_t ysz = y_is_f32 ? 4 : 2;
+
+  if (engine == BTC_ENGINE_AUTO) engine = choose_engine(d, batch);
 
   switch (engine) {
     case BTC_ENGINE_MFMA_ONE:
@@ -120,9 +135,60 @@ static btc_status gemv_dispatch(int engine, void* stream, const btc_shape* s, co
   return BTC_ERR_UNSUPPORTED;
 }
 
+// ---- the entry point that allocates nothing: scratch memory in a file-scope device array ----------------------
+constexpr size_t kStaticScratchBytes = 8u << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices];     // device address of `scratch` on each GPU, looked up once per device
+
+// Address of this device's copy of the array (the array's name is only a host-side handle).
+static btc_status static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return BTC_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return BTC_ERR_HIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return BTC_OK;
+}
+
+__global__ void clear_scratch_kernel(uint4* p, size_t n16) {
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
+    p[i] = make_uint4(0, 0, 0, 0);
+}
+
 }  // namespace btc
 
 extern "C" {
+
+btc_status btc_gemv_static(void* stream, const btc_shape* s, const uint32_t* packed, const uint32_t* codebook,
+                           const float* alpha, const float* mu, const void* x, int32_t batch, void* y,
+                           btc_dtype y_dtype) {
+  using namespace btc;
+  btc_status st = check_shape(s);
+  if (st != BTC_OK) return st;
+  if (batch < 1 || batch > 16) return BTC_ERR_UNSUPPORTED;
+  const Dims d = dims_of(*s);
+  const int engine = choose_engine(d, batch);
+  if (!engine_uses_workspace(engine))   // most single-row calls: nothing is parked anywhere
+    return gemv_dispatch(engine, stream, s, packed, codebook, alpha, mu, x, batch, y, y_dtype, nullptr, 0);
+  const size_t need = btc_workspace_bytes(s, batch, 0);
+  if (need > kStaticScratchBytes) return BTC_ERR_WORKSPACE;   // larger than the static array: use btc_gemv
+  void* ws = nullptr;
+  st = static_scratch(&ws);
+  if (st != BTC_OK) return st;
+  // The array keeps whatever the last call left (zeros, unless a call was cut short): what this call's engine
+  // expects to be zero is cleared by a small kernel first (no memset node, so that the call can be captured).
+  const size_t n16 = (need + 15) / 16;
+  clear_scratch_kernel<<<(unsigned)((n16 + 255) / 256 < 1024 ? (n16 + 255) / 256 : 1024), 256, 0, (hipStream_t)stream>>>((uint4*)ws, n16);
+  if (launch_status() != BTC_OK) return BTC_ERR_HIP;
+  return gemv_dispatch(engine, stream, s, packed, codebook, alpha, mu, x, batch, y, y_dtype, ws, kStaticScratchBytes);
+}
 
 btc_status btc_gemv(void* stream, const btc_shape* s, const uint32_t* packed, const uint32_t* codebook,
                     const float* alpha, const float* mu, const void* x, int32_t batch, void* y, btc_dtype y_dtype,
