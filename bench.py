@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the binary-codebook linear layer on one MI355X.
 
-Workload (BASELINE.json: "btc_gemv effective weight GB/s + us/call (13B shapes,
+Headline workload (BASELINE.json: "btc_gemv effective weight GB/s + us/call (13B shapes,
 0.8-bit); GEMM TFLOP/s"): the seven linear projections of a LLaMA-2-13B decoder
 layer (4 x 5120x5120, 2 x 13824x5120, 1 x 5120x13824) stored at v=10, K=256
 (8-bit indices, 0.8 bit/weight), Zipf(1.1) indices, batch-1 fp16 activations.
@@ -10,21 +10,31 @@ One STEP = one decoder layer = 7 btc_gemv calls.  Consecutive steps walk
 through `--layers` distinct copies of the packed weights (40 copies = 1.27 GB,
 five times the 256 MB last-level cache), so every call streams its indices from
 HBM ("cold").  value = algorithmic bytes of a step / time of a step.  All
-inputs are resident in HBM before the timed region.  The launches of one
-sweep over all copies are captured once in a HIP graph (the calls still go
-through the C ABI, which only enqueues kernels) so that Python's per-call
-overhead is not what is timed; --mode stream times plain per-call launches.
+inputs are resident in HBM before the timed region.  The launches of the K timed
+steps are captured once in a HIP graph (the calls still go through the C ABI, which
+only enqueues kernels) so that Python's per-call overhead is not what is timed;
+--mode stream times plain per-call launches.  The K-step region is timed `--repeats`
+times in a row (5 by default) and the mean is reported, every repeat listed.
 
-Also reported: prefill btc_gemm TFLOP/s on the same shapes (M = --gemm-m and
-512), decode timings of the 7B shapes at batch 1/4/16 and of a 70B-shaped
-layer at 1.11/0.9/0.7 bit, a roofline object for the GEMV, and the CPU oracle
-timed on the host cores.
+Every sweep takes its layers from the seeded recipe of btc_synth.config_cases (packed on the
+GPU by btc_pack).  For each decode shape the line carries: cold time (a graph over distinct
+copies worth >= 1 GiB, i.e. streamed from HBM), warm time (one buffer, which the caches hold;
+may exceed the HBM peak), the time of a single event-bracketed launch, and the in-kernel
+time of the rocprofv3 summary under profiles/ when that file lists the shape.  Fractions are
+given against the published peaks (8 TB/s, 2.5 PFLOP/s bf16) and against what plain
+read / matrix-core loops reach on this machine (6.4 TB/s, 2.2 PFLOP/s).
+
+Also reported: prefill btc_gemm TFLOP/s (config 3: M = 2048 and 512), the transform, the
+clustering kernels, roofline objects (13B step, 70B-shaped layer, prefill), and the CPU oracle
+timed on the host cores (all cores and one thread; unpack, materialise, multiply separately).
 """
 from __future__ import annotations
 
 import argparse
+import ctypes
 import json
 import os
+import re
 import sys
 import time
 
@@ -35,12 +45,14 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
-# HBM bytes of one step (7 calls) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
-# 256 MiB copy (profiles/gemv_13b_hbm_traffic.md): 37.1 MB fetched + 5.5 MB written.
-HBM_TRAFFIC_PER_STEP = 45.2e6
+# what a plain 16-byte-per-lane read of 2 GiB and a plain bf16 matrix-core loop reach on this machine
+HBM_MEASURED_GBS = 6400.0
+MFMA_BF16_MEASURED_TFLOPS = 2200.0
+PROFILE_FIGURES = os.path.join(ROOT, "profiles", "gemv_13b_hbm_traffic.md")
+PROFILE_KERNEL_US = os.path.join(ROOT, "profiles", "gemv_gemm_13b_kernel_trace.md")
 
-SHAPES_13B = [(5120, 5120, 4), (13824, 5120, 2), (5120, 13824, 1)]   # (out, in, count per layer)
-V, K = 10, 256
+SHAPES_13B_COUNT = {(5120, 5120): 4, (13824, 5120): 2, (5120, 13824): 1}
+COUNT_70B = {(8192, 8192): 2, (1024, 8192): 2, (28672, 8192): 2, (8192, 28672): 1}
 
 
 def gemv_bytes(s, batch, y_bytes=2):
@@ -48,18 +60,30 @@ def gemv_bytes(s, batch, y_bytes=2):
     return s.out * s.words_per_row * 4 + s.out * 8 + batch * s.in_ * 2 + batch * s.out * y_bytes + (1 << s.b) * 4
 
 
+def read_figures(path):
+    """`name = number` lines of a profile summary (the figures this script quotes rather than measures)."""
+    figs = {}
+    if os.path.exists(path):
+        for line in open(path):
+            m = re.match(r"^\s*([A-Za-z0-9_ .x=]+?)\s*=\s*([0-9.eE+-]+)\s*$", line)
+            if m:
+                figs[m.group(1).strip()] = float(m.group(2))
+    return figs
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--repeats", type=int, default=5, help="the timed K-step region is run this many times in a row")
     ap.add_argument("--layers", type=int, default=40, help="distinct weight copies walked by consecutive steps")
     ap.add_argument("--mode", choices=["graph", "stream"], default="graph")
     ap.add_argument("--gemm-m", type=int, default=2048)
     ap.add_argument("--gemm-iters", type=int, default=10)
     ap.add_argument("--no-gemm", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
-    ap.add_argument("--no-transform", action="store_true", help="skip the btc_transform timings")
+    ap.add_argument("--no-transform", action="store_true", help="skip the btc_transform / btc_assign timings")
     ap.add_argument("--no-other", action="store_true", help="skip the 7B (batch 1/4/16) and 70B decode sweeps")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run three 256 MiB device-to-device copies (reference for FETCH_SIZE/WRITE_SIZE) and exit")
@@ -85,25 +109,41 @@ def main():
     B.lib()  # raises if the HIP library was not built
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    figures = read_figures(PROFILE_FIGURES)
+    kernel_us = read_figures(PROFILE_KERNEL_US)
 
-    # ---- one seeded layer per shape, packed on the GPU through btc_pack
+    def events():
+        return torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def device_case(case, x_dtype=None):
+        """One seeded layer of the recipe, packed on the GPU through btc_pack."""
+        kw = dict(case)
+        if x_dtype is not None:
+            kw["x_dtype"] = x_dtype
+        layer, x = S.make_case(**kw)
+        s = B.btc_shape_init(layer.out, layer.n_in, layer.v, layer.K)
+        idx_d = torch.from_numpy(layer.idx).to(dev)
+        packed = torch.empty(layer.out * s.words_per_row, dtype=torch.int32, device=dev)
+        B.btc_pack(s, idx_d, packed, torch.zeros(64, dtype=torch.uint8, device=dev))
+        cb = np.zeros(1 << s.b, dtype=np.uint32)
+        cb[:layer.K] = layer.codebook
+        return dict(s=s, layer=layer, batch=case["batch"], packed=packed.view(layer.out, s.words_per_row),
+                    codebook=torch.from_numpy(cb.view(np.int32)).to(dev),
+                    alpha=torch.from_numpy(layer.alpha).to(dev), mu=torch.from_numpy(layer.mu).to(dev),
+                    x=torch.from_numpy(x.view(np.int16)).to(dev), x_host=x)
+
+    def rotated(p, n):
+        """n distinct copies of a packed matrix: the rows rotated by a copy-specific offset."""
+        out = p["s"].out
+        return [torch.roll(p["packed"], shifts=((i * 7 + 1) * 37) % out, dims=0).contiguous() for i in range(n)]
+
+    # ---- config 2: one seeded layer per 13B shape
     t_setup = time.time()
     protos = []
-    for (out, n_in, count) in SHAPES_13B:
-        layer, x = S.make_case(0, out, n_in, V, K, 1, dist="zipf")
-        s = B.btc_shape_init(out, n_in, V, K)
-        idx_d = torch.from_numpy(layer.idx).to(dev)
-        packed = torch.empty(out * s.words_per_row, dtype=torch.int32, device=dev)
-        ws = torch.zeros(64, dtype=torch.uint8, device=dev)
-        B.btc_pack(s, idx_d, packed, ws)
-        cb = np.zeros(1 << s.b, dtype=np.uint32)
-        cb[:K] = layer.codebook
-        protos.append(dict(s=s, layer=layer, count=count, packed=packed.view(out, s.words_per_row),
-                           codebook=torch.from_numpy(cb.view(np.int32)).to(dev),
-                           alpha=torch.from_numpy(layer.alpha).to(dev), mu=torch.from_numpy(layer.mu).to(dev),
-                           x=torch.from_numpy(x.view(np.int16)).to(dev), x_host=x))
-        del idx_d
-    # distinct copies: copy c of a matrix is the prototype with its rows rotated by a copy-specific offset
+    for case in S.config_cases(2):
+        p = device_case(case)
+        p["count"] = SHAPES_13B_COUNT[(case["out"], case["n_in"])]
+        protos.append(p)
     calls_per_layer = []
     for L in range(args.layers):
         calls = []
@@ -130,118 +170,147 @@ def main():
         run_layer(i % args.layers)
     torch.cuda.synchronize()
 
-    # ---- timed region: exactly `steps` layers
-    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    # ---- timed region: exactly `steps` layers, `repeats` times in a row
+    repeats = max(1, args.repeats)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(repeats + 1)]
     if args.mode == "graph":
         full_sweeps, rest = divmod(args.steps, args.layers)
-        g_full = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g_full):
-            for L in range(args.layers):
-                run_layer(L)
-        g_rest = None
+        g_full = g_rest = None
+        if full_sweeps:
+            g_full = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g_full):
+                for L in range(args.layers):
+                    run_layer(L)
+            g_full.replay()
         if rest:
             g_rest = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g_rest):
                 for L in range(rest):
                     run_layer(L)
-        g_full.replay()
-        torch.cuda.synchronize()
-        start.record()
-        for _ in range(full_sweeps):
-            g_full.replay()
-        if g_rest is not None:
             g_rest.replay()
-        stop.record()
+        torch.cuda.synchronize()
+        marks[0].record()
+        for r in range(repeats):
+            for _ in range(full_sweeps):
+                g_full.replay()
+            if g_rest is not None:
+                g_rest.replay()
+            marks[r + 1].record()
     else:
         torch.cuda.synchronize()
-        start.record()
-        for i in range(args.steps):
-            run_layer(i % args.layers)
-        stop.record()
+        marks[0].record()
+        for r in range(repeats):
+            for i in range(args.steps):
+                run_layer(i % args.layers)
+            marks[r + 1].record()
     torch.cuda.synchronize()
-    ms_total = start.elapsed_time(stop)
-    ms_per_step = ms_total / args.steps
+    ms_repeats = [marks[r].elapsed_time(marks[r + 1]) / args.steps for r in range(repeats)]
+    ms_per_step = marks[0].elapsed_time(marks[repeats]) / (args.steps * repeats)
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
     us_per_call = ms_per_step * 1e3 / n_calls
     fp16_equiv = sum(2 * c["p"]["s"].out * c["p"]["s"].in_ for c in calls_per_layer[0]) / (ms_per_step * 1e-3) / 1e9
 
-    # per-shape timing (cold, rotating through the copies), events on the launch stream
-    per_shape = {}
-    for si, p in enumerate(protos):
-        mats = [c for calls in calls_per_layer for c in calls if c["p"] is p]
-        reps = max(1, 200 // len(mats))
-        gs = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(gs):
-            for c in mats:
-                B.btc_gemv(p["s"], c["packed"], p["codebook"], p["alpha"], p["mu"], p["x"], 1, c["y"], B.BTC_F16, ws)
-        gs.replay()
+    def time_decode(p, min_calls=200):
+        """Cold / warm / single-launch times of btc_gemv on one seeded layer."""
+        s, batch = p["s"], p["batch"]
+        nbytes = s.out * s.words_per_row * 4
+        ncopies = int(min(1200, max(8, -(-(1 << 30) // nbytes))))
+        copies = rotated(p, ncopies)
+        y = torch.empty(batch * s.out, dtype=torch.float16, device=dev)
+        wsd = torch.zeros(B.btc_workspace_bytes(s, batch, False), dtype=torch.uint8, device=dev)
+        call = lambda w: B.btc_gemv(s, w, p["codebook"], p["alpha"], p["mu"], p["x"], batch, y, B.BTC_F16, wsd)
+        for w in copies[:8]:
+            call(w)
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        by = gemv_bytes(s, batch)
+        # cold, amortised over a graph of all copies
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for w in copies:
+                call(w)
+        g.replay()
+        torch.cuda.synchronize()
+        reps = max(2, -(-min_calls // ncopies))
+        e0, e1 = events()
         e0.record()
         for _ in range(reps):
-            gs.replay()
+            g.replay()
         e1.record()
         torch.cuda.synchronize()
-        us = e0.elapsed_time(e1) * 1e3 / (reps * len(mats))
-        by = gemv_bytes(p["s"], 1)
-        per_shape[f"{p['s'].out}x{p['s'].in_}"] = dict(us_per_call=round(us, 3), bytes=by,
-                                                        eff_GBps=round(by / us / 1e3, 1),
-                                                        frac_hbm=round(by / us / 1e3 / HBM_PEAK_GBS, 4))
-
-    # ---- the other decode configurations of the benchmark spec (timing only; random index words of the
-    # right shape, >= 1 GiB of distinct copies per shape so that every call streams from HBM)
-    other = None
-    if not args.no_other:
-        other = {}
-
-        def time_gemv(out_, in_, v_, K_, batch, reps_target=120):
-            s2 = B.btc_shape_init(out_, in_, v_, K_)
-            nbytes = out_ * s2.words_per_row * 4
-            ncopies = int(min(64, max(8, -(-(1 << 30) // nbytes))))
-            proto = torch.randint(0, 2**31 - 1, (out_, s2.words_per_row), dtype=torch.int32, device=dev)
-            copies = [torch.roll(proto, shifts=(i * 37 + 1) % out_, dims=0).contiguous() for i in range(ncopies)]
-            cb2 = torch.randint(0, 1 << v_, (1 << s2.b,), dtype=torch.int32, device=dev)
-            al2 = torch.rand(out_, device=dev) * 0.02
-            mu2 = torch.rand(out_, device=dev) * 0.002
-            x2 = torch.randn(batch, in_, device=dev).half()
-            y2 = torch.empty(batch, out_, dtype=torch.float16, device=dev)
-            ws2 = torch.zeros(B.btc_workspace_bytes(s2, batch, False), dtype=torch.uint8, device=dev)
-            for c in copies:
-                B.btc_gemv(s2, c, cb2, al2, mu2, x2, batch, y2, B.BTC_F16, ws2)
-            torch.cuda.synchronize()
-            g2 = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g2):
-                for c in copies:
-                    B.btc_gemv(s2, c, cb2, al2, mu2, x2, batch, y2, B.BTC_F16, ws2)
-            g2.replay()
-            torch.cuda.synchronize()
-            reps = max(1, reps_target // ncopies)
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        cold = e0.elapsed_time(e1) * 1e3 / (reps * ncopies)
+        # warm: the same buffer again and again
+        gw = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gw):
+            for _ in range(50):
+                call(copies[0])
+        gw.replay()
+        torch.cuda.synchronize()
+        e0, e1 = events()
+        e0.record()
+        for _ in range(4):
+            gw.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        warm = e0.elapsed_time(e1) * 1e3 / 200
+        # one launch between two events, on a copy not touched recently
+        singles = []
+        for i in range(min(ncopies, 24)):
+            e0, e1 = events()
             e0.record()
-            for _ in range(reps):
-                g2.replay()
+            call(copies[-1 - i])
             e1.record()
             torch.cuda.synchronize()
-            us = e0.elapsed_time(e1) * 1e3 / (reps * ncopies)
-            by = gemv_bytes(s2, batch)
-            del copies, proto
-            return dict(us_per_call=round(us, 2), eff_GBps=round(by / us / 1e3, 1),
-                        frac_hbm=round(by / us / 1e3 / HBM_PEAK_GBS, 4))
+            singles.append(e0.elapsed_time(e1) * 1e3)
+        del copies, g, gw
+        single = float(np.median(singles))
+        row = dict(bytes=by, cold_us=round(cold, 2), warm_us=round(warm, 2), single_launch_us=round(single, 2),
+                   eff_GBps=round(by / cold / 1e3, 1), frac_hbm=round(by / cold / 1e3 / HBM_PEAK_GBS, 4),
+                   frac_measured_peak=round(by / cold / 1e3 / HBM_MEASURED_GBS, 4),
+                   warm_GBps=round(by / warm / 1e3, 1), cold_copies=ncopies)
+        k_us = kernel_us.get(f"in_kernel_us {s.out}x{s.in_} v={s.v} K={s.K} batch={batch}")
+        if k_us is not None:
+            row["in_kernel_us"] = k_us
+        return row
 
+    # per-shape timing of the headline shapes
+    per_shape = {f"{p['s'].out}x{p['s'].in_}": time_decode(p) for p in protos}
+
+    # ---- the other decode configurations of the north star
+    other, roof70 = None, None
+    if not args.no_other:
+        other = {}
         seven = {}
-        for (o, i) in [(4096, 4096), (11008, 4096), (4096, 11008)]:
-            seven[f"{o}x{i}"] = {f"batch{b}": time_gemv(o, i, 10, 512, b) for b in (1, 4, 16)}
-        other["llama2-7b v=10 K=512 (0.9 bit)"] = seven
-        for (v_, K_, tag) in [(9, 1024, "1.11 bit"), (10, 512, "0.9 bit"), (10, 128, "0.7 bit")]:
-            per, layer_us, layer_bytes = {}, 0.0, 0
-            for (o, i, cnt) in [(8192, 8192, 2), (1024, 8192, 2), (28672, 8192, 2), (8192, 28672, 1)]:
-                r = time_gemv(o, i, v_, K_, 1, reps_target=60)
-                per[f"{o}x{i}"] = r
-                layer_us += cnt * r["us_per_call"]
-                layer_bytes += cnt * gemv_bytes(B.btc_shape_init(o, i, v_, K_), 1)
-            other[f"llama2-70b v={v_} K={K_} ({tag})"] = dict(
-                per_shape=per, layer_us=round(layer_us, 1), layer_eff_GBps=round(layer_bytes / layer_us / 1e3, 1),
-                layer_frac_hbm=round(layer_bytes / layer_us / 1e3 / HBM_PEAK_GBS, 4))
+        for case in S.config_cases(1):     # 7B shapes, 0.9 bit, 1 % outlier channels, batch 1 / 4 / 16
+            p = device_case(case)
+            seven.setdefault(f"{case['out']}x{case['n_in']}", {})[f"batch{case['batch']}"] = time_decode(p)
+            del p
+        other["llama2-7b v=10 K=512 (0.9 bit), outlier channels"] = seven
+        tags = {(9, 1024): "1.11 bit", (10, 512): "0.9 bit", (10, 128): "0.7 bit"}
+        layers70 = {}
+        for case in S.config_cases(4):     # 70B shapes at three settings
+            p = device_case(case)
+            key = f"llama2-70b v={case['v']} K={case['K']} ({tags[(case['v'], case['K'])]})"
+            d = layers70.setdefault(key, dict(per_shape={}, us=0.0, bytes=0))
+            r = time_decode(p, min_calls=80)
+            cnt = COUNT_70B[(case["out"], case["n_in"])]
+            d["per_shape"][f"{case['out']}x{case['n_in']}"] = r
+            d["us"] += cnt * r["cold_us"]
+            d["bytes"] += cnt * r["bytes"]
+            del p
+        for key, d in layers70.items():
+            gbs = d["bytes"] / d["us"] / 1e3
+            other[key] = dict(per_shape=d["per_shape"], layer_us=round(d["us"], 1), layer_eff_GBps=round(gbs, 1),
+                              layer_frac_hbm=round(gbs / HBM_PEAK_GBS, 4),
+                              layer_frac_measured_peak=round(gbs / HBM_MEASURED_GBS, 4))
+        key09 = "llama2-70b v=10 K=512 (0.9 bit)"
+        big = other[key09]["per_shape"]["28672x8192"]
+        roof70 = {"bound": "hbm", "achieved": big["eff_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                  "frac": big["frac_hbm"], "frac_measured_peak": big["frac_measured_peak"],
+                  "traffic": figures.get("traffic_bytes_per_call 28672x8192 v=10 K=512"),
+                  "layer_frac": other[key09]["layer_frac_hbm"],
+                  "note": "btc_gemv on 28672x8192 at 0.9 bit, batch 1, cold: algorithmic bytes of a call "
+                          f"({big['bytes']}) / graph-amortised time of a call; layer_frac = the seven matrices of "
+                          "a 70B-shaped decoder layer"}
         # independent projections (q, k, v of one layer) on three streams, one graph per stream
         p0 = protos[0]
         mats = [c for calls in calls_per_layer for c in calls if c["p"] is p0][:120]
@@ -277,7 +346,7 @@ def main():
                 torch.matmul(xd, w.t())
             torch.cuda.synchronize()
             reps = 8 if M <= 16 else 2
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0, e1 = events()
             e0.record()
             for _ in range(reps):
                 for w in Ws:
@@ -287,19 +356,16 @@ def main():
             del Ws
             return e0.elapsed_time(e1) * 1e3 / (reps * ncopies)
 
-        def time_gemm(out_, in_, v_, K_, M):
-            s2 = B.btc_shape_init(out_, in_, v_, K_)
-            pk = torch.randint(0, 2**31 - 1, (out_, s2.words_per_row), dtype=torch.int32, device=dev)
-            cb2 = torch.randint(0, 1 << v_, (1 << s2.b,), dtype=torch.int32, device=dev)
-            al2 = torch.rand(out_, device=dev) * 0.02
-            mu2 = torch.rand(out_, device=dev) * 0.002
-            X2 = torch.randn(M, in_, device=dev).bfloat16()
-            Y2 = torch.empty(M, out_, dtype=torch.bfloat16, device=dev)
-            ws2 = torch.zeros(B.btc_workspace_bytes(s2, M, True), dtype=torch.uint8, device=dev)
-            f = lambda: B.btc_gemm(s2, pk, cb2, al2, mu2, X2, B.BTC_BF16, M, Y2, B.BTC_BF16, ws2)
+        def time_gemm_call(p, M):
+            s = p["s"]
+            X2 = torch.randn(M, s.in_, device=dev).bfloat16()
+            Y2 = torch.empty(M, s.out, dtype=torch.bfloat16, device=dev)
+            ws2 = torch.zeros(B.btc_workspace_bytes(s, M, True), dtype=torch.uint8, device=dev)
+            f = lambda: B.btc_gemm(s, p["packed"], p["codebook"], p["alpha"], p["mu"], X2, B.BTC_BF16, M, Y2,
+                                   B.BTC_BF16, ws2)
             f()
             torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0, e1 = events()
             e0.record()
             for _ in range(4):
                 f()
@@ -313,35 +379,42 @@ def main():
             dense_us = time_dense(o_, i_, M, torch.float16)
             row = {"torch_fp16_us": round(dense_us, 1)}
             for (v_, K_, tag) in [(10, 512, "0.9 bit"), (10, 256, "0.8 bit"), (10, 128, "0.7 bit")]:
-                us = time_gemv(o_, i_, v_, K_, M, reps_target=40)["us_per_call"]
+                p = device_case(dict(seed=0, out=o_, n_in=i_, v=v_, K=K_, batch=M))
+                us = time_decode(p, min_calls=40)["cold_us"]
                 row[tag] = dict(us=us, speedup_over_fp16=round(dense_us / us, 2))
+                del p
             mlp[f"M{M}"] = row
+        p = device_case(dict(seed=0, out=o_, n_in=i_, v=10, K=256, batch=1))
         for M in (32, 64, 96, 128, 256, 512, 2048):        # btc_gemm, bf16 activations
             dense_us = time_dense(o_, i_, M, torch.bfloat16)
-            us = time_gemm(o_, i_, 10, 256, M)
+            us = time_gemm_call(p, M)
             mlp[f"M{M}"] = {"torch_bf16_us": round(dense_us, 1),
                             "0.8 bit": dict(us=round(us, 1), speedup_over_bf16=round(dense_us / us, 2),
                                             tflops=round(2.0 * M * o_ * i_ / us / 1e6, 1))}
+        del p
         other["mlp_8192x28672_vs_dense_torch"] = mlp
 
-    # ---- prefill GEMM on the same shapes (btc_gemm = one contraction kernel per call, plus a second pass when the call is split along k)
+    # ---- prefill GEMM, config 3 (uniform indices, bf16 activations, fp32 output): btc_gemm = one contraction
+    # kernel per call, plus a second pass when the call is split along k
     gemm = None
     if not args.no_gemm:
         gemm = {}
+        cases3 = {}
+        for case in S.config_cases(3):
+            cases3.setdefault(case["batch"], []).append(case)
         for M in sorted({args.gemm_m, 512}, reverse=True):
             per, tot_flop, tot_ms = {}, 0.0, 0.0
-            for p in protos:
+            for case in cases3.get(M) or [dict(c, batch=M) for c in cases3[2048]]:
+                p = device_case(case)
                 s = p["s"]
-                rng = np.random.Generator(np.random.PCG64(0))
-                Xb = S.draw_x(rng, M, s.in_, "bf16")
-                X = torch.from_numpy(Xb.view(np.int16)).to(dev)
+                X = p["x"]
                 Y = torch.empty(M * s.out, dtype=torch.float32, device=dev)
                 wsg = torch.zeros(B.btc_workspace_bytes(s, M, True), dtype=torch.uint8, device=dev)
                 call = lambda: B.btc_gemm(s, p["packed"], p["codebook"], p["alpha"], p["mu"], X, B.BTC_BF16, M, Y,
                                           B.BTC_F32, wsg)
                 call()
                 torch.cuda.synchronize()
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0, e1 = events()
                 e0.record()
                 for _ in range(args.gemm_iters):
                     call()
@@ -349,13 +422,15 @@ def main():
                 torch.cuda.synchronize()
                 ms = e0.elapsed_time(e1) / args.gemm_iters
                 flop = 2.0 * M * s.out * s.in_
+                cnt = SHAPES_13B_COUNT[(s.out, s.in_)]
                 per[f"{s.out}x{s.in_}"] = dict(ms=round(ms, 4), tflops=round(flop / ms / 1e9, 1))
-                tot_flop += flop * p["count"]
-                tot_ms += ms * p["count"]
-                del X, Y
+                tot_flop += flop * cnt
+                tot_ms += ms * cnt
+                del X, Y, p
             tf = tot_flop / tot_ms / 1e9
             gemm[f"M{M}"] = dict(M=M, x_dtype="bf16", y_dtype="f32", per_shape=per, layer_tflops=round(tf, 1),
-                                 frac_mfma_peak=round(tf / MFMA_BF16_PEAK_TFLOPS, 4))
+                                 frac_mfma_peak=round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
+                                 frac_measured_peak=round(tf / MFMA_BF16_MEASURED_TFLOPS, 4))
 
     # ---- the online activation transform in front of the layer (btc_transform), on the two input widths of
     # the 13B layer: decode rows from a captured graph of 20 launches, prefill rows event-timed
@@ -388,7 +463,7 @@ def main():
                             call()
                 run()
                 torch.cuda.synchronize()
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0, e1 = events()
                 e0.record()
                 for _ in range(5):
                     run()
@@ -425,7 +500,7 @@ def main():
                 run_layer_t(L)
         gt.replay()
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0, e1 = events()
         e0.record()
         for _ in range(5):
             gt.replay()
@@ -450,7 +525,7 @@ def main():
             call = lambda: B.btc_assign(vec, N, v_, cbk, K_, zz, dd)
             call()
             torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0, e1 = events()
             e0.record()
             for _ in range(5):
                 call()
@@ -476,29 +551,56 @@ def main():
             assign[tag] = row
             del vec, zz, dd
 
-    # ---- CPU oracle on the host cores, bounded sample of the same workload
+    # ---- CPU oracle on the host cores, bounded sample of the same workload: whole passes over one matrix of
+    # each 13B shape with all cores, then the same with one thread, each split into its three stages
     cpu = None
     if not args.no_cpu:
         import oracle
         oracle.build()
-        threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        omp = ctypes.CDLL("libgomp.so.1")
+        all_threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
         for p in protos:
             p["packed_h"] = oracle.pack(p["layer"].idx, p["layer"].K)
-        t0 = time.time()
-        done_bytes, reps, cpu_s = 0, 0, 0.0
-        while time.time() - t0 < 10.0:
-            t1 = time.time()
+
+        def oracle_pass(split):
+            """One pass over one matrix of each 13B shape; the three stages timed one by one."""
             for p in protos:
                 lay = p["layer"]
-                oracle.linear(p["packed_h"], lay.codebook, lay.alpha, lay.mu, p["x_host"], lay.n_in, lay.v, lay.K)
-                done_bytes += gemv_bytes(p["s"], 1)
-            reps += 1
-            cpu_s = time.time() - t1
-        cpu_elapsed = time.time() - t0
-        cpu = dict(value=round(done_bytes / cpu_elapsed / 1e9, 4), unit="GB/s", cores=threads, kind="oracle",
-                   sample=f"{reps} pass(es) over one matrix of each 13B shape (unpack + materialise fp64 + multiply), "
-                          f"{cpu_elapsed:.1f} s; last pass {cpu_s:.2f} s")
+                t0 = time.perf_counter()
+                oracle.unpack(p["packed_h"], p["s"].nchunks, lay.K)
+                t1 = time.perf_counter()
+                W = oracle.materialise(p["packed_h"], lay.codebook, lay.alpha, lay.mu, lay.n_in, lay.v, lay.K)
+                t2 = time.perf_counter()
+                oracle.matmul(W, oracle.widen(np.atleast_2d(p["x_host"]), "f16"))
+                t3 = time.perf_counter()
+                split["unpack_s"] += t1 - t0
+                split["materialise_s"] += t2 - t1
+                split["multiply_s"] += t3 - t2
+            return sum(gemv_bytes(p["s"], 1) for p in protos)
 
+        def timed(threads, budget_s):
+            omp.omp_set_num_threads(threads)
+            split = dict(unpack_s=0.0, materialise_s=0.0, multiply_s=0.0)
+            t0, done, reps = time.perf_counter(), 0, 0
+            while time.perf_counter() - t0 < budget_s:
+                done += oracle_pass(split)
+                reps += 1
+            el = time.perf_counter() - t0
+            return dict(value=round(done / el / 1e9, 4), passes=reps, seconds=round(el, 1),
+                        split_s_per_pass={k: round(v / reps, 4) for k, v in split.items()})
+
+        many = timed(all_threads, 8.0)
+        one = timed(1, 8.0)
+        omp.omp_set_num_threads(all_threads)
+        cpu = dict(value=many["value"], unit="GB/s", cores=all_threads, kind="oracle",
+                   sample=f"{many['passes']} pass(es) over one matrix of each 13B shape (unpack, materialise fp64, "
+                          f"multiply; each stage timed by itself), {many['seconds']} s with {all_threads} threads; "
+                          f"then {one['passes']} pass(es) in {one['seconds']} s with one thread",
+                   split_s_per_pass=many["split_s_per_pass"],
+                   single_thread=dict(value=one["value"], unit="GB/s", cores=1,
+                                      split_s_per_pass=one["split_s_per_pass"]))
+
+    traffic = figures.get("traffic_bytes_per_step")
     out = {
         "metric": "btc_gemv effective weight GB/s (13B shapes, 0.8-bit, batch 1, cold)",
         "value": round(value, 1),
@@ -507,6 +609,7 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 5),
+        "ms_per_step_repeats": [round(m, 5) for m in ms_repeats],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -515,21 +618,25 @@ def main():
         "config": {"workload": "llama2-13b decoder-layer projections (4x5120x5120, 2x13824x5120, 1x5120x13824), "
                                "v=10 K=256 (0.8 bit), Zipf(1.1) indices, batch-1 GEMV, "
                                f"{args.layers} distinct weight copies ({total_weight_bytes / 1e9:.2f} GB) walked cold",
-                   "step": "one decoder layer = 7 btc_gemv calls", "launch": args.mode},
+                   "step": "one decoder layer = 7 btc_gemv calls", "launch": args.mode,
+                   "timed": f"{repeats} x {args.steps} steps"},
         "us_per_call": round(us_per_call, 3),
         "fp16_equivalent_GBps": round(fp16_equiv, 1),
+        "frac_measured_peak": round(value / HBM_MEASURED_GBS, 4),
         "per_shape": per_shape,
         "gemm": gemm,
         "other_decode_configs": other,
         "roofline": {"bound": "hbm", "achieved": round(value, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(value / HBM_PEAK_GBS, 4), "traffic": HBM_TRAFFIC_PER_STEP,
+                     "frac": round(value / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "note": "algorithmic bytes of the 7 calls of a step / event-timed duration of a step; "
-                             "traffic = HBM bytes per step (fetched + written) from the rocprofv3 counter runs "
-                             "summarised in profiles/gemv_13b_hbm_traffic.md, algorithmic bytes per step "
+                             "traffic = HBM bytes per step (fetched + written) read from "
+                             "profiles/gemv_13b_hbm_traffic.md (rocprofv3 counter runs), algorithmic bytes per step "
                              f"{step_bytes}"},
+        "roofline_gemv_70b": roof70,
         "roofline_gemm": None if gemm is None else {
             "bound": "mfma", "achieved": gemm[f"M{args.gemm_m}"]["layer_tflops"], "peak": MFMA_BF16_PEAK_TFLOPS,
-            "unit": "TFLOP/s", "frac": gemm[f"M{args.gemm_m}"]["frac_mfma_peak"], "traffic": None,
+            "unit": "TFLOP/s", "frac": gemm[f"M{args.gemm_m}"]["frac_mfma_peak"],
+            "frac_measured_peak": gemm[f"M{args.gemm_m}"]["frac_measured_peak"], "traffic": None,
             "note": f"2*M*out*in flop of the 7 projections at M={args.gemm_m} / event-timed btc_gemm calls "
                     "(whole calls)"},
         "transform": transform,

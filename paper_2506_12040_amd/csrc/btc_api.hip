@@ -59,6 +59,8 @@ size_t btc_workspace_bytes(const btc_shape* s, int32_t rows, int is_gemm) {
     need += (((size_t)rows * sizeof(float)) + 15) & ~(size_t)15;  // fp32 row sums of X
     // partial sums of a call that the tiled contraction kernel splits along k
     if (btc::gemm_tiled_covers(d, rows)) need = std::max(need, btc::gemm_tiled_workspace_bytes(d, rows));
+    // the sign matrix as bytes, for calls with many rows
+    if (btc::gemm_wide_covers(d, rows)) need = std::max(need, btc::gemm_wide_workspace_bytes(d, rows));
     if (btc::gemm_rows_covers(d, rows)) need = std::max(need, btc::gemm_rows_workspace_bytes(d, rows));
     if (rows > 64 && rows <= 128 && btc::gemm_rows_covers(d, 64)) {   // may run as 64 rows + the rest
       need = std::max(need, btc::gemm_rows_workspace_bytes(d, 64));

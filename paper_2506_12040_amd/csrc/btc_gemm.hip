@@ -111,6 +111,9 @@ btc_status btc_gemm(void* stream, const btc_shape* s, const uint32_t* packed, co
     }
     return BTC_OK;
   }
+  // many rows and enough output tiles to fill the chip: expand the signs once, stream both operands (if the caller's workspace holds the bytes)
+  if (gemm_wide_covers(d, M) && workspace && workspace_bytes >= gemm_wide_workspace_bytes(d, M))
+    return gemm_wide(q, d, packed, codebook, alpha, mu, X, is_bf16, M, Y, (int)y_dtype, workspace, workspace_bytes);
   if (gemm_tiled_covers(d, M))   // adds the activation rows up itself
     return gemm_tiled(q, d, packed, codebook, alpha, mu, X, is_bf16, M, Y, (int)y_dtype, workspace, workspace_bytes,
                       /*clear_workspace=*/0);

@@ -1,7 +1,7 @@
 // Tuned prefill product for chunk length 10:  Y[M][out] = X[M][in] . W_hat^T.
 //
 // At many activation rows the layer is a dense contraction, so the index
-// tiles are decoded into +-1 16-bit tiles in LDS (exact in bf16 and fp16) and
+// tiles are decoded into +-1 tiles in LDS (exact in bf16 and fp16) and
 // contracted on the matrix cores with fp32 accumulation; alpha and mu are
 // applied afterwards in fp32 (Algorithm "Binary Transformation and
 // Compression": W_hat = alpha * B_hat + mu).
@@ -9,17 +9,24 @@
 // Roles inside a workgroup (wave specialisation):
 //   * 4 contraction waves, stacked along M.  Wave w owns 64 activation rows
 //     and all BN = 32 NF weight rows of the workgroup: 2 x NF accumulators
-//     of MFMA 32x32x16.  Its A operand (activations) never touches LDS: lane
-//     (row, h) loads 16 consecutive elements straight from global memory and
-//     uses them as the k-slices {16h..16h+7} and {16h+8..16h+15} of a block of
-//     32 columns.  The B operand uses the same permutation of k inside the
-//     block, which costs nothing because it is only an LDS address.
-//   * 4 decoder waves.  A work item (row, half) turns 8 chunk indices of one
-//     weight row into 80 +-1 values of the next k-tile while the contraction
-//     waves work on the current one.  Decoding therefore overlaps the MFMAs
-//     in hardware (two waves per SIMD), and its cost is paid once per
-//     workgroup, not once per contraction wave.
-//   * one barrier per k-tile of 160 columns (16 chunks), two tile buffers.
+//     of MFMA 32x32x16.  Both operands come from LDS and nothing else: two
+//     16-byte reads (activations) and NF 8-byte reads (weights) per k-slice
+//     of 16, issued one slice ahead of the MFMAs that use them.  The loop of
+//     these waves holds no global load, so the in-order issue of the one
+//     contraction wave per SIMD never waits for memory.
+//   * 4 staging waves.  They copy the next k-tile of the activation block
+//     (256 rows x 80 columns; coalesced 16-byte loads, ten lanes per row,
+//     requested two tiles ahead) into LDS, and decode the next k-tile of the
+//     weights: a work item turns 4 chunk indices of one weight row into 40
+//     bytes, one byte per weight -- the HIGH byte of +-1.0 in the operand's
+//     format.  A contraction wave widens 8 such bytes to an MFMA operand
+//     with four byte permutes.  One byte per weight halves the LDS space and
+//     traffic of the weight tile, which is what lets the whole activation
+//     tile live in LDS next to it.
+//   * one barrier per k-tile of 80 columns (8 chunks), two tile buffers.  A
+//     contraction wave reaches the barrier with the operands of the tile's
+//     last k-slice already in registers, reads the first slice of the next
+//     tile right after it and only then issues the last slice's MFMAs.
 //
 // Workgroups are numbered so that all workgroups of one block of activation
 // rows land on the same XCD: its 4 MB L2 then keeps that block of X resident
@@ -39,15 +46,18 @@ typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr int kV = 10;                  // chunk length this kernel is built for
-constexpr int kCH = 16;                 // chunks per k-tile
-constexpr int kKT = kV * kCH;           // 160 columns per k-tile = 5 blocks of 32
-constexpr int kRS = kKT + 8;            // LDS row stride in elements: 336 B, an odd multiple of 16 B
+constexpr int kCH = 8;                  // chunks per k-tile
+constexpr int kKT = kV * kCH;           // 80 columns per k-tile = 5 k-slices of 16
+constexpr int kNS = kKT / 16;           // k-slices per tile
+constexpr int kXRS = 2 * kKT + 16;      // bytes per staged activation row: an odd multiple of 16
+constexpr int kWRS = kKT + 8;           // bytes per decoded weight row: an odd multiple of 8
 constexpr int kBM = 256;                // activation rows per workgroup
+constexpr int kXT = kBM * kXRS;         // bytes of one activation tile buffer
 constexpr int kMW = 4;                  // contraction waves
-constexpr int kDW = 4;                  // decoder waves (8 waves per workgroup: 2 per SIMD, 256 registers each)
+constexpr int kDW = 4;                  // staging waves (8 waves per workgroup: 2 per SIMD, 256 registers each)
+constexpr int kXL = 11;                 // activation loads per staging thread and tile (the last one partial)
 constexpr uint32_t kOob = 0x80000000u;  // buffer offset that is always out of range
 constexpr int kRsrcFlags = 0x00020000;
-constexpr int kAStage = 2 * 32 * 64;     // bytes of a contraction wave's private activation slots in LDS
 
 template <bool BF16>
 __device__ __forceinline__ f32x16 mfma32(const uint4& a, const uint4& b, const f32x16& c) {
@@ -88,6 +98,17 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// 8 weight bytes (the high bytes of +-1.0) -> 8 16-bit operand elements; `low` holds the
+// low byte of 1.0 in the operand's format (0x80 for bf16, 0x00 for fp16) in its byte 0.
+__device__ __forceinline__ uint4 widen_weights(const uint2& raw, uint32_t low) {
+  uint4 r;
+  r.x = __builtin_amdgcn_perm(raw.x, low, 0x05000400u);
+  r.y = __builtin_amdgcn_perm(raw.x, low, 0x07000600u);
+  r.z = __builtin_amdgcn_perm(raw.y, low, 0x05000400u);
+  r.w = __builtin_amdgcn_perm(raw.y, low, 0x07000600u);
+  return r;
+}
+
 template <int NF, bool BF16>
 __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
     Dims d, const uint32_t* __restrict__ packed, const uint32_t* __restrict__ codebook,
@@ -95,9 +116,11 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
     void* __restrict__ Y, int y_dtype, int m_blocks, int n_blocks, int tiles_per_split, float* __restrict__ part,
     float* __restrict__ rpart) {
   constexpr int BN = 32 * NF;
+  constexpr int kWT = BN * kWRS;                         // bytes of one weight tile buffer
   extern __shared__ __align__(16) unsigned char smem[];
-  uint16_t* S = (uint16_t*)smem;                         // [2][BN][kRS]
-  uint32_t* E = (uint32_t*)(S + 2 * BN * kRS);           // [2^b][8]: codeword -> 5 dwords of +-1 pairs
+  // LDS: activation tiles [2][256][kXRS] at 0, weight tiles [2][BN][kWRS], codeword table [2^b][32 bytes]
+  unsigned char* const WT = smem + 2 * kXT;
+  unsigned char* const E = WT + 2 * kWT;
 
   // ---- workgroup -> (m block, n block); consecutive ids go to consecutive XCDs
   int mb, nb, sp;                                       // activation-row block, weight-row block, k split
@@ -123,107 +146,177 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
   // this workgroup's share of the k-tiles (the host makes every split non-empty)
   const int t_begin = sp * tiles_per_split;
   const int nt = min(ntiles, t_begin + tiles_per_split) - t_begin;
+  const int k_lim = min(d.in, (t_begin + nt) * kKT);     // columns of this workgroup's share end here
 
-  // Codeword table: built by all threads, but only after each role has put its first global
-  // loads in flight (the table needs a round trip of its own for the codebook).
+  // Codeword table, built by all threads after each role has put its first global loads in
+  // flight (the table needs a round trip of its own for the codebook).  An entry holds the ten
+  // weight bytes of a codeword twice: at byte 0 for a chunk that starts on a dword of its row
+  // (even position in its pair), and at byte 18 (i.e. shifted by two bytes in the second
+  // 16-byte half) for the chunk behind it, so that a pair of chunks is put together from
+  // whole dwords: {e0, e1, e2 | o0, o1, o2}.
   auto build_table = [&]() {
-    const uint32_t one2 = BF16 ? 0x3F803F80u : 0x3C003C00u;
+    const uint32_t hi = BF16 ? 0x3Fu : 0x3Cu;
     for (int k = tid; k < (1 << d.b); k += (kMW + kDW) * 64) {
       const uint32_t npat = ~codebook[k];
-      uint32_t e[5];
+      uint32_t by[10];
 #pragma unroll
-      for (int p = 0; p < 5; ++p)
-        e[p] = one2 | ((npat << (15 - 2 * p)) & 0x8000u) | ((npat << (30 - 2 * p)) & 0x80000000u);
-      *(uint4*)(E + 8 * k) = make_uint4(e[0], e[1], e[2], e[3]);
-      E[8 * k + 4] = e[4];
+      for (int t = 0; t < 10; ++t) by[t] = hi | (((npat >> t) & 1u) << 7);
+      uint4 ev, od;
+      ev.x = by[0] | (by[1] << 8) | (by[2] << 16) | (by[3] << 24);
+      ev.y = by[4] | (by[5] << 8) | (by[6] << 16) | (by[7] << 24);
+      ev.z = by[8] | (by[9] << 8);
+      ev.w = 0u;
+      od.x = (by[0] << 16) | (by[1] << 24);
+      od.y = by[2] | (by[3] << 8) | (by[4] << 16) | (by[5] << 24);
+      od.z = by[6] | (by[7] << 8) | (by[8] << 16) | (by[9] << 24);
+      od.w = 0u;
+      *(uint4*)(E + 32 * k) = ev;
+      *(uint4*)(E + 32 * k + 16) = od;
     }
     __syncthreads();
   };
 
   if (wave >= kMW) {
-    // =============================== decoder waves ===============================
+    // =============================== staging waves ===============================
+    // No branch below depends on the lane (threads without work of their own repeat a
+    // neighbour's, writing the same values to the same place), and every stage issues the same
+    // loads (those beyond the share return zeros): the number of loads in flight is a
+    // compile-time fact, so a stage waits for its own tile only, not for the younger requests.
     const int did = tid - kMW * 64;                      // 0 .. 255
-    // Work items (weight row r, half): 8 chunks = 80 values each, 64 NF items per tile;
-    // a thread owns items did and did + 256 (the second one only if it exists).
-    constexpr int NI = (2 * BN + kDW * 64 - 1) / (kDW * 64);
-    const uint32_t pk_bytes = (uint32_t)d.out * (uint32_t)d.wpr * 4u;
-    const __amdgpu_buffer_rsrc_t rP = __builtin_amdgcn_make_buffer_rsrc((void*)packed, 0, (int)pk_bytes, kRsrcFlags);
-    uint32_t W[NI][4];
-    const bool pair_loads = d.b == 8 && (d.wpr & 1) == 0;   // two-word loads stay 8-byte aligned
-    // the 8 b-bit fields of an item start at bit (t*16 + half*8) * b of the row: at most 4 words
-    auto fetch = [&](int t) {
+    // ---- activations: thread (row0, piece) copies piece `piece` (16 bytes) of the rows
+    // row0 + 25 i of the tile, i = 0..10 (the last round covers rows 250..255 only)
+    const __amdgpu_buffer_rsrc_t rX =
+        __builtin_amdgcn_make_buffer_rsrc((void*)X, 0, (int)((long long)M * d.in * 2), kRsrcFlags);
+    const int xt = min(did, 249);
+    const int xrow0 = xt / 10, xpiece = xt - 10 * xrow0;
+    // Rows m >= M need no test of their own: X is row-major, so they lie past the end of the
+    // buffer and the hardware range check returns zeros for them.
+    uint32_t xv[kXL];                                    // byte offset of this thread's piece in round i, tile 0
+    uint32_t xl[kXL];                                    // and where it goes in a tile buffer
 #pragma unroll
-      for (int it = 0; it < NI; ++it) {
-        const int item = did + it * kDW * 64;
-        const int r = item >> 1, half = item & 1;
-        const int n = n0 + r;
-        const int w0 = ((t * kCH + half * 8) * d.b) >> 5;
-        const bool ok = item < 2 * BN && n < d.out;
-        if (pair_loads) {
-          // 8-bit indices: the 8 fields of an item are exactly two words, fetched by one load.
-          // (Every lane access costs the L1 a cycle, and the L1 access rate bounds this kernel.)
-          const uint32_t off = (ok && w0 + 1 < d.wpr) ? ((uint32_t)n * (uint32_t)d.wpr + (uint32_t)w0) * 4u : kOob;
-          const uint2 w2 = __builtin_bit_cast(uint2, __builtin_amdgcn_raw_buffer_load_b64(rP, off, 0, 0));
-          W[it][0] = w2.x; W[it][1] = w2.y; W[it][2] = 0u; W[it][3] = 0u;
-        } else {
+    for (int i = 0; i < kXL; ++i) {
+      const int row = min(xrow0 + 25 * i, kBM - 1);
+      xv[i] = (uint32_t)(((long long)(m0 + row) * d.in + 8 * xpiece) * 2);
+      xl[i] = (uint32_t)(row * kXRS + xpiece * 16);
+    }
+    uint4 XS[3][kXL];                                    // three tiles in flight
+    auto load_x = [&](uint4 (&dst)[kXL], int t) {
+      if ((t + 1) * kKT <= k_lim) {                      // the whole tile lies inside the share: scalar column offset
 #pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            const uint32_t off = (ok && w0 + u < d.wpr) ? ((uint32_t)n * (uint32_t)d.wpr + (uint32_t)(w0 + u)) * 4u : kOob;
-            W[it][u] = __builtin_amdgcn_raw_buffer_load_b32(rP, off, 0, 0);
-          }
-        }
+        for (int i = 0; i < kXL; ++i)
+          dst[i] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rX, xv[i], t * kKT * 2, 0));
+      } else {
+        // `in` is a multiple of 16 for this kernel, so a piece lies wholly inside or outside the
+        // row (or this workgroup's share of it); outside, bit 31 of the offset is set
+        const uint32_t past = (uint32_t)(t * kKT + 8 * xpiece + 8 > k_lim) << 31;
+#pragma unroll
+        for (int i = 0; i < kXL; ++i)
+          dst[i] = __builtin_bit_cast(
+              uint4, __builtin_amdgcn_raw_buffer_load_b128(rX, (xv[i] + (uint32_t)(t * kKT) * 2u) | past, 0, 0));
       }
     };
-    fetch(t_begin);
-    build_table();
-    for (int lt = 0; lt <= nt; ++lt) {
-      const int t = t_begin + lt;
-      if (lt < nt) {
-        uint32_t A[NI][3];
+    auto store_x = [&](const uint4 (&src)[kXL], int buf) {
 #pragma unroll
-        for (int it = 0; it < NI; ++it) {                // align the window to the first field
-          const int half = (did + it * kDW * 64) & 1;
-          const uint32_t s0 = (uint32_t)((t * kCH + half * 8) * d.b) & 31u;
+      for (int i = 0; i < kXL; ++i) *(uint4*)(smem + buf * kXT + xl[i]) = src[i];
+    };
+    // ---- weights: a thread owns 4 chunks (a half of the 8 chunks a row has in a tile) of one of the
+    // first 128 weight rows, and -- with 160 rows per workgroup -- threads 0..127 also own 2 chunks (a
+    // quarter) of one of the rows 128..159.  The b-bit fields of either lie inside two words of
+    // the row for every b <= 10, since they start at a multiple of 2 b bits.
+    constexpr bool kQ = BN > 128;
+    const uint32_t pk_bytes = (uint32_t)d.out * (uint32_t)d.wpr * 4u;
+    const __amdgpu_buffer_rsrc_t rP = __builtin_amdgcn_make_buffer_rsrc((void*)packed, 0, (int)pk_bytes, kRsrcFlags);
+    const bool has_h = (did & ~63) < 2 * min(BN, 128);   // wave-uniform
+    const bool has_q = kQ && did < 128;                  // wave-uniform
+    const int hr = min(did >> 1, BN - 1), hh = did & 1;
+    const int qr = 128 + ((did & 127) >> 2), qq = did & 3;
+    // rows past the end of the matrix start past the end of the buffer: zeros, i.e. index 0
+    const uint32_t h_row = (uint32_t)(n0 + hr) * (uint32_t)d.wpr * 4u, h_bit = (uint32_t)(hh * 4 * d.b);
+    const uint32_t q_row = (uint32_t)(n0 + qr) * (uint32_t)d.wpr * 4u, q_bit = (uint32_t)(qq * 2 * d.b);
+    unsigned char* const h_dst = WT + hr * kWRS + hh * 40;
+    unsigned char* const q_dst = WT + qr * kWRS + qq * 20;
+    uint32_t IW[3][4];                                   // index words (half item: 0, 1; quarter item: 2, 3), three tiles in flight
+    auto fetch = [&](uint32_t (&dst)[4], int t) {
+      const uint32_t tb = (uint32_t)(t * kCH * d.b);
+      if (has_h) {
+        const uint32_t off = h_row + (((tb + h_bit) >> 5) << 2);
+        dst[0] = __builtin_amdgcn_raw_buffer_load_b32(rP, off, 0, 0);
+        dst[1] = __builtin_amdgcn_raw_buffer_load_b32(rP, off + 4u, 0, 0);
+      }
+      if (has_q) {
+        const uint32_t off = q_row + (((tb + q_bit) >> 5) << 2);
+        dst[2] = __builtin_amdgcn_raw_buffer_load_b32(rP, off, 0, 0);
+        dst[3] = __builtin_amdgcn_raw_buffer_load_b32(rP, off + 4u, 0, 0);
+      }
+    };
+    const uint32_t mask = (1u << d.b) - 1u;
+    auto decode = [&](const uint32_t (&src)[4], int t, int buf) {
+      const uint32_t tb = (uint32_t)(t * kCH * d.b);
+      uint4 e[4], f[2];
+      if (has_h) {
+        const uint32_t sh = (tb + h_bit) & 31u;
+        const uint32_t lo = __builtin_amdgcn_alignbit(src[1], src[0], sh);
+        const uint32_t hi = src[1] >> sh;
 #pragma unroll
-          for (int u = 0; u < 3; ++u) A[it][u] = __builtin_amdgcn_alignbit(W[it][u + 1], W[it][u], s0);
-        }
-        if (lt + 1 < nt) fetch(t + 1);                   // next tile's words fly while this one is expanded
-#pragma unroll
-        for (int it = 0; it < NI; ++it) {
-          const int item = did + it * kDW * 64;
-          if (item < 2 * BN) {
-            const int r = item >> 1, half = item & 1;
-            const bool row_ok = n0 + r < d.out;
-            uint16_t* dst = S + (lt & 1) * (BN * kRS) + r * kRS + half * (8 * kV);
-            const int j0 = t * kCH + half * 8;
-            const uint32_t mask = (1u << d.b) - 1u;
-#pragma unroll
-            for (int cs = 0; cs < 8; ++cs) {
-              // The lanes of a wave walk their 8 chunks in different rotations: with a common
-              // order all rows would hit the same 8 LDS banks (the row stride is a multiple of
-              // 16 bytes), rotated they spread over all of them.
-              const int c = (cs + r + (r >> 3)) & 7;
-              // field c sits at bit c*b of the aligned window (b <= 10: inside 3 words)
-              const uint32_t pos = (uint32_t)(c * d.b);
-              const uint32_t wlo = pos < 32 ? A[it][0] : (pos < 64 ? A[it][1] : A[it][2]);
-              const uint32_t whi = pos < 32 ? A[it][1] : A[it][2];
-              const uint32_t code = __builtin_amdgcn_alignbit(whi, wlo, pos & 31u) & mask;
-              const bool ok = row_ok && j0 + c < d.nchunks;
-              const uint4 e4 = *(const uint4*)(E + 8 * code);
-              const uint32_t e5 = E[8 * code + 4];
-              uint32_t w[5] = {e4.x, e4.y, e4.z, e4.w, e5};
-              if (!ok) {                                 // beyond the matrix: zeros (rare, edge tiles only)
-#pragma unroll
-                for (int p = 0; p < 5; ++p) w[p] = 0u;
-              }
-              uint32_t* o = (uint32_t*)(dst + c * kV);   // 20-byte chunks: 4-byte aligned
-#pragma unroll
-              for (int p = 0; p < 5; ++p) o[p] = w[p];
-            }
-          }
+        for (int c = 0; c < 4; ++c) {
+          const uint32_t code = __builtin_amdgcn_alignbit(hi, lo, (uint32_t)(c * d.b)) & mask;
+          e[c] = *(const uint4*)(E + 32 * code + 16 * (c & 1));
         }
       }
-      __syncthreads();                                   // tile t is complete; tile t-1 has been consumed
+      if (has_q) {
+        const uint32_t sh = (tb + q_bit) & 31u;
+        const uint32_t lo = __builtin_amdgcn_alignbit(src[3], src[2], sh);
+        f[0] = *(const uint4*)(E + 32 * (lo & mask));
+        f[1] = *(const uint4*)(E + 32 * ((lo >> d.b) & mask) + 16);
+      }
+      if (has_h) {
+        uint2* dst = (uint2*)(h_dst + buf * kWT);
+        dst[0] = make_uint2(e[0].x, e[0].y);
+        dst[1] = make_uint2(e[0].z | e[1].x, e[1].y);
+        dst[2] = make_uint2(e[1].z, e[2].x);
+        dst[3] = make_uint2(e[2].y, e[2].z | e[3].x);
+        dst[4] = make_uint2(e[3].y, e[3].z);
+      }
+      if (has_q) {
+        uint32_t* dst = (uint32_t*)(q_dst + buf * kWT);
+        dst[0] = f[0].x;
+        dst[1] = f[0].y;
+        dst[2] = f[0].z | f[1].x;
+        dst[3] = f[1].y;
+        dst[4] = f[1].z;
+      }
+    };
+#pragma unroll
+    for (int g = 0; g < 3; ++g) {                        // (beyond the share: out-of-range offsets, zeros)
+      fetch(IW[g], t_begin + g);
+      load_x(XS[g], t_begin + g);
+    }
+    build_table();
+    // Tile lt goes to tile buffer lt % 2 between the barrier that ends tile lt - 2 and the one
+    // that starts tile lt; its loads were requested three tiles earlier into register set lt % 3.
+    auto stage = [&](int lt, auto variant) {
+      constexpr int P2 = decltype(variant)::value % 2, P3 = decltype(variant)::value % 3;
+      store_x(XS[P3], P2);
+      decode(IW[P3], t_begin + lt, P2);
+      fetch(IW[P3], t_begin + lt + 3);
+      load_x(XS[P3], t_begin + lt + 3);
+      __syncthreads();
+    };
+    // nt + 1 barriers in all; the last stage writes a tile that nobody reads into the buffers
+    // whose tile (nt - 2) has been consumed
+    for (int lt = 0;; lt += 6) {
+      stage(lt, std::integral_constant<int, 0>{});
+      if (lt + 1 > nt) break;
+      stage(lt + 1, std::integral_constant<int, 1>{});
+      if (lt + 2 > nt) break;
+      stage(lt + 2, std::integral_constant<int, 2>{});
+      if (lt + 3 > nt) break;
+      stage(lt + 3, std::integral_constant<int, 3>{});
+      if (lt + 4 > nt) break;
+      stage(lt + 4, std::integral_constant<int, 4>{});
+      if (lt + 5 > nt) break;
+      stage(lt + 5, std::integral_constant<int, 5>{});
+      if (lt + 6 > nt) break;
     }
     return;
   }
@@ -245,142 +338,74 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[a][c][e] = 0.f;
 
-  // A operand (activations), 64 rows per wave in two fragments of 32.
-  // An MFMA lane holds 8 consecutive elements of ONE row, so loading the operand straight from
-  // memory makes every lane touch a cache line of its own, and the vector L1 -- about one lane
-  // access per cycle -- is what bounds this kernel.  Passing everything through LDS instead
-  // trades that for LDS waits of the single contraction wave per SIMD.  So the load is split:
-  //   fragment 0 (rows 0..31): lane (row l32, h) reads X[m][k0 + 16 h .. + 15] straight into
-  //     registers, three blocks of 32 columns in flight;
-  //   fragment 1 (rows 32..63): fetched coalesced -- four consecutive lanes read the 64 bytes a
-  //     row has in a block -- parked in a wave-private LDS slot and read back in MFMA layout.
-  //     Only this wave touches the slot, so no barrier is involved (LDS operations of a wave
-  //     complete in order).  The four 16-byte pieces of a row are stored at position
-  //     piece ^ ((row / 2) % 4): the read-back of 8 consecutive rows then hits 8 bank groups.
-  const __amdgpu_buffer_rsrc_t rX =
-      __builtin_amdgcn_make_buffer_rsrc((void*)X, 0, (int)((long long)M * d.in * 2), kRsrcFlags);
-  // Rows m >= M need no test of their own: X is row-major, so they lie past the end of the
-  // buffer and the hardware range check returns zeros for them.
-  const uint32_t xoff0 = (uint32_t)(((long long)(m0 + wave * 64 + l32) * d.in + 16 * h) * 2);
-  const int k_lim = min(d.in, (t_begin + nt) * kKT);     // columns of this workgroup's share end here
-  auto load_direct = [&](uint4 (&dst)[2], int k0) {      // k0: first column of a block of 32
-    // `in` is a multiple of 16 for this kernel; past the end of the row (or of this workgroup's share of
-    // it: those blocks are requested by the pipeline but never used) bit 31 of the offset is set
-    const uint32_t past = (uint32_t)(k0 + 16 * h + 16 > k_lim) << 31;
-    const uint32_t off = (xoff0 + (uint32_t)k0 * 2u) | past;
-    dst[0] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rX, off, 0, 0));
-    dst[1] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rX, off + 16u, 0, 0));
-  };
-  unsigned char* AS = smem + 2 * BN * kRS * 2 + ((size_t)32 << d.b) + wave * kAStage;   // [2][32 rows][64 B]
-  const int lrow = lane >> 2, lq = lane & 3;
-  const int lpiece = lq ^ ((lrow >> 1) & 3);             // the piece this lane fetches (parked at position lq)
-  const uint32_t goff0 = (uint32_t)(((long long)(m0 + wave * 64 + 32 + lrow) * d.in + 8 * lpiece) * 2);
-  const uint32_t gstep = (uint32_t)(16LL * d.in * 2);    // load j covers rows 32 + 16 j + lane / 4
-  auto load_stage = [&](uint4 (&dst)[2], int k0) {
-    const uint32_t past = (uint32_t)(k0 + 8 * lpiece + 8 > k_lim) << 31;
+  // Operand addresses: lane (l32, h) holds elements 8 h .. 8 h + 7 of a k-slice of 16, of
+  // activation row l32 of a fragment (A) and of weight row l32 of a block of 32 (B).
+  const unsigned char* const a_lane = smem + (wave * 64 + l32) * kXRS + h * 16;
+  const unsigned char* const b_lane = WT + l32 * kWRS + h * 8;
+  const uint32_t low = BF16 ? 0x80u : 0x00u;
+  uint4 afr[2][2];                                       // [register set][fragment]
+  uint2 bfr[2][NF];                                      // [register set][weight block]
+  float rsum[2] = {0.f, 0.f};                            // rows l32 and 32 + l32, this lane's half of the columns
+  auto read_slice = [&](int set, int buf, int s) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const uint32_t off = (goff0 + (uint32_t)j * gstep + (uint32_t)k0 * 2u) | past;
-      dst[j] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rX, off, 0, 0));
-    }
-  };
-  auto park = [&](int slot, const uint4 (&src)[2]) {
+    for (int a = 0; a < 2; ++a) afr[set][a] = *(const uint4*)(a_lane + buf * kXT + a * 32 * kXRS + s * 32);
 #pragma unroll
-    for (int j = 0; j < 2; ++j) *(uint4*)(AS + slot * 2048 + j * 1024 + lane * 16) = src[j];
+    for (int c = 0; c < NF; ++c) bfr[set][c] = *(const uint2*)(b_lane + buf * kWT + c * 32 * kWRS + s * 16);
   };
-  const int rsw = (l32 >> 1) & 3;
-  const unsigned char* ard0 = AS + l32 * 64 + 16 * ((2 * h) ^ rsw);       // k-slice 0: elements 16 h .. + 7
-  const unsigned char* ard1 = AS + l32 * 64 + 16 * ((2 * h + 1) ^ rsw);   // k-slice 1: elements 16 h + 8 .. + 15
-
-  // Software pipeline.  Fragment 0: kAS register slots, a block is requested kAS - 1 blocks
-  // before its use (a third slot does not fit the 256 registers next to 160 accumulators and
-  // measured no faster when it did).  Fragment 1: two register stages in
-  // flight from memory (requested three blocks ahead), two LDS slots (the block in use and the
-  // next), two fragment registers (the k-slice in use and the next).  Pattern fragments: one
-  // register set; fragment c of the next k-slice is read from LDS right after the two MFMAs
-  // that use fragment c of the current slice have been issued.  Slots are compile-time: a tile
-  // has 5 blocks, so register slot, LDS slot, stage and tile buffer all follow the parity of the
-  // tile's first block: 2 tile bodies.
-  constexpr int NB = kKT / 32;                           // blocks per k-tile
-  constexpr int kAS = 2;
-  uint4 ad[kAS][2];                                      // fragment 0: [slot][k-slice]
-  uint4 stg[2][2];                                       // fragment 1: [stage][load]
-  uint4 afr[2];                                          // fragment 1: [k-slice]
-  uint4 bfr[NF];
-  float rsum0 = 0.f;                                     // row l32, this lane's half of the columns
-  float rs2[2] = {0.f, 0.f};                             // row 32 + 16 j + lane / 4, this lane's piece
-  const int kb = t_begin * kKT;                          // first column of this workgroup's share
-#pragma unroll
-  for (int i = 0; i < kAS; ++i) load_direct(ad[i], kb + 32 * i);
-  load_stage(stg[0], kb);
-  load_stage(stg[1], kb + 32);
   build_table();
-  auto add_rows2 = [&](const uint4 (&src)[2]) {
+  __syncthreads();                                       // tile 0 staged
+  read_slice(0, 0, 0);
+  // A tile body: 5 k-slices; register sets alternate per slice, and since a tile has an odd
+  // number of slices the set of its first slice follows the tile's parity, like its buffer.
+  uint4 bw[2];                                           // widened weights, two sets in turn
+  auto tile = [&](bool has_next, auto parity) {
+    constexpr int P = decltype(parity)::value;
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      rs2[j] = pair_sum<BF16>(src[j].x, rs2[j]);
-      rs2[j] = pair_sum<BF16>(src[j].y, rs2[j]);
-      rs2[j] = pair_sum<BF16>(src[j].z, rs2[j]);
-      rs2[j] = pair_sum<BF16>(src[j].w, rs2[j]);
-    }
-  };
-  park(0, stg[0]);
-  add_rows2(stg[0]);
-  load_stage(stg[0], kb + 64);
-  afr[0] = *(const uint4*)ard0;
-  __syncthreads();                                       // tile 0 decoded
-  const uint16_t* sbase = S + l32 * kRS + 16 * h;
-  auto tile = [&](int t, auto variant) {
-    constexpr int PAR = decltype(variant)::value & 1;    // tile buffer; parity of the tile's first block
-    constexpr int PH = decltype(variant)::value % kAS;   // phase of the register-slot pattern
-    const uint16_t* st = sbase + PAR * (BN * kRS);
-#pragma unroll
-    for (int c = 0; c < NF; ++c) bfr[c] = *(const uint4*)(st + c * 32 * kRS);
-#pragma unroll
-    for (int T = 0; T < NB; ++T) {
-      constexpr int dummy = 0;
-      (void)dummy;
-      const int aslot = (NB * PH + T) % kAS;
-      const int bp = (PAR + T) & 1;                      // parity of this block
-      // Fragment 1 of the NEXT block moves from its register stage to the other LDS slot and
-      // the stage is refilled with the block three further on.  The scheduler must not move
-      // this (or the refills below) to the top of the tile: it would wait there for loads that
-      // are meant to stay in flight.
+    for (int s = 0; s < kNS; ++s) {
+      const int set = (P + s) & 1;
       __builtin_amdgcn_sched_barrier(0);
-      park(bp ^ 1, stg[bp ^ 1]);
-      add_rows2(stg[bp ^ 1]);                            // (zeros beyond this workgroup's share)
-      load_stage(stg[bp ^ 1], t * kKT + (T + 3) * 32);
+      if (s + 1 < kNS) {
+        read_slice(set ^ 1, P, s + 1);
+      } else {
+        __syncthreads();                                 // this tile is in registers; the next one is staged
+        if (has_next) read_slice(set ^ 1, P ^ 1, 0);
+      }
       __builtin_amdgcn_sched_barrier(0);
+      if (s == 0) bw[0] = widen_weights(bfr[set][0], low);
 #pragma unroll
-      for (int s = 0; s < 2; ++s) {
-        const int q = 2 * T + s;                         // slice number inside the tile
-        if (s == 0) afr[1] = *(const uint4*)(ard1 + bp * 2048);          // next slice: same block
-        else afr[0] = *(const uint4*)(ard0 + (bp ^ 1) * 2048);           //   first slice of the next block
-#pragma unroll
-        for (int c = 0; c < NF; ++c) {
-          acc[0][c] = mfma32<BF16>(ad[aslot][s], bfr[c], acc[0][c]);
-          acc[1][c] = mfma32<BF16>(afr[s], bfr[c], acc[1][c]);
-          if (q + 1 < 2 * NB) bfr[c] = *(const uint4*)(st + c * 32 * kRS + ((q + 1) >> 1) * 32 + 8 * ((q + 1) & 1));
+      for (int c = 0; c < NF; ++c) {
+        // order pinned: the permutes for the next block and the row-sum steps are issued in the
+        // shadow of this block's two MFMAs and write registers no MFMA in flight reads
+        __builtin_amdgcn_sched_barrier(0);
+        const int g = s * NF + c;                        // blocks alternate between the two widened sets
+        acc[0][c] = mfma32<BF16>(afr[set][0], bw[g & 1], acc[0][c]);
+        __builtin_amdgcn_sched_barrier(0);
+        if (c + 1 < NF) bw[(g + 1) & 1] = widen_weights(bfr[set][c + 1], low);
+        else if (s + 1 < kNS) bw[(g + 1) & 1] = widen_weights(bfr[set ^ 1][0], low);
+        __builtin_amdgcn_sched_barrier(0);
+        acc[1][c] = mfma32<BF16>(afr[set][1], bw[g & 1], acc[1][c]);
+        __builtin_amdgcn_sched_barrier(0);
+        if (c < 4) {
+          const uint32_t w0 = c == 0 ? afr[set][0].x : c == 1 ? afr[set][0].y : c == 2 ? afr[set][0].z : afr[set][0].w;
+          const uint32_t w1 = c == 0 ? afr[set][1].x : c == 1 ? afr[set][1].y : c == 2 ? afr[set][1].z : afr[set][1].w;
+          rsum[0] = pair_sum<BF16>(w0, rsum[0]);
+          rsum[1] = pair_sum<BF16>(w1, rsum[1]);
         }
       }
-      // row sums of fragment 0 from the block just used, then its slot is refilled
-      __builtin_amdgcn_sched_barrier(0);
+      if (NF < 4) {                                      // the row-sum steps that found no block to hide behind
 #pragma unroll
-      for (int s = 0; s < 2; ++s) {
-        rsum0 = pair_sum<BF16>(ad[aslot][s].x, rsum0);
-        rsum0 = pair_sum<BF16>(ad[aslot][s].y, rsum0);
-        rsum0 = pair_sum<BF16>(ad[aslot][s].z, rsum0);
-        rsum0 = pair_sum<BF16>(ad[aslot][s].w, rsum0);
+        for (int c = NF; c < 4; ++c) {
+          const uint32_t w0 = c == 2 ? afr[set][0].z : afr[set][0].w;
+          const uint32_t w1 = c == 2 ? afr[set][1].z : afr[set][1].w;
+          rsum[0] = pair_sum<BF16>(w0, rsum[0]);
+          rsum[1] = pair_sum<BF16>(w1, rsum[1]);
+        }
       }
-      load_direct(ad[aslot], t * kKT + (T + kAS) * 32);  // kAS blocks ahead (zeros past the end)
-      __builtin_amdgcn_sched_barrier(0);
     }
-    __syncthreads();                                     // tile t consumed; tile t+1 decoded
   };
-  for (int lt = 0; lt < nt; lt += 2) {                   // the tile body's variant follows the local tile number
-    const int t = t_begin + lt;
-    tile(t, std::integral_constant<int, 0>{});
-    if (lt + 1 < nt) tile(t + 1, std::integral_constant<int, 1>{});
+  for (int lt = 0; lt < nt; lt += 2) {
+    tile(lt + 1 < nt, std::integral_constant<int, 0>{});
+    if (lt + 1 < nt) tile(lt + 2 < nt, std::integral_constant<int, 1>{});
   }
 
   // ---- epilogue.  After the last barrier the tile buffers are free; each wave uses a part of
@@ -404,25 +429,14 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
     al[c] = split ? 1.f : (n < d.out ? alpha[n] : 0.f);
     mn[c] = split ? 0.f : (n < d.out ? mu[n] : 0.f);
   }
-  // row sums: the lanes that shared a row add up (two halves of fragment 0, four pieces of
-  // fragment 1), then every lane picks up the 32 sums it needs
-  rsum0 += __shfl_xor(rsum0, 32, 64);
+  // row sums: the two lanes that shared a row add up, then every lane picks up the 32 sums it needs
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    rs2[j] += __shfl_xor(rs2[j], 1, 64);
-    rs2[j] += __shfl_xor(rs2[j], 2, 64);
-  }
-  if (h == 0) {
-    rsb[l32] = rsum0;
-    const int m = m0 + wave * 64 + l32;
-    if (split && m < M) rpart[((size_t)sp * n_blocks + nb) * M + m] = rsum0;
-  }
-  if (lq == 0) {
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      rsb[32 + 16 * j + lrow] = rs2[j];
-      const int m = m0 + wave * 64 + 32 + 16 * j + lrow;
-      if (split && m < M) rpart[((size_t)sp * n_blocks + nb) * M + m] = rs2[j];
+  for (int a = 0; a < 2; ++a) {
+    rsum[a] += __shfl_xor(rsum[a], 32, 64);
+    if (h == 0) {
+      rsb[32 * a + l32] = rsum[a];
+      const int m = m0 + wave * 64 + 32 * a + l32;
+      if (split && m < M) rpart[((size_t)sp * n_blocks + nb) * M + m] = rsum[a];
     }
   }
   wave_lds_sync();
@@ -484,7 +498,7 @@ __global__ __launch_bounds__((kMW + kDW) * 64) void gemm_tiled_kernel(
 }
 
 template <int NF>
-static size_t lds_bytes(int b) { return (size_t)2 * 32 * NF * kRS * 2 + ((size_t)32 << b) + kMW * kAStage; }
+static size_t lds_bytes(int b) { return (size_t)2 * kXT + (size_t)2 * 32 * NF * kWRS + ((size_t)32 << b); }
 
 // Second pass of a k-split call:  Y = alpha * (sum of the splits' raw sums) + mu * (sum of their
 // activation row sums), in split order.  One small workgroup per (weight-row block, activation
@@ -553,9 +567,10 @@ struct Plan {
 
 // Tile width and k split.  A workgroup occupies a compute unit, so the kernel lasts about
 //   rounds x (k-tiles per workgroup) x (time per k-tile) + a fixed part,
-// all fitted to measurements (microseconds): a k-tile costs 0.15 + 0.17 NF + 0.45 per contraction
-// wave that has activation rows (their loads, one L1 access per lane and 16 bytes, bound the
-// kernel; the NF term is the decode); prologue and epilogue cost 10 + 2 NF.  Wide tiles win
+// all fitted to measurements (microseconds): a k-tile of 80 columns costs half of 0.15 + 0.17 NF +
+// 0.45 per contraction wave that has activation rows (the NF term is the decode and the weight
+// operands, the wave term the activation tile: LDS time bounds the kernel); prologue and epilogue
+// cost 10 + 2 NF.  Wide tiles win
 // unless they leave compute units idle; then the k-tiles of an output tile are dealt to several
 // workgroups, which costs a second pass over the partial sums.
 static Plan make_plan(const Dims& d, int M) {
@@ -565,11 +580,11 @@ static Plan make_plan(const Dims& d, int M) {
   Plan best{5, 1, ntiles, 0.0};
   double best_cost = 1e300;
   for (int nf = 2; nf <= 5; ++nf) {
-    const double t_tile = 0.15 + 0.17 * nf + 0.45 * waves;
+    const double t_tile = 0.5 * (0.15 + 0.17 * nf + 0.45 * waves);
     const long long tiles_out = (long long)m_blocks * ((d.out + 32 * nf - 1) / (32 * nf));
     for (int sp = 1; sp <= 8; ++sp) {
       const int tps = (ntiles + sp - 1) / sp;
-      if (sp > 1 && (tps < 4 || (sp - 1) * tps >= ntiles || M > 65535)) continue;   // short or empty splits; grid limit of the second pass
+      if (sp > 1 && (tps < 8 || (sp - 1) * tps >= ntiles || M > 65535)) continue;   // short or empty splits; grid limit of the second pass
       const long long rounds = (tiles_out * sp + 255) / 256;
       double cost = (double)rounds * tps * t_tile + 10.0 + 2.0 * nf;
       if (sp > 1) cost += 2.0 + (double)sp * M * d.out * 4.0 / 3.0e6;   // second pass over the partials

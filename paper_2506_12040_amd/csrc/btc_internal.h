@@ -74,6 +74,13 @@ btc_status gemm_tiled(hipStream_t q, const Dims& d, const uint32_t* packed, cons
                       const float* alpha, const float* mu, const void* X, int is_bf16, int M, void* Y, int y_dtype,
                       void* workspace, size_t workspace_bytes, int clear_workspace);
 size_t gemm_tiled_workspace_bytes(const Dims& d, int M);   // 0 unless the call is split along k
+// many activation rows (btc_gemm_wide.hip): the signs expanded once per call into a byte matrix in the workspace,
+// contracted by a kernel that streams both operands into LDS with load-to-LDS instructions
+bool gemm_wide_covers(const Dims& d, int M);
+size_t gemm_wide_workspace_bytes(const Dims& d, int M);
+btc_status gemm_wide(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
+                     const float* alpha, const float* mu, const void* X, int is_bf16, int M, void* Y, int y_dtype,
+                     void* workspace, size_t workspace_bytes);
 double gemm_tiled_estimate_us(const Dims& d, int M);       // rough duration, for engine selection
 // Leading part of a btc_gemv workspace that must stay zero between calls (the table engine's slots).
 size_t gemv_table_region_bytes(const Dims& d);

@@ -238,6 +238,34 @@ def test_gemm_small_full_compare(G, oracle, out, n_in, v, K, M, xd):
     assert np.array_equal(y2, y3), "two runs differ"
 
 
+# Many activation rows and enough 256 x 160 output tiles to fill the chip: the route that expands the signs
+# into bytes once per call and streams both operands into LDS.  Ragged last block of activation rows (one
+# row, a few rows), out % 4 != 0 (scalar stores), a last k-tile that is partly or wholly past `in`, fp16
+# and bf16, 10-bit indices, and chunk lengths other than 10 (the general expansion, also with a codebook
+# that no LDS table holds).
+GEMM_WIDE = [
+    # out, in, v, K, M, x_dtype
+    (6007, 400, 10, 256, 1300, "bf16"), (6100, 528, 10, 700, 1281, "f16"), (6000, 320, 8, 100, 1290, "bf16"),
+    (5930, 336, 12, 3000, 1537, "bf16"), (9000, 240, 10, 512, 1024, "f16"),
+]
+
+
+@pytest.mark.parametrize("out,n_in,v,K,M,xd", GEMM_WIDE)
+def test_gemm_many_rows_full_compare(G, oracle, out, n_in, v, K, M, xd):
+    B = G.B
+    say(f"gemm many rows out={out} in={n_in} v={v} K={K} M={M} {xd}")
+    layer, x = S.make_case(11, out, n_in, v, K, M, x_dtype=xd)
+    dl = G.DeviceLayer(layer, oracle)
+    xk = B.BTC_BF16 if xd == "bf16" else B.BTC_F16
+    y_ref = G.oracle_all_rows(oracle, dl, x, xd)
+    for yd in (B.BTC_F32, B.BTC_BF16 if xd == "bf16" else B.BTC_F16):
+        y = G.gemm(dl, x, xk, yd)
+        (G.assert_close_bf16_out if yd == B.BTC_BF16 else G.assert_close)(y, y_ref, "gemm, many rows")
+    y2 = G.gemm(dl, x, xk, B.BTC_F32)
+    y3 = G.gemm(dl, x, xk, B.BTC_F32)
+    assert np.array_equal(y2, y3), "two runs differ"
+
+
 @pytest.mark.parametrize("case", S.config_cases(3), ids=lambda c: f"{c['out']}x{c['n_in']}M{c['batch']}")
 def test_gemm_config_3_full_size(G, oracle, case):
     B = G.B
