@@ -148,7 +148,8 @@ enum {
   BTC_ENGINE_MFMA = 4,      /* fp16 matrix cores, up to 16 activation rows, two kernels            */
   BTC_ENGINE_TILED = 5,     /* the prefill kernel on a few rows                                    */
   BTC_ENGINE_GENERIC = 6,   /* any chunk length and index width                                    */
-  BTC_ENGINE_FP4 = 7        /* 4-bit matrix cores: weights as E2M1, activations as E5M2 pieces     */
+  BTC_ENGINE_FP4 = 7,       /* 4-bit matrix cores: weights as E2M1, activations as E5M2 pieces     */
+  BTC_ENGINE_CODE = 8       /* long vectors, large codebooks: the codebook itself in LDS           */
 };
 btc_status btc_gemv_engine(void* stream, const btc_shape* s, const uint32_t* packed,
                            const uint32_t* codebook, const float* alpha, const float* mu,

@@ -17,7 +17,7 @@ BTC_ERR_NULL, BTC_ERR_SHAPE, BTC_ERR_UNSUPPORTED, BTC_ERR_ALIGN = -1, -2, -3, -4
 BTC_ERR_INDEX_RANGE, BTC_ERR_HIP, BTC_ERR_WORKSPACE = -5, -6, -7
 BTC_F16, BTC_BF16, BTC_F32 = 0, 1, 2
 (BTC_ENGINE_AUTO, BTC_ENGINE_EXPAND, BTC_ENGINE_LUT, BTC_ENGINE_MFMA_ONE, BTC_ENGINE_MFMA, BTC_ENGINE_TILED,
- BTC_ENGINE_GENERIC, BTC_ENGINE_FP4) = range(8)
+ BTC_ENGINE_GENERIC, BTC_ENGINE_FP4, BTC_ENGINE_CODE) = range(9)
 
 
 class btc_shape(ctypes.Structure):

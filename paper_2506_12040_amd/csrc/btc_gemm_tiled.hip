@@ -56,7 +56,6 @@ constexpr int kXT = kBM * kXRS;         // bytes of one activation tile buffer
 constexpr int kMW = 4;                  // contraction waves
 constexpr int kDW = 4;                  // staging waves (8 waves per workgroup: 2 per SIMD, 256 registers each)
 constexpr int kXL = 11;                 // activation loads per staging thread and tile (the last one partial)
-constexpr uint32_t kOob = 0x80000000u;  // buffer offset that is always out of range
 constexpr int kRsrcFlags = 0x00020000;
 
 template <bool BF16>

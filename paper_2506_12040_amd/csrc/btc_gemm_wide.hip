@@ -26,6 +26,7 @@
 #include <hip/hip_bf16.h>
 #include <hip/hip_fp16.h>
 
+#include <algorithm>
 #include <type_traits>
 
 #include "btc_internal.h"
@@ -110,24 +111,34 @@ __device__ __forceinline__ void load_to_lds_16(const __amdgpu_buffer_rsrc_t& rsr
 
 // ---- first kernel: the sign matrix as bytes, WB[out][pitch] (pitch = 80 * number of k-tiles; the
 // columns past `in` hold the rest of the last chunk's pattern, then zeros: they only ever meet
-// zero activations).  One thread per 16 bytes.  The blocks from `expand_blocks` on add up the
-// activation rows instead (one wave per row, fp32): rs[m] = sum_k X[m][k], the factor of mu.
+// zero activations).  One thread per 16 bytes at a time.  The first blocks of the grid (all but
+// `expand_blocks`) add up the activation rows instead (one wave per row, fp32): rs[m] = sum_k X[m][k], the factor of mu.
 template <bool BF16>
 __global__ __launch_bounds__(256) void expand_signs_kernel(Dims d, const uint32_t* __restrict__ packed,
                                                            const uint32_t* __restrict__ codebook,
                                                            unsigned char* __restrict__ WB, int pitch, int expand_blocks,
                                                            const uint16_t* __restrict__ X, int M, float* __restrict__ rs) {
-  if ((int)blockIdx.x >= expand_blocks) {
-    const int m = ((int)blockIdx.x - expand_blocks) * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int sum_blocks = (int)gridDim.x - expand_blocks;
+  if ((int)blockIdx.x < sum_blocks) {                    // (first in the grid: they overlap the expansion)
+    const int m = (int)blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
     if (m >= M) return;
     const uint4* row = (const uint4*)(X + (size_t)m * d.in);             // `in` is a multiple of 16 here
+    const int n8 = d.in / 8;
     float acc = 0.f;
-    for (int i = lane; i < d.in / 8; i += 64) {
-      const uint4 v = row[i];
-      acc = pair_sum<BF16>(v.x, acc);
-      acc = pair_sum<BF16>(v.y, acc);
-      acc = pair_sum<BF16>(v.z, acc);
-      acc = pair_sum<BF16>(v.w, acc);
+    for (int base = 0; base < n8; base += 64 * 8) {      // eight loads in flight per lane
+      uint4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int i = base + 64 * u + lane;
+        v[u] = i < n8 ? row[i] : make_uint4(0u, 0u, 0u, 0u);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        acc = pair_sum<BF16>(v[u].x, acc);
+        acc = pair_sum<BF16>(v[u].y, acc);
+        acc = pair_sum<BF16>(v[u].z, acc);
+        acc = pair_sum<BF16>(v[u].w, acc);
+      }
     }
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) acc += __shfl_xor(acc, o, 64);
@@ -136,7 +147,7 @@ __global__ __launch_bounds__(256) void expand_signs_kernel(Dims d, const uint32_
   }
   const uint32_t hi_byte = BF16 ? 0x3Fu : 0x3Cu;
   const int pieces = pitch >> 4;
-  const uint32_t id = blockIdx.x * 256u + threadIdx.x;       // out * pitch < 2^31
+  const uint32_t id = (blockIdx.x - (uint32_t)sum_blocks) * 256u + threadIdx.x;       // out * pitch < 2^31
   const uint32_t mask = (1u << d.b) - 1u;
   if (d.v == 10 && d.b <= 10) {
     // Chunk length 10: the 16 columns of a piece lie inside three consecutive chunks.  Their
@@ -145,8 +156,9 @@ __global__ __launch_bounds__(256) void expand_signs_kernel(Dims d, const uint32_
     __shared__ uint32_t npat[1024];
     for (int k = threadIdx.x; k < (1 << d.b); k += 256) npat[k] = ~codebook[k] & 0x3FFu;
     __syncthreads();
-    if (id >= (uint32_t)d.out * (uint32_t)pieces) return;
-    const int row = (int)(id / (uint32_t)pieces), pc = (int)(id - (uint32_t)row * (uint32_t)pieces);
+    const uint32_t total = (uint32_t)d.out * (uint32_t)pieces;
+    for (uint32_t it = id; it < total; it += (uint32_t)expand_blocks * 256u) {
+    const int row = (int)(it / (uint32_t)pieces), pc = (int)(it - (uint32_t)row * (uint32_t)pieces);
     const uint32_t* prow = packed + (size_t)row * d.wpr;
     const int j0 = (pc * 16) / 10, t0 = pc * 16 - 10 * j0;
     uint32_t idx[3];
@@ -172,10 +184,11 @@ __global__ __launch_bounds__(256) void expand_signs_kernel(Dims d, const uint32_
     for (int q = 0; q < 4; ++q)
       w[q] = (((__umul24((n16 >> (4 * q)) & 0xFu, 0x204081u)) & 0x01010101u) << 7) | (hi_byte * 0x01010101u);
     *(uint4*)(WB + (size_t)row * pitch + (size_t)pc * 16) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
     return;
   }
-  if (id >= (uint32_t)d.out * (uint32_t)pieces) return;
-  const int row = (int)(id / (uint32_t)pieces), pc = (int)(id - (uint32_t)row * (uint32_t)pieces);
+  for (uint32_t it = id; it < (uint32_t)d.out * (uint32_t)pieces; it += (uint32_t)expand_blocks * 256u) {
+  const int row = (int)(it / (uint32_t)pieces), pc = (int)(it - (uint32_t)row * (uint32_t)pieces);
   const uint32_t* prow = packed + (size_t)row * d.wpr;
   int k = pc * 16;
   int j = k / d.v, t = k - j * d.v;
@@ -204,6 +217,7 @@ __global__ __launch_bounds__(256) void expand_signs_kernel(Dims d, const uint32_
     }
   }
   *(uint4*)(WB + (size_t)row * pitch + (size_t)pc * 16) = make_uint4(w[0], w[1], w[2], w[3]);
+  }
 }
 
 // ---- second kernel: the contraction
@@ -557,7 +571,8 @@ btc_status gemm_wide(hipStream_t q, const Dims& d, const uint32_t* packed, const
   unsigned char* WB = (unsigned char*)workspace;
   float* rs = (float*)(WB + sign_bytes(d));
   const long long pieces = (long long)d.out * (pitch / 16);
-  const int expand_blocks = (int)((pieces + 255) / 256), sum_blocks = (M + 3) / 4;
+  // a few thousand blocks that each walk over the pieces (the table in LDS is filled once per block)
+  const int expand_blocks = (int)std::min<long long>((pieces + 255) / 256, 4096), sum_blocks = (M + 3) / 4;
   if (is_bf16)
     expand_signs_kernel<true><<<expand_blocks + sum_blocks, 256, 0, q>>>(d, packed, codebook, WB, pitch, expand_blocks,
                                                                          (const uint16_t*)X, M, rs);

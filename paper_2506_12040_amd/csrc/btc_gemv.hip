@@ -47,6 +47,10 @@ static int choose_engine(const Dims& d, int batch) {
       engine = BTC_ENGINE_EXPAND;
     else if (lut_engine_covers(d))
       engine = BTC_ENGINE_LUT;
+    else if (batch == 1 && gemv_code_covers(d))
+      // long vectors or large codebooks (no tuned engine has tables for them): the codebook itself in LDS
+      // (4096 x 4096 at v = 16 with 65536 centroids: 32 us with the fallback kernel)
+      engine = BTC_ENGINE_CODE;
     else
       engine = BTC_ENGINE_GENERIC;
   }
@@ -129,6 +133,14 @@ static btc_status gemv_dispatch(int engine, void* stream, const btc_shape* s, co
         if (st != BTC_OK) return st;
       }
       return BTC_OK;
+    case BTC_ENGINE_CODE:
+      if (!gemv_code_covers(d)) return BTC_ERR_UNSUPPORTED;
+      for (int m = 0; m < batch; ++m) {   // one pass per activation row
+        st = gemv_code(q, d, packed, codebook, alpha, mu, (const char*)x + (size_t)m * d.in * 2,
+                       (char*)y + (size_t)m * d.out * ysz, y_is_f32);
+        if (st != BTC_OK) return st;
+      }
+      return BTC_OK;
     case BTC_ENGINE_GENERIC:
       return gemv_generic(q, d, packed, codebook, alpha, mu, x, batch, y, y_is_f32);
   }
@@ -200,7 +212,7 @@ btc_status btc_gemv(void* stream, const btc_shape* s, const uint32_t* packed, co
 btc_status btc_gemv_engine(void* stream, const btc_shape* s, const uint32_t* packed, const uint32_t* codebook,
                            const float* alpha, const float* mu, const void* x, int32_t batch, void* y,
                            btc_dtype y_dtype, void* workspace, size_t workspace_bytes, int32_t engine) {
-  if (engine < BTC_ENGINE_AUTO || engine > BTC_ENGINE_FP4) return BTC_ERR_UNSUPPORTED;
+  if (engine < BTC_ENGINE_AUTO || engine > BTC_ENGINE_CODE) return BTC_ERR_UNSUPPORTED;
   return btc::gemv_dispatch(engine, stream, s, packed, codebook, alpha, mu, x, batch, y, y_dtype, workspace,
                             workspace_bytes);
 }

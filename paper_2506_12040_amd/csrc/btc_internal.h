@@ -36,6 +36,10 @@ btc_status gemv_expand(hipStream_t q, const Dims& d, const uint32_t* packed, con
 bool gemv_fp4_covers(const Dims& d);
 btc_status gemv_fp4(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
                     const float* alpha, const float* mu, const void* x, void* y, int y_is_f32);
+// Long vectors and large codebooks, one activation row (btc_gemv_code.hip): the codebook itself in LDS.
+bool gemv_code_covers(const Dims& d);
+btc_status gemv_code(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
+                     const float* alpha, const float* mu, const void* x, void* y, int y_is_f32);
 // Fallback engine for every other setting (btc_gemv_generic.hip).
 btc_status gemv_generic(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
                         const float* alpha, const float* mu, const void* x, int batch, void* y, int y_is_f32);

@@ -11,7 +11,7 @@ import btc_synth as S
 
 pytestmark = pytest.mark.gpu
 
-ENGINE_NAMES = {1: "expand", 2: "lut", 3: "mfma_one", 4: "mfma", 5: "tiled", 6: "generic", 7: "fp4"}
+ENGINE_NAMES = {1: "expand", 2: "lut", 3: "mfma_one", 4: "mfma", 5: "tiled", 6: "generic", 7: "fp4", 8: "code"}
 
 
 @pytest.fixture(scope="module")
@@ -50,6 +50,11 @@ ENGINE_CASES = [
     (300, 5000, 9, 512, 1, "uniform"), (77, 2701, 9, 300, 1, "zipf"), (2100, 12006, 9, 1024, 1, "uniform"),
     (96, 4096, 10, 512, 4, "uniform"), (131, 6408, 10, 256, 7, "zipf"), (50, 333, 4, 9, 1, "uniform"),
     (31, 260, 8, 85, 2, "uniform"), (40, 330, 16, 7132, 4, "uniform"), (1030, 10240, 10, 256, 16, "uniform"),
+    # long vectors and large codebooks (the vector-length study's settings): codebook in LDS as 16-bit or 32-bit
+    # patterns, or gathered from memory; ragged last chunk, more chunks than one per lane, an odd number of rows
+    (1500, 4096, 16, 65536, 1, "uniform"), (700, 3000, 20, 65536, 1, "uniform"), (333, 2050, 12, 3000, 1, "zipf"),
+    (4099, 1234, 14, 9000, 1, "uniform"), (64, 16000, 18, 32768, 1, "uniform"), (257, 998, 6, 40, 1, "uniform"),
+    (90, 5000, 32, 100, 1, "uniform"),
 ]
 
 
