@@ -62,6 +62,8 @@ def lib() -> ctypes.CDLL:
         L.btc_oracle_matmul.argtypes = [c_vp, c_long, c_long, c_vp, c_long, c_vp]
         L.btc_oracle_transform.restype = None
         L.btc_oracle_transform.argtypes = [c_vp, c_long, c_long, c_long, c_vp, c_vp, c_vp, c_vp]
+        L.btc_oracle_quantize_rows.restype = None
+        L.btc_oracle_quantize_rows.argtypes = [c_vp, c_long, c_long, c_int, c_vp, c_vp, c_vp]
         L.btc_oracle_assign.restype = None
         L.btc_oracle_assign.argtypes = [c_vp, c_long, c_int, c_vp, c_long, c_vp, c_vp]
         L.btc_oracle_update.restype = c_int
@@ -190,6 +192,32 @@ def transform(x_bits, sign_bits, P1, P2, x_kind: str = "f16") -> np.ndarray:
     Y = np.empty(X.shape, dtype=np.float64)
     lib().btc_oracle_transform(_p(X), X.shape[0], n1, n2, _p(sign_bits), _p(P1), _p(P2), _p(Y))
     return Y
+
+
+def quantize_rows(x_bits, x_kind: str, bits: int):
+    """Min-max quantisation of every activation row to `bits` bits (fp32 arithmetic, see btc_oracle.cpp);
+    returns (q int32 [M][n], lo float32 [M], step float32 [M]) with x ~ lo + step * q."""
+    X = widen(np.atleast_2d(x_bits), x_kind).astype(np.float32)   # exact: 16-bit values
+    M, n = X.shape
+    q = np.empty((M, n), dtype=np.int32)
+    lo = np.empty(M, dtype=np.float32)
+    step = np.empty(M, dtype=np.float32)
+    lib().btc_oracle_quantize_rows(_p(X), M, n, int(bits), _p(q), _p(lo), _p(step))
+    return q, lo, step
+
+
+def dequantize_rows(q, lo, step) -> np.ndarray:
+    """lo[m] + step[m] * q[m][k] in float64 (the parameters are fp32 numbers, taken exactly)."""
+    q = np.asarray(q, dtype=np.float64)
+    return np.asarray(lo, dtype=np.float64)[:, None] + np.asarray(step, dtype=np.float64)[:, None] * q
+
+
+def linear_aq(packed, codebook, alpha, mu, q, lo, step, n_in: int, v: int, K: int,
+              rows: Optional[np.ndarray] = None) -> np.ndarray:
+    """The layer on quantised activations: dequantise, then the plain product with the materialised
+    W_hat; float64 [M][nrows]."""
+    W = materialise(packed, codebook, alpha, mu, n_in, v, K, rows)
+    return matmul(W, dequantize_rows(q, lo, step))
 
 
 def assign(vectors, v: int, codebook):

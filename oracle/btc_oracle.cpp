@@ -30,6 +30,12 @@
 // is written out as the definition too: the n x n matrix T is formed entry by
 // entry and the activation row multiplied with it (pins: tests/test_transform_pins.py).
 //
+// Also here: min-max quantisation of the activations to 8 or 4 bits (section "Activation
+// Quantization on sub-bit LLMs", appendix hyper-parameters: min-max quantisation with a scale per
+// channel), read as one (offset, step) pair per activation row -- a scale that varied along the
+// contraction index could not be taken out of the integer sum -- and the layer on the dequantised
+// activations (pins: tests/test_actquant_pins.py).
+//
 // Pins (tests/test_oracle_pins.py): brute force from a byte view of the
 // stream, full-codebook dense sign matrix, ones vector -> popcount integers,
 // linearity, affine split in (alpha, mu), XNOR-popcount closed form for +-1
@@ -271,6 +277,36 @@ int btc_oracle_update(const uint32_t* vectors, const int32_t* z, long N, int v, 
     codebook[k] = c;
   }
   return 0;
+}
+
+// Min-max quantisation of activation rows to `bits` bits (section "Activation Quantization on sub-bit
+// LLMs"; appendix: min-max quantisation, one scale per channel -- here: per activation row):
+//   lo[m]   = min_k x[m][k],  hi = max_k x[m][k]
+//   step[m] = (hi - lo) / (2^bits - 1)            (1 if the row is constant)
+//   q[m][k] = round_half_even((x[m][k] - lo[m]) / step[m])  clamped to [0, 2^bits - 1]
+//   x ~ lo[m] + step[m] * q[m][k]
+// The integer q is decided by floating-point arithmetic, so the precision is part of the definition:
+// every operation above is a single IEEE fp32 operation in the order written (x widened exactly).
+void btc_oracle_quantize_rows(const float* X, long M, long n, int bits, int32_t* q, float* lo, float* step) {
+  const float levels = (float)((1 << bits) - 1);
+#pragma omp parallel for schedule(static)
+  for (long m = 0; m < M; ++m) {
+    const float* x = X + m * n;
+    float mn = x[0], mx = x[0];
+    for (long k = 1; k < n; ++k) {
+      if (x[k] < mn) mn = x[k];
+      if (x[k] > mx) mx = x[k];
+    }
+    const float range = mx - mn;
+    const float st = range > 0.0f ? range / levels : 1.0f;
+    lo[m] = mn;
+    step[m] = st;
+    for (long k = 0; k < n; ++k) {
+      const float t = x[k] - mn;
+      const float r = __builtin_nearbyintf(t / st);     // round to nearest, ties to even
+      q[m * n + k] = r < 0.0f ? 0 : (r > levels ? (int32_t)levels : (int32_t)r);
+    }
+  }
 }
 
 }  // extern "C"

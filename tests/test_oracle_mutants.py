@@ -5,7 +5,8 @@ wrong reading of the paper would produce: the sign<->bit map of the packing algo
 of the dequantisation step dropped or applied to the wrong term, the element order inside a codeword or the
 bit order inside an index reversed, a transposed output, an off-by-one index width, the ragged last chunk
 read past the end of the row, the transform applied from the wrong side or with swapped Kronecker factors,
-ties of the E-step broken the other way, a zero mean of the M-step sent to -1."""
+ties of the E-step broken the other way, a zero mean of the M-step sent to -1, an activation grid with one
+level too many, ties or all fractions rounded the wrong way, the row offset left out."""
 import os
 import subprocess
 import sys
@@ -48,6 +49,15 @@ MUTANTS = [
      "test_assign_pins.py"),
     ("mstep_zero_mean_to_minus", "if (sum[t] >= 0) c |= 1u << t;", "if (sum[t] > 0) c |= 1u << t;",
      "test_assign_pins.py"),
+    ("quant_levels_power_of_two", "const float levels = (float)((1 << bits) - 1);", "const float levels = (float)(1 << bits);",
+     "test_actquant_pins.py"),
+    ("quant_rounds_half_up", "const float r = __builtin_nearbyintf(t / st);", "const float r = __builtin_floorf(t / st + 0.5f);",
+     "test_actquant_pins.py"),
+    ("quant_truncates", "const float r = __builtin_nearbyintf(t / st);", "const float r = __builtin_floorf(t / st);",
+     "test_actquant_pins.py"),
+    ("quant_symmetric_offset", "lo[m] = mn;", "lo[m] = 0.0f;", "test_actquant_pins.py"),
+    ("quant_constant_row_step_zero", "const float st = range > 0.0f ? range / levels : 1.0f;",
+     "const float st = range > 0.0f ? range / levels : 0.0f;", "test_actquant_pins.py"),
     ("mstep_empty_cluster_cleared", "if (size == 0) continue;", "if (size == 0) { codebook[k] = 0; continue; }",
      "test_assign_pins.py"),
 ]
