@@ -226,6 +226,40 @@ btc_status btc_update(void* stream, const uint32_t* vectors, const int32_t* z, i
                       int32_t v, uint32_t* codebook, int32_t K, void* workspace,
                       size_t workspace_bytes);
 
+/* The layer on quantised activations (section "Activation Quantization on sub-bit LLMs": W0.8A8 and
+ * W0.8A4; appendix hyper-parameters: min-max quantisation with a scale per channel, read here as one
+ * (offset, step) pair per activation row -- a scale that varied along the contraction index could not be
+ * taken out of the integer sum).  Three calls:
+ *
+ * btc_quantize_rows: for every row m of X,
+ *     lo[m] = min_k X[m][k],  step[m] = (max_k X[m][k] - lo[m]) / (2^bits - 1)   (1 for a constant row)
+ *     Q[m][k] = round-to-nearest-even((X[m][k] - lo[m]) / step[m]) clamped to [0, 2^bits - 1]
+ *   every operation a single IEEE fp32 operation in the order written (X widened exactly), so that the
+ *   integer codes are reproducible; X ~ lo + step * Q.
+ *     X : [M][n] of x_dtype (BTC_F16 or BTC_BF16), finite values;  bits : 8 or 4;  n <= 65536
+ *     Q : uint8 [M][n], one code per byte for both widths;  lo, step : float [M]
+ *     qsum : float [M] or NULL: sum_k Q[m][k] (an exact integer)
+ * btc_weight_rowsums: wsum[i] = sum_{k < in} W_hat[i][k] = alpha_i * (sum of the row's signs) + mu_i * in,
+ *   a per-layer constant of the third call.  wsum : float [out].
+ * btc_gemm_aq: Y[m][i] = sum_k W_hat[i][k] * (lo[m] + step[m] * Q[m][k])
+ *                     = step[m] * (alpha_i * sum_k B_hat[i][k] Q[m][k] + mu_i * sum_k Q[m][k]) + lo[m] * wsum[i],
+ *   any M >= 1 (decode and prefill).  The integer sums are exact (codes and signs are exact in the 16-bit
+ *   operand formats, fp32 sums of integers below 2^24); alpha, mu, step, lo are applied in fp32.
+ *     Y : [M][out] of y_dtype (BTC_F32, BTC_F16 or BTC_BF16)
+ * workspace (second and third call): btc_aq_workspace_bytes(s, M) bytes (M = 1 for btc_weight_rowsums), any
+ * contents, clobbered.  Device pointers owned by the caller, 16-byte aligned.  All three enqueue and return.
+ * Errors: BTC_ERR_NULL, _SHAPE, _UNSUPPORTED (bits, dtypes, n or in above 65536), _ALIGN, _WORKSPACE, _HIP. */
+btc_status btc_quantize_rows(void* stream, const void* X, btc_dtype x_dtype, int32_t M, int32_t n, int32_t bits,
+                             uint8_t* Q, float* lo, float* step, float* qsum);
+size_t btc_aq_workspace_bytes(const btc_shape* s, int32_t M);
+btc_status btc_weight_rowsums(void* stream, const btc_shape* s, const uint32_t* packed, const uint32_t* codebook,
+                              const float* alpha, const float* mu, float* wsum, void* workspace,
+                              size_t workspace_bytes);
+btc_status btc_gemm_aq(void* stream, const btc_shape* s, const uint32_t* packed, const uint32_t* codebook,
+                       const float* alpha, const float* mu, const float* wsum, const uint8_t* Q, const float* lo,
+                       const float* step, int32_t M, void* Y, btc_dtype y_dtype, void* workspace,
+                       size_t workspace_bytes);
+
 /* Host. Static string for a status code. */
 const char* btc_status_str(btc_status st);
 

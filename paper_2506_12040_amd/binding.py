@@ -69,6 +69,14 @@ def lib() -> ctypes.CDLL:
         L.btc_update_workspace_bytes.argtypes = [i32, i32]
         L.btc_update.restype = ctypes.c_int
         L.btc_update.argtypes = [vp, vp, vp, ctypes.c_int64, i32, vp, i32, vp, sz]
+        L.btc_quantize_rows.restype = ctypes.c_int
+        L.btc_quantize_rows.argtypes = [vp, vp, ctypes.c_int, i32, i32, i32, vp, vp, vp, vp]
+        L.btc_aq_workspace_bytes.restype = sz
+        L.btc_aq_workspace_bytes.argtypes = [sp, i32]
+        L.btc_weight_rowsums.restype = ctypes.c_int
+        L.btc_weight_rowsums.argtypes = [vp, sp, vp, vp, vp, vp, vp, vp, sz]
+        L.btc_gemm_aq.restype = ctypes.c_int
+        L.btc_gemm_aq.argtypes = [vp, sp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, ctypes.c_int, vp, sz]
         L.btc_status_str.restype = ctypes.c_char_p
         L.btc_status_str.argtypes = [ctypes.c_int]
         _lib = L
@@ -159,6 +167,27 @@ def btc_gemm(s: btc_shape, packed, codebook, alpha, mu, X, x_dtype: int, M: int,
 def btc_transform(X, x_dtype: int, M: int, n1: int, n2: int, sign_bits, P1, P2, Y, y_dtype: int, stream=None) -> None:
     _check(lib().btc_transform(_stream(stream), _ptr(X), x_dtype, M, n1, n2, _ptr(sign_bits), _ptr(P1), _ptr(P2),
                                _ptr(Y), y_dtype), "btc_transform")
+
+
+def btc_quantize_rows(X, x_dtype: int, M: int, n: int, bits: int, Q, lo, step, qsum=None, stream=None) -> None:
+    _check(lib().btc_quantize_rows(_stream(stream), _ptr(X), x_dtype, M, n, bits, _ptr(Q), _ptr(lo), _ptr(step),
+                                   _ptr(qsum)), "btc_quantize_rows")
+
+
+def btc_aq_workspace_bytes(s: BtcShape, M: int) -> int:
+    return lib().btc_aq_workspace_bytes(ctypes.byref(s), M)
+
+
+def btc_weight_rowsums(s: BtcShape, packed, codebook, alpha, mu, wsum, workspace, stream=None) -> None:
+    _check(lib().btc_weight_rowsums(_stream(stream), ctypes.byref(s), _ptr(packed), _ptr(codebook), _ptr(alpha),
+                                    _ptr(mu), _ptr(wsum), _ptr(workspace), _nbytes(workspace)), "btc_weight_rowsums")
+
+
+def btc_gemm_aq(s: BtcShape, packed, codebook, alpha, mu, wsum, Q, lo, step, M: int, Y, y_dtype: int, workspace,
+                stream=None) -> None:
+    _check(lib().btc_gemm_aq(_stream(stream), ctypes.byref(s), _ptr(packed), _ptr(codebook), _ptr(alpha), _ptr(mu),
+                             _ptr(wsum), _ptr(Q), _ptr(lo), _ptr(step), M, _ptr(Y), y_dtype, _ptr(workspace),
+                             _nbytes(workspace)), "btc_gemm_aq")
 
 
 def btc_assign(vectors, N: int, v: int, codebook, K: int, z, dist2=None, stream=None) -> None:

@@ -42,7 +42,7 @@ class GuardedOutput:
     def __init__(self, rows: int, cols: int, dtype: torch.dtype):
         self.rows, self.cols = rows, cols
         n = rows * cols
-        self.canary = 12345.0 if dtype != torch.int32 else 0x5A5A5A5A
+        self.canary = 12345.0 if dtype.is_floating_point else (0xA5 if dtype == torch.uint8 else 0x5A5A5A5A)
         self.buf = torch.full((n + 2 * GUARD,), self.canary, dtype=dtype, device="cuda")
         self.payload = self.buf[GUARD:GUARD + n]
         assert self.payload.data_ptr() % 16 == 0
