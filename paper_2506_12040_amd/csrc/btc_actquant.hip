@@ -11,8 +11,11 @@
 // The integer sums are exact: the codes (0 .. 255) are exact in fp16 and bf16, products with +-1 and their
 // fp32 sums stay below 2^24 for rows of up to 65793 weights, so the contraction is handed to the kernels
 // of btc_gemv / btc_gemm with the codes as 16-bit operands, and an epilogue applies step, lo and wsum.
+// Calls with enough rows to fill the chip go to the integer matrix cores instead (btc_gemm_wide_i8.hip).
 #include <hip/hip_bf16.h>
 #include <hip/hip_fp16.h>
+
+#include <algorithm>
 
 #include "btc_internal.h"
 
@@ -27,8 +30,10 @@ __device__ __forceinline__ float widen16(uint16_t h, int is_bf16) {
   return __half2float(__builtin_bit_cast(__half, h));
 }
 
-// One workgroup per activation row.  The decision arithmetic is fp32, one IEEE operation per step, in
-// this order: t = x - lo;  r = t / step;  q = round-to-nearest-even(r) clamped to the grid.
+// One workgroup per activation row, eight elements per load when the row allows it (n % 8 == 0; rows are
+// then 16-byte aligned).  The decision arithmetic is fp32, one IEEE operation per step, in this order:
+// t = x - lo;  r = t / step;  q = round-to-nearest-even(r) clamped to the grid.
+template <bool VEC>
 __global__ __launch_bounds__(kThreads) void quantize_rows_kernel(const uint16_t* __restrict__ X, int is_bf16, int n,
                                                                  int bits, uint8_t* __restrict__ Q,
                                                                  float* __restrict__ lo, float* __restrict__ step,
@@ -37,10 +42,23 @@ __global__ __launch_bounds__(kThreads) void quantize_rows_kernel(const uint16_t*
   const int m = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const uint16_t* x = X + (size_t)m * n;
   float mn = widen16(x[0], is_bf16), mx = mn;
-  for (int k = tid; k < n; k += kThreads) {
-    const float v = widen16(x[k], is_bf16);
-    mn = fminf(mn, v);
-    mx = fmaxf(mx, v);
+  if (VEC) {
+    for (int k = tid; k < n / 8; k += kThreads) {
+      const uint4 v = ((const uint4*)x)[k];
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float f = widen16((uint16_t)(w[e >> 1] >> (16 * (e & 1))), is_bf16);
+        mn = fminf(mn, f);
+        mx = fmaxf(mx, f);
+      }
+    }
+  } else {
+    for (int k = tid; k < n; k += kThreads) {
+      const float v = widen16(x[k], is_bf16);
+      mn = fminf(mn, v);
+      mx = fmaxf(mx, v);
+    }
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
@@ -61,12 +79,24 @@ __global__ __launch_bounds__(kThreads) void quantize_rows_kernel(const uint16_t*
   const float range = mx - mn;
   const float st = range > 0.0f ? range / levels : 1.0f;
   float sum = 0.f;                                       // integers: exact in any order
-  for (int k = tid; k < n; k += kThreads) {
-    const float t = widen16(x[k], is_bf16) - mn;
+  auto code = [&](uint16_t h) -> uint32_t {
+    const float t = widen16(h, is_bf16) - mn;
     float r = rintf(t / st);
     r = fminf(fmaxf(r, 0.0f), levels);
-    Q[(size_t)m * n + k] = (uint8_t)(int)r;
     sum += r;
+    return (uint32_t)(int)r;
+  };
+  if (VEC) {
+    for (int k = tid; k < n / 8; k += kThreads) {        // (a second read of the row: it is in the L2)
+      const uint4 v = ((const uint4*)x)[k];
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+      uint32_t o[2] = {0u, 0u};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e >> 2] |= code((uint16_t)(w[e >> 1] >> (16 * (e & 1)))) << (8 * (e & 3));
+      ((uint2*)(Q + (size_t)m * n))[k] = make_uint2(o[0], o[1]);
+    }
+  } else {
+    for (int k = tid; k < n; k += kThreads) Q[(size_t)m * n + k] = (uint8_t)code(x[k]);
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
@@ -143,8 +173,12 @@ btc_status btc_quantize_rows(void* stream, const void* X, btc_dtype x_dtype, int
   if (M <= 0 || n <= 0) return BTC_ERR_SHAPE;
   if ((bits != 8 && bits != 4) || (x_dtype != BTC_F16 && x_dtype != BTC_BF16) || n > aq::kMaxIn) return BTC_ERR_UNSUPPORTED;
   if (!aligned16(X) || !aligned16(Q) || !aligned16(lo) || !aligned16(step) || (qsum && !aligned16(qsum))) return BTC_ERR_ALIGN;
-  aq::quantize_rows_kernel<<<M, aq::kThreads, 0, (hipStream_t)stream>>>((const uint16_t*)X, x_dtype == BTC_BF16, n, bits, Q,
-                                                                         lo, step, qsum);
+  if (n % 8 == 0)
+    aq::quantize_rows_kernel<true><<<M, aq::kThreads, 0, (hipStream_t)stream>>>((const uint16_t*)X, x_dtype == BTC_BF16, n,
+                                                                                 bits, Q, lo, step, qsum);
+  else
+    aq::quantize_rows_kernel<false><<<M, aq::kThreads, 0, (hipStream_t)stream>>>((const uint16_t*)X, x_dtype == BTC_BF16, n,
+                                                                                  bits, Q, lo, step, qsum);
   return launch_status();
 }
 
@@ -155,7 +189,11 @@ size_t btc_aq_workspace_bytes(const btc_shape* s, int32_t M) {
   const size_t inner = M <= 16 ? btc_workspace_bytes(s, rows, 0) : btc_workspace_bytes(s, rows, 1);
   // 16-bit copy of the codes (or the row of ones of btc_weight_rowsums), the fp32 result of the
   // contraction, then the contraction's own workspace
-  return aq::align256((size_t)rows * s->in * 2) + aq::align256((size_t)rows * s->out * 4) + aq::align256(inner);
+  size_t need = aq::align256((size_t)rows * s->in * 2) + aq::align256((size_t)rows * s->out * 4) + aq::align256(inner);
+  // many rows: the sign matrix as int8 and the sums of the code rows, for the integer matrix cores
+  const Dims d = dims_of(*s);
+  if (gemm_wide_i8_covers(d, M)) need = std::max(need, aq::align256(gemm_wide_i8_workspace_bytes(d, M)));
+  return need;
 }
 
 btc_status btc_weight_rowsums(void* stream, const btc_shape* s, const uint32_t* packed, const uint32_t* codebook,
@@ -194,6 +232,12 @@ btc_status btc_gemm_aq(void* stream, const btc_shape* s, const uint32_t* packed,
     return BTC_ERR_ALIGN;
   if (workspace_bytes < btc_aq_workspace_bytes(s, M)) return BTC_ERR_WORKSPACE;
   hipStream_t q = (hipStream_t)stream;
+  {
+    const Dims d = dims_of(*s);
+    if (gemm_wide_i8_covers(d, M))   // enough rows to fill the chip: int8 operands on the integer matrix cores
+      return gemm_wide_i8(q, d, packed, codebook, alpha, mu, wsum, Q, lo, step, M, Y, (int)y_dtype, workspace,
+                          workspace_bytes);
+  }
   uint16_t* Q16 = (uint16_t*)workspace;
   float* T = (float*)((char*)workspace + aq::align256((size_t)M * s->in * 2));
   char* inner = (char*)T + aq::align256((size_t)M * s->out * 4);

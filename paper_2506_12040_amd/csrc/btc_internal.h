@@ -72,6 +72,13 @@ bool gemv_mfma_one_covers(const Dims& d);
 btc_status gemv_mfma_one(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
                          const float* alpha, const float* mu, const void* x, void* y, int y_is_f32);
 
+// The same scheme on int8 activation codes with the integer matrix cores (btc_gemm_wide_i8.hip):
+//   Y = step * (alpha * <signs, codes> + mu * sum(codes)) + lo * wsum
+bool gemm_wide_i8_covers(const Dims& d, int M);
+size_t gemm_wide_i8_workspace_bytes(const Dims& d, int M);
+btc_status gemm_wide_i8(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
+                        const float* alpha, const float* mu, const float* wsum, const uint8_t* Q, const float* lo,
+                        const float* step, int M, void* Y, int y_dtype, void* workspace, size_t workspace_bytes);
 // Prefill kernels: the tuned tiling (btc_gemm_tiled.hip) and the generic one (btc_gemm_generic.hip).
 bool gemm_tiled_covers(const Dims& d, int M);
 btc_status gemm_tiled(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,

@@ -54,7 +54,11 @@ AQ_CASES = [
     # out, in, v, K, M, kind, bits
     (300, 4096, 10, 512, 1, "f16", 8), (5120, 5120, 10, 256, 1, "f16", 8), (2100, 13824, 10, 256, 1, "bf16", 4),
     (777, 1234, 10, 100, 5, "f16", 8), (1030, 2570, 10, 256, 16, "bf16", 8), (260, 810, 9, 1024, 33, "f16", 4),
-    (1500, 1600, 10, 256, 300, "bf16", 8), (90, 512, 16, 7132, 40, "f16", 8), (6007, 400, 10, 256, 1300, "bf16", 8),
+    (1500, 1600, 10, 256, 300, "bf16", 8), (90, 512, 16, 7132, 40, "f16", 8),
+    # enough rows and output tiles to fill the chip: int8 operands on the integer matrix cores (ragged last block
+    # of rows, out % 4 != 0, a last k-tile partly past `in`, 4-bit codes, a chunk length other than 10)
+    (6007, 400, 10, 256, 1300, "bf16", 8), (6100, 528, 10, 700, 1281, "f16", 4), (6000, 320, 8, 100, 1290, "bf16", 8),
+    (9000, 256, 10, 512, 1024, "f16", 8),
 ]
 
 
