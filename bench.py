@@ -85,6 +85,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-transform", action="store_true", help="skip the btc_transform / btc_assign timings")
     ap.add_argument("--no-other", action="store_true", help="skip the 7B (batch 1/4/16) and 70B decode sweeps")
+    ap.add_argument("--profile-case", default=None,
+                    help="run 24 calls of one case and exit (for rocprofv3 counter runs): gemv,out,in,v,K,batch | "
+                         "gemm,out,in,v,K,M | gemm_aq,out,in,v,K,M | assign,N,v,K")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run three 256 MiB device-to-device copies (reference for FETCH_SIZE/WRITE_SIZE) and exit")
     args = ap.parse_args()
@@ -109,6 +112,56 @@ def main():
     B.lib()  # raises if the HIP library was not built
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.profile_case:
+        f = args.profile_case.split(",")
+        kind, nums = f[0], [int(a) for a in f[1:]]
+        if kind == "assign":
+            N, v_, K_ = nums
+            g = torch.Generator(device=dev)
+            g.manual_seed(0)
+            vec = torch.randint(0, 2 ** v_, (N,), dtype=torch.int32, device=dev, generator=g)
+            cbk = torch.randint(0, 2 ** v_, (K_,), dtype=torch.int32, device=dev, generator=g)
+            zz = torch.empty(N, dtype=torch.int32, device=dev)
+            for _ in range(6):
+                B.btc_assign(vec, N, v_, cbk, K_, zz, None)
+        else:
+            o, i, v_, K_, rows = nums
+            layer, x = S.make_case(0, o, i, v_, K_, rows, x_dtype="f16" if kind == "gemv" else "bf16")
+            s = B.btc_shape_init(o, i, v_, K_)
+            packed = torch.empty(o * s.words_per_row, dtype=torch.int32, device=dev)
+            B.btc_pack(s, torch.from_numpy(layer.idx).to(dev), packed, torch.zeros(64, dtype=torch.uint8, device=dev))
+            cb = np.zeros(1 << s.b, dtype=np.uint32)
+            cb[:K_] = layer.codebook
+            cb_d = torch.from_numpy(cb.view(np.int32)).to(dev)
+            al, mu = torch.from_numpy(layer.alpha).to(dev), torch.from_numpy(layer.mu).to(dev)
+            xd = torch.from_numpy(x.view(np.int16)).to(dev)
+            if kind == "gemv":   # cold: 24 distinct copies
+                y = torch.empty(rows * o, dtype=torch.float16, device=dev)
+                ws = torch.zeros(B.btc_workspace_bytes(s, rows, False), dtype=torch.uint8, device=dev)
+                pk = packed.view(o, s.words_per_row)
+                copies = [torch.roll(pk, shifts=(c * 37 + 1) % o, dims=0).contiguous() for c in range(24)]
+                for c in copies:
+                    B.btc_gemv(s, c, cb_d, al, mu, xd, rows, y, B.BTC_F16, ws)
+            elif kind == "gemm":
+                Y = torch.empty(rows * o, dtype=torch.float32, device=dev)
+                ws = torch.zeros(B.btc_workspace_bytes(s, rows, True), dtype=torch.uint8, device=dev)
+                for _ in range(6):
+                    B.btc_gemm(s, packed, cb_d, al, mu, xd, B.BTC_BF16, rows, Y, B.BTC_F32, ws)
+            else:
+                Y = torch.empty(rows * o, dtype=torch.float32, device=dev)
+                Qc = torch.empty(rows * i, dtype=torch.uint8, device=dev)
+                lo_d = torch.empty(max(rows, 4), dtype=torch.float32, device=dev)
+                st_d = torch.empty(max(rows, 4), dtype=torch.float32, device=dev)
+                wsum = torch.empty(o, dtype=torch.float32, device=dev)
+                ws1 = torch.zeros(B.btc_aq_workspace_bytes(s, 1), dtype=torch.uint8, device=dev)
+                ws = torch.zeros(B.btc_aq_workspace_bytes(s, rows), dtype=torch.uint8, device=dev)
+                B.btc_weight_rowsums(s, packed, cb_d, al, mu, wsum, ws1)
+                for _ in range(6):
+                    B.btc_quantize_rows(xd, B.BTC_BF16, rows, i, 8, Qc, lo_d, st_d)
+                    B.btc_gemm_aq(s, packed, cb_d, al, mu, wsum, Qc, lo_d, st_d, rows, Y, B.BTC_F32, ws)
+        torch.cuda.synchronize()
+        print(json.dumps({"profile_case": args.profile_case}))
+        return
     figures = read_figures(PROFILE_FIGURES)
     kernel_us = read_figures(PROFILE_KERNEL_US)
 
@@ -311,6 +364,14 @@ def main():
                   "note": "btc_gemv on 28672x8192 at 0.9 bit, batch 1, cold: algorithmic bytes of a call "
                           f"({big['bytes']}) / graph-amortised time of a call; layer_frac = the seven matrices of "
                           "a 70B-shaped decoder layer"}
+        # the long-vector settings of the paper's vector-length study (codebook itself in LDS, or gathered)
+        longc = {}
+        for (o, i, v_, K_) in [(4096, 4096, 16, 65536), (4096, 4096, 20, 65536), (4096, 4096, 16, 7132),
+                               (11008, 4096, 16, 65536), (8192, 8192, 16, 65536)]:
+            p = device_case(dict(seed=0, out=o, n_in=i, v=v_, K=K_, batch=1))
+            longc[f"{o}x{i} v={v_} K={K_}"] = time_decode(p, min_calls=80)
+            del p
+        other["long_vectors_large_codebooks"] = longc
         # independent projections (q, k, v of one layer) on three streams, one graph per stream
         p0 = protos[0]
         mats = [c for calls in calls_per_layer for c in calls if c["p"] is p0][:120]
@@ -431,6 +492,52 @@ def main():
             gemm[f"M{M}"] = dict(M=M, x_dtype="bf16", y_dtype="f32", per_shape=per, layer_tflops=round(tf, 1),
                                  frac_mfma_peak=round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
                                  frac_measured_peak=round(tf / MFMA_BF16_MEASURED_TFLOPS, 4))
+
+    # ---- the layer on 8-bit activation codes (W0.8A8): quantise + product, prefill rows on the integer matrix
+    # cores, one decode row through the decode engines
+    act_quant = None
+    if not args.no_gemm:
+        act_quant = {}
+        for M in (args.gemm_m, 1):
+            per, tot_op, tot_ms = {}, 0.0, 0.0
+            for case in S.config_cases(2):
+                p = device_case(dict(case, batch=M, x_dtype="bf16" if M > 1 else "f16"))
+                s = p["s"]
+                Qc = torch.empty(M * s.in_, dtype=torch.uint8, device=dev)
+                lo_d = torch.empty(max(M, 4), dtype=torch.float32, device=dev)
+                st_d = torch.empty(max(M, 4), dtype=torch.float32, device=dev)
+                Y = torch.empty(M * s.out, dtype=torch.float32, device=dev)
+                wsq = torch.zeros(B.btc_aq_workspace_bytes(s, M), dtype=torch.uint8, device=dev)
+                ws1 = torch.zeros(B.btc_aq_workspace_bytes(s, 1), dtype=torch.uint8, device=dev)
+                wsum = torch.empty(s.out, dtype=torch.float32, device=dev)
+                B.btc_weight_rowsums(s, p["packed"], p["codebook"], p["alpha"], p["mu"], wsum, ws1)
+                xdt = B.BTC_BF16 if M > 1 else B.BTC_F16
+
+                def call():
+                    B.btc_quantize_rows(p["x"], xdt, M, s.in_, 8, Qc, lo_d, st_d)
+                    B.btc_gemm_aq(s, p["packed"], p["codebook"], p["alpha"], p["mu"], wsum, Qc, lo_d, st_d, M, Y,
+                                  B.BTC_F32, wsq)
+                call()
+                torch.cuda.synchronize()
+                reps = 10 if M > 1 else 50
+                e0, e1 = events()
+                e0.record()
+                for _ in range(reps):
+                    call()
+                e1.record()
+                torch.cuda.synchronize()
+                ms = e0.elapsed_time(e1) / reps
+                ops = 2.0 * M * s.out * s.in_
+                cnt = SHAPES_13B_COUNT[(s.out, s.in_)]
+                per[f"{s.out}x{s.in_}"] = dict(us=round(ms * 1e3, 1), tops=round(ops / ms / 1e9, 1))
+                tot_op += ops * cnt
+                tot_ms += ms * cnt
+                del p, Qc, Y, wsq
+            row = dict(M=M, bits=8, per_shape=per, note="btc_quantize_rows + btc_gemm_aq, warm, stream-timed")
+            if M > 1:
+                tp = tot_op / tot_ms / 1e9
+                row.update(layer_tops=round(tp, 1), frac_int8_peak=round(tp / 5000.0, 4))
+            act_quant[f"M{M}"] = row
 
     # ---- the online activation transform in front of the layer (btc_transform), on the two input widths of
     # the 13B layer: decode rows from a captured graph of 20 launches, prefill rows event-timed
@@ -639,6 +746,7 @@ def main():
             "frac_measured_peak": gemm[f"M{args.gemm_m}"]["frac_measured_peak"], "traffic": None,
             "note": f"2*M*out*in flop of the 7 projections at M={args.gemm_m} / event-timed btc_gemm calls "
                     "(whole calls)"},
+        "act_quant": act_quant,
         "transform": transform,
         "assign": assign,
         "cpu_baseline": cpu,
