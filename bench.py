@@ -643,9 +643,10 @@ def main():
             row = dict(us=round(us, 1), vectors_per_s=round(N / us * 1e6, -6), GBps=round(12.0 * N / us / 1e3, 1))
             if table:
                 row.update(route="pattern table in LDS", frac_hbm=round(12.0 * N / us / 1e3 / HBM_PEAK_GBS, 4))
-            else:   # xor, bit count, shift-or, minimum per (vector, centroid) pair on 256 x 64 lanes at 2.4 GHz
-                row.update(route="all pairs", lane_ops_per_s=round(4.0 * N * K_ / us * 1e6, -9),
-                           frac_alu=round(4.0 * N * K_ / us * 1e6 / 39.3e12, 4))
+            else:   # 3.5 vector-ALU instructions per (vector, centroid) pair, counted with SQ_INSTS_VALU
+                    # (profiles/assign_kernel_trace.md), on 256 x 64 lanes at 2.4 GHz
+                row.update(route="all pairs", lane_ops_per_s=round(3.5 * N * K_ / us * 1e6, -9),
+                           frac_alu=round(3.5 * N * K_ / us * 1e6 / 39.3e12, 4))
             # the M-step on the assignment just computed (the call waits for the stream: host round trip included)
             wsu = torch.zeros(B.btc_update_workspace_bytes(v_, K_), dtype=torch.uint8, device=dev)
             cb2 = cbk.clone()

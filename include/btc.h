@@ -84,9 +84,16 @@ size_t btc_packed_bytes(const btc_shape* s);
  * fp32 partial sums behind them and zeroes them in its second pass), so one
  * buffer serves any number of calls
  * that are ordered on a stream.  Calls that may overlap in time (different
- * streams) need a buffer each: sharing one is a data race.  btc_gemm writes
- * scratch values there and needs no particular contents; give it a buffer of
- * its own, or zero the buffer again before the next btc_gemv. */
+ * streams) need a buffer each: sharing one is a data race.  btc_gemm (and
+ * btc_gemm_aq, btc_weight_rowsums) write scratch values there -- partial sums,
+ * and for calls with many rows the sign matrix as one byte per weight -- and
+ * need no particular contents; give them a buffer of their own, or zero the
+ * buffer again before the next btc_gemv: a stale non-zero word in a slot
+ * would be read as a valid partial sum, silently.  The table engine waits
+ * for a missing partial sum for a bounded number of polls and then stores
+ * NaN with status BTC_OK (it cannot happen while every workgroup of the call
+ * runs; it would after an aborted earlier call): the outputs are then NaN
+ * and the workspace must be zero-filled again. */
 size_t btc_workspace_bytes(const btc_shape* s, int32_t rows, int is_gemm);
 
 /* Index matrix -> bit stream (Compression Analysis; storage format of the
