@@ -58,6 +58,9 @@ def lib() -> ctypes.CDLL:
         L.btc_oracle_materialise.restype = None
         L.btc_oracle_materialise.argtypes = [c_vp, c_vp, c_vp, c_vp, c_long, c_long, c_int, c_int,
                                              c_vp, c_long, c_vp]
+        L.btc_oracle_materialise_groups.restype = None
+        L.btc_oracle_materialise_groups.argtypes = [c_vp, c_vp, c_vp, c_vp, c_vp, c_int, c_long, c_long, c_int, c_int,
+                                                    c_vp, c_long, c_vp]
         L.btc_oracle_matmul.restype = None
         L.btc_oracle_matmul.argtypes = [c_vp, c_long, c_long, c_vp, c_long, c_vp]
         L.btc_oracle_transform.restype = None
@@ -156,6 +159,39 @@ def materialise(packed, codebook, alpha, mu, n_in: int, v: int, K: int,
     lib().btc_oracle_materialise(_p(packed), _p(codebook), _p(alpha), _p(mu), out, int(n_in),
                                  int(v), int(K), rows_p, nrows, _p(W))
     return W
+
+
+def materialise_groups(packed, codebook, alpha, mu, gmap, n_in: int, v: int, K: int,
+                       rows: Optional[np.ndarray] = None) -> np.ndarray:
+    """W_hat with several (alpha, mu) groups per row: alpha, mu float32 [out][G]; gmap uint32
+    [out][ceil(2 n_in / 32)], 2 bits per weight (see btc_oracle.cpp).  float64 [nrows][n_in]."""
+    packed = _c(packed, np.uint32)
+    codebook = _c(codebook, np.uint32)
+    alpha = _c(alpha, np.float32)
+    mu = _c(mu, np.float32)
+    gmap = _c(gmap, np.uint32)
+    out = packed.shape[0]
+    G = alpha.shape[1]
+    assert alpha.shape == (out, G) and mu.shape == (out, G) and 1 <= G <= 4
+    assert packed.shape[1] == words_per_row(n_in, v, K) and gmap.shape == (out, (2 * n_in + 31) // 32)
+    assert codebook.shape[0] >= K
+    if rows is None:
+        nrows, rows_p = out, ctypes.c_void_p(0)
+    else:
+        rows = _c(rows, np.int64)
+        assert rows.min() >= 0 and rows.max() < out
+        nrows, rows_p = rows.shape[0], _p(rows)
+    W = np.empty((nrows, n_in), dtype=np.float64)
+    lib().btc_oracle_materialise_groups(_p(packed), _p(codebook), _p(alpha), _p(mu), _p(gmap), int(G), out, int(n_in),
+                                        int(v), int(K), rows_p, nrows, _p(W))
+    return W
+
+
+def linear_groups(packed, codebook, alpha, mu, gmap, x_bits, n_in: int, v: int, K: int, x_kind: str = "f16",
+                  rows: Optional[np.ndarray] = None) -> np.ndarray:
+    """The layer with several (alpha, mu) groups per row; float64 [M][nrows]."""
+    W = materialise_groups(packed, codebook, alpha, mu, gmap, n_in, v, K, rows)
+    return matmul(W, widen(np.atleast_2d(x_bits), x_kind))
 
 
 def matmul(W: np.ndarray, X: np.ndarray) -> np.ndarray:

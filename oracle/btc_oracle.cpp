@@ -36,6 +36,9 @@
 // contraction index could not be taken out of the integer sum -- and the layer on the dequantised
 // activations (pins: tests/test_actquant_pins.py).
 //
+// Also here: the storage variant with several (alpha, mu) groups per weight row
+// (btc_oracle_materialise_groups; pins: tests/test_groups_pins.py).
+//
 // Pins (tests/test_oracle_pins.py): brute force from a byte view of the
 // stream, full-codebook dense sign matrix, ones vector -> popcount integers,
 // linearity, affine split in (alpha, mu), XNOR-popcount closed form for +-1
@@ -170,6 +173,46 @@ void btc_oracle_materialise(const uint32_t* packed, const uint32_t* codebook,
         if (k >= in) break;
         const double sgn = ((pattern >> t) & 1u) ? 1.0 : -1.0;
         W[r * in + k] = a * sgn + m;
+      }
+    }
+  }
+}
+
+// The storage variant with several (alpha, mu) pairs per weight row (Table "Study of Number of Split
+// Points"; appendix hyper-parameters: 2 split points by default): the weights of a row are partitioned
+// into G groups, every group has its own scale and mean,
+//   W_hat[i][k] = alpha[i][g] * B_hat[i][k] + mu[i][g],   g = group[i][k] in [0, G).
+// The paper does not print a storage format for the partition; here it is an explicit map of 2 bits per
+// weight, row-major, LSB-first like the index stream: group of weight k of row i = bits [2k, 2k+2) of row
+// i's map, gwpr = ceil(2 in / 32) words per row.  alpha and mu are [out][G] row-major.  Same calling
+// convention as btc_oracle_materialise.
+void btc_oracle_materialise_groups(const uint32_t* packed, const uint32_t* codebook,
+                                   const float* alpha, const float* mu, const uint32_t* gmap, int G,
+                                   long out, long in, int v, int K,
+                                   const long* rows, long nrows, double* W) {
+  (void)out;
+  const int b = btc_oracle_index_bits(K);
+  const long nchunks = btc_oracle_num_chunks(in, v);
+  const long wpr = (nchunks * b + 31) / 32;
+  const long gwpr = (2 * in + 31) / 32;
+#pragma omp parallel for schedule(static)
+  for (long r = 0; r < nrows; ++r) {
+    const long i = rows ? rows[r] : r;
+    const uint32_t* row = packed + i * wpr;
+    const uint32_t* grow = gmap + i * gwpr;
+    for (long j = 0; j < nchunks; ++j) {
+      uint32_t code = 0;
+      for (int q = 0; q < b; ++q) {
+        const long p = j * b + q;
+        code |= ((row[p >> 5] >> (p & 31)) & 1u) << q;
+      }
+      const uint32_t pattern = codebook[code];
+      for (int t = 0; t < v; ++t) {
+        const long k = j * v + t;
+        if (k >= in) break;
+        const int g = (int)((grow[(2 * k) >> 5] >> ((2 * k) & 31)) & 3u);
+        const double sgn = ((pattern >> t) & 1u) ? 1.0 : -1.0;
+        W[r * in + k] = (double)alpha[i * G + g] * sgn + (double)mu[i * G + g];
       }
     }
   }

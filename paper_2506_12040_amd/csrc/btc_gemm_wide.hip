@@ -572,7 +572,7 @@ btc_status gemm_wide(hipStream_t q, const Dims& d, const uint32_t* packed, const
   float* rs = (float*)(WB + sign_bytes(d));
   const long long pieces = (long long)d.out * (pitch / 16);
   // a few thousand blocks that each walk over the pieces (the table in LDS is filled once per block)
-  const int expand_blocks = (int)std::min<long long>((pieces + 255) / 256, 4096), sum_blocks = (M + 3) / 4;
+  const int expand_blocks = (int)std::min<long long>((pieces + 255) / 256, 2048), sum_blocks = (M + 3) / 4;
   if (is_bf16)
     expand_signs_kernel<true><<<expand_blocks + sum_blocks, 256, 0, q>>>(d, packed, codebook, WB, pitch, expand_blocks,
                                                                          (const uint16_t*)X, M, rs);

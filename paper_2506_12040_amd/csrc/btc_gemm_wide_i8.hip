@@ -485,7 +485,7 @@ btc_status gemm_wide_i8(hipStream_t q, const Dims& d, const uint32_t* packed, co
   float* qs = (float*)(WB + sign_bytes(d));
   const long long pieces = (long long)d.out * (pitch / 16);
   // a few thousand blocks that each walk over the pieces
-  const int expand_blocks = (int)std::min<long long>((pieces + 255) / 256, 4096), sum_blocks = (M + 3) / 4;
+  const int expand_blocks = (int)std::min<long long>((pieces + 255) / 256, 2048), sum_blocks = (M + 3) / 4;
   expand_signs_i8_kernel<<<expand_blocks + sum_blocks, 256, 0, q>>>(d, packed, codebook, WB, pitch, expand_blocks, Q, M, qs);
   btc_status st = launch_status();
   if (st != BTC_OK) return st;

@@ -58,6 +58,12 @@ MUTANTS = [
     ("quant_symmetric_offset", "lo[m] = mn;", "lo[m] = 0.0f;", "test_actquant_pins.py"),
     ("quant_constant_row_step_zero", "const float st = range > 0.0f ? range / levels : 1.0f;",
      "const float st = range > 0.0f ? range / levels : 0.0f;", "test_actquant_pins.py"),
+    ("groups_map_one_bit_per_weight", "const int g = (int)((grow[(2 * k) >> 5] >> ((2 * k) & 31)) & 3u);",
+     "const int g = (int)((grow[k >> 5] >> (k & 31)) & 1u);", "test_groups_pins.py"),
+    ("groups_mean_of_group_zero", "W[r * in + k] = (double)alpha[i * G + g] * sgn + (double)mu[i * G + g];",
+     "W[r * in + k] = (double)alpha[i * G + g] * sgn + (double)mu[i * G];", "test_groups_pins.py"),
+    ("groups_parameters_transposed", "W[r * in + k] = (double)alpha[i * G + g] * sgn + (double)mu[i * G + g];",
+     "W[r * in + k] = (double)alpha[g * out + i] * sgn + (double)mu[g * out + i];", "test_groups_pins.py"),
     ("mstep_empty_cluster_cleared", "if (size == 0) continue;", "if (size == 0) { codebook[k] = 0; continue; }",
      "test_assign_pins.py"),
 ]
