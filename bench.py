@@ -539,6 +539,40 @@ def main():
                 row.update(layer_tops=round(tp, 1), frac_int8_peak=round(tp / 5000.0, 4))
             act_quant[f"M{M}"] = row
 
+    # ---- the storage variant with several (alpha, mu) groups per weight row (btc_gemv_groups), one decode row,
+    # three groups drawn uniformly; bytes = index stream + group map (2 bits per weight) + per-row constants
+    groups = None
+    if not args.no_other:
+        groups = {}
+        ng = 3
+        for case in S.config_cases(2):
+            p = device_case(dict(case, batch=1))
+            s = p["s"]
+            rng = np.random.Generator(np.random.PCG64(7))
+            fields = rng.integers(0, ng, size=(s.out, 16 * ((s.in_ + 15) // 16)), dtype=np.uint32)
+            fields[:, s.in_:] = 0
+            gm = np.zeros((s.out, fields.shape[1] // 16), dtype=np.uint32)
+            for t in range(16):
+                gm |= fields[:, t::16] << np.uint32(2 * t)
+            gm_d = torch.from_numpy(gm.view(np.int32)).to(dev)
+            al = torch.rand(s.out * ng, dtype=torch.float32, device=dev) * 0.02
+            mu_g = torch.randn(s.out * ng, dtype=torch.float32, device=dev) * 0.002
+            Y = torch.empty(s.out, dtype=torch.float32, device=dev)
+            call = lambda: B.btc_gemv_groups(s, p["packed"], p["codebook"], al, mu_g, gm_d, ng, p["x"], Y, B.BTC_F32)
+            call()
+            torch.cuda.synchronize()
+            e0, e1 = events()
+            e0.record()
+            for _ in range(50):
+                call()
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) / 50 * 1e3
+            nbytes = p["packed"].numel() * 4 + gm.nbytes + s.out * ng * 8
+            groups[f"{s.out}x{s.in_}"] = dict(groups=ng, us=round(us, 1), stored_bytes=int(nbytes),
+                                             gbs=round(nbytes / us / 1e3, 1))
+            del p, gm_d, Y
+
     # ---- the online activation transform in front of the layer (btc_transform), on the two input widths of
     # the 13B layer: decode rows from a captured graph of 20 launches, prefill rows event-timed
     transform = None
@@ -748,6 +782,7 @@ def main():
             "note": f"2*M*out*in flop of the 7 projections at M={args.gemm_m} / event-timed btc_gemm calls "
                     "(whole calls)"},
         "act_quant": act_quant,
+        "gemv_groups": groups,
         "transform": transform,
         "assign": assign,
         "cpu_baseline": cpu,

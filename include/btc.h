@@ -267,6 +267,20 @@ btc_status btc_gemm_aq(void* stream, const btc_shape* s, const uint32_t* packed,
                        const float* step, int32_t M, void* Y, btc_dtype y_dtype, void* workspace,
                        size_t workspace_bytes);
 
+/* Decode-time product for the storage variant with several (alpha, mu) pairs per weight row (Table "Study of
+ * Number of Split Points"; appendix hyper-parameters: 2 split points by default):
+ *   W_hat[i][k] = alpha[i][g] * B_hat[i][k] + mu[i][g],   g = group[i][k] in [0, ngroups),  ngroups 1..4
+ *   y[i] = sum_k W_hat[i][k] * x[k]
+ *   alpha, mu : float [out][ngroups], row-major
+ *   group_map : uint32 [out][ceil(2 in / 32)]: the group of weight k of row i in bits [2k, 2k+2) of row i's
+ *               map, bit p of a row's map being bit (p & 31) of its word (p >> 5); values >= ngroups must not occur
+ *   x : fp16 [in] (one activation row);  y : [out] of y_dtype (BTC_F16 or BTC_F32);  in <= 32768
+ * packed and codebook as for btc_gemv.  fp32 sums in a fixed order.  No workspace.  Enqueues and returns.
+ * Errors: BTC_ERR_NULL, _SHAPE, _UNSUPPORTED (ngroups, in, y_dtype), _ALIGN, _HIP. */
+btc_status btc_gemv_groups(void* stream, const btc_shape* s, const uint32_t* packed, const uint32_t* codebook,
+                           const float* alpha, const float* mu, const uint32_t* group_map, int32_t ngroups,
+                           const void* x, void* y, btc_dtype y_dtype);
+
 /* Host. Static string for a status code. */
 const char* btc_status_str(btc_status st);
 

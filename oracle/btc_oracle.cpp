@@ -203,15 +203,16 @@ void btc_oracle_materialise_groups(const uint32_t* packed, const uint32_t* codeb
     for (long j = 0; j < nchunks; ++j) {
       uint32_t code = 0;
       for (int q = 0; q < b; ++q) {
-        const long p = j * b + q;
-        code |= ((row[p >> 5] >> (p & 31)) & 1u) << q;
+        const long p = j * b + q;                                  // bit q of index j, LSB-first stream
+        const uint32_t bit = (row[p / 32] >> (p % 32)) & 1u;
+        code += bit << q;
       }
       const uint32_t pattern = codebook[code];
       for (int t = 0; t < v; ++t) {
         const long k = j * v + t;
         if (k >= in) break;
         const int g = (int)((grow[(2 * k) >> 5] >> ((2 * k) & 31)) & 3u);
-        const double sgn = ((pattern >> t) & 1u) ? 1.0 : -1.0;
+        const double sgn = (pattern & (1u << t)) != 0u ? 1.0 : -1.0;   // bit t set: +1
         W[r * in + k] = (double)alpha[i * G + g] * sgn + (double)mu[i * G + g];
       }
     }

@@ -77,6 +77,8 @@ def lib() -> ctypes.CDLL:
         L.btc_weight_rowsums.argtypes = [vp, sp, vp, vp, vp, vp, vp, vp, sz]
         L.btc_gemm_aq.restype = ctypes.c_int
         L.btc_gemm_aq.argtypes = [vp, sp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, ctypes.c_int, vp, sz]
+        L.btc_gemv_groups.restype = ctypes.c_int
+        L.btc_gemv_groups.argtypes = [vp, sp, vp, vp, vp, vp, vp, i32, vp, vp, ctypes.c_int]
         L.btc_status_str.restype = ctypes.c_char_p
         L.btc_status_str.argtypes = [ctypes.c_int]
         _lib = L
@@ -188,6 +190,12 @@ def btc_gemm_aq(s: BtcShape, packed, codebook, alpha, mu, wsum, Q, lo, step, M: 
     _check(lib().btc_gemm_aq(_stream(stream), ctypes.byref(s), _ptr(packed), _ptr(codebook), _ptr(alpha), _ptr(mu),
                              _ptr(wsum), _ptr(Q), _ptr(lo), _ptr(step), M, _ptr(Y), y_dtype, _ptr(workspace),
                              _nbytes(workspace)), "btc_gemm_aq")
+
+
+def btc_gemv_groups(s: BtcShape, packed, codebook, alpha, mu, group_map, ngroups: int, x, y, y_dtype: int,
+                    stream=None) -> None:
+    _check(lib().btc_gemv_groups(_stream(stream), ctypes.byref(s), _ptr(packed), _ptr(codebook), _ptr(alpha), _ptr(mu),
+                                 _ptr(group_map), ngroups, _ptr(x), _ptr(y), y_dtype), "btc_gemv_groups")
 
 
 def btc_assign(vectors, N: int, v: int, codebook, K: int, z, dist2=None, stream=None) -> None:

@@ -62,6 +62,9 @@ MUTANTS = [
      "const int g = (int)((grow[k >> 5] >> (k & 31)) & 1u);", "test_groups_pins.py"),
     ("groups_mean_of_group_zero", "W[r * in + k] = (double)alpha[i * G + g] * sgn + (double)mu[i * G + g];",
      "W[r * in + k] = (double)alpha[i * G + g] * sgn + (double)mu[i * G];", "test_groups_pins.py"),
+    ("groups_sign_map_flipped", "const double sgn = (pattern & (1u << t)) != 0u ? 1.0 : -1.0;",
+     "const double sgn = (pattern & (1u << t)) != 0u ? -1.0 : 1.0;", "test_groups_pins.py"),
+    ("groups_index_bits_reversed", "code += bit << q;", "code += bit << (b - 1 - q);", "test_groups_pins.py"),
     ("groups_parameters_transposed", "W[r * in + k] = (double)alpha[i * G + g] * sgn + (double)mu[i * G + g];",
      "W[r * in + k] = (double)alpha[g * out + i] * sgn + (double)mu[g * out + i];", "test_groups_pins.py"),
     ("mstep_empty_cluster_cleared", "if (size == 0) continue;", "if (size == 0) { codebook[k] = 0; continue; }",
