@@ -649,6 +649,46 @@ def main():
         torch.cuda.synchronize()
         transform["decoder_layer_decode_with_4_transforms_us"] = round(e0.elapsed_time(e1) * 1e3 / (5 * args.layers), 2)
         transform["decoder_layer_decode_without_us"] = round(ms_per_step * 1e3, 2)
+        # the same layer through btc_gemv_transformed: the first consumer of a transformed row computes it inside
+        # its own kernel (every workgroup, on the matrix cores, factors prepared once) and hands it to the others;
+        # factor sizes without a fused kernel (the input of down) run as the two launches inside the call
+        prep = {}
+        for n, (n1, n2, bd, p1d, p2d, xt) in tr.items():
+            nb = B.btc_transform_prepared_bytes(n1, n2)
+            prep[n] = None
+            if nb:
+                prep[n] = torch.empty(nb, dtype=torch.uint8, device=dev)
+                B.btc_transform_prepare(n1, n2, p1d, p2d, prep[n])
+
+        def run_layer_f(L):
+            for ci, c in enumerate(calls_per_layer[L]):
+                p = c["p"]
+                n1, n2, bd, p1d, p2d, xt = tr[p["s"].in_]
+                if ci in (0, 3, 4, 6):
+                    B.btc_gemv_transformed(p["s"], c["packed"], p["codebook"], p["alpha"], p["mu"], p["x"], n1, n2, bd, p1d,
+                                           p2d, prep[p["s"].in_], c["y"], B.BTC_F16, ws, xt_out=xt)
+                else:
+                    B.btc_gemv(p["s"], c["packed"], p["codebook"], p["alpha"], p["mu"], xt, 1, c["y"], B.BTC_F16, ws)
+
+        run_layer_f(0)
+        torch.cuda.synchronize()
+        gf = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gf):
+            for L in range(args.layers):
+                run_layer_f(L)
+        gf.replay()
+        torch.cuda.synchronize()
+        e0, e1 = events()
+        e0.record()
+        for _ in range(5):
+            gf.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        fused_us = e0.elapsed_time(e1) * 1e3 / (5 * args.layers)
+        transform["decoder_layer_decode_fused_us"] = round(fused_us, 2)
+        transform["fused_over_without"] = round(fused_us / (ms_per_step * 1e3), 3)
+        transform["two_launches_over_without"] = round(
+            transform["decoder_layer_decode_with_4_transforms_us"] / (ms_per_step * 1e3), 3)
 
     # ---- E-step of the codebook clustering (btc_assign): the length-10 vectors of a 5120 x 5120 and of a
     # 13824 x 5120 sign matrix against 256 centroids; a setting with long vectors (no pattern table)

@@ -193,6 +193,38 @@ btc_status btc_transform(void* stream, const void* X, btc_dtype x_dtype, int32_t
                          int32_t n2, const uint32_t* sign_bits, const float* P1, const float* P2,
                          void* Y, btc_dtype y_dtype);
 
+/* The decode-time product behind the online activation transform, as one call (sections "Learnable
+ * Transformation" and "Integration into Transformer Architecture": every compressed layer sees X T):
+ *   y[i] = sum_k W_hat[i][k] * x'[k],   x' = fp16( x T ),  T as in btc_transform, n1 * n2 = in
+ * i.e. btc_transform (one fp16 row in, fp16 out) followed by btc_gemv (batch 1), without the second launch
+ * where the fused engine covers the setting.
+ *
+ * btc_transform_prepared_bytes / btc_transform_prepare: once per layer, the factors P1, P2 are split into
+ * pairs of fp16 numbers and laid out as matrix-core operands in `prepared` (device memory owned by the
+ * caller, 16-byte aligned, at least btc_transform_prepared_bytes(n1, n2) bytes; that size is 0 when no fused
+ * kernel exists for the factor sizes: there is one for 64 x 64 and 64 x 80).  Entries of P1 and P2 must be at
+ * most 65504 in magnitude.  Enqueues and returns.  Errors: BTC_ERR_NULL, _SHAPE, _UNSUPPORTED (factor
+ * sizes), _WORKSPACE (prepared_bytes too small), _ALIGN, _HIP.
+ *
+ * btc_gemv_transformed: x fp16 [in]; y [out] of y_dtype (BTC_F16 or BTC_F32); sign_bits, P1, P2 as for
+ * btc_transform; `prepared` from btc_transform_prepare for the same n1, n2, P1, P2, or NULL; xt_out: fp16
+ * [in], receives x' for other consumers of the same transformed row (launched later on the stream), or NULL.
+ * With `prepared`, v = 10 and 7..10 index bits the call is one kernel: every workgroup computes x' into LDS on
+ * the matrix cores (fp32 accumulation; factors and intermediate carried as two fp16 parts, 2^-22 relative)
+ * and needs no workspace.  Otherwise it runs btc_transform (into xt_out, else into the head of the workspace)
+ * and btc_gemv: then `workspace` must hold btc_gemv_transformed_workspace_bytes(s) bytes and follow the
+ * rules of btc_gemv's workspace (zero-filled before first use).  x and xt_out must not overlap.  Errors: as
+ * btc_gemv and btc_transform, _SHAPE also when n1 * n2 != in. */
+size_t btc_transform_prepared_bytes(int32_t n1, int32_t n2);
+btc_status btc_transform_prepare(void* stream, int32_t n1, int32_t n2, const float* P1, const float* P2,
+                                 void* prepared, size_t prepared_bytes);
+size_t btc_gemv_transformed_workspace_bytes(const btc_shape* s);
+btc_status btc_gemv_transformed(void* stream, const btc_shape* s, const uint32_t* packed,
+                                const uint32_t* codebook, const float* alpha, const float* mu, const void* x,
+                                int32_t n1, int32_t n2, const uint32_t* sign_bits, const float* P1,
+                                const float* P2, const void* prepared, void* xt_out, void* y,
+                                btc_dtype y_dtype, void* workspace, size_t workspace_bytes);
+
 /* E-step of the binary codebook clustering (section "Flash and Accurate Binary
  * Codebook", step "E-step Assignment": z_i = argmin_k ||b_i - c_k||^2, which for
  * +-1 vectors is 4 * POPCNT(b_i xor c_k); a vector identical to a centroid goes to

@@ -77,6 +77,15 @@ def lib() -> ctypes.CDLL:
         L.btc_weight_rowsums.argtypes = [vp, sp, vp, vp, vp, vp, vp, vp, sz]
         L.btc_gemm_aq.restype = ctypes.c_int
         L.btc_gemm_aq.argtypes = [vp, sp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, ctypes.c_int, vp, sz]
+        L.btc_transform_prepared_bytes.restype = ctypes.c_size_t
+        L.btc_transform_prepared_bytes.argtypes = [i32, i32]
+        L.btc_transform_prepare.restype = ctypes.c_int
+        L.btc_transform_prepare.argtypes = [vp, i32, i32, vp, vp, vp, ctypes.c_size_t]
+        L.btc_gemv_transformed_workspace_bytes.restype = ctypes.c_size_t
+        L.btc_gemv_transformed_workspace_bytes.argtypes = [sp]
+        L.btc_gemv_transformed.restype = ctypes.c_int
+        L.btc_gemv_transformed.argtypes = [vp, sp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp,
+                                           ctypes.c_size_t]
         L.btc_gemv_groups.restype = ctypes.c_int
         L.btc_gemv_groups.argtypes = [vp, sp, vp, vp, vp, vp, vp, i32, vp, vp, ctypes.c_int]
         L.btc_status_str.restype = ctypes.c_char_p
@@ -190,6 +199,27 @@ def btc_gemm_aq(s: BtcShape, packed, codebook, alpha, mu, wsum, Q, lo, step, M: 
     _check(lib().btc_gemm_aq(_stream(stream), ctypes.byref(s), _ptr(packed), _ptr(codebook), _ptr(alpha), _ptr(mu),
                              _ptr(wsum), _ptr(Q), _ptr(lo), _ptr(step), M, _ptr(Y), y_dtype, _ptr(workspace),
                              _nbytes(workspace)), "btc_gemm_aq")
+
+
+def btc_transform_prepared_bytes(n1: int, n2: int) -> int:
+    return lib().btc_transform_prepared_bytes(n1, n2)
+
+
+def btc_transform_prepare(n1: int, n2: int, P1, P2, prepared, stream=None) -> None:
+    _check(lib().btc_transform_prepare(_stream(stream), n1, n2, _ptr(P1), _ptr(P2), _ptr(prepared), _nbytes(prepared)),
+           "btc_transform_prepare")
+
+
+def btc_gemv_transformed_workspace_bytes(s: BtcShape) -> int:
+    return lib().btc_gemv_transformed_workspace_bytes(ctypes.byref(s))
+
+
+def btc_gemv_transformed(s: BtcShape, packed, codebook, alpha, mu, x, n1: int, n2: int, sign_bits, P1, P2, prepared, y,
+                         y_dtype: int, workspace=None, xt_out=None, stream=None) -> None:
+    _check(lib().btc_gemv_transformed(_stream(stream), ctypes.byref(s), _ptr(packed), _ptr(codebook), _ptr(alpha),
+                                      _ptr(mu), _ptr(x), n1, n2, _ptr(sign_bits), _ptr(P1), _ptr(P2), _ptr(prepared),
+                                      _ptr(xt_out), _ptr(y), y_dtype, _ptr(workspace), _nbytes(workspace)),
+           "btc_gemv_transformed")
 
 
 def btc_gemv_groups(s: BtcShape, packed, codebook, alpha, mu, group_map, ngroups: int, x, y, y_dtype: int,

@@ -46,6 +46,7 @@
 #include <cstdlib>
 #include <type_traits>
 
+#include "btc_fused_transform.h"
 #include "btc_internal.h"
 
 namespace btc {
@@ -54,6 +55,7 @@ namespace fp4 {
 typedef __attribute__((ext_vector_type(8))) int i32x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((address_space(3))) unsigned long long lds_u64;
 
 constexpr uint32_t kOob = 0x80000000u;   // buffer offset that is always out of range (buffers are < 2 GiB)
@@ -63,7 +65,12 @@ constexpr int kSetBytes = 2048;          // B operands of four steps: 16 columns
 
 // CW column waves per team: 8, two teams (LDS permitting) -- or 16 in one team for rows of more than 15360
 // weights ("wide"), where every wave prepares its own B operands, one set at a time, in a small buffer.
-template <int V, int B, int T, int TEAMS, int CW>
+constexpr int kLdsMax = 160 * 1024 - 64;
+
+// FUSED: the kernel first computes the transformed activation row into an LDS area of its own (fp16, the whole
+// reach of the strands, zeros past the end of the row) and takes its activations from there; the table then gets
+// as many copies as still fit.
+template <int V, int B, int T, int TEAMS, int CW, bool FUSED = false>
 struct Cfg {
   static constexpr int W = CW * TEAMS;                      // waves per workgroup
   static constexpr bool WIDE = CW == 16;
@@ -78,15 +85,21 @@ struct Cfg {
   static constexpr int NLD = (16 + RPI - 1) / RPI;          // load instructions per row block
   static constexpr int S = 4 * ((LPR + 1) | 1);             // staged row stride in words: an odd number of 16-byte
                                                             // pieces, so that the 16 rows start in 16 different banks
-  static constexpr int C = (B <= 8) ? 32 : (B == 9) ? 16 : 8;   // table copies (32: no two lanes of a wave share a bank pair)
-  static constexpr int LOG2C = C == 32 ? 5 : (C == 16 ? 4 : 3);
-  static constexpr int kTableBytes = (1 << B) * C * 8;
   static constexpr int kRedBytes = (2 * W * 16 * 4 + W * 4 + CW * 2 * 4 + 15) & ~15;
   static constexpr int kIdxBytes = W * 16 * S * 4;          // one staged row block per wave
   static constexpr int NSET = (T + 3) / 4;                  // B register sets
   static constexpr int kStageBytes = WIDE ? 0 : CW * NSET * kSetBytes;   // wide: the wave's index area serves first
   static_assert(!WIDE || 16 * S * 4 >= kSetBytes, "a set fits the wave's index area");
-  static constexpr int kLdsBytes = kTableBytes + kRedBytes + kIdxBytes + kStageBytes;
+  static constexpr int kXfElems = CW * 4 * L * V;           // elements the strands of a team reach
+  static constexpr int kXfBytes = FUSED ? ((kXfElems * 2 + 15) & ~15) : 0;
+  static constexpr int kRestBytes = kRedBytes + kIdxBytes + kStageBytes + kXfBytes;
+  static constexpr int C0 = (B <= 8) ? 32 : (B == 9) ? 16 : 8;  // table copies (32: no two lanes of a wave share a bank pair)
+  static constexpr bool fits(int c) { return (1 << B) * c * 8 + kRestBytes <= kLdsMax; }
+  static constexpr int C = (!FUSED || fits(C0)) ? C0 : (C0 >= 16 && fits(C0 / 2)) ? C0 / 2 : (C0 >= 32 && fits(C0 / 4)) ? C0 / 4 : C0;
+  static constexpr int LOG2C = C == 32 ? 5 : (C == 16 ? 4 : 3);
+  static constexpr int kTableBytes = (1 << B) * C * 8;
+  static constexpr int kLdsBytes = kTableBytes + kRestBytes;
+  static constexpr int kExchangeBytes = kIdxBytes + kStageBytes;   // FUSED: the tiles of the intermediate pass through here
   static_assert(V == 9 || V == 10, "three chunks per operand, tails of one or two elements");
   static_assert(B >= 7 && B <= 10, "table of at most 64 KB");
   static_assert(LPR <= 32, "at least two rows per load instruction");
@@ -162,12 +175,16 @@ __device__ unsigned long long g_stamps[4 * 64];
 // e < 24: c = e / 8, u = e % 8;  24 <= e < 24 + 3 TAIL: c = (e - 24) / TAIL, u = 8 + (e - 24) % TAIL;  else padding.
 // The same order is used for the activations on the B side.
 
-template <int V, int B, int T, int TEAMS, int CW>
+// GN1, GN2: factor sizes of the activation transform computed in front of the product (0, 0: none).
+template <int V, int B, int T, int TEAMS, int CW, int GN1, int GN2>
 __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
     Dims d, const uint32_t* __restrict__ packed, const uint32_t* __restrict__ codebook,
     const float* __restrict__ alpha, const float* __restrict__ mu, const __half* __restrict__ x,
-    void* __restrict__ y, int y_is_f32, int n_rb, int x_dword) {
-  using K = Cfg<V, B, T, TEAMS, CW>;
+    void* __restrict__ y, int y_is_f32, int n_rb, int x_dword, ftr::Geo geo) {
+  constexpr bool FUSED = GN1 > 0;
+  using K = Cfg<V, B, T, TEAMS, CW, FUSED>;
+  using FT = ftr::Fixed<GN1, GN2>;
+  static_assert(!FUSED || V == 10, "the fused prologue reads aligned pairs of activations from LDS");
   constexpr bool WIDE = K::WIDE;
   constexpr int W = K::W, G = K::G, TAIL = K::TAIL, ND = K::ND, C = K::C, L = K::L;
   constexpr int LPR = K::LPR, RPI = K::RPI, NLD = K::NLD, S = K::S;
@@ -178,6 +195,7 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
   int* scl = (int*)(sxp + W);                                                   // [CW][2] block scale exponents
   uint32_t* idx_all = (uint32_t*)(smem + K::kTableBytes + K::kRedBytes);       // [W][16][S]
   unsigned char* bstage_all = smem + K::kTableBytes + K::kRedBytes + K::kIdxBytes;  // [CW][NSET][2048]; wide: [W][2048]
+  uint16_t* xf = (uint16_t*)(smem + K::kTableBytes + K::kRedBytes + K::kIdxBytes + K::kStageBytes);   // FUSED: [kXfElems]
 
   const int tid = threadIdx.x, lane = tid & 63;
   STAMP(0);
@@ -204,6 +222,26 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
   // wide: one half item (8 slots) per lane and set: step 4 tt + lane / 16, strand (lane / 4) % 4, half (lane / 2) % 2,
   // quarter lane % 2 -- chunk 0, chunk 1, chunk 2 (elements 0..7 each) or the three tails
   uint32_t hw[WIDE ? K::NSET : 1][4];
+  // 16 or 4 bytes of the activation row at a byte offset (a multiple of 4), zeros when !ok or past the end of the
+  // row: from global memory, or (FUSED) from the transformed row in LDS, which holds zeros past the end
+  auto xl128 = [&](bool ok, uint32_t off) __attribute__((always_inline)) -> u32x4 {
+    if constexpr (FUSED) {
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (ok) {
+        const uint32_t* p = (const uint32_t*)((const unsigned char*)xf + off);
+        v = u32x4{p[0], p[1], p[2], p[3]};
+      }
+      return v;
+    } else {
+      const auto t4 = __builtin_amdgcn_raw_buffer_load_b128(rx, ok ? off : kOob, 0, 0);
+      return u32x4{t4[0], t4[1], t4[2], t4[3]};
+    }
+  };
+  auto xl32 = [&](bool ok, uint32_t off) __attribute__((always_inline)) -> uint32_t {
+    if constexpr (FUSED) return ok ? *(const uint32_t*)((const unsigned char*)xf + off) : 0u;
+    else return __builtin_amdgcn_raw_buffer_load_b32(rx, ok ? off : kOob, 0, 0);
+  };
+  auto load_items = [&]() __attribute__((always_inline)) {
   if constexpr (WIDE) {
 #pragma unroll
     for (int tt = 0; tt < K::NSET; ++tt) {
@@ -211,12 +249,12 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
       const uint32_t xb = (uint32_t)((cw * 4 + qa) * L + G * t) * V;
       const bool live = t < T;
       if (x_dword) {
-        const auto a4 = __builtin_amdgcn_raw_buffer_load_b128(rx, (live && part < 3) ? (xb + part * V) * 2u : kOob, 0, 0);
+        const u32x4 a4 = xl128(live && part < 3, (xb + part * V) * 2u);
         uint32_t tl[3] = {0u, 0u, 0u};
         if constexpr (TAIL == 2) {
 #pragma unroll
           for (int c = 0; c < 3; ++c)
-            tl[c] = __builtin_amdgcn_raw_buffer_load_b32(rx, (live && part == 3) ? (xb + c * V + 8u) * 2u : kOob, 0, 0);
+            tl[c] = xl32(live && part == 3, (xb + c * V + 8u) * 2u);
         }
         hw[tt][0] = part < 3 ? a4[0] : tl[0];
         hw[tt][1] = part < 3 ? a4[1] : tl[1];
@@ -246,11 +284,11 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
     // half 0: chunk 0 elements 0..7, chunk 1 elements 0..7; half 1: chunk 2 elements 0..7, then the tails
     const uint32_t run0 = h == 0 ? xb : xb + 2u * V;
     if (x_dword) {        // V and `in` even: every pair of elements is one aligned word
-      const auto a4 = __builtin_amdgcn_raw_buffer_load_b128(rx, live ? run0 * 2u : kOob, 0, 0);
+      const u32x4 a4 = xl128(live, run0 * 2u);
 #pragma unroll
       for (int k = 0; k < 4; ++k) hx[ii][k] = a4[k];
       {
-        const auto b4 = __builtin_amdgcn_raw_buffer_load_b128(rx, (live && h == 0) ? (xb + V) * 2u : kOob, 0, 0);
+        const u32x4 b4 = xl128(live && h == 0, (xb + V) * 2u);
 #pragma unroll
         for (int k = 0; k < 4; ++k) hx[ii][4 + k] = b4[k];
       }
@@ -259,7 +297,7 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
           uint32_t tl[3];
 #pragma unroll
           for (int c = 0; c < 3; ++c)
-            tl[c] = __builtin_amdgcn_raw_buffer_load_b32(rx, (live && h == 1) ? (xb + c * V + 8u) * 2u : kOob, 0, 0);
+            tl[c] = xl32(live && h == 1, (xb + c * V + 8u) * 2u);
           if (h == 1) {
             hx[ii][4] = tl[0];
             hx[ii][5] = tl[1];
@@ -288,6 +326,9 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
       for (int k = 0; k < 8; ++k) hx[ii][k] = hv[2 * k] | (hv[2 * k + 1] << 16);
     }
   }
+
+  };   // load_items
+  if constexpr (!FUSED) load_items();
 
   // ---- index words.  The wave's four strands are one contiguous piece of every row: LPR lanes fetch it as
   // 16-byte pieces (neighbouring lanes read neighbouring addresses), RPI rows per instruction; the pieces go
@@ -326,6 +367,10 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
   // first burst, instead of queueing behind the later row blocks of the waves that happened to issue first.
   uint4 D0[NLD];
   load_block(rb_first, D0);
+  // the operands of the transform are requested after the first index words: they queue behind them in the
+  // memory pipeline of the compute unit and are needed later
+  typename FT::Ring ring;
+  if constexpr (FUSED) FT::ring_begin(geo, (const uint16_t*)x, wave, lane, ring);
   STAMP(1);
 
   // ---- codebook -> table of nibble patterns, every entry C times.  Thread k writes its entry's copies in
@@ -342,6 +387,21 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
   }
   STAMP(2);
 
+  if constexpr (FUSED) {
+    // the transformed row: zeros past its end, the row itself by the matrix cores; the tiles of the intermediate
+    // pass through the index and staging areas, which nothing has used yet
+    for (int i = d.in + tid; i < K::kXfElems; i += W * 64) xf[i] = 0;
+    static_assert(!FUSED || 2 * ftr::Fixed<GN1, GN2>::NT <= W, "a wave per tile and stage");
+    FT::transform_row(wave, lane, ring, xf, (uint4*)idx_all);
+    STAMP(3);
+    __syncthreads();
+    STAMP(4);
+    if (geo.xt_out != nullptr && blockIdx.x == 0)      // the row for other consumers of the same transform
+      for (int i = tid; i < d.in / 2; i += W * 64) ((uint32_t*)geo.xt_out)[i] = ((const uint32_t*)xf)[i];
+    load_items();
+    __syncthreads();   // the exchange area becomes the staging area again
+    STAMP(60);
+  }
   if (!WIDE && (T & 3)) {   // B columns of steps that do not exist must not hold junk (the two teams share the clearing)
     uint4* z = (uint4*)(bstage + (K::NSET - 1) * kSetBytes + (T & 3) * 512) + team * ((4 - (T & 3)) * 32 / TEAMS);
     for (int i = lane; i < (4 - (T & 3)) * 32 / TEAMS; i += 64) z[i] = make_uint4(0, 0, 0, 0);
@@ -532,7 +592,7 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
         for (int g = 0; g < G; ++g) {
           const int pos = (t * G + g) * B, w = pos >> 5, sb = pos & 31;
           uint32_t ofs;
-          if (B == 8) {
+          if (B == 8 && C == 32) {
             // byte-aligned indices, 32 copies: offset = index << 8 | copy, assembled by one byte permute
             ofs = __builtin_amdgcn_perm(R[w], lane_copy, 0x0C0C0000u | ((4u + (sb >> 3)) << 8));
           } else {
@@ -607,18 +667,23 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
   STAMP(63);
 }
 
-constexpr int kLdsMax = 160 * 1024 - 64;
-
-template <int V, int B, int T, int TEAMS, int CW>
+template <int V, int B, int T, int TEAMS, int CW, int GN1, int GN2>
 static btc_status launch3(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
-                          const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, bool dry) {
-  using K = Cfg<V, B, T, TEAMS, CW>;
+                          const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, bool dry,
+                          const ftr::Geo* geo) {
+  constexpr bool FUSED = GN1 > 0;
+  using K = Cfg<V, B, T, TEAMS, CW, FUSED>;
   static_assert(K::kLdsBytes <= kLdsMax, "LDS budget");
+  ftr::Geo g{};
+  if constexpr (FUSED) {
+    static_assert(ftr::exchange_bytes_c(GN1, GN2) <= K::kExchangeBytes, "the tiles of the intermediate fit");
+    g = *geo;
+  }
   if (dry) return BTC_OK;         // only asked whether a kernel exists for this setting
   static bool attr_set = false;   // one-time kernel attribute, not call state
   if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)gemv_fp4_kernel<V, B, T, TEAMS, CW>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            K::kLdsBytes) != hipSuccess)
+    if (hipFuncSetAttribute((const void*)gemv_fp4_kernel<V, B, T, TEAMS, CW, GN1, GN2>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, K::kLdsBytes) != hipSuccess)
       return BTC_ERR_HIP;
     attr_set = true;
   }
@@ -626,17 +691,17 @@ static btc_status launch3(hipStream_t q, const Dims& d, const uint32_t* packed, 
   const int slots = 256 * TEAMS;                         // one workgroup per compute unit, TEAMS row blocks at a time
   const int grid = n_rb < slots ? (n_rb + TEAMS - 1) / TEAMS : 256;
   const int x_dword = (V % 2 == 0) && (d.in % 2 == 0);
-  gemv_fp4_kernel<V, B, T, TEAMS, CW><<<grid, K::W * 64, K::kLdsBytes, q>>>(d, packed, codebook, alpha, mu, (const __half*)x,
-                                                                          y, y_is_f32, n_rb, x_dword);
+  gemv_fp4_kernel<V, B, T, TEAMS, CW, GN1, GN2><<<grid, K::W * 64, K::kLdsBytes, q>>>(
+      d, packed, codebook, alpha, mu, (const __half*)x, y, y_is_f32, n_rb, x_dword, g);
   return launch_status();
 }
 
 // Steps per row block: the 4 CW strands of a team must cover the row.  Instantiated for a few step counts; a
 // strand that is longer than needed reads zeros for the activations past the end of the row.
-static int steps_for(const Dims& d, int cw) {
-  const int need = (d.nchunks + cw * 4 * 3 - 1) / (cw * 4 * 3);
-  static const int have[] = {3, 4, 5, 6, 8, 9, 10, 12, 15, 16};
-  static const int have_wide[] = {9, 10, 12, 15, 16};     // 17 steps no longer fit 128 registers
+constexpr int steps_for_chunks(int nchunks, int cw) {
+  const int need = (nchunks + cw * 4 * 3 - 1) / (cw * 4 * 3);
+  constexpr int have[] = {3, 4, 5, 6, 8, 9, 10, 12, 15, 16};
+  constexpr int have_wide[] = {9, 10, 12, 15, 16};        // 17 steps no longer fit 128 registers
   if (cw == 8) {
     for (int t : have) if (need <= t) return t;
   } else {
@@ -644,24 +709,25 @@ static int steps_for(const Dims& d, int cw) {
   }
   return 0;
 }
+static int steps_for(const Dims& d, int cw) { return steps_for_chunks(d.nchunks, cw); }
 
 template <int V, int B>
 static btc_status launch2(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
                           const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, bool dry) {
   // two teams whenever table, staging areas and B operands of 16 waves fit the LDS
-#define BTC_FP4_CASE(TT)                                                                             \
-  case TT:                                                                                           \
-    if constexpr (Cfg<V, B, TT, 2, 8>::kLdsBytes <= kLdsMax)                                         \
-      return launch3<V, B, TT, 2, 8>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry);        \
-    else if constexpr (Cfg<V, B, TT, 1, 8>::kLdsBytes <= kLdsMax)                                    \
-      return launch3<V, B, TT, 1, 8>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry);        \
-    else                                                                                             \
+#define BTC_FP4_CASE(TT)                                                                                   \
+  case TT:                                                                                                 \
+    if constexpr (Cfg<V, B, TT, 2, 8>::kLdsBytes <= kLdsMax)                                               \
+      return launch3<V, B, TT, 2, 8, 0, 0>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry, nullptr); \
+    else if constexpr (Cfg<V, B, TT, 1, 8>::kLdsBytes <= kLdsMax)                                          \
+      return launch3<V, B, TT, 1, 8, 0, 0>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry, nullptr); \
+    else                                                                                                   \
       break;
-#define BTC_FP4_WIDE(TT)                                                                             \
-  case TT:                                                                                           \
-    if constexpr (Cfg<V, B, TT, 1, 16>::kLdsBytes <= kLdsMax)                                        \
-      return launch3<V, B, TT, 1, 16>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry);       \
-    else                                                                                             \
+#define BTC_FP4_WIDE(TT)                                                                                   \
+  case TT:                                                                                                 \
+    if constexpr (Cfg<V, B, TT, 1, 16>::kLdsBytes <= kLdsMax)                                              \
+      return launch3<V, B, TT, 1, 16, 0, 0>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry, nullptr); \
+    else                                                                                                   \
       break;
   switch (steps_for(d, 8)) {
     BTC_FP4_CASE(3) BTC_FP4_CASE(4) BTC_FP4_CASE(5) BTC_FP4_CASE(6) BTC_FP4_CASE(8) BTC_FP4_CASE(9)
@@ -687,6 +753,34 @@ static btc_status launch1(hipStream_t q, const Dims& d, const uint32_t* packed, 
   return BTC_ERR_UNSUPPORTED;
 }
 
+// The product behind the transform: chunk length 10, the row is the N1 x N2 activation matrix, so the step count is
+// a constant too; two teams of eight column waves (16 waves: up to eight tiles per stage).
+template <int B, int N1, int N2>
+static btc_status launch_fused(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
+                               const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, bool dry,
+                               const ftr::Geo* geo) {
+  constexpr int T = steps_for_chunks((N1 * N2 + 9) / 10, 8);
+  if constexpr (T > 0 && 2 * ftr::Fixed<N1, N2>::NT <= 16) {
+    if constexpr (Cfg<10, B, T, 2, 8, true>::kLdsBytes <= kLdsMax &&
+                  ftr::exchange_bytes_c(N1, N2) <= Cfg<10, B, T, 2, 8, true>::kExchangeBytes)
+      return launch3<10, B, T, 2, 8, N1, N2>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry, geo);
+  }
+  return BTC_ERR_UNSUPPORTED;
+}
+
+template <int N1, int N2>
+static btc_status launch_fused_b(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
+                                 const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, bool dry,
+                                 const ftr::Geo* geo) {
+  switch (d.b) {
+    case 7: return launch_fused<7, N1, N2>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry, geo);
+    case 8: return launch_fused<8, N1, N2>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry, geo);
+    case 9: return launch_fused<9, N1, N2>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry, geo);
+    case 10: return launch_fused<10, N1, N2>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry, geo);
+  }
+  return BTC_ERR_UNSUPPORTED;
+}
+
 }  // namespace fp4
 
 #ifdef BTC_FP4_STAMPS
@@ -696,11 +790,23 @@ extern "C" int btc_debug_fp4_stamps(unsigned long long* host, int n) {
 #endif
 
 static btc_status fp4_dispatch(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
-                               const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, bool dry) {
+                               const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, bool dry,
+                               const ftr::Geo* geo = nullptr) {
   if (d.v != 9 && d.v != 10) return BTC_ERR_UNSUPPORTED;
   if (d.b < 7 || d.b > 10) return BTC_ERR_UNSUPPORTED;
   if ((long long)d.out * d.wpr * 4 >= (1LL << 31)) return BTC_ERR_UNSUPPORTED;     // 32-bit byte offsets
   if ((long long)d.nchunks * d.v * 2 >= (1LL << 31)) return BTC_ERR_UNSUPPORTED;
+  if (geo) {
+    // The transformed row is made in LDS first: aligned pairs of activations, and factor sizes with an instantiated
+    // kernel (ftr::geometry_ok) -- the pairs whose product is the hidden width of LLaMA-2 7B and 13B.  Larger
+    // factors (64 x 128 for 8192; 86 x 128, 108 x 128, 128 x 224 for the intermediate widths) are two to four times
+    // the operand traffic and arithmetic per workgroup and no longer fit the registers of a 16-wave workgroup: they
+    // cost more inside every workgroup than as a launch of their own.
+    if (d.v != 10 || geo->n1 * geo->n2 != d.in) return BTC_ERR_UNSUPPORTED;
+    if (geo->n1 == 64 && geo->n2 == 64) return fp4::launch_fused_b<64, 64>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry, geo);
+    if (geo->n1 == 64 && geo->n2 == 80) return fp4::launch_fused_b<64, 80>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry, geo);
+    return BTC_ERR_UNSUPPORTED;
+  }
   if (d.v == 9) return fp4::launch1<9>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry);
   return fp4::launch1<10>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry);
 }
@@ -712,6 +818,19 @@ bool gemv_fp4_covers(const Dims& d) {
 btc_status gemv_fp4(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
                     const float* alpha, const float* mu, const void* x, void* y, int y_is_f32) {
   return fp4_dispatch(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, /*dry=*/false);
+}
+
+bool gemv_fp4_fused_covers(const Dims& d, int n1, int n2) {
+  const ftr::Geo g = ftr::make_geo(nullptr, nullptr, n1, n2);
+  return fp4_dispatch(nullptr, d, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0, /*dry=*/true, &g) == BTC_OK;
+}
+
+btc_status gemv_fp4_fused(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
+                          const float* alpha, const float* mu, const void* x, int n1, int n2, const uint32_t* sign_bits,
+                          const void* prepared, void* xt_out, void* y, int y_is_f32) {
+  ftr::Geo g = ftr::make_geo(sign_bits, prepared, n1, n2);
+  g.xt_out = (uint16_t*)xt_out;
+  return fp4_dispatch(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, /*dry=*/false, &g);
 }
 
 }  // namespace btc
