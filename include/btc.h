@@ -201,8 +201,9 @@ btc_status btc_transform(void* stream, const void* X, btc_dtype x_dtype, int32_t
  *
  * btc_transform_prepared_bytes / btc_transform_prepare: once per layer, the factors P1, P2 are split into
  * pairs of fp16 numbers and laid out as matrix-core operands in `prepared` (device memory owned by the
- * caller, 16-byte aligned, at least btc_transform_prepared_bytes(n1, n2) bytes; that size is 0 when no fused
- * kernel exists for the factor sizes: there is one for 64 x 64 and 64 x 80).  Entries of P1 and P2 must be at
+ * caller, 16-byte aligned, at least btc_transform_prepared_bytes(n1, n2) bytes; that size is 0 when nothing
+ * uses prepared operands of these sizes: the fused kernel exists for 64 x 64 and 64 x 80, a matrix-core
+ * kernel for the transform of one row also for 64 x 128, 86 x 128 and 108 x 128).  Entries of P1 and P2 must be at
  * most 65504 in magnitude.  Enqueues and returns.  Errors: BTC_ERR_NULL, _SHAPE, _UNSUPPORTED (factor
  * sizes), _WORKSPACE (prepared_bytes too small), _ALIGN, _HIP.
  *
@@ -211,8 +212,8 @@ btc_status btc_transform(void* stream, const void* X, btc_dtype x_dtype, int32_t
  * [in], receives x' for other consumers of the same transformed row (launched later on the stream), or NULL.
  * With `prepared`, v = 10 and 7..10 index bits the call is one kernel: every workgroup computes x' into LDS on
  * the matrix cores (fp32 accumulation; factors and intermediate carried as two fp16 parts, 2^-22 relative)
- * and needs no workspace.  Otherwise it runs btc_transform (into xt_out, else into the head of the workspace)
- * and btc_gemv: then `workspace` must hold btc_gemv_transformed_workspace_bytes(s) bytes and follow the
+ * and needs no workspace.  Otherwise it runs the transform as a launch of its own (on the matrix cores where
+ * prepared operands exist, else btc_transform; into xt_out, else into the head of the workspace) and btc_gemv: then `workspace` must hold btc_gemv_transformed_workspace_bytes(s) bytes and follow the
  * rules of btc_gemv's workspace (zero-filled before first use).  x and xt_out must not overlap.  Errors: as
  * btc_gemv and btc_transform, _SHAPE also when n1 * n2 != in. */
 size_t btc_transform_prepared_bytes(int32_t n1, int32_t n2);

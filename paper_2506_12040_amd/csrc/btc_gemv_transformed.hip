@@ -49,13 +49,59 @@ __global__ __launch_bounds__(256) void prepare_kernel(int n1, int n2, int IT, in
 
 static size_t x_region_bytes(const Dims& d) { return (((size_t)d.in * 2) + 255) & ~(size_t)255; }
 
+// The transform of one row as a kernel of its own, from prepared operands: workgroup c computes the 32 output
+// columns j2 of block c for all j1 -- wave a < IT tile (a, c) of stage 1, wave IT + a tile (a, c) of stage 2 -- and
+// stores them as fp16.  Same arithmetic as the fused prologue (it is the same code with a global destination).
+template <int N1, int N2>
+__global__ __launch_bounds__(128 * ((N1 + 31) / 32)) void transform_row_kernel(Geo g, const uint16_t* __restrict__ x,
+                                                                             uint16_t* __restrict__ y) {
+  using FT = Fixed<N1, N2>;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int lane = threadIdx.x & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int c = blockIdx.x;
+  // the tile numbering of Fixed: stage-1 wave a JT + c, stage-2 wave NT + a JT + c
+  const int vw = wv < FT::IT ? wv * FT::JT + c : FT::NT + (wv - FT::IT) * FT::JT + c;
+  typename FT::Ring ring;
+  FT::ring_begin(g, x, vw, lane, ring);
+  FT::transform_row(vw, lane, ring, y, (uint4*)smem);
+}
+
+template <int N1, int N2>
+static btc_status launch_row(hipStream_t q, const Geo& g, const void* x, void* y) {
+  using FT = Fixed<N1, N2>;
+  const size_t lds = exchange_bytes_c(N1, N2);
+  static bool attr_set = false;   // one-time kernel attribute, not call state
+  if (!attr_set) {
+    if (hipFuncSetAttribute((const void*)transform_row_kernel<N1, N2>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds) != hipSuccess)
+      return BTC_ERR_HIP;
+    attr_set = true;
+  }
+  transform_row_kernel<N1, N2><<<FT::JT, 128 * FT::IT, lds, q>>>(g, (const uint16_t*)x, (uint16_t*)y);
+  return launch_status();
+}
+
+// Factor sizes with a row kernel: the pairs of the LLaMA-2 widths with n2 <= 128.
+static bool row_kernel_covers(int n1, int n2) {
+  return (n1 == 64 && (n2 == 64 || n2 == 80 || n2 == 128)) || (n2 == 128 && (n1 == 86 || n1 == 108));
+}
+static btc_status transform_row(hipStream_t q, const Geo& g, const void* x, void* y) {
+  if (g.n1 == 64 && g.n2 == 64) return launch_row<64, 64>(q, g, x, y);
+  if (g.n1 == 64 && g.n2 == 80) return launch_row<64, 80>(q, g, x, y);
+  if (g.n1 == 64 && g.n2 == 128) return launch_row<64, 128>(q, g, x, y);
+  if (g.n1 == 86 && g.n2 == 128) return launch_row<86, 128>(q, g, x, y);
+  if (g.n1 == 108 && g.n2 == 128) return launch_row<108, 128>(q, g, x, y);
+  return BTC_ERR_UNSUPPORTED;
+}
+
 }  // namespace ftr
 }  // namespace btc
 
 extern "C" {
 
 size_t btc_transform_prepared_bytes(int32_t n1, int32_t n2) {
-  if (!btc::ftr::geometry_ok(n1, n2)) return 0;
+  if (!btc::ftr::geometry_ok(n1, n2) && !btc::ftr::row_kernel_covers(n1, n2)) return 0;
   return btc::ftr::prepared_bytes(n1, n2);
 }
 
@@ -64,7 +110,7 @@ btc_status btc_transform_prepare(void* stream, int32_t n1, int32_t n2, const flo
   using namespace btc;
   if (!P1 || !P2 || !prepared) return BTC_ERR_NULL;
   if (n1 <= 0 || n2 <= 0) return BTC_ERR_SHAPE;
-  if (!ftr::geometry_ok(n1, n2)) return BTC_ERR_UNSUPPORTED;
+  if (!ftr::geometry_ok(n1, n2) && !ftr::row_kernel_covers(n1, n2)) return BTC_ERR_UNSUPPORTED;
   if (prepared_bytes < ftr::prepared_bytes(n1, n2)) return BTC_ERR_WORKSPACE;
   if (!aligned16(P1) || !aligned16(P2) || !aligned16(prepared)) return BTC_ERR_ALIGN;
   const ftr::Geo g = ftr::make_geo(nullptr, nullptr, n1, n2);
@@ -105,7 +151,10 @@ btc_status btc_gemv_transformed(void* stream, const btc_shape* s, const uint32_t
   if (!aligned16(workspace)) return BTC_ERR_ALIGN;
   void* xt = xt_out ? xt_out : workspace;
   if (xt == x) return BTC_ERR_UNSUPPORTED;
-  st = btc_transform(stream, x, BTC_F16, 1, n1, n2, sign_bits, P1, P2, xt, BTC_F16);
+  if (prepared && ftr::row_kernel_covers(n1, n2))   // the row on the matrix cores, from the prepared operands
+    st = ftr::transform_row(q, ftr::make_geo(sign_bits, prepared, n1, n2), x, xt);
+  else
+    st = btc_transform(stream, x, BTC_F16, 1, n1, n2, sign_bits, P1, P2, xt, BTC_F16);
   if (st != BTC_OK) return st;
   return btc_gemv(stream, s, packed, codebook, alpha, mu, xt, 1, y, y_dtype, (unsigned char*)workspace + head,
                   workspace_bytes - head);

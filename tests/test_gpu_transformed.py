@@ -60,7 +60,8 @@ def test_transformed_layer_matches_the_oracle(G, oracle, out, n1, n2, v, K, prep
     ws = torch.zeros(B.btc_gemv_transformed_workspace_bytes(dl.shape), dtype=torch.uint8, device="cuda")
     # the fused engine needs no workspace; the two launches refuse to run without one
     fused = prepared is not None and v == 10 and 128 <= K <= 1024 and (n1, n2) in ((64, 64), (64, 80))
-    assert (nb > 0) == ((n1, n2) in ((64, 64), (64, 80)))
+    # prepared operands exist for the fused pairs and for the pairs with a matrix-core kernel for one row
+    assert (nb > 0) == ((n1, n2) in ((64, 64), (64, 80), (64, 128), (86, 128), (108, 128)))
     if not fused:
         from paper_2506_12040_amd import binding as BB
         with pytest.raises(BB.BtcError) as e:
@@ -108,6 +109,7 @@ def test_prepare_argument_errors(G):
     buf = torch.zeros(1 << 17, dtype=torch.uint8, device="cuda")
     assert B.btc_transform_prepared_bytes(64, 80) > 0 and B.btc_transform_prepared_bytes(64, 81) == 0
     assert B.btc_transform_prepared_bytes(129, 64) == 0 and B.btc_transform_prepared_bytes(64, 144) == 0
+    assert B.btc_transform_prepared_bytes(108, 128) == (4 * 8 + 4 * 7) * 2048
     with pytest.raises(BB.BtcError) as e:
         B.btc_transform_prepare(64, 81, P, P, buf)
     assert e.value.status == BB.BTC_ERR_UNSUPPORTED
