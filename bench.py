@@ -79,6 +79,9 @@ def main():
     ap.add_argument("--repeats", type=int, default=5, help="the timed K-step region is run this many times in a row")
     ap.add_argument("--layers", type=int, default=40, help="distinct weight copies walked by consecutive steps")
     ap.add_argument("--mode", choices=["graph", "stream"], default="graph")
+    ap.add_argument("--launches", choices=["grouped", "separate"], default="grouped",
+                    help="grouped: the projections of a decoder layer that share their input (q, k, v; gate, up) go "
+                         "through btc_gemv_multi, one launch per group; separate: seven btc_gemv calls")
     ap.add_argument("--gemm-m", type=int, default=2048)
     ap.add_argument("--gemm-iters", type=int, default=10)
     ap.add_argument("--no-gemm", action="store_true")
@@ -213,52 +216,74 @@ def main():
     torch.cuda.synchronize()
     t_setup = time.time() - t_setup
 
-    def run_layer(L):
+    def run_layer_separate(L):
         for c in calls_per_layer[L]:
             p = c["p"]
             B.btc_gemv(p["s"], c["packed"], p["codebook"], p["alpha"], p["mu"], p["x"], 1, c["y"], B.BTC_F16, ws)
 
-    # ---- warmup
-    for i in range(max(args.warmup, 1)):
-        run_layer(i % args.layers)
-    torch.cuda.synchronize()
+    # q, k, v (calls 0..2) and gate, up (calls 4, 5) share their input: one launch per group
+    GROUPS = [(0, 3), (3, 4), (4, 6), (6, 7)]
 
-    # ---- timed region: exactly `steps` layers, `repeats` times in a row
-    repeats = max(1, args.repeats)
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(repeats + 1)]
-    if args.mode == "graph":
-        full_sweeps, rest = divmod(args.steps, args.layers)
-        g_full = g_rest = None
-        if full_sweeps:
-            g_full = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g_full):
-                for L in range(args.layers):
-                    run_layer(L)
-            g_full.replay()
-        if rest:
-            g_rest = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g_rest):
-                for L in range(rest):
-                    run_layer(L)
-            g_rest.replay()
+    def run_layer_grouped(L):
+        calls = calls_per_layer[L]
+        for (a, b) in GROUPS:
+            p = calls[a]["p"]
+            if b - a == 1:
+                B.btc_gemv(p["s"], calls[a]["packed"], p["codebook"], p["alpha"], p["mu"], p["x"], 1, calls[a]["y"],
+                           B.BTC_F16, ws)
+            else:
+                grp = calls[a:b]
+                B.btc_gemv_multi(p["s"], [c["packed"] for c in grp], [p["codebook"]] * (b - a), [p["alpha"]] * (b - a),
+                                 [p["mu"]] * (b - a), p["x"], [c["y"] for c in grp], B.BTC_F16, ws)
+
+    def time_step(run_fn):
+        """Warm-up, then exactly `steps` layers `repeats` times in a row; returns (ms per step, per repeat)."""
+        for i in range(max(args.warmup, 1)):
+            run_fn(i % args.layers)
         torch.cuda.synchronize()
-        marks[0].record()
-        for r in range(repeats):
-            for _ in range(full_sweeps):
+        reps_ = max(1, args.repeats)
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(reps_ + 1)]
+        if args.mode == "graph":
+            full_sweeps, rest = divmod(args.steps, args.layers)
+            g_full = g_rest = None
+            if full_sweeps:
+                g_full = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g_full):
+                    for L in range(args.layers):
+                        run_fn(L)
                 g_full.replay()
-            if g_rest is not None:
+            if rest:
+                g_rest = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g_rest):
+                    for L in range(rest):
+                        run_fn(L)
                 g_rest.replay()
-            marks[r + 1].record()
-    else:
+            torch.cuda.synchronize()
+            marks[0].record()
+            for r in range(reps_):
+                for _ in range(full_sweeps):
+                    g_full.replay()
+                if g_rest is not None:
+                    g_rest.replay()
+                marks[r + 1].record()
+        else:
+            torch.cuda.synchronize()
+            marks[0].record()
+            for r in range(reps_):
+                for i in range(args.steps):
+                    run_fn(i % args.layers)
+                marks[r + 1].record()
         torch.cuda.synchronize()
-        marks[0].record()
-        for r in range(repeats):
-            for i in range(args.steps):
-                run_layer(i % args.layers)
-            marks[r + 1].record()
-    torch.cuda.synchronize()
-    ms_repeats = [marks[r].elapsed_time(marks[r + 1]) / args.steps for r in range(repeats)]
-    ms_per_step = marks[0].elapsed_time(marks[repeats]) / (args.steps * repeats)
+        return (marks[0].elapsed_time(marks[reps_]) / (args.steps * reps_),
+                [marks[r].elapsed_time(marks[r + 1]) / args.steps for r in range(reps_)])
+
+    repeats = max(1, args.repeats)
+    run_layer = run_layer_grouped if args.launches == "grouped" else run_layer_separate
+    ms_per_step, ms_repeats = time_step(run_layer)
+    # the other way of launching the same step, for comparison
+    other_fn = run_layer_separate if args.launches == "grouped" else run_layer_grouped
+    ms_other, _ = time_step(other_fn)
+    n_launches = len(GROUPS) if args.launches == "grouped" else n_calls
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
     us_per_call = ms_per_step * 1e3 / n_calls
     fp16_equiv = sum(2 * c["p"]["s"].out * c["p"]["s"].in_ for c in calls_per_layer[0]) / (ms_per_step * 1e-3) / 1e9
@@ -648,7 +673,8 @@ def main():
         e1.record()
         torch.cuda.synchronize()
         transform["decoder_layer_decode_with_4_transforms_us"] = round(e0.elapsed_time(e1) * 1e3 / (5 * args.layers), 2)
-        transform["decoder_layer_decode_without_us"] = round(ms_per_step * 1e3, 2)
+        ms_sep = ms_other if args.launches == "grouped" else ms_per_step     # seven separate btc_gemv calls
+        transform["decoder_layer_decode_without_us"] = round(ms_sep * 1e3, 2)
         # the same layer through btc_gemv_transformed: the first consumer of a transformed row computes it inside
         # its own kernel (every workgroup, on the matrix cores, factors prepared once) and hands it to the others;
         # factor sizes without a fused kernel (the input of down) run as the two launches inside the call
@@ -661,14 +687,18 @@ def main():
                 B.btc_transform_prepare(n1, n2, p1d, p2d, prep[n])
 
         def run_layer_f(L):
-            for ci, c in enumerate(calls_per_layer[L]):
-                p = c["p"]
+            calls = calls_per_layer[L]
+            for (a, b) in GROUPS:
+                p = calls[a]["p"]
                 n1, n2, bd, p1d, p2d, xt = tr[p["s"].in_]
-                if ci in (0, 3, 4, 6):
-                    B.btc_gemv_transformed(p["s"], c["packed"], p["codebook"], p["alpha"], p["mu"], p["x"], n1, n2, bd, p1d,
-                                           p2d, prep[p["s"].in_], c["y"], B.BTC_F16, ws, xt_out=xt)
-                else:
-                    B.btc_gemv(p["s"], c["packed"], p["codebook"], p["alpha"], p["mu"], xt, 1, c["y"], B.BTC_F16, ws)
+                grp = calls[a:b] if args.launches == "grouped" else calls[a:a + 1]
+                k = len(grp)
+                B.btc_gemv_transformed_multi(p["s"], [c["packed"] for c in grp], [p["codebook"]] * k, [p["alpha"]] * k,
+                                             [p["mu"]] * k, p["x"], n1, n2, bd, p1d, p2d, prep[p["s"].in_],
+                                             [c["y"] for c in grp], B.BTC_F16, ws, xt_out=xt)
+                if args.launches != "grouped":
+                    for c in calls[a + 1:b]:      # the other consumers of the row: plain calls
+                        B.btc_gemv(p["s"], c["packed"], p["codebook"], p["alpha"], p["mu"], xt, 1, c["y"], B.BTC_F16, ws)
 
         run_layer_f(0)
         torch.cuda.synchronize()
@@ -686,9 +716,12 @@ def main():
         torch.cuda.synchronize()
         fused_us = e0.elapsed_time(e1) * 1e3 / (5 * args.layers)
         transform["decoder_layer_decode_fused_us"] = round(fused_us, 2)
-        transform["fused_over_without"] = round(fused_us / (ms_per_step * 1e3), 3)
+        ms_same = ms_per_step                      # the plain step launched the same way as the fused one
+        transform["decoder_layer_decode_fused_launches"] = args.launches
+        transform["decoder_layer_decode_without_same_launches_us"] = round(ms_same * 1e3, 2)
+        transform["fused_over_without"] = round(fused_us / (ms_same * 1e3), 3)
         transform["two_launches_over_without"] = round(
-            transform["decoder_layer_decode_with_4_transforms_us"] / (ms_per_step * 1e3), 3)
+            transform["decoder_layer_decode_with_4_transforms_us"] / (ms_sep * 1e3), 3)
 
     # ---- E-step of the codebook clustering (btc_assign): the length-10 vectors of a 5120 x 5120 and of a
     # 13824 x 5120 sign matrix against 256 centroids; a setting with long vectors (no pattern table)
@@ -800,9 +833,15 @@ def main():
         "config": {"workload": "llama2-13b decoder-layer projections (4x5120x5120, 2x13824x5120, 1x5120x13824), "
                                "v=10 K=256 (0.8 bit), Zipf(1.1) indices, batch-1 GEMV, "
                                f"{args.layers} distinct weight copies ({total_weight_bytes / 1e9:.2f} GB) walked cold",
-                   "step": "one decoder layer = 7 btc_gemv calls", "launch": args.mode,
+                   "step": "one decoder layer = 7 projections" + (
+                       ", 4 launches: btc_gemv_multi for q/k/v and for gate/up (shared input), btc_gemv for o and down"
+                       if args.launches == "grouped" else ", 7 btc_gemv calls"), "launch": args.mode,
                    "timed": f"{repeats} x {args.steps} steps"},
         "us_per_call": round(us_per_call, 3),
+        "launches_per_step": n_launches,
+        ("separate_launches" if args.launches == "grouped" else "grouped_launches"): {
+            "ms_per_step": round(ms_other, 5), "value": round(step_bytes / (ms_other * 1e-3) / 1e9, 1), "unit": "GB/s",
+            "launches_per_step": n_calls if args.launches == "grouped" else len(GROUPS)},
         "fp16_equivalent_GBps": round(fp16_equiv, 1),
         "frac_measured_peak": round(value / HBM_MEASURED_GBS, 4),
         "per_shape": per_shape,

@@ -163,6 +163,19 @@ btc_status btc_gemv_engine(void* stream, const btc_shape* s, const uint32_t* pac
                            const void* x, int32_t batch, void* y, btc_dtype y_dtype,
                            void* workspace, size_t workspace_bytes, int32_t engine);
 
+/* btc_gemv (one activation row) for `count` (1..4) matrices of the SAME shape applied to the SAME activation
+ * row, e.g. the q, k, v or the gate, up projections of a decoder layer: y[m] = W_hat[m] . x.  packed, codebook,
+ * alpha, mu, y are HOST arrays of `count` device pointers (read before the call returns), each as for btc_gemv;
+ * x fp16 [in]; y[m] [out] of y_dtype (BTC_F16 or BTC_F32).  Where the engine on the 4-bit matrix cores covers
+ * the setting (v 9 or 10, 7..10 index bits) this is ONE launch whose workgroups are shared out among the
+ * matrices -- a decode product of this size is bound by its launch and prologue, not by its bytes -- and every
+ * y[m] is bit-identical to that engine's result for matrix m alone; otherwise it is `count` btc_gemv calls
+ * sharing the workspace (btc_workspace_bytes(s, 1, 0) bytes, rules as for btc_gemv).  Errors as btc_gemv. */
+btc_status btc_gemv_multi(void* stream, const btc_shape* s, int32_t count, const uint32_t* const* packed,
+                          const uint32_t* const* codebook, const float* const* alpha,
+                          const float* const* mu, const void* x, void* const* y, btc_dtype y_dtype,
+                          void* workspace, size_t workspace_bytes);
+
 /* Prefill product for many activation rows; same definition as btc_gemv with
  *   X : [M][in] of x_dtype (BTC_BF16 or BTC_F16), M >= 1
  *   Y : [M][out] of y_dtype (BTC_F32, BTC_BF16 or BTC_F16)
@@ -213,9 +226,14 @@ btc_status btc_transform(void* stream, const void* X, btc_dtype x_dtype, int32_t
  * With `prepared`, v = 10 and 7..10 index bits the call is one kernel: every workgroup computes x' into LDS on
  * the matrix cores (fp32 accumulation; factors and intermediate carried as two fp16 parts, 2^-22 relative)
  * and needs no workspace.  Otherwise it runs the transform as a launch of its own (on the matrix cores where
- * prepared operands exist, else btc_transform; into xt_out, else into the head of the workspace) and btc_gemv: then `workspace` must hold btc_gemv_transformed_workspace_bytes(s) bytes and follow the
- * rules of btc_gemv's workspace (zero-filled before first use).  x and xt_out must not overlap.  Errors: as
- * btc_gemv and btc_transform, _SHAPE also when n1 * n2 != in. */
+ * prepared operands exist, else btc_transform; into xt_out, else into the head of the workspace) and btc_gemv:
+ * then `workspace` must hold btc_gemv_transformed_workspace_bytes(s) bytes and follow the rules of btc_gemv's
+ * workspace (zero-filled before first use).  x and xt_out must not overlap.  Errors: as btc_gemv and
+ * btc_transform, _SHAPE also when n1 * n2 != in.
+ *
+ * btc_gemv_transformed_multi: the same for `count` (1..4) matrices of one shape that consume the same
+ * transformed row (q, k, v; gate, up), pointer arrays as for btc_gemv_multi: one kernel where the fused
+ * engine covers the setting, else the transform launch followed by btc_gemv_multi. */
 size_t btc_transform_prepared_bytes(int32_t n1, int32_t n2);
 btc_status btc_transform_prepare(void* stream, int32_t n1, int32_t n2, const float* P1, const float* P2,
                                  void* prepared, size_t prepared_bytes);
@@ -225,6 +243,12 @@ btc_status btc_gemv_transformed(void* stream, const btc_shape* s, const uint32_t
                                 int32_t n1, int32_t n2, const uint32_t* sign_bits, const float* P1,
                                 const float* P2, const void* prepared, void* xt_out, void* y,
                                 btc_dtype y_dtype, void* workspace, size_t workspace_bytes);
+btc_status btc_gemv_transformed_multi(void* stream, const btc_shape* s, int32_t count,
+                                      const uint32_t* const* packed, const uint32_t* const* codebook,
+                                      const float* const* alpha, const float* const* mu, const void* x,
+                                      int32_t n1, int32_t n2, const uint32_t* sign_bits, const float* P1,
+                                      const float* P2, const void* prepared, void* xt_out, void* const* y,
+                                      btc_dtype y_dtype, void* workspace, size_t workspace_bytes);
 
 /* E-step of the binary codebook clustering (section "Flash and Accurate Binary
  * Codebook", step "E-step Assignment": z_i = argmin_k ||b_i - c_k||^2, which for

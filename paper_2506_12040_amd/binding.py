@@ -86,6 +86,11 @@ def lib() -> ctypes.CDLL:
         L.btc_gemv_transformed.restype = ctypes.c_int
         L.btc_gemv_transformed.argtypes = [vp, sp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp,
                                            ctypes.c_size_t]
+        L.btc_gemv_transformed_multi.restype = ctypes.c_int
+        L.btc_gemv_transformed_multi.argtypes = [vp, sp, i32, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp,
+                                                 ctypes.c_int, vp, ctypes.c_size_t]
+        L.btc_gemv_multi.restype = ctypes.c_int
+        L.btc_gemv_multi.argtypes = [vp, sp, i32, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, ctypes.c_size_t]
         L.btc_gemv_groups.restype = ctypes.c_int
         L.btc_gemv_groups.argtypes = [vp, sp, vp, vp, vp, vp, vp, i32, vp, vp, ctypes.c_int]
         L.btc_status_str.restype = ctypes.c_char_p
@@ -220,6 +225,27 @@ def btc_gemv_transformed(s: BtcShape, packed, codebook, alpha, mu, x, n1: int, n
                                       _ptr(mu), _ptr(x), n1, n2, _ptr(sign_bits), _ptr(P1), _ptr(P2), _ptr(prepared),
                                       _ptr(xt_out), _ptr(y), y_dtype, _ptr(workspace), _nbytes(workspace)),
            "btc_gemv_transformed")
+
+
+def _ptr_array(ts):
+    return (ctypes.c_void_p * len(ts))(*[_ptr(t).value for t in ts])
+
+
+def btc_gemv_multi(s: BtcShape, packed, codebook, alpha, mu, x, y, y_dtype: int, workspace=None, stream=None) -> None:
+    """packed, codebook, alpha, mu, y: sequences of the same length (1..4), one entry per matrix."""
+    _check(lib().btc_gemv_multi(_stream(stream), ctypes.byref(s), len(packed), _ptr_array(packed), _ptr_array(codebook),
+                                _ptr_array(alpha), _ptr_array(mu), _ptr(x), _ptr_array(y), y_dtype, _ptr(workspace),
+                                _nbytes(workspace)), "btc_gemv_multi")
+
+
+def btc_gemv_transformed_multi(s: BtcShape, packed, codebook, alpha, mu, x, n1: int, n2: int, sign_bits, P1, P2, prepared,
+                               y, y_dtype: int, workspace=None, xt_out=None, stream=None) -> None:
+    """packed, codebook, alpha, mu, y: sequences of the same length (1..4), one entry per matrix."""
+    _check(lib().btc_gemv_transformed_multi(_stream(stream), ctypes.byref(s), len(packed), _ptr_array(packed),
+                                            _ptr_array(codebook), _ptr_array(alpha), _ptr_array(mu), _ptr(x), n1, n2,
+                                            _ptr(sign_bits), _ptr(P1), _ptr(P2), _ptr(prepared), _ptr(xt_out),
+                                            _ptr_array(y), y_dtype, _ptr(workspace), _nbytes(workspace)),
+           "btc_gemv_transformed_multi")
 
 
 def btc_gemv_groups(s: BtcShape, packed, codebook, alpha, mu, group_map, ngroups: int, x, y, y_dtype: int,

@@ -175,12 +175,26 @@ __device__ unsigned long long g_stamps[4 * 64];
 // e < 24: c = e / 8, u = e % 8;  24 <= e < 24 + 3 TAIL: c = (e - 24) / TAIL, u = 8 + (e - 24) % TAIL;  else padding.
 // The same order is used for the activations on the B side.
 
+// The matrices of one launch: up to kMaxMulti matrices of the same shape applied to the same activation row
+// (the q, k, v or the gate, up projections of a decoder layer).  Workgroups m wpm .. (m + 1) wpm - 1 work on matrix m.
+constexpr int kMaxMulti = 4;
+struct Multi {
+  const uint32_t* packed[kMaxMulti];
+  const uint32_t* codebook[kMaxMulti];
+  const float* alpha[kMaxMulti];
+  const float* mu[kMaxMulti];
+  void* y[kMaxMulti];
+  int count, wpm;
+};
+struct Extra {
+  ftr::Geo geo;
+  Multi multi;
+};
+
 // GN1, GN2: factor sizes of the activation transform computed in front of the product (0, 0: none).
 template <int V, int B, int T, int TEAMS, int CW, int GN1, int GN2>
 __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
-    Dims d, const uint32_t* __restrict__ packed, const uint32_t* __restrict__ codebook,
-    const float* __restrict__ alpha, const float* __restrict__ mu, const __half* __restrict__ x,
-    void* __restrict__ y, int y_is_f32, int n_rb, int x_dword, ftr::Geo geo) {
+    Dims d, Multi mm, const __half* __restrict__ x, int y_is_f32, int n_rb, int x_dword, ftr::Geo geo) {
   constexpr bool FUSED = GN1 > 0;
   using K = Cfg<V, B, T, TEAMS, CW, FUSED>;
   using FT = ftr::Fixed<GN1, GN2>;
@@ -202,7 +216,15 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int cw = wave & (CW - 1), team = wave / CW;          // column wave, team
   const int r = lane & 15, q = lane >> 4;
-  const int stride = gridDim.x;                              // row blocks between successive ones of a team slot
+  // this workgroup's matrix, and its number among the workgroups of that matrix
+  const int mat = mm.count > 1 ? (int)blockIdx.x / mm.wpm : 0;
+  const int bid = (int)blockIdx.x - mat * mm.wpm;
+  const uint32_t* __restrict__ packed = mm.packed[mat];
+  const uint32_t* __restrict__ codebook = mm.codebook[mat];
+  const float* __restrict__ alpha = mm.alpha[mat];
+  const float* __restrict__ mu = mm.mu[mat];
+  void* __restrict__ y = mm.y[mat];
+  const int stride = mm.wpm;                                 // row blocks between successive ones of a team slot
 
   // ---- small loads first (their data is needed first): codewords, then this wave's share of the activations.
   // An item is 16 consecutive B bytes of one step: (step t, strand qa, half h) = slots e = 16 h .. 16 h + 15
@@ -361,8 +383,8 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
       if (lrow < RPI && rr < 16) *(uint4*)(idx_stage + rr * S + 4 * lpc) = src[j];
     }
   };
-  // this wave's row blocks: blockIdx.x + (TEAMS * i + team) * stride, i = 0, 1, ...
-  const int rb_first = blockIdx.x + team * stride, rb_step = TEAMS * stride;
+  // this wave's row blocks: bid + (TEAMS * i + team) * stride, i = 0, 1, ...
+  const int rb_first = bid + team * stride, rb_step = TEAMS * stride;
   // Only the first row block is requested now: all waves of all workgroups get their first words within the
   // first burst, instead of queueing behind the later row blocks of the waves that happened to issue first.
   uint4 D0[NLD];
@@ -668,17 +690,12 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
 }
 
 template <int V, int B, int T, int TEAMS, int CW, int GN1, int GN2>
-static btc_status launch3(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
-                          const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, bool dry,
-                          const ftr::Geo* geo) {
+static btc_status launch3(hipStream_t q, const Dims& d, const void* x, int y_is_f32, bool dry, const Extra& ex) {
   constexpr bool FUSED = GN1 > 0;
   using K = Cfg<V, B, T, TEAMS, CW, FUSED>;
   static_assert(K::kLdsBytes <= kLdsMax, "LDS budget");
-  ftr::Geo g{};
-  if constexpr (FUSED) {
+  if constexpr (FUSED)
     static_assert(ftr::exchange_bytes_c(GN1, GN2) <= K::kExchangeBytes, "the tiles of the intermediate fit");
-    g = *geo;
-  }
   if (dry) return BTC_OK;         // only asked whether a kernel exists for this setting
   static bool attr_set = false;   // one-time kernel attribute, not call state
   if (!attr_set) {
@@ -688,11 +705,14 @@ static btc_status launch3(hipStream_t q, const Dims& d, const uint32_t* packed, 
     attr_set = true;
   }
   const int n_rb = (d.out + 15) / 16;
-  const int slots = 256 * TEAMS;                         // one workgroup per compute unit, TEAMS row blocks at a time
-  const int grid = n_rb < slots ? (n_rb + TEAMS - 1) / TEAMS : 256;
+  // one workgroup per compute unit, TEAMS row blocks at a time; the matrices of a launch share the compute units
+  Multi mm = ex.multi;
+  const int per_matrix = 256 / mm.count;
+  mm.wpm = n_rb < per_matrix * TEAMS ? (n_rb + TEAMS - 1) / TEAMS : per_matrix;
+  const int grid = mm.wpm * mm.count;
   const int x_dword = (V % 2 == 0) && (d.in % 2 == 0);
   gemv_fp4_kernel<V, B, T, TEAMS, CW, GN1, GN2><<<grid, K::W * 64, K::kLdsBytes, q>>>(
-      d, packed, codebook, alpha, mu, (const __half*)x, y, y_is_f32, n_rb, x_dword, g);
+      d, mm, (const __half*)x, y_is_f32, n_rb, x_dword, ex.geo);
   return launch_status();
 }
 
@@ -712,21 +732,20 @@ constexpr int steps_for_chunks(int nchunks, int cw) {
 static int steps_for(const Dims& d, int cw) { return steps_for_chunks(d.nchunks, cw); }
 
 template <int V, int B>
-static btc_status launch2(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
-                          const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, bool dry) {
+static btc_status launch2(hipStream_t q, const Dims& d, const void* x, int y_is_f32, bool dry, const Extra& ex) {
   // two teams whenever table, staging areas and B operands of 16 waves fit the LDS
 #define BTC_FP4_CASE(TT)                                                                                   \
   case TT:                                                                                                 \
     if constexpr (Cfg<V, B, TT, 2, 8>::kLdsBytes <= kLdsMax)                                               \
-      return launch3<V, B, TT, 2, 8, 0, 0>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry, nullptr); \
+      return launch3<V, B, TT, 2, 8, 0, 0>(q, d, x, y_is_f32, dry, ex); \
     else if constexpr (Cfg<V, B, TT, 1, 8>::kLdsBytes <= kLdsMax)                                          \
-      return launch3<V, B, TT, 1, 8, 0, 0>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry, nullptr); \
+      return launch3<V, B, TT, 1, 8, 0, 0>(q, d, x, y_is_f32, dry, ex); \
     else                                                                                                   \
       break;
 #define BTC_FP4_WIDE(TT)                                                                                   \
   case TT:                                                                                                 \
     if constexpr (Cfg<V, B, TT, 1, 16>::kLdsBytes <= kLdsMax)                                              \
-      return launch3<V, B, TT, 1, 16, 0, 0>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry, nullptr); \
+      return launch3<V, B, TT, 1, 16, 0, 0>(q, d, x, y_is_f32, dry, ex); \
     else                                                                                                   \
       break;
   switch (steps_for(d, 8)) {
@@ -742,13 +761,12 @@ static btc_status launch2(hipStream_t q, const Dims& d, const uint32_t* packed, 
 }
 
 template <int V>
-static btc_status launch1(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
-                          const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, bool dry) {
+static btc_status launch1(hipStream_t q, const Dims& d, const void* x, int y_is_f32, bool dry, const Extra& ex) {
   switch (d.b) {
-    case 7: return launch2<V, 7>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry);
-    case 8: return launch2<V, 8>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry);
-    case 9: return launch2<V, 9>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry);
-    case 10: return launch2<V, 10>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry);
+    case 7: return launch2<V, 7>(q, d, x, y_is_f32, dry, ex);
+    case 8: return launch2<V, 8>(q, d, x, y_is_f32, dry, ex);
+    case 9: return launch2<V, 9>(q, d, x, y_is_f32, dry, ex);
+    case 10: return launch2<V, 10>(q, d, x, y_is_f32, dry, ex);
   }
   return BTC_ERR_UNSUPPORTED;
 }
@@ -756,27 +774,23 @@ static btc_status launch1(hipStream_t q, const Dims& d, const uint32_t* packed, 
 // The product behind the transform: chunk length 10, the row is the N1 x N2 activation matrix, so the step count is
 // a constant too; two teams of eight column waves (16 waves: up to eight tiles per stage).
 template <int B, int N1, int N2>
-static btc_status launch_fused(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
-                               const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, bool dry,
-                               const ftr::Geo* geo) {
+static btc_status launch_fused(hipStream_t q, const Dims& d, const void* x, int y_is_f32, bool dry, const Extra& ex) {
   constexpr int T = steps_for_chunks((N1 * N2 + 9) / 10, 8);
   if constexpr (T > 0 && 2 * ftr::Fixed<N1, N2>::NT <= 16) {
     if constexpr (Cfg<10, B, T, 2, 8, true>::kLdsBytes <= kLdsMax &&
                   ftr::exchange_bytes_c(N1, N2) <= Cfg<10, B, T, 2, 8, true>::kExchangeBytes)
-      return launch3<10, B, T, 2, 8, N1, N2>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry, geo);
+      return launch3<10, B, T, 2, 8, N1, N2>(q, d, x, y_is_f32, dry, ex);
   }
   return BTC_ERR_UNSUPPORTED;
 }
 
 template <int N1, int N2>
-static btc_status launch_fused_b(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
-                                 const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, bool dry,
-                                 const ftr::Geo* geo) {
+static btc_status launch_fused_b(hipStream_t q, const Dims& d, const void* x, int y_is_f32, bool dry, const Extra& ex) {
   switch (d.b) {
-    case 7: return launch_fused<7, N1, N2>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry, geo);
-    case 8: return launch_fused<8, N1, N2>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry, geo);
-    case 9: return launch_fused<9, N1, N2>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry, geo);
-    case 10: return launch_fused<10, N1, N2>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry, geo);
+    case 7: return launch_fused<7, N1, N2>(q, d, x, y_is_f32, dry, ex);
+    case 8: return launch_fused<8, N1, N2>(q, d, x, y_is_f32, dry, ex);
+    case 9: return launch_fused<9, N1, N2>(q, d, x, y_is_f32, dry, ex);
+    case 10: return launch_fused<10, N1, N2>(q, d, x, y_is_f32, dry, ex);
   }
   return BTC_ERR_UNSUPPORTED;
 }
@@ -789,48 +803,87 @@ extern "C" int btc_debug_fp4_stamps(unsigned long long* host, int n) {
 }
 #endif
 
-static btc_status fp4_dispatch(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
-                               const float* alpha, const float* mu, const void* x, void* y, int y_is_f32, bool dry,
-                               const ftr::Geo* geo = nullptr) {
+static btc_status fp4_dispatch(hipStream_t q, const Dims& d, const void* x, int y_is_f32, bool dry, const fp4::Extra& ex,
+                               bool fused) {
   if (d.v != 9 && d.v != 10) return BTC_ERR_UNSUPPORTED;
   if (d.b < 7 || d.b > 10) return BTC_ERR_UNSUPPORTED;
   if ((long long)d.out * d.wpr * 4 >= (1LL << 31)) return BTC_ERR_UNSUPPORTED;     // 32-bit byte offsets
   if ((long long)d.nchunks * d.v * 2 >= (1LL << 31)) return BTC_ERR_UNSUPPORTED;
-  if (geo) {
+  if (fused) {
     // The transformed row is made in LDS first: aligned pairs of activations, and factor sizes with an instantiated
     // kernel (ftr::geometry_ok) -- the pairs whose product is the hidden width of LLaMA-2 7B and 13B.  Larger
     // factors (64 x 128 for 8192; 86 x 128, 108 x 128, 128 x 224 for the intermediate widths) are two to four times
     // the operand traffic and arithmetic per workgroup and no longer fit the registers of a 16-wave workgroup: they
     // cost more inside every workgroup than as a launch of their own.
-    if (d.v != 10 || geo->n1 * geo->n2 != d.in) return BTC_ERR_UNSUPPORTED;
-    if (geo->n1 == 64 && geo->n2 == 64) return fp4::launch_fused_b<64, 64>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry, geo);
-    if (geo->n1 == 64 && geo->n2 == 80) return fp4::launch_fused_b<64, 80>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry, geo);
+    const ftr::Geo& g = ex.geo;
+    if (d.v != 10 || g.n1 * g.n2 != d.in) return BTC_ERR_UNSUPPORTED;
+    if (g.n1 == 64 && g.n2 == 64) return fp4::launch_fused_b<64, 64>(q, d, x, y_is_f32, dry, ex);
+    if (g.n1 == 64 && g.n2 == 80) return fp4::launch_fused_b<64, 80>(q, d, x, y_is_f32, dry, ex);
     return BTC_ERR_UNSUPPORTED;
   }
-  if (d.v == 9) return fp4::launch1<9>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry);
-  return fp4::launch1<10>(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, dry);
+  if (d.v == 9) return fp4::launch1<9>(q, d, x, y_is_f32, dry, ex);
+  return fp4::launch1<10>(q, d, x, y_is_f32, dry, ex);
+}
+
+static fp4::Extra extra_one(const uint32_t* packed, const uint32_t* codebook, const float* alpha, const float* mu, void* y) {
+  fp4::Extra ex{};
+  ex.multi.packed[0] = packed;
+  ex.multi.codebook[0] = codebook;
+  ex.multi.alpha[0] = alpha;
+  ex.multi.mu[0] = mu;
+  ex.multi.y[0] = y;
+  ex.multi.count = 1;
+  return ex;
 }
 
 bool gemv_fp4_covers(const Dims& d) {
-  return fp4_dispatch(nullptr, d, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0, /*dry=*/true) == BTC_OK;
+  return fp4_dispatch(nullptr, d, nullptr, 0, /*dry=*/true, extra_one(nullptr, nullptr, nullptr, nullptr, nullptr), false) == BTC_OK;
 }
 
 btc_status gemv_fp4(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
                     const float* alpha, const float* mu, const void* x, void* y, int y_is_f32) {
-  return fp4_dispatch(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, /*dry=*/false);
+  return fp4_dispatch(q, d, x, y_is_f32, /*dry=*/false, extra_one(packed, codebook, alpha, mu, y), false);
+}
+
+btc_status gemv_fp4_multi(hipStream_t q, const Dims& d, int count, const uint32_t* const* packed,
+                          const uint32_t* const* codebook, const float* const* alpha, const float* const* mu,
+                          const void* x, void* const* y, int y_is_f32) {
+  if (count < 1 || count > fp4::kMaxMulti) return BTC_ERR_UNSUPPORTED;
+  fp4::Extra ex{};
+  for (int m = 0; m < count; ++m) {
+    ex.multi.packed[m] = packed[m];
+    ex.multi.codebook[m] = codebook[m];
+    ex.multi.alpha[m] = alpha[m];
+    ex.multi.mu[m] = mu[m];
+    ex.multi.y[m] = y[m];
+  }
+  ex.multi.count = count;
+  return fp4_dispatch(q, d, x, y_is_f32, /*dry=*/false, ex, false);
 }
 
 bool gemv_fp4_fused_covers(const Dims& d, int n1, int n2) {
-  const ftr::Geo g = ftr::make_geo(nullptr, nullptr, n1, n2);
-  return fp4_dispatch(nullptr, d, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0, /*dry=*/true, &g) == BTC_OK;
+  fp4::Extra ex = extra_one(nullptr, nullptr, nullptr, nullptr, nullptr);
+  ex.geo = ftr::make_geo(nullptr, nullptr, n1, n2);
+  return fp4_dispatch(nullptr, d, nullptr, 0, /*dry=*/true, ex, true) == BTC_OK;
 }
 
-btc_status gemv_fp4_fused(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
-                          const float* alpha, const float* mu, const void* x, int n1, int n2, const uint32_t* sign_bits,
-                          const void* prepared, void* xt_out, void* y, int y_is_f32) {
-  ftr::Geo g = ftr::make_geo(sign_bits, prepared, n1, n2);
-  g.xt_out = (uint16_t*)xt_out;
-  return fp4_dispatch(q, d, packed, codebook, alpha, mu, x, y, y_is_f32, /*dry=*/false, &g);
+btc_status gemv_fp4_fused(hipStream_t q, const Dims& d, int count, const uint32_t* const* packed,
+                          const uint32_t* const* codebook, const float* const* alpha, const float* const* mu,
+                          const void* x, int n1, int n2, const uint32_t* sign_bits, const void* prepared, void* xt_out,
+                          void* const* y, int y_is_f32) {
+  if (count < 1 || count > fp4::kMaxMulti) return BTC_ERR_UNSUPPORTED;
+  fp4::Extra ex{};
+  for (int m = 0; m < count; ++m) {
+    ex.multi.packed[m] = packed[m];
+    ex.multi.codebook[m] = codebook[m];
+    ex.multi.alpha[m] = alpha[m];
+    ex.multi.mu[m] = mu[m];
+    ex.multi.y[m] = y[m];
+  }
+  ex.multi.count = count;
+  ex.geo = ftr::make_geo(sign_bits, prepared, n1, n2);
+  ex.geo.xt_out = (uint16_t*)xt_out;
+  return fp4_dispatch(q, d, x, y_is_f32, /*dry=*/false, ex, true);
 }
 
 }  // namespace btc

@@ -126,26 +126,33 @@ size_t btc_gemv_transformed_workspace_bytes(const btc_shape* s) {
   return btc::ftr::x_region_bytes(d) + btc_workspace_bytes(s, 1, 0);
 }
 
-btc_status btc_gemv_transformed(void* stream, const btc_shape* s, const uint32_t* packed, const uint32_t* codebook,
-                                const float* alpha, const float* mu, const void* x, int32_t n1, int32_t n2,
-                                const uint32_t* sign_bits, const float* P1, const float* P2, const void* prepared,
-                                void* xt_out, void* y, btc_dtype y_dtype, void* workspace, size_t workspace_bytes) {
+btc_status btc_gemv_transformed_multi(void* stream, const btc_shape* s, int32_t count, const uint32_t* const* packed,
+                                      const uint32_t* const* codebook, const float* const* alpha,
+                                      const float* const* mu, const void* x, int32_t n1, int32_t n2,
+                                      const uint32_t* sign_bits, const float* P1, const float* P2, const void* prepared,
+                                      void* xt_out, void* const* y, btc_dtype y_dtype, void* workspace,
+                                      size_t workspace_bytes) {
   using namespace btc;
   btc_status st = check_shape(s);
   if (st != BTC_OK) return st;
   if (!packed || !codebook || !alpha || !mu || !x || !sign_bits || !P1 || !P2 || !y) return BTC_ERR_NULL;
+  if (count < 1 || count > 4) return BTC_ERR_UNSUPPORTED;
   if (n1 <= 0 || n2 <= 0 || (long long)n1 * n2 != s->in) return BTC_ERR_SHAPE;
   if (y_dtype != BTC_F16 && y_dtype != BTC_F32) return BTC_ERR_UNSUPPORTED;
-  if (!aligned16(packed) || !aligned16(codebook) || !aligned16(alpha) || !aligned16(mu) || !aligned16(x) ||
-      !aligned16(sign_bits) || !aligned16(P1) || !aligned16(P2) || !aligned16(y) || (prepared && !aligned16(prepared)) ||
+  if (!aligned16(x) || !aligned16(sign_bits) || !aligned16(P1) || !aligned16(P2) || (prepared && !aligned16(prepared)) ||
       (xt_out && !aligned16(xt_out)))
     return BTC_ERR_ALIGN;
+  for (int m = 0; m < count; ++m) {
+    if (!packed[m] || !codebook[m] || !alpha[m] || !mu[m] || !y[m]) return BTC_ERR_NULL;
+    if (!aligned16(packed[m]) || !aligned16(codebook[m]) || !aligned16(alpha[m]) || !aligned16(mu[m]) || !aligned16(y[m]))
+      return BTC_ERR_ALIGN;
+  }
   const Dims d = dims_of(*s);
   hipStream_t q = (hipStream_t)stream;
   if (prepared && gemv_fp4_fused_covers(d, n1, n2))
-    return gemv_fp4_fused(q, d, packed, codebook, alpha, mu, x, n1, n2, sign_bits, prepared, xt_out, y,
+    return gemv_fp4_fused(q, d, count, packed, codebook, alpha, mu, x, n1, n2, sign_bits, prepared, xt_out, y,
                           y_dtype == BTC_F32);
-  // two launches: the transformed row goes through xt_out, or else through the head of the workspace
+  // the transform as a launch of its own: the row goes through xt_out, or else through the head of the workspace
   const size_t head = xt_out ? 0 : ftr::x_region_bytes(d);
   if (!workspace || workspace_bytes < head + btc_workspace_bytes(s, 1, 0)) return BTC_ERR_WORKSPACE;
   if (!aligned16(workspace)) return BTC_ERR_ALIGN;
@@ -156,8 +163,16 @@ btc_status btc_gemv_transformed(void* stream, const btc_shape* s, const uint32_t
   else
     st = btc_transform(stream, x, BTC_F16, 1, n1, n2, sign_bits, P1, P2, xt, BTC_F16);
   if (st != BTC_OK) return st;
-  return btc_gemv(stream, s, packed, codebook, alpha, mu, xt, 1, y, y_dtype, (unsigned char*)workspace + head,
-                  workspace_bytes - head);
+  return btc_gemv_multi(stream, s, count, packed, codebook, alpha, mu, xt, y, y_dtype, (unsigned char*)workspace + head,
+                        workspace_bytes - head);
+}
+
+btc_status btc_gemv_transformed(void* stream, const btc_shape* s, const uint32_t* packed, const uint32_t* codebook,
+                                const float* alpha, const float* mu, const void* x, int32_t n1, int32_t n2,
+                                const uint32_t* sign_bits, const float* P1, const float* P2, const void* prepared,
+                                void* xt_out, void* y, btc_dtype y_dtype, void* workspace, size_t workspace_bytes) {
+  return btc_gemv_transformed_multi(stream, s, 1, &packed, &codebook, &alpha, &mu, x, n1, n2, sign_bits, P1, P2, prepared,
+                                    xt_out, &y, y_dtype, workspace, workspace_bytes);
 }
 
 }  // extern "C"

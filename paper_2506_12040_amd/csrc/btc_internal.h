@@ -36,13 +36,19 @@ btc_status gemv_expand(hipStream_t q, const Dims& d, const uint32_t* packed, con
 bool gemv_fp4_covers(const Dims& d);
 btc_status gemv_fp4(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
                     const float* alpha, const float* mu, const void* x, void* y, int y_is_f32);
+// The same engine on up to four matrices of one shape applied to the same activation row, in one launch
+// (host arrays of device pointers).
+btc_status gemv_fp4_multi(hipStream_t q, const Dims& d, int count, const uint32_t* const* packed,
+                          const uint32_t* const* codebook, const float* const* alpha, const float* const* mu,
+                          const void* x, void* const* y, int y_is_f32);
 // The same engine behind the online activation transform of the row (factors n1 x n1, n2 x n2, n1 n2 = in),
 // which every workgroup computes into LDS first; `prepared` from btc_transform_prepare; xt_out: where the
-// transformed row is also stored (fp16 [in]), or null.
+// transformed row is also stored (fp16 [in]), or null; `count` matrices as in gemv_fp4_multi.
 bool gemv_fp4_fused_covers(const Dims& d, int n1, int n2);
-btc_status gemv_fp4_fused(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
-                          const float* alpha, const float* mu, const void* x, int n1, int n2, const uint32_t* sign_bits,
-                          const void* prepared, void* xt_out, void* y, int y_is_f32);
+btc_status gemv_fp4_fused(hipStream_t q, const Dims& d, int count, const uint32_t* const* packed,
+                          const uint32_t* const* codebook, const float* const* alpha, const float* const* mu,
+                          const void* x, int n1, int n2, const uint32_t* sign_bits, const void* prepared, void* xt_out,
+                          void* const* y, int y_is_f32);
 // Long vectors and large codebooks, one activation row (btc_gemv_code.hip): the codebook itself in LDS.
 bool gemv_code_covers(const Dims& d);
 btc_status gemv_code(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,

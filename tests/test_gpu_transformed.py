@@ -101,6 +101,45 @@ def test_transformed_layer_matches_the_oracle(G, oracle, out, n1, n2, v, K, prep
     assert np.count_nonzero(got != xt_bits[0]) <= max(2, n // 500)
 
 
+@pytest.mark.parametrize("out,n1,n2,K,count", [(5120, 64, 80, 256, 3), (13824, 64, 80, 256, 2), (1000, 64, 64, 512, 4),
+                                                (3000, 108, 128, 256, 2), (400, 7, 32, 256, 3)])
+def test_grouped_transformed_layer(G, oracle, out, n1, n2, K, count):
+    """Several matrices behind one transformed row: every output of every matrix against the oracle; where the fused
+    engine covers the setting the result is bit for bit that of the single fused calls."""
+    import torch
+    B = G.B
+    n, v = n1 * n2, 10
+    print(f"gemv_transformed_multi out={out} n1={n1} n2={n2} K={K} count={count}", flush=True)
+    layers, x = [], None
+    for m in range(count):
+        layer, xm = S.make_case(90 + m, out, n, v, K, 1)
+        layers.append(G.DeviceLayer(layer, oracle))
+        x = xm if x is None else x
+    bits, P1, P2 = S.draw_transform(5 + n1, n1, n2)
+    xt_bits = _fp16_bits(oracle.transform(x, bits, P1, P2, "f16"))
+    P1_d, P2_d, bits_d, x_d = G.dev(P1), G.dev(P2), G.dev(bits), G.dev(x)
+    nb = B.btc_transform_prepared_bytes(n1, n2)
+    prepared = None
+    if nb:
+        prepared = torch.empty(nb, dtype=torch.uint8, device="cuda")
+        B.btc_transform_prepare(n1, n2, P1_d, P2_d, prepared)
+    shape = layers[0].shape
+    ws = torch.zeros(B.btc_gemv_transformed_workspace_bytes(shape), dtype=torch.uint8, device="cuda")
+    Ys = [G.GuardedOutput(1, out, torch.float32) for _ in range(count)]
+    B.btc_gemv_transformed_multi(shape, [l.packed for l in layers], [l.codebook for l in layers],
+                                 [l.alpha for l in layers], [l.mu for l in layers], x_d, n1, n2, bits_d, P1_d, P2_d,
+                                 prepared, [Y.payload for Y in Ys], B.BTC_F32, ws)
+    fused = (n1, n2) in ((64, 64), (64, 80))
+    for m, (l, Y) in enumerate(zip(layers, Ys)):
+        Y.check_guards()
+        G.assert_close(Y.numpy(), G.oracle_all_rows(oracle, l, xt_bits), f"matrix {m}")
+        if fused:
+            y1 = torch.empty(out, dtype=torch.float32, device="cuda")
+            B.btc_gemv_transformed(shape, l.packed, l.codebook, l.alpha, l.mu, x_d, n1, n2, bits_d, P1_d, P2_d, prepared,
+                                   y1, B.BTC_F32, None)
+            assert torch.equal(y1, Y.payload.view(-1)), f"matrix {m}: grouped and single fused call differ"
+
+
 def test_prepare_argument_errors(G):
     import torch
     B = G.B
