@@ -84,6 +84,7 @@ def main():
                          "through btc_gemv_multi, one launch per group; separate: seven btc_gemv calls")
     ap.add_argument("--gemm-m", type=int, default=2048)
     ap.add_argument("--gemm-iters", type=int, default=10)
+    ap.add_argument("--no-compare", action="store_true", help="do not also time the other way of launching the step")
     ap.add_argument("--no-gemm", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-transform", action="store_true", help="skip the btc_transform / btc_assign timings")
@@ -129,7 +130,8 @@ def main():
                 B.btc_assign(vec, N, v_, cbk, K_, zz, None)
         else:
             o, i, v_, K_, rows = nums
-            layer, x = S.make_case(0, o, i, v_, K_, rows, x_dtype="f16" if kind == "gemv" else "bf16")
+            layer, x = S.make_case(0, o, i, v_, K_, 1 if kind == "multi" else rows,
+                                   x_dtype="f16" if kind in ("gemv", "multi") else "bf16")
             s = B.btc_shape_init(o, i, v_, K_)
             packed = torch.empty(o * s.words_per_row, dtype=torch.int32, device=dev)
             B.btc_pack(s, torch.from_numpy(layer.idx).to(dev), packed, torch.zeros(64, dtype=torch.uint8, device=dev))
@@ -145,6 +147,14 @@ def main():
                 copies = [torch.roll(pk, shifts=(c * 37 + 1) % o, dims=0).contiguous() for c in range(24)]
                 for c in copies:
                     B.btc_gemv(s, c, cb_d, al, mu, xd, rows, y, B.BTC_F16, ws)
+            elif kind == "multi":   # cold: 24 launches of `rows` distinct copies each, on one activation row
+                ys = [torch.empty(o, dtype=torch.float16, device=dev) for _ in range(rows)]
+                ws = torch.zeros(B.btc_workspace_bytes(s, 1, False), dtype=torch.uint8, device=dev)
+                pk = packed.view(o, s.words_per_row)
+                copies = [torch.roll(pk, shifts=(c * 37 + 1) % o, dims=0).contiguous() for c in range(24 * rows)]
+                for c in range(24):
+                    B.btc_gemv_multi(s, copies[c * rows:(c + 1) * rows], [cb_d] * rows, [al] * rows, [mu] * rows, xd, ys,
+                                     B.BTC_F16, ws)
             elif kind == "gemm":
                 Y = torch.empty(rows * o, dtype=torch.float32, device=dev)
                 ws = torch.zeros(B.btc_workspace_bytes(s, rows, True), dtype=torch.uint8, device=dev)
@@ -282,7 +292,7 @@ def main():
     ms_per_step, ms_repeats = time_step(run_layer)
     # the other way of launching the same step, for comparison
     other_fn = run_layer_separate if args.launches == "grouped" else run_layer_grouped
-    ms_other, _ = time_step(other_fn)
+    ms_other = float("nan") if args.no_compare else time_step(other_fn)[0]
     n_launches = len(GROUPS) if args.launches == "grouped" else n_calls
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
     us_per_call = ms_per_step * 1e3 / n_calls
@@ -350,6 +360,38 @@ def main():
             row["in_kernel_us"] = k_us
         return row
 
+    def time_pair(p, min_calls=80):
+        """Cold time of ONE btc_gemv_multi launch over two distinct copies of a matrix (the k, v or the gate, up
+        projections of a layer), amortised over a graph of such launches."""
+        s = p["s"]
+        nbytes = s.out * s.words_per_row * 4
+        npairs = int(min(600, max(4, -(-(1 << 29) // nbytes))))
+        copies = rotated(p, 2 * npairs)
+        ys = [torch.empty(s.out, dtype=torch.float16, device=dev) for _ in range(2)]
+        wsd = torch.zeros(B.btc_workspace_bytes(s, 1, False), dtype=torch.uint8, device=dev)
+        call = lambda i: B.btc_gemv_multi(s, [copies[2 * i], copies[2 * i + 1]], [p["codebook"]] * 2, [p["alpha"]] * 2,
+                                          [p["mu"]] * 2, p["x"], ys, B.BTC_F16, wsd)
+        call(0)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i in range(npairs):
+                call(i)
+        g.replay()
+        torch.cuda.synchronize()
+        reps = max(2, -(-min_calls // npairs))
+        e0, e1 = events()
+        e0.record()
+        for _ in range(reps):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / (reps * npairs)
+        by = 2 * gemv_bytes(s, 1)
+        del copies, g
+        return dict(us_per_launch=round(us, 2), bytes=by, eff_GBps=round(by / us / 1e3, 1),
+                    frac_hbm=round(by / us / 1e3 / HBM_PEAK_GBS, 4))
+
     # per-shape timing of the headline shapes
     per_shape = {f"{p['s'].out}x{p['s'].in_}": time_decode(p) for p in protos}
 
@@ -374,18 +416,33 @@ def main():
             d["per_shape"][f"{case['out']}x{case['n_in']}"] = r
             d["us"] += cnt * r["cold_us"]
             d["bytes"] += cnt * r["bytes"]
+            # k, v and gate, up share their input: one launch per pair; q and o stay single calls
+            if (case["out"], case["n_in"]) in ((1024, 8192), (28672, 8192)):
+                pr = time_pair(p)
+                d.setdefault("pairs", {})[f"2 x {case['out']}x{case['n_in']}"] = pr
+                d["us_grouped"] = d.get("us_grouped", 0.0) + pr["us_per_launch"]
+            else:
+                d["us_grouped"] = d.get("us_grouped", 0.0) + cnt * r["cold_us"]
             del p
         for key, d in layers70.items():
             gbs = d["bytes"] / d["us"] / 1e3
+            gbs_g = d["bytes"] / d["us_grouped"] / 1e3
             other[key] = dict(per_shape=d["per_shape"], layer_us=round(d["us"], 1), layer_eff_GBps=round(gbs, 1),
                               layer_frac_hbm=round(gbs / HBM_PEAK_GBS, 4),
-                              layer_frac_measured_peak=round(gbs / HBM_MEASURED_GBS, 4))
+                              layer_frac_measured_peak=round(gbs / HBM_MEASURED_GBS, 4),
+                              pairs_one_launch=d.get("pairs"), layer_us_grouped=round(d["us_grouped"], 1),
+                              layer_eff_GBps_grouped=round(gbs_g, 1),
+                              layer_frac_hbm_grouped=round(gbs_g / HBM_PEAK_GBS, 4))
         key09 = "llama2-70b v=10 K=512 (0.9 bit)"
         big = other[key09]["per_shape"]["28672x8192"]
         roof70 = {"bound": "hbm", "achieved": big["eff_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                   "frac": big["frac_hbm"], "frac_measured_peak": big["frac_measured_peak"],
                   "traffic": figures.get("traffic_bytes_per_call 28672x8192 v=10 K=512"),
                   "layer_frac": other[key09]["layer_frac_hbm"],
+                  "layer_frac_grouped": other[key09]["layer_frac_hbm_grouped"],
+                  "gate_up_one_launch": dict(other[key09]["pairs_one_launch"]["2 x 28672x8192"],
+                                             traffic=figures.get("traffic_bytes_per_launch 2x28672x8192 v=10 K=512"),
+                                             in_kernel_us=kernel_us.get("in_kernel_us 2x28672x8192 v=10 K=512 one launch")),
                   "note": "btc_gemv on 28672x8192 at 0.9 bit, batch 1, cold: algorithmic bytes of a call "
                           f"({big['bytes']}) / graph-amortised time of a call; layer_frac = the seven matrices of "
                           "a 70B-shaped decoder layer"}
@@ -674,6 +731,8 @@ def main():
         torch.cuda.synchronize()
         transform["decoder_layer_decode_with_4_transforms_us"] = round(e0.elapsed_time(e1) * 1e3 / (5 * args.layers), 2)
         ms_sep = ms_other if args.launches == "grouped" else ms_per_step     # seven separate btc_gemv calls
+        if args.no_compare and args.launches == "grouped":
+            ms_sep = time_step(run_layer_separate)[0]
         transform["decoder_layer_decode_without_us"] = round(ms_sep * 1e3, 2)
         # the same layer through btc_gemv_transformed: the first consumer of a transformed row computes it inside
         # its own kernel (every workgroup, on the matrix cores, factors prepared once) and hands it to the others;
@@ -815,7 +874,7 @@ def main():
                    single_thread=dict(value=one["value"], unit="GB/s", cores=1,
                                       split_s_per_pass=one["split_s_per_pass"]))
 
-    traffic = figures.get("traffic_bytes_per_step")
+    traffic = figures.get("traffic_bytes_per_step" if args.launches == "grouped" else "traffic_bytes_per_step separate")
     out = {
         "metric": "btc_gemv effective weight GB/s (13B shapes, 0.8-bit, batch 1, cold)",
         "value": round(value, 1),
@@ -839,7 +898,7 @@ def main():
                    "timed": f"{repeats} x {args.steps} steps"},
         "us_per_call": round(us_per_call, 3),
         "launches_per_step": n_launches,
-        ("separate_launches" if args.launches == "grouped" else "grouped_launches"): {
+        ("separate_launches" if args.launches == "grouped" else "grouped_launches"): None if args.no_compare else {
             "ms_per_step": round(ms_other, 5), "value": round(step_bytes / (ms_other * 1e-3) / 1e9, 1), "unit": "GB/s",
             "launches_per_step": n_calls if args.launches == "grouped" else len(GROUPS)},
         "fp16_equivalent_GBps": round(fp16_equiv, 1),
@@ -849,7 +908,8 @@ def main():
         "other_decode_configs": other,
         "roofline": {"bound": "hbm", "achieved": round(value, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(value / HBM_PEAK_GBS, 4), "traffic": traffic,
-                     "note": "algorithmic bytes of the 7 calls of a step / event-timed duration of a step; "
+                     "note": "algorithmic bytes of the 7 projections of a step / event-timed duration of a step "
+                             f"({n_launches} launches); "
                              "traffic = HBM bytes per step (fetched + written) read from "
                              "profiles/gemv_13b_hbm_traffic.md (rocprofv3 counter runs), algorithmic bytes per step "
                              f"{step_bytes}"},
