@@ -56,7 +56,8 @@ typedef __attribute__((ext_vector_type(8))) int i32x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-typedef __attribute__((address_space(3))) unsigned long long lds_u64;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((address_space(3))) u32x2 lds_u32x2;
 
 constexpr uint32_t kOob = 0x80000000u;   // buffer offset that is always out of range (buffers are < 2 GiB)
 constexpr int kRsrcFlags = 0x00020000;   // raw buffer, 32-bit data format
@@ -608,8 +609,10 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
       // B operand) are issued before the entries of step t are merged and contracted, so an LDS round trip
       // is covered by a step's worth of arithmetic.  (Left to itself the compiler waits for every read.)
       f32x4 acc[4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-      unsigned long long E[2][G];   // [pipeline stage][chunk]
-      auto issue = [&](int t, unsigned long long (&dst)[G]) {
+      // a table entry as two separate words (as one 64-bit integer the compiler turns "high word << 8" into a
+      // funnel shift of both words plus a mask)
+      u32x2 E[2][G];   // [pipeline stage][chunk]
+      auto issue = [&](int t, u32x2 (&dst)[G]) {
 #pragma unroll
         for (int g = 0; g < G; ++g) {
           const int pos = (t * G + g) * B, w = pos >> 5, sb = pos & 31;
@@ -628,13 +631,20 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
             ofs = (sh & mask) | lane_copy;
           }
           // the table starts at LDS address 0 (this kernel has no static LDS), so the offset IS the address
-          dst[g] = *(const lds_u64*)(uintptr_t)ofs;
+          dst[g] = *(const lds_u32x2*)(uintptr_t)ofs;
         }
       };
-      auto consume = [&](int t, const unsigned long long (&src)[G]) {
-        const uint32_t t0 = (uint32_t)(src[0] >> 32), t1 = (uint32_t)(src[1] >> 32), t2 = (uint32_t)(src[2] >> 32);
-        const uint32_t tails = t0 | (t1 << (4 * TAIL)) | (t2 << (8 * TAIL));
-        const i32x8 Av = {(int)(uint32_t)src[0], (int)(uint32_t)src[1], (int)(uint32_t)src[2], (int)tails, 0, 0, 0, 0};
+      auto consume = [&](int t, const u32x2 (&src)[G]) {
+        // two shift-and-or instructions (the byte permute keeps the compiler from re-associating them into two
+        // shifts and a three-way or)
+        uint32_t tails;
+        if constexpr (TAIL == 2) {
+          const uint32_t t01 = __builtin_amdgcn_perm(src[1].y, src[0].y, 0x0C0C0400u);   // bytes: t0, t1, 0, 0
+          tails = __builtin_amdgcn_perm(src[2].y, t01, 0x0C040100u);                     // bytes: t0, t1, t2, 0
+        } else {
+          tails = src[0].y | (src[1].y << (4 * TAIL)) | (src[2].y << (8 * TAIL));
+        }
+        const i32x8 Av = {(int)src[0].x, (int)src[1].x, (int)src[2].x, (int)tails, 0, 0, 0, 0};
         acc[t & 3] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(Av, Bq[t >> 2], acc[t & 3], 4 /* A: E2M1 */,
                                                                       1 /* B: E5M2 */, 0, 0, 0, 0);
       };
