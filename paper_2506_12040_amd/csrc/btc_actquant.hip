@@ -209,8 +209,10 @@ btc_status btc_weight_rowsums(void* stream, const btc_shape* s, const uint32_t* 
   char* inner = (char*)workspace + aq::align256((size_t)s->in * 2) + aq::align256((size_t)s->out * 4);
   const size_t inner_bytes = btc_workspace_bytes(s, 1, 0);
   hipStream_t q = (hipStream_t)stream;
-  st = aq::zero_fill(q, inner, inner_bytes);
-  if (st != BTC_OK) return st;
+  if (gemv_auto_uses_workspace(dims_of(*s), 1)) {
+    st = aq::zero_fill(q, inner, inner_bytes);
+    if (st != BTC_OK) return st;
+  }
   aq::fill_ones_kernel<<<(s->in + aq::kThreads - 1) / aq::kThreads, aq::kThreads, 0, q>>>(ones, s->in);
   st = launch_status();
   if (st != BTC_OK) return st;
@@ -247,9 +249,11 @@ btc_status btc_gemm_aq(void* stream, const btc_shape* s, const uint32_t* packed,
   st = launch_status();
   if (st != BTC_OK) return st;
   if (M <= 16) {
-    // the decode engines want their workspace zero-filled and hand it back that way
-    st = aq::zero_fill(q, inner, inner_bytes);
-    if (st != BTC_OK) return st;
+    // the decode engines that park partial sums want their workspace zero-filled and hand it back that way
+    if (gemv_auto_uses_workspace(dims_of(*s), M)) {
+      st = aq::zero_fill(q, inner, inner_bytes);
+      if (st != BTC_OK) return st;
+    }
     st = btc_gemv(stream, s, packed, codebook, alpha, mu, Q16, M, T, BTC_F32, inner, inner_bytes);
   } else {
     st = btc_gemm(stream, s, packed, codebook, alpha, mu, Q16, BTC_F16, M, T, BTC_F32, inner, inner_bytes);

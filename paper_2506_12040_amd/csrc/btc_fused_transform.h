@@ -81,13 +81,144 @@ __device__ __forceinline__ void split2(float v, uint32_t& hi, uint32_t& lo) {
   lo = (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)((v - (float)h) * 2048.0f));
 }
 
-// The factor sizes are compile-time constants inside a decode kernel, so that both stages are straight-line code
-// whose operands are ALL requested when the kernel starts (ring_begin) and arrive while the caller does other
-// work.  The two stages run on different waves: waves 0 .. IT JT - 1 take the tiles of stage 1, the next IT JT waves
+// The factor sizes are compile-time constants inside a decode kernel, so that both stages are straight-line code.
+// Every workgroup needs ALL operands -- the prepared factors and the row, 56 KB at 64 x 80 -- and each of its tiles
+// needs a third of them; fetched per tile that is 138 KB per workgroup through a 64 B/clk L1 and, summed over the
+// chip, most of what the L2 can deliver in the time available.  So the workgroup fetches every operand ONCE:
+// all NTHR threads copy the prepared buffer and the row into an LDS scratch area (requested when the kernel
+// starts -- begin -- and stored when they have arrived), and the tiles read their operands from there.  The row's
+// lines are padded by 16 bytes so that the 16-byte reads of 16 consecutive rows hit different banks.
+// Waves 0 .. IT JT - 1 take the tiles of stage 1, the next IT JT waves those of stage 2 (one tile each).
+template <int N1, int N2, int NTHR>
+struct Shared {
+  static constexpr int IT = (N1 + 31) / 32, JT = (N2 + 31) / 32, KS1 = (N1 + 15) / 16, KS2 = N2 / 16;
+  static constexpr int NT = IT * JT;                    // tiles per stage
+  static_assert(N2 % 16 == 0 && N1 >= 1 && N1 <= 128 && N2 <= 128, "factor sizes");
+  // the scratch area, in units of 16 bytes: P2op, P1op (as prepared), the row (N2 / 8 + 1 units per line), the
+  // tiles of the intermediate
+  static constexpr int kPrep = (JT * KS2 + IT * KS1) * 2 * 64;
+  static constexpr int kXLine = N2 / 8 + 1;
+  static constexpr int kXAt = kPrep, kX = N1 * kXLine;
+  static constexpr int kDxAt = kXAt + kX, kDx = JT * KS1 * 2 * 64;
+  static constexpr int kScratchBytes = (kDxAt + kDx) * 16;
+  static constexpr int kCopy = kPrep + N1 * (N2 / 8);   // units to copy
+  static constexpr int LPT = (kCopy + NTHR - 1) / NTHR; // per thread
+  struct Ring {
+    u32x4 r[LPT];
+    uint32_t sg[KS2];
+  };
+
+  static __device__ __forceinline__ void begin(const Geo& g, const uint16_t* __restrict__ x, int tid, int wave, int lane,
+                                                Ring& R) {
+    const u32x4* prep = (const u32x4*)g.prep;
+    const u32x4* x4 = (const u32x4*)x;
+#pragma unroll
+    for (int u = 0; u < LPT; ++u) {
+      const int i = tid + u * NTHR;
+      const u32x4* src = i < kPrep ? prep + i : x4 + min(i - kPrep, N1 * (N2 / 8) - 1);
+      R.r[u] = *src;
+    }
+    if (wave < NT) {                                            // the signs of this wave's stage-1 tile
+      const int a = wave / JT;
+      const int i1 = min(a * 32 + (lane & 31), N1 - 1);
+#pragma unroll
+      for (int u = 0; u < KS2; ++u) R.sg[u] = g.sign_bytes[(i1 * N2 + 16 * u + 8 * (lane >> 5)) >> 3];
+    }
+  }
+
+  // All waves of the workgroup call this (it holds two workgroup barriers); on return every wave has WRITTEN its
+  // part of xf -- the caller's next workgroup barrier makes the row visible.  xf: fp16 [N1 N2] in LDS; S: the
+  // scratch area in LDS (kScratchBytes).  R: what begin requested for this thread.
+  static __device__ __forceinline__ void transform_row(int tid, int wave, int lane, Ring& R, uint16_t* xf, u32x4* S) {
+    const int l32 = lane & 31, h = lane >> 5;
+#pragma unroll
+    for (int u = 0; u < LPT; ++u) {
+      const int i = tid + u * NTHR;
+      if (i < kPrep) {
+        S[i] = R.r[u];
+      } else if (i < kCopy) {
+        const int q = i - kPrep, row = q / (N2 / 8), col = q - row * (N2 / 8);
+        S[kXAt + row * kXLine + col] = R.r[u];
+      }
+    }
+    __syncthreads();
+    if (wave < NT) {                                            // ---- stage 1
+      const int a = wave / JT, c = wave - a * JT;
+      f32x16 dm, dc;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) dm[e] = dc[e] = 0.f;
+      const int i1 = a * 32 + l32;
+      const bool row_ok = i1 < N1;
+      const u32x4* ap = S + kXAt + min(i1, N1 - 1) * kXLine + h;
+      const u32x4* bp = S + (c * KS2 * 2) * 64 + lane;
+#pragma unroll
+      for (int u = 0; u < KS2; ++u) {
+        const uint32_t minus = ~R.sg[u] & 0xFFu;               // bit e set: element e changes sign
+        u32x4 av = ap[2 * u];
+        av.x ^= ((minus & 1u) << 15) | ((minus & 2u) << 30);
+        av.y ^= ((minus & 4u) << 13) | ((minus & 8u) << 28);
+        av.z ^= ((minus & 16u) << 11) | ((minus & 32u) << 26);
+        av.w ^= ((minus & 64u) << 9) | ((minus & 128u) << 24);
+        if (!row_ok) av = u32x4{0u, 0u, 0u, 0u};
+        dm = mfma16(av, bp[u * 128], dm);
+        dc = mfma16(av, bp[u * 128 + 64], dc);
+      }
+      // the tile as B operands of stage 2: step s2 of this row block takes elements 8 s2 .. 8 s2 + 7
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        if (2 * a + s2 < KS1) {
+          uint32_t qh[8], ql[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) split2(fmaf(dc[8 * s2 + e], 0x1p-11f, dm[8 * s2 + e]), qh[e], ql[e]);
+          u32x4* dst = S + kDxAt + ((c * KS1 + 2 * a + s2) * 2) * 64 + lane;
+          dst[0] = u32x4{qh[0] | qh[1] << 16, qh[2] | qh[3] << 16, qh[4] | qh[5] << 16, qh[6] | qh[7] << 16};
+          dst[64] = u32x4{ql[0] | ql[1] << 16, ql[2] | ql[3] << 16, ql[4] | ql[5] << 16, ql[6] | ql[7] << 16};
+        }
+      }
+    }
+    __syncthreads();
+    if (wave >= NT && wave < 2 * NT) {                          // ---- stage 2
+      const int a = (wave - NT) / JT, c = (wave - NT) - a * JT;
+      const u32x4* ap = S + (JT * KS2 * 2) * 64 + (a * KS1 * 2) * 64 + lane;
+      const u32x4* bp = S + kDxAt + (c * KS1 * 2) * 64 + lane;
+      f32x16 zm, zc;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) zm[e] = zc[e] = 0.f;
+#pragma unroll
+      for (int u = 0; u < KS1; ++u) {
+        const u32x4 a0 = ap[u * 128], a1 = ap[u * 128 + 64];
+        const u32x4 b0 = bp[u * 128], b1 = bp[u * 128 + 64];
+        zm = mfma16(a0, b0, zm);
+        zc = mfma16(a1, b0, zc);
+        zc = mfma16(a0, b1, zc);
+      }
+      const int j2 = c * 32 + l32;
+      if (j2 < N2) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int j1 = a * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
+          if (j1 < N1) xf[j1 * N2 + j2] = __builtin_bit_cast(uint16_t, (_Float16)fmaf(zc[e], 0x1p-11f, zm[e]));
+        }
+      }
+    }
+  }
+};
+
+// not fused: nothing to hold
+template <int NTHR>
+struct Shared<0, 0, NTHR> {
+  struct Ring {};
+  static constexpr int NT = 0, kScratchBytes = 0;
+};
+
+// Direct: every tile fetches its own operands from global memory into registers -- for the kernel that transforms
+// one row by itself (one workgroup per 32 output columns: nothing is shared between its tiles but the row), where
+// the scratch area of Shared would not fit (108 x 128).  The factor sizes are compile-time constants, so that both
+// stages are straight-line code whose operands are ALL requested when the kernel starts (ring_begin).  The two stages run on different waves: waves 0 .. IT JT - 1 take the tiles of stage 1, the next IT JT waves
 // those of stage 2 (one tile each: the workgroup needs 2 IT JT waves).  One register file serves both roles:
 // stage 1 holds (a, b hi, b lo) of step u in r[3 u ..], stage 2 (a hi, a lo) in r[2 u ..].
 template <int N1, int N2>
-struct Fixed {
+struct Direct {
   static constexpr int IT = (N1 + 31) / 32, JT = (N2 + 31) / 32, KS1 = (N1 + 15) / 16, KS2 = N2 / 16;
   static constexpr int NT = IT * JT;                    // tiles per stage
   static constexpr int NR = 3 * KS2 > 2 * KS1 ? 3 * KS2 : 2 * KS1;
@@ -188,10 +319,6 @@ struct Fixed {
 };
 
 // not fused: nothing to hold
-template <>
-struct Fixed<0, 0> {
-  struct Ring {};
-};
 
 }  // namespace ftr
 }  // namespace btc

@@ -63,6 +63,9 @@ static bool engine_uses_workspace(int engine) {
   return engine == BTC_ENGINE_LUT || engine == BTC_ENGINE_MFMA || engine == BTC_ENGINE_TILED;
 }
 
+// Whether btc_gemv on this shape and batch parks anything in (and expects zeros in) its workspace.
+bool gemv_auto_uses_workspace(const Dims& d, int batch) { return engine_uses_workspace(choose_engine(d, batch)); }
+
 // One decode call through a chosen engine (engine = BTC_ENGINE_AUTO: the dispatcher's own choice).  A forced
 // engine that does not cover the shape or the batch returns BTC_ERR_UNSUPPORTED.
 static btc_status gemv_dispatch(int engine, void* stream, const btc_shape* s, const uint32_t* packed,

@@ -71,8 +71,9 @@ constexpr int kLdsMax = 160 * 1024 - 64;
 // FUSED: the kernel first computes the transformed activation row into an LDS area of its own (fp16, the whole
 // reach of the strands, zeros past the end of the row) and takes its activations from there; the table then gets
 // as many copies as still fit.
-template <int V, int B, int T, int TEAMS, int CW, bool FUSED = false>
+template <int V, int B, int T, int TEAMS, int CW, int GN1 = 0, int GN2 = 0>
 struct Cfg {
+  static constexpr bool FUSED = GN1 > 0;
   static constexpr int W = CW * TEAMS;                      // waves per workgroup
   static constexpr bool WIDE = CW == 16;
   static constexpr int G = 3;                               // chunks per 128-bit operand of a lane
@@ -93,14 +94,17 @@ struct Cfg {
   static_assert(!WIDE || 16 * S * 4 >= kSetBytes, "a set fits the wave's index area");
   static constexpr int kXfElems = CW * 4 * L * V;           // elements the strands of a team reach
   static constexpr int kXfBytes = FUSED ? ((kXfElems * 2 + 15) & ~15) : 0;
-  static constexpr int kRestBytes = kRedBytes + kIdxBytes + kStageBytes + kXfBytes;
+  // the index and staging areas; FUSED: before they are used, the scratch area of the transform (all its operands
+  // and the tiles of its intermediate), which may be larger
+  static constexpr int kTrBytes = ftr::Shared<GN1, GN2, CW * TEAMS * 64>::kScratchBytes;
+  static constexpr int kWorkBytes = kIdxBytes + kStageBytes > kTrBytes ? kIdxBytes + kStageBytes : kTrBytes;
+  static constexpr int kRestBytes = kRedBytes + kWorkBytes + kXfBytes;
   static constexpr int C0 = (B <= 8) ? 32 : (B == 9) ? 16 : 8;  // table copies (32: no two lanes of a wave share a bank pair)
   static constexpr bool fits(int c) { return (1 << B) * c * 8 + kRestBytes <= kLdsMax; }
   static constexpr int C = (!FUSED || fits(C0)) ? C0 : (C0 >= 16 && fits(C0 / 2)) ? C0 / 2 : (C0 >= 32 && fits(C0 / 4)) ? C0 / 4 : C0;
   static constexpr int LOG2C = C == 32 ? 5 : (C == 16 ? 4 : 3);
   static constexpr int kTableBytes = (1 << B) * C * 8;
   static constexpr int kLdsBytes = kTableBytes + kRestBytes;
-  static constexpr int kExchangeBytes = kIdxBytes + kStageBytes;   // FUSED: the tiles of the intermediate pass through here
   static_assert(V == 9 || V == 10, "three chunks per operand, tails of one or two elements");
   static_assert(B >= 7 && B <= 10, "table of at most 64 KB");
   static_assert(LPR <= 32, "at least two rows per load instruction");
@@ -197,8 +201,9 @@ template <int V, int B, int T, int TEAMS, int CW, int GN1, int GN2>
 __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
     Dims d, Multi mm, const __half* __restrict__ x, int y_is_f32, int n_rb, int x_dword, ftr::Geo geo) {
   constexpr bool FUSED = GN1 > 0;
-  using K = Cfg<V, B, T, TEAMS, CW, FUSED>;
-  using FT = ftr::Fixed<GN1, GN2>;
+  using K = Cfg<V, B, T, TEAMS, CW, GN1, GN2>;
+  using FT = ftr::Shared<GN1, GN2, CW * TEAMS * 64>;
+  constexpr int FT_NT = FT::NT;                               // tiles per stage of the transform
   static_assert(!FUSED || V == 10, "the fused prologue reads aligned pairs of activations from LDS");
   constexpr bool WIDE = K::WIDE;
   constexpr int W = K::W, G = K::G, TAIL = K::TAIL, ND = K::ND, C = K::C, L = K::L;
@@ -210,7 +215,7 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
   int* scl = (int*)(sxp + W);                                                   // [CW][2] block scale exponents
   uint32_t* idx_all = (uint32_t*)(smem + K::kTableBytes + K::kRedBytes);       // [W][16][S]
   unsigned char* bstage_all = smem + K::kTableBytes + K::kRedBytes + K::kIdxBytes;  // [CW][NSET][2048]; wide: [W][2048]
-  uint16_t* xf = (uint16_t*)(smem + K::kTableBytes + K::kRedBytes + K::kIdxBytes + K::kStageBytes);   // FUSED: [kXfElems]
+  uint16_t* xf = (uint16_t*)(smem + K::kTableBytes + K::kRedBytes + K::kWorkBytes);   // FUSED: [kXfElems]
 
   const int tid = threadIdx.x, lane = tid & 63;
   STAMP(0);
@@ -231,10 +236,15 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
   // An item is 16 consecutive B bytes of one step: (step t, strand qa, half h) = slots e = 16 h .. 16 h + 15
   // of strand qa.  Slot k = 32 qa + e of an instruction sits in B lane k block q' = 2 (qa & 1) + (e >> 4) at
   // byte 16 (qa >> 1) + (e & 15).  The two teams share the B operands: team h prepares the items of half h.
-  constexpr int KPT = ((1 << B) + W * 64 - 1) / (W * 64);
+  // FUSED: the waves that own a stage-1 tile of the transform leave the table to the others, so that their
+  // matrix-core work overlaps the table build instead of following it.
+  constexpr int TW0 = FUSED ? FT_NT : 0;                     // first wave that builds the table
+  constexpr int TT = (W - TW0) * 64;                         // threads that build it
+  constexpr int KPT = ((1 << B) + TT - 1) / TT;
+  const int ttid = tid - TW0 * 64;                           // this thread's number among them (negative: not one)
   uint32_t cwd[KPT];
 #pragma unroll
-  for (int i = 0; i < KPT; ++i) cwd[i] = codebook[min(tid + i * W * 64, (1 << B) - 1)];
+  for (int i = 0; i < KPT; ++i) cwd[i] = codebook[min(max(ttid, 0) + i * TT, (1 << B) - 1)];
   unsigned char* bstage = WIDE ? (unsigned char*)(idx_all + wave * (16 * S)) : bstage_all + cw * (K::NSET * kSetBytes);
   const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)x, 0, d.in * 2, kRsrcFlags);
   // With two teams, team e prepares the steps t = e, e + 2, ...: a step's B operand then carries one block
@@ -393,7 +403,7 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
   // the operands of the transform are requested after the first index words: they queue behind them in the
   // memory pipeline of the compute unit and are needed later
   typename FT::Ring ring;
-  if constexpr (FUSED) FT::ring_begin(geo, (const uint16_t*)x, wave, lane, ring);
+  if constexpr (FUSED) FT::begin(geo, (const uint16_t*)x, tid, wave, lane, ring);
   STAMP(1);
 
   // ---- codebook -> table of nibble patterns, every entry C times.  Thread k writes its entry's copies in
@@ -401,8 +411,8 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
   // bank pairs, although an entry's copies are 128 bytes or more apart from the next entry's.
 #pragma unroll
   for (int i = 0; i < KPT; ++i) {
-    const int k = tid + i * W * 64;
-    if (k < (1 << B)) {
+    const int k = ttid + i * TT;
+    if (ttid >= 0 && k < (1 << B)) {
       const unsigned long long ent = expand_codeword<V>(cwd[i]);
 #pragma unroll
       for (int c = 0; c < C; ++c) table[k * C + ((c + k) & (C - 1))] = ent;
@@ -414,8 +424,8 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
     // the transformed row: zeros past its end, the row itself by the matrix cores; the tiles of the intermediate
     // pass through the index and staging areas, which nothing has used yet
     for (int i = d.in + tid; i < K::kXfElems; i += W * 64) xf[i] = 0;
-    static_assert(!FUSED || 2 * ftr::Fixed<GN1, GN2>::NT <= W, "a wave per tile and stage");
-    FT::transform_row(wave, lane, ring, xf, (uint4*)idx_all);
+    static_assert(!FUSED || 2 * FT::NT <= W, "a wave per tile and stage");
+    FT::transform_row(tid, wave, lane, ring, xf, (ftr::u32x4*)idx_all);
     STAMP(3);
     __syncthreads();
     STAMP(4);
@@ -701,11 +711,8 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
 
 template <int V, int B, int T, int TEAMS, int CW, int GN1, int GN2>
 static btc_status launch3(hipStream_t q, const Dims& d, const void* x, int y_is_f32, bool dry, const Extra& ex) {
-  constexpr bool FUSED = GN1 > 0;
-  using K = Cfg<V, B, T, TEAMS, CW, FUSED>;
+  using K = Cfg<V, B, T, TEAMS, CW, GN1, GN2>;
   static_assert(K::kLdsBytes <= kLdsMax, "LDS budget");
-  if constexpr (FUSED)
-    static_assert(ftr::exchange_bytes_c(GN1, GN2) <= K::kExchangeBytes, "the tiles of the intermediate fit");
   if (dry) return BTC_OK;         // only asked whether a kernel exists for this setting
   static bool attr_set = false;   // one-time kernel attribute, not call state
   if (!attr_set) {
@@ -786,9 +793,8 @@ static btc_status launch1(hipStream_t q, const Dims& d, const void* x, int y_is_
 template <int B, int N1, int N2>
 static btc_status launch_fused(hipStream_t q, const Dims& d, const void* x, int y_is_f32, bool dry, const Extra& ex) {
   constexpr int T = steps_for_chunks((N1 * N2 + 9) / 10, 8);
-  if constexpr (T > 0 && 2 * ftr::Fixed<N1, N2>::NT <= 16) {
-    if constexpr (Cfg<10, B, T, 2, 8, true>::kLdsBytes <= kLdsMax &&
-                  ftr::exchange_bytes_c(N1, N2) <= Cfg<10, B, T, 2, 8, true>::kExchangeBytes)
+  if constexpr (T > 0 && 2 * ftr::Shared<N1, N2, 1024>::NT <= 16) {
+    if constexpr (Cfg<10, B, T, 2, 8, N1, N2>::kLdsBytes <= kLdsMax)
       return launch3<10, B, T, 2, 8, N1, N2>(q, d, x, y_is_f32, dry, ex);
   }
   return BTC_ERR_UNSUPPORTED;

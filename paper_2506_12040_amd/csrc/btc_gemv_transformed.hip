@@ -55,12 +55,12 @@ static size_t x_region_bytes(const Dims& d) { return (((size_t)d.in * 2) + 255) 
 template <int N1, int N2>
 __global__ __launch_bounds__(128 * ((N1 + 31) / 32)) void transform_row_kernel(Geo g, const uint16_t* __restrict__ x,
                                                                              uint16_t* __restrict__ y) {
-  using FT = Fixed<N1, N2>;
+  using FT = Direct<N1, N2>;
   extern __shared__ __align__(16) unsigned char smem[];
   const int lane = threadIdx.x & 63;
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int c = blockIdx.x;
-  // the tile numbering of Fixed: stage-1 wave a JT + c, stage-2 wave NT + a JT + c
+  // the tile numbering of Direct: stage-1 wave a JT + c, stage-2 wave NT + a JT + c
   const int vw = wv < FT::IT ? wv * FT::JT + c : FT::NT + (wv - FT::IT) * FT::JT + c;
   typename FT::Ring ring;
   FT::ring_begin(g, x, vw, lane, ring);
@@ -69,7 +69,7 @@ __global__ __launch_bounds__(128 * ((N1 + 31) / 32)) void transform_row_kernel(G
 
 template <int N1, int N2>
 static btc_status launch_row(hipStream_t q, const Geo& g, const void* x, void* y) {
-  using FT = Fixed<N1, N2>;
+  using FT = Direct<N1, N2>;
   const size_t lds = exchange_bytes_c(N1, N2);
   static bool attr_set = false;   // one-time kernel attribute, not call state
   if (!attr_set) {

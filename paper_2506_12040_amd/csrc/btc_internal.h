@@ -31,6 +31,8 @@ btc_status gemv_lut(hipStream_t q, const Dims& d, const uint32_t* packed, const 
 bool expand_engine_covers(const Dims& d);
 btc_status gemv_expand(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
                        const float* alpha, const float* mu, const void* x, void* y, int y_is_f32);
+// Whether btc_gemv's own choice of engine for this shape and batch uses (and wants zero-filled) its workspace.
+bool gemv_auto_uses_workspace(const Dims& d, int batch);
 // Engine on the 4-bit matrix cores (btc_gemv_fp4.hip): weights as E2M1, activations as E5M2 pieces; one
 // kernel, no workspace.
 bool gemv_fp4_covers(const Dims& d);
