@@ -57,6 +57,35 @@ def test_multi_matches_the_oracle_and_the_single_calls(G, oracle, out, n_in, v, 
             assert torch.equal(y1, Y.payload.view(-1)), f"matrix {m}: one launch and single call differ"
 
 
+def test_configuration_2_as_the_benchmark_launches_it(G, oracle):
+    """The 13B decoder-layer step the way bench.py launches it: q, k, v (three copies of the 5120x5120 layer of the
+    recipe, rows rotated as the benchmark rotates them) in one launch, gate and up (two copies of 13824x5120) in
+    one launch; Zipf(1.1) indices; every output of every matrix against the oracle."""
+    import torch
+    B = G.B
+    cases = [c for c in S.config_cases(2)]
+    for case, count in ((cases[0], 3), (cases[1], 2)):
+        layer, x = S.make_case(**case)
+        print(f"config 2 grouped: {layer.out}x{layer.n_in} x {count}", flush=True)
+        dl = G.DeviceLayer(layer, oracle)
+        shifts = [((L * 7 + r * 3 + 1) * 37) % layer.out for (L, r) in ((0, 0), (0, 1), (1, 2))][:count]
+        packed2d = dl.packed.view(layer.out, -1)
+        copies = [torch.roll(packed2d, shifts=sft, dims=0).contiguous() for sft in shifts]
+        ws = torch.zeros(B.btc_workspace_bytes(dl.shape, 1, False), dtype=torch.uint8, device="cuda")
+        Ys = [G.GuardedOutput(1, layer.out, torch.float16) for _ in range(count)]
+        B.btc_gemv_multi(dl.shape, copies, [dl.codebook] * count, [dl.alpha] * count, [dl.mu] * count, G.dev(x),
+                         [Y.payload for Y in Ys], B.BTC_F16, ws)
+        for sft, Y in zip(shifts, Ys):
+            Y.check_guards()
+            # rolling the packed rows by s moves weight row i to row i + s: y[i + s] = alpha[i + s] * d[i] + mu[i + s] * sum(x);
+            # the oracle of the rolled matrix is computed from the rolled index matrix
+            rolled = np.roll(dl.packed_host, sft, axis=0)
+            y_ref = np.concatenate([oracle.linear(rolled, dl.codebook_host, layer.alpha, layer.mu, x, layer.n_in, layer.v,
+                                                  layer.K, rows=np.arange(r0, min(layer.out, r0 + 4096)))
+                                    for r0 in range(0, layer.out, 4096)], axis=1)
+            G.assert_close(Y.numpy(), y_ref, f"rolled by {sft}")
+
+
 def test_argument_errors(G):
     import torch
     B = G.B
