@@ -147,6 +147,7 @@ btc_status btc_gemv_transformed_multi(void* stream, const btc_shape* s, int32_t 
     if (!aligned16(packed[m]) || !aligned16(codebook[m]) || !aligned16(alpha[m]) || !aligned16(mu[m]) || !aligned16(y[m]))
       return BTC_ERR_ALIGN;
   }
+  if (xt_out == x) return BTC_ERR_UNSUPPORTED;   // workgroups read x while another one stores the transformed row
   const Dims d = dims_of(*s);
   hipStream_t q = (hipStream_t)stream;
   if (prepared && gemv_fp4_fused_covers(d, n1, n2))

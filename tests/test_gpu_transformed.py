@@ -163,6 +163,9 @@ def test_prepare_argument_errors(G):
     with pytest.raises(BB.BtcError) as e:      # n1 n2 != in
         B.btc_gemv_transformed(s, t, t, t, t, t, 64, 64, t, t, t, None, t, B.BTC_F32, t)
     assert e.value.status == BB.BTC_ERR_SHAPE
+    with pytest.raises(BB.BtcError) as e:      # the transformed row must not land on the input
+        B.btc_gemv_transformed(s, t, t, t, t, t, 64, 80, t, t, t, None, t[4096:], B.BTC_F32, t, xt_out=t)
+    assert e.value.status == BB.BTC_ERR_UNSUPPORTED
     with pytest.raises(BB.BtcError) as e:      # two launches need the workspace
         B.btc_gemv_transformed(s, t, t, t, t, t, 64, 80, t, t, t, None, t, B.BTC_F32, None)
     assert e.value.status == BB.BTC_ERR_WORKSPACE
