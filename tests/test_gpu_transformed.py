@@ -36,6 +36,19 @@ def _fp16_bits(a):
     return np.ascontiguousarray(a.astype(np.float16)).view(np.uint16)
 
 
+def _same_up_to_rounding(got, ref, n):
+    """Two fp16 rows that should be the same rounding of the same numbers: a few elements (about one in a thousand:
+    those within the arithmetic's error of a rounding boundary) may fall to the neighbouring fp16 value, none
+    further -- except outputs that are tiny next to the row (cancellation), which are held to the absolute error
+    of the fp32 sums, 1e-6 of the row's largest element."""
+    diff = np.nonzero(got != ref)[0]
+    assert len(diff) <= max(4, n // 200), len(diff)
+    g = got[diff].view(np.float16).astype(np.float64)
+    r = ref[diff].view(np.float16).astype(np.float64)
+    big = np.max(np.abs(ref.view(np.float16).astype(np.float64)))
+    assert np.all(np.abs(g - r) <= np.maximum(np.abs(r) * 2.0 ** -10, 1e-6 * big)), (g, r)
+
+
 @pytest.mark.parametrize("out,n1,n2,v,K,prep,scale", CASES)
 def test_transformed_layer_matches_the_oracle(G, oracle, out, n1, n2, v, K, prep, scale):
     import torch
@@ -81,7 +94,7 @@ def test_transformed_layer_matches_the_oracle(G, oracle, out, n1, n2, v, K, prep
         if yd == B.BTC_F32:
             # the row handed out: the oracle's up to the rounding of a few elements, and exactly the row the product used
             got = XT.payload.cpu().numpy().view(np.uint16)
-            assert np.count_nonzero(got != xt_bits[0]) <= max(2, n // 500)
+            _same_up_to_rounding(got, xt_bits[0], n)
             Y3 = torch.empty(out, dtype=torch.float32, device="cuda")
             ws3 = torch.zeros(B.btc_workspace_bytes(dl.shape, 1, False), dtype=torch.uint8, device="cuda")
             if fused:
@@ -98,7 +111,7 @@ def test_transformed_layer_matches_the_oracle(G, oracle, out, n1, n2, v, K, prep
     assert rel <= 2e-4, rel
     # the transformed row itself, rounded: at most a few elements may differ from the oracle's rounding, by one ulp
     got = xt_d.cpu().numpy().view(np.uint16)
-    assert np.count_nonzero(got != xt_bits[0]) <= max(2, n // 500)
+    _same_up_to_rounding(got, xt_bits[0], n)
 
 
 @pytest.mark.parametrize("out,n1,n2,K,count", [(5120, 64, 80, 256, 3), (13824, 64, 80, 256, 2), (1000, 64, 64, 512, 4),
