@@ -109,6 +109,9 @@ __device__ __forceinline__ void load_to_lds_16(const __amdgpu_buffer_rsrc_t& rsr
 #endif
 }
 
+constexpr int kRowsAtOnce = 4;      // rows of index words a block of the first kernel holds in LDS
+constexpr int kRowWords = 1024;     // words per such row at most (longer rows: read from memory)
+
 // ---- first kernel: the sign matrix as bytes, WB[out][pitch] (pitch = 80 * number of k-tiles; the
 // columns past `in` hold the rest of the last chunk's pattern, then zeros: they only ever meet
 // zero activations).  One thread per 16 bytes at a time.  The first blocks of the grid (all but
@@ -149,10 +152,53 @@ __global__ __launch_bounds__(256) void expand_signs_kernel(Dims d, const uint32_
   const int pieces = pitch >> 4;
   const uint32_t id = (blockIdx.x - (uint32_t)sum_blocks) * 256u + threadIdx.x;       // out * pitch < 2^31
   const uint32_t mask = (1u << d.b) - 1u;
-  if (d.v == 10 && d.b <= 10) {
+  if (d.v == 10 && d.b <= 10 && d.wpr <= kRowWords) {
     // Chunk length 10: the 16 columns of a piece lie inside three consecutive chunks.  Their
     // (inverted) patterns, from a table in LDS, are strung together, shifted to the piece's first
     // column, and every 4 bits are spread over the 4 bytes of a word by one 24-bit multiply.
+    // A block takes kRowsAtOnce rows at a time: their index words are fetched once, coalesced, into
+    // LDS, and the threads pick their three index fields from there (as loads from memory the
+    // six words per thread cost more than everything else in this kernel).
+    __shared__ uint32_t npat[1024];
+    __shared__ uint32_t words[kRowsAtOnce * kRowWords + 1];
+    for (int k = threadIdx.x; k < (1 << d.b); k += 256) npat[k] = ~codebook[k] & 0x3FFu;
+    const int groups = (d.out + kRowsAtOnce - 1) / kRowsAtOnce;
+    for (int grp = (int)blockIdx.x - sum_blocks; grp < groups; grp += expand_blocks) {
+      const int row0 = grp * kRowsAtOnce, rows = min(kRowsAtOnce, d.out - row0);
+      __syncthreads();                                     // the previous group's words are no longer read
+      for (int i = threadIdx.x; i < rows * d.wpr; i += 256) words[i] = packed[(size_t)row0 * d.wpr + i];
+      __syncthreads();
+      int r = 0, pc = threadIdx.x;
+      while (pc >= pieces) { pc -= pieces; ++r; }
+      while (r < rows) {
+        const uint32_t* prow = words + r * d.wpr;
+        const int j0 = (pc * 16) / 10, t0 = pc * 16 - 10 * j0;
+        uint32_t bits = 0u;
+#pragma unroll
+        for (int u = 0; u < 3; ++u) {
+          const int j = j0 + u;
+          if (j < d.nchunks) {                             // (past the last chunk: +1 bytes, they meet zero activations)
+            const uint32_t bit = (uint32_t)j * (uint32_t)d.b;
+            const uint32_t w0 = bit >> 5, sh = bit & 31u;
+            const uint32_t lo = prow[w0];
+            const uint32_t hi = prow[w0 + 1];              // (one word past the row at most: inside `words`, shifted out)
+            bits |= npat[__builtin_amdgcn_alignbit(hi, lo, sh) & mask] << (10 * u);
+          }
+        }
+        const uint32_t n16 = bits >> t0;
+        uint32_t w[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          w[q] = (((__umul24((n16 >> (4 * q)) & 0xFu, 0x204081u)) & 0x01010101u) << 7) | (hi_byte * 0x01010101u);
+        *(uint4*)(WB + (size_t)(row0 + r) * pitch + (size_t)pc * 16) = make_uint4(w[0], w[1], w[2], w[3]);
+        pc += 256;
+        while (pc >= pieces) { pc -= pieces; ++r; }
+      }
+    }
+    return;
+  }
+  if (d.v == 10 && d.b <= 10) {
+    // The same for rows too long for the LDS copy: index words straight from memory.
     __shared__ uint32_t npat[1024];
     for (int k = threadIdx.x; k < (1 << d.b); k += 256) npat[k] = ~codebook[k] & 0x3FFu;
     __syncthreads();
@@ -572,7 +618,10 @@ btc_status gemm_wide(hipStream_t q, const Dims& d, const uint32_t* packed, const
   float* rs = (float*)(WB + sign_bytes(d));
   const long long pieces = (long long)d.out * (pitch / 16);
   // a few thousand blocks that each walk over the pieces (the table in LDS is filled once per block)
-  const int expand_blocks = (int)std::min<long long>((pieces + 255) / 256, 2048), sum_blocks = (M + 3) / 4;
+  int expand_blocks = (int)std::min<long long>((pieces + 255) / 256, 2048);
+  const int sum_blocks = (M + 3) / 4;
+  if (d.v == 10 && d.b <= 10 && d.wpr <= kRowWords)      // blocks walk over groups of kRowsAtOnce rows
+    expand_blocks = std::min((d.out + kRowsAtOnce - 1) / kRowsAtOnce, 2048);
   if (is_bf16)
     expand_signs_kernel<true><<<expand_blocks + sum_blocks, 256, 0, q>>>(d, packed, codebook, WB, pitch, expand_blocks,
                                                                          (const uint16_t*)X, M, rs);
