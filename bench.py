@@ -546,7 +546,7 @@ def main():
         for case in S.config_cases(3):
             cases3.setdefault(case["batch"], []).append(case)
         for M in sorted({args.gemm_m, 512}, reverse=True):
-            per, tot_flop, tot_ms = {}, 0.0, 0.0
+            per, tot_flop, tot_ms, tot_ms_b = {}, 0.0, 0.0, 0.0
             for case in cases3.get(M) or [dict(c, batch=M) for c in cases3[2048]]:
                 p = device_case(case)
                 s = p["s"]
@@ -569,9 +569,25 @@ def main():
                 per[f"{s.out}x{s.in_}"] = dict(ms=round(ms, 4), tflops=round(flop / ms / 1e9, 1))
                 tot_flop += flop * cnt
                 tot_ms += ms * cnt
-                del X, Y, p
+                # the same call with the output rounded to bf16 (half the bytes written by the epilogue)
+                Yb = torch.empty(M * s.out, dtype=torch.bfloat16, device=dev)
+                callb = lambda: B.btc_gemm(s, p["packed"], p["codebook"], p["alpha"], p["mu"], X, B.BTC_BF16, M, Yb,
+                                           B.BTC_BF16, wsg)
+                callb()
+                torch.cuda.synchronize()
+                e0, e1 = events()
+                e0.record()
+                for _ in range(args.gemm_iters):
+                    callb()
+                e1.record()
+                torch.cuda.synchronize()
+                msb = e0.elapsed_time(e1) / args.gemm_iters
+                per[f"{s.out}x{s.in_}"]["tflops_bf16_out"] = round(flop / msb / 1e9, 1)
+                tot_ms_b += msb * cnt
+                del X, Y, Yb, p
             tf = tot_flop / tot_ms / 1e9
             gemm[f"M{M}"] = dict(M=M, x_dtype="bf16", y_dtype="f32", per_shape=per, layer_tflops=round(tf, 1),
+                                 layer_tflops_bf16_out=round(tot_flop / tot_ms_b / 1e9, 1),
                                  frac_mfma_peak=round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
                                  frac_measured_peak=round(tf / MFMA_BF16_MEASURED_TFLOPS, 4))
 
