@@ -120,3 +120,55 @@ def test_argument_checks_need_no_gpu(B):
     t = B.btc_shape_init(64, 100, 10, 512)
     t.words_per_row += 1                 # a shape edited after btc_shape_init
     assert L.btc_unpack(None, ctypes.byref(t), fake, fake) == E.BTC_ERR_SHAPE
+
+
+def test_argument_checks_of_the_later_entry_points(B):
+    """btc_gemv_multi, btc_gemv_groups, btc_transform_prepare, btc_gemv_transformed(_multi), btc_quantize_rows,
+    btc_gemm_aq: rejected calls return before anything is enqueued."""
+    L = B.lib()
+    E = B.binding
+    s = B.btc_shape_init(64, 5120, 10, 256)
+    sp = ctypes.byref(s)
+    fake, odd, other = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1004), ctypes.c_void_p(0x2000)
+    arr = lambda *ps: (ctypes.c_void_p * len(ps))(*[p.value if p is not None else None for p in ps])
+    four = arr(fake, fake, fake, fake)
+    # several matrices in one launch
+    assert L.btc_gemv_multi(None, sp, 0, four, four, four, four, fake, four, E.BTC_F16, None, 0) == E.BTC_ERR_UNSUPPORTED
+    assert L.btc_gemv_multi(None, sp, 5, four, four, four, four, fake, four, E.BTC_F16, None, 0) == E.BTC_ERR_UNSUPPORTED
+    assert L.btc_gemv_multi(None, sp, 2, None, four, four, four, fake, four, E.BTC_F16, None, 0) == E.BTC_ERR_NULL
+    assert L.btc_gemv_multi(None, sp, 2, arr(fake, None), four, four, four, fake, four, E.BTC_F16, None, 0) == E.BTC_ERR_NULL
+    assert L.btc_gemv_multi(None, sp, 2, arr(fake, odd), four, four, four, fake, four, E.BTC_F16, None, 0) == E.BTC_ERR_ALIGN
+    assert L.btc_gemv_multi(None, sp, 2, four, four, four, four, fake, four, E.BTC_BF16, None, 0) == E.BTC_ERR_UNSUPPORTED
+    # several (alpha, mu) groups per row
+    assert L.btc_gemv_groups(None, sp, fake, fake, fake, fake, fake, 0, fake, fake, E.BTC_F32) == E.BTC_ERR_UNSUPPORTED
+    assert L.btc_gemv_groups(None, sp, fake, fake, fake, fake, fake, 5, fake, fake, E.BTC_F32) == E.BTC_ERR_UNSUPPORTED
+    assert L.btc_gemv_groups(None, sp, fake, fake, fake, fake, None, 2, fake, fake, E.BTC_F32) == E.BTC_ERR_NULL
+    assert L.btc_gemv_groups(None, sp, fake, fake, fake, fake, odd, 2, fake, fake, E.BTC_F32) == E.BTC_ERR_ALIGN
+    assert L.btc_gemv_groups(None, sp, fake, fake, fake, fake, fake, 2, fake, fake, E.BTC_BF16) == E.BTC_ERR_UNSUPPORTED
+    # the transform inside the product
+    assert L.btc_transform_prepared_bytes(64, 80) == (3 * 5 + 2 * 4) * 2048 and L.btc_transform_prepared_bytes(64, 81) == 0
+    assert L.btc_transform_prepared_bytes(108, 128) == (4 * 8 + 4 * 7) * 2048 and L.btc_transform_prepared_bytes(128, 224) == 0
+    assert L.btc_transform_prepare(None, 64, 80, None, fake, fake, 1 << 20) == E.BTC_ERR_NULL
+    assert L.btc_transform_prepare(None, 0, 80, fake, fake, fake, 1 << 20) == E.BTC_ERR_SHAPE
+    assert L.btc_transform_prepare(None, 64, 81, fake, fake, fake, 1 << 20) == E.BTC_ERR_UNSUPPORTED
+    assert L.btc_transform_prepare(None, 64, 80, fake, fake, fake, 1024) == E.BTC_ERR_WORKSPACE
+    assert L.btc_transform_prepare(None, 64, 80, fake, odd, fake, 1 << 20) == E.BTC_ERR_ALIGN
+    gt = lambda *a: L.btc_gemv_transformed(None, sp, fake, fake, fake, fake, *a)
+    assert gt(fake, 64, 64, fake, fake, fake, None, None, other, E.BTC_F32, fake, 1 << 24) == E.BTC_ERR_SHAPE     # n1 n2 != in
+    assert gt(fake, 64, 80, None, fake, fake, None, None, other, E.BTC_F32, fake, 1 << 24) == E.BTC_ERR_NULL
+    assert gt(fake, 64, 80, fake, fake, fake, None, None, other, E.BTC_BF16, fake, 1 << 24) == E.BTC_ERR_UNSUPPORTED
+    assert gt(fake, 64, 80, fake, fake, fake, None, fake, other, E.BTC_F32, fake, 1 << 24) == E.BTC_ERR_UNSUPPORTED   # xt_out == x
+    assert gt(fake, 64, 80, fake, fake, fake, None, None, other, E.BTC_F32, None, 0) == E.BTC_ERR_WORKSPACE       # two launches
+    assert gt(fake, 64, 80, fake, odd, fake, None, None, other, E.BTC_F32, fake, 1 << 24) == E.BTC_ERR_ALIGN
+    assert L.btc_gemv_transformed_workspace_bytes(sp) >= 5120 * 2 + 16 and L.btc_gemv_transformed_workspace_bytes(None) == 0
+    assert L.btc_gemv_transformed_multi(None, sp, 5, four, four, four, four, fake, 64, 80, fake, fake, fake, None, None,
+                                        four, E.BTC_F32, fake, 1 << 24) == E.BTC_ERR_UNSUPPORTED
+    # the layer on activation codes
+    assert L.btc_quantize_rows(None, None, E.BTC_F16, 1, 64, 8, fake, fake, fake, None) == E.BTC_ERR_NULL
+    assert L.btc_quantize_rows(None, fake, E.BTC_F16, 0, 64, 8, other, fake, fake, None) == E.BTC_ERR_SHAPE
+    assert L.btc_quantize_rows(None, fake, E.BTC_F16, 1, 64, 5, other, fake, fake, None) == E.BTC_ERR_UNSUPPORTED
+    assert L.btc_quantize_rows(None, fake, E.BTC_F32, 1, 64, 8, other, fake, fake, None) == E.BTC_ERR_UNSUPPORTED
+    assert L.btc_aq_workspace_bytes(sp, 1) > 0 and L.btc_aq_workspace_bytes(None, 1) == 0
+    assert L.btc_gemm_aq(None, sp, fake, fake, fake, fake, fake, fake, fake, fake, 0, other, E.BTC_F32, fake, 1 << 26) == E.BTC_ERR_SHAPE
+    assert L.btc_gemm_aq(None, sp, fake, fake, fake, fake, None, fake, fake, fake, 1, other, E.BTC_F32, fake, 1 << 26) == E.BTC_ERR_NULL
+    assert L.btc_gemm_aq(None, sp, fake, fake, fake, fake, fake, fake, fake, fake, 1, other, E.BTC_F32, fake, 64) == E.BTC_ERR_WORKSPACE
