@@ -271,7 +271,7 @@ template <int NF, bool BF16>
 __global__ __launch_bounds__((kMW + kLW) * 64) void gemm_wide_kernel(
     int in, int out, const unsigned char* __restrict__ WB, int pitch, const float* __restrict__ alpha,
     const float* __restrict__ mu, const uint16_t* __restrict__ X, const float* __restrict__ rs_all, int M,
-    void* __restrict__ Y, int y_dtype, int m_blocks, int n_blocks) {
+    void* __restrict__ Y, int y_dtype, int m_blocks, int n_blocks, int gm) {
   constexpr int BN = 32 * NF;
   constexpr int kWJ = (BN * 5 + 63) / 64;                // weight loads (of 1 KB) per tile
   extern __shared__ __align__(16) unsigned char smem[];
@@ -282,15 +282,16 @@ __global__ __launch_bounds__((kMW + kLW) * 64) void gemm_wide_kernel(
   int mb, nb;
   {
     const int L = blockIdx.x;
-    if (m_blocks >= 8) {
-      const int xcd = L & 7, s = L >> 3;
-      const int per_xcd = (m_blocks + 7) >> 3;
-      mb = xcd + 8 * (s % per_xcd);
-      nb = s / per_xcd;
-    } else {
-      mb = L % m_blocks;
-      nb = L / m_blocks;
-    }
+    // Workgroup L runs on XCD L % 8.  The XCDs form a grid of gm x gn (gm gn = 8): XCD (xm, xn) takes the
+    // m blocks = xm (mod gm) and the n blocks = xn (mod gn), so the chip reads the weight bytes gm times and the
+    // activations gn times (through eight separate L2 caches); the host picks the split with the least traffic.
+    // Consecutive workgroups of an XCD share their weight tile.
+    const int x = L & 7, sq = L >> 3;
+    const int gn = 8 / gm;
+    const int xm = x % gm, xn = x / gm;
+    const int pm = (m_blocks + gm - 1) / gm;
+    mb = xm + gm * (sq % pm);
+    nb = xn + gn * (sq / pm);
     if (mb >= m_blocks || nb >= n_blocks) return;
   }
   const int m0 = mb * kBM, n0 = nb * BN;
@@ -585,9 +586,25 @@ static btc_status launch(hipStream_t q, const Dims& d, const unsigned char* WB, 
     attr_set = true;
   }
   const int m_blocks = (M + kBM - 1) / kBM, n_blocks = (d.out + 32 * NF - 1) / (32 * NF);
-  const int grid = m_blocks >= 8 ? 8 * ((m_blocks + 7) / 8) * n_blocks : m_blocks * n_blocks;
+  // split of the eight XCDs over m blocks (gm) and n blocks (8 / gm): least bytes read by the chip,
+  // gm x (weight bytes) + (8 / gm) x (activation bytes); no more XCD rows than m blocks
+  int gm = 1;
+  {
+    const double wbytes = (double)d.out * pitch, abytes = (double)M * d.in * 2;
+    double best = 1e300;
+    for (int g = 1; g <= 8; g *= 2) {
+      if (g > m_blocks && g > 1) break;
+      if (8 / g > n_blocks && g < 8) continue;
+      const double t = g * wbytes + (8 / g) * abytes;
+      if (t < best) {
+        best = t;
+        gm = g;
+      }
+    }
+  }
+  const int grid = 8 * ((m_blocks + gm - 1) / gm) * ((n_blocks + 8 / gm - 1) / (8 / gm));
   gemm_wide_kernel<NF, BF16><<<grid, (kMW + kLW) * 64, 3 * kXB + 3 * kWBmax, q>>>(
-      d.in, d.out, WB, pitch, alpha, mu, (const uint16_t*)X, rs, M, Y, y_dtype, m_blocks, n_blocks);
+      d.in, d.out, WB, pitch, alpha, mu, (const uint16_t*)X, rs, M, Y, y_dtype, m_blocks, n_blocks, gm);
   return launch_status();
 }
 
