@@ -266,6 +266,18 @@ __global__ __launch_bounds__(256) void expand_signs_kernel(Dims d, const uint32_
   }
 }
 
+#ifdef BTC_WIDE_STAMPS
+__device__ unsigned long long g_stamps[3 * 2 * 16];
+// thread 0 of a loader wave (role 1) and of contraction wave 0 (role 0), in the first, middle and last workgroup
+#define WSTAMP(role, i)                                                                              \
+  do {                                                                                               \
+    if (lane == 0 && (blockIdx.x == 0 || blockIdx.x == gridDim.x / 2 || blockIdx.x == gridDim.x - 9))  \
+      g_stamps[((blockIdx.x == 0 ? 0 : (blockIdx.x == gridDim.x - 9 ? 2 : 1)) * 2 + (role)) * 16 + (i)] = wall_clock64(); \
+  } while (0)
+#else
+#define WSTAMP(role, i)
+#endif
+
 // ---- second kernel: the contraction
 template <int NF, bool BF16>
 __global__ __launch_bounds__((kMW + kLW) * 64) void gemm_wide_kernel(
@@ -350,9 +362,11 @@ __global__ __launch_bounds__((kMW + kLW) * 64) void gemm_wide_kernel(
     };
     // Tile t lives in buffer t % 3.  Its loads are issued right after the barrier that ends tile
     // t - 3 (whose buffer it takes over) and must have landed at the barrier that ends tile t - 1.
+    if (lw == 0) WSTAMP(1, 0);
     issue(0, 0);
     issue(1, 1);
     __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0)
+    if (lw == 0) WSTAMP(1, 1);
     __builtin_amdgcn_s_barrier();                        // tiles 0 and 1 are in LDS
     int buf = 2;
     for (int t = 0; t < nt; ++t) {
@@ -421,7 +435,9 @@ __global__ __launch_bounds__((kMW + kLW) * 64) void gemm_wide_kernel(
     if (s & 1) { lo = bq[set][c].z; hi = bq[set][c].w; }
     else { lo = bq[set][c].x; hi = bq[set][c].y; }
   };
+  if (wave == 0) WSTAMP(0, 0);
   __syncthreads();                                       // tiles 0 and 1 are in LDS
+  if (wave == 0) WSTAMP(0, 1);
   read_a(0, 0, 0);
   read_b(0, 0, 0);
   // Register sets: activations alternate per step, weights per 16-byte read (steps 0, 2, 4); a tile
@@ -485,6 +501,7 @@ __global__ __launch_bounds__((kMW + kLW) * 64) void gemm_wide_kernel(
     }
   }
 
+  if (wave == 0) WSTAMP(0, 2);
   // ---- epilogue.  After the last barrier the tile buffers are free; each wave uses a part of
   // them to turn its accumulators (lane = weight row n, 16 activation rows per register set)
   // into rows of Y, so that a lane stores 4 consecutive outputs at once.
@@ -504,6 +521,7 @@ __global__ __launch_bounds__((kMW + kLW) * 64) void gemm_wide_kernel(
     rsb[lane] = m < M ? rs_all[m] : 0.f;
   }
   wave_lds_sync();
+  if (wave == 0) WSTAMP(0, 3);
   const bool vec = (out & 3) == 0;                             // 4 outputs of a row are aligned and inside
 #pragma unroll
   for (int a = 0; a < 2; ++a) {
@@ -554,7 +572,12 @@ __global__ __launch_bounds__((kMW + kLW) * 64) void gemm_wide_kernel(
       }
     }
     wave_lds_sync();                                           // before the second half overwrites the rows
+    if (wave == 0) WSTAMP(0, 4 + a);
   }
+#ifdef BTC_WIDE_STAMPS
+  __builtin_amdgcn_s_waitcnt(0x0F70);                          // the stores have left
+  if (wave == 0) WSTAMP(0, 6);
+#endif
 }
 
 static int pitch_of(const Dims& d) { return (d.in + kKT - 1) / kKT * kKT; }
@@ -609,6 +632,12 @@ static btc_status launch(hipStream_t q, const Dims& d, const unsigned char* WB, 
 }
 
 }  // namespace wide
+
+#ifdef BTC_WIDE_STAMPS
+extern "C" int btc_debug_wide_stamps(unsigned long long* host, int n) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(wide::g_stamps), sizeof(unsigned long long) * n);
+}
+#endif
 
 bool gemm_wide_covers(const Dims& d, int M) {
   // worth its first kernel only when the 256 x 160 output tiles fill the chip (below that the tiled
