@@ -274,26 +274,32 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
     if constexpr (FUSED) return ok ? *(const uint32_t*)((const unsigned char*)xf + off) : 0u;
     else return __builtin_amdgcn_raw_buffer_load_b32(rx, ok ? off : kOob, 0, 0);
   };
+  // The loads of the aligned path (x_dword) are only issued by load_items; merge_items, called where the
+  // values are first needed, puts them together.  Every load of the prologue -- codewords, activations, first
+  // index words -- is then in flight before the first wait (merged on the spot, the activations cost a trip
+  // to memory of their own before the index words were even requested).
+  constexpr int NRAW = WIDE ? K::NSET : NI;
+  u32x4 raw_a[NRAW], raw_b[WIDE ? 1 : NI];
+  uint32_t raw_t[NRAW][3];
   auto load_items = [&]() __attribute__((always_inline)) {
   if constexpr (WIDE) {
+    if (x_dword) {
 #pragma unroll
-    for (int tt = 0; tt < K::NSET; ++tt) {
-      const int t = 4 * tt + (lane >> 4), qa = (lane >> 2) & 3, part = lane & 3;
-      const uint32_t xb = (uint32_t)((cw * 4 + qa) * L + G * t) * V;
-      const bool live = t < T;
-      if (x_dword) {
-        const u32x4 a4 = xl128(live && part < 3, (xb + part * V) * 2u);
-        uint32_t tl[3] = {0u, 0u, 0u};
-        if constexpr (TAIL == 2) {
+      for (int tt = 0; tt < K::NSET; ++tt) {
+        const int t = 4 * tt + (lane >> 4), qa = (lane >> 2) & 3, part = lane & 3;
+        const uint32_t xb = (uint32_t)((cw * 4 + qa) * L + G * t) * V;
+        const bool live = t < T;
+        raw_a[tt] = xl128(live && part < 3, (xb + part * V) * 2u);
 #pragma unroll
-          for (int c = 0; c < 3; ++c)
-            tl[c] = xl32(live && part == 3, (xb + c * V + 8u) * 2u);
-        }
-        hw[tt][0] = part < 3 ? a4[0] : tl[0];
-        hw[tt][1] = part < 3 ? a4[1] : tl[1];
-        hw[tt][2] = part < 3 ? a4[2] : tl[2];
-        hw[tt][3] = part < 3 ? a4[3] : 0u;
-      } else {
+        for (int c = 0; c < 3; ++c)
+          raw_t[tt][c] = TAIL == 2 ? xl32(live && part == 3, (xb + c * V + 8u) * 2u) : 0u;
+      }
+    } else {
+#pragma unroll
+      for (int tt = 0; tt < K::NSET; ++tt) {
+        const int t = 4 * tt + (lane >> 4), qa = (lane >> 2) & 3, part = lane & 3;
+        const uint32_t xb = (uint32_t)((cw * 4 + qa) * L + G * t) * V;
+        const bool live = t < T;
         uint32_t hv[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -317,28 +323,11 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
     // half 0: chunk 0 elements 0..7, chunk 1 elements 0..7; half 1: chunk 2 elements 0..7, then the tails
     const uint32_t run0 = h == 0 ? xb : xb + 2u * V;
     if (x_dword) {        // V and `in` even: every pair of elements is one aligned word
-      const u32x4 a4 = xl128(live, run0 * 2u);
+      raw_a[ii] = xl128(live, run0 * 2u);
+      raw_b[ii] = xl128(live && h == 0, (xb + V) * 2u);
 #pragma unroll
-      for (int k = 0; k < 4; ++k) hx[ii][k] = a4[k];
-      {
-        const u32x4 b4 = xl128(live && h == 0, (xb + V) * 2u);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) hx[ii][4 + k] = b4[k];
-      }
-      {
-        if constexpr (TAIL == 2) {
-          uint32_t tl[3];
-#pragma unroll
-          for (int c = 0; c < 3; ++c)
-            tl[c] = xl32(live && h == 1, (xb + c * V + 8u) * 2u);
-          if (h == 1) {
-            hx[ii][4] = tl[0];
-            hx[ii][5] = tl[1];
-            hx[ii][6] = tl[2];
-            hx[ii][7] = 0u;
-          }
-        }
-      }
+      for (int c = 0; c < 3; ++c)
+        raw_t[ii][c] = TAIL == 2 ? xl32(live && h == 1, (xb + c * V + 8u) * 2u) : 0u;
     } else {
       uint32_t hv[16];
 #pragma unroll
@@ -361,6 +350,29 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
   }
 
   };   // load_items
+  // (out-of-range loads return zeros: a lane has either the second 16 bytes or the tails, never both)
+  auto merge_items = [&]() __attribute__((always_inline)) {
+    if (!x_dword) return;
+    if constexpr (WIDE) {
+#pragma unroll
+      for (int tt = 0; tt < K::NSET; ++tt) {
+        hw[tt][0] = raw_a[tt][0] | raw_t[tt][0];
+        hw[tt][1] = raw_a[tt][1] | raw_t[tt][1];
+        hw[tt][2] = raw_a[tt][2] | raw_t[tt][2];
+        hw[tt][3] = raw_a[tt][3];
+      }
+    } else {
+#pragma unroll
+      for (int ii = 0; ii < NI; ++ii) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) hx[ii][k] = raw_a[ii][k];
+        hx[ii][4] = raw_b[ii][0] | raw_t[ii][0];
+        hx[ii][5] = raw_b[ii][1] | raw_t[ii][1];
+        hx[ii][6] = raw_b[ii][2] | raw_t[ii][2];
+        hx[ii][7] = raw_b[ii][3];
+      }
+    }
+  };
   if constexpr (!FUSED) load_items();
 
   // ---- index words.  The wave's four strands are one contiguous piece of every row: LPR lanes fetch it as
@@ -443,6 +455,7 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
   // leaves at most 8 significant bits, exactly), written in B-operand layout: 16 bytes per item and piece
   // Block scale: 2^k brings the largest element this wave stages to 2^14..2^15 (positive fp16 bit patterns
   // order like integers); the B lanes that hold this wave's items hand 2^-k to the matrix instruction.
+  merge_items();
   float sx_lane = 0.f;
   int k_scale;
   {
