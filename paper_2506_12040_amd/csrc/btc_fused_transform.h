@@ -118,8 +118,11 @@ struct Shared {
       const u32x4* src = i < kPrep ? prep + i : x4 + min(i - kPrep, N1 * (N2 / 8) - 1);
       R.r[u] = *src;
     }
-    if (wave < NT) {                                            // the signs of this wave's stage-1 tile
-      const int a = wave / JT;
+    {
+      // the signs of this wave's stage-1 tile.  Waves without a tile fetch those of tile 0 and never use them: under
+      // a test of the wave number the compiler copies the fetched bytes where the two paths join, i.e. waits for
+      // them, and with them for every load requested before them, right here.
+      const int a = (wave < NT ? wave : 0) / JT;
       const int i1 = min(a * 32 + (lane & 31), N1 - 1);
 #pragma unroll
       for (int u = 0; u < KS2; ++u) R.sg[u] = g.sign_bytes[(i1 * N2 + 16 * u + 8 * (lane >> 5)) >> 3];

@@ -199,7 +199,7 @@ struct Extra {
 // GN1, GN2: factor sizes of the activation transform computed in front of the product (0, 0: none).
 template <int V, int B, int T, int TEAMS, int CW, int GN1, int GN2>
 __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
-    Dims d, Multi mm, const __half* __restrict__ x, int y_is_f32, int n_rb, int x_dword, ftr::Geo geo) {
+    Dims d_arg, Multi mm, const __half* __restrict__ x_arg, int y_is_f32_arg, int n_rb_arg, int x_dword_arg, ftr::Geo geo) {
   constexpr bool FUSED = GN1 > 0;
   using K = Cfg<V, B, T, TEAMS, CW, GN1, GN2>;
   using FT = ftr::Shared<GN1, GN2, CW * TEAMS * 64>;
@@ -223,14 +223,36 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
   const int cw = wave & (CW - 1), team = wave / CW;          // column wave, team
   const int r = lane & 15, q = lane >> 4;
   // this workgroup's matrix, and its number among the workgroups of that matrix
-  const int mat = mm.count > 1 ? (int)blockIdx.x / mm.wpm : 0;
-  const int bid = (int)blockIdx.x - mat * mm.wpm;
-  const uint32_t* __restrict__ packed = mm.packed[mat];
-  const uint32_t* __restrict__ codebook = mm.codebook[mat];
-  const float* __restrict__ alpha = mm.alpha[mat];
-  const float* __restrict__ mu = mm.mu[mat];
-  void* __restrict__ y = mm.y[mat];
-  const int stride = mm.wpm;                                 // row blocks between successive ones of a team slot
+  // No division, and the pointers of all four matrices are fetched from the kernel arguments at fixed offsets and
+  // then selected: indexed by `mat` they would be fetched only after `mat` is known -- three dependent trips to
+  // memory before the first vector load instead of one.  (The empty statement pins all fetches in front of the
+  // selection; left alone, the compiler moves each one under a branch on `mat`, behind the wait for `wpm`.)
+  int wpm = mm.wpm;
+  const uint32_t *pk0 = mm.packed[0], *pk1 = mm.packed[1], *pk2 = mm.packed[2], *pk3 = mm.packed[3];
+  const uint32_t *cb0 = mm.codebook[0], *cb1 = mm.codebook[1], *cb2 = mm.codebook[2], *cb3 = mm.codebook[3];
+  const float *al0 = mm.alpha[0], *al1 = mm.alpha[1], *al2 = mm.alpha[2], *al3 = mm.alpha[3];
+  const float *mu0 = mm.mu[0], *mu1 = mm.mu[1], *mu2 = mm.mu[2], *mu3 = mm.mu[3];
+  void *y0 = mm.y[0], *y1 = mm.y[1], *y2 = mm.y[2], *y3 = mm.y[3];
+  Dims d = d_arg;
+  const __half* x = x_arg;
+  int y_is_f32 = y_is_f32_arg, n_rb = n_rb_arg, x_dword = x_dword_arg;
+  asm volatile("" : "+s"(wpm), "+s"(pk0), "+s"(pk1), "+s"(pk2), "+s"(pk3), "+s"(cb0), "+s"(cb1), "+s"(cb2), "+s"(cb3),
+                    "+s"(al0), "+s"(al1), "+s"(al2), "+s"(al3), "+s"(mu0), "+s"(mu1), "+s"(mu2), "+s"(mu3),
+                    "+s"(y0), "+s"(y1), "+s"(y2), "+s"(y3), "+s"(x), "+s"(y_is_f32), "+s"(n_rb), "+s"(x_dword),
+                    "+s"(d.in), "+s"(d.out), "+s"(d.wpr));
+  const int bx = (int)blockIdx.x;
+  const int mat = (bx >= wpm ? 1 : 0) + (bx >= 2 * wpm ? 1 : 0) + (bx >= 3 * wpm ? 1 : 0);
+  const int bid = bx - mat * wpm;
+  auto pick = [mat](auto a0, auto a1, auto a2, auto a3) { return mat == 0 ? a0 : mat == 1 ? a1 : mat == 2 ? a2 : a3; };
+  // (behind the empty statement the compiler no longer knows that these point to global memory: said again)
+  typedef const __attribute__((address_space(1))) uint32_t* gu32;
+  typedef const __attribute__((address_space(1))) float* gf32;
+  const uint32_t* __restrict__ packed = pick(pk0, pk1, pk2, pk3);
+  const gu32 codebook = (gu32)pick(cb0, cb1, cb2, cb3);
+  const gf32 alpha = (gf32)pick(al0, al1, al2, al3);
+  const gf32 mu = (gf32)pick(mu0, mu1, mu2, mu3);
+  void* const y = pick(y0, y1, y2, y3);
+  const int stride = wpm;                                    // row blocks between successive ones of a team slot
 
   // ---- small loads first (their data is needed first): codewords, then this wave's share of the activations.
   // An item is 16 consecutive B bytes of one step: (step t, strand qa, half h) = slots e = 16 h .. 16 h + 15
@@ -415,7 +437,7 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
   // the operands of the transform are requested after the first index words: they queue behind them in the
   // memory pipeline of the compute unit and are needed later
   typename FT::Ring ring;
-  if constexpr (FUSED) FT::begin(geo, (const uint16_t*)x, tid, wave, lane, ring);
+  if constexpr (FUSED) FT::begin(geo, (const uint16_t*)x_arg, tid, wave, lane, ring);   // (the argument itself: known to be global memory)
   STAMP(1);
 
   // ---- codebook -> table of nibble patterns, every entry C times.  Thread k writes its entry's copies in
@@ -712,8 +734,8 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
 #pragma unroll
         for (int w = 0; w < CW; ++w) tot += rbuf[w * 16 + lane];
         const float res = al * tot + mm * sx;
-        if (y_is_f32) ((float*)y)[my_row] = res;
-        else ((__half*)y)[my_row] = __float2half_rn(res);
+        if (y_is_f32) ((__attribute__((address_space(1))) float*)y)[my_row] = res;
+        else ((__attribute__((address_space(1))) uint16_t*)y)[my_row] = __half_as_ushort(__float2half_rn(res));
       }
       if (it < 8) STAMP(12 + 5 * it);
       ++it;
