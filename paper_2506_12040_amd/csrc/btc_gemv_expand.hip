@@ -70,6 +70,10 @@ __global__ __launch_bounds__(kWaves * 64) void gemv_expand_kernel(Dims d, const 
   __shared__ float red[kWaves * 2];
   __shared__ float rowpart[kMaxRowsPerGroup * kWaves];
 
+  // every kernel argument is fetched now, in one trip to memory (the empty statement needs them all in registers;
+  // left alone the compiler fetches each one next to its first use, one dependent trip after another)
+  asm volatile("" ::"s"(packed), "s"(codebook), "s"(alpha), "s"(mu), "s"(x), "s"(y), "s"(y_is_f32), "s"(CS),
+               "s"(rows_per_group), "s"(slot_dwords), "s"(x_vec), "s"(d.out), "s"(d.in), "s"(d.wpr), "s"(d.nchunks));
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int RG = kWaves / CS;            // row groups (of CS waves) per workgroup
