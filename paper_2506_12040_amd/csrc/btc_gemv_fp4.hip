@@ -249,9 +249,6 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
   typedef const __attribute__((address_space(1))) float* gf32;
   const uint32_t* __restrict__ packed = pick(pk0, pk1, pk2, pk3);
   const gu32 codebook = (gu32)pick(cb0, cb1, cb2, cb3);
-  const gf32 alpha = (gf32)pick(al0, al1, al2, al3);
-  const gf32 mu = (gf32)pick(mu0, mu1, mu2, mu3);
-  void* const y = pick(y0, y1, y2, y3);
   const int stride = wpm;                                    // row blocks between successive ones of a team slot
 
   // ---- small loads first (their data is needed first): codewords, then this wave's share of the activations.
@@ -438,6 +435,10 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
   // memory pipeline of the compute unit and are needed later
   typename FT::Ring ring;
   if constexpr (FUSED) FT::begin(geo, (const uint16_t*)x_arg, tid, wave, lane, ring);   // (the argument itself: known to be global memory)
+  // (selected only now: the row loop is their first user, and the loads above are not kept waiting for them)
+  const gf32 alpha = (gf32)pick(al0, al1, al2, al3);
+  const gf32 mu = (gf32)pick(mu0, mu1, mu2, mu3);
+  void* const y = pick(y0, y1, y2, y3);
   STAMP(1);
 
   // ---- codebook -> table of nibble patterns, every entry C times.  Thread k writes its entry's copies in
