@@ -603,8 +603,15 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
   __syncthreads();   // table complete, B operands staged, sums of x stored
   STAMP(7);
   float sx = 0.f;
+  static_assert(W % 4 == 0 && (K::kTableBytes + 2 * W * 16 * 4) % 16 == 0, "the wave sums are read four at a time");
 #pragma unroll
-  for (int w = 0; w < W; ++w) sx += sxp[w];
+  for (int w = 0; w < W; w += 4) {   // (same order of additions in every wave)
+    const float4 v = *(const float4*)(sxp + w);
+    sx += v.x;
+    sx += v.y;
+    sx += v.z;
+    sx += v.w;
+  }
 
   // ---- per-lane constants of the read-back: lane (r, q) starts at bit ws0 + q L B of its staged row
   const uint32_t lbit = (wbit0 & 31u) + (uint32_t)(q * L) * B;
