@@ -17,13 +17,16 @@ static int choose_engine(const Dims& d, int batch) {
   int engine = BTC_ENGINE_AUTO;
   {
     // One activation row on the tuned settings (v = 9, 10; 7..10 index bits; rows of at most 30720 weights) and a
-    // matrix of 3.5 MiB or more: the engine on the 4-bit matrix cores.  Measured against the engines below on the
+    // matrix of 2.5 MiB or more: the engine on the 4-bit matrix cores.  Measured against the engines below on the
     // LLaMA-2 7B / 13B / 70B projection shapes at 0.7 .. 1.11 bit: 7.5 against 10.5 us on 11008 x 4096, 7.8 against
-    // 11.5 on 8192 x 8192, 15.0 against 21.6 on 28672 x 8192; level at 13824 x 5120 (8.3 us); below 3 MiB its longer
-    // prologue (table and activation operands are built per workgroup) leaves the register-resident engine ahead
-    // (6.0 against 6.2 us on 5120 x 5120) -- unless the rows are long (6000 weights or more), where that engine and
-    // the table engine fall behind from 1 MiB on (2362 x 7266 at 1.0 bit: 9.8 and 8.4 against 7.8 us).
-    if (batch == 1 && (bytes >= (7LL << 19) || (bytes >= (1LL << 20) && d.nchunks >= 600)) && gemv_fp4_covers(d))
+    // 11.5 on 8192 x 8192, 15.0 against 21.6 on 28672 x 8192; level at 13824 x 5120 (8.3 us).  On 5120 x 5120
+    // (2.5 MiB) it takes 6.2 us whatever the indices are; the register-resident engine takes 6.2 us on Zipf
+    // indices and 7.0 us on uniform ones (its table reads collide less when few codewords dominate).  Below that
+    // the longer prologue (table and activation operands are built per workgroup) leaves the register-resident
+    // engine ahead (5.4 .. 5.9 against 6.2 us on 4096 x 4096 at 0.9 bit) -- unless the rows are long (6000 weights
+    // or more), where that engine and the table engine fall behind from 1 MiB on (2362 x 7266 at 1.0 bit: 9.8 and
+    // 8.4 against 7.8 us).
+    if (batch == 1 && (bytes >= (5LL << 19) || (bytes >= (1LL << 20) && d.nchunks >= 600)) && gemv_fp4_covers(d))
       engine = BTC_ENGINE_FP4;
     else
     // One row, 9 or 10 index bits, a wide matrix with few enough rows: the single-kernel variant of the
