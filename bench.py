@@ -392,6 +392,41 @@ def main():
         return dict(us_per_launch=round(us, 2), bytes=by, eff_GBps=round(by / us / 1e3, 1),
                     frac_hbm=round(by / us / 1e3 / HBM_PEAK_GBS, 4))
 
+    def time_qkv(pq, pkv, min_calls=80):
+        """Cold time of ONE btc_gemv_multi_shapes launch over q (pq's shape) and k, v (two distinct copies of pkv's
+        shape: fewer rows under grouped-query attention), amortised over a graph of such launches."""
+        sq, sk = pq["s"], pkv["s"]
+        nbytes = (sq.out + 2 * sk.out) * sq.words_per_row * 4
+        n = int(min(300, max(4, -(-(1 << 29) // nbytes))))
+        cq, ck = rotated(pq, n), rotated(pkv, 2 * n)
+        ys = [torch.empty(o, dtype=torch.float16, device=dev) for o in (sq.out, sk.out, sk.out)]
+        wsd = torch.zeros(max(B.btc_workspace_bytes(sq, 1, False), B.btc_workspace_bytes(sk, 1, False)),
+                          dtype=torch.uint8, device=dev)
+        call = lambda i: B.btc_gemv_multi_shapes([sq, sk, sk], [cq[i], ck[2 * i], ck[2 * i + 1]],
+                                                 [pq["codebook"], pkv["codebook"], pkv["codebook"]],
+                                                 [pq["alpha"], pkv["alpha"], pkv["alpha"]],
+                                                 [pq["mu"], pkv["mu"], pkv["mu"]], pq["x"], ys, B.BTC_F16, wsd)
+        call(0)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i in range(n):
+                call(i)
+        g.replay()
+        torch.cuda.synchronize()
+        reps = max(2, -(-min_calls // n))
+        e0, e1 = events()
+        e0.record()
+        for _ in range(reps):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / (reps * n)
+        by = gemv_bytes(sq, 1) + 2 * gemv_bytes(sk, 1)
+        del cq, ck, g
+        return dict(us_per_launch=round(us, 2), bytes=by, eff_GBps=round(by / us / 1e3, 1),
+                    frac_hbm=round(by / us / 1e3 / HBM_PEAK_GBS, 4))
+
     # per-shape timing of the headline shapes
     per_shape = {f"{p['s'].out}x{p['s'].in_}": time_decode(p) for p in protos}
 
@@ -416,8 +451,20 @@ def main():
             d["per_shape"][f"{case['out']}x{case['n_in']}"] = r
             d["us"] += cnt * r["cold_us"]
             d["bytes"] += cnt * r["bytes"]
-            # k, v and gate, up share their input: one launch per pair; q and o stay single calls
-            if (case["out"], case["n_in"]) in ((1024, 8192), (28672, 8192)):
+            # q, k, v share their input (k and v have an eighth of q's rows): one launch through btc_gemv_multi_shapes;
+            # gate, up: one launch through btc_gemv_multi; o and down stay single calls
+            shp = (case["out"], case["n_in"])
+            if shp == (8192, 8192):
+                d["us_grouped"] = d.get("us_grouped", 0.0) + r["cold_us"]          # o
+                d["q_proto"] = p                                                    # kept until k, v arrive
+                continue
+            if shp == (1024, 8192):
+                pr = time_pair(p)
+                d.setdefault("pairs", {})[f"2 x {case['out']}x{case['n_in']}"] = pr
+                qkv = time_qkv(d.pop("q_proto"), p)
+                d["pairs"]["8192x8192 + 2 x 1024x8192 (q, k, v)"] = qkv
+                d["us_grouped"] = d.get("us_grouped", 0.0) + qkv["us_per_launch"]
+            elif shp == (28672, 8192):
                 pr = time_pair(p)
                 d.setdefault("pairs", {})[f"2 x {case['out']}x{case['n_in']}"] = pr
                 d["us_grouped"] = d.get("us_grouped", 0.0) + pr["us_per_launch"]

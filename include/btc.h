@@ -176,6 +176,17 @@ btc_status btc_gemv_multi(void* stream, const btc_shape* s, int32_t count, const
                           const float* const* mu, const void* x, void* const* y, btc_dtype y_dtype,
                           void* workspace, size_t workspace_bytes);
 
+/* The same for matrices whose NUMBER OF ROWS differs (Section "Integration into Transformer Architecture":
+ * the projections that read one activation row; with grouped-query attention q has more rows than k and v):
+ * shapes is a HOST array of `count` shapes that agree in `in`, `v` and `K` (else BTC_ERR_SHAPE); y[m] has
+ * shapes[m]->out elements.  In the one-launch case the compute units are shared out among the matrices in
+ * proportion to their rows; results are bit-identical to btc_gemv_multi / btc_gemv on each matrix.  The
+ * workspace must hold the largest btc_workspace_bytes(shapes[m], 1, 0).  Errors as btc_gemv_multi. */
+btc_status btc_gemv_multi_shapes(void* stream, const btc_shape* const* shapes, int32_t count,
+                                 const uint32_t* const* packed, const uint32_t* const* codebook,
+                                 const float* const* alpha, const float* const* mu, const void* x,
+                                 void* const* y, btc_dtype y_dtype, void* workspace, size_t workspace_bytes);
+
 /* Prefill product for many activation rows; same definition as btc_gemv with
  *   X : [M][in] of x_dtype (BTC_BF16 or BTC_F16), M >= 1
  *   Y : [M][out] of y_dtype (BTC_F32, BTC_BF16 or BTC_F16)

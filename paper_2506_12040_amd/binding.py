@@ -91,6 +91,8 @@ def lib() -> ctypes.CDLL:
                                                  ctypes.c_int, vp, ctypes.c_size_t]
         L.btc_gemv_multi.restype = ctypes.c_int
         L.btc_gemv_multi.argtypes = [vp, sp, i32, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, ctypes.c_size_t]
+        L.btc_gemv_multi_shapes.restype = ctypes.c_int
+        L.btc_gemv_multi_shapes.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, ctypes.c_size_t]
         L.btc_gemv_groups.restype = ctypes.c_int
         L.btc_gemv_groups.argtypes = [vp, sp, vp, vp, vp, vp, vp, i32, vp, vp, ctypes.c_int]
         L.btc_status_str.restype = ctypes.c_char_p
@@ -236,6 +238,15 @@ def btc_gemv_multi(s: BtcShape, packed, codebook, alpha, mu, x, y, y_dtype: int,
     _check(lib().btc_gemv_multi(_stream(stream), ctypes.byref(s), len(packed), _ptr_array(packed), _ptr_array(codebook),
                                 _ptr_array(alpha), _ptr_array(mu), _ptr(x), _ptr_array(y), y_dtype, _ptr(workspace),
                                 _nbytes(workspace)), "btc_gemv_multi")
+
+
+def btc_gemv_multi_shapes(shapes, packed, codebook, alpha, mu, x, y, y_dtype: int, workspace=None, stream=None) -> None:
+    """shapes, packed, codebook, alpha, mu, y: sequences of the same length (1..4), one entry per matrix; the shapes
+    agree in everything but the number of rows."""
+    arr = (ctypes.POINTER(btc_shape) * len(shapes))(*[ctypes.pointer(s) for s in shapes])
+    _check(lib().btc_gemv_multi_shapes(_stream(stream), arr, len(shapes), _ptr_array(packed), _ptr_array(codebook),
+                                       _ptr_array(alpha), _ptr_array(mu), _ptr(x), _ptr_array(y), y_dtype,
+                                       _ptr(workspace), _nbytes(workspace)), "btc_gemv_multi_shapes")
 
 
 def btc_gemv_transformed_multi(s: BtcShape, packed, codebook, alpha, mu, x, n1: int, n2: int, sign_bits, P1, P2, prepared,

@@ -223,31 +223,50 @@ btc_status btc_gemv_engine(void* stream, const btc_shape* s, const uint32_t* pac
                             workspace_bytes);
 }
 
-btc_status btc_gemv_multi(void* stream, const btc_shape* s, int32_t count, const uint32_t* const* packed,
-                          const uint32_t* const* codebook, const float* const* alpha, const float* const* mu,
-                          const void* x, void* const* y, btc_dtype y_dtype, void* workspace, size_t workspace_bytes) {
+btc_status btc_gemv_multi_shapes(void* stream, const btc_shape* const* shapes, int32_t count,
+                                 const uint32_t* const* packed, const uint32_t* const* codebook,
+                                 const float* const* alpha, const float* const* mu, const void* x, void* const* y,
+                                 btc_dtype y_dtype, void* workspace, size_t workspace_bytes) {
   using namespace btc;
-  btc_status st = check_shape(s);
-  if (st != BTC_OK) return st;
-  if (!packed || !codebook || !alpha || !mu || !x || !y) return BTC_ERR_NULL;
+  if (!shapes || !packed || !codebook || !alpha || !mu || !x || !y) return BTC_ERR_NULL;
   if (count < 1 || count > 4) return BTC_ERR_UNSUPPORTED;
   if (y_dtype != BTC_F16 && y_dtype != BTC_F32) return BTC_ERR_UNSUPPORTED;
   if (!aligned16(x)) return BTC_ERR_ALIGN;
+  int outs[4] = {0, 0, 0, 0}, widest = 0;
   for (int m = 0; m < count; ++m) {
+    if (!shapes[m]) return BTC_ERR_NULL;
+    const btc_status st = check_shape(shapes[m]);
+    if (st != BTC_OK) return st;
+    // rows of one length, cut and coded the same way: only the number of rows may differ
+    if (shapes[m]->in != shapes[0]->in || shapes[m]->v != shapes[0]->v || shapes[m]->K != shapes[0]->K)
+      return BTC_ERR_SHAPE;
     if (!packed[m] || !codebook[m] || !alpha[m] || !mu[m] || !y[m]) return BTC_ERR_NULL;
     if (!aligned16(packed[m]) || !aligned16(codebook[m]) || !aligned16(alpha[m]) || !aligned16(mu[m]) || !aligned16(y[m]))
       return BTC_ERR_ALIGN;
+    outs[m] = shapes[m]->out;
+    if (shapes[m]->out > shapes[widest]->out) widest = m;
   }
-  const Dims d = dims_of(*s);
   // one launch where the engine on the 4-bit matrix cores covers the setting (its workgroups are shared out among
-  // the matrices); else one call per matrix
+  // the matrices in proportion to their rows); else one call per matrix
+  const Dims d = dims_of(*shapes[widest]);
   if (count > 1 && gemv_fp4_covers(d))
-    return gemv_fp4_multi((hipStream_t)stream, d, count, packed, codebook, alpha, mu, x, y, y_dtype == BTC_F32);
+    return gemv_fp4_multi((hipStream_t)stream, d, count, outs, packed, codebook, alpha, mu, x, y, y_dtype == BTC_F32);
   for (int m = 0; m < count; ++m) {
-    st = btc_gemv(stream, s, packed[m], codebook[m], alpha[m], mu[m], x, 1, y[m], y_dtype, workspace, workspace_bytes);
+    const btc_status st = btc_gemv(stream, shapes[m], packed[m], codebook[m], alpha[m], mu[m], x, 1, y[m], y_dtype,
+                                   workspace, workspace_bytes);
     if (st != BTC_OK) return st;
   }
   return BTC_OK;
+}
+
+btc_status btc_gemv_multi(void* stream, const btc_shape* s, int32_t count, const uint32_t* const* packed,
+                          const uint32_t* const* codebook, const float* const* alpha, const float* const* mu,
+                          const void* x, void* const* y, btc_dtype y_dtype, void* workspace, size_t workspace_bytes) {
+  if (!s) return BTC_ERR_NULL;
+  if (count < 1 || count > 4) return BTC_ERR_UNSUPPORTED;
+  const btc_shape* shapes[4] = {s, s, s, s};
+  return btc_gemv_multi_shapes(stream, shapes, count, packed, codebook, alpha, mu, x, y, y_dtype, workspace,
+                               workspace_bytes);
 }
 
 }  // extern "C"

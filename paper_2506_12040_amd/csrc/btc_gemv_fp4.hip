@@ -180,8 +180,10 @@ __device__ unsigned long long g_stamps[4 * 64];
 // e < 24: c = e / 8, u = e % 8;  24 <= e < 24 + 3 TAIL: c = (e - 24) / TAIL, u = 8 + (e - 24) % TAIL;  else padding.
 // The same order is used for the activations on the B side.
 
-// The matrices of one launch: up to kMaxMulti matrices of the same shape applied to the same activation row
-// (the q, k, v or the gate, up projections of a decoder layer).  Workgroups m wpm .. (m + 1) wpm - 1 work on matrix m.
+// The matrices of one launch: up to kMaxMulti matrices with rows of the same length (same chunk length and codebook
+// size; the number of rows may differ) applied to the same activation row -- the q, k, v or the gate, up projections
+// of a decoder layer.  Workgroups first[m] .. first[m + 1] - 1 work on matrix m (first[m] = the grid size for the
+// slots past `count`); out[m] = its rows (0 on the host side: the rows of the shape handed to the launch).
 constexpr int kMaxMulti = 4;
 struct Multi {
   const uint32_t* packed[kMaxMulti];
@@ -189,7 +191,9 @@ struct Multi {
   const float* alpha[kMaxMulti];
   const float* mu[kMaxMulti];
   void* y[kMaxMulti];
-  int count, wpm;
+  int out[kMaxMulti];
+  int first[kMaxMulti + 1];
+  int count;
 };
 struct Extra {
   ftr::Geo geo;
@@ -199,7 +203,7 @@ struct Extra {
 // GN1, GN2: factor sizes of the activation transform computed in front of the product (0, 0: none).
 template <int V, int B, int T, int TEAMS, int CW, int GN1, int GN2>
 __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
-    Dims d_arg, Multi mm, const __half* __restrict__ x_arg, int y_is_f32_arg, int n_rb_arg, int x_dword_arg, ftr::Geo geo) {
+    Dims d_arg, Multi mm, const __half* __restrict__ x_arg, int y_is_f32, int x_dword_arg, ftr::Geo geo) {
   constexpr bool FUSED = GN1 > 0;
   using K = Cfg<V, B, T, TEAMS, CW, GN1, GN2>;
   using FT = ftr::Shared<GN1, GN2, CW * TEAMS * 64>;
@@ -223,33 +227,37 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
   const int cw = wave & (CW - 1), team = wave / CW;          // column wave, team
   const int r = lane & 15, q = lane >> 4;
   // this workgroup's matrix, and its number among the workgroups of that matrix
-  // No division, and the pointers of all four matrices are fetched from the kernel arguments at fixed offsets and
-  // then selected: indexed by `mat` they would be fetched only after `mat` is known -- three dependent trips to
-  // memory before the first vector load instead of one.  (The empty statement pins all fetches in front of the
-  // selection; left alone, the compiler moves each one under a branch on `mat`, behind the wait for `wpm`.)
-  int wpm = mm.wpm;
+  // No division, and the pointers and row counts of all four matrices are fetched from the kernel arguments at fixed
+  // offsets and then selected: indexed by `mat` they would be fetched only after `mat` is known -- three dependent
+  // trips to memory before the first vector load instead of one.  (The empty statement pins all fetches in front of
+  // the selection; left alone, the compiler moves each one under a branch on `mat`, behind the wait for `first`.)
+  int f1 = mm.first[1], f2 = mm.first[2], f3 = mm.first[3], f4 = mm.first[4];
+  int o0 = mm.out[0], o1 = mm.out[1], o2 = mm.out[2], o3 = mm.out[3];
   const uint32_t *pk0 = mm.packed[0], *pk1 = mm.packed[1], *pk2 = mm.packed[2], *pk3 = mm.packed[3];
   const uint32_t *cb0 = mm.codebook[0], *cb1 = mm.codebook[1], *cb2 = mm.codebook[2], *cb3 = mm.codebook[3];
   const float *al0 = mm.alpha[0], *al1 = mm.alpha[1], *al2 = mm.alpha[2], *al3 = mm.alpha[3];
   const float *mu0 = mm.mu[0], *mu1 = mm.mu[1], *mu2 = mm.mu[2], *mu3 = mm.mu[3];
-  void *y0 = mm.y[0], *y1 = mm.y[1], *y2 = mm.y[2], *y3 = mm.y[3];
   Dims d = d_arg;
   const __half* x = x_arg;
-  int y_is_f32 = y_is_f32_arg, n_rb = n_rb_arg, x_dword = x_dword_arg;
-  asm volatile("" : "+s"(wpm), "+s"(pk0), "+s"(pk1), "+s"(pk2), "+s"(pk3), "+s"(cb0), "+s"(cb1), "+s"(cb2), "+s"(cb3),
+  int x_dword = x_dword_arg;
+  asm volatile("" : "+s"(f1), "+s"(f2), "+s"(f3), "+s"(f4), "+s"(o0), "+s"(o1), "+s"(o2), "+s"(o3),
+                    "+s"(pk0), "+s"(pk1), "+s"(pk2), "+s"(pk3), "+s"(cb0), "+s"(cb1), "+s"(cb2), "+s"(cb3),
                     "+s"(al0), "+s"(al1), "+s"(al2), "+s"(al3), "+s"(mu0), "+s"(mu1), "+s"(mu2), "+s"(mu3),
-                    "+s"(y0), "+s"(y1), "+s"(y2), "+s"(y3), "+s"(x), "+s"(y_is_f32), "+s"(n_rb), "+s"(x_dword),
-                    "+s"(d.in), "+s"(d.out), "+s"(d.wpr));
+                    "+s"(x), "+s"(x_dword), "+s"(d.in), "+s"(d.wpr));
   const int bx = (int)blockIdx.x;
-  const int mat = (bx >= wpm ? 1 : 0) + (bx >= 2 * wpm ? 1 : 0) + (bx >= 3 * wpm ? 1 : 0);
-  const int bid = bx - mat * wpm;
+  const int mat = (bx >= f1 ? 1 : 0) + (bx >= f2 ? 1 : 0) + (bx >= f3 ? 1 : 0);
   auto pick = [mat](auto a0, auto a1, auto a2, auto a3) { return mat == 0 ? a0 : mat == 1 ? a1 : mat == 2 ? a2 : a3; };
+  const int wg_first = pick(0, f1, f2, f3);
+  const int bid = bx - wg_first;
+  const int stride = pick(f1, f2, f3, f4) - wg_first;        // workgroups of this matrix = row blocks between
+                                                             // successive ones of a team slot
+  d.out = pick(o0, o1, o2, o3);
+  const int n_rb = (d.out + 15) >> 4;
   // (behind the empty statement the compiler no longer knows that these point to global memory: said again)
   typedef const __attribute__((address_space(1))) uint32_t* gu32;
   typedef const __attribute__((address_space(1))) float* gf32;
   const uint32_t* __restrict__ packed = pick(pk0, pk1, pk2, pk3);
   const gu32 codebook = (gu32)pick(cb0, cb1, cb2, cb3);
-  const int stride = wpm;                                    // row blocks between successive ones of a team slot
 
   // ---- small loads first (their data is needed first): codewords, then this wave's share of the activations.
   // An item is 16 consecutive B bytes of one step: (step t, strand qa, half h) = slots e = 16 h .. 16 h + 15
@@ -438,7 +446,7 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
   // (selected only now: the row loop is their first user, and the loads above are not kept waiting for them)
   const gf32 alpha = (gf32)pick(al0, al1, al2, al3);
   const gf32 mu = (gf32)pick(mu0, mu1, mu2, mu3);
-  void* const y = pick(y0, y1, y2, y3);
+  void* const y = pick(mm.y[0], mm.y[1], mm.y[2], mm.y[3]);
   STAMP(1);
 
   // ---- codebook -> table of nibble patterns, every entry C times.  Thread k writes its entry's copies in
@@ -764,15 +772,34 @@ static btc_status launch3(hipStream_t q, const Dims& d, const void* x, int y_is_
       return BTC_ERR_HIP;
     attr_set = true;
   }
-  const int n_rb = (d.out + 15) / 16;
-  // one workgroup per compute unit, TEAMS row blocks at a time; the matrices of a launch share the compute units
+  // One workgroup per compute unit, TEAMS row blocks at a time; the matrices of a launch share the 256 compute
+  // units in proportion to their rows: every matrix starts with one workgroup, and the next workgroup goes to the
+  // matrix whose workgroups have the most row blocks to walk (the first of them on a tie), until the compute
+  // units are used up or no matrix can use another one.
   Multi mm = ex.multi;
-  const int per_matrix = 256 / mm.count;
-  mm.wpm = n_rb < per_matrix * TEAMS ? (n_rb + TEAMS - 1) / TEAMS : per_matrix;
-  const int grid = mm.wpm * mm.count;
+  int nrb[kMaxMulti] = {0, 0, 0, 0}, cap[kMaxMulti] = {0, 0, 0, 0}, wg[kMaxMulti] = {0, 0, 0, 0};
+  int used = 0;
+  for (int m = 0; m < mm.count; ++m) {
+    if (mm.out[m] <= 0) mm.out[m] = d.out;
+    nrb[m] = (mm.out[m] + 15) / 16;
+    cap[m] = (nrb[m] + TEAMS - 1) / TEAMS;
+    wg[m] = 1;
+    ++used;
+  }
+  while (used < 256) {
+    int best = -1;
+    for (int m = 0; m < mm.count; ++m)
+      if (wg[m] < cap[m] && (best < 0 || (long long)nrb[m] * wg[best] > (long long)nrb[best] * wg[m])) best = m;
+    if (best < 0) break;
+    ++wg[best];
+    ++used;
+  }
+  mm.first[0] = 0;
+  for (int m = 0; m < kMaxMulti; ++m) mm.first[m + 1] = mm.first[m] + wg[m];
+  const int grid = mm.first[kMaxMulti];
   const int x_dword = (V % 2 == 0) && (d.in % 2 == 0);
   gemv_fp4_kernel<V, B, T, TEAMS, CW, GN1, GN2><<<grid, K::W * 64, K::kLdsBytes, q>>>(
-      d, mm, (const __half*)x, y_is_f32, n_rb, x_dword, ex.geo);
+      d, mm, (const __half*)x, y_is_f32, x_dword, ex.geo);
   return launch_status();
 }
 
@@ -904,12 +931,16 @@ btc_status gemv_fp4(hipStream_t q, const Dims& d, const uint32_t* packed, const 
   return fp4_dispatch(q, d, x, y_is_f32, /*dry=*/false, extra_one(packed, codebook, alpha, mu, y), false);
 }
 
-btc_status gemv_fp4_multi(hipStream_t q, const Dims& d, int count, const uint32_t* const* packed,
+btc_status gemv_fp4_multi(hipStream_t q, const Dims& d, int count, const int* outs, const uint32_t* const* packed,
                           const uint32_t* const* codebook, const float* const* alpha, const float* const* mu,
                           const void* x, void* const* y, int y_is_f32) {
   if (count < 1 || count > fp4::kMaxMulti) return BTC_ERR_UNSUPPORTED;
   fp4::Extra ex{};
   for (int m = 0; m < count; ++m) {
+    if (outs) {
+      if (outs[m] < 1 || outs[m] > d.out) return BTC_ERR_SHAPE;   // d carries the largest row count of the launch
+      ex.multi.out[m] = outs[m];
+    }
     ex.multi.packed[m] = packed[m];
     ex.multi.codebook[m] = codebook[m];
     ex.multi.alpha[m] = alpha[m];

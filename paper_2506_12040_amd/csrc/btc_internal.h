@@ -38,9 +38,10 @@ bool gemv_auto_uses_workspace(const Dims& d, int batch);
 bool gemv_fp4_covers(const Dims& d);
 btc_status gemv_fp4(hipStream_t q, const Dims& d, const uint32_t* packed, const uint32_t* codebook,
                     const float* alpha, const float* mu, const void* x, void* y, int y_is_f32);
-// The same engine on up to four matrices of one shape applied to the same activation row, in one launch
-// (host arrays of device pointers).
-btc_status gemv_fp4_multi(hipStream_t q, const Dims& d, int count, const uint32_t* const* packed,
+// The same engine on up to four matrices applied to the same activation row, in one launch (host arrays of
+// device pointers).  outs: the rows of each matrix (all at most d.out; the rest of the shape is d's), or null:
+// d.out rows each.
+btc_status gemv_fp4_multi(hipStream_t q, const Dims& d, int count, const int* outs, const uint32_t* const* packed,
                           const uint32_t* const* codebook, const float* const* alpha, const float* const* mu,
                           const void* x, void* const* y, int y_is_f32);
 // The same engine behind the online activation transform of the row (factors n1 x n1, n2 x n2, n1 n2 = in),

@@ -123,7 +123,7 @@ def test_argument_checks_need_no_gpu(B):
 
 
 def test_argument_checks_of_the_later_entry_points(B):
-    """btc_gemv_multi, btc_gemv_groups, btc_transform_prepare, btc_gemv_transformed(_multi), btc_quantize_rows,
+    """btc_gemv_multi, btc_gemv_multi_shapes, btc_gemv_groups, btc_transform_prepare, btc_gemv_transformed(_multi), btc_quantize_rows,
     btc_gemm_aq: rejected calls return before anything is enqueued."""
     L = B.lib()
     E = B.binding
@@ -139,6 +139,17 @@ def test_argument_checks_of_the_later_entry_points(B):
     assert L.btc_gemv_multi(None, sp, 2, arr(fake, None), four, four, four, fake, four, E.BTC_F16, None, 0) == E.BTC_ERR_NULL
     assert L.btc_gemv_multi(None, sp, 2, arr(fake, odd), four, four, four, fake, four, E.BTC_F16, None, 0) == E.BTC_ERR_ALIGN
     assert L.btc_gemv_multi(None, sp, 2, four, four, four, four, fake, four, E.BTC_BF16, None, 0) == E.BTC_ERR_UNSUPPORTED
+    # ... whose numbers of rows differ
+    s_kv, s_in, s_K = B.btc_shape_init(8, 5120, 10, 256), B.btc_shape_init(8, 5130, 10, 256), B.btc_shape_init(8, 5120, 10, 128)
+    shp = lambda *ss: (ctypes.POINTER(type(s)) * len(ss))(*[ctypes.pointer(x) if x is not None else None for x in ss])
+    two = arr(fake, fake)
+    assert L.btc_gemv_multi_shapes(None, None, 2, two, two, two, two, fake, two, E.BTC_F16, None, 0) == E.BTC_ERR_NULL
+    assert L.btc_gemv_multi_shapes(None, shp(s, None), 2, two, two, two, two, fake, two, E.BTC_F16, None, 0) == E.BTC_ERR_NULL
+    assert L.btc_gemv_multi_shapes(None, shp(s, s_kv), 5, two, two, two, two, fake, two, E.BTC_F16, None, 0) == E.BTC_ERR_UNSUPPORTED
+    assert L.btc_gemv_multi_shapes(None, shp(s, s_in), 2, two, two, two, two, fake, two, E.BTC_F16, None, 0) == E.BTC_ERR_SHAPE
+    assert L.btc_gemv_multi_shapes(None, shp(s, s_K), 2, two, two, two, two, fake, two, E.BTC_F16, None, 0) == E.BTC_ERR_SHAPE
+    assert L.btc_gemv_multi_shapes(None, shp(s, s_kv), 2, arr(fake, odd), two, two, two, fake, two, E.BTC_F16, None, 0) == E.BTC_ERR_ALIGN
+    assert L.btc_gemv_multi_shapes(None, shp(s, s_kv), 2, two, two, two, arr(fake, None), fake, two, E.BTC_F16, None, 0) == E.BTC_ERR_NULL
     # several (alpha, mu) groups per row
     assert L.btc_gemv_groups(None, sp, fake, fake, fake, fake, fake, 0, fake, fake, E.BTC_F32) == E.BTC_ERR_UNSUPPORTED
     assert L.btc_gemv_groups(None, sp, fake, fake, fake, fake, fake, 5, fake, fake, E.BTC_F32) == E.BTC_ERR_UNSUPPORTED

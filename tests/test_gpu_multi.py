@@ -57,6 +57,44 @@ def test_multi_matches_the_oracle_and_the_single_calls(G, oracle, out, n_in, v, 
             assert torch.equal(y1, Y.payload.view(-1)), f"matrix {m}: one launch and single call differ"
 
 
+# outs, in, v, K: matrices that differ in their number of rows only (q, k, v under grouped-query attention: the 70B
+# shapes at the three bit settings; ragged and tiny row counts; a setting the one-launch engine does not cover)
+ROWS_CASES = [
+    ((8192, 1024, 1024), 8192, 10, 512), ((8192, 1024, 1024), 8192, 9, 1024), ((8192, 1024, 1024), 8192, 10, 128),
+    ((33, 700, 16, 5), 4100, 10, 128), ((4096, 17), 4096, 10, 512), ((1, 5120), 5120, 10, 256),
+    ((5000, 5120, 40), 13824, 10, 256), ((300, 64), 999, 7, 100),
+]
+
+
+@pytest.mark.parametrize("outs,n_in,v,K", ROWS_CASES)
+def test_multi_shapes_matches_the_oracle_and_the_single_calls(G, oracle, outs, n_in, v, K):
+    import torch
+    B = G.B
+    from paper_2506_12040_amd import binding as BB
+    print(f"gemv_multi_shapes outs={outs} in={n_in} v={v} K={K}", flush=True)
+    layers = []
+    x = None
+    for m, out in enumerate(outs):
+        layer, xm = S.make_case(90 + m, out, n_in, v, K, 1)
+        layers.append(G.DeviceLayer(layer, oracle))
+        x = xm if x is None else x
+    x_d = G.dev(x)
+    ws = torch.zeros(max(B.btc_workspace_bytes(l.shape, 1, False) for l in layers), dtype=torch.uint8, device="cuda")
+    for yd, tdt in ((B.BTC_F32, torch.float32), (B.BTC_F16, torch.float16)):
+        Ys = [G.GuardedOutput(1, out, tdt) for out in outs]
+        B.btc_gemv_multi_shapes([l.shape for l in layers], [l.packed for l in layers], [l.codebook for l in layers],
+                                [l.alpha for l in layers], [l.mu for l in layers], x_d, [Y.payload for Y in Ys], yd, ws)
+        for m, (l, Y) in enumerate(zip(layers, Ys)):
+            Y.check_guards()
+            G.assert_close(Y.numpy(), G.oracle_all_rows(oracle, l, x), f"matrix {m}")
+            y1 = torch.empty(outs[m], dtype=tdt, device="cuda")
+            try:
+                B.btc_gemv_engine(l.shape, l.packed, l.codebook, l.alpha, l.mu, x_d, 1, y1, yd, 7, ws)
+            except BB.BtcError:
+                continue                      # the engine does not cover the setting: separate calls were made
+            assert torch.equal(y1, Y.payload.view(-1)), f"matrix {m}: one launch and single call differ"
+
+
 def test_configuration_2_as_the_benchmark_launches_it(G, oracle):
     """The 13B decoder-layer step the way bench.py launches it: q, k, v (three copies of the 5120x5120 layer of the
     recipe, rows rotated as the benchmark rotates them) in one launch, gate and up (two copies of 13824x5120) in
@@ -98,3 +136,11 @@ def test_argument_errors(G):
     with pytest.raises(BB.BtcError) as e:
         B.btc_gemv_multi(s, [t, None], [t, t], [t, t], [t, t], t, [t, t], B.BTC_F32, t)
     assert e.value.status == BB.BTC_ERR_NULL
+    s2 = B.btc_shape_init(32, 650, 10, 256)       # another row length: not one launch, not one input
+    with pytest.raises(BB.BtcError) as e:
+        B.btc_gemv_multi_shapes([s, s2], [t, t], [t, t], [t, t], [t, t], t, [t, t], B.BTC_F32, t)
+    assert e.value.status == BB.BTC_ERR_SHAPE
+    s3 = B.btc_shape_init(32, 640, 10, 128)       # another codebook size
+    with pytest.raises(BB.BtcError) as e:
+        B.btc_gemv_multi_shapes([s, s3], [t, t], [t, t], [t, t], [t, t], t, [t, t], B.BTC_F32, t)
+    assert e.value.status == BB.BTC_ERR_SHAPE
