@@ -675,10 +675,26 @@ def main():
                 ops = 2.0 * M * s.out * s.in_
                 cnt = SHAPES_13B_COUNT[(s.out, s.in_)]
                 per[f"{s.out}x{s.in_}"] = dict(us=round(ms * 1e3, 1), tops=round(ops / ms / 1e9, 1))
+                if M == 1:
+                    # one decode row is a few small launches: also timed the way the headline is, replayed from a graph
+                    g = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g):
+                        for _ in range(20):
+                            call()
+                    g.replay()
+                    torch.cuda.synchronize()
+                    e0, e1 = events()
+                    e0.record()
+                    for _ in range(5):
+                        g.replay()
+                    e1.record()
+                    torch.cuda.synchronize()
+                    per[f"{s.out}x{s.in_}"]["us_graph"] = round(e0.elapsed_time(e1) * 1e3 / 100, 1)
+                    del g
                 tot_op += ops * cnt
                 tot_ms += ms * cnt
                 del p, Qc, Y, wsq
-            row = dict(M=M, bits=8, per_shape=per, note="btc_quantize_rows + btc_gemm_aq, warm, stream-timed")
+            row = dict(M=M, bits=8, per_shape=per, note="btc_quantize_rows + btc_gemm_aq, warm, stream-timed" + (" (us) and replayed from a graph of 20 (us_graph)" if M == 1 else ""))
             if M > 1:
                 tp = tot_op / tot_ms / 1e9
                 row.update(layer_tops=round(tp, 1), frac_int8_peak=round(tp / 5000.0, 4))
