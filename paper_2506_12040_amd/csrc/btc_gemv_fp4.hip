@@ -39,7 +39,7 @@
 //    partial sums meet in LDS and one wave applies alpha, mu * sum(x) and stores.  Two such teams of eight
 //    waves work on two row blocks at a time and share the table, the B operands and one barrier per step
 //    of the row loop.  No workspace, no traffic between workgroups, one launch, deterministic.
-//  * Index words are requested three row blocks ahead; a row block is 16 whole rows of the stream, so
+//  * Index words are requested two row blocks ahead; a row block is 16 whole rows of the stream, so
 //    the matrix is read front to back in large contiguous pieces.
 #include <hip/hip_fp16.h>
 
@@ -61,7 +61,6 @@ typedef __attribute__((address_space(3))) u32x2 lds_u32x2;
 
 constexpr uint32_t kOob = 0x80000000u;   // buffer offset that is always out of range (buffers are < 2 GiB)
 constexpr int kRsrcFlags = 0x00020000;   // raw buffer, 32-bit data format
-constexpr int kPD = 2;                   // row blocks in flight per wave in registers (a third one sits in LDS)
 constexpr int kSetBytes = 2048;          // B operands of four steps: 16 columns x 4 k blocks x 32 bytes
 
 // CW column waves per team: 8, two teams (LDS permitting) -- or 16 in one team for rows of more than 15360
@@ -79,6 +78,10 @@ struct Cfg {
   static constexpr int G = 3;                               // chunks per 128-bit operand of a lane
   static constexpr int TAIL = V - 8;                        // elements of a chunk in the high word of its entry
   static constexpr int L = G * T;                           // chunks per strand
+  // Row blocks in flight per wave in registers (one more sits in LDS).  One: measured against two and three, fewer
+  // requests in flight are FASTER here (28672 x 8192: 13.9 / 14.3 / 15.2 us with 1 / 2 / 3) -- a wave's later row
+  // blocks otherwise queue in front of the blocks other waves need first.
+  static constexpr int PD = 1;
   static constexpr int ND = (L * B + 31) / 32 + 1;          // index words a lane needs per row block
   // index words of a wave's four strands inside one row, fetched as 16-byte pieces by LPR lanes per row
   static constexpr int NW = (4 * L * B + 31) / 32 + 1;
@@ -211,7 +214,7 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
   static_assert(!FUSED || V == 10, "the fused prologue reads aligned pairs of activations from LDS");
   constexpr bool WIDE = K::WIDE;
   constexpr int W = K::W, G = K::G, TAIL = K::TAIL, ND = K::ND, C = K::C, L = K::L;
-  constexpr int LPR = K::LPR, RPI = K::RPI, NLD = K::NLD, S = K::S;
+  constexpr int LPR = K::LPR, RPI = K::RPI, NLD = K::NLD, S = K::S, kPD = K::PD;
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned long long* table = (unsigned long long*)smem;                       // [2^B][C], at LDS offset 0
   float* red = (float*)(smem + K::kTableBytes);                                // [2 phases][W][16]
