@@ -37,6 +37,7 @@ namespace wide {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
 typedef __attribute__((address_space(3))) void lds_void;
@@ -539,25 +540,44 @@ __global__ __launch_bounds__((kMW + kLW) * 64) void gemm_wide_kernel(
         Tw[(8 * (e >> 2) + 4 * h + (e & 3)) * TS + c * 32 + l32] = al[c] * acc[a][c][e] + mn[c] * rs[e];
     wave_lds_sync();
     if (vec) {
-#pragma unroll 4
-      for (int i = 0; i < BN / 8; ++i) {
-        const int idx = i * 64 + lane;
-        const int r = idx / (BN / 4), c4 = idx - r * (BN / 4);
-        const float4 v = *(const float4*)(Tw + r * TS + 4 * c4);
-        const int m = mrow0 + r, n = n0 + 4 * c4;
-        if (m < M && n < out) {
-          const long long o = (long long)m * out + n;
-          if (y_dtype == BTC_F32) {
-            *(float4*)((float*)Y + o) = v;
-          } else if (y_dtype == BTC_BF16) {
-            *(uint2*)((uint16_t*)Y + o) = make_uint2(bf16_bits(v.x) | (bf16_bits(v.y) << 16),
-                                                     bf16_bits(v.z) | (bf16_bits(v.w) << 16));
-          } else {
-            *(uint2*)((uint16_t*)Y + o) = make_uint2(f16_bits(v.x) | (f16_bits(v.y) << 16),
-                                                     f16_bits(v.z) | (f16_bits(v.w) << 16));
+      // The staged rows leave in batches: all LDS reads of a batch are issued, then its stores, and the output
+      // type is tested outside the loops.  (One read, one wait, one store at a time under a three-way branch took
+      // 3.5 us per half -- for 16-bit output, half the bytes, even longer.)
+      constexpr int NI = BN / 8, NB = (NI + 1) / 2;             // 16-byte reads per lane and half; per batch
+      auto rows_out = [&](auto kind) {
+        constexpr int KIND = decltype(kind)::value;
+#pragma unroll
+        for (int b0 = 0; b0 < NI; b0 += NB) {
+          f32x4 v[NB];   // (a vector type: an array of structs would live in scratch memory)
+#pragma unroll
+          for (int u = 0; u < NB; ++u) {
+            const int idx = (b0 + u) * 64 + lane;
+            const int r = idx / (BN / 4), c4 = idx - r * (BN / 4);
+            if (b0 + u < NI) v[u] = *(const f32x4*)(Tw + r * TS + 4 * c4);
+          }
+#pragma unroll
+          for (int u = 0; u < NB; ++u) {
+            const int idx = (b0 + u) * 64 + lane;
+            const int r = idx / (BN / 4), c4 = idx - r * (BN / 4);
+            const int m = mrow0 + r, n = n0 + 4 * c4;
+            if (b0 + u < NI && m < M && n < out) {
+              const long long o = (long long)m * out + n;
+              if constexpr (KIND == BTC_F32) {
+                *(f32x4*)((float*)Y + o) = v[u];
+              } else if constexpr (KIND == BTC_BF16) {
+                *(uint2*)((uint16_t*)Y + o) = make_uint2(bf16_bits(v[u].x) | (bf16_bits(v[u].y) << 16),
+                                                         bf16_bits(v[u].z) | (bf16_bits(v[u].w) << 16));
+              } else {
+                *(uint2*)((uint16_t*)Y + o) = make_uint2(f16_bits(v[u].x) | (f16_bits(v[u].y) << 16),
+                                                         f16_bits(v[u].z) | (f16_bits(v[u].w) << 16));
+              }
+            }
           }
         }
-      }
+      };
+      if (y_dtype == BTC_F32) rows_out(std::integral_constant<int, BTC_F32>{});
+      else if (y_dtype == BTC_BF16) rows_out(std::integral_constant<int, BTC_BF16>{});
+      else rows_out(std::integral_constant<int, BTC_F16>{});
     } else {
       for (int idx = lane; idx < 32 * BN; idx += 64) {
         const int r = idx / BN, cc = idx - r * BN;
