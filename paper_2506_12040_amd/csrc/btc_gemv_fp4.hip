@@ -279,7 +279,13 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
   const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)x, 0, d.in * 2, kRsrcFlags);
   // With two teams, team e prepares the steps t = e, e + 2, ...: a step's B operand then carries one block
   // scale, and steps of different parity never share an accumulator.
-  constexpr int n_items = WIDE ? 0 : 8 * (TEAMS == 2 ? (T + 1) / 2 : T);
+  // SOLO: with at most eight steps the items of BOTH teams fit one wave (8 T <= 64 lanes), so team 0 prepares all B
+  // operands of its column wave, under one block scale, and the waves of team 1 skip the conversion: half as many
+  // prologue instructions on every SIMD (with three steps per team only 24 of a wave's 64 lanes had an item).
+  constexpr bool SOLO = !WIDE && TEAMS == 2 && 8 * T <= 64;
+  constexpr bool SPLIT = TEAMS == 2 && !SOLO;               // the teams prepare the steps of one parity each
+  const bool prep = !SOLO || team == 0;                     // (wave-uniform) this wave prepares B operands
+  constexpr int n_items = WIDE ? 0 : 8 * (SPLIT ? (T + 1) / 2 : T);
   constexpr int NI = WIDE ? 1 : (n_items + 63) / 64;
   uint32_t hx[NI][8];                                      // 16 fp16 values per item, in slot order
   // wide: one half item (8 slots) per lane and set: step 4 tt + lane / 16, strand (lane / 4) % 4, half (lane / 2) % 2,
@@ -345,7 +351,7 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
 #pragma unroll
   for (int ii = 0; ii < (WIDE ? 0 : NI); ++ii) {
     const int item = lane + 64 * ii;
-    const int t = TEAMS == 2 ? 2 * (item >> 3) + team : item >> 3;
+    const int t = SPLIT ? 2 * (item >> 3) + team : item >> 3;
     const int qa = (item >> 1) & 3;
     const int h = item & 1;
     const uint32_t xb = (uint32_t)((cw * 4 + qa) * L + G * t) * V;   // first element of the step's three chunks
@@ -403,7 +409,9 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
       }
     }
   };
-  if constexpr (!FUSED) load_items();
+  if constexpr (!FUSED) {
+    if (prep) load_items();
+  }
 
   // ---- index words.  The wave's four strands are one contiguous piece of every row: LPR lanes fetch it as
   // 16-byte pieces (neighbouring lanes read neighbouring addresses), RPI rows per instruction; the pieces go
@@ -477,7 +485,7 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
     STAMP(4);
     if (geo.xt_out != nullptr && blockIdx.x == 0)      // the row for other consumers of the same transform
       for (int i = tid; i < d.in / 2; i += W * 64) ((uint32_t*)geo.xt_out)[i] = ((const uint32_t*)xf)[i];
-    load_items();
+    if (prep) load_items();
     __syncthreads();   // the exchange area becomes the staging area again
     STAMP(60);
   }
@@ -489,10 +497,10 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
   // leaves at most 8 significant bits, exactly), written in B-operand layout: 16 bytes per item and piece
   // Block scale: 2^k brings the largest element this wave stages to 2^14..2^15 (positive fp16 bit patterns
   // order like integers); the B lanes that hold this wave's items hand 2^-k to the matrix instruction.
-  merge_items();
+  if (prep) merge_items();
   float sx_lane = 0.f;
-  int k_scale;
-  {
+  int k_scale = 0;
+  if (prep) {
     // largest magnitude of this lane's items: packed fp16 maximum of the absolute values, then the two halves
     f16x2 m2 = {(_Float16)0.0f, (_Float16)0.0f};
 #pragma unroll
@@ -513,7 +521,7 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
     const int e_field = (int)(mx >> 10);                 // 0 for subnormals, 31 for infinities and NaNs
     k_scale = 29 - max(e_field, 1);
     if (lane == 0) {
-      if (TEAMS == 2) scl[cw * 2 + team] = k_scale;
+      if (SPLIT) scl[cw * 2 + team] = k_scale;
       else scl[cw * 2] = scl[cw * 2 + 1] = k_scale;
     }
   }
@@ -554,10 +562,11 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
       wave_lds_order();
     }
   }
+  if (prep) {
 #pragma unroll
   for (int ii = 0; ii < (WIDE ? 0 : NI); ++ii) {
     const int item = lane + 64 * ii;
-    const int t = TEAMS == 2 ? 2 * (item >> 3) + team : item >> 3;
+    const int t = SPLIT ? 2 * (item >> 3) + team : item >> 3;
     const int qa = (item >> 1) & 3;
     const int h = item & 1;
     // piece n of step t is column 4 (t % 4) + n of set t / 4
@@ -602,6 +611,7 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
       }
     }
   }
+  }   // prep
   STAMP(5);
   // sum of this wave's share of the activations (every element belongs to exactly one item)
   sx_lane = wave_sum_to_lane63(sx_lane);
