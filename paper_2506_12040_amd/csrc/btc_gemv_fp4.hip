@@ -460,16 +460,19 @@ __global__ __launch_bounds__(CW * TEAMS * 64) void gemv_fp4_kernel(
   void* const y = pick(mm.y[0], mm.y[1], mm.y[2], mm.y[3]);
   STAMP(1);
 
-  // ---- codebook -> table of nibble patterns, every entry C times.  Thread k writes its entry's copies in
-  // the order k, k + 1, ... (mod C): at every step the 16 threads of consecutive entries write 16 different
-  // bank pairs, although an entry's copies are 128 bytes or more apart from the next entry's.
+  // ---- codebook -> table of nibble patterns, every entry C times, two copies per 16-byte write.  Thread k writes
+  // its entry's pairs of copies in the order k, k + 1, ... (mod C / 2): at every step the 16 threads of consecutive
+  // entries write 16 different groups of four banks, although an entry's copies are 128 bytes or more apart from
+  // the next entry's.
 #pragma unroll
   for (int i = 0; i < KPT; ++i) {
     const int k = ttid + i * TT;
     if (ttid >= 0 && k < (1 << B)) {
       const unsigned long long ent = expand_codeword<V>(cwd[i]);
+      const u32x4 two = {(uint32_t)ent, (uint32_t)(ent >> 32), (uint32_t)ent, (uint32_t)(ent >> 32)};
+      u32x4* const row = (u32x4*)(table + k * C);
 #pragma unroll
-      for (int c = 0; c < C; ++c) table[k * C + ((c + k) & (C - 1))] = ent;
+      for (int c = 0; c < C / 2; ++c) row[(c + k) & (C / 2 - 1)] = two;
     }
   }
   STAMP(2);
