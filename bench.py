@@ -84,6 +84,7 @@ def main():
                          "through btc_gemv_multi, one launch per group; separate: seven btc_gemv calls")
     ap.add_argument("--gemm-m", type=int, default=2048)
     ap.add_argument("--gemm-iters", type=int, default=10)
+    ap.add_argument("--gemm-warmup-ms", type=float, default=40.0, help="the GEMM legs repeat a call untimed for this long first")
     ap.add_argument("--no-compare", action="store_true", help="do not also time the other way of launching the step")
     ap.add_argument("--no-gemm", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
@@ -427,6 +428,29 @@ def main():
         return dict(us_per_launch=round(us, 2), bytes=by, eff_GBps=round(by / us / 1e3, 1),
                     frac_hbm=round(by / us / 1e3 / HBM_PEAK_GBS, 4))
 
+    def time_gemm_steady(fn, first=None):
+        """ms per call in the steady state: the calls are repeated untimed until --gemm-warmup-ms have gone by (the
+        clock of a chip that has been idle or under light load takes tens of milliseconds of this load to settle:
+        the first ten calls run 5 to 15 % slower than the hundredth), then the median of three timed runs of
+        --gemm-iters calls.  first: a dict that receives the ms per call of the very first run, before the warm-up."""
+        def run():
+            e0, e1 = events()
+            e0.record()
+            for _ in range(args.gemm_iters):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / args.gemm_iters
+        fn()
+        torch.cuda.synchronize()
+        t_first = run()
+        if first is not None:
+            first["ms_first_run"] = round(t_first, 4)
+        spent = t_first * args.gemm_iters
+        while spent < args.gemm_warmup_ms:
+            spent += run() * args.gemm_iters
+        return sorted(run() for _ in range(3))[1]
+
     # per-shape timing of the headline shapes
     per_shape = {f"{p['s'].out}x{p['s'].in_}": time_decode(p) for p in protos}
 
@@ -535,7 +559,14 @@ def main():
             for w in Ws:
                 torch.matmul(xd, w.t())
             torch.cuda.synchronize()
-            reps = 8 if M <= 16 else 2
+            if M > 16:            # compute-bound sizes: both sides in the steady state (see time_gemm_steady)
+                def one_pass():
+                    for w in Ws:
+                        torch.matmul(xd, w.t())
+                us = time_gemm_steady(one_pass) * 1e3 / ncopies
+                del Ws
+                return us
+            reps = 8
             e0, e1 = events()
             e0.record()
             for _ in range(reps):
@@ -553,15 +584,7 @@ def main():
             ws2 = torch.zeros(B.btc_workspace_bytes(s, M, True), dtype=torch.uint8, device=dev)
             f = lambda: B.btc_gemm(s, p["packed"], p["codebook"], p["alpha"], p["mu"], X2, B.BTC_BF16, M, Y2,
                                    B.BTC_BF16, ws2)
-            f()
-            torch.cuda.synchronize()
-            e0, e1 = events()
-            e0.record()
-            for _ in range(4):
-                f()
-            e1.record()
-            torch.cuda.synchronize()
-            return e0.elapsed_time(e1) * 1e3 / 4
+            return time_gemm_steady(f) * 1e3
 
         mlp = {}
         o_, i_ = 8192, 28672
@@ -593,7 +616,7 @@ def main():
         for case in S.config_cases(3):
             cases3.setdefault(case["batch"], []).append(case)
         for M in sorted({args.gemm_m, 512}, reverse=True):
-            per, tot_flop, tot_ms, tot_ms_b = {}, 0.0, 0.0, 0.0
+            per, tot_flop, tot_ms, tot_ms_b, tot_ms_first = {}, 0.0, 0.0, 0.0, 0.0
             for case in cases3.get(M) or [dict(c, batch=M) for c in cases3[2048]]:
                 p = device_case(case)
                 s = p["s"]
@@ -602,39 +625,30 @@ def main():
                 wsg = torch.zeros(B.btc_workspace_bytes(s, M, True), dtype=torch.uint8, device=dev)
                 call = lambda: B.btc_gemm(s, p["packed"], p["codebook"], p["alpha"], p["mu"], X, B.BTC_BF16, M, Y,
                                           B.BTC_F32, wsg)
-                call()
-                torch.cuda.synchronize()
-                e0, e1 = events()
-                e0.record()
-                for _ in range(args.gemm_iters):
-                    call()
-                e1.record()
-                torch.cuda.synchronize()
-                ms = e0.elapsed_time(e1) / args.gemm_iters
+                first = {}
+                ms = time_gemm_steady(call, first)
                 flop = 2.0 * M * s.out * s.in_
                 cnt = SHAPES_13B_COUNT[(s.out, s.in_)]
-                per[f"{s.out}x{s.in_}"] = dict(ms=round(ms, 4), tflops=round(flop / ms / 1e9, 1))
+                per[f"{s.out}x{s.in_}"] = dict(ms=round(ms, 4), tflops=round(flop / ms / 1e9, 1),
+                                               tflops_first_run=round(flop / first["ms_first_run"] / 1e9, 1))
                 tot_flop += flop * cnt
                 tot_ms += ms * cnt
+                tot_ms_first += first["ms_first_run"] * cnt
                 # the same call with the output rounded to bf16 (half the bytes written by the epilogue)
                 Yb = torch.empty(M * s.out, dtype=torch.bfloat16, device=dev)
                 callb = lambda: B.btc_gemm(s, p["packed"], p["codebook"], p["alpha"], p["mu"], X, B.BTC_BF16, M, Yb,
                                            B.BTC_BF16, wsg)
-                callb()
-                torch.cuda.synchronize()
-                e0, e1 = events()
-                e0.record()
-                for _ in range(args.gemm_iters):
-                    callb()
-                e1.record()
-                torch.cuda.synchronize()
-                msb = e0.elapsed_time(e1) / args.gemm_iters
+                msb = time_gemm_steady(callb)
                 per[f"{s.out}x{s.in_}"]["tflops_bf16_out"] = round(flop / msb / 1e9, 1)
                 tot_ms_b += msb * cnt
                 del X, Y, Yb, p
             tf = tot_flop / tot_ms / 1e9
             gemm[f"M{M}"] = dict(M=M, x_dtype="bf16", y_dtype="f32", per_shape=per, layer_tflops=round(tf, 1),
                                  layer_tflops_bf16_out=round(tot_flop / tot_ms_b / 1e9, 1),
+                                 layer_tflops_first_run=round(tot_flop / tot_ms_first / 1e9, 1),
+                                 timing=f"steady state: median of 3 runs of {args.gemm_iters} calls after "
+                                        f"{args.gemm_warmup_ms:g} ms of the same call; first_run: the first "
+                                        f"{args.gemm_iters} calls after the decode legs (clock not settled yet)",
                                  frac_mfma_peak=round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
                                  frac_measured_peak=round(tf / MFMA_BF16_MEASURED_TFLOPS, 4))
 
@@ -664,14 +678,17 @@ def main():
                                   B.BTC_F32, wsq)
                 call()
                 torch.cuda.synchronize()
-                reps = 10 if M > 1 else 50
-                e0, e1 = events()
-                e0.record()
-                for _ in range(reps):
-                    call()
-                e1.record()
-                torch.cuda.synchronize()
-                ms = e0.elapsed_time(e1) / reps
+                if M > 1:
+                    ms = time_gemm_steady(call)
+                else:
+                    reps = 50
+                    e0, e1 = events()
+                    e0.record()
+                    for _ in range(reps):
+                        call()
+                    e1.record()
+                    torch.cuda.synchronize()
+                    ms = e0.elapsed_time(e1) / reps
                 ops = 2.0 * M * s.out * s.in_
                 cnt = SHAPES_13B_COUNT[(s.out, s.in_)]
                 per[f"{s.out}x{s.in_}"] = dict(us=round(ms * 1e3, 1), tops=round(ops / ms / 1e9, 1))
@@ -997,8 +1014,9 @@ def main():
             "bound": "mfma", "achieved": gemm[f"M{args.gemm_m}"]["layer_tflops"], "peak": MFMA_BF16_PEAK_TFLOPS,
             "unit": "TFLOP/s", "frac": gemm[f"M{args.gemm_m}"]["frac_mfma_peak"],
             "frac_measured_peak": gemm[f"M{args.gemm_m}"]["frac_measured_peak"], "traffic": None,
+            "achieved_first_run": gemm[f"M{args.gemm_m}"]["layer_tflops_first_run"],
             "note": f"2*M*out*in flop of the 7 projections at M={args.gemm_m} / event-timed btc_gemm calls "
-                    "(whole calls)"},
+                    "(whole calls); " + gemm[f"M{args.gemm_m}"]["timing"]},
         "act_quant": act_quant,
         "gemv_groups": groups,
         "transform": transform,
